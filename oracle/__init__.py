@@ -1,0 +1,146 @@
+"""ctypes front end of the CPU oracle (oracle/alaya_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+bench's cpu_baseline leg.  It never imports the HIP package, and the HIP
+package never imports it.
+
+All array arguments are numpy arrays; K and V are token-major
+[n][n_kv_heads][head_dim], stored either as float32 or as bf16 bit patterns in
+uint16 (dtype is inferred from the numpy dtype).  Results are fp64.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "alaya_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+BF16, F32 = 0, 1
+TOPK, DIPR, FULL = 0, 1, 2
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (a second or so)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+                               "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        vp, i32, i64, f64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_double
+        lib.oracle_scores.argtypes = [vp, vp, i32, i64, i32, i32, i32, vp]
+        lib.oracle_scores.restype = None
+        lib.oracle_select_topk.argtypes = [vp, i64, i64, vp]
+        lib.oracle_select_topk.restype = i64
+        lib.oracle_select_dipr.argtypes = [vp, i64, f64, vp]
+        lib.oracle_select_dipr.restype = i64
+        lib.oracle_attend.argtypes = [vp, vp, i32, i32, i32, i32, vp, i64, f64, vp]
+        lib.oracle_attend.restype = None
+        lib.oracle_sparse_attn.argtypes = [vp, vp, vp, i32, i64, i32, i32, i32, i32, i64, f64, f64,
+                                           vp, vp, i64, vp, vp, i32]
+        lib.oracle_sparse_attn.restype = i32
+        _lib = lib
+    return _lib
+
+
+def _dt(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.uint16:
+        return BF16
+    raise TypeError(f"oracle takes float32 or uint16 (bf16 bits), got {a.dtype}")
+
+
+def _c(a: np.ndarray) -> np.ndarray:
+    return np.ascontiguousarray(a)
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def scores(q_h: np.ndarray, K: np.ndarray, g: int) -> np.ndarray:
+    """Raw inner products of one query head against KV head g: fp64 [n]."""
+    q_h, K = _c(q_h), _c(K)
+    n, hk, d = K.shape
+    assert q_h.shape == (d,) and _dt(q_h) == _dt(K)
+    s = np.empty(n, dtype=np.float64)
+    _load().oracle_scores(_p(q_h), _p(K), _dt(K), n, hk, g, d, _p(s))
+    return s
+
+
+def select_topk(s: np.ndarray, k: int) -> np.ndarray:
+    s = _c(s.astype(np.float64, copy=False))
+    ids = np.empty(max(1, min(max(k, 0), s.size)), dtype=np.int32)
+    cnt = _load().oracle_select_topk(_p(s), s.size, k, _p(ids))
+    if cnt < 0:
+        raise ValueError("k must be positive")
+    return ids[:cnt].copy()
+
+
+def select_dipr(s: np.ndarray, beta: float) -> np.ndarray:
+    s = _c(s.astype(np.float64, copy=False))
+    ids = np.empty(max(1, s.size), dtype=np.int32)
+    cnt = _load().oracle_select_dipr(_p(s), s.size, float(beta), _p(ids))
+    if cnt < 0:
+        raise ValueError("beta must be >= 0")
+    return ids[:cnt].copy()
+
+
+def attend(s: np.ndarray, V: np.ndarray, g: int, ids: np.ndarray, scale: Optional[float] = None) -> np.ndarray:
+    """Softmax over the given token set and the weighted sum of its V rows: fp64 [d]."""
+    s, V = _c(s.astype(np.float64, copy=False)), _c(V)
+    ids = _c(np.asarray(ids, dtype=np.int32))
+    n, hk, d = V.shape
+    assert s.shape == (n,)
+    if ids.size and (ids.min() < 0 or ids.max() >= n):
+        raise IndexError("token id out of range")
+    sc = float(scale) if scale is not None else 1.0 / np.sqrt(d)
+    o = np.empty(d, dtype=np.float64)
+    _load().oracle_attend(_p(s), _p(V), _dt(V), hk, g, d, _p(ids), ids.size, sc, _p(o))
+    return o
+
+
+def sparse_attn(q: np.ndarray, K: np.ndarray, V: np.ndarray, mode: int, k: int = 0, beta: float = 0.0,
+                scale: Optional[float] = None, want_ids: bool = True, want_scores: bool = False,
+                threads: int = 0) -> dict:
+    """One request, all heads.  q [n_q_heads][d]; K, V [n][n_kv_heads][d].
+
+    Returns {"out": fp64 [Hq][d], "counts": int64 [Hq], "ids": list of int32 arrays (ascending),
+             "scores": fp64 [Hq][n] or None, "threads": OpenMP threads used}.
+    """
+    q, K, V = _c(q), _c(K), _c(V)
+    n, hk, d = K.shape
+    hq = q.shape[0]
+    assert V.shape == K.shape and q.shape == (hq, d) and _dt(q) == _dt(K) == _dt(V)
+    out = np.empty((hq, d), dtype=np.float64)
+    counts = np.zeros(hq, dtype=np.int64)
+    stride = n if want_ids else 0
+    ids = np.empty((hq, stride), dtype=np.int32) if want_ids else None
+    sc = np.empty((hq, n), dtype=np.float64) if want_scores else None
+    rc = _load().oracle_sparse_attn(_p(q), _p(K), _p(V), _dt(K), n, hq, hk, d, int(mode), int(k),
+                                    float(beta), float(scale) if scale else 0.0,
+                                    _p(out), _p(ids), stride, _p(counts), _p(sc), int(threads))
+    if rc < 0:
+        raise ValueError({-1: "bad shapes or n == 0", -2: "k must be positive",
+                          -3: "beta must be >= 0"}.get(rc, f"oracle error {rc}"))
+    id_list = [ids[h, :counts[h]].copy() for h in range(hq)] if want_ids else None
+    return {"out": out, "counts": counts, "ids": id_list, "scores": sc, "threads": rc}
+
+
+def full_attn(q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: Optional[float] = None,
+              threads: int = 0) -> np.ndarray:
+    return sparse_attn(q, K, V, FULL, scale=scale, want_ids=False, threads=threads)["out"]

@@ -1,0 +1,183 @@
+/*
+ * CPU oracle for the decode-step sparse-attention query.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, slow, and written from the paper's
+ * definitions; it shares no code with the HIP library and must never be
+ * called from the product path.  Only the tests, the smoke check and the
+ * bench's cpu_baseline leg may load it.
+ *
+ * What it computes, per query head h (KV head g = h / G), over n cached tokens:
+ *   scores   s_j = q_h . k_{g,j}                      raw inner product (Eq. 1 numerator; Def. 2)
+ *   top-k    the min(k, n) tokens with the largest s_j (Sec. 5.1.1); equal scores: smaller j first
+ *   DIPR     every j with s_j >= max_s s_s - beta, beta >= 0, inclusive (Def. 2, Def. 3)
+ *   attend   z_j = s_j * scale (scale = 1/sqrt(d)); a = softmax over the SELECTED set only;
+ *            o = sum_j a_j v_{g,j}                    (Eq. 1 restricted to the critical tokens,
+ *                                                      Sec. 2 "Sparse Attention")
+ *   full     the same with every token selected       (Eq. 1)
+ *
+ * All arithmetic is fp64.  Inputs are the stored bytes (bf16 or fp32), widened
+ * exactly.  K and V are token-major: element (j, g, c) sits at (j*n_kv_heads + g)*d + c.
+ *
+ * Every function here is pinned by tests/test_oracle_pins.py against facts that
+ * do not depend on this file (a dense library softmax, Theorem 1's alpha form,
+ * brute force, invariances, a hand-derived closed form).
+ */
+#define _GNU_SOURCE /* qsort_r */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_BF16 = 0, ORACLE_F32 = 1 };
+enum { ORACLE_TOPK = 0, ORACLE_DIPR = 1, ORACLE_FULL = 2 };
+
+static double widen(const void *base, int dtype, int64_t idx)
+{
+    if (dtype == ORACLE_F32)
+        return (double)((const float *)base)[idx];
+    uint32_t bits = (uint32_t)((const uint16_t *)base)[idx] << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+/* s_j = sum_c q[c] * K[j][g][c]  for j < n.  q points at this head's d elements. */
+void oracle_scores(const void *q, const void *K, int dtype, int64_t n,
+                   int n_kv_heads, int g, int d, double *s)
+{
+    for (int64_t j = 0; j < n; ++j) {
+        double acc = 0.0;
+        int64_t row = (j * n_kv_heads + g) * (int64_t)d;
+        for (int c = 0; c < d; ++c)
+            acc += widen(q, dtype, c) * widen(K, dtype, row + c);
+        s[j] = acc;
+    }
+}
+
+static int by_score_desc_then_id(const void *a, const void *b, void *ctx)
+{
+    const double *s = (const double *)ctx;
+    int32_t ia = *(const int32_t *)a, ib = *(const int32_t *)b;
+    if (s[ia] > s[ib]) return -1;
+    if (s[ia] < s[ib]) return 1;
+    return (ia > ib) - (ia < ib);
+}
+
+static int by_id(const void *a, const void *b)
+{
+    int32_t ia = *(const int32_t *)a, ib = *(const int32_t *)b;
+    return (ia > ib) - (ia < ib);
+}
+
+/* Top-k query: rank every token by score, keep the first min(k, n); ids come
+ * back ascending.  Returns the count, or -1 if k <= 0. */
+int64_t oracle_select_topk(const double *s, int64_t n, int64_t k, int32_t *ids)
+{
+    if (k <= 0) return -1;
+    if (n <= 0) return 0;
+    int64_t kk = k < n ? k : n;
+    int32_t *order = (int32_t *)malloc((size_t)n * sizeof *order);
+    for (int64_t j = 0; j < n; ++j) order[j] = (int32_t)j;
+    qsort_r(order, (size_t)n, sizeof *order, by_score_desc_then_id, (void *)s);
+    memcpy(ids, order, (size_t)kk * sizeof *ids);
+    free(order);
+    qsort(ids, (size_t)kk, sizeof *ids, by_id);
+    return kk;
+}
+
+/* DIPR(q, beta): all tokens whose inner product is within beta of the maximum.
+ * ids ascending.  Returns the count (>= 1 for n >= 1), or -1 if beta < 0 or NaN. */
+int64_t oracle_select_dipr(const double *s, int64_t n, double beta, int32_t *ids)
+{
+    if (!(beta >= 0.0)) return -1;
+    if (n <= 0) return 0;
+    double m = s[0];
+    for (int64_t j = 1; j < n; ++j)
+        if (s[j] > m) m = s[j];
+    int64_t cnt = 0;
+    for (int64_t j = 0; j < n; ++j)
+        if (s[j] >= m - beta) ids[cnt++] = (int32_t)j;
+    return cnt;
+}
+
+/* Softmax over the selected set and the weighted sum of its value rows. */
+void oracle_attend(const double *s, const void *V, int dtype, int n_kv_heads, int g, int d,
+                   const int32_t *ids, int64_t cnt, double scale, double *o)
+{
+    for (int c = 0; c < d; ++c) o[c] = 0.0;
+    if (cnt <= 0) return;
+    double zmax = s[ids[0]] * scale;
+    for (int64_t i = 1; i < cnt; ++i) {
+        double z = s[ids[i]] * scale;
+        if (z > zmax) zmax = z;
+    }
+    double denom = 0.0;
+    for (int64_t i = 0; i < cnt; ++i)
+        denom += exp(s[ids[i]] * scale - zmax);
+    for (int64_t i = 0; i < cnt; ++i) {
+        double a = exp(s[ids[i]] * scale - zmax) / denom;
+        int64_t row = ((int64_t)ids[i] * n_kv_heads + g) * (int64_t)d;
+        for (int c = 0; c < d; ++c)
+            o[c] += a * widen(V, dtype, row + c);
+    }
+}
+
+/*
+ * One request, all query heads: scores -> select -> attend.
+ *   q        [n_q_heads][d]          storage dtype
+ *   K, V     [n][n_kv_heads][d]      storage dtype
+ *   mode     ORACLE_TOPK (uses k), ORACLE_DIPR (uses beta), ORACLE_FULL
+ *   scale    softmax scale; <= 0 means 1/sqrt(d)
+ *   out      [n_q_heads][d] fp64
+ *   ids      optional [n_q_heads][ids_stride] ascending token ids (first min(count, stride))
+ *   counts   optional [n_q_heads] true selected count
+ *   scores   optional [n_q_heads][n] fp64 raw inner products
+ * Heads run in an OpenMP loop with at most n_threads threads (0 = library default).
+ * Returns the number of threads used, or a negative value on invalid arguments.
+ */
+int oracle_sparse_attn(const void *q, const void *K, const void *V, int dtype, int64_t n,
+                       int n_q_heads, int n_kv_heads, int d, int mode, int64_t k, double beta,
+                       double scale, double *out, int32_t *ids, int64_t ids_stride,
+                       int64_t *counts, double *scores, int n_threads)
+{
+    if (n <= 0 || n_q_heads <= 0 || n_kv_heads <= 0 || d <= 0 || n_q_heads % n_kv_heads) return -1;
+    if (mode == ORACLE_TOPK && k <= 0) return -2;
+    if (mode == ORACLE_DIPR && !(beta >= 0.0)) return -3;
+    if (!(scale > 0.0)) scale = 1.0 / sqrt((double)d);
+    const int G = n_q_heads / n_kv_heads;
+    const size_t esz = dtype == ORACLE_F32 ? 4 : 2;
+    int used = 1;
+#ifdef _OPENMP
+    if (n_threads <= 0) n_threads = omp_get_max_threads();
+    if (n_threads > n_q_heads) n_threads = n_q_heads;
+    used = n_threads;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(n_threads)
+#endif
+    for (int h = 0; h < n_q_heads; ++h) {
+        const int g = h / G;
+        double *s = scores ? scores + (size_t)h * (size_t)n : (double *)malloc((size_t)n * sizeof(double));
+        int32_t *sel = (int32_t *)malloc((size_t)n * sizeof(int32_t));
+        oracle_scores((const char *)q + (size_t)h * (size_t)d * esz, K, dtype, n, n_kv_heads, g, d, s);
+        int64_t cnt;
+        if (mode == ORACLE_TOPK) {
+            cnt = oracle_select_topk(s, n, k, sel);
+        } else if (mode == ORACLE_DIPR) {
+            cnt = oracle_select_dipr(s, n, beta, sel);
+        } else {
+            for (int64_t j = 0; j < n; ++j) sel[j] = (int32_t)j;
+            cnt = n;
+        }
+        oracle_attend(s, V, dtype, n_kv_heads, g, d, sel, cnt, scale, out + (size_t)h * (size_t)d);
+        if (counts) counts[h] = cnt;
+        if (ids) {
+            int64_t m = cnt < ids_stride ? cnt : ids_stride;
+            memcpy(ids + (size_t)h * (size_t)ids_stride, sel, (size_t)m * sizeof(int32_t));
+        }
+        free(sel);
+        if (!scores) free(s);
+    }
+    return used;
+}

@@ -1,0 +1,314 @@
+"""Pins for the CPU oracle: facts fixed by the paper and by mathematics, none by the oracle itself.
+
+Each test names the passage it takes its fact from.  A plausible mistake in
+oracle/alaya_oracle.c (a dropped 1/sqrt(d), a softmax over all tokens instead
+of the selected ones, a wrong KV-head index, '>' for '>=', a wrong tie order,
+transposed K) fails at least one of them.
+"""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+
+
+def _small(seed, n=96, hq=4, hk=2, d=16, dtype="f32"):
+    w = wl.Workload("pin", hq, hk, d, (n,), dtype, 4, "topk", topk=(8,), seed=seed)
+    g = wl.generate(w, threads=1)
+    return w, g["q"][0], g["K"][0], g["V"][0]
+
+
+def _f64(a, dtype):
+    return (wl.bf16_bits_to_f32(a) if dtype == "bf16" else a).astype(np.float64)
+
+
+def _dense(q, K, V, dtype):
+    """softmax(q K^T / sqrt(d)) V with GQA, by library routines only (Eq. 1)."""
+    qf, Kf, Vf = _f64(q, dtype), _f64(K, dtype), _f64(V, dtype)
+    hq, d = qf.shape
+    hk = Kf.shape[1]
+    G = hq // hk
+    s = np.einsum("hc,jhc->hj", qf, np.repeat(Kf, G, axis=1))          # [hq][n]
+    z = s / math.sqrt(d)
+    a = np.exp(z - z.max(axis=1, keepdims=True))
+    a /= a.sum(axis=1, keepdims=True)
+    o = np.einsum("hj,jhc->hc", a, np.repeat(Vf, G, axis=1))
+    return s, a, o
+
+
+# ---------------------------------------------------------------- closed form
+def test_closed_form_weights_1_2_4():
+    """Eq. (1) by hand: d = 4 so 1/sqrt(d) = 1/2; q.k_j = 2 ln w_j gives softmax weights w_j / sum w."""
+    w = np.array([1.0, 2.0, 4.0])
+    q = np.array([[1.0, 0.0, 0.0, 0.0]], dtype=np.float32)
+    K = np.zeros((3, 1, 4), dtype=np.float32)
+    K[:, 0, 0] = 2.0 * np.log(w)
+    K[:, 0, 1:] = [[5.0, -3.0, 2.0], [1.0, 1.0, 1.0], [-7.0, 0.5, 0.25]]   # orthogonal to q: must not matter
+    V = np.array([[[7.0, 0.0, 14.0, -7.0]], [[0.0, 7.0, 7.0, 7.0]], [[-7.0, 3.5, 0.0, 1.75]]], dtype=np.float32)
+    full = oracle.full_attn(q, K, V)
+    exp_full = (1 * V[0, 0] + 2 * V[1, 0] + 4 * V[2, 0]) / 7.0
+    np.testing.assert_allclose(full[0], exp_full, rtol=0, atol=1e-6)
+    # top-2 keeps weights 2 and 4, renormalised over the selected set: 1/3, 2/3 (Sec. 2 "Sparse Attention")
+    r = oracle.sparse_attn(q, K, V, oracle.TOPK, k=2)
+    assert list(r["ids"][0]) == [1, 2]
+    np.testing.assert_allclose(r["out"][0], (2 * V[1, 0] + 4 * V[2, 0]) / 6.0, rtol=0, atol=1e-6)
+    # scores are 0, 2 ln 2 = 1.386, 2 ln 4 = 2.773.  beta = 1.5 keeps the top two, beta = 1.3 only the top (Def. 2)
+    assert list(oracle.sparse_attn(q, K, V, oracle.DIPR, beta=1.5)["ids"][0]) == [1, 2]
+    assert list(oracle.sparse_attn(q, K, V, oracle.DIPR, beta=1.3)["ids"][0]) == [2]
+    assert list(oracle.sparse_attn(q, K, V, oracle.DIPR, beta=2.8)["ids"][0]) == [0, 1, 2]
+
+
+def test_inclusive_boundary():
+    """Def. 2 uses '>=': a key exactly beta below the maximum is critical."""
+    s = np.array([1.0, 3.0, 5.0, 4.0])
+    assert list(oracle.select_dipr(s, 2.0)) == [1, 2, 3]
+    assert list(oracle.select_dipr(s, 1.0)) == [2, 3]
+    assert list(oracle.select_dipr(s, 0.999)) == [2]
+
+
+# ---------------------------------------------------------------- P1: library routine
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("seed", [0, 1])
+def test_scores_and_full_attention_match_dense_library(seed, dtype):
+    """Eq. (1): scores, then softmax(z) V over all tokens, against numpy and torch SDPA in fp64."""
+    w, q, K, V = _small(seed, n=200, hq=8, hk=2, d=32, dtype=dtype)
+    s_ref, _, o_ref = _dense(q, K, V, dtype)
+    G = w.group
+    for h in range(w.n_q_heads):
+        np.testing.assert_allclose(oracle.scores(q[h], K, h // G), s_ref[h], rtol=0, atol=1e-12)
+    o = oracle.full_attn(q, K, V)
+    np.testing.assert_allclose(o, o_ref, rtol=0, atol=1e-12)
+    tq = torch.from_numpy(_f64(q, dtype))[None, :, None, :]                       # [1][hq][1][d]
+    tk = torch.from_numpy(_f64(K, dtype)).permute(1, 0, 2).repeat_interleave(G, 0)[None]
+    tv = torch.from_numpy(_f64(V, dtype)).permute(1, 0, 2).repeat_interleave(G, 0)[None]
+    t = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv)[0, :, 0, :].numpy()
+    np.testing.assert_allclose(o, t, rtol=0, atol=1e-10)
+
+
+@pytest.mark.parametrize("seed", [0, 3])
+def test_k_equal_n_and_unbounded_beta_are_full_attention(seed):
+    """Selecting everything must reproduce Eq. (1) exactly."""
+    w, q, K, V = _small(seed, n=150)
+    full = oracle.full_attn(q, K, V)
+    a = oracle.sparse_attn(q, K, V, oracle.TOPK, k=150)
+    b = oracle.sparse_attn(q, K, V, oracle.TOPK, k=10 ** 6)        # k > n clamps to n
+    c = oracle.sparse_attn(q, K, V, oracle.DIPR, beta=float("inf"))
+    for r in (a, b, c):
+        assert (r["counts"] == 150).all()
+        np.testing.assert_allclose(r["out"], full, rtol=0, atol=1e-13)
+
+
+def test_tiny_workload_full_attention_dense():
+    """The tiny configuration (4096 tokens, fp32, d = 128) against the dense library form."""
+    w = wl.config("tiny")
+    g = wl.generate(w, threads=1)
+    _, _, o_ref = _dense(g["q"][0], g["K"][0], g["V"][0], "f32")
+    np.testing.assert_allclose(oracle.full_attn(g["q"][0], g["K"][0], g["V"][0]), o_ref, rtol=0, atol=1e-12)
+
+
+# ---------------------------------------------------------------- P2: Theorem 1
+@pytest.mark.parametrize("beta", [0.0, 0.3, 1.0, 2.5, 7.0])
+def test_dipr_equals_alpha_form(beta):
+    """Theorem 1: {q.k >= max - beta} == {a_j >= alpha max a}, alpha = exp(-beta / sqrt(d))."""
+    w, q, K, V = _small(5, n=300, hq=4, hk=2, d=16)
+    s, a, _ = _dense(q, K, V, "f32")
+    alpha = math.exp(-beta / math.sqrt(w.head_dim))
+    r = oracle.sparse_attn(q, K, V, oracle.DIPR, beta=beta)
+    for h in range(w.n_q_heads):
+        ratio = a[h] / a[h].max()
+        far = np.abs(ratio - alpha) > 1e-9          # leave out keys on the razor's edge of fp64 rounding
+        want = set(np.nonzero((ratio >= alpha) & far)[0])
+        got = set(r["ids"][h])
+        assert want <= got and got - want <= set(np.nonzero(~far)[0])
+
+
+# ---------------------------------------------------------------- P3: beta = 0
+def test_beta_zero_is_argmax_and_top1():
+    w, q, K, V = _small(7, n=120)
+    s, _, _ = _dense(q, K, V, "f32")
+    r0 = oracle.sparse_attn(q, K, V, oracle.DIPR, beta=0.0)
+    r1 = oracle.sparse_attn(q, K, V, oracle.TOPK, k=1)
+    Vf = V.astype(np.float64)
+    for h in range(w.n_q_heads):
+        j = int(np.argmax(s[h]))
+        assert list(r0["ids"][h]) == [j] == list(r1["ids"][h])
+        np.testing.assert_allclose(r0["out"][h], Vf[j, h // w.group], rtol=0, atol=1e-15)
+        np.testing.assert_allclose(r1["out"][h], Vf[j, h // w.group], rtol=0, atol=1e-15)
+
+
+# ---------------------------------------------------------------- P4 / P5: nesting, two paths agree
+def test_nesting_counts_and_cross_check():
+    w, q, K, V = _small(11, n=257)
+    prev_b, prev_k = None, None
+    for beta in [0.0, 0.5, 1.0, 2.0, 4.0, 100.0]:
+        r = oracle.sparse_attn(q, K, V, oracle.DIPR, beta=beta, want_scores=True)
+        sets = [set(x) for x in r["ids"]]
+        for h, S in enumerate(sets):
+            assert len(S) >= 1 and int(np.argmax(r["scores"][h])) in S
+            # Sec. 5.1.2 (i): a DIPR answer is the top-k' answer for k' = its own size
+            kprime = len(S)
+            assert S == set(oracle.select_topk(r["scores"][h], kprime))
+        if prev_b is not None:
+            assert all(a <= b for a, b in zip(prev_b, sets))
+        prev_b = sets
+    for k in [1, 2, 17, 64, 256, 257, 300]:
+        r = oracle.sparse_attn(q, K, V, oracle.TOPK, k=k)
+        sets = [set(x) for x in r["ids"]]
+        assert all(len(S) == min(k, 257) for S in sets) and (r["counts"] == min(k, 257)).all()
+        if prev_k is not None:
+            assert all(a <= b for a, b in zip(prev_k, sets))
+        prev_k = sets
+
+
+# ---------------------------------------------------------------- P6: permutation invariance
+def test_token_permutation_invariance():
+    """Attention has no positional term once K, V are cached (Eq. 1): permuting tokens maps S and keeps o."""
+    w, q, K, V = _small(13, n=180)
+    perm = np.random.default_rng(0).permutation(180)
+    inv = np.argsort(perm)
+    for mode, kw in [(oracle.TOPK, dict(k=23)), (oracle.DIPR, dict(beta=1.5))]:
+        a = oracle.sparse_attn(q, K, V, mode, **kw)
+        b = oracle.sparse_attn(q, K[perm], V[perm], mode, **kw)
+        np.testing.assert_allclose(a["out"], b["out"], rtol=0, atol=1e-13)
+        for h in range(w.n_q_heads):
+            assert set(a["ids"][h]) == set(perm[b["ids"][h]])
+            assert set(inv[a["ids"][h]]) == set(b["ids"][h])
+
+
+# ---------------------------------------------------------------- P7 / P8: brute force
+@pytest.mark.parametrize("seed", range(4))
+def test_bruteforce_tiny(seed):
+    """n = 12: sort for top-k, enumerate every subset for the recovery ratio (Sec. 5.1.2, Observation I)."""
+    n, k = 12, 4
+    w, q, K, V = _small(seed, n=n, hq=2, hk=1, d=8)
+    qf, Kf, Vf = q.astype(np.float64), K.astype(np.float64), V.astype(np.float64)
+    r = oracle.sparse_attn(q, K, V, oracle.TOPK, k=k)
+    for h in range(2):
+        s = [sum(qf[h, c] * Kf[j, 0, c] for c in range(8)) for j in range(n)]
+        order = sorted(range(n), key=lambda j: (-s[j], j))
+        assert sorted(order[:k]) == list(r["ids"][h])
+        z = [x / math.sqrt(8) for x in s]
+        a = [math.exp(x - max(z)) for x in z]
+        tot = sum(a)
+        best = max(itertools.combinations(range(n), k), key=lambda S: sum(a[j] for j in S))
+        assert set(best) == set(r["ids"][h])
+        S = order[:k]
+        den = sum(a[j] for j in S)
+        o = [sum(a[j] / den * Vf[j, 0, c] for j in S) for c in range(8)]
+        np.testing.assert_allclose(r["out"][h], o, rtol=0, atol=1e-13)
+        assert sum(a[j] for j in S) / tot <= 1.0
+
+
+def test_ties_prefer_smaller_index():
+    """Equal scores at the k-th place: the earlier token wins (this build's reading; the paper is silent)."""
+    s = np.array([1.0, 5.0, 3.0, 3.0, 3.0, 0.0, 3.0])
+    assert list(oracle.select_topk(s, 1)) == [1]
+    assert list(oracle.select_topk(s, 2)) == [1, 2]
+    assert list(oracle.select_topk(s, 3)) == [1, 2, 3]
+    assert list(oracle.select_topk(s, 4)) == [1, 2, 3, 4]
+    assert list(oracle.select_topk(s, 5)) == [1, 2, 3, 4, 6]
+    assert list(oracle.select_topk(s, 6)) == [0, 1, 2, 3, 4, 6]
+    K = np.ones((5, 1, 4), dtype=np.float32)           # duplicate keys are legal
+    V = np.arange(20, dtype=np.float32).reshape(5, 1, 4)
+    q = np.ones((1, 4), dtype=np.float32)
+    r = oracle.sparse_attn(q, K, V, oracle.TOPK, k=2)
+    assert list(r["ids"][0]) == [0, 1]
+    np.testing.assert_allclose(r["out"][0], V[:2, 0].mean(axis=0))
+
+
+# ---------------------------------------------------------------- P9: partial attention merge
+def test_partial_attention_merge():
+    """Sec. 6.2, data-centric engine: parts computed independently and merged by (max, sum, acc) equal one pass."""
+    w, q, K, V = _small(17, n=222, hq=2, hk=1, d=16)
+    s, _, _ = _dense(q, K, V, "f32")
+    rng = np.random.default_rng(1)
+    for h in range(2):
+        ids = oracle.select_topk(s[h], 50)
+        whole = oracle.attend(s[h], V, 0, ids)
+        cut = np.sort(rng.choice(np.arange(1, 50), size=3, replace=False))
+        parts = np.split(rng.permutation(ids), cut)
+        scale = 1 / math.sqrt(16)
+        m = [float((s[h][p] * scale).max()) for p in parts]
+        l = [float(np.exp(s[h][p] * scale - mi).sum()) for p, mi in zip(parts, m)]
+        o = [oracle.attend(s[h], V, 0, np.sort(p)) for p in parts]
+        M = max(m)
+        wts = np.array([li * math.exp(mi - M) for li, mi in zip(l, m)])
+        merged = sum(wi * oi for wi, oi in zip(wts, o)) / wts.sum()
+        np.testing.assert_allclose(merged, whole, rtol=0, atol=1e-13)
+
+
+# ---------------------------------------------------------------- P10: GQA
+def test_gqa_equals_replicated_mha():
+    """Sec. 6.2, GQA: the heads of a group query the same key/value head."""
+    w, q, K, V = _small(19, n=140, hq=8, hk=2, d=16)
+    G = w.group
+    Kr, Vr = np.repeat(K, G, axis=1), np.repeat(V, G, axis=1)
+    for mode, kw in [(oracle.TOPK, dict(k=9)), (oracle.DIPR, dict(beta=2.0)), (oracle.FULL, {})]:
+        a = oracle.sparse_attn(q, K, V, mode, **kw)
+        b = oracle.sparse_attn(q, Kr, Vr, mode, **kw)
+        np.testing.assert_allclose(a["out"], b["out"], rtol=0, atol=1e-14)
+        assert all((x == y).all() for x, y in zip(a["ids"], b["ids"]))
+    # and the heads of one group do differ from each other (a wrong head index would hide behind symmetry)
+    a = oracle.sparse_attn(q, K, V, oracle.TOPK, k=9)
+    assert not np.allclose(a["out"][0], a["out"][1])
+    assert not np.allclose(a["out"][0], a["out"][G])
+
+
+# ---------------------------------------------------------------- P11: shift and scale
+def test_shift_and_scale_invariance():
+    """Def. 2 and softmax: adding c to every key shifts all scores by q.c; scaling q scales beta."""
+    w, q, K, V = _small(23, n=160, hq=2, hk=1, d=8)
+    # use exactly representable numbers so the shift itself adds no rounding
+    q = np.round(q * 8) / 8
+    K = np.round(K * 8) / 8
+    c = (np.arange(8, dtype=np.float32) - 3.0) / 4.0
+    Ks = (K + c).astype(np.float32)
+    for mode, kw in [(oracle.TOPK, dict(k=11)), (oracle.DIPR, dict(beta=1.25))]:
+        a = oracle.sparse_attn(q.astype(np.float32), K.astype(np.float32), V, mode, **kw)
+        b = oracle.sparse_attn(q.astype(np.float32), Ks, V, mode, **kw)
+        assert all((x == y).all() for x, y in zip(a["ids"], b["ids"]))
+        np.testing.assert_allclose(a["out"], b["out"], rtol=0, atol=1e-12)
+    a = oracle.sparse_attn(q.astype(np.float32), K.astype(np.float32), V, oracle.DIPR, beta=1.25)
+    b = oracle.sparse_attn((2 * q).astype(np.float32), K.astype(np.float32), V, oracle.DIPR, beta=2.5)
+    assert all((x == y).all() for x, y in zip(a["ids"], b["ids"]))
+    a = oracle.sparse_attn(q.astype(np.float32), K.astype(np.float32), V, oracle.TOPK, k=11)
+    b = oracle.sparse_attn((2 * q).astype(np.float32), K.astype(np.float32), V, oracle.TOPK, k=11)
+    assert all((x == y).all() for x, y in zip(a["ids"], b["ids"]))
+
+
+# ---------------------------------------------------------------- P12: convex hull
+def test_output_in_hull_of_selected_values():
+    w, q, K, V = _small(29, n=130)
+    r = oracle.sparse_attn(q, K, V, oracle.TOPK, k=13)
+    Vf = V.astype(np.float64)
+    for h in range(w.n_q_heads):
+        rows = Vf[r["ids"][h], h // w.group]
+        assert (r["out"][h] >= rows.min(axis=0) - 1e-12).all() and (r["out"][h] <= rows.max(axis=0) + 1e-12).all()
+
+
+# ---------------------------------------------------------------- argument handling
+def test_invalid_arguments():
+    w, q, K, V = _small(0, n=10)
+    with pytest.raises(ValueError):
+        oracle.sparse_attn(q, K, V, oracle.TOPK, k=0)
+    with pytest.raises(ValueError):
+        oracle.sparse_attn(q, K, V, oracle.DIPR, beta=-1.0)
+    with pytest.raises(ValueError):
+        oracle.sparse_attn(q, K, V, oracle.DIPR, beta=float("nan"))
+
+
+def test_bf16_widening_is_exact():
+    """bf16 bits are widened exactly: a score of bf16 inputs equals the fp64 sum of exact products."""
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((7, 1, 16)).astype(np.float32)
+    kb = wl.to_bf16_bits(x)
+    qb = wl.to_bf16_bits(rng.standard_normal(16).astype(np.float32))
+    kf, qf = wl.bf16_bits_to_f32(kb).astype(np.float64), wl.bf16_bits_to_f32(qb).astype(np.float64)
+    np.testing.assert_allclose(oracle.scores(qb, kb, 0), kf[:, 0, :] @ qf, rtol=0, atol=1e-14)
+    # round-to-nearest-even of the generator: 1 + 2^-8 is a tie and goes to the even mantissa (1.0)
+    assert wl.to_bf16_bits(np.array([1.0 + 2.0 ** -8], dtype=np.float32))[0] == 0x3F80
+    assert wl.to_bf16_bits(np.array([1.0 + 3 * 2.0 ** -8], dtype=np.float32))[0] == 0x3F82
