@@ -1,0 +1,176 @@
+/*
+ * alaya.h - C ABI of the MI355X sparse-attention decode library.
+ *
+ * One alaya_cache is ONE transformer layer's paged key/value store in HBM,
+ * holding many sequences.  Per decode step the caller appends the new token's
+ * key and value (the paper's Session.update, Sec. 5 "User Interface", Table 2)
+ * and then asks for attention of the new query against everything cached (the
+ * paper's Session.attention): score every cached key, select the critical
+ * tokens, and take the softmax-weighted sum of their values.
+ *
+ *   scores      s[h][j] = q_h . k_{h/G, j}         raw inner product, no 1/sqrt(d)  (Eq. 1; Def. 2)
+ *   top-k       the min(k, n) tokens with the largest s[h][.]                        (Sec. 5.1.1)
+ *   DIPR        every j with s[h][j] >= max_j s[h][j] - beta,  beta >= 0            (Def. 2, Def. 3)
+ *   attention   softmax of s * scale over the SELECTED tokens, times their values   (Eq. 1, Sec. 2
+ *               "Sparse Attention"; partial results merged by running max / sum,
+ *               Sec. 6.2 "Data-centric Attention Engine")
+ *   GQA         query head h reads key/value head h / G, G = n_q_heads / n_kv_heads (Sec. 6.2)
+ *
+ * Conventions
+ *   - Every pointer is tagged HOST or DEVICE below.  The library never allocates
+ *     or frees device memory: pools and workspace are the caller's, and stay the
+ *     caller's.  It keeps a few KB of pinned host memory per cache for descriptors.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
+ *     asynchronous on it.  All calls on one cache must use one stream at a time; the
+ *     handle is not thread-safe; distinct caches are independent.
+ *   - Every function returns an alaya_status (or a size / length).  Errors that the
+ *     host can see (bad handle, shapes, k <= 0, beta < 0 or NaN, empty sequence, pool
+ *     exhausted) are returned BEFORE anything is launched and leave the cache unchanged.
+ *     alaya_last_error() gives a thread-local message for the last failure.
+ *   - Only head_dim 64 or 128, page_tokens 64 and G in {1, 2, 4, 8} are built.
+ *   - NaN or Inf in keys, values or queries is undefined behaviour of the arithmetic
+ *     (never of memory safety).
+ */
+#ifndef ALAYA_H
+#define ALAYA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct alaya_cache alaya_cache; /* opaque host-side handle */
+
+typedef enum { ALAYA_BF16 = 0, ALAYA_F32 = 1 } alaya_dtype;
+typedef enum { ALAYA_TOPK = 0, ALAYA_DIPR = 1 } alaya_mode;
+
+typedef enum {
+    ALAYA_OK = 0,
+    ALAYA_E_INVAL = -1,    /* bad argument */
+    ALAYA_E_NOMEM = -2,    /* page pool or workspace too small */
+    ALAYA_E_CAPACITY = -3, /* a selected set was larger than the caller's id buffer */
+    ALAYA_E_EMPTY = -4,    /* a sequence in the call holds no tokens */
+    ALAYA_E_DEVICE = -5    /* a HIP call failed */
+} alaya_status;
+
+/*
+ * Shape of one cache.  Storage layout inside the pools (both are
+ * n_phys_pages * n_kv_heads * 64 * head_dim elements of `dtype`):
+ *   V pool  [phys_page][kv_head][token_in_page (64)][head_dim]                row-major rows
+ *   K pool  [phys_page][kv_head][head_dim / E][token_in_page (64)][E]         E = 16 bytes of elements
+ *           (8 for bf16, 4 for fp32): the 64 tokens of a page are adjacent for each 16-byte slice
+ *           of the head dimension, so that one wavefront (lane = token) reads every slice of a
+ *           page as one contiguous 1 KiB run.
+ * Only alaya_append_kv writes the pools; callers treat them as raw memory.
+ */
+typedef struct {
+    int32_t n_q_heads;          /* query heads per attention call                          */
+    int32_t n_kv_heads;         /* key/value heads; n_q_heads % n_kv_heads == 0            */
+    int32_t head_dim;           /* 64 or 128                                               */
+    int32_t page_tokens;        /* 64                                                      */
+    int32_t dtype;              /* alaya_dtype of K, V and q                               */
+    int32_t max_seqs;           /* sequences the cache can hold (ids 0 .. max_seqs-1)      */
+    int32_t max_batch;          /* requests in one attention call                          */
+    int32_t reserved;           /* 0                                                       */
+    int64_t max_tokens_per_seq; /* longest sequence                                        */
+    int64_t max_batch_tokens;   /* largest sum of sequence lengths in one attention call   */
+    int64_t n_phys_pages;       /* pages in each pool                                      */
+} alaya_cache_config;
+
+/* Bytes of ONE pool (K or V) / of the workspace for this configuration; 0 if cfg is invalid. */
+size_t alaya_pool_bytes(const alaya_cache_config *cfg);
+size_t alaya_workspace_bytes(const alaya_cache_config *cfg);
+
+/*
+ * Create a cache over caller-owned DEVICE memory: k_pool, v_pool (alaya_pool_bytes each) and
+ * workspace (>= alaya_workspace_bytes, 256-byte aligned; holds the page table, scores,
+ * selected ids and partial results - its contents are the library's while the cache lives).
+ * phys_page_order: HOST, optional, n_phys_pages distinct page numbers - the order in which
+ * physical pages are handed to growing sequences (NULL = 0, 1, 2, ...).  Copied.
+ * No device work happens here; the first append or attention call initialises the workspace.
+ */
+int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k_pool, void *v_pool,
+                       const int32_t *phys_page_order, void *workspace, size_t workspace_bytes);
+int alaya_destroy_cache(alaya_cache *c);
+
+/*
+ * Session.update: append t tokens to sequence `seq`.
+ * k, v: DEVICE, [t][n_kv_heads][head_dim] of the cache dtype (token-major, as a model emits them).
+ * Pages are taken from the pool as needed; if it runs out: ALAYA_E_NOMEM and nothing changes.
+ * A token appended here is visible to every later attention call on the same stream
+ * (update, then attention on the whole cache: Sec. 5 "User Interface").
+ */
+int alaya_append_kv(alaya_cache *c, int seq, const void *k, const void *v, int64_t t, void *stream);
+
+/* Tokens cached for seq (host bookkeeping, includes appends still in flight); -1 on a bad argument. */
+int64_t alaya_seq_len(const alaya_cache *c, int seq);
+
+/* Forget seq and return its pages to the pool (host bookkeeping only; the caller must make
+ * sure no launched work still reads the sequence). */
+int alaya_reset_seq(alaya_cache *c, int seq);
+
+typedef struct {
+    int32_t mode;          /* alaya_mode                                                        */
+    int32_t reserved;      /* 0                                                                 */
+    const int32_t *topk;   /* HOST [B], ALAYA_TOPK: per-request k > 0 (k > n means all n)       */
+    const float *beta;     /* HOST [B], ALAYA_DIPR: per-request beta >= 0, +inf allowed         */
+    float scale;           /* softmax scale; 0 means 1 / sqrt(head_dim)                         */
+    int32_t reserved2;     /* 0                                                                 */
+    int32_t *out_ids;      /* DEVICE, optional [B][n_q_heads][ids_stride]: selected token ids   */
+    int32_t *out_counts;   /* DEVICE, optional [B][n_q_heads]: TRUE size of each selected set   */
+    int64_t ids_stride;    /* capacity per head of out_ids                                      */
+} alaya_sparse_params;
+
+/*
+ * Session.attention, sparse: for each request b (sequence seqs[b]) and each query head, score all
+ * cached keys, select (top-k or DIPR), and attend over the selected tokens.
+ *   seqs  HOST [B], distinct or repeated sequence ids      q    DEVICE [B][n_q_heads][head_dim], cache dtype
+ *   out   DEVICE [B][n_q_heads][head_dim], fp32
+ * Selection runs on raw fp32 inner products (bf16 products are exact in fp32; accumulation is fp32).
+ * Among equal scores at the k-th place the smaller token id is taken, so results are reproducible.
+ * out_ids come back in an unspecified but deterministic order.  If a set is larger than ids_stride
+ * the first ids_stride ids are written, out_counts still holds the true size, the attention output
+ * is still over the whole set, and alaya_poll_status reports ALAYA_E_CAPACITY after the stream syncs.
+ */
+int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q,
+                      const alaya_sparse_params *p, float *out, void *stream);
+
+/* Session.attention, dense: Eq. (1) over every cached token (same q / out layout as above). */
+int alaya_full_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q,
+                    float scale, float *out, void *stream);
+
+/* Synchronises `stream`, then returns and clears the device-side status word of the cache:
+ * ALAYA_OK or ALAYA_E_CAPACITY (or ALAYA_E_DEVICE if the sync fails). */
+int alaya_poll_status(alaya_cache *c, void *stream);
+
+/*
+ * Kernel timing with HIP events recorded on the call's own stream.
+ * alaya_set_profiling(c, 1) makes every later call bracket each of its kernels with events;
+ * alaya_kernel_times synchronises them and returns, per kernel slot, the summed duration in
+ * milliseconds and the number of launches since profiling was (re)enabled.
+ * Slots: 0 score, 1 select, 2 attend, 3 combine, 4 full-attention partial, 5 append.
+ * sum_ms, launches: HOST arrays of n_slots entries (n_slots <= ALAYA_N_KERNEL_SLOTS).
+ */
+#define ALAYA_N_KERNEL_SLOTS 6
+int alaya_set_profiling(alaya_cache *c, int enabled);
+int alaya_kernel_times(alaya_cache *c, double *sum_ms, int64_t *launches, int n_slots);
+
+/* Launch-shape knobs for measurement sweeps; each <= 0 keeps the built-in choice.
+ * score_pages_per_wave: pages one wavefront scores in a row (1..64).
+ * attend_splits: workgroups that share one head's selected set (1..64). */
+int alaya_set_tuning(alaya_cache *c, int score_pages_per_wave, int attend_splits);
+
+/* Inspection hook for tests: DEVICE pointer to the fp32 scores the last alaya_sparse_attn call left
+ * in the workspace, request after request, each block [n_q_heads][n_pad] with n_pad = n rounded up to
+ * a whole page (entries j >= n are unspecified).  Valid until the next call on the cache. */
+const float *alaya_debug_scores(const alaya_cache *c);
+
+/* Thread-local description of the last error returned on this thread ("" if none). */
+const char *alaya_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ALAYA_H */

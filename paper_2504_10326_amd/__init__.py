@@ -1,0 +1,309 @@
+"""Python binding of libalaya.so (include/alaya.h): argument marshalling only.
+
+Every step of the decode-step sparse-attention query runs in the HIP kernels
+behind the C ABI.  PyTorch is used for device memory and for the stream handle,
+nothing else.  There is no CPU fallback: if the library has not been built,
+or no GPU is present when a kernel is needed, the call fails loudly.
+
+Module-level functions carry the C names (alaya_create_cache, alaya_append_kv,
+alaya_sparse_attn, alaya_full_attn, ...) and take raw pointers / torch tensors;
+`Cache` bundles a handle with the torch tensors that back its pools.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libalaya.so")
+
+ALAYA_BF16, ALAYA_F32 = 0, 1
+ALAYA_TOPK, ALAYA_DIPR = 0, 1
+ALAYA_OK, ALAYA_E_INVAL, ALAYA_E_NOMEM, ALAYA_E_CAPACITY, ALAYA_E_EMPTY, ALAYA_E_DEVICE = 0, -1, -2, -3, -4, -5
+N_KERNEL_SLOTS = 6
+KERNEL_SLOTS = ("score", "select", "attend", "combine", "full_partial", "append")
+
+EXPORTS = (
+    "alaya_pool_bytes", "alaya_workspace_bytes", "alaya_create_cache", "alaya_destroy_cache",
+    "alaya_append_kv", "alaya_seq_len", "alaya_reset_seq", "alaya_sparse_attn", "alaya_full_attn",
+    "alaya_poll_status", "alaya_set_profiling", "alaya_kernel_times", "alaya_set_tuning", "alaya_debug_scores",
+    "alaya_last_error",
+)
+
+
+class AlayaError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"alaya status {code}: {message}")
+        self.code = code
+
+
+class CacheConfig(ctypes.Structure):
+    _fields_ = [
+        ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+        ("page_tokens", ctypes.c_int32), ("dtype", ctypes.c_int32), ("max_seqs", ctypes.c_int32),
+        ("max_batch", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("max_tokens_per_seq", ctypes.c_int64), ("max_batch_tokens", ctypes.c_int64),
+        ("n_phys_pages", ctypes.c_int64),
+    ]
+
+
+class SparseParams(ctypes.Structure):
+    _fields_ = [
+        ("mode", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("topk", ctypes.POINTER(ctypes.c_int32)), ("beta", ctypes.POINTER(ctypes.c_float)),
+        ("scale", ctypes.c_float), ("reserved2", ctypes.c_int32),
+        ("out_ids", ctypes.c_void_p), ("out_counts", ctypes.c_void_p), ("ids_stride", ctypes.c_int64),
+    ]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded shared library.  Raises if it has not been built (python -m paper_2504_10326_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2504_10326_amd.build`; "
+                               "there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t
+        cfgp = ctypes.POINTER(CacheConfig)
+        L.alaya_pool_bytes.argtypes = [cfgp]; L.alaya_pool_bytes.restype = sz
+        L.alaya_workspace_bytes.argtypes = [cfgp]; L.alaya_workspace_bytes.restype = sz
+        L.alaya_create_cache.argtypes = [ctypes.POINTER(vp), cfgp, vp, vp, ctypes.POINTER(ctypes.c_int32), vp, sz]
+        L.alaya_create_cache.restype = i32
+        L.alaya_destroy_cache.argtypes = [vp]; L.alaya_destroy_cache.restype = i32
+        L.alaya_append_kv.argtypes = [vp, i32, vp, vp, i64, vp]; L.alaya_append_kv.restype = i32
+        L.alaya_seq_len.argtypes = [vp, i32]; L.alaya_seq_len.restype = i64
+        L.alaya_reset_seq.argtypes = [vp, i32]; L.alaya_reset_seq.restype = i32
+        L.alaya_sparse_attn.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), i32, i32, vp,
+                                        ctypes.POINTER(SparseParams), vp, vp]
+        L.alaya_sparse_attn.restype = i32
+        L.alaya_full_attn.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), i32, i32, vp, ctypes.c_float, vp, vp]
+        L.alaya_full_attn.restype = i32
+        L.alaya_poll_status.argtypes = [vp, vp]; L.alaya_poll_status.restype = i32
+        L.alaya_set_profiling.argtypes = [vp, i32]; L.alaya_set_profiling.restype = i32
+        L.alaya_kernel_times.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64), i32]
+        L.alaya_kernel_times.restype = i32
+        L.alaya_set_tuning.argtypes = [vp, i32, i32]; L.alaya_set_tuning.restype = i32
+        L.alaya_debug_scores.argtypes = [vp]; L.alaya_debug_scores.restype = vp
+        L.alaya_last_error.argtypes = []; L.alaya_last_error.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def alaya_last_error() -> str:
+    return lib().alaya_last_error().decode()
+
+
+def _check(rc: int) -> None:
+    if rc != ALAYA_OK:
+        raise AlayaError(rc, alaya_last_error())
+
+
+def _i32_array(xs: Optional[Sequence[int]]):
+    if xs is None:
+        return None
+    return (ctypes.c_int32 * len(xs))(*[int(x) for x in xs])
+
+
+def _f32_array(xs: Optional[Sequence[float]]):
+    if xs is None:
+        return None
+    return (ctypes.c_float * len(xs))(*[float(x) for x in xs])
+
+
+def _ptr(t) -> Optional[int]:
+    """Device pointer of a torch tensor (or an int passed through)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+# ---- functions with the C names -------------------------------------------------------------------
+
+def alaya_pool_bytes(cfg: CacheConfig) -> int:
+    return lib().alaya_pool_bytes(ctypes.byref(cfg))
+
+
+def alaya_workspace_bytes(cfg: CacheConfig) -> int:
+    return lib().alaya_workspace_bytes(ctypes.byref(cfg))
+
+
+def alaya_create_cache(cfg: CacheConfig, k_pool, v_pool, phys_page_order: Optional[Sequence[int]],
+                       workspace, workspace_bytes: int) -> int:
+    h = ctypes.c_void_p()
+    order = None
+    if phys_page_order is not None:
+        import numpy as np
+        arr = np.ascontiguousarray(np.asarray(phys_page_order, dtype=np.int32))
+        order = arr.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    _check(lib().alaya_create_cache(ctypes.byref(h), ctypes.byref(cfg), _ptr(k_pool), _ptr(v_pool), order,
+                                    _ptr(workspace), workspace_bytes))
+    return h.value
+
+
+def alaya_destroy_cache(handle: int) -> None:
+    _check(lib().alaya_destroy_cache(handle))
+
+
+def alaya_append_kv(handle: int, seq: int, k, v, t: int, stream=0) -> None:
+    _check(lib().alaya_append_kv(handle, seq, _ptr(k), _ptr(v), t, stream or None))
+
+
+def alaya_seq_len(handle: int, seq: int) -> int:
+    return lib().alaya_seq_len(handle, seq)
+
+
+def alaya_reset_seq(handle: int, seq: int) -> None:
+    _check(lib().alaya_reset_seq(handle, seq))
+
+
+def alaya_sparse_attn(handle: int, seqs: Sequence[int], n_q_heads: int, q, mode: int,
+                      topk: Optional[Sequence[int]], beta: Optional[Sequence[float]], scale: float, out,
+                      out_ids=None, out_counts=None, ids_stride: int = 0, stream=0) -> None:
+    p = SparseParams()
+    p.mode = mode
+    tk, bt = _i32_array(topk), _f32_array(beta)
+    p.topk = ctypes.cast(tk, ctypes.POINTER(ctypes.c_int32)) if tk is not None else None
+    p.beta = ctypes.cast(bt, ctypes.POINTER(ctypes.c_float)) if bt is not None else None
+    p.scale = scale
+    p.out_ids = _ptr(out_ids)
+    p.out_counts = _ptr(out_counts)
+    p.ids_stride = ids_stride
+    sq = _i32_array(seqs)
+    _check(lib().alaya_sparse_attn(handle, sq, len(seqs), n_q_heads, _ptr(q), ctypes.byref(p), _ptr(out),
+                                   stream or None))
+
+
+def alaya_full_attn(handle: int, seqs: Sequence[int], n_q_heads: int, q, scale: float, out, stream=0) -> None:
+    sq = _i32_array(seqs)
+    _check(lib().alaya_full_attn(handle, sq, len(seqs), n_q_heads, _ptr(q), scale, _ptr(out), stream or None))
+
+
+def alaya_poll_status(handle: int, stream=0) -> int:
+    return lib().alaya_poll_status(handle, stream or None)
+
+
+# ---- a handle bundled with the torch memory behind it ---------------------------------------------
+
+class Cache:
+    """One layer's paged KV store on one GPU.  torch allocates the pools and the workspace."""
+
+    def __init__(self, n_q_heads: int, n_kv_heads: int, head_dim: int, dtype: str, max_seqs: int,
+                 max_batch: int, max_tokens_per_seq: int, max_batch_tokens: int, n_phys_pages: int,
+                 phys_page_order: Optional[Sequence[int]] = None, device: str = "cuda:0"):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: the sparse-attention path has no CPU fallback")
+        self.torch = torch
+        self.device = torch.device(device)
+        self.dtype = {"bf16": ALAYA_BF16, "f32": ALAYA_F32}[dtype]
+        self.torch_dtype = torch.bfloat16 if dtype == "bf16" else torch.float32
+        cfg = CacheConfig(n_q_heads, n_kv_heads, head_dim, 64, self.dtype, max_seqs, max_batch, 0,
+                          max_tokens_per_seq, max_batch_tokens, n_phys_pages)
+        self.cfg = cfg
+        pool, ws = alaya_pool_bytes(cfg), alaya_workspace_bytes(cfg)
+        if pool == 0 or ws == 0:
+            raise AlayaError(ALAYA_E_INVAL, "invalid cache configuration")
+        self.k_pool = torch.empty(pool, dtype=torch.uint8, device=self.device)
+        self.v_pool = torch.empty(pool, dtype=torch.uint8, device=self.device)
+        self.workspace = torch.empty(ws, dtype=torch.uint8, device=self.device)
+        self.workspace_bytes = ws
+        self.handle = alaya_create_cache(cfg, self.k_pool, self.v_pool, phys_page_order, self.workspace, ws)
+
+    def close(self) -> None:
+        if getattr(self, "handle", None):
+            self.torch.cuda.synchronize(self.device)
+            alaya_destroy_cache(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- Session.update
+    def append_kv(self, seq: int, k, v, stream=None) -> None:
+        assert k.is_cuda and v.is_cuda and k.is_contiguous() and v.is_contiguous()
+        assert k.dtype == self.torch_dtype and v.dtype == self.torch_dtype and k.shape == v.shape
+        assert tuple(k.shape[1:]) == (self.cfg.n_kv_heads, self.cfg.head_dim)
+        alaya_append_kv(self.handle, seq, k, v, k.shape[0], _stream(stream))
+
+    def seq_len(self, seq: int) -> int:
+        return alaya_seq_len(self.handle, seq)
+
+    def reset_seq(self, seq: int) -> None:
+        alaya_reset_seq(self.handle, seq)
+
+    # -- Session.attention
+    def _q_out(self, seqs, q):
+        B = len(seqs)
+        assert q.is_cuda and q.is_contiguous() and q.dtype == self.torch_dtype
+        assert tuple(q.shape) == (B, self.cfg.n_q_heads, self.cfg.head_dim)
+        return self.torch.empty((B, self.cfg.n_q_heads, self.cfg.head_dim), dtype=self.torch.float32,
+                                device=self.device)
+
+    def sparse_attn(self, seqs: Sequence[int], q, mode: int, topk=None, beta=None, scale: float = 0.0,
+                    ids_stride: int = 0, out=None, stream=None):
+        """Returns out [B][Hq][d] fp32, or (out, ids [B][Hq][ids_stride] int32, counts [B][Hq] int32)."""
+        if out is None:
+            out = self._q_out(seqs, q)
+        ids = counts = None
+        if ids_stride > 0:
+            ids = self.torch.full((len(seqs), self.cfg.n_q_heads, ids_stride), -1, dtype=self.torch.int32,
+                                  device=self.device)
+            counts = self.torch.zeros((len(seqs), self.cfg.n_q_heads), dtype=self.torch.int32, device=self.device)
+        alaya_sparse_attn(self.handle, seqs, self.cfg.n_q_heads, q, mode, topk, beta, scale, out, ids, counts,
+                          ids_stride, _stream(stream))
+        return out if ids is None else (out, ids, counts)
+
+    def full_attn(self, seqs: Sequence[int], q, scale: float = 0.0, out=None, stream=None):
+        if out is None:
+            out = self._q_out(seqs, q)
+        alaya_full_attn(self.handle, seqs, self.cfg.n_q_heads, q, scale, out, _stream(stream))
+        return out
+
+    def poll_status(self, stream=None) -> int:
+        return alaya_poll_status(self.handle, _stream(stream))
+
+    # -- measurement
+    def set_profiling(self, enabled: bool) -> None:
+        _check(lib().alaya_set_profiling(self.handle, int(enabled)))
+
+    def kernel_times(self) -> dict:
+        ms = (ctypes.c_double * N_KERNEL_SLOTS)()
+        n = (ctypes.c_int64 * N_KERNEL_SLOTS)()
+        _check(lib().alaya_kernel_times(self.handle, ms, n, N_KERNEL_SLOTS))
+        return {name: {"sum_ms": ms[i], "launches": n[i]} for i, name in enumerate(KERNEL_SLOTS)}
+
+    def debug_scores(self, lens: Sequence[int]):
+        """fp32 scores of the last sparse call as a list of torch views [Hq][n] (one per request)."""
+        torch = self.torch
+        base = lib().alaya_debug_scores(self.handle)
+        off = base - self.workspace.data_ptr()
+        views = []
+        for n in lens:
+            n_pad = (n + 63) // 64 * 64
+            nbytes = self.cfg.n_q_heads * n_pad * 4
+            blk = self.workspace[off:off + nbytes].view(torch.float32).view(self.cfg.n_q_heads, n_pad)
+            views.append(blk[:, :n])
+            off += nbytes
+        return views
+
+    def set_tuning(self, score_pages_per_wave: int = 0, attend_splits: int = 0) -> None:
+        _check(lib().alaya_set_tuning(self.handle, score_pages_per_wave, attend_splits))

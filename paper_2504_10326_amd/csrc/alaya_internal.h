@@ -1,0 +1,88 @@
+// Internal declarations shared by the host side (api.hip) and the kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace alaya {
+
+constexpr int kPageTokens = 64;      // one page == one wavefront of tokens
+constexpr int kScoreWaves = 4;       // wavefronts per scoring workgroup
+constexpr int kSelectThreads = 1024; // one workgroup selects for one (request, query head)
+constexpr int kAttendThreads = 256;
+constexpr int kMaxSplits = 64;
+
+// Per-request descriptor, built on the host for every attention call and copied to the device.
+struct ReqDesc {
+    int32_t pt_off;      // first entry of this sequence's row in the device page table
+    int32_t n;           // cached tokens
+    int32_t n_pad;       // n rounded up to whole pages: stride between heads in the score arrays
+    int32_t k;           // top-k, already clamped to n (0 in DIPR mode)
+    float beta;          // DIPR margin (raw inner-product units)
+    int32_t tile_start;  // first scoring / full-attention tile of this request (prefix sum)
+    int64_t score_off;   // offset (elements) of this request's [n_q_heads][n_pad] block
+};
+static_assert(sizeof(ReqDesc) == 32, "ReqDesc layout");
+
+// Device views handed to the launchers.
+struct DeviceViews {
+    const ReqDesc *desc;       // [B]
+    const int32_t *page_table; // [max_seqs][max_pages_per_seq]
+    const void *k_pool;
+    const void *v_pool;
+    float *scores;             // [sum n_pad * n_q_heads]
+    int32_t *sel_ids;          // same extent
+    float *sel_scores;         // same extent
+    uint32_t *head_max;        // [max_batch * n_q_heads], order-preserving image of the running max
+    float *head_M;             // [max_batch * n_q_heads], the max as a float, once selection has read it
+    int32_t *counts;           // [max_batch * n_q_heads]
+    float *partials;           // attend / full-attention partial results
+    int32_t *status;           // device status word
+};
+
+struct Shape {
+    int dtype;      // alaya_dtype
+    int head_dim;
+    int n_q_heads;
+    int n_kv_heads;
+};
+
+// Launchers (one per kernel family).  Each returns the hipError_t of its launch.
+hipError_t launch_append(const Shape &sh, const int32_t *page_table_row, void *k_pool, void *v_pool,
+                         const void *k, const void *v, int64_t n_old, int64_t t, hipStream_t st);
+
+hipError_t launch_score(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles,
+                        int pages_per_wave, hipStream_t st);
+
+hipError_t launch_select(const Shape &sh, const DeviceViews &dv, int B, int mode, int32_t *out_ids,
+                         int32_t *out_counts, int64_t ids_stride, hipStream_t st);
+
+hipError_t launch_attend(const Shape &sh, const DeviceViews &dv, int B, float scale, int splits,
+                         hipStream_t st);
+
+// partial layout: [slot][head_dim + 2] = {m (already times scale), l, acc[head_dim]}
+// sparse: slot = (b * n_q_heads + h) * splits + s           (per_request_tiles == 0)
+// full  : slot = (tile_start[b] + t) * n_q_heads + h        (per_request_tiles == 1)
+hipError_t launch_combine(const Shape &sh, const DeviceViews &dv, int B, int splits, int per_request_tiles,
+                          int pages_per_tile, float *out, hipStream_t st);
+
+hipError_t launch_full_partial(const Shape &sh, const DeviceViews &dv, int B, const void *q, float scale,
+                               int total_tiles, int pages_per_tile, hipStream_t st);
+
+hipError_t launch_fill_u32(uint32_t *p, size_t n, uint32_t v, hipStream_t st);
+
+// ---- device helpers ---------------------------------------------------------------------------
+
+// Order-preserving map float -> uint32 (larger float <=> larger unsigned).  0 is below every float.
+__device__ __forceinline__ uint32_t ord_key(float x)
+{
+    uint32_t b = __float_as_uint(x);
+    if (b == 0x80000000u) b = 0u; // -0 and +0 are one score
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float ord_float(uint32_t k)
+{
+    uint32_t b = (k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k;
+    return __uint_as_float(b);
+}
+
+} // namespace alaya

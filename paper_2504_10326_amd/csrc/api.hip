@@ -1,0 +1,568 @@
+// Host side of the C ABI declared in include/alaya.h: argument checks, the page allocator and page
+// table, per-call descriptors, launch shapes, event timing.  No device memory is allocated here.
+#include "../../include/alaya.h"
+#include "alaya_internal.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace alaya;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+int fail_hip(hipError_t e, const char *what)
+{
+    return fail(ALAYA_E_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+constexpr int kRing = 16;          // descriptor slots in pinned host memory
+constexpr int kProfPairs = 1024;   // event pairs before a forced harvest
+constexpr int kTargetGroups = 2048;
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+bool cfg_ok(const alaya_cache_config *c)
+{
+    if (!c) return false;
+    if (c->head_dim != 64 && c->head_dim != 128) return false;
+    if (c->page_tokens != kPageTokens) return false;
+    if (c->dtype != ALAYA_BF16 && c->dtype != ALAYA_F32) return false;
+    if (c->n_kv_heads <= 0 || c->n_q_heads <= 0 || c->n_q_heads % c->n_kv_heads) return false;
+    const int G = c->n_q_heads / c->n_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return false;
+    if (c->max_seqs <= 0 || c->max_batch <= 0 || c->max_tokens_per_seq <= 0 || c->max_batch_tokens <= 0) return false;
+    if (c->n_phys_pages <= 0 || c->n_phys_pages > INT32_MAX) return false;
+    if (c->max_tokens_per_seq > (int64_t)INT32_MAX - 64) return false; // token ids are int32
+    const int64_t mpps = (c->max_tokens_per_seq + kPageTokens - 1) / kPageTokens;
+    if (mpps * c->max_seqs > INT32_MAX) return false;                 // page-table offsets are int32
+    return true;
+}
+
+struct Layout {
+    size_t page_table, desc, scores, sel_ids, sel_scores, head_max, head_M, counts, partials, status, total;
+    int64_t mpps;        // max pages per sequence
+    int64_t score_elems; // capacity of each of scores / sel_ids / sel_scores
+    int64_t max_tiles;   // full-attention tiles
+};
+
+Layout make_layout(const alaya_cache_config &c)
+{
+    Layout L{};
+    L.mpps = (c.max_tokens_per_seq + kPageTokens - 1) / kPageTokens;
+    L.score_elems = (int64_t)c.n_q_heads * (c.max_batch_tokens + (int64_t)kPageTokens * c.max_batch);
+    L.max_tiles = kTargetGroups / c.n_kv_heads + 1 + c.max_batch;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    L.page_table = take((size_t)L.mpps * c.max_seqs * sizeof(int32_t));
+    L.desc = take((size_t)c.max_batch * sizeof(ReqDesc));
+    L.scores = take((size_t)L.score_elems * sizeof(float));
+    L.sel_ids = take((size_t)L.score_elems * sizeof(int32_t));
+    L.sel_scores = take((size_t)L.score_elems * sizeof(float));
+    L.head_max = take((size_t)c.max_batch * c.n_q_heads * sizeof(uint32_t));
+    L.head_M = take((size_t)c.max_batch * c.n_q_heads * sizeof(float));
+    L.counts = take((size_t)c.max_batch * c.n_q_heads * sizeof(int32_t));
+    const size_t sparse_slots = (size_t)c.max_batch * c.n_q_heads * kMaxSplits;
+    const size_t full_slots = (size_t)L.max_tiles * c.n_q_heads;
+    L.partials = take((sparse_slots > full_slots ? sparse_slots : full_slots) * (c.head_dim + 2) * sizeof(float));
+    L.status = take(256);
+    L.total = o;
+    return L;
+}
+
+} // namespace
+
+struct alaya_cache {
+    alaya_cache_config cfg;
+    Layout L;
+    char *ws;
+    void *k_pool, *v_pool;
+    DeviceViews dv;
+    // host bookkeeping
+    std::vector<int32_t> free_pages; // stack: back() is handed out next
+    std::vector<int64_t> seq_len;
+    int32_t *h_page_table;           // pinned when a device is present
+    bool h_page_table_pinned;
+    ReqDesc *h_desc;                 // pinned ring [kRing][max_batch]
+    hipEvent_t ring_ev[kRing];
+    bool ring_used[kRing];
+    int ring_pos;
+    bool dev_ready;
+    int tune_ppw, tune_splits;
+    // profiling
+    bool prof;
+    std::vector<hipEvent_t> ev;      // 2 * kProfPairs, created on demand
+    int ev_slot[kProfPairs];
+    int ev_n;
+    double sum_ms[ALAYA_N_KERNEL_SLOTS];
+    int64_t launches[ALAYA_N_KERNEL_SLOTS];
+};
+
+namespace {
+
+int harvest(alaya_cache *c)
+{
+    for (int i = 0; i < c->ev_n; ++i) {
+        hipError_t e = hipEventSynchronize(c->ev[2 * i + 1]);
+        if (e != hipSuccess) return fail_hip(e, "hipEventSynchronize");
+        float ms = 0.f;
+        e = hipEventElapsedTime(&ms, c->ev[2 * i], c->ev[2 * i + 1]);
+        if (e != hipSuccess) return fail_hip(e, "hipEventElapsedTime");
+        c->sum_ms[c->ev_slot[i]] += ms;
+        c->launches[c->ev_slot[i]] += 1;
+    }
+    c->ev_n = 0;
+    return ALAYA_OK;
+}
+
+// Brackets one launch with events when profiling is on.
+struct Timed {
+    alaya_cache *c;
+    hipStream_t st;
+    int idx;
+    Timed(alaya_cache *c_, int slot, hipStream_t st_) : c(c_), st(st_), idx(-1)
+    {
+        if (!c->prof) return;
+        if (c->ev_n == kProfPairs && harvest(c) != ALAYA_OK) return;
+        if (c->ev.empty()) {
+            c->ev.resize(2 * kProfPairs);
+            for (auto &e : c->ev)
+                if (hipEventCreate(&e) != hipSuccess) { c->ev.clear(); return; }
+        }
+        idx = c->ev_n++;
+        c->ev_slot[idx] = slot;
+        (void)hipEventRecord(c->ev[2 * idx], st);
+    }
+    ~Timed()
+    {
+        if (idx >= 0) (void)hipEventRecord(c->ev[2 * idx + 1], st);
+    }
+};
+
+int ensure_device(alaya_cache *c, hipStream_t st)
+{
+    if (c->dev_ready) return ALAYA_OK;
+    const size_t nh = (size_t)c->cfg.max_batch * c->cfg.n_q_heads;
+    hipError_t e = launch_fill_u32(c->dv.head_max, nh, 0u, st);
+    if (e == hipSuccess) e = launch_fill_u32((uint32_t *)c->dv.status, 1, 0u, st);
+    if (e != hipSuccess) return fail_hip(e, "workspace initialisation");
+    c->dev_ready = true;
+    return ALAYA_OK;
+}
+
+// Reserve the next descriptor slot; waits only if the copy issued kRing calls ago is still pending.
+int ring_acquire(alaya_cache *c, ReqDesc **slot, int *idx)
+{
+    const int i = c->ring_pos;
+    if (c->ring_used[i]) {
+        hipError_t e = hipEventSynchronize(c->ring_ev[i]);
+        if (e != hipSuccess) return fail_hip(e, "hipEventSynchronize(descriptor ring)");
+    }
+    *slot = c->h_desc + (size_t)i * c->cfg.max_batch;
+    *idx = i;
+    return ALAYA_OK;
+}
+
+int ring_publish(alaya_cache *c, int idx, int B, hipStream_t st)
+{
+    hipError_t e = hipMemcpyAsync((void *)c->dv.desc, c->h_desc + (size_t)idx * c->cfg.max_batch,
+                                  (size_t)B * sizeof(ReqDesc), hipMemcpyHostToDevice, st);
+    if (e != hipSuccess) return fail_hip(e, "descriptor copy");
+    e = hipEventRecord(c->ring_ev[idx], st);
+    if (e != hipSuccess) return fail_hip(e, "hipEventRecord");
+    c->ring_used[idx] = true;
+    c->ring_pos = (idx + 1) % kRing;
+    return ALAYA_OK;
+}
+
+// Checks shared by both attention calls; fills n[] with the sequence lengths.
+int check_call(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q, const float *out,
+               int64_t *total_pages, int64_t *total_tokens)
+{
+    if (!c) return fail(ALAYA_E_INVAL, "null cache handle");
+    if (!seqs || !q || !out) return fail(ALAYA_E_INVAL, "null seqs, q or out");
+    if (B <= 0 || B > c->cfg.max_batch) return fail(ALAYA_E_INVAL, "batch %d outside 1..%d", B, c->cfg.max_batch);
+    if (n_q_heads != c->cfg.n_q_heads)
+        return fail(ALAYA_E_INVAL, "n_q_heads %d differs from the cache's %d", n_q_heads, c->cfg.n_q_heads);
+    int64_t pages = 0, toks = 0;
+    for (int b = 0; b < B; ++b) {
+        if (seqs[b] < 0 || seqs[b] >= c->cfg.max_seqs)
+            return fail(ALAYA_E_INVAL, "request %d: sequence id %d outside 0..%d", b, seqs[b], c->cfg.max_seqs - 1);
+        const int64_t n = c->seq_len[seqs[b]];
+        if (n <= 0) return fail(ALAYA_E_EMPTY, "request %d: sequence %d holds no tokens", b, seqs[b]);
+        pages += (n + kPageTokens - 1) / kPageTokens;
+        toks += n;
+    }
+    if (toks > c->cfg.max_batch_tokens)
+        return fail(ALAYA_E_NOMEM, "call covers %lld tokens, workspace was sized for %lld", (long long)toks,
+                    (long long)c->cfg.max_batch_tokens);
+    *total_pages = pages;
+    *total_tokens = toks;
+    return ALAYA_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+const char *alaya_last_error(void) { return g_err.c_str(); }
+
+size_t alaya_pool_bytes(const alaya_cache_config *cfg)
+{
+    if (!cfg_ok(cfg)) return 0;
+    return (size_t)cfg->n_phys_pages * cfg->n_kv_heads * kPageTokens * cfg->head_dim *
+           (cfg->dtype == ALAYA_BF16 ? 2 : 4);
+}
+
+size_t alaya_workspace_bytes(const alaya_cache_config *cfg)
+{
+    if (!cfg_ok(cfg)) return 0;
+    return make_layout(*cfg).total;
+}
+
+int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k_pool, void *v_pool,
+                       const int32_t *phys_page_order, void *workspace, size_t workspace_bytes)
+{
+    if (!out) return fail(ALAYA_E_INVAL, "null out pointer");
+    *out = nullptr;
+    if (!cfg_ok(cfg)) return fail(ALAYA_E_INVAL, "invalid cache configuration");
+    if (!k_pool || !v_pool || !workspace) return fail(ALAYA_E_INVAL, "null pool or workspace");
+    if (((uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)workspace) & 255)
+        return fail(ALAYA_E_INVAL, "pools and workspace must be 256-byte aligned");
+    const Layout L = make_layout(*cfg);
+    if (workspace_bytes < L.total)
+        return fail(ALAYA_E_NOMEM, "workspace has %zu bytes, %zu needed", workspace_bytes, L.total);
+    const int64_t np = cfg->n_phys_pages;
+    std::vector<int32_t> order((size_t)np);
+    if (phys_page_order) {
+        std::vector<char> seen((size_t)np, 0);
+        for (int64_t i = 0; i < np; ++i) {
+            const int32_t p = phys_page_order[i];
+            if (p < 0 || p >= np || seen[(size_t)p]) return fail(ALAYA_E_INVAL, "phys_page_order is not a permutation");
+            seen[(size_t)p] = 1;
+            order[(size_t)i] = p;
+        }
+    } else {
+        for (int64_t i = 0; i < np; ++i) order[(size_t)i] = (int32_t)i;
+    }
+    alaya_cache *c = new (std::nothrow) alaya_cache();
+    if (!c) return fail(ALAYA_E_NOMEM, "host allocation failed");
+    c->cfg = *cfg;
+    c->L = L;
+    c->ws = (char *)workspace;
+    c->k_pool = k_pool;
+    c->v_pool = v_pool;
+    c->dv.desc = (const ReqDesc *)(c->ws + L.desc);
+    c->dv.page_table = (const int32_t *)(c->ws + L.page_table);
+    c->dv.k_pool = k_pool;
+    c->dv.v_pool = v_pool;
+    c->dv.scores = (float *)(c->ws + L.scores);
+    c->dv.sel_ids = (int32_t *)(c->ws + L.sel_ids);
+    c->dv.sel_scores = (float *)(c->ws + L.sel_scores);
+    c->dv.head_max = (uint32_t *)(c->ws + L.head_max);
+    c->dv.head_M = (float *)(c->ws + L.head_M);
+    c->dv.counts = (int32_t *)(c->ws + L.counts);
+    c->dv.partials = (float *)(c->ws + L.partials);
+    c->dv.status = (int32_t *)(c->ws + L.status);
+    c->free_pages.assign(order.rbegin(), order.rend()); // back() == first page of the order
+    c->seq_len.assign((size_t)cfg->max_seqs, 0);
+    const size_t pt_bytes = (size_t)L.mpps * cfg->max_seqs * sizeof(int32_t);
+    const size_t ring_bytes = (size_t)kRing * cfg->max_batch * sizeof(ReqDesc);
+    // Pinned host memory lets the table and descriptor copies run asynchronously.  Without a device
+    // (host-only use: argument and allocator checks) plain memory serves.
+    void *p = nullptr;
+    if (hipHostMalloc(&p, pt_bytes + ring_bytes, hipHostMallocDefault) == hipSuccess) {
+        c->h_page_table_pinned = true;
+    } else {
+        (void)hipGetLastError();
+        p = malloc(pt_bytes + ring_bytes);
+        c->h_page_table_pinned = false;
+        if (!p) { delete c; return fail(ALAYA_E_NOMEM, "host allocation failed"); }
+    }
+    c->h_page_table = (int32_t *)p;
+    c->h_desc = (ReqDesc *)((char *)p + pt_bytes);
+    for (int i = 0; i < kRing; ++i) { c->ring_ev[i] = nullptr; c->ring_used[i] = false; }
+    c->ring_pos = 0;
+    c->dev_ready = false;
+    c->tune_ppw = 0;
+    c->tune_splits = 0;
+    c->prof = false;
+    c->ev_n = 0;
+    for (int i = 0; i < ALAYA_N_KERNEL_SLOTS; ++i) { c->sum_ms[i] = 0.0; c->launches[i] = 0; }
+    *out = c;
+    return ALAYA_OK;
+}
+
+int alaya_destroy_cache(alaya_cache *c)
+{
+    if (!c) return fail(ALAYA_E_INVAL, "null cache handle");
+    for (int i = 0; i < kRing; ++i)
+        if (c->ring_ev[i]) { (void)hipEventSynchronize(c->ring_ev[i]); (void)hipEventDestroy(c->ring_ev[i]); }
+    for (auto &e : c->ev) (void)hipEventDestroy(e);
+    if (c->h_page_table_pinned) (void)hipHostFree(c->h_page_table);
+    else free(c->h_page_table);
+    delete c;
+    return ALAYA_OK;
+}
+
+int64_t alaya_seq_len(const alaya_cache *c, int seq)
+{
+    if (!c || seq < 0 || seq >= c->cfg.max_seqs) { fail(ALAYA_E_INVAL, "bad handle or sequence id"); return -1; }
+    return c->seq_len[(size_t)seq];
+}
+
+int alaya_reset_seq(alaya_cache *c, int seq)
+{
+    if (!c || seq < 0 || seq >= c->cfg.max_seqs) return fail(ALAYA_E_INVAL, "bad handle or sequence id");
+    const int64_t pages = (c->seq_len[(size_t)seq] + kPageTokens - 1) / kPageTokens;
+    const int32_t *row = c->h_page_table + (size_t)seq * c->L.mpps;
+    for (int64_t i = pages - 1; i >= 0; --i) c->free_pages.push_back(row[i]);
+    c->seq_len[(size_t)seq] = 0;
+    return ALAYA_OK;
+}
+
+int alaya_append_kv(alaya_cache *c, int seq, const void *k, const void *v, int64_t t, void *stream)
+{
+    if (!c) return fail(ALAYA_E_INVAL, "null cache handle");
+    if (seq < 0 || seq >= c->cfg.max_seqs) return fail(ALAYA_E_INVAL, "sequence id %d outside 0..%d", seq, c->cfg.max_seqs - 1);
+    if (t < 0) return fail(ALAYA_E_INVAL, "negative token count");
+    if (t == 0) return ALAYA_OK;
+    if (!k || !v) return fail(ALAYA_E_INVAL, "null k or v");
+    const int64_t n_old = c->seq_len[(size_t)seq], n_new = n_old + t;
+    if (n_new > c->cfg.max_tokens_per_seq)
+        return fail(ALAYA_E_NOMEM, "sequence %d would hold %lld tokens, limit %lld", seq, (long long)n_new,
+                    (long long)c->cfg.max_tokens_per_seq);
+    const int64_t have = (n_old + kPageTokens - 1) / kPageTokens, want = (n_new + kPageTokens - 1) / kPageTokens;
+    const int64_t take = want - have;
+    if (take > (int64_t)c->free_pages.size())
+        return fail(ALAYA_E_NOMEM, "page pool exhausted: %lld pages needed, %zu free", (long long)take, c->free_pages.size());
+    hipStream_t st = (hipStream_t)stream;
+    int32_t *row = c->h_page_table + (size_t)seq * c->L.mpps;
+    for (int64_t i = 0; i < take; ++i) {
+        row[have + i] = c->free_pages.back();
+        c->free_pages.pop_back();
+    }
+    auto rollback = [&]() {
+        for (int64_t i = take - 1; i >= 0; --i) c->free_pages.push_back(row[have + i]);
+    };
+    int rc = ensure_device(c, st);
+    if (rc != ALAYA_OK) { rollback(); return rc; }
+    int32_t *d_row = (int32_t *)c->dv.page_table + (size_t)seq * c->L.mpps;
+    if (take > 0) {
+        hipError_t e = hipMemcpyAsync(d_row + have, row + have, (size_t)take * sizeof(int32_t), hipMemcpyHostToDevice, st);
+        if (e != hipSuccess) { rollback(); return fail_hip(e, "page table copy"); }
+    }
+    const Shape sh{c->cfg.dtype, c->cfg.head_dim, c->cfg.n_q_heads, c->cfg.n_kv_heads};
+    hipError_t e;
+    {
+        Timed tm(c, 5, st);
+        e = launch_append(sh, d_row, c->k_pool, c->v_pool, k, v, n_old, t, st);
+    }
+    if (e != hipSuccess) { rollback(); return fail_hip(e, "append launch"); }
+    c->seq_len[(size_t)seq] = n_new;
+    return ALAYA_OK;
+}
+
+int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q,
+                      const alaya_sparse_params *p, float *out, void *stream)
+{
+    int64_t total_pages = 0, total_tokens = 0;
+    int rc = check_call(c, seqs, B, n_q_heads, q, out, &total_pages, &total_tokens);
+    if (rc != ALAYA_OK) return rc;
+    if (!p) return fail(ALAYA_E_INVAL, "null params");
+    if (p->mode != ALAYA_TOPK && p->mode != ALAYA_DIPR) return fail(ALAYA_E_INVAL, "unknown mode %d", p->mode);
+    if (!(p->scale >= 0.f) || std::isinf(p->scale)) return fail(ALAYA_E_INVAL, "scale must be finite and >= 0");
+    if (p->mode == ALAYA_TOPK) {
+        if (!p->topk) return fail(ALAYA_E_INVAL, "top-k mode needs topk[]");
+        for (int b = 0; b < B; ++b)
+            if (p->topk[b] <= 0) return fail(ALAYA_E_INVAL, "request %d: k = %d must be positive", b, p->topk[b]);
+    } else {
+        if (!p->beta) return fail(ALAYA_E_INVAL, "DIPR mode needs beta[]");
+        for (int b = 0; b < B; ++b)
+            if (!(p->beta[b] >= 0.f)) return fail(ALAYA_E_INVAL, "request %d: beta must be >= 0", b);
+    }
+    if (p->out_ids && p->ids_stride <= 0) return fail(ALAYA_E_INVAL, "out_ids given with ids_stride <= 0");
+
+    hipStream_t st = (hipStream_t)stream;
+    int ppw = c->tune_ppw;
+    if (ppw <= 0) {
+        ppw = (int)((total_pages * c->cfg.n_kv_heads + (int64_t)kScoreWaves * kTargetGroups - 1) /
+                    ((int64_t)kScoreWaves * kTargetGroups));
+        if (ppw < 1) ppw = 1;
+        if (ppw > 16) ppw = 16;
+    }
+    int splits = c->tune_splits;
+    if (splits <= 0) {
+        splits = 512 / (B * n_q_heads);
+        if (splits < 1) splits = 1;
+        if (splits > 32) splits = 32;
+    }
+
+    ReqDesc *hd;
+    int slot;
+    rc = ring_acquire(c, &hd, &slot);
+    if (rc != ALAYA_OK) return rc;
+    int tiles = 0;
+    int64_t off = 0;
+    for (int b = 0; b < B; ++b) {
+        const int64_t n = c->seq_len[(size_t)seqs[b]];
+        const int64_t pages = (n + kPageTokens - 1) / kPageTokens;
+        ReqDesc &d = hd[b];
+        d.pt_off = (int32_t)((int64_t)seqs[b] * c->L.mpps);
+        d.n = (int32_t)n;
+        d.n_pad = (int32_t)(pages * kPageTokens);
+        d.k = p->mode == ALAYA_TOPK ? (int32_t)((int64_t)p->topk[b] < n ? p->topk[b] : n) : 0;
+        d.beta = p->mode == ALAYA_DIPR ? p->beta[b] : 0.f;
+        d.tile_start = tiles;
+        d.score_off = off;
+        tiles += (int)((pages + (int64_t)kScoreWaves * ppw - 1) / ((int64_t)kScoreWaves * ppw));
+        off += (int64_t)n_q_heads * d.n_pad;
+    }
+    if (off > c->L.score_elems) return fail(ALAYA_E_NOMEM, "score workspace too small");
+    if (!c->ring_ev[slot]) {
+        hipError_t e = hipEventCreateWithFlags(&c->ring_ev[slot], hipEventDisableTiming);
+        if (e != hipSuccess) { c->ring_ev[slot] = nullptr; return fail_hip(e, "hipEventCreate"); }
+    }
+    rc = ensure_device(c, st);
+    if (rc != ALAYA_OK) return rc;
+    rc = ring_publish(c, slot, B, st);
+    if (rc != ALAYA_OK) return rc;
+
+    const Shape sh{c->cfg.dtype, c->cfg.head_dim, n_q_heads, c->cfg.n_kv_heads};
+    const float scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)c->cfg.head_dim);
+    hipError_t e;
+    { Timed tm(c, 0, st); e = launch_score(sh, c->dv, B, q, tiles, ppw, st); }
+    if (e != hipSuccess) return fail_hip(e, "score launch");
+    { Timed tm(c, 1, st); e = launch_select(sh, c->dv, B, p->mode, p->out_ids, p->out_counts, p->ids_stride, st); }
+    if (e != hipSuccess) return fail_hip(e, "select launch");
+    { Timed tm(c, 2, st); e = launch_attend(sh, c->dv, B, scale, splits, st); }
+    if (e != hipSuccess) return fail_hip(e, "attend launch");
+    { Timed tm(c, 3, st); e = launch_combine(sh, c->dv, B, splits, 0, 0, out, st); }
+    if (e != hipSuccess) return fail_hip(e, "combine launch");
+    return ALAYA_OK;
+}
+
+int alaya_full_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q, float scale_in,
+                    float *out, void *stream)
+{
+    int64_t total_pages = 0, total_tokens = 0;
+    int rc = check_call(c, seqs, B, n_q_heads, q, out, &total_pages, &total_tokens);
+    if (rc != ALAYA_OK) return rc;
+    if (!(scale_in >= 0.f) || std::isinf(scale_in)) return fail(ALAYA_E_INVAL, "scale must be finite and >= 0");
+    hipStream_t st = (hipStream_t)stream;
+    int64_t ppt = (total_pages * c->cfg.n_kv_heads + kTargetGroups - 1) / kTargetGroups;
+    ppt = (ppt + 3) / 4 * 4;
+    if (ppt < 4) ppt = 4;
+
+    ReqDesc *hd;
+    int slot;
+    rc = ring_acquire(c, &hd, &slot);
+    if (rc != ALAYA_OK) return rc;
+    int tiles = 0;
+    for (int b = 0; b < B; ++b) {
+        const int64_t n = c->seq_len[(size_t)seqs[b]];
+        const int64_t pages = (n + kPageTokens - 1) / kPageTokens;
+        ReqDesc &d = hd[b];
+        d.pt_off = (int32_t)((int64_t)seqs[b] * c->L.mpps);
+        d.n = (int32_t)n;
+        d.n_pad = (int32_t)(pages * kPageTokens);
+        d.k = 0;
+        d.beta = 0.f;
+        d.tile_start = tiles;
+        d.score_off = 0;
+        tiles += (int)((pages + ppt - 1) / ppt);
+    }
+    if (tiles > c->L.max_tiles) return fail(ALAYA_E_NOMEM, "partial-result workspace too small");
+    if (!c->ring_ev[slot]) {
+        hipError_t e = hipEventCreateWithFlags(&c->ring_ev[slot], hipEventDisableTiming);
+        if (e != hipSuccess) { c->ring_ev[slot] = nullptr; return fail_hip(e, "hipEventCreate"); }
+    }
+    rc = ensure_device(c, st);
+    if (rc != ALAYA_OK) return rc;
+    rc = ring_publish(c, slot, B, st);
+    if (rc != ALAYA_OK) return rc;
+
+    const Shape sh{c->cfg.dtype, c->cfg.head_dim, n_q_heads, c->cfg.n_kv_heads};
+    const float scale = scale_in > 0.f ? scale_in : 1.0f / std::sqrt((float)c->cfg.head_dim);
+    hipError_t e;
+    { Timed tm(c, 4, st); e = launch_full_partial(sh, c->dv, B, q, scale, tiles, (int)ppt, st); }
+    if (e != hipSuccess) return fail_hip(e, "full-attention launch");
+    { Timed tm(c, 3, st); e = launch_combine(sh, c->dv, B, 0, 1, (int)ppt, out, st); }
+    if (e != hipSuccess) return fail_hip(e, "combine launch");
+    return ALAYA_OK;
+}
+
+int alaya_poll_status(alaya_cache *c, void *stream)
+{
+    if (!c) return fail(ALAYA_E_INVAL, "null cache handle");
+    if (!c->dev_ready) return ALAYA_OK;
+    hipStream_t st = (hipStream_t)stream;
+    int32_t word = 0;
+    hipError_t e = hipMemcpyAsync(&word, c->dv.status, sizeof word, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return fail_hip(e, "status read");
+    if (word) {
+        e = launch_fill_u32((uint32_t *)c->dv.status, 1, 0u, st);
+        if (e != hipSuccess) return fail_hip(e, "status clear");
+        return fail(ALAYA_E_CAPACITY, "a selected set was larger than ids_stride; out_counts holds the true sizes");
+    }
+    return ALAYA_OK;
+}
+
+int alaya_set_profiling(alaya_cache *c, int enabled)
+{
+    if (!c) return fail(ALAYA_E_INVAL, "null cache handle");
+    if (c->prof) {
+        int rc = harvest(c);
+        if (rc != ALAYA_OK) return rc;
+    }
+    c->prof = enabled != 0;
+    if (c->prof)
+        for (int i = 0; i < ALAYA_N_KERNEL_SLOTS; ++i) { c->sum_ms[i] = 0.0; c->launches[i] = 0; }
+    return ALAYA_OK;
+}
+
+int alaya_kernel_times(alaya_cache *c, double *sum_ms, int64_t *launches, int n_slots)
+{
+    if (!c || !sum_ms || !launches || n_slots < 0 || n_slots > ALAYA_N_KERNEL_SLOTS)
+        return fail(ALAYA_E_INVAL, "bad arguments");
+    int rc = harvest(c);
+    if (rc != ALAYA_OK) return rc;
+    for (int i = 0; i < n_slots; ++i) { sum_ms[i] = c->sum_ms[i]; launches[i] = c->launches[i]; }
+    return ALAYA_OK;
+}
+
+const float *alaya_debug_scores(const alaya_cache *c)
+{
+    if (!c) { fail(ALAYA_E_INVAL, "null cache handle"); return nullptr; }
+    return c->dv.scores;
+}
+
+int alaya_set_tuning(alaya_cache *c, int score_pages_per_wave, int attend_splits)
+{
+    if (!c) return fail(ALAYA_E_INVAL, "null cache handle");
+    if (score_pages_per_wave > 64 || attend_splits > kMaxSplits) return fail(ALAYA_E_INVAL, "knob out of range");
+    c->tune_ppw = score_pages_per_wave > 0 ? score_pages_per_wave : 0;
+    c->tune_splits = attend_splits > 0 ? attend_splits : 0;
+    return ALAYA_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,291 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded bytes.
+
+Sizes here are ones the oracle finishes in seconds but that still span several scoring tiles, a ragged
+last page and multi-chunk selection.  Full-size cases live in test_gpu_fullsize.py.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2504_10326_amd as A
+import workloads as wl
+from parity_util import (BAND, OUT_TOL, compare_sparse, make_cache, run_and_compare, to_device)
+
+pytestmark = pytest.mark.gpu
+
+
+def _llama(lens, seed=0, **kw):
+    base = wl.config("llama8b_128k", seed)
+    return wl.resized(base, lens, **kw)
+
+
+# ------------------------------------------------------------------------------------------ append
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_append_layout_through_page_table(dtype):
+    """Appending in ragged pieces with permuted physical pages lands every element where the layout says."""
+    w = wl.Workload("append", 8, 2, 128, (300,), dtype, 4, "topk", topk=(8,), permute_pages=True, seed=3)
+    g = wl.generate(w, threads=1)
+    c = make_cache(w, g, chunks=[100, 101, 128, 250])
+    E = 8 if dtype == "bf16" else 4
+    tdt = torch.int16 if dtype == "bf16" else torch.float32
+    kp = c.k_pool.view(tdt).view(-1, 2, 128 // E, 64, E).cpu().numpy()
+    vp = c.v_pool.view(tdt).view(-1, 2, 64, 128).cpu().numpy()
+    K = g["K"][0].view(np.int16) if dtype == "bf16" else g["K"][0]
+    V = g["V"][0].view(np.int16) if dtype == "bf16" else g["V"][0]
+    order = g["page_order"]
+    for j in range(300):
+        phys, slot = order[j // 64], j % 64
+        for kvh in range(2):
+            assert (kp[phys, kvh, :, slot, :].reshape(-1) == K[j, kvh]).all()
+            assert (vp[phys, kvh, slot] == V[j, kvh]).all()
+    assert c.seq_len(0) == 300
+    c.close()
+
+
+# ------------------------------------------------------------------------------------------ tiny
+def test_tiny_config_topk64_fp32():
+    """Configuration 'tiny': 1 head, d = 128, 4096 tokens, fp32, top-k = 64."""
+    w = wl.config("tiny")
+    g = wl.generate(w, threads=1)
+    c = make_cache(w, g)
+    st = run_and_compare(c, w, g, A.ALAYA_TOPK, topk=w.topk)
+    full = c.full_attn([0], to_device(g["q"], "f32")).cpu().numpy()
+    ref = oracle.full_attn(g["q"][0], g["K"][0], g["V"][0])
+    assert np.abs(full[0] - ref).max() <= OUT_TOL
+    assert st["max_out_err"] <= OUT_TOL
+    c.close()
+
+
+# ------------------------------------------------------------------------------------------ top-k
+@pytest.mark.parametrize("n,k", [(5000, 2048), (12345, 100), (64 * 37, 1), (8191, 8190)])
+def test_topk_llama_shape(n, k):
+    """32 q heads / 8 KV heads, d = 128, bf16: ragged tail, several tiles, k from 1 to n - 1."""
+    w = _llama([n], topk=[k])
+    g = wl.generate(w)
+    c = make_cache(w, g)
+    st = run_and_compare(c, w, g, A.ALAYA_TOPK, topk=w.topk)
+    assert st["max_score_err"] <= 2e-5
+    c.close()
+
+
+def test_k_at_least_n_and_unbounded_beta_equal_full_attention():
+    """k = n, k > n and beta = +inf must all reproduce Eq. (1) over every token."""
+    w = _llama([3000], topk=[3000])
+    g = wl.generate(w)
+    c = make_cache(w, g)
+    q = to_device(g["q"], w.dtype)
+    full = c.full_attn([0], q).cpu().numpy()
+    ref = oracle.full_attn(g["q"][0], g["K"][0], g["V"][0])
+    assert np.abs(full[0] - ref).max() <= OUT_TOL
+    for mode, kw in [(A.ALAYA_TOPK, dict(topk=[3000])), (A.ALAYA_TOPK, dict(topk=[10 ** 9])),
+                     (A.ALAYA_DIPR, dict(beta=[float("inf")]))]:
+        out, ids, counts = c.sparse_attn([0], q, mode, ids_stride=3000, **kw)
+        assert (counts.cpu().numpy() == 3000).all()
+        assert (np.sort(ids.cpu().numpy(), axis=2) == np.arange(3000)).all()
+        assert np.abs(out.cpu().numpy()[0] - ref).max() <= OUT_TOL
+        assert np.abs(out.cpu().numpy()[0] - full[0]).max() <= 1e-5
+    c.close()
+
+
+# ------------------------------------------------------------------------------------------ DIPR
+def test_dipr_beta_sweep():
+    """Range query: every key within beta of the maximum inner product, beta from 0 to 4 (and 0 = arg-max)."""
+    w = wl.resized(wl.config("range_256k"), [9000])
+    g = wl.generate(w)
+    c = make_cache(w, g)
+    sizes = []
+    for beta in (0.0, 0.5, 1.0, 2.0, 4.0, 8.0):
+        st = run_and_compare(c, w, g, A.ALAYA_DIPR, beta=[beta])
+        sizes.append(sum(st["counts"]))
+    assert sizes == sorted(sizes) and sizes[0] == w.n_q_heads     # beta = 0 keeps exactly the arg-max
+    c.close()
+
+
+# ------------------------------------------------------------------------------------------ paging
+def test_permuted_pages_do_not_change_the_answer():
+    """Physical page order is invisible: same ids, bit-identical output as with pages in order."""
+    base = wl.resized(wl.config("paged_1m"), [20000], topk=[512])
+    g = wl.generate(base)
+    c1 = make_cache(base, g)
+    st = run_and_compare(c1, base, g, A.ALAYA_TOPK, topk=base.topk)
+    plain = wl.resized(base, [20000], topk=[512], permute_pages=False)
+    c2 = make_cache(plain, g)
+    q = to_device(g["q"], base.dtype)
+    o1, i1, n1 = c1.sparse_attn([0], q, A.ALAYA_TOPK, topk=[512], ids_stride=512)
+    o2, i2, n2 = c2.sparse_attn([0], q, A.ALAYA_TOPK, topk=[512], ids_stride=512)
+    assert torch.equal(i1, i2) and torch.equal(n1, n2) and torch.equal(o1, o2)
+    c1.close(); c2.close()
+
+
+def test_token_permutation_invariance_on_gpu():
+    """Permuting the cached tokens maps the selected set through the permutation and keeps the output."""
+    w = _llama([4000], topk=[300])
+    g = wl.generate(w)
+    perm = np.random.default_rng(5).permutation(4000)
+    g2 = dict(g, K=[g["K"][0][perm]], V=[g["V"][0][perm]])
+    c1, c2 = make_cache(w, g), make_cache(w, g2)
+    q = to_device(g["q"], w.dtype)
+    o1, i1, _ = c1.sparse_attn([0], q, A.ALAYA_TOPK, topk=[300], ids_stride=300)
+    o2, i2, _ = c2.sparse_attn([0], q, A.ALAYA_TOPK, topk=[300], ids_stride=300)
+    assert np.abs(o1.cpu().numpy() - o2.cpu().numpy()).max() <= 1e-5
+    a, b = i1.cpu().numpy()[0], perm[i2.cpu().numpy()[0]]
+    assert (np.sort(a, axis=1) == np.sort(b, axis=1)).all()
+    c1.close(); c2.close()
+
+
+# ------------------------------------------------------------------------------------------ batched
+def test_batched_ragged_lengths_one_call():
+    """Several requests of very different lengths in one call, k = 2 % of each length."""
+    lens = [1, 63, 64, 65, 3000, 8191, 517]
+    w = wl.resized(wl.config("batched_16"), lens)
+    g = wl.generate(w)
+    c = make_cache(w, g)
+    run_and_compare(c, w, g, A.ALAYA_TOPK, topk=w.topk)
+    run_and_compare(c, w, g, A.ALAYA_DIPR, beta=[0.5, 1.0, 0.0, 2.0, 1.0, 3.0, 100.0])
+    q = to_device(g["q"], w.dtype)
+    full = c.full_attn(list(range(len(lens))), q).cpu().numpy()
+    for r in range(len(lens)):
+        ref = oracle.full_attn(g["q"][r], g["K"][r], g["V"][r])
+        assert np.abs(full[r] - ref).max() <= OUT_TOL
+    # a sub-batch in another order, with a repeated sequence
+    seqs = [4, 1, 4]
+    out, ids, counts = c.sparse_attn(seqs, q[[4, 1, 4]].contiguous(), A.ALAYA_TOPK, topk=[60, 2, 60], ids_stride=60)
+    w2 = wl.resized(w, [lens[s] for s in seqs], topk=[60, 2, 60])
+    g2 = dict(g, K=[g["K"][s] for s in seqs], V=[g["V"][s] for s in seqs], q=g["q"][seqs])
+    compare_sparse(w2, g2, out, ids, counts, A.ALAYA_TOPK, topk=[60, 2, 60])
+    c.close()
+
+
+# ------------------------------------------------------------------------------------------ other shapes
+@pytest.mark.parametrize("hq,hk,d,dtype", [(4, 4, 128, "bf16"), (8, 4, 64, "bf16"), (16, 2, 128, "bf16"),
+                                            (4, 2, 64, "f32"), (8, 1, 128, "f32")])
+def test_other_group_sizes_and_head_dims(hq, hk, d, dtype):
+    w = wl.Workload("shape", hq, hk, d, (2500, 700), dtype, 8, "topk", topk=(200, 33), seed=9)
+    g = wl.generate(w)
+    c = make_cache(w, g)
+    run_and_compare(c, w, g, A.ALAYA_TOPK, topk=w.topk)
+    run_and_compare(c, w, g, A.ALAYA_DIPR, beta=[1.5, 0.7])
+    full = c.full_attn([0, 1], to_device(g["q"], dtype)).cpu().numpy()
+    for r in range(2):
+        assert np.abs(full[r] - oracle.full_attn(g["q"][r], g["K"][r], g["V"][r])).max() <= OUT_TOL
+    c.close()
+
+
+# ------------------------------------------------------------------------------------------ semantics
+def test_update_then_attend_sees_the_new_token():
+    """A token appended in this step is visible to this step's query (update, then attention)."""
+    w = _llama([1000], topk=[16])
+    g = wl.generate(w)
+    c = make_cache(w, g, extra_tokens=64)
+    q = to_device(g["q"], w.dtype)
+    qf = wl.bf16_bits_to_f32(g["q"][0])                                     # [32][128]
+    knew = np.zeros((1, w.n_kv_heads, 128), dtype=np.float32)
+    for kv in range(w.n_kv_heads):
+        knew[0, kv] = 40.0 * qf[kv * 4] / np.linalg.norm(qf[kv * 4])        # aligned with the group's first head
+    vnew = np.full((1, w.n_kv_heads, 128), 3.0, dtype=np.float32)
+    kb, vb = wl.to_bf16_bits(knew), wl.to_bf16_bits(vnew)
+    c.append_kv(0, to_device(kb, "bf16"), to_device(vb, "bf16"))
+    assert c.seq_len(0) == 1001
+    out, ids, counts = c.sparse_attn([0], q, A.ALAYA_DIPR, beta=[0.0], ids_stride=4)
+    ids, out = ids.cpu().numpy(), out.cpu().numpy()
+    for kv in range(w.n_kv_heads):
+        assert ids[0, kv * 4, 0] == 1000 and counts[0, kv * 4] == 1
+        assert np.allclose(out[0, kv * 4], 3.0)
+    g2 = dict(g, K=[np.concatenate([g["K"][0], kb])], V=[np.concatenate([g["V"][0], vb])])
+    w2 = wl.resized(w, [1001], topk=[16])
+    out, ids, counts = c.sparse_attn([0], q, A.ALAYA_TOPK, topk=[16], ids_stride=16)
+    compare_sparse(w2, g2, out, ids, counts, A.ALAYA_TOPK, topk=[16])
+    c.close()
+
+
+def test_single_token_sequence_and_reset():
+    w = _llama([1], topk=[5])
+    g = wl.generate(w)
+    c = make_cache(w, g, extra_tokens=200)
+    q = to_device(g["q"], w.dtype)
+    out, ids, counts = c.sparse_attn([0], q, A.ALAYA_TOPK, topk=[5], ids_stride=5)
+    v = wl.bf16_bits_to_f32(g["V"][0])[0]                                   # [8][128]
+    assert (counts.cpu().numpy() == 1).all() and (ids.cpu().numpy()[:, :, 0] == 0).all()
+    assert np.allclose(out.cpu().numpy()[0], np.repeat(v, 4, axis=0))
+    torch.cuda.synchronize()
+    c.reset_seq(0)
+    assert c.seq_len(0) == 0
+    with pytest.raises(A.AlayaError) as e:
+        c.sparse_attn([0], q, A.ALAYA_TOPK, topk=[5])
+    assert e.value.code == A.ALAYA_E_EMPTY
+    k2, v2 = wl.extra_tokens(w, 0, 130)
+    c.append_kv(0, to_device(k2, "bf16"), to_device(v2, "bf16"))
+    w2, g2 = wl.resized(w, [130], topk=[5]), dict(g, K=[k2], V=[v2])
+    out, ids, counts = c.sparse_attn([0], q, A.ALAYA_TOPK, topk=[5], ids_stride=5)
+    compare_sparse(w2, g2, out, ids, counts, A.ALAYA_TOPK, topk=[5])
+    c.close()
+
+
+def test_exact_ties_go_to_the_smaller_id_and_runs_are_identical():
+    """Duplicate keys give exactly equal scores: the first copies win, and two runs agree bit for bit."""
+    w = _llama([2048], topk=[100])
+    g = wl.generate(w)
+    K = g["K"][0].copy(); V = g["V"][0]
+    K[1024:] = K[:1024]                                                    # every key appears twice
+    g2 = dict(g, K=[K])
+    c = make_cache(w, g2)
+    q = to_device(g["q"], w.dtype)
+    for k in (100, 101, 7):
+        o1, i1, n1 = c.sparse_attn([0], q, A.ALAYA_TOPK, topk=[k], ids_stride=k)
+        o2, i2, n2 = c.sparse_attn([0], q, A.ALAYA_TOPK, topk=[k], ids_stride=k)
+        assert torch.equal(o1, o2) and torch.equal(i1, i2)
+        st = compare_sparse(w, g2, o1, i1, n1, A.ALAYA_TOPK, topk=[k])
+        if st["band_heads"] == 0:                                          # exact ties alone need no band
+            ids = np.sort(i1.cpu().numpy()[0], axis=1)
+            orc = oracle.sparse_attn(g["q"][0], K, V, oracle.TOPK, k=k)
+            for h in range(32):
+                assert (ids[h] == orc["ids"][h]).all()
+    c.close()
+
+
+def test_capacity_overflow_is_reported_not_truncated():
+    w = _llama([3000], topk=[50])
+    g = wl.generate(w)
+    c = make_cache(w, g)
+    q = to_device(g["q"], w.dtype)
+    full_ids = c.sparse_attn([0], q, A.ALAYA_DIPR, beta=[3.0], ids_stride=3000)
+    out, ids, counts = c.sparse_attn([0], q, A.ALAYA_DIPR, beta=[3.0], ids_stride=8)
+    assert c.poll_status() == A.ALAYA_E_CAPACITY
+    assert c.poll_status() == A.ALAYA_OK                                   # cleared by the read
+    assert torch.equal(counts, full_ids[2]) and int(counts.max()) > 8     # true counts
+    assert torch.equal(out, full_ids[0])                                   # attention still over the whole set
+    assert torch.equal(ids, full_ids[1][:, :, :8])
+    c.close()
+
+
+def test_invalid_call_arguments_on_a_live_cache():
+    w = _llama([500], topk=[5])
+    g = wl.generate(w)
+    c = make_cache(w, g)
+    q = to_device(g["q"], w.dtype)
+    ref = c.sparse_attn([0], q, A.ALAYA_TOPK, topk=[5])
+    for kw in [dict(mode=A.ALAYA_TOPK, topk=[0]), dict(mode=A.ALAYA_TOPK, topk=[-3]), dict(mode=A.ALAYA_TOPK),
+               dict(mode=A.ALAYA_DIPR, beta=[-0.5]), dict(mode=A.ALAYA_DIPR, beta=[float("nan")]),
+               dict(mode=A.ALAYA_DIPR), dict(mode=7, topk=[5]), dict(mode=A.ALAYA_TOPK, topk=[5], scale=-1.0)]:
+        with pytest.raises(A.AlayaError) as e:
+            c.sparse_attn([0], q, **kw)
+        assert e.value.code == A.ALAYA_E_INVAL, kw
+    assert torch.equal(ref, c.sparse_attn([0], q, A.ALAYA_TOPK, topk=[5]))   # the cache is unharmed
+    c.close()
+
+
+def test_custom_scale_and_profiling_hooks():
+    w = _llama([2000], topk=[64])
+    g = wl.generate(w)
+    c = make_cache(w, g)
+    run_and_compare(c, w, g, A.ALAYA_TOPK, topk=w.topk, scale=0.25)
+    c.set_profiling(True)
+    for ppw, splits in [(1, 1), (3, 7), (16, 64)]:
+        c.set_tuning(ppw, splits)
+        run_and_compare(c, w, g, A.ALAYA_TOPK, topk=w.topk)
+    t = c.kernel_times()
+    assert t["score"]["launches"] == 3 and t["score"]["sum_ms"] > 0 and t["combine"]["launches"] == 3
+    c.close()
