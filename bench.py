@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Decode-step sparse-attention benchmark on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama8b_128k]
+
+One step = one decode step of one layer: append the new token's key/value (Session.update), then
+the sparse-attention query (Session.attention): score every cached key, select top-k (or DIPR),
+gather the selected value rows, softmax-weighted sum, merge.  Inputs are resident in HBM before the
+timed region.  Prints ONE JSON line:
+
+  value       keys scored per second over the whole step  (a key-score = one (query head, token) pair)
+  roofline    the scoring kernel against the 8 TB/s HBM peak: algorithmic bytes per launch
+              (read each K row once, 256 B; write its G fp32 scores, 4 B each) over the kernel's
+              average duration, taken with HIP events on the launch stream in a profiled repeat of
+              the timed loop (events between kernels would lengthen the timed steps themselves)
+  cpu_baseline  the CPU oracle on the same step, on this host's cores (a reported baseline only)
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="llama8b_128k",
+                    choices=["llama8b_128k", "range_256k", "paged_1m", "batched_16"])
+    ap.add_argument("--beta", type=float, default=2.0, help="DIPR margin for range_256k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pages-per-wave", type=int, default=0)
+    ap.add_argument("--attend-splits", type=int, default=0)
+    ap.add_argument("--segment-tokens", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2504_10326_amd as A
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 1
+    A.lib()
+    K_steps, W = args.steps, args.warmup
+    w = wl.config(args.workload)
+    t0 = time.time()
+    g = wl.generate(w)
+    print(f"[bench] generated {w.name}: {w.total_tokens} tokens in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
+
+    # Each step appends one token per request, so leave room for every step of both passes.
+    extra = 2 * (W + K_steps) + 8
+    n_phys = g["n_phys_pages"] + w.batch * ((extra + 63) // 64 + 1)
+    order = g["page_order"]
+    if len(order) < n_phys:
+        order = np.concatenate([order, np.arange(len(order), n_phys, dtype=np.int32)])
+    c = A.Cache(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, max_seqs=w.batch, max_batch=w.batch,
+                max_tokens_per_seq=max(w.lens) + extra, max_batch_tokens=w.total_tokens + w.batch * extra,
+                n_phys_pages=n_phys, phys_page_order=order if w.permute_pages else None)
+    tdt = torch.bfloat16
+
+    def dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda().view(tdt)
+
+    # The cache starts one token short; the first step's append brings it to the stated length.
+    for r, n in enumerate(w.lens):
+        c.append_kv(r, dev(g["K"][r][:n - 1]), dev(g["V"][r][:n - 1]))
+    q = dev(g["q"])
+    new_k = [dev(g["K"][r][w.lens[r] - 1:]) for r in range(w.batch)]
+    new_v = [dev(g["V"][r][w.lens[r] - 1:]) for r in range(w.batch)]
+    seqs = list(range(w.batch))
+    out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    if w.mode == "topk":
+        mode, kw = A.ALAYA_TOPK, dict(topk=list(w.topk))
+    else:
+        mode, kw = A.ALAYA_DIPR, dict(beta=[args.beta] * w.batch)
+    c.set_tuning(args.pages_per_wave, args.attend_splits, args.segment_tokens)
+    torch.cuda.synchronize()
+
+    def step():
+        for r in range(w.batch):
+            c.append_kv(r, new_k[r], new_v[r])
+        c.sparse_attn(seqs, q, mode, out=out, **kw)
+
+    def run(n_steps):
+        """n_steps steps bracketed by synchronisation; returns (seconds, key-scores, K rows scored)."""
+        before = sum(c.seq_len(r) for r in seqs)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(n_steps):
+            step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t
+        # step i (1-based) scores before + i * batch tokens in total
+        toks = n_steps * before + w.batch * n_steps * (n_steps + 1) // 2
+        return dt, w.n_q_heads * toks, w.n_kv_heads * toks
+
+    run(W)
+    secs, keys, rows = run(K_steps)
+    ms_per_step = secs / K_steps * 1e3
+
+    # Profiled repeat of the same loop: per-kernel durations from HIP events on the launch stream.
+    c.set_profiling(True)
+    _, _, rows_p = run(K_steps)
+    kt = c.kernel_times()
+    c.set_profiling(False)
+    score_ms = kt["score"]["sum_ms"] / max(1, kt["score"]["launches"])
+    G = w.n_q_heads // w.n_kv_heads
+    bytes_per_row = w.head_dim * 2 + 4 * G                    # read the K row once, write G fp32 scores
+    bytes_per_launch = rows_p / K_steps * bytes_per_row
+    achieved = bytes_per_launch / (score_ms * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "paper_2504_10326_amd", "measured_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(w.name, {}).get("score_kernel_hbm_bytes_per_launch")
+    kernels_us = {k: round(v["sum_ms"] / v["launches"] * 1e3, 2) for k, v in kt.items() if v["launches"]}
+
+    # Dense attention over the same cache, for context (reads K and V once each).
+    torch.cuda.synchronize()
+    t = time.perf_counter()
+    for _ in range(10):
+        c.full_attn(seqs, q, out=out)
+    torch.cuda.synchronize()
+    full_ms = (time.perf_counter() - t) / 10 * 1e3
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        # One whole step of the first request on the oracle (scores, selection, attention; fp64).
+        n = w.lens[0]
+        t = time.perf_counter()
+        res = oracle.sparse_attn(g["q"][0], g["K"][0], g["V"][0],
+                                 oracle.TOPK if w.mode == "topk" else oracle.DIPR,
+                                 k=w.topk[0] if w.topk else 0, beta=args.beta, want_ids=False)
+        dt = time.perf_counter() - t
+        cpu = {"value": w.n_q_heads * n / dt, "unit": "keys/s", "cores": int(res["threads"]), "kind": "oracle",
+               "sample": f"one full step of request 0 ({n} tokens x {w.n_q_heads} heads), {dt:.2f} s wall"}
+
+    total_n = sum(c.seq_len(r) for r in seqs)
+    line = {
+        "metric": "keys scored/s (one layer, sparse decode step: append + score + select + gather + attend)",
+        "value": keys / secs, "unit": "keys/s", "n_gpus": 1, "steps": K_steps, "warmup": W,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 inputs, fp32 accumulate", "data": "synthetic",
+        "config": {"workload": w.name, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
+                   "batch": w.batch, "tokens": total_n, "mode": w.mode,
+                   "topk": list(w.topk) if w.topk else None, "beta": args.beta if w.mode == "dipr" else None,
+                   "paged": "64-token pages" + (", randomly permuted" if w.permute_pages else "")},
+        "latency_us_per_layer": ms_per_step * 1e3,
+        "k_rows_per_s": rows / secs,
+        "kernels_us": kernels_us,
+        "full_attn_ms": full_ms,
+        "roofline": {"bound": "hbm", "kernel": "score_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "bytes_per_launch": bytes_per_launch, "avg_us": score_ms * 1e3},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+    c.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -159,12 +159,15 @@ int alaya_kernel_times(alaya_cache *c, double *sum_ms, int64_t *launches, int n_
 
 /* Launch-shape knobs for measurement sweeps; each <= 0 keeps the built-in choice.
  * score_pages_per_wave: pages one wavefront scores in a row (1..64).
- * attend_splits: workgroups that share one head's selected set (1..64). */
-int alaya_set_tuning(alaya_cache *c, int score_pages_per_wave, int attend_splits);
+ * attend_splits: workgroups that share one head's selected set (1..64).
+ * select_segment_tokens: tokens of one head that one selection workgroup scans (rounded up to whole
+ * 4096-token chunks; at most 64 segments per head are used whatever the value). */
+int alaya_set_tuning(alaya_cache *c, int score_pages_per_wave, int attend_splits, int select_segment_tokens);
 
 /* Inspection hook for tests: DEVICE pointer to the fp32 scores the last alaya_sparse_attn call left
- * in the workspace, request after request, each block [n_q_heads][n_pad] with n_pad = n rounded up to
- * a whole page (entries j >= n are unspecified).  Valid until the next call on the cache. */
+ * in the workspace, request after request, each block [n_q_heads][stride] with stride = n rounded up
+ * to a whole page plus ALAYA_SCORE_PAD (entries j >= n are unspecified).  Valid until the next call. */
+#define ALAYA_SCORE_PAD 1088
 const float *alaya_debug_scores(const alaya_cache *c);
 
 /* Thread-local description of the last error returned on this thread ("" if none). */

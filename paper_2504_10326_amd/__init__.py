@@ -21,6 +21,7 @@ LIB_PATH = os.path.join(_HERE, "libalaya.so")
 ALAYA_BF16, ALAYA_F32 = 0, 1
 ALAYA_TOPK, ALAYA_DIPR = 0, 1
 ALAYA_OK, ALAYA_E_INVAL, ALAYA_E_NOMEM, ALAYA_E_CAPACITY, ALAYA_E_EMPTY, ALAYA_E_DEVICE = 0, -1, -2, -3, -4, -5
+SCORE_PAD = 1088
 N_KERNEL_SLOTS = 6
 KERNEL_SLOTS = ("score", "select", "attend", "combine", "full_partial", "append")
 
@@ -87,7 +88,7 @@ def lib() -> ctypes.CDLL:
         L.alaya_set_profiling.argtypes = [vp, i32]; L.alaya_set_profiling.restype = i32
         L.alaya_kernel_times.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64), i32]
         L.alaya_kernel_times.restype = i32
-        L.alaya_set_tuning.argtypes = [vp, i32, i32]; L.alaya_set_tuning.restype = i32
+        L.alaya_set_tuning.argtypes = [vp, i32, i32, i32]; L.alaya_set_tuning.restype = i32
         L.alaya_debug_scores.argtypes = [vp]; L.alaya_debug_scores.restype = vp
         L.alaya_last_error.argtypes = []; L.alaya_last_error.restype = ctypes.c_char_p
         _lib = L
@@ -298,12 +299,13 @@ class Cache:
         off = base - self.workspace.data_ptr()
         views = []
         for n in lens:
-            n_pad = (n + 63) // 64 * 64
-            nbytes = self.cfg.n_q_heads * n_pad * 4
-            blk = self.workspace[off:off + nbytes].view(torch.float32).view(self.cfg.n_q_heads, n_pad)
+            stride = (n + 63) // 64 * 64 + SCORE_PAD
+            nbytes = self.cfg.n_q_heads * stride * 4
+            blk = self.workspace[off:off + nbytes].view(torch.float32).view(self.cfg.n_q_heads, stride)
             views.append(blk[:, :n])
             off += nbytes
         return views
 
-    def set_tuning(self, score_pages_per_wave: int = 0, attend_splits: int = 0) -> None:
-        _check(lib().alaya_set_tuning(self.handle, score_pages_per_wave, attend_splits))
+    def set_tuning(self, score_pages_per_wave: int = 0, attend_splits: int = 0,
+                   select_segment_tokens: int = 0) -> None:
+        _check(lib().alaya_set_tuning(self.handle, score_pages_per_wave, attend_splits, select_segment_tokens))

@@ -15,13 +15,25 @@ constexpr int kMaxSplits = 64;
 struct ReqDesc {
     int32_t pt_off;      // first entry of this sequence's row in the device page table
     int32_t n;           // cached tokens
-    int32_t n_pad;       // n rounded up to whole pages: stride between heads in the score arrays
+    int32_t head_stride; // elements between consecutive heads in the score / id arrays
     int32_t k;           // top-k, already clamped to n (0 in DIPR mode)
     float beta;          // DIPR margin (raw inner-product units)
     int32_t tile_start;  // first scoring / full-attention tile of this request (prefix sum)
-    int64_t score_off;   // offset (elements) of this request's [n_q_heads][n_pad] block
+    int64_t score_off;   // offset (elements) of this request's [n_q_heads][head_stride] block
+    int32_t seg_start;   // first selection segment of this request (prefix sum, per head)
+    int32_t nseg;        // selection segments per head
+    int32_t seg_len;     // tokens per segment (a multiple of the selection chunk)
+    int32_t n_tiles;     // scoring tiles of this request
 };
-static_assert(sizeof(ReqDesc) == 32, "ReqDesc layout");
+static_assert(sizeof(ReqDesc) == 48, "ReqDesc layout");
+
+// Elements added to each head's row of scores so that the rows of different heads, which are written
+// at the same token offset at the same time, do not all start on the same memory channel.
+constexpr int kScorePad = 1088; // 17 * 256 bytes
+
+constexpr int kHistBins = 2048; // top 11 bits of the order-preserving score image
+constexpr int kSelChunkTokens = 4096;
+constexpr int kMaxSegs = 64;
 
 // Device views handed to the launchers.
 struct DeviceViews {
@@ -29,12 +41,15 @@ struct DeviceViews {
     const int32_t *page_table; // [max_seqs][max_pages_per_seq]
     const void *k_pool;
     const void *v_pool;
-    float *scores;             // [sum n_pad * n_q_heads]
+    float *scores;             // [sum over requests of n_q_heads * head_stride]
     int32_t *sel_ids;          // same extent
     float *sel_scores;         // same extent
-    uint32_t *head_max;        // [max_batch * n_q_heads], order-preserving image of the running max
-    float *head_M;             // [max_batch * n_q_heads], the max as a float, once selection has read it
-    int32_t *counts;           // [max_batch * n_q_heads]
+    float *tile_max;           // [scoring tiles][n_q_heads]: maximum score of each tile
+    uint32_t *hist;            // [max_batch * n_q_heads][kHistBins]; zero between calls
+    int32_t *seg_counts;       // [max_batch * n_q_heads][kMaxSegs][2]
+    float *head_M;             // [max_batch * n_q_heads]: maximum score per head
+    int32_t *head_info;        // [max_batch * n_q_heads][2]: bucket of the k-th score (-1: threshold rule), tokens above it
+    int32_t *counts;           // [max_batch * n_q_heads]: size of the selected set
     float *partials;           // attend / full-attention partial results
     int32_t *status;           // device status word
 };
@@ -51,10 +66,11 @@ hipError_t launch_append(const Shape &sh, const int32_t *page_table_row, void *k
                          const void *k, const void *v, int64_t n_old, int64_t t, hipStream_t st);
 
 hipError_t launch_score(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles,
-                        int pages_per_wave, hipStream_t st);
+                        int pages_per_wave, int want_hist, hipStream_t st);
 
-hipError_t launch_select(const Shape &sh, const DeviceViews &dv, int B, int mode, int32_t *out_ids,
-                         int32_t *out_counts, int64_t ids_stride, hipStream_t st);
+// count -> place -> finish; total_segs = sum over requests of nseg
+hipError_t launch_select(const Shape &sh, const DeviceViews &dv, int B, int mode, int total_segs,
+                         int32_t *out_ids, int32_t *out_counts, int64_t ids_stride, hipStream_t st);
 
 hipError_t launch_attend(const Shape &sh, const DeviceViews &dv, int B, float scale, int splits,
                          hipStream_t st);

@@ -58,18 +58,21 @@ bool cfg_ok(const alaya_cache_config *c)
 }
 
 struct Layout {
-    size_t page_table, desc, scores, sel_ids, sel_scores, head_max, head_M, counts, partials, status, total;
-    int64_t mpps;        // max pages per sequence
-    int64_t score_elems; // capacity of each of scores / sel_ids / sel_scores
-    int64_t max_tiles;   // full-attention tiles
+    size_t page_table, desc, scores, sel_ids, sel_scores, tile_max, hist, seg_counts, head_M, head_info, counts,
+        partials, status, total;
+    int64_t mpps;            // max pages per sequence
+    int64_t score_elems;     // capacity of each of scores / sel_ids / sel_scores
+    int64_t max_tiles;       // full-attention tiles
+    int64_t max_score_tiles; // scoring tiles (pages_per_wave = 1 is the worst case)
 };
 
 Layout make_layout(const alaya_cache_config &c)
 {
     Layout L{};
     L.mpps = (c.max_tokens_per_seq + kPageTokens - 1) / kPageTokens;
-    L.score_elems = (int64_t)c.n_q_heads * (c.max_batch_tokens + (int64_t)kPageTokens * c.max_batch);
+    L.score_elems = (int64_t)c.n_q_heads * (c.max_batch_tokens + (int64_t)(kPageTokens + kScorePad) * c.max_batch);
     L.max_tiles = kTargetGroups / c.n_kv_heads + 1 + c.max_batch;
+    L.max_score_tiles = (c.max_batch_tokens / kPageTokens + c.max_batch) / kScoreWaves + c.max_batch;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     L.page_table = take((size_t)L.mpps * c.max_seqs * sizeof(int32_t));
@@ -77,8 +80,11 @@ Layout make_layout(const alaya_cache_config &c)
     L.scores = take((size_t)L.score_elems * sizeof(float));
     L.sel_ids = take((size_t)L.score_elems * sizeof(int32_t));
     L.sel_scores = take((size_t)L.score_elems * sizeof(float));
-    L.head_max = take((size_t)c.max_batch * c.n_q_heads * sizeof(uint32_t));
+    L.tile_max = take((size_t)L.max_score_tiles * c.n_q_heads * sizeof(float));
+    L.hist = take((size_t)c.max_batch * c.n_q_heads * kHistBins * sizeof(uint32_t));
+    L.seg_counts = take((size_t)c.max_batch * c.n_q_heads * kMaxSegs * 2 * sizeof(int32_t));
     L.head_M = take((size_t)c.max_batch * c.n_q_heads * sizeof(float));
+    L.head_info = take((size_t)c.max_batch * c.n_q_heads * 2 * sizeof(int32_t));
     L.counts = take((size_t)c.max_batch * c.n_q_heads * sizeof(int32_t));
     const size_t sparse_slots = (size_t)c.max_batch * c.n_q_heads * kMaxSplits;
     const size_t full_slots = (size_t)L.max_tiles * c.n_q_heads;
@@ -106,7 +112,7 @@ struct alaya_cache {
     bool ring_used[kRing];
     int ring_pos;
     bool dev_ready;
-    int tune_ppw, tune_splits;
+    int tune_ppw, tune_splits, tune_seg;
     // profiling
     bool prof;
     std::vector<hipEvent_t> ev;      // 2 * kProfPairs, created on demand
@@ -160,8 +166,8 @@ struct Timed {
 int ensure_device(alaya_cache *c, hipStream_t st)
 {
     if (c->dev_ready) return ALAYA_OK;
-    const size_t nh = (size_t)c->cfg.max_batch * c->cfg.n_q_heads;
-    hipError_t e = launch_fill_u32(c->dv.head_max, nh, 0u, st);
+    const size_t nh = (size_t)c->cfg.max_batch * c->cfg.n_q_heads * kHistBins;
+    hipError_t e = launch_fill_u32(c->dv.hist, nh, 0u, st);
     if (e == hipSuccess) e = launch_fill_u32((uint32_t *)c->dv.status, 1, 0u, st);
     if (e != hipSuccess) return fail_hip(e, "workspace initialisation");
     c->dev_ready = true;
@@ -277,7 +283,10 @@ int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k
     c->dv.scores = (float *)(c->ws + L.scores);
     c->dv.sel_ids = (int32_t *)(c->ws + L.sel_ids);
     c->dv.sel_scores = (float *)(c->ws + L.sel_scores);
-    c->dv.head_max = (uint32_t *)(c->ws + L.head_max);
+    c->dv.tile_max = (float *)(c->ws + L.tile_max);
+    c->dv.hist = (uint32_t *)(c->ws + L.hist);
+    c->dv.seg_counts = (int32_t *)(c->ws + L.seg_counts);
+    c->dv.head_info = (int32_t *)(c->ws + L.head_info);
     c->dv.head_M = (float *)(c->ws + L.head_M);
     c->dv.counts = (int32_t *)(c->ws + L.counts);
     c->dv.partials = (float *)(c->ws + L.partials);
@@ -304,6 +313,7 @@ int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k
     c->dev_ready = false;
     c->tune_ppw = 0;
     c->tune_splits = 0;
+    c->tune_seg = 0;
     c->prof = false;
     c->ev_n = 0;
     for (int i = 0; i < ALAYA_N_KERNEL_SLOTS; ++i) { c->sum_ms[i] = 0.0; c->launches[i] = 0; }
@@ -409,6 +419,7 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
         if (ppw < 1) ppw = 1;
         if (ppw > 16) ppw = 16;
     }
+    const int64_t seg_tokens = c->tune_seg > 0 ? c->tune_seg : 16384;
     int splits = c->tune_splits;
     if (splits <= 0) {
         splits = 512 / (B * n_q_heads);
@@ -420,7 +431,7 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
     int slot;
     rc = ring_acquire(c, &hd, &slot);
     if (rc != ALAYA_OK) return rc;
-    int tiles = 0;
+    int tiles = 0, segs = 0;
     int64_t off = 0;
     for (int b = 0; b < B; ++b) {
         const int64_t n = c->seq_len[(size_t)seqs[b]];
@@ -428,15 +439,25 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
         ReqDesc &d = hd[b];
         d.pt_off = (int32_t)((int64_t)seqs[b] * c->L.mpps);
         d.n = (int32_t)n;
-        d.n_pad = (int32_t)(pages * kPageTokens);
+        d.head_stride = (int32_t)(pages * kPageTokens + kScorePad);
         d.k = p->mode == ALAYA_TOPK ? (int32_t)((int64_t)p->topk[b] < n ? p->topk[b] : n) : 0;
         d.beta = p->mode == ALAYA_DIPR ? p->beta[b] : 0.f;
         d.tile_start = tiles;
         d.score_off = off;
-        tiles += (int)((pages + (int64_t)kScoreWaves * ppw - 1) / ((int64_t)kScoreWaves * ppw));
-        off += (int64_t)n_q_heads * d.n_pad;
+        d.n_tiles = (int32_t)((pages + (int64_t)kScoreWaves * ppw - 1) / ((int64_t)kScoreWaves * ppw));
+        // selection segments: about seg_tokens tokens each, whole chunks, at most kMaxSegs per head
+        int64_t chunks = (n + kSelChunkTokens - 1) / kSelChunkTokens;
+        int64_t cps = (seg_tokens + kSelChunkTokens - 1) / kSelChunkTokens; // chunks per segment
+        if ((chunks + cps - 1) / cps > kMaxSegs) cps = (chunks + kMaxSegs - 1) / kMaxSegs;
+        d.seg_len = (int32_t)(cps * kSelChunkTokens);
+        d.nseg = (int32_t)((chunks + cps - 1) / cps);
+        d.seg_start = segs;
+        tiles += d.n_tiles;
+        segs += d.nseg;
+        off += (int64_t)n_q_heads * d.head_stride;
     }
     if (off > c->L.score_elems) return fail(ALAYA_E_NOMEM, "score workspace too small");
+    if (tiles > c->L.max_score_tiles) return fail(ALAYA_E_NOMEM, "tile workspace too small");
     if (!c->ring_ev[slot]) {
         hipError_t e = hipEventCreateWithFlags(&c->ring_ev[slot], hipEventDisableTiming);
         if (e != hipSuccess) { c->ring_ev[slot] = nullptr; return fail_hip(e, "hipEventCreate"); }
@@ -449,9 +470,9 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
     const Shape sh{c->cfg.dtype, c->cfg.head_dim, n_q_heads, c->cfg.n_kv_heads};
     const float scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)c->cfg.head_dim);
     hipError_t e;
-    { Timed tm(c, 0, st); e = launch_score(sh, c->dv, B, q, tiles, ppw, st); }
+    { Timed tm(c, 0, st); e = launch_score(sh, c->dv, B, q, tiles, ppw, p->mode == ALAYA_TOPK, st); }
     if (e != hipSuccess) return fail_hip(e, "score launch");
-    { Timed tm(c, 1, st); e = launch_select(sh, c->dv, B, p->mode, p->out_ids, p->out_counts, p->ids_stride, st); }
+    { Timed tm(c, 1, st); e = launch_select(sh, c->dv, B, p->mode, segs, p->out_ids, p->out_counts, p->ids_stride, st); }
     if (e != hipSuccess) return fail_hip(e, "select launch");
     { Timed tm(c, 2, st); e = launch_attend(sh, c->dv, B, scale, splits, st); }
     if (e != hipSuccess) return fail_hip(e, "attend launch");
@@ -483,12 +504,14 @@ int alaya_full_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, c
         ReqDesc &d = hd[b];
         d.pt_off = (int32_t)((int64_t)seqs[b] * c->L.mpps);
         d.n = (int32_t)n;
-        d.n_pad = (int32_t)(pages * kPageTokens);
+        d.head_stride = 0;
         d.k = 0;
         d.beta = 0.f;
         d.tile_start = tiles;
         d.score_off = 0;
-        tiles += (int)((pages + ppt - 1) / ppt);
+        d.seg_start = d.nseg = d.seg_len = 0;
+        d.n_tiles = (int32_t)((pages + ppt - 1) / ppt);
+        tiles += d.n_tiles;
     }
     if (tiles > c->L.max_tiles) return fail(ALAYA_E_NOMEM, "partial-result workspace too small");
     if (!c->ring_ev[slot]) {
@@ -556,12 +579,13 @@ const float *alaya_debug_scores(const alaya_cache *c)
     return c->dv.scores;
 }
 
-int alaya_set_tuning(alaya_cache *c, int score_pages_per_wave, int attend_splits)
+int alaya_set_tuning(alaya_cache *c, int score_pages_per_wave, int attend_splits, int select_segment_tokens)
 {
     if (!c) return fail(ALAYA_E_INVAL, "null cache handle");
     if (score_pages_per_wave > 64 || attend_splits > kMaxSplits) return fail(ALAYA_E_INVAL, "knob out of range");
     c->tune_ppw = score_pages_per_wave > 0 ? score_pages_per_wave : 0;
     c->tune_splits = attend_splits > 0 ? attend_splits : 0;
+    c->tune_seg = select_segment_tokens > 0 ? select_segment_tokens : 0;
     return ALAYA_OK;
 }
 

@@ -63,7 +63,7 @@ __global__ __launch_bounds__(kAttendThreads) void attend_kernel(
     const int r = rh / H_q, h = rh % H_q;
     const int kvh = h / (H_q / H_kv);
     const ReqDesc dsc = desc[r];
-    const size_t off = (size_t)dsc.score_off + (size_t)h * dsc.n_pad;
+    const size_t off = (size_t)dsc.score_off + (size_t)h * dsc.head_stride;
     const int32_t *ids = sel_ids + off;
     const float *ss = sel_scores + off;
     const int cnt = counts[rh];
@@ -174,15 +174,33 @@ __global__ __launch_bounds__(D) void combine_kernel(const ReqDesc *__restrict__ 
         first = (size_t)rh * splits * (D + 2);
         stride = D + 2;
     }
+    // loads are issued eight at a time so that their latencies overlap; the merge order stays fixed
+    constexpr int U = 8;
     float M = -INFINITY;
-    for (int i = 0; i < np; ++i) M = fmaxf(M, partials[first + i * stride]);
+    for (int i0 = 0; i0 < np; i0 += U) {
+        float mm[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) mm[u] = i0 + u < np ? partials[first + (size_t)(i0 + u) * stride] : -INFINITY;
+#pragma unroll
+        for (int u = 0; u < U; ++u) M = fmaxf(M, mm[u]);
+    }
     float L = 0.f, o = 0.f;
-    for (int i = 0; i < np; ++i) {
-        const float *p = partials + first + i * stride;
-        const float m = p[0];
-        const float w = m == -INFINITY ? 0.f : __expf(m - M);
-        L = fmaf(w, p[1], L);
-        o = fmaf(w, p[2 + threadIdx.x], o);
+    for (int i0 = 0; i0 < np; i0 += U) {
+        float mm[U], ll[U], aa[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const bool ok = i0 + u < np;
+            const float *p = partials + first + (size_t)(ok ? i0 + u : 0) * stride;
+            mm[u] = ok ? p[0] : -INFINITY;
+            ll[u] = p[1];
+            aa[u] = p[2 + threadIdx.x];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float w = mm[u] == -INFINITY ? 0.f : __expf(mm[u] - M);
+            L = fmaf(w, ll[u], L);
+            o = fmaf(w, aa[u], o);
+        }
     }
     out[(size_t)rh * D + threadIdx.x] = o / L;
 }
@@ -304,6 +322,10 @@ __global__ __launch_bounds__(256) void full_partial_kernel(const ReqDesc *__rest
                 const int tok = t4 * 4 + grp;
                 float v[EPL];
                 RS::load(vbase + (size_t)tok * ROW_BYTES, sub, v);
+                if (p * kPageTokens + tok >= dsc.n) { // unwritten tail of the last page: weight 0, but 0 * NaN is NaN
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) v[e] = 0.f;
+                }
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
                     const float pg = ps[wave][g][tok];

@@ -82,18 +82,37 @@ hipError_t launch_append(const Shape &sh, const int32_t *pt_row, void *k_pool, v
 // Scoring.  Grid: one workgroup per (tile, KV head); KV head is the fastest index so that with
 // 8 KV heads each head's stream stays on one XCD (workgroups are dealt to XCDs round-robin).
 // A tile is kScoreWaves * pages_per_wave consecutive pages of one request; each wavefront scores
-// pages_per_wave pages in a row.  Epilogue: the running maximum per (request, head), kept as an
-// order-preserving integer so that atomicMax is exact and order-free.
+// pages_per_wave pages in a row.
+//
+// The query stays in scalar registers: its address is wave-uniform, so the compiler fetches it with
+// scalar loads and feeds it to the vector ALU as the scalar operand.  bf16 uses the packed
+// dot-product instruction (two bf16 products and the fp32 accumulate in one op, both operands used
+// as stored); fp32 uses fused multiply-add.
+//
+// Epilogue, no global float atomics and nothing to reset:
+//   tile_max[tile][head]   maximum score of the tile (the heads' global maxima are reduced from these)
+//   hist[request, head][.] (top-k only) counts per top-11-bit bucket of the order-preserving score
+//                          image, gathered in LDS and flushed with integer atomics (exact, order-free)
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c,
+                                           false);
+}
+
 template <int DT, int D, int G>
 __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ desc, int B,
                                                      const int32_t *__restrict__ page_table,
-                                                     const void *__restrict__ qv, const uint4 *__restrict__ k_pool,
-                                                     float *__restrict__ scores, uint32_t *__restrict__ head_max,
-                                                     int H_kv, int ppw)
+                                                     const uint32_t *__restrict__ qw, const uint4 *__restrict__ k_pool,
+                                                     float *__restrict__ scores, float *__restrict__ tile_max,
+                                                     uint32_t *__restrict__ hist, int H_kv, int ppw, int want_hist)
 {
-    constexpr int E = Chunk<DT>::E;
-    constexpr int NC = D / E;
-    __shared__ float qs[G][D];
+    constexpr int NC = D * (DT == 0 ? 2 : 4) / 16; // 16-byte chunks per key
+    constexpr int QW = D * (DT == 0 ? 2 : 4) / 4;  // 32-bit words per query head
+    // two 16-bit counters per word: a workgroup scores at most 4 * 64 * 64 = 16384 tokens per head
+    __shared__ uint32_t lhist[G][kHistBins / 2];
+    __shared__ float wmax[kScoreWaves][G];
 
     const int kvh = blockIdx.x % H_kv;
     const int tile = blockIdx.x / H_kv;
@@ -102,18 +121,17 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
     const ReqDesc dsc = desc[r];
     const int H_q = H_kv * G;
 
-    for (int i = threadIdx.x; i < G * D; i += 256) {
-        const int g = i / D, c = i % D;
-        const size_t qi = ((size_t)r * H_q + kvh * G + g) * D + c;
-        qs[g][c] = DT == 0 ? bf16_to_f32(((const uint16_t *)qv)[qi]) : ((const float *)qv)[qi];
+    if (want_hist) {
+        for (int i = threadIdx.x; i < G * (kHistBins / 2); i += 256) (&lhist[0][0])[i] = 0u;
+        __syncthreads();
     }
-    __syncthreads();
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int n_pages = (dsc.n + kPageTokens - 1) >> 6;
     const int p_begin = ((tile - dsc.tile_start) * kScoreWaves + wave) * ppw;
     const int p_end = min(p_begin + ppw, n_pages);
+    const uint32_t *qh = qw + ((size_t)r * H_q + kvh * G) * QW; // wave-uniform: scalar loads
 
     float lmax[G];
 #pragma unroll
@@ -130,19 +148,32 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
         for (int g = 0; g < G; ++g) acc[g] = 0.f;
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-            float kf[E];
-            Chunk<DT>::unpack(kc[c], kf);
 #pragma unroll
-            for (int e = 0; e < E; ++e)
-#pragma unroll
-                for (int g = 0; g < G; ++g) acc[g] = fmaf(kf[e], qs[g][c * E + e], acc[g]);
+            for (int g = 0; g < G; ++g) {
+                const uint32_t *qg = qh + g * QW + c * 4;
+                if constexpr (DT == 0) {
+                    acc[g] = dot2_bf16(kc[c].x, qg[0], acc[g]);
+                    acc[g] = dot2_bf16(kc[c].y, qg[1], acc[g]);
+                    acc[g] = dot2_bf16(kc[c].z, qg[2], acc[g]);
+                    acc[g] = dot2_bf16(kc[c].w, qg[3], acc[g]);
+                } else {
+                    acc[g] = fmaf(__uint_as_float(kc[c].x), __uint_as_float(qg[0]), acc[g]);
+                    acc[g] = fmaf(__uint_as_float(kc[c].y), __uint_as_float(qg[1]), acc[g]);
+                    acc[g] = fmaf(__uint_as_float(kc[c].z), __uint_as_float(qg[2]), acc[g]);
+                    acc[g] = fmaf(__uint_as_float(kc[c].w), __uint_as_float(qg[3]), acc[g]);
+                }
+            }
         }
         const int j = p * kPageTokens + lane;
         if (j < dsc.n) {
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                scores[dsc.score_off + (size_t)(kvh * G + g) * dsc.n_pad + j] = acc[g];
+                scores[dsc.score_off + (size_t)(kvh * G + g) * dsc.head_stride + j] = acc[g];
                 lmax[g] = fmaxf(lmax[g], acc[g]);
+                if (want_hist) {
+                    const uint32_t bin = ord_key(acc[g]) >> 21;
+                    atomicAdd(&lhist[g][bin >> 1], 1u << ((bin & 1u) * 16u));
+                }
             }
         }
     }
@@ -152,19 +183,35 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
         float m = lmax[g];
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-        if (lane == 0 && m > -INFINITY) atomicMax(&head_max[r * H_q + kvh * G + g], ord_key(m));
+        if (lane == 0) wmax[wave][g] = m;
+    }
+    __syncthreads();
+    if (threadIdx.x < G) {
+        float m = wmax[0][threadIdx.x];
+#pragma unroll
+        for (int w = 1; w < kScoreWaves; ++w) m = fmaxf(m, wmax[w][threadIdx.x]);
+        tile_max[(size_t)tile * H_q + kvh * G + threadIdx.x] = m; // -inf if the tile's pages were all out of range
+    }
+    if (want_hist) {
+        uint32_t *gh = hist + ((size_t)r * H_q + kvh * G) * kHistBins;
+        for (int i = threadIdx.x; i < G * (kHistBins / 2); i += 256) {
+            const uint32_t v = (&lhist[0][0])[i];
+            if (v & 0xFFFFu) atomicAdd(&gh[2 * i], v & 0xFFFFu);
+            if (v >> 16) atomicAdd(&gh[2 * i + 1], v >> 16);
+        }
     }
 }
 
 template <int DT, int D>
 static hipError_t launch_score_g(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles,
-                                 int ppw, hipStream_t st)
+                                 int ppw, int want_hist, hipStream_t st)
 {
     const int G = sh.n_q_heads / sh.n_kv_heads;
     const dim3 grid((unsigned)(total_tiles * sh.n_kv_heads)), block(256);
-#define ALAYA_SCORE(GG)                                                                                     \
-    score_kernel<DT, D, GG><<<grid, block, 0, st>>>(dv.desc, B, dv.page_table, q, (const uint4 *)dv.k_pool, \
-                                                    dv.scores, dv.head_max, sh.n_kv_heads, ppw)
+#define ALAYA_SCORE(GG)                                                                                       \
+    score_kernel<DT, D, GG><<<grid, block, 0, st>>>(dv.desc, B, dv.page_table, (const uint32_t *)q,           \
+                                                    (const uint4 *)dv.k_pool, dv.scores, dv.tile_max, dv.hist, \
+                                                    sh.n_kv_heads, ppw, want_hist)
     switch (G) {
     case 1: ALAYA_SCORE(1); break;
     case 2: ALAYA_SCORE(2); break;
@@ -177,14 +224,14 @@ static hipError_t launch_score_g(const Shape &sh, const DeviceViews &dv, int B, 
 }
 
 hipError_t launch_score(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles, int ppw,
-                        hipStream_t st)
+                        int want_hist, hipStream_t st)
 {
     if (sh.dtype == 0) {
-        if (sh.head_dim == 128) return launch_score_g<0, 128>(sh, dv, B, q, total_tiles, ppw, st);
-        if (sh.head_dim == 64) return launch_score_g<0, 64>(sh, dv, B, q, total_tiles, ppw, st);
+        if (sh.head_dim == 128) return launch_score_g<0, 128>(sh, dv, B, q, total_tiles, ppw, want_hist, st);
+        if (sh.head_dim == 64) return launch_score_g<0, 64>(sh, dv, B, q, total_tiles, ppw, want_hist, st);
     } else {
-        if (sh.head_dim == 128) return launch_score_g<1, 128>(sh, dv, B, q, total_tiles, ppw, st);
-        if (sh.head_dim == 64) return launch_score_g<1, 64>(sh, dv, B, q, total_tiles, ppw, st);
+        if (sh.head_dim == 128) return launch_score_g<1, 128>(sh, dv, B, q, total_tiles, ppw, want_hist, st);
+        if (sh.head_dim == 64) return launch_score_g<1, 64>(sh, dv, B, q, total_tiles, ppw, want_hist, st);
     }
     return hipErrorInvalidValue;
 }

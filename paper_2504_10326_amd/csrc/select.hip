@@ -1,26 +1,28 @@
-// Selection of the critical tokens of one (request, query head) from its fp32 scores.
+// Selection of the critical tokens of every (request, query head) from its fp32 scores.
 //   top-k (Sec. 5.1.1): the k largest scores; equal scores at the k-th place go to the smaller id.
 //   DIPR  (Def. 2, 3) : every token with score >= max - beta.
-// One 1024-thread workgroup owns one head.  Everything is exact and order-deterministic: counting
-// is integer (radix select on the order-preserving image of the score), and placement is an ordered
-// compaction, so the selected list is the same on every run.
+// Everything is exact and order-deterministic: counting is integer (radix select on the
+// order-preserving image of the score) and placement is an ordered compaction, so the selected list
+// is the same on every run.
 //
-// top-k in four steps:
-//   1. histogram of the top 11 key bits over all n scores (LDS atomics)
-//   2. walk the histogram from the top: bucket b holds the k-th score; buckets above it are taken whole
-//   3. one ordered pass over the scores: tokens above b go to the front of the list ("definite"),
-//      tokens in b go behind them ("candidates"), each kept in ascending token order
-//   4. radix-refine the remaining 21 bits over the candidates only, then compact them in place:
-//      keep key > T, and the first `ties` tokens with key == T
-// DIPR is step 3 alone with the predicate score >= max - beta.
+// A head's n scores are cut into segments; one 1024-thread workgroup owns one segment.
+//   count   per segment: how many tokens are "definite" (top-k: bucket above the bucket b of the k-th
+//           score, which is read off the histogram the scoring pass left; DIPR: score >= max - beta)
+//           and how many are "candidates" (top-k only: bucket == b)
+//   place   per segment: prefix over the earlier segments' counts gives the write offsets; an ordered
+//           compaction puts definite tokens at the front of the head's list and candidates behind them,
+//           both in ascending token order
+//   finish  per head: (top-k) radix-refine the remaining 21 key bits over the candidates only and
+//           compact them in place - keep key > T and the first `ties` tokens with key == T; publish
+//           the count, copy ids out if asked, and zero the head's histogram for the next call
 #include "alaya_internal.h"
 
 namespace alaya {
 
-constexpr int kSelE = 4;                         // scores per thread per chunk
-constexpr int kSelWaves = kSelectThreads / 64;   // 16
-constexpr int kSelChunk = kSelectThreads * kSelE;
+constexpr int kSelE = 4;                       // scores per thread per chunk
+constexpr int kSelWaves = kSelectThreads / 64; // 16
 static_assert(kSelE * kSelWaves == 64, "the cross-wave scan maps one (e, wave) pair to one lane of wave 0");
+static_assert(kSelE * kSelectThreads == kSelChunkTokens, "chunk size");
 
 struct ScanShared {
     int32_t cnt[2][2][64]; // [parity][list][e * 16 + wave]
@@ -69,7 +71,7 @@ __device__ __forceinline__ void chunk_ranks(ScanShared &sh, int parity, const bo
     totB = sh.tot[parity][1];
 }
 
-// Walk a histogram from its top bin down (wave 0 only): find the bin holding the `need`-th largest
+// Walk a histogram from its top bin down (one wavefront): find the bin holding the `need`-th largest
 // element.  res[0] = bin, res[1] = elements in bins above it.
 __device__ __forceinline__ void find_bin(const uint32_t *hist, int nbins, int need, int32_t *res)
 {
@@ -95,171 +97,278 @@ __device__ __forceinline__ void find_bin(const uint32_t *hist, int nbins, int ne
     if (lane == 0) { res[0] = 0; res[1] = above - (int)hist[0]; } // unreachable when need <= total
 }
 
-__global__ __launch_bounds__(kSelectThreads) void select_kernel(
-    const ReqDesc *__restrict__ desc, int H_q, int mode, const float *__restrict__ scores,
-    uint32_t *__restrict__ head_max, float *__restrict__ head_M, int32_t *__restrict__ sel_ids,
+// blockIdx -> (request, head, segment).  Heads are the fastest index.
+struct SegId { int r, h, seg; };
+__device__ __forceinline__ SegId seg_of_block(const ReqDesc *desc, int B, int H_q)
+{
+    const int h = blockIdx.x % H_q;
+    const int gs = blockIdx.x / H_q;
+    int r = 0;
+    while (r + 1 < B && desc[r + 1].seg_start <= gs) ++r;
+    return {r, h, gs - desc[r].seg_start};
+}
+
+// What a token's score means for the selection, given the head's threshold data.
+struct Rule {
+    int topk;     // 1: bucket rule, 0: threshold rule
+    uint32_t b1;  // bucket of the k-th score
+    float thr;    // threshold rule: definite iff score >= thr
+    __device__ __forceinline__ void classify(float v, bool in, bool &definite, bool &candidate) const
+    {
+        if (topk) {
+            const uint32_t bin = ord_key(v) >> 21;
+            definite = in && bin > b1;
+            candidate = in && bin == b1;
+        } else {
+            definite = in && v >= thr;
+            candidate = false;
+        }
+    }
+};
+
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kSelectThreads) void select_count_kernel(
+    const ReqDesc *__restrict__ desc, int B, int H_q, int mode, const float *__restrict__ scores,
+    const float *__restrict__ tile_max, const uint32_t *__restrict__ hist, float *__restrict__ head_M,
+    int32_t *__restrict__ head_info, int32_t *__restrict__ seg_counts)
+{
+    __shared__ uint32_t lh[kHistBins];
+    __shared__ float wred[kSelWaves];
+    __shared__ int32_t ired[2][kSelWaves];
+    __shared__ int32_t res[2];
+
+    const SegId id = seg_of_block(desc, B, H_q);
+    const ReqDesc dsc = desc[id.r];
+    const int rh = id.r * H_q + id.h;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = dsc.n;
+
+    // the head's maximum score, from the scoring pass's per-tile maxima
+    float m = -INFINITY;
+    for (int t = tid; t < dsc.n_tiles; t += kSelectThreads)
+        m = fmaxf(m, tile_max[(size_t)(dsc.tile_start + t) * H_q + id.h]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if (lane == 0) wred[wave] = m;
+    const bool bucket_rule = mode == 0 && dsc.k < n;
+    if (bucket_rule)
+        for (int i = tid; i < kHistBins; i += kSelectThreads) lh[i] = hist[(size_t)rh * kHistBins + i];
+    __syncthreads();
+    float M = wred[0];
+#pragma unroll
+    for (int w = 1; w < kSelWaves; ++w) M = fmaxf(M, wred[w]);
+    if (bucket_rule && tid < 64) find_bin(lh, kHistBins, dsc.k, res);
+    __syncthreads();
+
+    Rule rule;
+    rule.topk = bucket_rule;
+    rule.b1 = bucket_rule ? (uint32_t)res[0] : 0u;
+    rule.thr = mode == 1 ? M - dsc.beta : -INFINITY; // top-k with k >= n: every token
+    if (id.seg == 0 && tid == 0) {
+        head_M[rh] = M;
+        head_info[2 * rh] = bucket_rule ? res[0] : -1;
+        head_info[2 * rh + 1] = bucket_rule ? res[1] : 0;
+    }
+
+    const float *s = scores + (size_t)dsc.score_off + (size_t)id.h * dsc.head_stride;
+    const int begin = id.seg * dsc.seg_len, end = min(n, begin + dsc.seg_len);
+    int ca = 0, cc = 0;
+    for (int c0 = begin; c0 < end; c0 += kSelChunkTokens) {
+#pragma unroll
+        for (int e = 0; e < kSelE; ++e) {
+            const int j = c0 + e * kSelectThreads + tid;
+            const bool in = j < end;
+            const float v = in ? s[j] : 0.f;
+            bool a, c;
+            rule.classify(v, in, a, c);
+            ca += a;
+            cc += c;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        ca += __shfl_xor(ca, o);
+        cc += __shfl_xor(cc, o);
+    }
+    if (lane == 0) { ired[0][wave] = ca; ired[1][wave] = cc; }
+    __syncthreads();
+    if (tid < 2) {
+        int t = 0;
+#pragma unroll
+        for (int w = 0; w < kSelWaves; ++w) t += ired[tid][w];
+        seg_counts[((size_t)rh * kMaxSegs + id.seg) * 2 + tid] = t;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kSelectThreads) void select_place_kernel(
+    const ReqDesc *__restrict__ desc, int B, int H_q, int mode, const float *__restrict__ scores,
+    const float *__restrict__ head_M, const int32_t *__restrict__ head_info,
+    const int32_t *__restrict__ seg_counts, int32_t *__restrict__ sel_ids, float *__restrict__ sel_scores)
+{
+    __shared__ ScanShared scan;
+    __shared__ int32_t base[2];
+
+    const SegId id = seg_of_block(desc, B, H_q);
+    const ReqDesc dsc = desc[id.r];
+    const int rh = id.r * H_q + id.h;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int n = dsc.n;
+
+    Rule rule;
+    rule.topk = head_info[2 * rh] >= 0;
+    rule.b1 = (uint32_t)head_info[2 * rh];
+    rule.thr = mode == 1 ? head_M[rh] - dsc.beta : -INFINITY;
+    const int above1 = head_info[2 * rh + 1];
+
+    if (tid < 64) { // earlier segments of this head: at most kMaxSegs = 64 of them
+        int a = 0, c = 0;
+        if (lane < id.seg) {
+            a = seg_counts[((size_t)rh * kMaxSegs + lane) * 2];
+            c = seg_counts[((size_t)rh * kMaxSegs + lane) * 2 + 1];
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            a += __shfl_xor(a, o);
+            c += __shfl_xor(c, o);
+        }
+        if (lane == 0) { base[0] = a; base[1] = above1 + c; }
+    }
+    __syncthreads();
+    int baseA = base[0], baseC = base[1];
+
+    const size_t off = (size_t)dsc.score_off + (size_t)id.h * dsc.head_stride;
+    const float *s = scores + off;
+    int32_t *ids = sel_ids + off;
+    float *ss = sel_scores + off;
+    const int begin = id.seg * dsc.seg_len, end = min(n, begin + dsc.seg_len);
+    int parity = 0;
+    for (int c0 = begin; c0 < end; c0 += kSelChunkTokens) {
+        float v[kSelE];
+        bool fa[kSelE], fb[kSelE];
+#pragma unroll
+        for (int e = 0; e < kSelE; ++e) {
+            const int j = c0 + e * kSelectThreads + tid;
+            const bool in = j < end;
+            v[e] = in ? s[j] : 0.f;
+            rule.classify(v[e], in, fa[e], fb[e]);
+        }
+        int exA[kSelE], exB[kSelE], totA, totB;
+        chunk_ranks(scan, parity, fa, fb, exA, exB, totA, totB);
+        parity ^= 1;
+#pragma unroll
+        for (int e = 0; e < kSelE; ++e) {
+            const int j = c0 + e * kSelectThreads + tid;
+            if (fa[e]) { ids[baseA + exA[e]] = j; ss[baseA + exA[e]] = v[e]; }
+            if (fb[e]) { ids[baseC + exB[e]] = j; ss[baseC + exB[e]] = v[e]; }
+        }
+        baseA += totA;
+        baseC += totB;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
+    const ReqDesc *__restrict__ desc, int H_q, int mode, const int32_t *__restrict__ head_info,
+    const int32_t *__restrict__ seg_counts, uint32_t *__restrict__ hist, int32_t *__restrict__ sel_ids,
     float *__restrict__ sel_scores, int32_t *__restrict__ counts, int32_t *__restrict__ out_ids,
     int32_t *__restrict__ out_counts, int64_t ids_stride, int32_t *__restrict__ status)
 {
-    __shared__ uint32_t hist[2048];
+    __shared__ uint32_t lh[kHistBins];
     __shared__ ScanShared scan;
     __shared__ int32_t res[2];
-    __shared__ float s_M;
+    __shared__ int32_t tot[2];
 
     const int rh = blockIdx.x;
     const int r = rh / H_q, h = rh % H_q;
     const ReqDesc dsc = desc[r];
-    const int n = dsc.n;
-    const size_t off = (size_t)dsc.score_off + (size_t)h * dsc.n_pad;
-    const float *s = scores + off;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const size_t off = (size_t)dsc.score_off + (size_t)h * dsc.head_stride;
     int32_t *ids = sel_ids + off;
     float *ss = sel_scores + off;
-    const int tid = threadIdx.x;
-    int parity = 0;
 
-    // The scoring pass left the running maximum here; take it and leave the slot clean for the next call.
-    if (tid == 0) {
-        const uint32_t e = head_max[rh];
-        const float M = ord_float(e);
-        s_M = M;
-        head_M[rh] = M;
-        head_max[rh] = 0u;
+    if (tid < 64) {
+        int a = 0, c = 0;
+        if (lane < dsc.nseg) {
+            a = seg_counts[((size_t)rh * kMaxSegs + lane) * 2];
+            c = seg_counts[((size_t)rh * kMaxSegs + lane) * 2 + 1];
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            a += __shfl_xor(a, o);
+            c += __shfl_xor(c, o);
+        }
+        if (lane == 0) { tot[0] = a; tot[1] = c; }
     }
     __syncthreads();
-    const float M = s_M;
-    int count = 0;
+    const bool bucket_rule = head_info[2 * rh] >= 0;
+    int count = tot[0];
 
-    if (mode == 1 /* DIPR */ || dsc.k >= n) {
-        // DIPR: threshold pass.  top-k with k >= n: every token (threshold -inf).
-        const float thr = (mode == 1) ? (M - dsc.beta) : -INFINITY;
-        int base = 0;
-        for (int c0 = 0; c0 < n; c0 += kSelChunk) {
-            float v[kSelE];
-            bool fa[kSelE], fb[kSelE];
-#pragma unroll
-            for (int e = 0; e < kSelE; ++e) {
-                const int j = c0 + e * kSelectThreads + tid;
-                v[e] = j < n ? s[j] : 0.f;
-                fa[e] = j < n && v[e] >= thr;
-                fb[e] = false;
-            }
-            int exA[kSelE], exB[kSelE], totA, totB;
-            chunk_ranks(scan, parity, fa, fb, exA, exB, totA, totB);
-            parity ^= 1;
-#pragma unroll
-            for (int e = 0; e < kSelE; ++e)
-                if (fa[e]) {
-                    ids[base + exA[e]] = c0 + e * kSelectThreads + tid;
-                    ss[base + exA[e]] = v[e];
-                }
-            base += totA;
-        }
-        count = base;
-    } else {
-        const int kk = dsc.k;
-        // 1. histogram of the top 11 bits
-        for (int i = tid; i < 2048; i += kSelectThreads) hist[i] = 0u;
-        __syncthreads();
-        for (int j = tid; j < n; j += kSelectThreads) atomicAdd(&hist[ord_key(s[j]) >> 21], 1u);
-        __syncthreads();
-        // 2. bucket of the k-th score
-        if (tid < 64) find_bin(hist, 2048, kk, res);
-        __syncthreads();
-        const uint32_t b1 = (uint32_t)res[0];
-        const int above1 = res[1];
-        const int cb = (int)hist[b1];
-        int need = kk - above1; // 1 <= need <= cb
-        __syncthreads();
-        // 3. ordered split into definite (front) and candidates (behind them)
-        {
-            int baseA = 0, baseC = above1;
-            for (int c0 = 0; c0 < n; c0 += kSelChunk) {
-                float v[kSelE];
-                bool fa[kSelE], fb[kSelE];
-#pragma unroll
-                for (int e = 0; e < kSelE; ++e) {
-                    const int j = c0 + e * kSelectThreads + tid;
-                    v[e] = j < n ? s[j] : 0.f;
-                    const uint32_t bin = ord_key(v[e]) >> 21;
-                    fa[e] = j < n && bin > b1;
-                    fb[e] = j < n && bin == b1;
-                }
-                int exA[kSelE], exB[kSelE], totA, totB;
-                chunk_ranks(scan, parity, fa, fb, exA, exB, totA, totB);
-                parity ^= 1;
-#pragma unroll
-                for (int e = 0; e < kSelE; ++e) {
-                    const int j = c0 + e * kSelectThreads + tid;
-                    if (fa[e]) { ids[baseA + exA[e]] = j; ss[baseA + exA[e]] = v[e]; }
-                    if (fb[e]) { ids[baseC + exB[e]] = j; ss[baseC + exB[e]] = v[e]; }
-                }
-                baseA += totA;
-                baseC += totB;
-            }
-        }
-        __syncthreads(); // candidate writes visible to the whole workgroup
+    if (bucket_rule) {
+        const uint32_t b1 = (uint32_t)head_info[2 * rh];
+        const int above1 = head_info[2 * rh + 1]; // == tot[0]
+        const int cb = tot[1];
+        int need = dsc.k - above1; // 1 <= need <= cb
+        int parity = 0;
         if (need < cb) {
-            // 4. refine over the candidates: bits [20:10], then bits [9:0]
+            // refine over the candidates: key bits [20:10], then bits [9:0]
             const float *cs = ss + above1;
-            for (int i = tid; i < 2048; i += kSelectThreads) hist[i] = 0u;
+            for (int i = tid; i < kHistBins; i += kSelectThreads) lh[i] = 0u;
             __syncthreads();
-            for (int i = tid; i < cb; i += kSelectThreads) atomicAdd(&hist[(ord_key(cs[i]) >> 10) & 0x7FFu], 1u);
+            for (int i = tid; i < cb; i += kSelectThreads) atomicAdd(&lh[(ord_key(cs[i]) >> 10) & 0x7FFu], 1u);
             __syncthreads();
-            if (tid < 64) find_bin(hist, 2048, need, res);
+            if (tid < 64) find_bin(lh, 2048, need, res);
             __syncthreads();
             const uint32_t b2 = (uint32_t)res[0];
             need -= res[1];
             __syncthreads();
-            for (int i = tid; i < 1024; i += kSelectThreads) hist[i] = 0u;
+            for (int i = tid; i < 1024; i += kSelectThreads) lh[i] = 0u;
             __syncthreads();
             const uint32_t pre = (b1 << 11) | b2; // key >> 10 of the threshold
             for (int i = tid; i < cb; i += kSelectThreads) {
                 const uint32_t key = ord_key(cs[i]);
-                if ((key >> 10) == pre) atomicAdd(&hist[key & 0x3FFu], 1u);
+                if ((key >> 10) == pre) atomicAdd(&lh[key & 0x3FFu], 1u);
             }
             __syncthreads();
-            if (tid < 64) find_bin(hist, 1024, need, res);
+            if (tid < 64) find_bin(lh, 1024, need, res);
             __syncthreads();
             const uint32_t T = (pre << 10) | (uint32_t)res[0];
-            const int ties = need - res[1]; // how many tokens with key == T are taken, smallest ids first
-            // ordered in-place compaction of the candidates
-            int baseG = 0, baseT = 0, kept = 0;
-            for (int c0 = 0; c0 < cb; c0 += kSelChunk) {
+            const int ties = need - res[1]; // tokens with key == T that are taken, smallest ids first
+            // ordered in-place compaction of the candidates (writes never pass the chunk being read)
+            int baseG = 0, baseT = 0;
+            for (int c0 = 0; c0 < cb; c0 += kSelChunkTokens) {
                 float v[kSelE];
-                int id[kSelE];
+                int idv[kSelE];
                 bool fa[kSelE], fb[kSelE];
 #pragma unroll
                 for (int e = 0; e < kSelE; ++e) {
                     const int i = c0 + e * kSelectThreads + tid;
                     v[e] = i < cb ? cs[i] : 0.f;
-                    id[e] = i < cb ? ids[above1 + i] : 0;
+                    idv[e] = i < cb ? ids[above1 + i] : 0;
                     const uint32_t key = ord_key(v[e]);
                     fa[e] = i < cb && key > T;
                     fb[e] = i < cb && key == T;
                 }
                 int exA[kSelE], exB[kSelE], totA, totB;
-                chunk_ranks(scan, parity, fa, fb, exA, exB, totA, totB); // barriers: all reads of this chunk done
+                chunk_ranks(scan, parity, fa, fb, exA, exB, totA, totB); // barriers: this chunk is fully read
                 parity ^= 1;
 #pragma unroll
                 for (int e = 0; e < kSelE; ++e) {
                     const int tb = baseT + exB[e]; // ties before this element
-                    const bool keep = fa[e] || (fb[e] && tb < ties);
-                    if (keep) {
+                    if (fa[e] || (fb[e] && tb < ties)) {
                         const int pos = above1 + baseG + exA[e] + min(tb, ties);
-                        ids[pos] = id[e];
+                        ids[pos] = idv[e];
                         ss[pos] = v[e];
                     }
                 }
                 baseG += totA;
                 baseT += totB;
-                kept = baseG + min(baseT, ties);
             }
-            (void)kept;
         }
-        count = kk;
+        count = dsc.k;
     }
 
-    __syncthreads(); // list complete and visible
+    __syncthreads(); // list complete and visible to the whole workgroup
     if (tid == 0) {
         counts[rh] = count;
         if (out_counts) out_counts[rh] = count;
@@ -270,13 +379,25 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
         int32_t *dst = out_ids + (size_t)rh * (size_t)ids_stride;
         for (int i = tid; i < m; i += kSelectThreads) dst[i] = ids[i];
     }
+    if (mode == 0) // the scoring pass of a top-k call filled this head's histogram: leave it clean
+        for (int i = tid; i < kHistBins; i += kSelectThreads) hist[(size_t)rh * kHistBins + i] = 0u;
 }
 
-hipError_t launch_select(const Shape &sh, const DeviceViews &dv, int B, int mode, int32_t *out_ids,
+hipError_t launch_select(const Shape &sh, const DeviceViews &dv, int B, int mode, int total_segs, int32_t *out_ids,
                          int32_t *out_counts, int64_t ids_stride, hipStream_t st)
 {
-    select_kernel<<<dim3((unsigned)(B * sh.n_q_heads)), dim3(kSelectThreads), 0, st>>>(
-        dv.desc, sh.n_q_heads, mode, dv.scores, dv.head_max, dv.head_M, dv.sel_ids, dv.sel_scores, dv.counts,
+    const dim3 block(kSelectThreads);
+    const dim3 seg_grid((unsigned)(total_segs * sh.n_q_heads));
+    select_count_kernel<<<seg_grid, block, 0, st>>>(dv.desc, B, sh.n_q_heads, mode, dv.scores, dv.tile_max, dv.hist,
+                                                    dv.head_M, dv.head_info, dv.seg_counts);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    select_place_kernel<<<seg_grid, block, 0, st>>>(dv.desc, B, sh.n_q_heads, mode, dv.scores, dv.head_M,
+                                                    dv.head_info, dv.seg_counts, dv.sel_ids, dv.sel_scores);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    select_finish_kernel<<<dim3((unsigned)(B * sh.n_q_heads)), block, 0, st>>>(
+        dv.desc, sh.n_q_heads, mode, dv.head_info, dv.seg_counts, dv.hist, dv.sel_ids, dv.sel_scores, dv.counts,
         out_ids, out_counts, ids_stride, dv.status);
     return hipGetLastError();
 }

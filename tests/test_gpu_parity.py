@@ -283,8 +283,8 @@ def test_custom_scale_and_profiling_hooks():
     c = make_cache(w, g)
     run_and_compare(c, w, g, A.ALAYA_TOPK, topk=w.topk, scale=0.25)
     c.set_profiling(True)
-    for ppw, splits in [(1, 1), (3, 7), (16, 64)]:
-        c.set_tuning(ppw, splits)
+    for ppw, splits, seg in [(1, 1, 1), (3, 7, 5000), (16, 64, 10 ** 6)]:
+        c.set_tuning(ppw, splits, seg)
         run_and_compare(c, w, g, A.ALAYA_TOPK, topk=w.topk)
     t = c.kernel_times()
     assert t["score"]["launches"] == 3 and t["score"]["sum_ms"] > 0 and t["combine"]["launches"] == 3
