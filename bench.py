@@ -42,6 +42,8 @@ def main() -> int:
     ap.add_argument("--pages-per-wave", type=int, default=0)
     ap.add_argument("--attend-splits", type=int, default=0)
     ap.add_argument("--segment-tokens", type=int, default=0)
+    ap.add_argument("--calibration-copy-mb", type=int, default=0,
+                    help="also run a plain device copy of this many MiB (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -137,6 +139,15 @@ def main() -> int:
         c.full_attn(seqs, q, out=out)
     torch.cuda.synchronize()
     full_ms = (time.perf_counter() - t) / 10 * 1e3
+
+    if args.calibration_copy_mb > 0:
+        # A plain copy of known size: what FETCH_SIZE / WRITE_SIZE read for it gives the counters' scale.
+        src = torch.ones(args.calibration_copy_mb << 18, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     cpu = None
     if not args.no_cpu_baseline:
