@@ -41,7 +41,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pages-per-wave", type=int, default=0)
     ap.add_argument("--attend-splits", type=int, default=0)
-    ap.add_argument("--segment-tokens", type=int, default=0)
+    ap.add_argument("--segment-pages", type=int, default=0)
+    ap.add_argument("--write-all-scores", action="store_true")
     ap.add_argument("--calibration-copy-mb", type=int, default=0,
                     help="also run a plain device copy of this many MiB (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -91,7 +92,7 @@ def main() -> int:
         mode, kw = A.ALAYA_TOPK, dict(topk=list(w.topk))
     else:
         mode, kw = A.ALAYA_DIPR, dict(beta=[args.beta] * w.batch)
-    c.set_tuning(args.pages_per_wave, args.attend_splits, args.segment_tokens)
+    c.set_tuning(args.pages_per_wave, args.attend_splits, args.segment_pages, args.write_all_scores)
     torch.cuda.synchronize()
 
     def step():

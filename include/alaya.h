@@ -150,25 +150,36 @@ int alaya_poll_status(alaya_cache *c, void *stream);
  * alaya_set_profiling(c, 1) makes every later call bracket each of its kernels with events;
  * alaya_kernel_times synchronises them and returns, per kernel slot, the summed duration in
  * milliseconds and the number of launches since profiling was (re)enabled.
- * Slots: 0 score, 1 select, 2 attend, 3 combine, 4 full-attention partial, 5 append.
+ * Slots: 0 score (the main scoring pass), 1 select, 2 attend, 3 combine, 4 full-attention partial,
+ * 5 append, 6 sample (scoring of the sampled strips + the threshold bound).
  * sum_ms, launches: HOST arrays of n_slots entries (n_slots <= ALAYA_N_KERNEL_SLOTS).
  */
-#define ALAYA_N_KERNEL_SLOTS 6
+#define ALAYA_N_KERNEL_SLOTS 7
 int alaya_set_profiling(alaya_cache *c, int enabled);
 int alaya_kernel_times(alaya_cache *c, double *sum_ms, int64_t *launches, int n_slots);
 
-/* Launch-shape knobs for measurement sweeps; each <= 0 keeps the built-in choice.
- * score_pages_per_wave: pages one wavefront scores in a row (1..64).
+/* Launch-shape knobs for measurement sweeps and tests; each <= 0 keeps the built-in choice.
+ * score_pages_per_wave: pages one wavefront scores in a row in the main scoring pass (1..16).
  * attend_splits: workgroups that share one head's selected set (1..64).
- * select_segment_tokens: tokens of one head that one selection workgroup scans (rounded up to whole
- * 4096-token chunks; at most 64 segments per head are used whatever the value). */
-int alaya_set_tuning(alaya_cache *c, int score_pages_per_wave, int attend_splits, int select_segment_tokens);
+ * select_segment_pages: pages of one head that one selection workgroup handles (1..2048; at most 64
+ * segments per head are used whatever the value).
+ * write_all_scores: 1 makes the scoring pass write every score instead of only those that can still
+ * be selected (results are identical either way; it exists so that tests can read all scores). */
+int alaya_set_tuning(alaya_cache *c, int score_pages_per_wave, int attend_splits, int select_segment_pages,
+                     int write_all_scores);
 
 /* Inspection hook for tests: DEVICE pointer to the fp32 scores the last alaya_sparse_attn call left
- * in the workspace, request after request, each block [n_q_heads][stride] with stride = n rounded up
- * to a whole page plus ALAYA_SCORE_PAD (entries j >= n are unspecified).  Valid until the next call. */
+ * in the workspace.  Meaningful only if that call ran with write_all_scores = 1.  Requests follow
+ * each other, each block being n_q_heads * (n rounded up to a whole page + ALAYA_SCORE_PAD) floats, of
+ * which the first n_pages * n_q_heads * 64 are laid out [page][head][64]: the score of token j sits
+ * in page j / 64 at position j % 64.  Valid until the next call on the cache. */
 #define ALAYA_SCORE_PAD 1088
 const float *alaya_debug_scores(const alaya_cache *c);
+
+/* Inspection hook for tests and measurement: synchronises `stream` and returns how many (token, score)
+ * pairs the scoring pass of the last alaya_sparse_attn call wrote, summed over requests and heads
+ * (with write_all_scores = 0 it is the number of scores that survived the running bound); -1 on error. */
+int64_t alaya_debug_survivors(alaya_cache *c, void *stream);
 
 /* Thread-local description of the last error returned on this thread ("" if none). */
 const char *alaya_last_error(void);

@@ -22,13 +22,14 @@ ALAYA_BF16, ALAYA_F32 = 0, 1
 ALAYA_TOPK, ALAYA_DIPR = 0, 1
 ALAYA_OK, ALAYA_E_INVAL, ALAYA_E_NOMEM, ALAYA_E_CAPACITY, ALAYA_E_EMPTY, ALAYA_E_DEVICE = 0, -1, -2, -3, -4, -5
 SCORE_PAD = 1088
-N_KERNEL_SLOTS = 6
-KERNEL_SLOTS = ("score", "select", "attend", "combine", "full_partial", "append")
+N_KERNEL_SLOTS = 7
+KERNEL_SLOTS = ("score", "select", "attend", "combine", "full_partial", "append", "sample")
 
 EXPORTS = (
     "alaya_pool_bytes", "alaya_workspace_bytes", "alaya_create_cache", "alaya_destroy_cache",
     "alaya_append_kv", "alaya_seq_len", "alaya_reset_seq", "alaya_sparse_attn", "alaya_full_attn",
     "alaya_poll_status", "alaya_set_profiling", "alaya_kernel_times", "alaya_set_tuning", "alaya_debug_scores",
+    "alaya_debug_survivors",
     "alaya_last_error",
 )
 
@@ -88,8 +89,9 @@ def lib() -> ctypes.CDLL:
         L.alaya_set_profiling.argtypes = [vp, i32]; L.alaya_set_profiling.restype = i32
         L.alaya_kernel_times.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64), i32]
         L.alaya_kernel_times.restype = i32
-        L.alaya_set_tuning.argtypes = [vp, i32, i32, i32]; L.alaya_set_tuning.restype = i32
+        L.alaya_set_tuning.argtypes = [vp, i32, i32, i32, i32]; L.alaya_set_tuning.restype = i32
         L.alaya_debug_scores.argtypes = [vp]; L.alaya_debug_scores.restype = vp
+        L.alaya_debug_survivors.argtypes = [vp, vp]; L.alaya_debug_survivors.restype = i64
         L.alaya_last_error.argtypes = []; L.alaya_last_error.restype = ctypes.c_char_p
         _lib = L
     return _lib
@@ -293,19 +295,30 @@ class Cache:
         return {name: {"sum_ms": ms[i], "launches": n[i]} for i, name in enumerate(KERNEL_SLOTS)}
 
     def debug_scores(self, lens: Sequence[int]):
-        """fp32 scores of the last sparse call as a list of torch views [Hq][n] (one per request)."""
+        """fp32 scores of the last sparse call (made with write_all_scores=1): list of tensors [Hq][n]."""
         torch = self.torch
         base = lib().alaya_debug_scores(self.handle)
         off = base - self.workspace.data_ptr()
+        hq = self.cfg.n_q_heads
         views = []
         for n in lens:
-            stride = (n + 63) // 64 * 64 + SCORE_PAD
-            nbytes = self.cfg.n_q_heads * stride * 4
-            blk = self.workspace[off:off + nbytes].view(torch.float32).view(self.cfg.n_q_heads, stride)
-            views.append(blk[:, :n])
-            off += nbytes
+            pages = (n + 63) // 64
+            blk = self.workspace[off:off + pages * hq * 64 * 4].view(torch.float32).view(pages, hq, 64)
+            views.append(blk.permute(1, 0, 2).reshape(hq, pages * 64)[:, :n])
+            off += hq * (pages * 64 + SCORE_PAD) * 4
         return views
 
+    def debug_survivors(self, stream=None) -> int:
+        """(token, score) pairs written by the scoring pass of the last sparse call, over all heads."""
+        return lib().alaya_debug_survivors(self.handle, _stream(stream))
+
     def set_tuning(self, score_pages_per_wave: int = 0, attend_splits: int = 0,
-                   select_segment_tokens: int = 0) -> None:
-        _check(lib().alaya_set_tuning(self.handle, score_pages_per_wave, attend_splits, select_segment_tokens))
+                   select_segment_pages: int = 0, write_all_scores: bool = False) -> None:
+        _check(lib().alaya_set_tuning(self.handle, score_pages_per_wave, attend_splits, select_segment_pages,
+                                      int(write_all_scores)))
+        self._tuning = (score_pages_per_wave, attend_splits, select_segment_pages, bool(write_all_scores))
+
+    def set_write_all_scores(self, flag: bool) -> None:
+        """Toggle only the write-everything switch, keeping the other knobs."""
+        t = getattr(self, "_tuning", (0, 0, 0, False))
+        self.set_tuning(t[0], t[1], t[2], flag)

@@ -7,45 +7,59 @@ namespace alaya {
 
 constexpr int kPageTokens = 64;      // one page == one wavefront of tokens
 constexpr int kScoreWaves = 4;       // wavefronts per scoring workgroup
-constexpr int kSelectThreads = 1024; // one workgroup selects for one (request, query head)
+constexpr int kMaxPagesPerWave = 16; // pages one wavefront scores in a row, at most
+constexpr int kSelectThreads = 1024;
 constexpr int kAttendThreads = 256;
 constexpr int kMaxSplits = 64;
+constexpr int kHistBins = 2048;      // top 11 bits of the order-preserving score image
+constexpr int kMaxSegs = 64;         // selection segments per head
+constexpr int kMaxSegPages = 2048;   // pages per selection segment
+
+// Elements added to each head's row in the per-head arrays so that rows of different heads, touched
+// at the same offset at the same time, do not all start on the same memory channel.
+constexpr int kScorePad = 1088; // 17 * 256 bytes
 
 // Per-request descriptor, built on the host for every attention call and copied to the device.
 struct ReqDesc {
-    int32_t pt_off;      // first entry of this sequence's row in the device page table
-    int32_t n;           // cached tokens
-    int32_t head_stride; // elements between consecutive heads in the score / id arrays
-    int32_t k;           // top-k, already clamped to n (0 in DIPR mode)
-    float beta;          // DIPR margin (raw inner-product units)
-    int32_t tile_start;  // first scoring / full-attention tile of this request (prefix sum)
-    int64_t score_off;   // offset (elements) of this request's [n_q_heads][head_stride] block
-    int32_t seg_start;   // first selection segment of this request (prefix sum, per head)
-    int32_t nseg;        // selection segments per head
-    int32_t seg_len;     // tokens per segment (a multiple of the selection chunk)
-    int32_t n_tiles;     // scoring tiles of this request
+    int32_t pt_off;        // first entry of this sequence's row in the device page table
+    int32_t n;             // cached tokens
+    int32_t head_stride;   // elements between consecutive heads in the per-head arrays
+    int32_t k;             // top-k, already clamped to n (0 in DIPR mode)
+    float beta;            // DIPR margin (raw inner-product units)
+    int32_t tile_start;    // first phase-A scoring tile / full-attention tile of this request (prefix sum)
+    int64_t score_off;     // offset (elements) of this request's block in every per-token array
+    int32_t page_start;    // pages of the requests before this one (prefix sum)
+    int32_t n_pages;       // pages of this request
+    int32_t seg_start;     // first selection segment of this request (prefix sum, per head)
+    int32_t nseg;          // selection segments per head
+    int32_t seg_pages;     // pages per selection segment
+    int32_t tileb_start;   // first phase-B scoring tile of this request (prefix sum)
+    int32_t sample_stride; // S: phase A scores pages 0, S, 2S, ... in full; 1 = no pruning
+    int32_t reserved;
 };
-static_assert(sizeof(ReqDesc) == 48, "ReqDesc layout");
+static_assert(sizeof(ReqDesc) == 64, "ReqDesc layout");
 
-// Elements added to each head's row of scores so that the rows of different heads, which are written
-// at the same token offset at the same time, do not all start on the same memory channel.
-constexpr int kScorePad = 1088; // 17 * 256 bytes
-
-constexpr int kHistBins = 2048; // top 11 bits of the order-preserving score image
-constexpr int kSelChunkTokens = 4096;
-constexpr int kMaxSegs = 64;
-
-// Device views handed to the launchers.
+// Device views handed to the launchers.  "per-token arrays" hold one element per (query head, token):
+// a request's block starts at score_off and spans n_q_heads * head_stride elements.
 struct DeviceViews {
     const ReqDesc *desc;       // [B]
     const int32_t *page_table; // [max_seqs][max_pages_per_seq]
     const void *k_pool;
     const void *v_pool;
-    float *scores;             // [sum over requests of n_q_heads * head_stride]
-    int32_t *sel_ids;          // same extent
-    float *sel_scores;         // same extent
-    float *tile_max;           // [scoring tiles][n_q_heads]: maximum score of each tile
-    uint32_t *hist;            // [max_batch * n_q_heads][kHistBins]; zero between calls
+    // scoring output: the survivors of each page, [page][head][64] inside the request's block ...
+    float *cand_scores;
+    int32_t *cand_ids;
+    int32_t *page_cnt;         // ... and how many there are: [head][n_pages] per request, requests in order
+    // selection, stage 1: per (head, segment) local lists, [head][head_stride] inside the block,
+    // segment s at s * seg_pages * 64: definite tokens first, tie-bucket tokens behind them
+    float *loc_scores;
+    int32_t *loc_ids;
+    // selection, stage 2 = what attention reads: [head][head_stride] inside the block
+    float *sel_scores;
+    int32_t *sel_ids;
+    uint32_t *hist;            // [max_batch * n_q_heads][kHistBins] bucket counts of the survivors; zero between calls
+    uint32_t *head_maxkey;     // [max_batch * n_q_heads] maximum score as an ordered key; zero between calls
+    uint32_t *tau;             // [max_batch * n_q_heads] lower bound of the selection threshold (ordered key)
     int32_t *seg_counts;       // [max_batch * n_q_heads][kMaxSegs][2]
     float *head_M;             // [max_batch * n_q_heads]: maximum score per head
     int32_t *head_info;        // [max_batch * n_q_heads][2]: bucket of the k-th score (-1: threshold rule), tokens above it
@@ -65,10 +79,13 @@ struct Shape {
 hipError_t launch_append(const Shape &sh, const int32_t *page_table_row, void *k_pool, void *v_pool,
                          const void *k, const void *v, int64_t n_old, int64_t t, hipStream_t st);
 
+// phase 0 scores the sampled pages in full, phase 1 the other pages against dv.tau.
 hipError_t launch_score(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles,
-                        int pages_per_wave, int want_hist, hipStream_t st);
+                        int pages_per_wave, int phase, hipStream_t st);
+// mode: 0 top-k, 1 DIPR
+hipError_t launch_tau(const Shape &sh, const DeviceViews &dv, int B, int mode, hipStream_t st);
 
-// count -> place -> finish; total_segs = sum over requests of nseg
+// stats -> local -> finish; total_segs = sum over requests of nseg
 hipError_t launch_select(const Shape &sh, const DeviceViews &dv, int B, int mode, int total_segs,
                          int32_t *out_ids, int32_t *out_counts, int64_t ids_stride, hipStream_t st);
 

@@ -58,12 +58,12 @@ bool cfg_ok(const alaya_cache_config *c)
 }
 
 struct Layout {
-    size_t page_table, desc, scores, sel_ids, sel_scores, tile_max, hist, seg_counts, head_M, head_info, counts,
-        partials, status, total;
-    int64_t mpps;            // max pages per sequence
-    int64_t score_elems;     // capacity of each of scores / sel_ids / sel_scores
-    int64_t max_tiles;       // full-attention tiles
-    int64_t max_score_tiles; // scoring tiles (pages_per_wave = 1 is the worst case)
+    size_t page_table, desc, cand_scores, cand_ids, loc_scores, loc_ids, sel_scores, sel_ids, page_cnt, hist,
+        head_maxkey, tau, seg_counts, head_M, head_info, counts, partials, status, total;
+    int64_t mpps;        // max pages per sequence
+    int64_t score_elems; // capacity of each per-token array
+    int64_t max_tiles;   // full-attention tiles
+    int64_t max_pages;   // pages over one call
 };
 
 Layout make_layout(const alaya_cache_config &c)
@@ -72,16 +72,21 @@ Layout make_layout(const alaya_cache_config &c)
     L.mpps = (c.max_tokens_per_seq + kPageTokens - 1) / kPageTokens;
     L.score_elems = (int64_t)c.n_q_heads * (c.max_batch_tokens + (int64_t)(kPageTokens + kScorePad) * c.max_batch);
     L.max_tiles = kTargetGroups / c.n_kv_heads + 1 + c.max_batch;
-    L.max_score_tiles = (c.max_batch_tokens / kPageTokens + c.max_batch) / kScoreWaves + c.max_batch;
+    L.max_pages = c.max_batch_tokens / kPageTokens + c.max_batch;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     L.page_table = take((size_t)L.mpps * c.max_seqs * sizeof(int32_t));
     L.desc = take((size_t)c.max_batch * sizeof(ReqDesc));
-    L.scores = take((size_t)L.score_elems * sizeof(float));
-    L.sel_ids = take((size_t)L.score_elems * sizeof(int32_t));
+    L.cand_scores = take((size_t)L.score_elems * sizeof(float));
+    L.cand_ids = take((size_t)L.score_elems * sizeof(int32_t));
+    L.loc_scores = take((size_t)L.score_elems * sizeof(float));
+    L.loc_ids = take((size_t)L.score_elems * sizeof(int32_t));
     L.sel_scores = take((size_t)L.score_elems * sizeof(float));
-    L.tile_max = take((size_t)L.max_score_tiles * c.n_q_heads * sizeof(float));
+    L.sel_ids = take((size_t)L.score_elems * sizeof(int32_t));
+    L.page_cnt = take((size_t)L.max_pages * c.n_q_heads * sizeof(int32_t));
     L.hist = take((size_t)c.max_batch * c.n_q_heads * kHistBins * sizeof(uint32_t));
+    L.head_maxkey = take((size_t)c.max_batch * c.n_q_heads * sizeof(uint32_t));
+    L.tau = take((size_t)c.max_batch * c.n_q_heads * sizeof(uint32_t));
     L.seg_counts = take((size_t)c.max_batch * c.n_q_heads * kMaxSegs * 2 * sizeof(int32_t));
     L.head_M = take((size_t)c.max_batch * c.n_q_heads * sizeof(float));
     L.head_info = take((size_t)c.max_batch * c.n_q_heads * 2 * sizeof(int32_t));
@@ -112,7 +117,9 @@ struct alaya_cache {
     bool ring_used[kRing];
     int ring_pos;
     bool dev_ready;
-    int tune_ppw, tune_splits, tune_seg;
+    int tune_ppw, tune_splits, tune_seg, tune_noprune;
+    int last_ppw; // pages per wavefront of the last sparse call (layout of the survivor lists)
+    int last_pages, last_heads;
     // profiling
     bool prof;
     std::vector<hipEvent_t> ev;      // 2 * kProfPairs, created on demand
@@ -166,7 +173,8 @@ struct Timed {
 int ensure_device(alaya_cache *c, hipStream_t st)
 {
     if (c->dev_ready) return ALAYA_OK;
-    const size_t nh = (size_t)c->cfg.max_batch * c->cfg.n_q_heads * kHistBins;
+    // the histograms and the running maxima sit next to each other in the workspace: one fill
+    const size_t nh = (size_t)(c->L.tau - c->L.hist) / sizeof(uint32_t);
     hipError_t e = launch_fill_u32(c->dv.hist, nh, 0u, st);
     if (e == hipSuccess) e = launch_fill_u32((uint32_t *)c->dv.status, 1, 0u, st);
     if (e != hipSuccess) return fail_hip(e, "workspace initialisation");
@@ -280,11 +288,16 @@ int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k
     c->dv.page_table = (const int32_t *)(c->ws + L.page_table);
     c->dv.k_pool = k_pool;
     c->dv.v_pool = v_pool;
-    c->dv.scores = (float *)(c->ws + L.scores);
-    c->dv.sel_ids = (int32_t *)(c->ws + L.sel_ids);
+    c->dv.cand_scores = (float *)(c->ws + L.cand_scores);
+    c->dv.cand_ids = (int32_t *)(c->ws + L.cand_ids);
+    c->dv.loc_scores = (float *)(c->ws + L.loc_scores);
+    c->dv.loc_ids = (int32_t *)(c->ws + L.loc_ids);
     c->dv.sel_scores = (float *)(c->ws + L.sel_scores);
-    c->dv.tile_max = (float *)(c->ws + L.tile_max);
+    c->dv.sel_ids = (int32_t *)(c->ws + L.sel_ids);
+    c->dv.page_cnt = (int32_t *)(c->ws + L.page_cnt);
     c->dv.hist = (uint32_t *)(c->ws + L.hist);
+    c->dv.head_maxkey = (uint32_t *)(c->ws + L.head_maxkey);
+    c->dv.tau = (uint32_t *)(c->ws + L.tau);
     c->dv.seg_counts = (int32_t *)(c->ws + L.seg_counts);
     c->dv.head_info = (int32_t *)(c->ws + L.head_info);
     c->dv.head_M = (float *)(c->ws + L.head_M);
@@ -314,6 +327,9 @@ int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k
     c->tune_ppw = 0;
     c->tune_splits = 0;
     c->tune_seg = 0;
+    c->tune_noprune = 0;
+    c->last_ppw = 0;
+    c->last_pages = c->last_heads = 0;
     c->prof = false;
     c->ev_n = 0;
     for (int i = 0; i < ALAYA_N_KERNEL_SLOTS; ++i) { c->sum_ms[i] = 0.0; c->launches[i] = 0; }
@@ -412,14 +428,15 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
     if (p->out_ids && p->ids_stride <= 0) return fail(ALAYA_E_INVAL, "out_ids given with ids_stride <= 0");
 
     hipStream_t st = (hipStream_t)stream;
+    // pages per wavefront in the main scoring pass: aim at about 8192 workgroups
     int ppw = c->tune_ppw;
     if (ppw <= 0) {
-        ppw = (int)((total_pages * c->cfg.n_kv_heads + (int64_t)kScoreWaves * kTargetGroups - 1) /
-                    ((int64_t)kScoreWaves * kTargetGroups));
+        ppw = (int)((total_pages * c->cfg.n_kv_heads + (int64_t)kScoreWaves * 8192 - 1) /
+                    ((int64_t)kScoreWaves * 8192));
         if (ppw < 1) ppw = 1;
-        if (ppw > 16) ppw = 16;
+        if (ppw > 8) ppw = 8;
     }
-    const int64_t seg_tokens = c->tune_seg > 0 ? c->tune_seg : 16384;
+    const int64_t seg_pages_want = c->tune_seg > 0 ? c->tune_seg : 256;
     int splits = c->tune_splits;
     if (splits <= 0) {
         splits = 512 / (B * n_q_heads);
@@ -431,7 +448,7 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
     int slot;
     rc = ring_acquire(c, &hd, &slot);
     if (rc != ALAYA_OK) return rc;
-    int tiles = 0, segs = 0;
+    int tiles = 0, tiles_b = 0, segs = 0, all_pages = 0;
     int64_t off = 0;
     for (int b = 0; b < B; ++b) {
         const int64_t n = c->seq_len[(size_t)seqs[b]];
@@ -444,20 +461,43 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
         d.beta = p->mode == ALAYA_DIPR ? p->beta[b] : 0.f;
         d.tile_start = tiles;
         d.score_off = off;
-        d.n_tiles = (int32_t)((pages + (int64_t)kScoreWaves * ppw - 1) / ((int64_t)kScoreWaves * ppw));
-        // selection segments: about seg_tokens tokens each, whole chunks, at most kMaxSegs per head
-        int64_t chunks = (n + kSelChunkTokens - 1) / kSelChunkTokens;
-        int64_t cps = (seg_tokens + kSelChunkTokens - 1) / kSelChunkTokens; // chunks per segment
-        if ((chunks + cps - 1) / cps > kMaxSegs) cps = (chunks + kMaxSegs - 1) / kMaxSegs;
-        d.seg_len = (int32_t)(cps * kSelChunkTokens);
-        d.nseg = (int32_t)((chunks + cps - 1) / cps);
+        if (pages > (int64_t)kMaxSegs * kMaxSegPages)
+            return fail(ALAYA_E_INVAL, "request %d: %lld tokens exceed the selection layout (%lld)", b, (long long)n,
+                        (long long)kMaxSegs * kMaxSegPages * kPageTokens);
+        d.n_pages = (int32_t)pages;
+        d.page_start = all_pages;
+        // selection segments: seg_pages pages each, at most kMaxSegs per head
+        int64_t per = seg_pages_want;
+        if ((pages + per - 1) / per > kMaxSegs) per = (pages + kMaxSegs - 1) / kMaxSegs;
+        d.seg_pages = (int32_t)per;
+        d.nseg = (int32_t)((pages + per - 1) / per);
         d.seg_start = segs;
-        tiles += d.n_tiles;
+        // Sample stride S: phase A writes n / S scores, phase B about k * S survivors; their sum is
+        // smallest at S = sqrt(n / k).  Powers of two, at most 32, and the sample must hold 2k tokens.
+        int S = 1;
+        if (!c->tune_noprune && pages >= 4) {
+            if (p->mode == ALAYA_TOPK) {
+                while (S < 32 && (int64_t)(2 * S) * (2 * S) * d.k <= n && (int64_t)2 * S * d.k * 2 <= n) S *= 2;
+            } else {
+                S = 16;
+            }
+            while (S > 1 && pages / S < 2) S /= 2;
+        }
+        d.sample_stride = S;
+        const int n_a = (int)((pages + S - 1) / S);
+        d.tileb_start = tiles_b;
+        d.reserved = 0;
+        tiles += (n_a + kScoreWaves - 1) / kScoreWaves;                                  // one page per wavefront
+        tiles_b += (int)((pages - n_a + (int64_t)kScoreWaves * ppw - 1) / ((int64_t)kScoreWaves * ppw));
+        all_pages += (int)pages;
         segs += d.nseg;
         off += (int64_t)n_q_heads * d.head_stride;
     }
+    c->last_ppw = ppw;
+    c->last_pages = all_pages;
+    c->last_heads = n_q_heads;
     if (off > c->L.score_elems) return fail(ALAYA_E_NOMEM, "score workspace too small");
-    if (tiles > c->L.max_score_tiles) return fail(ALAYA_E_NOMEM, "tile workspace too small");
+    if (all_pages > c->L.max_pages) return fail(ALAYA_E_NOMEM, "page-count workspace too small");
     if (!c->ring_ev[slot]) {
         hipError_t e = hipEventCreateWithFlags(&c->ring_ev[slot], hipEventDisableTiming);
         if (e != hipSuccess) { c->ring_ev[slot] = nullptr; return fail_hip(e, "hipEventCreate"); }
@@ -470,7 +510,16 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
     const Shape sh{c->cfg.dtype, c->cfg.head_dim, n_q_heads, c->cfg.n_kv_heads};
     const float scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)c->cfg.head_dim);
     hipError_t e;
-    { Timed tm(c, 0, st); e = launch_score(sh, c->dv, B, q, tiles, ppw, p->mode == ALAYA_TOPK, st); }
+    {
+        Timed tm(c, 6, st);
+        e = launch_score(sh, c->dv, B, q, tiles, 1, 0, st);
+        if (e == hipSuccess && tiles_b > 0) e = launch_tau(sh, c->dv, B, p->mode, st);
+    }
+    if (e != hipSuccess) return fail_hip(e, "sample scoring launch");
+    if (tiles_b > 0) {
+        Timed tm(c, 0, st);
+        e = launch_score(sh, c->dv, B, q, tiles_b, ppw, 1, st);
+    }
     if (e != hipSuccess) return fail_hip(e, "score launch");
     { Timed tm(c, 1, st); e = launch_select(sh, c->dv, B, p->mode, segs, p->out_ids, p->out_counts, p->ids_stride, st); }
     if (e != hipSuccess) return fail_hip(e, "select launch");
@@ -509,9 +558,11 @@ int alaya_full_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, c
         d.beta = 0.f;
         d.tile_start = tiles;
         d.score_off = 0;
-        d.seg_start = d.nseg = d.seg_len = 0;
-        d.n_tiles = (int32_t)((pages + ppt - 1) / ppt);
-        tiles += d.n_tiles;
+        d.page_start = d.n_pages = d.seg_start = d.nseg = d.seg_pages = 0;
+        d.tileb_start = 0;
+        d.sample_stride = 1;
+        d.reserved = 0;
+        tiles += (int)((pages + ppt - 1) / ppt);
     }
     if (tiles > c->L.max_tiles) return fail(ALAYA_E_NOMEM, "partial-result workspace too small");
     if (!c->ring_ev[slot]) {
@@ -576,16 +627,35 @@ int alaya_kernel_times(alaya_cache *c, double *sum_ms, int64_t *launches, int n_
 const float *alaya_debug_scores(const alaya_cache *c)
 {
     if (!c) { fail(ALAYA_E_INVAL, "null cache handle"); return nullptr; }
-    return c->dv.scores;
+    return c->dv.cand_scores;
 }
 
-int alaya_set_tuning(alaya_cache *c, int score_pages_per_wave, int attend_splits, int select_segment_tokens)
+int64_t alaya_debug_survivors(alaya_cache *c, void *stream)
+{
+    if (!c) { fail(ALAYA_E_INVAL, "null cache handle"); return -1; }
+    const size_t n = (size_t)c->last_pages * c->last_heads;
+    if (n == 0) return 0;
+    std::vector<int32_t> h(n);
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = hipMemcpyAsync(h.data(), c->dv.page_cnt, n * sizeof(int32_t), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) { fail_hip(e, "survivor count read"); return -1; }
+    int64_t tot = 0;
+    for (size_t i = 0; i < n; ++i) tot += h[i];
+    return tot;
+}
+
+int alaya_set_tuning(alaya_cache *c, int score_pages_per_wave, int attend_splits, int select_segment_pages,
+                     int write_all_scores)
 {
     if (!c) return fail(ALAYA_E_INVAL, "null cache handle");
-    if (score_pages_per_wave > 64 || attend_splits > kMaxSplits) return fail(ALAYA_E_INVAL, "knob out of range");
+    if (score_pages_per_wave > kMaxPagesPerWave || attend_splits > kMaxSplits ||
+        select_segment_pages > kMaxSegPages)
+        return fail(ALAYA_E_INVAL, "knob out of range");
     c->tune_ppw = score_pages_per_wave > 0 ? score_pages_per_wave : 0;
     c->tune_splits = attend_splits > 0 ? attend_splits : 0;
-    c->tune_seg = select_segment_tokens > 0 ? select_segment_tokens : 0;
+    c->tune_seg = select_segment_pages > 0 ? select_segment_pages : 0;
+    c->tune_noprune = write_all_scores > 0 ? 1 : 0;
     return ALAYA_OK;
 }
 

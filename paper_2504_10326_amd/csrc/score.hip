@@ -11,34 +11,10 @@
 
 namespace alaya {
 
-__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
-__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
-
-// Unpack one 16-byte chunk into floats: 8 bf16 or 4 fp32.
-template <int DT> struct Chunk;
-template <> struct Chunk<0> {
-    static constexpr int E = 8;
-    __device__ static __forceinline__ void unpack(const uint4 &c, float *f)
-    {
-        f[0] = bf16_lo(c.x); f[1] = bf16_hi(c.x); f[2] = bf16_lo(c.y); f[3] = bf16_hi(c.y);
-        f[4] = bf16_lo(c.z); f[5] = bf16_hi(c.z); f[6] = bf16_lo(c.w); f[7] = bf16_hi(c.w);
-    }
-};
-template <> struct Chunk<1> {
-    static constexpr int E = 4;
-    __device__ static __forceinline__ void unpack(const uint4 &c, float *f)
-    {
-        f[0] = __uint_as_float(c.x); f[1] = __uint_as_float(c.y);
-        f[2] = __uint_as_float(c.z); f[3] = __uint_as_float(c.w);
-    }
-};
-
 // ------------------------------------------------------------------------------------------------
 // Append: one thread moves one 16-byte slice of one token's key and of its value.
 //   k, v   [t][H_kv][D] token-major (what the model emits)
 //   K pool [page][kvh][D/E][64][E]      V pool [page][kvh][64][D]
-template <int DT>
 __global__ __launch_bounds__(256) void append_kernel(const int32_t *__restrict__ pt_row,
                                                       uint4 *__restrict__ k_pool, uint4 *__restrict__ v_pool,
                                                       const uint4 *__restrict__ k, const uint4 *__restrict__ v,
@@ -61,38 +37,41 @@ __global__ __launch_bounds__(256) void append_kernel(const int32_t *__restrict__
 hipError_t launch_append(const Shape &sh, const int32_t *pt_row, void *k_pool, void *v_pool, const void *k,
                          const void *v, int64_t n_old, int64_t t, hipStream_t st)
 {
-    const int E = sh.dtype == 0 ? 8 : 4;
-    const int NC = sh.head_dim / E;
+    const int NC = sh.head_dim * (sh.dtype == 0 ? 2 : 4) / 16;
     const int64_t total = t * sh.n_kv_heads * NC;
     int64_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
     if (blocks < 1) blocks = 1;
-    if (sh.dtype == 0)
-        append_kernel<0><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(pt_row, (uint4 *)k_pool, (uint4 *)v_pool,
-                                                                       (const uint4 *)k, (const uint4 *)v, n_old, t,
-                                                                       sh.n_kv_heads, NC);
-    else
-        append_kernel<1><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(pt_row, (uint4 *)k_pool, (uint4 *)v_pool,
-                                                                       (const uint4 *)k, (const uint4 *)v, n_old, t,
-                                                                       sh.n_kv_heads, NC);
+    append_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(pt_row, (uint4 *)k_pool, (uint4 *)v_pool,
+                                                                (const uint4 *)k, (const uint4 *)v, n_old, t,
+                                                                sh.n_kv_heads, NC);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------------
 // Scoring.  Grid: one workgroup per (tile, KV head); KV head is the fastest index so that with
 // 8 KV heads each head's stream stays on one XCD (workgroups are dealt to XCDs round-robin).
-// A tile is kScoreWaves * pages_per_wave consecutive pages of one request; each wavefront scores
-// pages_per_wave pages in a row.
+// A tile is four wavefronts' worth of pages; a wavefront scores pages_per_wave pages of one request.
 //
-// The query stays in scalar registers: its address is wave-uniform, so the compiler fetches it with
-// scalar loads and feeds it to the vector ALU as the scalar operand.  bf16 uses the packed
-// dot-product instruction (two bf16 products and the fp32 accumulate in one op, both operands used
-// as stored); fp32 uses fused multiply-add.
+// bf16 uses the packed dot-product instruction (two bf16 products and the fp32 accumulate in one op,
+// both operands used as stored), the query streamed through scalar registers; fp32 uses fused
+// multiply-add.
 //
-// Epilogue, no global float atomics and nothing to reset:
-//   tile_max[tile][head]   maximum score of the tile (the heads' global maxima are reduced from these)
-//   hist[request, head][.] (top-k only) counts per top-11-bit bucket of the order-preserving score
-//                          image, gathered in LDS and flushed with integer atomics (exact, order-free)
+// What is written.  Writing every fp32 score back costs far more than its 6 % share of the bytes (HBM
+// dislikes a write stream mixed into the read stream: a read-only scan of the same keys runs at
+// 6.3 TB/s, the same scan writing all scores at 5.3), and nearly all of those scores can never be
+// selected.  So a wavefront writes only the SURVIVORS of each page - (token id, score) pairs,
+// compacted, ascending, plus their count - where a survivor is a score at or above `tau`, a lower
+// bound of the head's final selection threshold.  The bound comes from a sample, with no atomics and no feedback between
+// workgroups:
+//   phase A  scores every S-th page of each request and writes all of those scores (tau = 0);
+//   tau      (tau_kernel) top-k: the k-th largest score of a SUBSET is never above the k-th largest of
+//            the whole, so the lower edge of the histogram bucket holding the sample's k-th largest
+//            score is a valid tau; DIPR: tau = (sample max) - beta <= (true max) - beta;
+//   phase B  scores the remaining pages against tau.
+// tau never exceeds the final threshold, so nothing that can be selected is ever dropped: the
+// selection that follows is exact.  It is also deterministic - the survivor lists depend on the
+// data only, not on timing.
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 
 __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c)
@@ -101,48 +80,62 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c)
                                            false);
 }
 
+// Page number (within its request) of the i-th page of a phase, for sample stride S.
+// Phase A takes pages 0, S, 2S, ...; phase B the others, in order.
+__device__ __forceinline__ int phase_page(int phase, int i, int S)
+{
+    return phase == 0 ? i * S : i + i / (S - 1) + 1;
+}
+
 template <int DT, int D, int G>
 __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ desc, int B,
                                                      const int32_t *__restrict__ page_table,
                                                      const uint32_t *__restrict__ qw, const uint4 *__restrict__ k_pool,
-                                                     float *__restrict__ scores, float *__restrict__ tile_max,
-                                                     uint32_t *__restrict__ hist, int H_kv, int ppw, int want_hist)
+                                                     float *__restrict__ cand_scores, int32_t *__restrict__ cand_ids,
+                                                     int32_t *__restrict__ page_cnt,
+                                                     const uint32_t *__restrict__ tau_in, int H_kv, int ppw,
+                                                     int phase)
 {
     constexpr int NC = D * (DT == 0 ? 2 : 4) / 16; // 16-byte chunks per key
     constexpr int QW = D * (DT == 0 ? 2 : 4) / 4;  // 32-bit words per query head
-    // two 16-bit counters per word: a workgroup scores at most 4 * 64 * 64 = 16384 tokens per head
-    __shared__ uint32_t lhist[G][kHistBins / 2];
-    __shared__ float wmax[kScoreWaves][G];
 
     const int kvh = blockIdx.x % H_kv;
     const int tile = blockIdx.x / H_kv;
     int r = 0;
-    while (r + 1 < B && desc[r + 1].tile_start <= tile) ++r;
+    if (phase == 0) while (r + 1 < B && desc[r + 1].tile_start <= tile) ++r;
+    else while (r + 1 < B && desc[r + 1].tileb_start <= tile) ++r;
     const ReqDesc dsc = desc[r];
     const int H_q = H_kv * G;
-
-    if (want_hist) {
-        for (int i = threadIdx.x; i < G * (kHistBins / 2); i += 256) (&lhist[0][0])[i] = 0u;
-        __syncthreads();
-    }
+    const int rh0 = r * H_q + kvh * G; // first head of this group
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
-    const int n_pages = (dsc.n + kPageTokens - 1) >> 6;
-    const int p_begin = ((tile - dsc.tile_start) * kScoreWaves + wave) * ppw;
-    const int p_end = min(p_begin + ppw, n_pages);
-    const uint32_t *qh = qw + ((size_t)r * H_q + kvh * G) * QW; // wave-uniform: scalar loads
+    const int S = dsc.sample_stride;
+    const int n_a = (dsc.n_pages + S - 1) / S;                   // pages of phase A
+    const int n_mine = phase == 0 ? n_a : dsc.n_pages - n_a;     // pages of this phase
+    // a wavefront takes `ppw` consecutive pages of its phase
+    const int i_begin = ((tile - (phase == 0 ? dsc.tile_start : dsc.tileb_start)) * kScoreWaves + wave) * ppw;
+    const int i_end = min(i_begin + ppw, n_mine);
+    if (i_begin >= i_end) return;                                // whole wavefront; no barriers below
+    const uint4 *qh = (const uint4 *)(qw + (size_t)rh0 * QW);    // wave-uniform address: scalar loads
 
-    float lmax[G];
+    uint32_t tau[G];
 #pragma unroll
-    for (int g = 0; g < G; ++g) lmax[g] = -INFINITY;
+    for (int g = 0; g < G; ++g) tau[g] = phase == 0 ? 0u : tau_in[rh0 + g];
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
 
-    for (int p = p_begin; p < p_end; ++p) {
+    for (int i = i_begin; i < i_end; ++i) {
+        const int p = phase_page(phase, i, S);
         const int phys = page_table[dsc.pt_off + p];
         const uint4 *base = k_pool + ((size_t)phys * H_kv + kvh) * (size_t)(NC * 64) + lane;
         uint4 kc[NC];
 #pragma unroll
         for (int c = 0; c < NC; ++c) kc[c] = base[c * 64];
+        // The query (64 * G words) is streamed through scalar registers for every page.  The offset
+        // is opaque to the compiler so that it does not hoist all of it out of the page loop.
+        int opaque_zero = 0;
+        asm volatile("" : "+s"(opaque_zero));
+        const uint4 *qp = qh + opaque_zero;
         float acc[G];
 #pragma unroll
         for (int g = 0; g < G; ++g) acc[g] = 0.f;
@@ -150,68 +143,48 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
         for (int c = 0; c < NC; ++c) {
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                const uint32_t *qg = qh + g * QW + c * 4;
+                const uint4 qc = qp[g * (QW / 4) + c];
                 if constexpr (DT == 0) {
-                    acc[g] = dot2_bf16(kc[c].x, qg[0], acc[g]);
-                    acc[g] = dot2_bf16(kc[c].y, qg[1], acc[g]);
-                    acc[g] = dot2_bf16(kc[c].z, qg[2], acc[g]);
-                    acc[g] = dot2_bf16(kc[c].w, qg[3], acc[g]);
+                    acc[g] = dot2_bf16(kc[c].x, qc.x, acc[g]);
+                    acc[g] = dot2_bf16(kc[c].y, qc.y, acc[g]);
+                    acc[g] = dot2_bf16(kc[c].z, qc.z, acc[g]);
+                    acc[g] = dot2_bf16(kc[c].w, qc.w, acc[g]);
                 } else {
-                    acc[g] = fmaf(__uint_as_float(kc[c].x), __uint_as_float(qg[0]), acc[g]);
-                    acc[g] = fmaf(__uint_as_float(kc[c].y), __uint_as_float(qg[1]), acc[g]);
-                    acc[g] = fmaf(__uint_as_float(kc[c].z), __uint_as_float(qg[2]), acc[g]);
-                    acc[g] = fmaf(__uint_as_float(kc[c].w), __uint_as_float(qg[3]), acc[g]);
+                    acc[g] = fmaf(__uint_as_float(kc[c].x), __uint_as_float(qc.x), acc[g]);
+                    acc[g] = fmaf(__uint_as_float(kc[c].y), __uint_as_float(qc.y), acc[g]);
+                    acc[g] = fmaf(__uint_as_float(kc[c].z), __uint_as_float(qc.z), acc[g]);
+                    acc[g] = fmaf(__uint_as_float(kc[c].w), __uint_as_float(qc.w), acc[g]);
                 }
             }
         }
         const int j = p * kPageTokens + lane;
-        if (j < dsc.n) {
+        const bool valid = j < dsc.n;
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                scores[dsc.score_off + (size_t)(kvh * G + g) * dsc.head_stride + j] = acc[g];
-                lmax[g] = fmaxf(lmax[g], acc[g]);
-                if (want_hist) {
-                    const uint32_t bin = ord_key(acc[g]) >> 21;
-                    atomicAdd(&lhist[g][bin >> 1], 1u << ((bin & 1u) * 16u));
-                }
+        for (int g = 0; g < G; ++g) {
+            const bool keep = valid && ord_key(acc[g]) >= tau[g];
+            const unsigned long long m = __ballot(keep);
+            if (keep) {
+                const size_t pos = (size_t)dsc.score_off + ((size_t)p * H_q + kvh * G + g) * kPageTokens +
+                                   (size_t)__popcll(m & lt_mask);
+                cand_scores[pos] = acc[g];
+                cand_ids[pos] = j;
             }
-        }
-    }
-
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        float m = lmax[g];
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-        if (lane == 0) wmax[wave][g] = m;
-    }
-    __syncthreads();
-    if (threadIdx.x < G) {
-        float m = wmax[0][threadIdx.x];
-#pragma unroll
-        for (int w = 1; w < kScoreWaves; ++w) m = fmaxf(m, wmax[w][threadIdx.x]);
-        tile_max[(size_t)tile * H_q + kvh * G + threadIdx.x] = m; // -inf if the tile's pages were all out of range
-    }
-    if (want_hist) {
-        uint32_t *gh = hist + ((size_t)r * H_q + kvh * G) * kHistBins;
-        for (int i = threadIdx.x; i < G * (kHistBins / 2); i += 256) {
-            const uint32_t v = (&lhist[0][0])[i];
-            if (v & 0xFFFFu) atomicAdd(&gh[2 * i], v & 0xFFFFu);
-            if (v >> 16) atomicAdd(&gh[2 * i + 1], v >> 16);
+            if (lane == g) // survivors of this page for head g
+                page_cnt[(size_t)dsc.page_start * H_q + (size_t)(kvh * G + g) * dsc.n_pages + p] = __popcll(m);
         }
     }
 }
 
 template <int DT, int D>
 static hipError_t launch_score_g(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles,
-                                 int ppw, int want_hist, hipStream_t st)
+                                 int ppw, int phase, hipStream_t st)
 {
     const int G = sh.n_q_heads / sh.n_kv_heads;
     const dim3 grid((unsigned)(total_tiles * sh.n_kv_heads)), block(256);
-#define ALAYA_SCORE(GG)                                                                                       \
-    score_kernel<DT, D, GG><<<grid, block, 0, st>>>(dv.desc, B, dv.page_table, (const uint32_t *)q,           \
-                                                    (const uint4 *)dv.k_pool, dv.scores, dv.tile_max, dv.hist, \
-                                                    sh.n_kv_heads, ppw, want_hist)
+#define ALAYA_SCORE(GG)                                                                                    \
+    score_kernel<DT, D, GG><<<grid, block, 0, st>>>(dv.desc, B, dv.page_table, (const uint32_t *)q,        \
+                                                    (const uint4 *)dv.k_pool, dv.cand_scores, dv.cand_ids, \
+                                                    dv.page_cnt, dv.tau, sh.n_kv_heads, ppw, phase)
     switch (G) {
     case 1: ALAYA_SCORE(1); break;
     case 2: ALAYA_SCORE(2); break;
@@ -224,16 +197,92 @@ static hipError_t launch_score_g(const Shape &sh, const DeviceViews &dv, int B, 
 }
 
 hipError_t launch_score(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles, int ppw,
-                        int want_hist, hipStream_t st)
+                        int phase, hipStream_t st)
 {
+    if (total_tiles <= 0) return hipSuccess;
     if (sh.dtype == 0) {
-        if (sh.head_dim == 128) return launch_score_g<0, 128>(sh, dv, B, q, total_tiles, ppw, want_hist, st);
-        if (sh.head_dim == 64) return launch_score_g<0, 64>(sh, dv, B, q, total_tiles, ppw, want_hist, st);
+        if (sh.head_dim == 128) return launch_score_g<0, 128>(sh, dv, B, q, total_tiles, ppw, phase, st);
+        if (sh.head_dim == 64) return launch_score_g<0, 64>(sh, dv, B, q, total_tiles, ppw, phase, st);
     } else {
-        if (sh.head_dim == 128) return launch_score_g<1, 128>(sh, dv, B, q, total_tiles, ppw, want_hist, st);
-        if (sh.head_dim == 64) return launch_score_g<1, 64>(sh, dv, B, q, total_tiles, ppw, want_hist, st);
+        if (sh.head_dim == 128) return launch_score_g<1, 128>(sh, dv, B, q, total_tiles, ppw, phase, st);
+        if (sh.head_dim == 64) return launch_score_g<1, 64>(sh, dv, B, q, total_tiles, ppw, phase, st);
     }
     return hipErrorInvalidValue;
+}
+
+// ------------------------------------------------------------------------------------------------
+// tau: the lower bound of each head's selection threshold, from the pages phase A scored in full
+// (every valid token of a sampled page was written, in order).  One 1024-thread workgroup per
+// (request, head); the loop over the sample is flat, so its loads are independent.
+__global__ __launch_bounds__(kSelectThreads) void tau_kernel(const ReqDesc *__restrict__ desc, int H_q, int mode,
+                                                              const float *__restrict__ cand_scores,
+                                                              uint32_t *__restrict__ tau)
+{
+    __shared__ uint32_t lh[kHistBins];
+    __shared__ float wred[kSelectThreads / 64];
+    __shared__ int32_t wtot[kSelectThreads / 64];
+    __shared__ int32_t found;
+
+    const int rh = blockIdx.x;
+    const int r = rh / H_q, h = rh % H_q;
+    const ReqDesc dsc = desc[r];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int S = dsc.sample_stride;
+    const int n_a = (dsc.n_pages + S - 1) / S;
+    const int total = n_a * kPageTokens;
+    const float *sc = cand_scores + (size_t)dsc.score_off + (size_t)h * kPageTokens;
+
+    if (mode == 1) { // DIPR: (maximum over the sample) - beta
+        float m = -INFINITY;
+        for (int t = tid; t < total; t += kSelectThreads) {
+            const int p = (t >> 6) * S, e = t & 63;
+            if (p * kPageTokens + e < dsc.n) m = fmaxf(m, sc[(size_t)p * H_q * kPageTokens + e]);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+        if (lane == 0) wred[wave] = m;
+        __syncthreads();
+        if (tid == 0) {
+            float M = wred[0];
+            for (int w = 1; w < kSelectThreads / 64; ++w) M = fmaxf(M, wred[w]);
+            tau[rh] = ord_key(M - dsc.beta);
+        }
+        return;
+    }
+    // top-k: bucket of the k-th largest score of the sample
+    for (int i = tid; i < kHistBins; i += kSelectThreads) lh[i] = 0u;
+    if (tid == 0) found = -1;
+    __syncthreads();
+    for (int t = tid; t < total; t += kSelectThreads) {
+        const int p = (t >> 6) * S, e = t & 63;
+        if (p * kPageTokens + e < dsc.n)
+            atomicAdd(&lh[ord_key(sc[(size_t)p * H_q * kPageTokens + e]) >> 21], 1u);
+    }
+    __syncthreads();
+    // walk down from the top bucket: two buckets per thread, thread 0 holding the top ones
+    const int b0 = kHistBins - 1 - 2 * tid;
+    const int c0 = (int)lh[b0], c1 = (int)lh[b0 - 1];
+    int inc = c0 + c1;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(inc, o);
+        if (lane >= o) inc += t;
+    }
+    if (lane == 63) wtot[wave] = inc;
+    __syncthreads();
+    int above = inc - (c0 + c1);
+    for (int w = 0; w < wave; ++w) above += wtot[w];
+    if (above < dsc.k && above + c0 + c1 >= dsc.k) found = above + c0 >= dsc.k ? b0 : b0 - 1;
+    __syncthreads();
+    // fewer than k scores in the sample: no bound
+    if (tid == 0) tau[rh] = found >= 0 ? (uint32_t)found << 21 : 0u;
+}
+
+hipError_t launch_tau(const Shape &sh, const DeviceViews &dv, int B, int mode, hipStream_t st)
+{
+    tau_kernel<<<dim3((unsigned)(B * sh.n_q_heads)), dim3(kSelectThreads), 0, st>>>(dv.desc, sh.n_q_heads, mode,
+                                                                                   dv.cand_scores, dv.tau);
+    return hipGetLastError();
 }
 
 __global__ void fill_u32_kernel(uint32_t *p, size_t n, uint32_t v)

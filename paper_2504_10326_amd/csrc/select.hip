@@ -1,28 +1,36 @@
-// Selection of the critical tokens of every (request, query head) from its fp32 scores.
+// Selection of the critical tokens of every (request, query head) from the survivors the scoring
+// pass wrote (every token that can possibly be selected is among them; each page's list is ascending).
 //   top-k (Sec. 5.1.1): the k largest scores; equal scores at the k-th place go to the smaller id.
 //   DIPR  (Def. 2, 3) : every token with score >= max - beta.
 // Everything is exact and order-deterministic: counting is integer (radix select on the
 // order-preserving image of the score) and placement is an ordered compaction, so the selected list
 // is the same on every run.
 //
-// A head's n scores are cut into segments; one 1024-thread workgroup owns one segment.
-//   count   per segment: how many tokens are "definite" (top-k: bucket above the bucket b of the k-th
-//           score, which is read off the histogram the scoring pass left; DIPR: score >= max - beta)
-//           and how many are "candidates" (top-k only: bucket == b)
-//   place   per segment: prefix over the earlier segments' counts gives the write offsets; an ordered
-//           compaction puts definite tokens at the front of the head's list and candidates behind them,
-//           both in ascending token order
-//   finish  per head: (top-k) radix-refine the remaining 21 key bits over the candidates only and
-//           compact them in place - keep key > T and the first `ties` tokens with key == T; publish
-//           the count, copy ids out if asked, and zero the head's histogram for the next call
+// A head's pages are cut into segments; one 1024-thread workgroup owns one (head, segment).  The
+// survivors of a segment are addressed through a FLAT index: the pages' survivor counts are scanned
+// in LDS, and element t of the concatenation is found by a binary search over the prefix sums.  All
+// loads of a pass are therefore independent, and the flat order is ascending token order.
+//   stats   the head's maximum score (the arg-max always survives) and, for top-k, the bucket counts
+//           of the survivors (top 11 bits of the ordered key): LDS first, then at most kMaxSegs
+//           workgroups per head add to the same global counters
+//   local   classify each survivor: "definite" (top-k: its bucket lies above the bucket b of the k-th
+//           score, read off the histogram; DIPR: score >= max - beta), "candidate" (top-k only:
+//           bucket == b) or neither, and compact the segment into its own region: definite tokens
+//           first, candidates behind them, both in ascending token order
+//   finish  per head: gather the segments' definite lists into the head's final list (a binary search
+//           over the segment prefix sums finds each element's source), gather the candidates behind
+//           them, radix-refine the remaining 21 key bits over the candidates and compact them in
+//           place - keep key > T and the first `ties` tokens with key == T; publish the count, copy
+//           ids out if asked, and reset the head's histogram and maximum for the next call
 #include "alaya_internal.h"
 
 namespace alaya {
 
-constexpr int kSelE = 4;                       // scores per thread per chunk
+constexpr int kSelE = 4;                       // elements per thread per chunk
 constexpr int kSelWaves = kSelectThreads / 64; // 16
+constexpr int kSelChunk = kSelE * kSelectThreads;
 static_assert(kSelE * kSelWaves == 64, "the cross-wave scan maps one (e, wave) pair to one lane of wave 0");
-static_assert(kSelE * kSelectThreads == kSelChunkTokens, "chunk size");
+static_assert(kMaxSegPages == 2 * kSelectThreads, "the page-count scan takes two pages per thread");
 
 struct ScanShared {
     int32_t cnt[2][2][64]; // [parity][list][e * 16 + wave]
@@ -71,30 +79,34 @@ __device__ __forceinline__ void chunk_ranks(ScanShared &sh, int parity, const bo
     totB = sh.tot[parity][1];
 }
 
-// Walk a histogram from its top bin down (one wavefront): find the bin holding the `need`-th largest
-// element.  res[0] = bin, res[1] = elements in bins above it.
-__device__ __forceinline__ void find_bin(const uint32_t *hist, int nbins, int need, int32_t *res)
+// Find the bin that holds the `need`-th largest element of a histogram, walking from the top bin
+// down: res[0] = bin, res[1] = elements in bins above it.  All 1024 threads take part (nbins is 1024
+// or 2048: one or two bins per thread, thread 0 holding the top ones).  Two barriers.  If the
+// histogram holds fewer than `need` elements nothing is written.
+__device__ __forceinline__ void block_find_bin(const uint32_t *hist, int nbins, int need, int32_t *wtot,
+                                               int32_t *res)
 {
-    const int lane = threadIdx.x & 63;
-    int above = 0;
-    for (int top = nbins - 64; top >= 0; top -= 64) {
-        const int bin = top + 63 - lane; // lane 0 takes the highest bin of this group
-        const int c = (int)hist[bin];
-        int inc = c;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int per = nbins / kSelectThreads;
+    const int b0 = nbins - 1 - per * tid;
+    const int c0 = (int)hist[b0];
+    const int c1 = per == 2 ? (int)hist[b0 - 1] : 0;
+    const int local = c0 + c1;
+    int inc = local;
 #pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int t = __shfl_up(inc, o);
-            if (lane >= o) inc += t;
-        }
-        const unsigned long long hit = __ballot(above + inc >= need);
-        if (hit) {
-            const int first = __ffsll((long long)hit) - 1;
-            if (lane == first) { res[0] = bin; res[1] = above + inc - c; }
-            return;
-        }
-        above += __shfl(inc, 63);
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(inc, o);
+        if (lane >= o) inc += t;
     }
-    if (lane == 0) { res[0] = 0; res[1] = above - (int)hist[0]; } // unreachable when need <= total
+    if (lane == 63) wtot[wave] = inc;
+    __syncthreads();
+    int above = inc - local;
+    for (int w = 0; w < wave; ++w) above += wtot[w];
+    if (above < need && above + local >= need) {
+        if (above + c0 >= need) { res[0] = b0; res[1] = above; }
+        else { res[0] = b0 - 1; res[1] = above + c0; }
+    }
+    __syncthreads();
 }
 
 // blockIdx -> (request, head, segment).  Heads are the fastest index.
@@ -108,7 +120,57 @@ __device__ __forceinline__ SegId seg_of_block(const ReqDesc *desc, int B, int H_
     return {r, h, gs - desc[r].seg_start};
 }
 
-// What a token's score means for the selection, given the head's threshold data.
+// The survivors of the pages [p_begin, p_end) of one head, addressed by a flat index.
+struct SegView {
+    int p_begin, np, total; // first page, pages, survivors
+    size_t base;            // element offset of (page 0, this head) in the survivor arrays
+    size_t page_stride;     // elements between consecutive pages of this head (H_q * 64)
+};
+
+// Loads the pages' survivor counts and leaves their exclusive prefix sums in off[0 .. np]
+// (off[np] = total).  Two pages per thread; two barriers.
+__device__ __forceinline__ SegView load_segment(const ReqDesc &dsc, int H_q, int h, int seg,
+                                                const int32_t *__restrict__ page_cnt, int32_t *off, int32_t *wtot)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    SegView v;
+    v.p_begin = seg * dsc.seg_pages;
+    v.np = min(dsc.n_pages, v.p_begin + dsc.seg_pages) - v.p_begin;
+    v.base = (size_t)dsc.score_off + (size_t)h * kPageTokens;
+    v.page_stride = (size_t)H_q * kPageTokens;
+    const int32_t *cnt = page_cnt + (size_t)dsc.page_start * H_q + (size_t)h * dsc.n_pages + v.p_begin;
+    const int i0 = 2 * tid, i1 = 2 * tid + 1;
+    const int a0 = i0 < v.np ? cnt[i0] : 0, a1 = i1 < v.np ? cnt[i1] : 0;
+    int inc = a0 + a1;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(inc, o);
+        if (lane >= o) inc += t;
+    }
+    if (lane == 63) wtot[wave] = inc;
+    __syncthreads();
+    int pre = inc - (a0 + a1);
+    for (int w = 0; w < wave; ++w) pre += wtot[w];
+    if (i0 <= v.np) off[i0] = pre;
+    if (i1 <= v.np) off[i1] = pre + a0;
+    if (tid == kSelectThreads - 1 && v.np == kMaxSegPages) off[v.np] = pre + a0 + a1;
+    __syncthreads();
+    v.total = off[v.np];
+    return v;
+}
+
+// Flat index t -> element offset in the survivor arrays.
+__device__ __forceinline__ size_t flat_to_offset(const SegView &v, const int32_t *off, int t)
+{
+    int lo = 0, hi = v.np; // page index in [lo, hi): the last page whose prefix is <= t
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (off[mid] <= t) lo = mid; else hi = mid;
+    }
+    return v.base + (size_t)(v.p_begin + lo) * v.page_stride + (size_t)(t - off[lo]);
+}
+
+// What a survivor's score means for the selection, given the head's threshold data.
 struct Rule {
     int topk;     // 1: bucket rule, 0: threshold rule
     uint32_t b1;  // bucket of the k-th score
@@ -127,39 +189,69 @@ struct Rule {
 };
 
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kSelectThreads) void select_count_kernel(
-    const ReqDesc *__restrict__ desc, int B, int H_q, int mode, const float *__restrict__ scores,
-    const float *__restrict__ tile_max, const uint32_t *__restrict__ hist, float *__restrict__ head_M,
-    int32_t *__restrict__ head_info, int32_t *__restrict__ seg_counts)
+__global__ __launch_bounds__(kSelectThreads) void select_stats_kernel(
+    const ReqDesc *__restrict__ desc, int B, int H_q, int mode, const float *__restrict__ cand_scores,
+    const int32_t *__restrict__ page_cnt, uint32_t *__restrict__ hist, uint32_t *__restrict__ head_maxkey)
 {
     __shared__ uint32_t lh[kHistBins];
+    __shared__ int32_t off[kMaxSegPages + 1];
+    __shared__ int32_t wtot[kSelWaves];
     __shared__ float wred[kSelWaves];
-    __shared__ int32_t ired[2][kSelWaves];
+
+    const SegId id = seg_of_block(desc, B, H_q);
+    const ReqDesc dsc = desc[id.r];
+    const int rh = id.r * H_q + id.h;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bool want_hist = mode == 0 && dsc.k < dsc.n;
+    if (want_hist)
+        for (int i = tid; i < kHistBins; i += kSelectThreads) lh[i] = 0u;
+    const SegView v = load_segment(dsc, H_q, id.h, id.seg, page_cnt, off, wtot); // barriers inside
+    float m = -INFINITY;
+    for (int t = tid; t < v.total; t += kSelectThreads) {
+        const float s = cand_scores[flat_to_offset(v, off, t)];
+        m = fmaxf(m, s);
+        if (want_hist) atomicAdd(&lh[ord_key(s) >> 21], 1u);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if (lane == 0) wred[wave] = m;
+    __syncthreads();
+    if (tid == 0) {
+        float M = wred[0];
+        for (int w = 1; w < kSelWaves; ++w) M = fmaxf(M, wred[w]);
+        if (M > -INFINITY) atomicMax(&head_maxkey[rh], ord_key(M));
+    }
+    if (want_hist)
+        for (int i = tid; i < kHistBins; i += kSelectThreads)
+            if (lh[i]) atomicAdd(&hist[(size_t)rh * kHistBins + i], lh[i]);
+}
+
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kSelectThreads) void select_local_kernel(
+    const ReqDesc *__restrict__ desc, int B, int H_q, int mode, const float *__restrict__ cand_scores,
+    const int32_t *__restrict__ cand_ids, const int32_t *__restrict__ page_cnt,
+    const uint32_t *__restrict__ hist, const uint32_t *__restrict__ head_maxkey, float *__restrict__ head_M,
+    int32_t *__restrict__ head_info, int32_t *__restrict__ seg_counts, float *__restrict__ loc_scores,
+    int32_t *__restrict__ loc_ids)
+{
+    __shared__ uint32_t lh[kHistBins];
+    __shared__ int32_t off[kMaxSegPages + 1];
+    __shared__ ScanShared scan;
+    __shared__ int32_t wtot[kSelWaves];
     __shared__ int32_t res[2];
 
     const SegId id = seg_of_block(desc, B, H_q);
     const ReqDesc dsc = desc[id.r];
     const int rh = id.r * H_q + id.h;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n = dsc.n;
 
-    // the head's maximum score, from the scoring pass's per-tile maxima
-    float m = -INFINITY;
-    for (int t = tid; t < dsc.n_tiles; t += kSelectThreads)
-        m = fmaxf(m, tile_max[(size_t)(dsc.tile_start + t) * H_q + id.h]);
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-    if (lane == 0) wred[wave] = m;
-    const bool bucket_rule = mode == 0 && dsc.k < n;
-    if (bucket_rule)
+    const float M = ord_float(head_maxkey[rh]);
+    const bool bucket_rule = mode == 0 && dsc.k < dsc.n;
+    if (bucket_rule) {
         for (int i = tid; i < kHistBins; i += kSelectThreads) lh[i] = hist[(size_t)rh * kHistBins + i];
-    __syncthreads();
-    float M = wred[0];
-#pragma unroll
-    for (int w = 1; w < kSelWaves; ++w) M = fmaxf(M, wred[w]);
-    if (bucket_rule && tid < 64) find_bin(lh, kHistBins, dsc.k, res);
-    __syncthreads();
-
+        __syncthreads();
+        block_find_bin(lh, kHistBins, dsc.k, wtot, res);
+    }
     Rule rule;
     rule.topk = bucket_rule;
     rule.b1 = bucket_rule ? (uint32_t)res[0] : 0u;
@@ -169,115 +261,75 @@ __global__ __launch_bounds__(kSelectThreads) void select_count_kernel(
         head_info[2 * rh] = bucket_rule ? res[0] : -1;
         head_info[2 * rh + 1] = bucket_rule ? res[1] : 0;
     }
+    __syncthreads(); // wtot is reused below
 
-    const float *s = scores + (size_t)dsc.score_off + (size_t)id.h * dsc.head_stride;
-    const int begin = id.seg * dsc.seg_len, end = min(n, begin + dsc.seg_len);
-    int ca = 0, cc = 0;
-    for (int c0 = begin; c0 < end; c0 += kSelChunkTokens) {
+    const SegView v = load_segment(dsc, H_q, id.h, id.seg, page_cnt, off, wtot);
+
+    // 1. how many definite tokens the segment holds (its candidates go behind them)
+    int ca = 0;
+    if (bucket_rule) {
+        for (int t = tid; t < v.total; t += kSelectThreads) {
+            bool fa, fc;
+            rule.classify(cand_scores[flat_to_offset(v, off, t)], true, fa, fc);
+            ca += fa;
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) ca += __shfl_xor(ca, o);
+        __syncthreads();
+        if (lane == 0) wtot[wave] = ca;
+        __syncthreads();
+        ca = 0;
+        for (int w = 0; w < kSelWaves; ++w) ca += wtot[w];
+    }
+
+    // 2. ordered placement into the segment's region, chunk by chunk in flat (= token) order
+    const size_t loc = (size_t)dsc.score_off + (size_t)id.h * dsc.head_stride +
+                       (size_t)id.seg * dsc.seg_pages * kPageTokens;
+    int baseA = 0, baseC = ca, parity = 0;
+    for (int c0 = 0; c0 < v.total; c0 += kSelChunk) {
+        float sv[kSelE];
+        int tok[kSelE];
+        bool fa[kSelE], fc[kSelE];
 #pragma unroll
         for (int e = 0; e < kSelE; ++e) {
-            const int j = c0 + e * kSelectThreads + tid;
-            const bool in = j < end;
-            const float v = in ? s[j] : 0.f;
-            bool a, c;
-            rule.classify(v, in, a, c);
-            ca += a;
-            cc += c;
+            const int t = c0 + e * kSelectThreads + tid;
+            const bool in = t < v.total;
+            const size_t o = in ? flat_to_offset(v, off, t) : v.base;
+            sv[e] = in ? cand_scores[o] : 0.f;
+            tok[e] = in ? cand_ids[o] : 0;
+            rule.classify(sv[e], in, fa[e], fc[e]);
         }
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        ca += __shfl_xor(ca, o);
-        cc += __shfl_xor(cc, o);
-    }
-    if (lane == 0) { ired[0][wave] = ca; ired[1][wave] = cc; }
-    __syncthreads();
-    if (tid < 2) {
-        int t = 0;
-#pragma unroll
-        for (int w = 0; w < kSelWaves; ++w) t += ired[tid][w];
-        seg_counts[((size_t)rh * kMaxSegs + id.seg) * 2 + tid] = t;
-    }
-}
-
-// ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kSelectThreads) void select_place_kernel(
-    const ReqDesc *__restrict__ desc, int B, int H_q, int mode, const float *__restrict__ scores,
-    const float *__restrict__ head_M, const int32_t *__restrict__ head_info,
-    const int32_t *__restrict__ seg_counts, int32_t *__restrict__ sel_ids, float *__restrict__ sel_scores)
-{
-    __shared__ ScanShared scan;
-    __shared__ int32_t base[2];
-
-    const SegId id = seg_of_block(desc, B, H_q);
-    const ReqDesc dsc = desc[id.r];
-    const int rh = id.r * H_q + id.h;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int n = dsc.n;
-
-    Rule rule;
-    rule.topk = head_info[2 * rh] >= 0;
-    rule.b1 = (uint32_t)head_info[2 * rh];
-    rule.thr = mode == 1 ? head_M[rh] - dsc.beta : -INFINITY;
-    const int above1 = head_info[2 * rh + 1];
-
-    if (tid < 64) { // earlier segments of this head: at most kMaxSegs = 64 of them
-        int a = 0, c = 0;
-        if (lane < id.seg) {
-            a = seg_counts[((size_t)rh * kMaxSegs + lane) * 2];
-            c = seg_counts[((size_t)rh * kMaxSegs + lane) * 2 + 1];
-        }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            a += __shfl_xor(a, o);
-            c += __shfl_xor(c, o);
-        }
-        if (lane == 0) { base[0] = a; base[1] = above1 + c; }
-    }
-    __syncthreads();
-    int baseA = base[0], baseC = base[1];
-
-    const size_t off = (size_t)dsc.score_off + (size_t)id.h * dsc.head_stride;
-    const float *s = scores + off;
-    int32_t *ids = sel_ids + off;
-    float *ss = sel_scores + off;
-    const int begin = id.seg * dsc.seg_len, end = min(n, begin + dsc.seg_len);
-    int parity = 0;
-    for (int c0 = begin; c0 < end; c0 += kSelChunkTokens) {
-        float v[kSelE];
-        bool fa[kSelE], fb[kSelE];
-#pragma unroll
-        for (int e = 0; e < kSelE; ++e) {
-            const int j = c0 + e * kSelectThreads + tid;
-            const bool in = j < end;
-            v[e] = in ? s[j] : 0.f;
-            rule.classify(v[e], in, fa[e], fb[e]);
-        }
-        int exA[kSelE], exB[kSelE], totA, totB;
-        chunk_ranks(scan, parity, fa, fb, exA, exB, totA, totB);
+        int exA[kSelE], exC[kSelE], totA, totC;
+        chunk_ranks(scan, parity, fa, fc, exA, exC, totA, totC);
         parity ^= 1;
 #pragma unroll
         for (int e = 0; e < kSelE; ++e) {
-            const int j = c0 + e * kSelectThreads + tid;
-            if (fa[e]) { ids[baseA + exA[e]] = j; ss[baseA + exA[e]] = v[e]; }
-            if (fb[e]) { ids[baseC + exB[e]] = j; ss[baseC + exB[e]] = v[e]; }
+            if (fa[e]) { loc_scores[loc + baseA + exA[e]] = sv[e]; loc_ids[loc + baseA + exA[e]] = tok[e]; }
+            if (fc[e]) { loc_scores[loc + baseC + exC[e]] = sv[e]; loc_ids[loc + baseC + exC[e]] = tok[e]; }
         }
         baseA += totA;
-        baseC += totB;
+        baseC += totC;
+    }
+    if (tid == 0) {
+        seg_counts[((size_t)rh * kMaxSegs + id.seg) * 2] = baseA;
+        seg_counts[((size_t)rh * kMaxSegs + id.seg) * 2 + 1] = baseC - ca;
     }
 }
 
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
     const ReqDesc *__restrict__ desc, int H_q, int mode, const int32_t *__restrict__ head_info,
-    const int32_t *__restrict__ seg_counts, uint32_t *__restrict__ hist, int32_t *__restrict__ sel_ids,
-    float *__restrict__ sel_scores, int32_t *__restrict__ counts, int32_t *__restrict__ out_ids,
-    int32_t *__restrict__ out_counts, int64_t ids_stride, int32_t *__restrict__ status)
+    const int32_t *__restrict__ seg_counts, const float *__restrict__ loc_scores,
+    const int32_t *__restrict__ loc_ids, uint32_t *__restrict__ hist, uint32_t *__restrict__ head_maxkey,
+    int32_t *__restrict__ sel_ids, float *__restrict__ sel_scores, int32_t *__restrict__ counts,
+    int32_t *__restrict__ out_ids, int32_t *__restrict__ out_counts, int64_t ids_stride,
+    int32_t *__restrict__ status)
 {
     __shared__ uint32_t lh[kHistBins];
     __shared__ ScanShared scan;
+    __shared__ int32_t preA[kMaxSegs + 1], preC[kMaxSegs + 1], cntA[kMaxSegs];
+    __shared__ int32_t wtot[kSelWaves];
     __shared__ int32_t res[2];
-    __shared__ int32_t tot[2];
 
     const int rh = blockIdx.x;
     const int r = rh / H_q, h = rh % H_q;
@@ -286,28 +338,60 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
     const size_t off = (size_t)dsc.score_off + (size_t)h * dsc.head_stride;
     int32_t *ids = sel_ids + off;
     float *ss = sel_scores + off;
+    const float *ls = loc_scores + off;
+    const int32_t *li = loc_ids + off;
+    const size_t seg_region = (size_t)dsc.seg_pages * kPageTokens;
+    const int nseg = dsc.nseg;
 
     if (tid < 64) {
         int a = 0, c = 0;
-        if (lane < dsc.nseg) {
+        if (lane < nseg) {
             a = seg_counts[((size_t)rh * kMaxSegs + lane) * 2];
             c = seg_counts[((size_t)rh * kMaxSegs + lane) * 2 + 1];
         }
+        int ia = a, ic = c;
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            a += __shfl_xor(a, o);
-            c += __shfl_xor(c, o);
+        for (int o = 1; o < 64; o <<= 1) {
+            const int ta = __shfl_up(ia, o), tc = __shfl_up(ic, o);
+            if (lane >= o) { ia += ta; ic += tc; }
         }
-        if (lane == 0) { tot[0] = a; tot[1] = c; }
+        preA[lane] = ia - a; // exclusive
+        preC[lane] = ic - c;
+        cntA[lane] = a;
+        if (lane == 63) { preA[64] = ia; preC[64] = ic; }
     }
     __syncthreads();
+    const int totA = preA[64], totC = preC[64];
+
+    // gather: element e of the concatenation lives in the last segment whose prefix is <= e
+    auto find_seg = [&](const int32_t *pre, int e) {
+        int lo = 0, hi = nseg; // answer in [lo, hi)
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (pre[mid] <= e) lo = mid; else hi = mid;
+        }
+        return lo;
+    };
+    for (int e = tid; e < totA; e += kSelectThreads) {
+        const int s = find_seg(preA, e);
+        const size_t src = (size_t)s * seg_region + (size_t)(e - preA[s]);
+        ids[e] = li[src];
+        ss[e] = ls[src];
+    }
     const bool bucket_rule = head_info[2 * rh] >= 0;
-    int count = tot[0];
+    int count = totA;
 
     if (bucket_rule) {
+        for (int e = tid; e < totC; e += kSelectThreads) {
+            const int s = find_seg(preC, e);
+            const size_t src = (size_t)s * seg_region + (size_t)cntA[s] + (size_t)(e - preC[s]);
+            ids[totA + e] = li[src];
+            ss[totA + e] = ls[src];
+        }
+        __syncthreads(); // candidates visible to the whole workgroup
         const uint32_t b1 = (uint32_t)head_info[2 * rh];
-        const int above1 = head_info[2 * rh + 1]; // == tot[0]
-        const int cb = tot[1];
+        const int above1 = totA; // == head_info[2 * rh + 1]: every token above bucket b1
+        const int cb = totC;
         int need = dsc.k - above1; // 1 <= need <= cb
         int parity = 0;
         if (need < cb) {
@@ -317,8 +401,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
             __syncthreads();
             for (int i = tid; i < cb; i += kSelectThreads) atomicAdd(&lh[(ord_key(cs[i]) >> 10) & 0x7FFu], 1u);
             __syncthreads();
-            if (tid < 64) find_bin(lh, 2048, need, res);
-            __syncthreads();
+            block_find_bin(lh, 2048, need, wtot, res);
             const uint32_t b2 = (uint32_t)res[0];
             need -= res[1];
             __syncthreads();
@@ -330,13 +413,12 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
                 if ((key >> 10) == pre) atomicAdd(&lh[key & 0x3FFu], 1u);
             }
             __syncthreads();
-            if (tid < 64) find_bin(lh, 1024, need, res);
-            __syncthreads();
+            block_find_bin(lh, 1024, need, wtot, res);
             const uint32_t T = (pre << 10) | (uint32_t)res[0];
             const int ties = need - res[1]; // tokens with key == T that are taken, smallest ids first
             // ordered in-place compaction of the candidates (writes never pass the chunk being read)
             int baseG = 0, baseT = 0;
-            for (int c0 = 0; c0 < cb; c0 += kSelChunkTokens) {
+            for (int c0 = 0; c0 < cb; c0 += kSelChunk) {
                 float v[kSelE];
                 int idv[kSelE];
                 bool fa[kSelE], fb[kSelE];
@@ -349,8 +431,8 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
                     fa[e] = i < cb && key > T;
                     fb[e] = i < cb && key == T;
                 }
-                int exA[kSelE], exB[kSelE], totA, totB;
-                chunk_ranks(scan, parity, fa, fb, exA, exB, totA, totB); // barriers: this chunk is fully read
+                int exA[kSelE], exB[kSelE], tA, tB;
+                chunk_ranks(scan, parity, fa, fb, exA, exB, tA, tB); // barriers: this chunk is fully read
                 parity ^= 1;
 #pragma unroll
                 for (int e = 0; e < kSelE; ++e) {
@@ -361,8 +443,8 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
                         ss[pos] = v[e];
                     }
                 }
-                baseG += totA;
-                baseT += totB;
+                baseG += tA;
+                baseT += tB;
             }
         }
         count = dsc.k;
@@ -373,13 +455,14 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
         counts[rh] = count;
         if (out_counts) out_counts[rh] = count;
         if (out_ids && (int64_t)count > ids_stride) atomicOr(status, 1);
+        head_maxkey[rh] = 0u; // leave the running maximum and the histogram clean for the next call
     }
     if (out_ids) {
         const int m = (int)((int64_t)count < ids_stride ? (int64_t)count : ids_stride);
         int32_t *dst = out_ids + (size_t)rh * (size_t)ids_stride;
         for (int i = tid; i < m; i += kSelectThreads) dst[i] = ids[i];
     }
-    if (mode == 0) // the scoring pass of a top-k call filled this head's histogram: leave it clean
+    if (mode == 0)
         for (int i = tid; i < kHistBins; i += kSelectThreads) hist[(size_t)rh * kHistBins + i] = 0u;
 }
 
@@ -388,17 +471,18 @@ hipError_t launch_select(const Shape &sh, const DeviceViews &dv, int B, int mode
 {
     const dim3 block(kSelectThreads);
     const dim3 seg_grid((unsigned)(total_segs * sh.n_q_heads));
-    select_count_kernel<<<seg_grid, block, 0, st>>>(dv.desc, B, sh.n_q_heads, mode, dv.scores, dv.tile_max, dv.hist,
-                                                    dv.head_M, dv.head_info, dv.seg_counts);
+    select_stats_kernel<<<seg_grid, block, 0, st>>>(dv.desc, B, sh.n_q_heads, mode, dv.cand_scores, dv.page_cnt,
+                                                    dv.hist, dv.head_maxkey);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    select_place_kernel<<<seg_grid, block, 0, st>>>(dv.desc, B, sh.n_q_heads, mode, dv.scores, dv.head_M,
-                                                    dv.head_info, dv.seg_counts, dv.sel_ids, dv.sel_scores);
+    select_local_kernel<<<seg_grid, block, 0, st>>>(dv.desc, B, sh.n_q_heads, mode, dv.cand_scores, dv.cand_ids,
+                                                    dv.page_cnt, dv.hist, dv.head_maxkey, dv.head_M, dv.head_info,
+                                                    dv.seg_counts, dv.loc_scores, dv.loc_ids);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     select_finish_kernel<<<dim3((unsigned)(B * sh.n_q_heads)), block, 0, st>>>(
-        dv.desc, sh.n_q_heads, mode, dv.head_info, dv.seg_counts, dv.hist, dv.sel_ids, dv.sel_scores, dv.counts,
-        out_ids, out_counts, ids_stride, dv.status);
+        dv.desc, sh.n_q_heads, mode, dv.head_info, dv.seg_counts, dv.loc_scores, dv.loc_ids, dv.hist,
+        dv.head_maxkey, dv.sel_ids, dv.sel_scores, dv.counts, out_ids, out_counts, ids_stride, dv.status);
     return hipGetLastError();
 }
 

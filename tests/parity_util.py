@@ -110,6 +110,17 @@ def run_and_compare(c: A.Cache, w, g, mode, topk=None, beta=None, scale=None, id
         ids_stride = max(w.lens) if mode == A.ALAYA_DIPR else max(min(k, n) for k, n in zip(topk, w.lens))
     out, ids, counts = c.sparse_attn(seqs, q, mode, topk=topk, beta=beta, scale=scale or 0.0, ids_stride=ids_stride)
     torch.cuda.synchronize()
-    sg = c.debug_scores(w.lens) if check_scores else None
     assert c.poll_status() == A.ALAYA_OK
+    sg = None
+    if check_scores:
+        # The same call with every score written: the scores themselves can then be compared, and the
+        # pruned run above must have produced bit-identical ids, counts and outputs.
+        c.set_write_all_scores(True)
+        out2, ids2, counts2 = c.sparse_attn(seqs, q, mode, topk=topk, beta=beta, scale=scale or 0.0,
+                                            ids_stride=ids_stride)
+        torch.cuda.synchronize()
+        sg = [s.clone() for s in c.debug_scores(w.lens)]
+        c.set_write_all_scores(False)
+        assert torch.equal(counts, counts2) and torch.equal(ids, ids2), "pruned and unpruned selections differ"
+        assert torch.equal(out, out2), "pruned and unpruned outputs differ"
     return compare_sparse(w, g, out, ids, counts, mode, topk, beta, scale, scores_gpu=sg, threads=threads)

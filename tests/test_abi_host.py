@@ -133,5 +133,5 @@ def test_null_handle():
     L = A.lib()
     assert L.alaya_destroy_cache(None) == A.ALAYA_E_INVAL
     assert L.alaya_seq_len(None, 0) == -1
-    assert L.alaya_set_tuning(None, 1, 1, 1) == A.ALAYA_E_INVAL
+    assert L.alaya_set_tuning(None, 1, 1, 1, 0) == A.ALAYA_E_INVAL
     assert "null" in A.alaya_last_error()

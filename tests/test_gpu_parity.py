@@ -283,9 +283,11 @@ def test_custom_scale_and_profiling_hooks():
     c = make_cache(w, g)
     run_and_compare(c, w, g, A.ALAYA_TOPK, topk=w.topk, scale=0.25)
     c.set_profiling(True)
-    for ppw, splits, seg in [(1, 1, 1), (3, 7, 5000), (16, 64, 10 ** 6)]:
+    for ppw, splits, seg in [(1, 1, 1), (3, 7, 5), (16, 64, 2048)]:
         c.set_tuning(ppw, splits, seg)
         run_and_compare(c, w, g, A.ALAYA_TOPK, topk=w.topk)
     t = c.kernel_times()
-    assert t["score"]["launches"] == 3 and t["score"]["sum_ms"] > 0 and t["combine"]["launches"] == 3
+    # every run_and_compare makes two calls: one pruned, one with all scores written
+    assert t["sample"]["launches"] == 6 and t["sample"]["sum_ms"] > 0 and t["combine"]["launches"] == 6
+    assert 0 < t["score"]["launches"] <= 6        # the main scoring pass runs only when there is something to prune
     c.close()
