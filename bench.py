@@ -9,10 +9,12 @@ gather the selected value rows, softmax-weighted sum, merge.  Inputs are residen
 timed region.  Prints ONE JSON line:
 
   value       keys scored per second over the whole step  (a key-score = one (query head, token) pair)
-  roofline    the scoring kernel against the 8 TB/s HBM peak: algorithmic bytes per launch
-              (read each K row once, 256 B; write its G fp32 scores, 4 B each) over the kernel's
-              average duration, taken with HIP events on the launch stream in a profiled repeat of
-              the timed loop (events between kernels would lengthen the timed steps themselves)
+  roofline    the main scoring kernel against the 8 TB/s HBM peak.  Algorithmic bytes per launch =
+              256 B (one bf16 K row, read once) x the K rows that launch scores (the pages that the
+              sample pass did not take, x 64 tokens x KV heads); the few survivors it writes are not
+              counted.  Duration = the kernel's average over a profiled repeat of the timed loop,
+              taken with HIP events on the launch stream (events between kernels would lengthen the
+              timed steps themselves).
   cpu_baseline  the CPU oracle on the same step, on this host's cores (a reported baseline only)
 """
 from __future__ import annotations
@@ -119,13 +121,14 @@ def main() -> int:
 
     # Profiled repeat of the same loop: per-kernel durations from HIP events on the launch stream.
     c.set_profiling(True)
-    _, _, rows_p = run(K_steps)
+    run(K_steps)
     kt = c.kernel_times()
     c.set_profiling(False)
+    pages_sampled, pages_main = c.debug_pages()              # of the last step (the context grows by one token a step)
+    survivors = c.debug_survivors()
     score_ms = kt["score"]["sum_ms"] / max(1, kt["score"]["launches"])
-    G = w.n_q_heads // w.n_kv_heads
-    bytes_per_row = w.head_dim * 2 + 4 * G                    # read the K row once, write G fp32 scores
-    bytes_per_launch = rows_p / K_steps * bytes_per_row
+    bytes_per_row = w.head_dim * 2                            # one bf16 K row, read once
+    bytes_per_launch = pages_main * 64 * w.n_kv_heads * bytes_per_row
     achieved = bytes_per_launch / (score_ms * 1e-3) / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "paper_2504_10326_amd", "measured_traffic.json")
@@ -177,8 +180,10 @@ def main() -> int:
         "k_rows_per_s": rows / secs,
         "kernels_us": kernels_us,
         "full_attn_ms": full_ms,
-        "roofline": {"bound": "hbm", "kernel": "score_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+        "survivor_fraction": survivors / (w.n_q_heads * total_n),
+        "pages": {"sampled": pages_sampled, "main_pass": pages_main},
+        "roofline": {"bound": "hbm", "kernel": "score_kernel (main pass)", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "bytes_per_launch": bytes_per_launch, "avg_us": score_ms * 1e3},
         "cpu_baseline": cpu,
     }

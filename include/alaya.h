@@ -181,6 +181,11 @@ const float *alaya_debug_scores(const alaya_cache *c);
  * (with write_all_scores = 0 it is the number of scores that survived the running bound); -1 on error. */
 int64_t alaya_debug_survivors(alaya_cache *c, void *stream);
 
+/* How the last alaya_sparse_attn call split its pages (one page = 64 tokens of one sequence, scored
+ * for every KV head): *sampled pages were scored in full to bound the threshold, *main_pass pages
+ * were scored against that bound by the main scoring kernel.  HOST pointers. */
+int alaya_debug_pages(const alaya_cache *c, int64_t *sampled, int64_t *main_pass);
+
 /* Thread-local description of the last error returned on this thread ("" if none). */
 const char *alaya_last_error(void);
 

@@ -120,6 +120,7 @@ struct alaya_cache {
     int tune_ppw, tune_splits, tune_seg, tune_noprune;
     int last_ppw; // pages per wavefront of the last sparse call (layout of the survivor lists)
     int last_pages, last_heads;
+    int64_t last_pages_a, last_pages_b; // pages of the last sparse call scored by the sample / the main pass
     // profiling
     bool prof;
     std::vector<hipEvent_t> ev;      // 2 * kProfPairs, created on demand
@@ -330,6 +331,7 @@ int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k
     c->tune_noprune = 0;
     c->last_ppw = 0;
     c->last_pages = c->last_heads = 0;
+    c->last_pages_a = c->last_pages_b = 0;
     c->prof = false;
     c->ev_n = 0;
     for (int i = 0; i < ALAYA_N_KERNEL_SLOTS; ++i) { c->sum_ms[i] = 0.0; c->launches[i] = 0; }
@@ -439,7 +441,7 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
     const int64_t seg_pages_want = c->tune_seg > 0 ? c->tune_seg : 256;
     int splits = c->tune_splits;
     if (splits <= 0) {
-        splits = 512 / (B * n_q_heads);
+        splits = 1024 / (B * n_q_heads);
         if (splits < 1) splits = 1;
         if (splits > 32) splits = 32;
     }
@@ -449,6 +451,7 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
     rc = ring_acquire(c, &hd, &slot);
     if (rc != ALAYA_OK) return rc;
     int tiles = 0, tiles_b = 0, segs = 0, all_pages = 0;
+    int64_t pages_a = 0;
     int64_t off = 0;
     for (int b = 0; b < B; ++b) {
         const int64_t n = c->seq_len[(size_t)seqs[b]];
@@ -490,11 +493,14 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
         tiles += (n_a + kScoreWaves - 1) / kScoreWaves;                                  // one page per wavefront
         tiles_b += (int)((pages - n_a + (int64_t)kScoreWaves * ppw - 1) / ((int64_t)kScoreWaves * ppw));
         all_pages += (int)pages;
+        pages_a += n_a;
         segs += d.nseg;
         off += (int64_t)n_q_heads * d.head_stride;
     }
     c->last_ppw = ppw;
     c->last_pages = all_pages;
+    c->last_pages_a = pages_a;
+    c->last_pages_b = all_pages - pages_a;
     c->last_heads = n_q_heads;
     if (off > c->L.score_elems) return fail(ALAYA_E_NOMEM, "score workspace too small");
     if (all_pages > c->L.max_pages) return fail(ALAYA_E_NOMEM, "page-count workspace too small");
@@ -628,6 +634,14 @@ const float *alaya_debug_scores(const alaya_cache *c)
 {
     if (!c) { fail(ALAYA_E_INVAL, "null cache handle"); return nullptr; }
     return c->dv.cand_scores;
+}
+
+int alaya_debug_pages(const alaya_cache *c, int64_t *sampled, int64_t *main_pass)
+{
+    if (!c || !sampled || !main_pass) return fail(ALAYA_E_INVAL, "bad arguments");
+    *sampled = c->last_pages_a;
+    *main_pass = c->last_pages_b;
+    return ALAYA_OK;
 }
 
 int64_t alaya_debug_survivors(alaya_cache *c, void *stream)

@@ -232,11 +232,27 @@ __global__ __launch_bounds__(kSelectThreads) void tau_kernel(const ReqDesc *__re
     const int total = n_a * kPageTokens;
     const float *sc = cand_scores + (size_t)dsc.score_off + (size_t)h * kPageTokens;
 
+    // eight independent loads per thread and step, so that their latencies overlap
+    constexpr int U = 8;
+    auto load8 = [&](int t0, float *v, bool *ok) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int t = t0 + u * kSelectThreads;
+            const int p = (t >> 6) * S, e = t & 63;
+            ok[u] = t < total && p * kPageTokens + e < dsc.n;
+            v[u] = ok[u] ? sc[(size_t)p * H_q * kPageTokens + e] : 0.f;
+        }
+    };
+
     if (mode == 1) { // DIPR: (maximum over the sample) - beta
         float m = -INFINITY;
-        for (int t = tid; t < total; t += kSelectThreads) {
-            const int p = (t >> 6) * S, e = t & 63;
-            if (p * kPageTokens + e < dsc.n) m = fmaxf(m, sc[(size_t)p * H_q * kPageTokens + e]);
+        for (int t0 = tid; t0 < total; t0 += U * kSelectThreads) {
+            float v[U];
+            bool ok[U];
+            load8(t0, v, ok);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (ok[u]) m = fmaxf(m, v[u]);
         }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
@@ -253,10 +269,13 @@ __global__ __launch_bounds__(kSelectThreads) void tau_kernel(const ReqDesc *__re
     for (int i = tid; i < kHistBins; i += kSelectThreads) lh[i] = 0u;
     if (tid == 0) found = -1;
     __syncthreads();
-    for (int t = tid; t < total; t += kSelectThreads) {
-        const int p = (t >> 6) * S, e = t & 63;
-        if (p * kPageTokens + e < dsc.n)
-            atomicAdd(&lh[ord_key(sc[(size_t)p * H_q * kPageTokens + e]) >> 21], 1u);
+    for (int t0 = tid; t0 < total; t0 += U * kSelectThreads) {
+        float v[U];
+        bool ok[U];
+        load8(t0, v, ok);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (ok[u]) atomicAdd(&lh[ord_key(v[u]) >> 21], 1u);
     }
     __syncthreads();
     // walk down from the top bucket: two buckets per thread, thread 0 holding the top ones

@@ -207,10 +207,19 @@ __global__ __launch_bounds__(kSelectThreads) void select_stats_kernel(
         for (int i = tid; i < kHistBins; i += kSelectThreads) lh[i] = 0u;
     const SegView v = load_segment(dsc, H_q, id.h, id.seg, page_cnt, off, wtot); // barriers inside
     float m = -INFINITY;
-    for (int t = tid; t < v.total; t += kSelectThreads) {
-        const float s = cand_scores[flat_to_offset(v, off, t)];
-        m = fmaxf(m, s);
-        if (want_hist) atomicAdd(&lh[ord_key(s) >> 21], 1u);
+    constexpr int U = 4; // independent loads per thread and step
+    for (int t0 = tid; t0 < v.total; t0 += U * kSelectThreads) {
+        float s[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int t = t0 + u * kSelectThreads;
+            s[u] = t < v.total ? cand_scores[flat_to_offset(v, off, t)] : -INFINITY;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            m = fmaxf(m, s[u]);
+            if (want_hist && s[u] > -INFINITY) atomicAdd(&lh[ord_key(s[u]) >> 21], 1u);
+        }
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
@@ -265,27 +274,13 @@ __global__ __launch_bounds__(kSelectThreads) void select_local_kernel(
 
     const SegView v = load_segment(dsc, H_q, id.h, id.seg, page_cnt, off, wtot);
 
-    // 1. how many definite tokens the segment holds (its candidates go behind them)
-    int ca = 0;
-    if (bucket_rule) {
-        for (int t = tid; t < v.total; t += kSelectThreads) {
-            bool fa, fc;
-            rule.classify(cand_scores[flat_to_offset(v, off, t)], true, fa, fc);
-            ca += fa;
-        }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) ca += __shfl_xor(ca, o);
-        __syncthreads();
-        if (lane == 0) wtot[wave] = ca;
-        __syncthreads();
-        ca = 0;
-        for (int w = 0; w < kSelWaves; ++w) ca += wtot[w];
-    }
-
-    // 2. ordered placement into the segment's region, chunk by chunk in flat (= token) order
+    // Ordered placement into the segment's region, chunk by chunk in flat (= token) order: definite
+    // tokens grow from the front, candidates from the back (so they end up in descending token order;
+    // the finishing pass reads them backwards).
     const size_t loc = (size_t)dsc.score_off + (size_t)id.h * dsc.head_stride +
                        (size_t)id.seg * dsc.seg_pages * kPageTokens;
-    int baseA = 0, baseC = ca, parity = 0;
+    const size_t last = loc + (size_t)v.np * kPageTokens - 1; // the region holds np * 64 elements
+    int baseA = 0, baseC = 0, parity = 0;
     for (int c0 = 0; c0 < v.total; c0 += kSelChunk) {
         float sv[kSelE];
         int tok[kSelE];
@@ -305,14 +300,14 @@ __global__ __launch_bounds__(kSelectThreads) void select_local_kernel(
 #pragma unroll
         for (int e = 0; e < kSelE; ++e) {
             if (fa[e]) { loc_scores[loc + baseA + exA[e]] = sv[e]; loc_ids[loc + baseA + exA[e]] = tok[e]; }
-            if (fc[e]) { loc_scores[loc + baseC + exC[e]] = sv[e]; loc_ids[loc + baseC + exC[e]] = tok[e]; }
+            if (fc[e]) { loc_scores[last - (baseC + exC[e])] = sv[e]; loc_ids[last - (baseC + exC[e])] = tok[e]; }
         }
         baseA += totA;
         baseC += totC;
     }
     if (tid == 0) {
         seg_counts[((size_t)rh * kMaxSegs + id.seg) * 2] = baseA;
-        seg_counts[((size_t)rh * kMaxSegs + id.seg) * 2 + 1] = baseC - ca;
+        seg_counts[((size_t)rh * kMaxSegs + id.seg) * 2 + 1] = baseC;
     }
 }
 
@@ -384,7 +379,8 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
     if (bucket_rule) {
         for (int e = tid; e < totC; e += kSelectThreads) {
             const int s = find_seg(preC, e);
-            const size_t src = (size_t)s * seg_region + (size_t)cntA[s] + (size_t)(e - preC[s]);
+            const int np_s = min(dsc.n_pages, (s + 1) * dsc.seg_pages) - s * dsc.seg_pages;
+            const size_t src = (size_t)s * seg_region + (size_t)np_s * kPageTokens - 1 - (size_t)(e - preC[s]);
             ids[totA + e] = li[src];
             ss[totA + e] = ls[src];
         }
