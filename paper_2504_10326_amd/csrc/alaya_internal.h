@@ -46,9 +46,9 @@ struct DeviceViews {
     const int32_t *page_table; // [max_seqs][max_pages_per_seq]
     const void *k_pool;
     const void *v_pool;
-    // scoring output: the survivors of each page, [page][head][64] inside the request's block ...
-    float *cand_scores;
-    int32_t *cand_ids;
+    // scoring output: the survivors of each page as (score bits, token id) pairs, [page][head][64]
+    // inside the request's block ...
+    uint2 *cand;
     int32_t *page_cnt;         // ... and how many there are: [head][n_pages] per request, requests in order
     // selection, stage 1: per (head, segment) local lists, [head][head_stride] inside the block,
     // segment s at s * seg_pages * 64: definite tokens first, tie-bucket tokens behind them
@@ -59,6 +59,8 @@ struct DeviceViews {
     int32_t *sel_ids;
     uint32_t *hist;            // [max_batch * n_q_heads][kHistBins] bucket counts of the survivors; zero between calls
     uint32_t *head_maxkey;     // [max_batch * n_q_heads] maximum score as an ordered key; zero between calls
+    uint32_t *sample_hist;     // [max_batch * n_q_heads][kHistBins] bucket counts of the sampled pages; zero between calls
+    uint32_t *sample_maxkey;   // [max_batch * n_q_heads] maximum over the sampled pages; zero between calls
     uint32_t *tau;             // [max_batch * n_q_heads] lower bound of the selection threshold (ordered key)
     int32_t *seg_counts;       // [max_batch * n_q_heads][kMaxSegs][2]
     float *head_M;             // [max_batch * n_q_heads]: maximum score per head
@@ -81,7 +83,7 @@ hipError_t launch_append(const Shape &sh, const int32_t *page_table_row, void *k
 
 // phase 0 scores the sampled pages in full, phase 1 the other pages against dv.tau.
 hipError_t launch_score(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles,
-                        int pages_per_wave, int phase, hipStream_t st);
+                        int pages_per_wave, int phase, int mode, hipStream_t st);
 // mode: 0 top-k, 1 DIPR
 hipError_t launch_tau(const Shape &sh, const DeviceViews &dv, int B, int mode, hipStream_t st);
 

@@ -58,8 +58,8 @@ bool cfg_ok(const alaya_cache_config *c)
 }
 
 struct Layout {
-    size_t page_table, desc, cand_scores, cand_ids, loc_scores, loc_ids, sel_scores, sel_ids, page_cnt, hist,
-        head_maxkey, tau, seg_counts, head_M, head_info, counts, partials, status, total;
+    size_t page_table, desc, cand, loc_scores, loc_ids, sel_scores, sel_ids, page_cnt, hist,
+        head_maxkey, sample_hist, sample_maxkey, tau, seg_counts, head_M, head_info, counts, partials, status, total;
     int64_t mpps;        // max pages per sequence
     int64_t score_elems; // capacity of each per-token array
     int64_t max_tiles;   // full-attention tiles
@@ -77,8 +77,7 @@ Layout make_layout(const alaya_cache_config &c)
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     L.page_table = take((size_t)L.mpps * c.max_seqs * sizeof(int32_t));
     L.desc = take((size_t)c.max_batch * sizeof(ReqDesc));
-    L.cand_scores = take((size_t)L.score_elems * sizeof(float));
-    L.cand_ids = take((size_t)L.score_elems * sizeof(int32_t));
+    L.cand = take((size_t)L.score_elems * sizeof(uint2));
     L.loc_scores = take((size_t)L.score_elems * sizeof(float));
     L.loc_ids = take((size_t)L.score_elems * sizeof(int32_t));
     L.sel_scores = take((size_t)L.score_elems * sizeof(float));
@@ -86,6 +85,8 @@ Layout make_layout(const alaya_cache_config &c)
     L.page_cnt = take((size_t)L.max_pages * c.n_q_heads * sizeof(int32_t));
     L.hist = take((size_t)c.max_batch * c.n_q_heads * kHistBins * sizeof(uint32_t));
     L.head_maxkey = take((size_t)c.max_batch * c.n_q_heads * sizeof(uint32_t));
+    L.sample_hist = take((size_t)c.max_batch * c.n_q_heads * kHistBins * sizeof(uint32_t));
+    L.sample_maxkey = take((size_t)c.max_batch * c.n_q_heads * sizeof(uint32_t));
     L.tau = take((size_t)c.max_batch * c.n_q_heads * sizeof(uint32_t));
     L.seg_counts = take((size_t)c.max_batch * c.n_q_heads * kMaxSegs * 2 * sizeof(int32_t));
     L.head_M = take((size_t)c.max_batch * c.n_q_heads * sizeof(float));
@@ -289,8 +290,7 @@ int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k
     c->dv.page_table = (const int32_t *)(c->ws + L.page_table);
     c->dv.k_pool = k_pool;
     c->dv.v_pool = v_pool;
-    c->dv.cand_scores = (float *)(c->ws + L.cand_scores);
-    c->dv.cand_ids = (int32_t *)(c->ws + L.cand_ids);
+    c->dv.cand = (uint2 *)(c->ws + L.cand);
     c->dv.loc_scores = (float *)(c->ws + L.loc_scores);
     c->dv.loc_ids = (int32_t *)(c->ws + L.loc_ids);
     c->dv.sel_scores = (float *)(c->ws + L.sel_scores);
@@ -298,6 +298,8 @@ int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k
     c->dv.page_cnt = (int32_t *)(c->ws + L.page_cnt);
     c->dv.hist = (uint32_t *)(c->ws + L.hist);
     c->dv.head_maxkey = (uint32_t *)(c->ws + L.head_maxkey);
+    c->dv.sample_hist = (uint32_t *)(c->ws + L.sample_hist);
+    c->dv.sample_maxkey = (uint32_t *)(c->ws + L.sample_maxkey);
     c->dv.tau = (uint32_t *)(c->ws + L.tau);
     c->dv.seg_counts = (int32_t *)(c->ws + L.seg_counts);
     c->dv.head_info = (int32_t *)(c->ws + L.head_info);
@@ -438,7 +440,12 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
         if (ppw < 1) ppw = 1;
         if (ppw > 8) ppw = 8;
     }
-    const int64_t seg_pages_want = c->tune_seg > 0 ? c->tune_seg : 256;
+    // pages per selection segment: about 512 segment workgroups in all, 128 to 2048 pages each
+    int64_t seg_pages_want = c->tune_seg;
+    if (seg_pages_want <= 0) {
+        seg_pages_want = 128;
+        while (seg_pages_want < kMaxSegPages && seg_pages_want * 512 < total_pages * n_q_heads) seg_pages_want *= 2;
+    }
     int splits = c->tune_splits;
     if (splits <= 0) {
         splits = 1024 / (B * n_q_heads);
@@ -518,13 +525,13 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
     hipError_t e;
     {
         Timed tm(c, 6, st);
-        e = launch_score(sh, c->dv, B, q, tiles, 1, 0, st);
+        e = launch_score(sh, c->dv, B, q, tiles, 1, 0, tiles_b > 0 ? p->mode : -1, st);
         if (e == hipSuccess && tiles_b > 0) e = launch_tau(sh, c->dv, B, p->mode, st);
     }
     if (e != hipSuccess) return fail_hip(e, "sample scoring launch");
     if (tiles_b > 0) {
         Timed tm(c, 0, st);
-        e = launch_score(sh, c->dv, B, q, tiles_b, ppw, 1, st);
+        e = launch_score(sh, c->dv, B, q, tiles_b, ppw, 1, p->mode, st);
     }
     if (e != hipSuccess) return fail_hip(e, "score launch");
     { Timed tm(c, 1, st); e = launch_select(sh, c->dv, B, p->mode, segs, p->out_ids, p->out_counts, p->ids_stride, st); }
@@ -633,7 +640,7 @@ int alaya_kernel_times(alaya_cache *c, double *sum_ms, int64_t *launches, int n_
 const float *alaya_debug_scores(const alaya_cache *c)
 {
     if (!c) { fail(ALAYA_E_INVAL, "null cache handle"); return nullptr; }
-    return c->dv.cand_scores;
+    return (const float *)c->dv.cand;
 }
 
 int alaya_debug_pages(const alaya_cache *c, int64_t *sampled, int64_t *main_pass)

@@ -87,17 +87,32 @@ __device__ __forceinline__ int phase_page(int phase, int i, int S)
     return phase == 0 ? i * S : i + i / (S - 1) + 1;
 }
 
-template <int DT, int D, int G>
+// PHASE 0 (sample, top-k): the workgroup also counts its scores per bucket in LDS and adds the
+// non-empty buckets to the head's sample histogram; PHASE 0 (DIPR): it raises the head's sample
+// maximum.  Few workgroups run in phase 0 (a 1/S share of the pages), so these atomics are cheap; the
+// main pass (PHASE 1) has none.
+template <int DT, int D, int G, int PHASE>
 __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ desc, int B,
                                                      const int32_t *__restrict__ page_table,
                                                      const uint32_t *__restrict__ qw, const uint4 *__restrict__ k_pool,
-                                                     float *__restrict__ cand_scores, int32_t *__restrict__ cand_ids,
-                                                     int32_t *__restrict__ page_cnt,
-                                                     const uint32_t *__restrict__ tau_in, int H_kv, int ppw,
-                                                     int phase)
+                                                     uint2 *__restrict__ cand, int32_t *__restrict__ page_cnt,
+                                                     const uint32_t *__restrict__ tau_in,
+                                                     uint32_t *__restrict__ sample_hist,
+                                                     uint32_t *__restrict__ sample_maxkey, int H_kv, int ppw, int mode)
 {
+    constexpr int phase = PHASE;
     constexpr int NC = D * (DT == 0 ? 2 : 4) / 16; // 16-byte chunks per key
     constexpr int QW = D * (DT == 0 ? 2 : 4) / 4;  // 32-bit words per query head
+    // two 16-bit counters per word: a phase-0 workgroup scores 4 pages = 256 tokens per head
+    __shared__ uint32_t lhist[PHASE == 0 ? G : 1][PHASE == 0 ? kHistBins / 2 : 1];
+    __shared__ float wmax[kScoreWaves][G];
+    const bool sample_hist_on = PHASE == 0 && mode == 0 && ppw == 1;
+    if (PHASE == 0) {
+        if (sample_hist_on)
+            for (int i = threadIdx.x; i < G * (kHistBins / 2); i += 256) (&lhist[0][0])[i] = 0u;
+        if (threadIdx.x < kScoreWaves * G) (&wmax[0][0])[threadIdx.x] = -INFINITY;
+        __syncthreads();
+    }
 
     const int kvh = blockIdx.x % H_kv;
     const int tile = blockIdx.x / H_kv;
@@ -116,13 +131,18 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
     // a wavefront takes `ppw` consecutive pages of its phase
     const int i_begin = ((tile - (phase == 0 ? dsc.tile_start : dsc.tileb_start)) * kScoreWaves + wave) * ppw;
     const int i_end = min(i_begin + ppw, n_mine);
-    if (i_begin >= i_end) return;                                // whole wavefront; no barriers below
+    const bool idle = i_begin >= i_end;
+    if (PHASE == 1 && idle) return;                              // whole wavefront; the main pass has no barriers
     const uint4 *qh = (const uint4 *)(qw + (size_t)rh0 * QW);    // wave-uniform address: scalar loads
 
     uint32_t tau[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) tau[g] = phase == 0 ? 0u : tau_in[rh0 + g];
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
+
+    float lmax[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) lmax[g] = -INFINITY;
 
     for (int i = i_begin; i < i_end; ++i) {
         const int p = phase_page(phase, i, S);
@@ -166,25 +186,68 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
             if (keep) {
                 const size_t pos = (size_t)dsc.score_off + ((size_t)p * H_q + kvh * G + g) * kPageTokens +
                                    (size_t)__popcll(m & lt_mask);
-                cand_scores[pos] = acc[g];
-                cand_ids[pos] = j;
+                cand[pos] = make_uint2(__float_as_uint(acc[g]), (uint32_t)j); // one 8-byte store
             }
             if (lane == g) // survivors of this page for head g
                 page_cnt[(size_t)dsc.page_start * H_q + (size_t)(kvh * G + g) * dsc.n_pages + p] = __popcll(m);
+            if (PHASE == 0 && valid) {
+                lmax[g] = fmaxf(lmax[g], acc[g]);
+                if (sample_hist_on) {
+                    const uint32_t bin = ord_key(acc[g]) >> 21;
+                    atomicAdd(&lhist[g][bin >> 1], 1u << ((bin & 1u) * 16u));
+                }
+            }
+        }
+    }
+    if (PHASE == 0) {
+        // what the sample says about this head: bucket counts (top-k) or the maximum (DIPR)
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float m = lmax[g];
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+            if (lane == 0) wmax[wave][g] = m;
+        }
+        __syncthreads();
+        if (mode == 1) {
+            if (threadIdx.x < G) {
+                float m = wmax[0][threadIdx.x];
+#pragma unroll
+                for (int w = 1; w < kScoreWaves; ++w) m = fmaxf(m, wmax[w][threadIdx.x]);
+                if (m > -INFINITY) {
+                    const uint32_t key = ord_key(m);
+                    uint32_t *dst = sample_maxkey + rh0 + threadIdx.x;
+                    if (key > *dst) atomicMax(dst, key); // the plain read only skips atomics that cannot matter
+                }
+            }
+        } else if (sample_hist_on) {
+            uint32_t *gh = sample_hist + (size_t)rh0 * kHistBins;
+            for (int i = threadIdx.x; i < G * (kHistBins / 2); i += 256) {
+                const uint32_t v = (&lhist[0][0])[i];
+                if (v & 0xFFFFu) atomicAdd(&gh[2 * i], v & 0xFFFFu);
+                if (v >> 16) atomicAdd(&gh[2 * i + 1], v >> 16);
+            }
         }
     }
 }
 
 template <int DT, int D>
 static hipError_t launch_score_g(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles,
-                                 int ppw, int phase, hipStream_t st)
+                                 int ppw, int phase, int mode, hipStream_t st)
 {
     const int G = sh.n_q_heads / sh.n_kv_heads;
     const dim3 grid((unsigned)(total_tiles * sh.n_kv_heads)), block(256);
-#define ALAYA_SCORE(GG)                                                                                    \
-    score_kernel<DT, D, GG><<<grid, block, 0, st>>>(dv.desc, B, dv.page_table, (const uint32_t *)q,        \
-                                                    (const uint4 *)dv.k_pool, dv.cand_scores, dv.cand_ids, \
-                                                    dv.page_cnt, dv.tau, sh.n_kv_heads, ppw, phase)
+#define ALAYA_SCORE(GG)                                                                                       \
+    do {                                                                                                      \
+        if (phase == 0)                                                                                       \
+            score_kernel<DT, D, GG, 0><<<grid, block, 0, st>>>(                                               \
+                dv.desc, B, dv.page_table, (const uint32_t *)q, (const uint4 *)dv.k_pool, dv.cand, dv.page_cnt, \
+                dv.tau, dv.sample_hist, dv.sample_maxkey, sh.n_kv_heads, ppw, mode);                          \
+        else                                                                                                  \
+            score_kernel<DT, D, GG, 1><<<grid, block, 0, st>>>(                                               \
+                dv.desc, B, dv.page_table, (const uint32_t *)q, (const uint4 *)dv.k_pool, dv.cand, dv.page_cnt, \
+                dv.tau, dv.sample_hist, dv.sample_maxkey, sh.n_kv_heads, ppw, mode);                          \
+    } while (0)
     switch (G) {
     case 1: ALAYA_SCORE(1); break;
     case 2: ALAYA_SCORE(2); break;
@@ -197,90 +260,51 @@ static hipError_t launch_score_g(const Shape &sh, const DeviceViews &dv, int B, 
 }
 
 hipError_t launch_score(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles, int ppw,
-                        int phase, hipStream_t st)
+                        int phase, int mode, hipStream_t st)
 {
     if (total_tiles <= 0) return hipSuccess;
     if (sh.dtype == 0) {
-        if (sh.head_dim == 128) return launch_score_g<0, 128>(sh, dv, B, q, total_tiles, ppw, phase, st);
-        if (sh.head_dim == 64) return launch_score_g<0, 64>(sh, dv, B, q, total_tiles, ppw, phase, st);
+        if (sh.head_dim == 128) return launch_score_g<0, 128>(sh, dv, B, q, total_tiles, ppw, phase, mode, st);
+        if (sh.head_dim == 64) return launch_score_g<0, 64>(sh, dv, B, q, total_tiles, ppw, phase, mode, st);
     } else {
-        if (sh.head_dim == 128) return launch_score_g<1, 128>(sh, dv, B, q, total_tiles, ppw, phase, st);
-        if (sh.head_dim == 64) return launch_score_g<1, 64>(sh, dv, B, q, total_tiles, ppw, phase, st);
+        if (sh.head_dim == 128) return launch_score_g<1, 128>(sh, dv, B, q, total_tiles, ppw, phase, mode, st);
+        if (sh.head_dim == 64) return launch_score_g<1, 64>(sh, dv, B, q, total_tiles, ppw, phase, mode, st);
     }
     return hipErrorInvalidValue;
 }
 
 // ------------------------------------------------------------------------------------------------
-// tau: the lower bound of each head's selection threshold, from the pages phase A scored in full
-// (every valid token of a sampled page was written, in order).  One 1024-thread workgroup per
-// (request, head); the loop over the sample is flat, so its loads are independent.
+// tau: the lower bound of each head's selection threshold, from what the sample pass accumulated.
+// One 1024-thread workgroup per (request, head).  It consumes the sample histogram / maximum and
+// leaves them zero for the next call.
 __global__ __launch_bounds__(kSelectThreads) void tau_kernel(const ReqDesc *__restrict__ desc, int H_q, int mode,
-                                                              const float *__restrict__ cand_scores,
+                                                              uint32_t *__restrict__ sample_hist,
+                                                              uint32_t *__restrict__ sample_maxkey,
                                                               uint32_t *__restrict__ tau)
 {
-    __shared__ uint32_t lh[kHistBins];
-    __shared__ float wred[kSelectThreads / 64];
     __shared__ int32_t wtot[kSelectThreads / 64];
     __shared__ int32_t found;
 
     const int rh = blockIdx.x;
-    const int r = rh / H_q, h = rh % H_q;
-    const ReqDesc dsc = desc[r];
+    const ReqDesc dsc = desc[rh / H_q];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int S = dsc.sample_stride;
-    const int n_a = (dsc.n_pages + S - 1) / S;
-    const int total = n_a * kPageTokens;
-    const float *sc = cand_scores + (size_t)dsc.score_off + (size_t)h * kPageTokens;
-
-    // eight independent loads per thread and step, so that their latencies overlap
-    constexpr int U = 8;
-    auto load8 = [&](int t0, float *v, bool *ok) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int t = t0 + u * kSelectThreads;
-            const int p = (t >> 6) * S, e = t & 63;
-            ok[u] = t < total && p * kPageTokens + e < dsc.n;
-            v[u] = ok[u] ? sc[(size_t)p * H_q * kPageTokens + e] : 0.f;
-        }
-    };
 
     if (mode == 1) { // DIPR: (maximum over the sample) - beta
-        float m = -INFINITY;
-        for (int t0 = tid; t0 < total; t0 += U * kSelectThreads) {
-            float v[U];
-            bool ok[U];
-            load8(t0, v, ok);
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (ok[u]) m = fmaxf(m, v[u]);
-        }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-        if (lane == 0) wred[wave] = m;
-        __syncthreads();
         if (tid == 0) {
-            float M = wred[0];
-            for (int w = 1; w < kSelectThreads / 64; ++w) M = fmaxf(M, wred[w]);
-            tau[rh] = ord_key(M - dsc.beta);
+            const uint32_t mk = sample_maxkey[rh];
+            tau[rh] = mk ? ord_key(ord_float(mk) - dsc.beta) : 0u;
+            sample_maxkey[rh] = 0u;
         }
         return;
     }
-    // top-k: bucket of the k-th largest score of the sample
-    for (int i = tid; i < kHistBins; i += kSelectThreads) lh[i] = 0u;
-    if (tid == 0) found = -1;
-    __syncthreads();
-    for (int t0 = tid; t0 < total; t0 += U * kSelectThreads) {
-        float v[U];
-        bool ok[U];
-        load8(t0, v, ok);
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (ok[u]) atomicAdd(&lh[ord_key(v[u]) >> 21], 1u);
-    }
-    __syncthreads();
-    // walk down from the top bucket: two buckets per thread, thread 0 holding the top ones
+    // top-k: lower edge of the bucket that holds the k-th largest score of the sample.
+    // Walk down from the top bucket: two buckets per thread, thread 0 holding the top ones.
+    uint32_t *gh = sample_hist + (size_t)rh * kHistBins;
     const int b0 = kHistBins - 1 - 2 * tid;
-    const int c0 = (int)lh[b0], c1 = (int)lh[b0 - 1];
+    const int c0 = (int)gh[b0], c1 = (int)gh[b0 - 1];
+    gh[b0] = 0u;
+    gh[b0 - 1] = 0u;
+    if (tid == 0) found = -1;
     int inc = c0 + c1;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
@@ -299,8 +323,8 @@ __global__ __launch_bounds__(kSelectThreads) void tau_kernel(const ReqDesc *__re
 
 hipError_t launch_tau(const Shape &sh, const DeviceViews &dv, int B, int mode, hipStream_t st)
 {
-    tau_kernel<<<dim3((unsigned)(B * sh.n_q_heads)), dim3(kSelectThreads), 0, st>>>(dv.desc, sh.n_q_heads, mode,
-                                                                                   dv.cand_scores, dv.tau);
+    tau_kernel<<<dim3((unsigned)(B * sh.n_q_heads)), dim3(kSelectThreads), 0, st>>>(
+        dv.desc, sh.n_q_heads, mode, dv.sample_hist, dv.sample_maxkey, dv.tau);
     return hipGetLastError();
 }
 

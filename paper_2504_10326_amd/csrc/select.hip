@@ -127,20 +127,29 @@ struct SegView {
     size_t page_stride;     // elements between consecutive pages of this head (H_q * 64)
 };
 
-// Loads the pages' survivor counts and leaves their exclusive prefix sums in off[0 .. np]
-// (off[np] = total).  Two pages per thread; two barriers.
-__device__ __forceinline__ SegView load_segment(const ReqDesc &dsc, int H_q, int h, int seg,
-                                                const int32_t *__restrict__ page_cnt, int32_t *off, int32_t *wtot)
+// Loads the pages' survivor counts (two pages per thread) ...
+__device__ __forceinline__ SegView begin_segment(const ReqDesc &dsc, int H_q, int h, int seg,
+                                                 const int32_t *__restrict__ page_cnt, int &a0, int &a1)
 {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x;
     SegView v;
     v.p_begin = seg * dsc.seg_pages;
     v.np = min(dsc.n_pages, v.p_begin + dsc.seg_pages) - v.p_begin;
     v.base = (size_t)dsc.score_off + (size_t)h * kPageTokens;
     v.page_stride = (size_t)H_q * kPageTokens;
+    v.total = 0;
     const int32_t *cnt = page_cnt + (size_t)dsc.page_start * H_q + (size_t)h * dsc.n_pages + v.p_begin;
     const int i0 = 2 * tid, i1 = 2 * tid + 1;
-    const int a0 = i0 < v.np ? cnt[i0] : 0, a1 = i1 < v.np ? cnt[i1] : 0;
+    a0 = i0 < v.np ? cnt[i0] : 0;
+    a1 = i1 < v.np ? cnt[i1] : 0;
+    return v;
+}
+
+// ... and leaves their exclusive prefix sums in off[0 .. np] (off[np] = total).  Two barriers.
+__device__ __forceinline__ void scan_segment(SegView &v, int a0, int a1, int32_t *off, int32_t *wtot)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i0 = 2 * tid, i1 = 2 * tid + 1;
     int inc = a0 + a1;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
@@ -156,7 +165,6 @@ __device__ __forceinline__ SegView load_segment(const ReqDesc &dsc, int H_q, int
     if (tid == kSelectThreads - 1 && v.np == kMaxSegPages) off[v.np] = pre + a0 + a1;
     __syncthreads();
     v.total = off[v.np];
-    return v;
 }
 
 // Flat index t -> element offset in the survivor arrays.
@@ -190,7 +198,7 @@ struct Rule {
 
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kSelectThreads) void select_stats_kernel(
-    const ReqDesc *__restrict__ desc, int B, int H_q, int mode, const float *__restrict__ cand_scores,
+    const ReqDesc *__restrict__ desc, int B, int H_q, int mode, const uint2 *__restrict__ cand,
     const int32_t *__restrict__ page_cnt, uint32_t *__restrict__ hist, uint32_t *__restrict__ head_maxkey)
 {
     __shared__ uint32_t lh[kHistBins];
@@ -205,7 +213,9 @@ __global__ __launch_bounds__(kSelectThreads) void select_stats_kernel(
     const bool want_hist = mode == 0 && dsc.k < dsc.n;
     if (want_hist)
         for (int i = tid; i < kHistBins; i += kSelectThreads) lh[i] = 0u;
-    const SegView v = load_segment(dsc, H_q, id.h, id.seg, page_cnt, off, wtot); // barriers inside
+    int a0, a1;
+    SegView v = begin_segment(dsc, H_q, id.h, id.seg, page_cnt, a0, a1);
+    scan_segment(v, a0, a1, off, wtot); // barriers inside
     float m = -INFINITY;
     constexpr int U = 4; // independent loads per thread and step
     for (int t0 = tid; t0 < v.total; t0 += U * kSelectThreads) {
@@ -213,7 +223,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_stats_kernel(
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int t = t0 + u * kSelectThreads;
-            s[u] = t < v.total ? cand_scores[flat_to_offset(v, off, t)] : -INFINITY;
+            s[u] = t < v.total ? __uint_as_float(cand[flat_to_offset(v, off, t)].x) : -INFINITY;
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -237,8 +247,8 @@ __global__ __launch_bounds__(kSelectThreads) void select_stats_kernel(
 
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kSelectThreads) void select_local_kernel(
-    const ReqDesc *__restrict__ desc, int B, int H_q, int mode, const float *__restrict__ cand_scores,
-    const int32_t *__restrict__ cand_ids, const int32_t *__restrict__ page_cnt,
+    const ReqDesc *__restrict__ desc, int B, int H_q, int mode, const uint2 *__restrict__ cand,
+    const int32_t *__restrict__ page_cnt,
     const uint32_t *__restrict__ hist, const uint32_t *__restrict__ head_maxkey, float *__restrict__ head_M,
     int32_t *__restrict__ head_info, int32_t *__restrict__ seg_counts, float *__restrict__ loc_scores,
     int32_t *__restrict__ loc_ids)
@@ -254,6 +264,9 @@ __global__ __launch_bounds__(kSelectThreads) void select_local_kernel(
     const int rh = id.r * H_q + id.h;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
+    // issue every independent load first: the page counts, the maximum, the histogram
+    int a0, a1;
+    SegView v = begin_segment(dsc, H_q, id.h, id.seg, page_cnt, a0, a1);
     const float M = ord_float(head_maxkey[rh]);
     const bool bucket_rule = mode == 0 && dsc.k < dsc.n;
     if (bucket_rule) {
@@ -271,8 +284,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_local_kernel(
         head_info[2 * rh + 1] = bucket_rule ? res[1] : 0;
     }
     __syncthreads(); // wtot is reused below
-
-    const SegView v = load_segment(dsc, H_q, id.h, id.seg, page_cnt, off, wtot);
+    scan_segment(v, a0, a1, off, wtot);
 
     // Ordered placement into the segment's region, chunk by chunk in flat (= token) order: definite
     // tokens grow from the front, candidates from the back (so they end up in descending token order;
@@ -290,8 +302,9 @@ __global__ __launch_bounds__(kSelectThreads) void select_local_kernel(
             const int t = c0 + e * kSelectThreads + tid;
             const bool in = t < v.total;
             const size_t o = in ? flat_to_offset(v, off, t) : v.base;
-            sv[e] = in ? cand_scores[o] : 0.f;
-            tok[e] = in ? cand_ids[o] : 0;
+            const uint2 pr = in ? cand[o] : make_uint2(0u, 0u);
+            sv[e] = __uint_as_float(pr.x);
+            tok[e] = (int)pr.y;
             rule.classify(sv[e], in, fa[e], fc[e]);
         }
         int exA[kSelE], exC[kSelE], totA, totC;
@@ -376,7 +389,69 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
     const bool bucket_rule = head_info[2 * rh] >= 0;
     int count = totA;
 
-    if (bucket_rule) {
+    if (bucket_rule && totC <= kSelChunk) {
+        // The usual case: the tie bucket's tokens fit in registers (four per thread, in token order).
+        // They are gathered once, refined from registers, and only the kept ones are written.
+        const uint32_t b1 = (uint32_t)head_info[2 * rh];
+        const int cb = totC;
+        int need = dsc.k - totA; // 1 <= need <= cb
+        float v[kSelE];
+        int idv[kSelE];
+        uint32_t key[kSelE];
+        bool in[kSelE];
+#pragma unroll
+        for (int e = 0; e < kSelE; ++e) {
+            const int i = e * kSelectThreads + tid;
+            in[e] = i < cb;
+            const int sgm = in[e] ? find_seg(preC, i) : 0;
+            const int np_s = min(dsc.n_pages, (sgm + 1) * dsc.seg_pages) - sgm * dsc.seg_pages;
+            const size_t src = (size_t)sgm * seg_region + (size_t)np_s * kPageTokens - 1 - (size_t)(i - preC[sgm]);
+            v[e] = in[e] ? ls[src] : 0.f;
+            idv[e] = in[e] ? li[src] : 0;
+            key[e] = ord_key(v[e]);
+        }
+        uint32_t T = 0u; // keep key > T, and the first `ties` tokens with key == T
+        int ties = 0;
+        if (need < cb) {
+            for (int i = tid; i < kHistBins; i += kSelectThreads) lh[i] = 0u;
+            __syncthreads();
+#pragma unroll
+            for (int e = 0; e < kSelE; ++e)
+                if (in[e]) atomicAdd(&lh[(key[e] >> 10) & 0x7FFu], 1u);
+            __syncthreads();
+            block_find_bin(lh, 2048, need, wtot, res);
+            const uint32_t b2 = (uint32_t)res[0];
+            need -= res[1];
+            __syncthreads();
+            for (int i = tid; i < 1024; i += kSelectThreads) lh[i] = 0u;
+            __syncthreads();
+            const uint32_t pre = (b1 << 11) | b2; // key >> 10 of the threshold
+#pragma unroll
+            for (int e = 0; e < kSelE; ++e)
+                if (in[e] && (key[e] >> 10) == pre) atomicAdd(&lh[key[e] & 0x3FFu], 1u);
+            __syncthreads();
+            block_find_bin(lh, 1024, need, wtot, res);
+            T = (pre << 10) | (uint32_t)res[0];
+            ties = need - res[1];
+        }
+        bool fa[kSelE], fb[kSelE];
+#pragma unroll
+        for (int e = 0; e < kSelE; ++e) {
+            fa[e] = in[e] && key[e] > T;
+            fb[e] = in[e] && key[e] == T;
+        }
+        int exA[kSelE], exB[kSelE], tA, tB;
+        chunk_ranks(scan, 0, fa, fb, exA, exB, tA, tB);
+#pragma unroll
+        for (int e = 0; e < kSelE; ++e) {
+            if (fa[e] || (fb[e] && exB[e] < ties)) {
+                const int pos = totA + exA[e] + min(exB[e], ties);
+                ids[pos] = idv[e];
+                ss[pos] = v[e];
+            }
+        }
+        count = dsc.k;
+    } else if (bucket_rule) {
         for (int e = tid; e < totC; e += kSelectThreads) {
             const int s = find_seg(preC, e);
             const int np_s = min(dsc.n_pages, (s + 1) * dsc.seg_pages) - s * dsc.seg_pages;
@@ -467,11 +542,11 @@ hipError_t launch_select(const Shape &sh, const DeviceViews &dv, int B, int mode
 {
     const dim3 block(kSelectThreads);
     const dim3 seg_grid((unsigned)(total_segs * sh.n_q_heads));
-    select_stats_kernel<<<seg_grid, block, 0, st>>>(dv.desc, B, sh.n_q_heads, mode, dv.cand_scores, dv.page_cnt,
+    select_stats_kernel<<<seg_grid, block, 0, st>>>(dv.desc, B, sh.n_q_heads, mode, dv.cand, dv.page_cnt,
                                                     dv.hist, dv.head_maxkey);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    select_local_kernel<<<seg_grid, block, 0, st>>>(dv.desc, B, sh.n_q_heads, mode, dv.cand_scores, dv.cand_ids,
+    select_local_kernel<<<seg_grid, block, 0, st>>>(dv.desc, B, sh.n_q_heads, mode, dv.cand,
                                                     dv.page_cnt, dv.hist, dv.head_maxkey, dv.head_M, dv.head_info,
                                                     dv.seg_counts, dv.loc_scores, dv.loc_ids);
     e = hipGetLastError();
