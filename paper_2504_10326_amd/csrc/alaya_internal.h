@@ -57,10 +57,10 @@ struct DeviceViews {
     // selection, stage 2 = what attention reads: [head][head_stride] inside the block
     float *sel_scores;
     int32_t *sel_ids;
-    uint32_t *hist;            // [max_batch * n_q_heads][kHistBins] bucket counts of the survivors; zero between calls
-    uint32_t *head_maxkey;     // [max_batch * n_q_heads] maximum score as an ordered key; zero between calls
-    uint32_t *sample_hist;     // [max_batch * n_q_heads][kHistBins] bucket counts of the sampled pages; zero between calls
-    uint32_t *sample_maxkey;   // [max_batch * n_q_heads] maximum over the sampled pages; zero between calls
+    // Bucket counts (top-k only) and maximum (as an ordered key) of the head's scores: the sample pass
+    // enters the sampled pages, the selection the survivors of the others.  Zero between calls.
+    uint32_t *hist;            // [max_batch * n_q_heads][kHistBins]
+    uint32_t *head_maxkey;     // [max_batch * n_q_heads]
     uint32_t *tau;             // [max_batch * n_q_heads] lower bound of the selection threshold (ordered key)
     int32_t *seg_counts;       // [max_batch * n_q_heads][kMaxSegs][2]
     float *head_M;             // [max_batch * n_q_heads]: maximum score per head

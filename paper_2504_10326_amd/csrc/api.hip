@@ -59,7 +59,7 @@ bool cfg_ok(const alaya_cache_config *c)
 
 struct Layout {
     size_t page_table, desc, cand, loc_scores, loc_ids, sel_scores, sel_ids, page_cnt, hist,
-        head_maxkey, sample_hist, sample_maxkey, tau, seg_counts, head_M, head_info, counts, partials, status, total;
+        head_maxkey, tau, seg_counts, head_M, head_info, counts, partials, status, total;
     int64_t mpps;        // max pages per sequence
     int64_t score_elems; // capacity of each per-token array
     int64_t max_tiles;   // full-attention tiles
@@ -85,8 +85,6 @@ Layout make_layout(const alaya_cache_config &c)
     L.page_cnt = take((size_t)L.max_pages * c.n_q_heads * sizeof(int32_t));
     L.hist = take((size_t)c.max_batch * c.n_q_heads * kHistBins * sizeof(uint32_t));
     L.head_maxkey = take((size_t)c.max_batch * c.n_q_heads * sizeof(uint32_t));
-    L.sample_hist = take((size_t)c.max_batch * c.n_q_heads * kHistBins * sizeof(uint32_t));
-    L.sample_maxkey = take((size_t)c.max_batch * c.n_q_heads * sizeof(uint32_t));
     L.tau = take((size_t)c.max_batch * c.n_q_heads * sizeof(uint32_t));
     L.seg_counts = take((size_t)c.max_batch * c.n_q_heads * kMaxSegs * 2 * sizeof(int32_t));
     L.head_M = take((size_t)c.max_batch * c.n_q_heads * sizeof(float));
@@ -298,8 +296,6 @@ int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k
     c->dv.page_cnt = (int32_t *)(c->ws + L.page_cnt);
     c->dv.hist = (uint32_t *)(c->ws + L.hist);
     c->dv.head_maxkey = (uint32_t *)(c->ws + L.head_maxkey);
-    c->dv.sample_hist = (uint32_t *)(c->ws + L.sample_hist);
-    c->dv.sample_maxkey = (uint32_t *)(c->ws + L.sample_maxkey);
     c->dv.tau = (uint32_t *)(c->ws + L.tau);
     c->dv.seg_counts = (int32_t *)(c->ws + L.seg_counts);
     c->dv.head_info = (int32_t *)(c->ws + L.head_info);
@@ -448,7 +444,16 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
     }
     int splits = c->tune_splits;
     if (splits <= 0) {
-        splits = 1024 / (B * n_q_heads);
+        // enough workgroups to fill the chip, and at most about 512 selected tokens per workgroup
+        // (a threshold set's size is not known here: assume 4096)
+        int kmax = 4096;
+        if (p->mode == ALAYA_TOPK) {
+            kmax = 1;
+            for (int b = 0; b < B; ++b) kmax = p->topk[b] > kmax ? p->topk[b] : kmax;
+        }
+        const int fill = (2048 + B * n_q_heads - 1) / (B * n_q_heads);
+        const int per = (int)(((int64_t)kmax + 511) / 512);
+        splits = fill > per ? fill : per;
         if (splits < 1) splits = 1;
         if (splits > 32) splits = 32;
     }
@@ -522,20 +527,22 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
 
     const Shape sh{c->cfg.dtype, c->cfg.head_dim, n_q_heads, c->cfg.n_kv_heads};
     const float scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)c->cfg.head_dim);
+    // (a launch that fails below may leave the running histogram and maximum half-filled: dev_ready is
+    // dropped so that the next call zeroes them again)
     hipError_t e;
     {
         Timed tm(c, 6, st);
-        e = launch_score(sh, c->dv, B, q, tiles, 1, 0, tiles_b > 0 ? p->mode : -1, st);
+        e = launch_score(sh, c->dv, B, q, tiles, 1, 0, p->mode, st);
         if (e == hipSuccess && tiles_b > 0) e = launch_tau(sh, c->dv, B, p->mode, st);
     }
-    if (e != hipSuccess) return fail_hip(e, "sample scoring launch");
+    if (e != hipSuccess) { c->dev_ready = false; return fail_hip(e, "sample scoring launch"); }
     if (tiles_b > 0) {
         Timed tm(c, 0, st);
         e = launch_score(sh, c->dv, B, q, tiles_b, ppw, 1, p->mode, st);
     }
-    if (e != hipSuccess) return fail_hip(e, "score launch");
+    if (e != hipSuccess) { c->dev_ready = false; return fail_hip(e, "score launch"); }
     { Timed tm(c, 1, st); e = launch_select(sh, c->dv, B, p->mode, segs, p->out_ids, p->out_counts, p->ids_stride, st); }
-    if (e != hipSuccess) return fail_hip(e, "select launch");
+    if (e != hipSuccess) { c->dev_ready = false; return fail_hip(e, "select launch"); }
     { Timed tm(c, 2, st); e = launch_attend(sh, c->dv, B, scale, splits, st); }
     if (e != hipSuccess) return fail_hip(e, "attend launch");
     { Timed tm(c, 3, st); e = launch_combine(sh, c->dv, B, splits, 0, 0, out, st); }

@@ -87,18 +87,20 @@ __device__ __forceinline__ int phase_page(int phase, int i, int S)
     return phase == 0 ? i * S : i + i / (S - 1) + 1;
 }
 
-// PHASE 0 (sample, top-k): the workgroup also counts its scores per bucket in LDS and adds the
-// non-empty buckets to the head's sample histogram; PHASE 0 (DIPR): it raises the head's sample
-// maximum.  Few workgroups run in phase 0 (a 1/S share of the pages), so these atomics are cheap; the
-// main pass (PHASE 1) has none.
+// PHASE 0 (sample pass): the workgroup also enters its scores into the head's statistics: for DIPR it
+// raises the running maximum, for top-k it counts them per bucket in LDS and adds the non-empty
+// buckets to the histogram.  The bound
+// kernel reads both right after this pass; the selection later adds only the survivors of the OTHER
+// pages to them.  Few workgroups run in phase 0 (a 1/S share of the pages), so these atomics are
+// cheap; the main pass (PHASE 1) has none.
 template <int DT, int D, int G, int PHASE>
 __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ desc, int B,
                                                      const int32_t *__restrict__ page_table,
                                                      const uint32_t *__restrict__ qw, const uint4 *__restrict__ k_pool,
                                                      uint2 *__restrict__ cand, int32_t *__restrict__ page_cnt,
                                                      const uint32_t *__restrict__ tau_in,
-                                                     uint32_t *__restrict__ sample_hist,
-                                                     uint32_t *__restrict__ sample_maxkey, int H_kv, int ppw, int mode)
+                                                     uint32_t *__restrict__ hist,
+                                                     uint32_t *__restrict__ head_maxkey, int H_kv, int ppw, int mode)
 {
     constexpr int phase = PHASE;
     constexpr int NC = D * (DT == 0 ? 2 : 4) / 16; // 16-byte chunks per key
@@ -216,12 +218,13 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
                 for (int w = 1; w < kScoreWaves; ++w) m = fmaxf(m, wmax[w][threadIdx.x]);
                 if (m > -INFINITY) {
                     const uint32_t key = ord_key(m);
-                    uint32_t *dst = sample_maxkey + rh0 + threadIdx.x;
+                    uint32_t *dst = head_maxkey + rh0 + threadIdx.x;
                     if (key > *dst) atomicMax(dst, key); // the plain read only skips atomics that cannot matter
                 }
             }
-        } else if (sample_hist_on) {
-            uint32_t *gh = sample_hist + (size_t)rh0 * kHistBins;
+        }
+        if (sample_hist_on) {
+            uint32_t *gh = hist + (size_t)rh0 * kHistBins;
             for (int i = threadIdx.x; i < G * (kHistBins / 2); i += 256) {
                 const uint32_t v = (&lhist[0][0])[i];
                 if (v & 0xFFFFu) atomicAdd(&gh[2 * i], v & 0xFFFFu);
@@ -242,11 +245,11 @@ static hipError_t launch_score_g(const Shape &sh, const DeviceViews &dv, int B, 
         if (phase == 0)                                                                                       \
             score_kernel<DT, D, GG, 0><<<grid, block, 0, st>>>(                                               \
                 dv.desc, B, dv.page_table, (const uint32_t *)q, (const uint4 *)dv.k_pool, dv.cand, dv.page_cnt, \
-                dv.tau, dv.sample_hist, dv.sample_maxkey, sh.n_kv_heads, ppw, mode);                          \
+                dv.tau, dv.hist, dv.head_maxkey, sh.n_kv_heads, ppw, mode);                          \
         else                                                                                                  \
             score_kernel<DT, D, GG, 1><<<grid, block, 0, st>>>(                                               \
                 dv.desc, B, dv.page_table, (const uint32_t *)q, (const uint4 *)dv.k_pool, dv.cand, dv.page_cnt, \
-                dv.tau, dv.sample_hist, dv.sample_maxkey, sh.n_kv_heads, ppw, mode);                          \
+                dv.tau, dv.hist, dv.head_maxkey, sh.n_kv_heads, ppw, mode);                          \
     } while (0)
     switch (G) {
     case 1: ALAYA_SCORE(1); break;
@@ -275,11 +278,11 @@ hipError_t launch_score(const Shape &sh, const DeviceViews &dv, int B, const voi
 
 // ------------------------------------------------------------------------------------------------
 // tau: the lower bound of each head's selection threshold, from what the sample pass accumulated.
-// One 1024-thread workgroup per (request, head).  It consumes the sample histogram / maximum and
-// leaves them zero for the next call.
+// One 1024-thread workgroup per (request, head); runs between the sample pass and the main pass, when
+// the histogram and the maximum hold the sampled pages only.
 __global__ __launch_bounds__(kSelectThreads) void tau_kernel(const ReqDesc *__restrict__ desc, int H_q, int mode,
-                                                              uint32_t *__restrict__ sample_hist,
-                                                              uint32_t *__restrict__ sample_maxkey,
+                                                              const uint32_t *__restrict__ hist,
+                                                              const uint32_t *__restrict__ head_maxkey,
                                                               uint32_t *__restrict__ tau)
 {
     __shared__ int32_t wtot[kSelectThreads / 64];
@@ -291,19 +294,16 @@ __global__ __launch_bounds__(kSelectThreads) void tau_kernel(const ReqDesc *__re
 
     if (mode == 1) { // DIPR: (maximum over the sample) - beta
         if (tid == 0) {
-            const uint32_t mk = sample_maxkey[rh];
+            const uint32_t mk = head_maxkey[rh];
             tau[rh] = mk ? ord_key(ord_float(mk) - dsc.beta) : 0u;
-            sample_maxkey[rh] = 0u;
         }
         return;
     }
     // top-k: lower edge of the bucket that holds the k-th largest score of the sample.
     // Walk down from the top bucket: two buckets per thread, thread 0 holding the top ones.
-    uint32_t *gh = sample_hist + (size_t)rh * kHistBins;
+    const uint32_t *gh = hist + (size_t)rh * kHistBins;
     const int b0 = kHistBins - 1 - 2 * tid;
     const int c0 = (int)gh[b0], c1 = (int)gh[b0 - 1];
-    gh[b0] = 0u;
-    gh[b0 - 1] = 0u;
     if (tid == 0) found = -1;
     int inc = c0 + c1;
 #pragma unroll
@@ -324,7 +324,7 @@ __global__ __launch_bounds__(kSelectThreads) void tau_kernel(const ReqDesc *__re
 hipError_t launch_tau(const Shape &sh, const DeviceViews &dv, int B, int mode, hipStream_t st)
 {
     tau_kernel<<<dim3((unsigned)(B * sh.n_q_heads)), dim3(kSelectThreads), 0, st>>>(
-        dv.desc, sh.n_q_heads, mode, dv.sample_hist, dv.sample_maxkey, dv.tau);
+        dv.desc, sh.n_q_heads, mode, dv.hist, dv.head_maxkey, dv.tau);
     return hipGetLastError();
 }
 

@@ -210,11 +210,16 @@ __global__ __launch_bounds__(kSelectThreads) void select_stats_kernel(
     const ReqDesc dsc = desc[id.r];
     const int rh = id.r * H_q + id.h;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // The sampled pages entered the histogram and the maximum when they were scored.
+    const int S = dsc.sample_stride;
+    if (S == 1) return; // whole workgroup: every page was a sampled page
     const bool want_hist = mode == 0 && dsc.k < dsc.n;
     if (want_hist)
         for (int i = tid; i < kHistBins; i += kSelectThreads) lh[i] = 0u;
     int a0, a1;
     SegView v = begin_segment(dsc, H_q, id.h, id.seg, page_cnt, a0, a1);
+    if (((v.p_begin + 2 * tid) & (S - 1)) == 0) a0 = 0;
+    if (((v.p_begin + 2 * tid + 1) & (S - 1)) == 0) a1 = 0;
     scan_segment(v, a0, a1, off, wtot); // barriers inside
     float m = -INFINITY;
     constexpr int U = 4; // independent loads per thread and step
@@ -235,7 +240,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_stats_kernel(
     for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
     if (lane == 0) wred[wave] = m;
     __syncthreads();
-    if (tid == 0) {
+    if (tid == 0 && mode == 1) { // top-k takes its maximum from the finished set instead
         float M = wred[0];
         for (int w = 1; w < kSelWaves; ++w) M = fmaxf(M, wred[w]);
         if (M > -INFINITY) atomicMax(&head_maxkey[rh], ord_key(M));
@@ -279,7 +284,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_local_kernel(
     rule.b1 = bucket_rule ? (uint32_t)res[0] : 0u;
     rule.thr = mode == 1 ? M - dsc.beta : -INFINITY; // top-k with k >= n: every token
     if (id.seg == 0 && tid == 0) {
-        head_M[rh] = M;
+        if (mode == 1) head_M[rh] = M; // top-k: written by the finishing pass
         head_info[2 * rh] = bucket_rule ? res[0] : -1;
         head_info[2 * rh + 1] = bucket_rule ? res[1] : 0;
     }
@@ -331,9 +336,10 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
     const int32_t *__restrict__ loc_ids, uint32_t *__restrict__ hist, uint32_t *__restrict__ head_maxkey,
     int32_t *__restrict__ sel_ids, float *__restrict__ sel_scores, int32_t *__restrict__ counts,
     int32_t *__restrict__ out_ids, int32_t *__restrict__ out_counts, int64_t ids_stride,
-    int32_t *__restrict__ status)
+    int32_t *__restrict__ status, float *__restrict__ head_M)
 {
     __shared__ uint32_t lh[kHistBins];
+    __shared__ float wred[kSelWaves];
     __shared__ ScanShared scan;
     __shared__ int32_t preA[kMaxSegs + 1], preC[kMaxSegs + 1], cntA[kMaxSegs];
     __shared__ int32_t wtot[kSelWaves];
@@ -380,11 +386,14 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
         }
         return lo;
     };
+    float mx = -INFINITY; // maximum of the scores this thread enters into the final list
     for (int e = tid; e < totA; e += kSelectThreads) {
         const int s = find_seg(preA, e);
         const size_t src = (size_t)s * seg_region + (size_t)(e - preA[s]);
+        const float x = ls[src];
         ids[e] = li[src];
-        ss[e] = ls[src];
+        ss[e] = x;
+        mx = fmaxf(mx, x);
     }
     const bool bucket_rule = head_info[2 * rh] >= 0;
     int count = totA;
@@ -448,6 +457,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
                 const int pos = totA + exA[e] + min(exB[e], ties);
                 ids[pos] = idv[e];
                 ss[pos] = v[e];
+                mx = fmaxf(mx, v[e]);
             }
         }
         count = dsc.k;
@@ -456,8 +466,10 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
             const int s = find_seg(preC, e);
             const int np_s = min(dsc.n_pages, (s + 1) * dsc.seg_pages) - s * dsc.seg_pages;
             const size_t src = (size_t)s * seg_region + (size_t)np_s * kPageTokens - 1 - (size_t)(e - preC[s]);
+            const float x = ls[src];
             ids[totA + e] = li[src];
-            ss[totA + e] = ls[src];
+            ss[totA + e] = x;
+            mx = fmaxf(mx, x); // the candidates dropped below are the smallest ones
         }
         __syncthreads(); // candidates visible to the whole workgroup
         const uint32_t b1 = (uint32_t)head_info[2 * rh];
@@ -521,8 +533,16 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
         count = dsc.k;
     }
 
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    if (lane == 0) wred[tid >> 6] = mx;
     __syncthreads(); // list complete and visible to the whole workgroup
     if (tid == 0) {
+        if (mode == 0) { // top-k: the largest score overall is the largest selected one
+            float M = wred[0];
+            for (int w = 1; w < kSelWaves; ++w) M = fmaxf(M, wred[w]);
+            head_M[rh] = M;
+        }
         counts[rh] = count;
         if (out_counts) out_counts[rh] = count;
         if (out_ids && (int64_t)count > ids_stride) atomicOr(status, 1);
@@ -553,7 +573,8 @@ hipError_t launch_select(const Shape &sh, const DeviceViews &dv, int B, int mode
     if (e != hipSuccess) return e;
     select_finish_kernel<<<dim3((unsigned)(B * sh.n_q_heads)), block, 0, st>>>(
         dv.desc, sh.n_q_heads, mode, dv.head_info, dv.seg_counts, dv.loc_scores, dv.loc_ids, dv.hist,
-        dv.head_maxkey, dv.sel_ids, dv.sel_scores, dv.counts, out_ids, out_counts, ids_stride, dv.status);
+        dv.head_maxkey, dv.sel_ids, dv.sel_scores, dv.counts, out_ids, out_counts, ids_stride, dv.status,
+        dv.head_M);
     return hipGetLastError();
 }
 
