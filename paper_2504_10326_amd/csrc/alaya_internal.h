@@ -12,6 +12,7 @@ constexpr int kSelectThreads = 1024;
 constexpr int kAttendThreads = 256;
 constexpr int kMaxSplits = 64;
 constexpr int kHistBins = 2048;      // top 11 bits of the order-preserving score image
+constexpr int kMaxSlots = 64;        // addresses one head's sample-pass maxima are spread over
 constexpr int kMaxSegs = 64;         // selection segments per head
 constexpr int kMaxSegPages = 2048;   // pages per selection segment
 
@@ -61,6 +62,7 @@ struct DeviceViews {
     // enters the sampled pages, the selection the survivors of the others.  Zero between calls.
     uint32_t *hist;            // [max_batch * n_q_heads][kHistBins]
     uint32_t *head_maxkey;     // [max_batch * n_q_heads]
+    uint32_t *sample_max;      // [max_batch * n_q_heads][kMaxSlots] maxima of the sample pass (DIPR); zero between calls
     uint32_t *tau;             // [max_batch * n_q_heads] lower bound of the selection threshold (ordered key)
     int32_t *seg_counts;       // [max_batch * n_q_heads][kMaxSegs][2]
     float *head_M;             // [max_batch * n_q_heads]: maximum score per head

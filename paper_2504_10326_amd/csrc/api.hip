@@ -59,7 +59,7 @@ bool cfg_ok(const alaya_cache_config *c)
 
 struct Layout {
     size_t page_table, desc, cand, loc_scores, loc_ids, sel_scores, sel_ids, page_cnt, hist,
-        head_maxkey, tau, seg_counts, head_M, head_info, counts, partials, status, total;
+        head_maxkey, sample_max, tau, seg_counts, head_M, head_info, counts, partials, status, total;
     int64_t mpps;        // max pages per sequence
     int64_t score_elems; // capacity of each per-token array
     int64_t max_tiles;   // full-attention tiles
@@ -85,6 +85,7 @@ Layout make_layout(const alaya_cache_config &c)
     L.page_cnt = take((size_t)L.max_pages * c.n_q_heads * sizeof(int32_t));
     L.hist = take((size_t)c.max_batch * c.n_q_heads * kHistBins * sizeof(uint32_t));
     L.head_maxkey = take((size_t)c.max_batch * c.n_q_heads * sizeof(uint32_t));
+    L.sample_max = take((size_t)c.max_batch * c.n_q_heads * kMaxSlots * sizeof(uint32_t));
     L.tau = take((size_t)c.max_batch * c.n_q_heads * sizeof(uint32_t));
     L.seg_counts = take((size_t)c.max_batch * c.n_q_heads * kMaxSegs * 2 * sizeof(int32_t));
     L.head_M = take((size_t)c.max_batch * c.n_q_heads * sizeof(float));
@@ -296,6 +297,7 @@ int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k
     c->dv.page_cnt = (int32_t *)(c->ws + L.page_cnt);
     c->dv.hist = (uint32_t *)(c->ws + L.hist);
     c->dv.head_maxkey = (uint32_t *)(c->ws + L.head_maxkey);
+    c->dv.sample_max = (uint32_t *)(c->ws + L.sample_max);
     c->dv.tau = (uint32_t *)(c->ws + L.tau);
     c->dv.seg_counts = (int32_t *)(c->ws + L.seg_counts);
     c->dv.head_info = (int32_t *)(c->ws + L.head_info);
@@ -533,7 +535,8 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
     {
         Timed tm(c, 6, st);
         e = launch_score(sh, c->dv, B, q, tiles, 1, 0, p->mode, st);
-        if (e == hipSuccess && tiles_b > 0) e = launch_tau(sh, c->dv, B, p->mode, st);
+        // (DIPR: the bound kernel also gathers the sample pass's maxima, so it runs even with no main pass)
+        if (e == hipSuccess && (tiles_b > 0 || p->mode == ALAYA_DIPR)) e = launch_tau(sh, c->dv, B, p->mode, st);
     }
     if (e != hipSuccess) { c->dev_ready = false; return fail_hip(e, "sample scoring launch"); }
     if (tiles_b > 0) {

@@ -88,8 +88,9 @@ __device__ __forceinline__ int phase_page(int phase, int i, int S)
 }
 
 // PHASE 0 (sample pass): the workgroup also enters its scores into the head's statistics: for DIPR it
-// raises the running maximum, for top-k it counts them per bucket in LDS and adds the non-empty
-// buckets to the histogram.  The bound
+// raises one of the head's kMaxSlots sample maxima (many atomics on ONE address are slow: they are
+// carried out one after the other at the memory side), for top-k it counts them per bucket in LDS and
+// adds the non-empty buckets to the histogram.  The bound
 // kernel reads both right after this pass; the selection later adds only the survivors of the OTHER
 // pages to them.  Few workgroups run in phase 0 (a 1/S share of the pages), so these atomics are
 // cheap; the main pass (PHASE 1) has none.
@@ -100,7 +101,7 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
                                                      uint2 *__restrict__ cand, int32_t *__restrict__ page_cnt,
                                                      const uint32_t *__restrict__ tau_in,
                                                      uint32_t *__restrict__ hist,
-                                                     uint32_t *__restrict__ head_maxkey, int H_kv, int ppw, int mode)
+                                                     uint32_t *__restrict__ sample_max, int H_kv, int ppw, int mode)
 {
     constexpr int phase = PHASE;
     constexpr int NC = D * (DT == 0 ? 2 : 4) / 16; // 16-byte chunks per key
@@ -218,8 +219,7 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
                 for (int w = 1; w < kScoreWaves; ++w) m = fmaxf(m, wmax[w][threadIdx.x]);
                 if (m > -INFINITY) {
                     const uint32_t key = ord_key(m);
-                    uint32_t *dst = head_maxkey + rh0 + threadIdx.x;
-                    if (key > *dst) atomicMax(dst, key); // the plain read only skips atomics that cannot matter
+                    atomicMax(sample_max + (size_t)(rh0 + threadIdx.x) * kMaxSlots + (tile & (kMaxSlots - 1)), key);
                 }
             }
         }
@@ -245,11 +245,11 @@ static hipError_t launch_score_g(const Shape &sh, const DeviceViews &dv, int B, 
         if (phase == 0)                                                                                       \
             score_kernel<DT, D, GG, 0><<<grid, block, 0, st>>>(                                               \
                 dv.desc, B, dv.page_table, (const uint32_t *)q, (const uint4 *)dv.k_pool, dv.cand, dv.page_cnt, \
-                dv.tau, dv.hist, dv.head_maxkey, sh.n_kv_heads, ppw, mode);                          \
+                dv.tau, dv.hist, dv.sample_max, sh.n_kv_heads, ppw, mode);                          \
         else                                                                                                  \
             score_kernel<DT, D, GG, 1><<<grid, block, 0, st>>>(                                               \
                 dv.desc, B, dv.page_table, (const uint32_t *)q, (const uint4 *)dv.k_pool, dv.cand, dv.page_cnt, \
-                dv.tau, dv.hist, dv.head_maxkey, sh.n_kv_heads, ppw, mode);                          \
+                dv.tau, dv.hist, dv.sample_max, sh.n_kv_heads, ppw, mode);                          \
     } while (0)
     switch (G) {
     case 1: ALAYA_SCORE(1); break;
@@ -282,7 +282,8 @@ hipError_t launch_score(const Shape &sh, const DeviceViews &dv, int B, const voi
 // the histogram and the maximum hold the sampled pages only.
 __global__ __launch_bounds__(kSelectThreads) void tau_kernel(const ReqDesc *__restrict__ desc, int H_q, int mode,
                                                               const uint32_t *__restrict__ hist,
-                                                              const uint32_t *__restrict__ head_maxkey,
+                                                              uint32_t *__restrict__ sample_max,
+                                                              uint32_t *__restrict__ head_maxkey,
                                                               uint32_t *__restrict__ tau)
 {
     __shared__ int32_t wtot[kSelectThreads / 64];
@@ -293,9 +294,16 @@ __global__ __launch_bounds__(kSelectThreads) void tau_kernel(const ReqDesc *__re
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
     if (mode == 1) { // DIPR: (maximum over the sample) - beta
-        if (tid == 0) {
-            const uint32_t mk = head_maxkey[rh];
-            tau[rh] = mk ? ord_key(ord_float(mk) - dsc.beta) : 0u;
+        if (tid < 64) {
+            static_assert(kMaxSlots == 64, "one slot per lane");
+            uint32_t mk = sample_max[(size_t)rh * kMaxSlots + tid];
+            sample_max[(size_t)rh * kMaxSlots + tid] = 0u; // consumed: zero for the next call
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) mk = max(mk, (uint32_t)__shfl_xor((int)mk, o));
+            if (tid == 0) {
+                head_maxkey[rh] = mk; // the selection raises it further with the other pages' survivors
+                tau[rh] = mk ? ord_key(ord_float(mk) - dsc.beta) : 0u;
+            }
         }
         return;
     }
@@ -324,7 +332,7 @@ __global__ __launch_bounds__(kSelectThreads) void tau_kernel(const ReqDesc *__re
 hipError_t launch_tau(const Shape &sh, const DeviceViews &dv, int B, int mode, hipStream_t st)
 {
     tau_kernel<<<dim3((unsigned)(B * sh.n_q_heads)), dim3(kSelectThreads), 0, st>>>(
-        dv.desc, sh.n_q_heads, mode, dv.hist, dv.head_maxkey, dv.tau);
+        dv.desc, sh.n_q_heads, mode, dv.hist, dv.sample_max, dv.head_maxkey, dv.tau);
     return hipGetLastError();
 }
 
