@@ -264,18 +264,22 @@ class Cache:
                                 device=self.device)
 
     def sparse_attn(self, seqs: Sequence[int], q, mode: int, topk=None, beta=None, scale: float = 0.0,
-                    ids_stride: int = 0, out=None, stream=None):
-        """Returns out [B][Hq][d] fp32, or (out, ids [B][Hq][ids_stride] int32, counts [B][Hq] int32)."""
+                    ids_stride: int = 0, out=None, stream=None, want_counts: bool = False):
+        """Returns out [B][Hq][d] fp32, or (out, ids [B][Hq][ids_stride] int32, counts [B][Hq] int32) when
+        ids_stride > 0, or (out, counts) when only want_counts is set."""
         if out is None:
             out = self._q_out(seqs, q)
         ids = counts = None
         if ids_stride > 0:
             ids = self.torch.full((len(seqs), self.cfg.n_q_heads, ids_stride), -1, dtype=self.torch.int32,
                                   device=self.device)
+        if ids_stride > 0 or want_counts:
             counts = self.torch.zeros((len(seqs), self.cfg.n_q_heads), dtype=self.torch.int32, device=self.device)
         alaya_sparse_attn(self.handle, seqs, self.cfg.n_q_heads, q, mode, topk, beta, scale, out, ids, counts,
                           ids_stride, _stream(stream))
-        return out if ids is None else (out, ids, counts)
+        if ids is not None:
+            return out, ids, counts
+        return (out, counts) if want_counts else out
 
     def full_attn(self, seqs: Sequence[int], q, scale: float = 0.0, out=None, stream=None):
         if out is None:
