@@ -171,9 +171,8 @@ int alaya_set_tuning(alaya_cache *c, int score_pages_per_wave, int attend_splits
 /* Inspection hook for tests: DEVICE pointer to the fp32 scores the last alaya_sparse_attn call left
  * in the workspace.  Meaningful only if that call ran with write_all_scores = 1.  Requests follow
  * each other, each block being n_q_heads * (n rounded up to a whole page + ALAYA_SCORE_PAD) pairs of
- * (fp32 score, int32 token id), of which the first n_pages * n_q_heads * 64 are laid out
- * [page][head][64]: the pair of token j sits in page j / 64 at position j % 64.  Valid until the next
- * call on the cache. */
+ * (fp32 score, int32 token id) laid out [head][that many pairs]: the pair of token j of head h is
+ * pair j of row h.  Valid until the next call on the cache. */
 #define ALAYA_SCORE_PAD 1088
 const float *alaya_debug_scores(const alaya_cache *c);
 

@@ -309,9 +309,10 @@ class Cache:
         views = []
         for n in lens:
             pages = (n + 63) // 64
-            blk = self.workspace[off:off + pages * hq * 64 * 8].view(torch.float32).view(pages, hq, 64, 2)
-            views.append(blk[..., 0].permute(1, 0, 2).reshape(hq, pages * 64)[:, :n])
-            off += hq * (pages * 64 + SCORE_PAD) * 8
+            stride = pages * 64 + SCORE_PAD
+            blk = self.workspace[off:off + hq * stride * 8].view(torch.float32).view(hq, stride, 2)
+            views.append(blk[:, :n, 0])
+            off += hq * stride * 8
         return views
 
     def debug_survivors(self, stream=None) -> int:

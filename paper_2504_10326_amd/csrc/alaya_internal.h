@@ -36,7 +36,7 @@ struct ReqDesc {
     int32_t seg_pages;     // pages per selection segment
     int32_t tileb_start;   // first phase-B scoring tile of this request (prefix sum)
     int32_t sample_stride; // S: phase A scores pages 0, S, 2S, ... in full; 1 = no pruning
-    int32_t reserved;
+    int32_t chunk_pages;   // pages one wavefront of the main pass covers: a power of two, at most S
 };
 static_assert(sizeof(ReqDesc) == 64, "ReqDesc layout");
 
@@ -47,10 +47,13 @@ struct DeviceViews {
     const int32_t *page_table; // [max_seqs][max_pages_per_seq]
     const void *k_pool;
     const void *v_pool;
-    // scoring output: the survivors of each page as (score bits, token id) pairs, [page][head][64]
-    // inside the request's block ...
+    // scoring output: survivors as (score bits, token id) pairs, [head][head_stride] inside the request's
+    // block with 64 slots per page; a list starts in the slot of its first page and may run on through
+    // the slots of the pages that the same wavefront scored after it ...
     uint2 *cand;
-    int32_t *page_cnt;         // ... and how many there are: [head][n_pages] per request, requests in order
+    // ... and the lists' lengths: [head][n_pages] per request, requests in order; a page inside another
+    // page's list has 0
+    int32_t *page_cnt;
     // selection, stage 1: per (head, segment) local lists, [head][head_stride] inside the block,
     // segment s at s * seg_pages * 64: definite tokens first, tie-bucket tokens behind them
     float *loc_scores;

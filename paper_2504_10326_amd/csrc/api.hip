@@ -486,6 +486,7 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
         // selection segments: seg_pages pages each, at most kMaxSegs per head
         int64_t per = seg_pages_want;
         if ((pages + per - 1) / per > kMaxSegs) per = (pages + kMaxSegs - 1) / kMaxSegs;
+        per = (per + kMaxPagesPerWave - 1) / kMaxPagesPerWave * kMaxPagesPerWave; // whole scoring chunks
         d.seg_pages = (int32_t)per;
         d.nseg = (int32_t)((pages + per - 1) / per);
         d.seg_start = segs;
@@ -503,9 +504,11 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
         d.sample_stride = S;
         const int n_a = (int)((pages + S - 1) / S);
         d.tileb_start = tiles_b;
-        d.reserved = 0;
+        int cp = 1; // pages per wavefront in the main pass: a power of two, at most min(ppw, S)
+        while (2 * cp <= ppw && 2 * cp <= S) cp *= 2;
+        d.chunk_pages = cp;
         tiles += (n_a + kScoreWaves - 1) / kScoreWaves;                                  // one page per wavefront
-        tiles_b += (int)((pages - n_a + (int64_t)kScoreWaves * ppw - 1) / ((int64_t)kScoreWaves * ppw));
+        if (S > 1) tiles_b += (int)((pages + (int64_t)kScoreWaves * cp - 1) / ((int64_t)kScoreWaves * cp));
         all_pages += (int)pages;
         pages_a += n_a;
         segs += d.nseg;
@@ -584,7 +587,7 @@ int alaya_full_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, c
         d.page_start = d.n_pages = d.seg_start = d.nseg = d.seg_pages = 0;
         d.tileb_start = 0;
         d.sample_stride = 1;
-        d.reserved = 0;
+        d.chunk_pages = 1;
         tiles += (int)((pages + ppt - 1) / ppt);
     }
     if (tiles > c->L.max_tiles) return fail(ALAYA_E_NOMEM, "partial-result workspace too small");

@@ -60,7 +60,7 @@ hipError_t launch_append(const Shape &sh, const int32_t *pt_row, void *k_pool, v
 // What is written.  Writing every fp32 score back costs far more than its 6 % share of the bytes (HBM
 // dislikes a write stream mixed into the read stream: a read-only scan of the same keys runs at
 // 6.3 TB/s, the same scan writing all scores at 5.3), and nearly all of those scores can never be
-// selected.  So a wavefront writes only the SURVIVORS of each page - (token id, score) pairs,
+// selected.  So a wavefront writes only the SURVIVORS of its pages - (score, token id) pairs,
 // compacted, ascending, plus their count - where a survivor is a score at or above `tau`, a lower
 // bound of the head's final selection threshold.  The bound comes from a sample, with no atomics and no feedback between
 // workgroups:
@@ -80,13 +80,6 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c)
                                            false);
 }
 
-// Page number (within its request) of the i-th page of a phase, for sample stride S.
-// Phase A takes pages 0, S, 2S, ...; phase B the others, in order.
-__device__ __forceinline__ int phase_page(int phase, int i, int S)
-{
-    return phase == 0 ? i * S : i + i / (S - 1) + 1;
-}
-
 // PHASE 0 (sample pass): the workgroup also enters its scores into the head's statistics: for DIPR it
 // raises one of the head's kMaxSlots sample maxima (many atomics on ONE address are slow: they are
 // carried out one after the other at the memory side), for top-k it counts them per bucket in LDS and
@@ -94,7 +87,8 @@ __device__ __forceinline__ int phase_page(int phase, int i, int S)
 // kernel reads both right after this pass; the selection later adds only the survivors of the OTHER
 // pages to them.  Few workgroups run in phase 0 (a 1/S share of the pages), so these atomics are
 // cheap; the main pass (PHASE 1) has none.
-template <int DT, int D, int G, int PHASE>
+// RING: a wavefront may cover several pages; their survivors are staged and leave as one list.
+template <int DT, int D, int G, int PHASE, bool RING>
 __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ desc, int B,
                                                      const int32_t *__restrict__ page_table,
                                                      const uint32_t *__restrict__ qw, const uint4 *__restrict__ k_pool,
@@ -129,13 +123,15 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int S = dsc.sample_stride;
-    const int n_a = (dsc.n_pages + S - 1) / S;                   // pages of phase A
-    const int n_mine = phase == 0 ? n_a : dsc.n_pages - n_a;     // pages of this phase
-    // a wavefront takes `ppw` consecutive pages of its phase
-    const int i_begin = ((tile - (phase == 0 ? dsc.tile_start : dsc.tileb_start)) * kScoreWaves + wave) * ppw;
-    const int i_end = min(i_begin + ppw, n_mine);
-    const bool idle = i_begin >= i_end;
-    if (PHASE == 1 && idle) return;                              // whole wavefront; the main pass has no barriers
+    // Phase 0: wavefront w of the request takes the sampled page w * S.  Phase 1: it takes the aligned
+    // chunk of `cp` consecutive pages [w * cp, (w + 1) * cp) without the sampled ones; cp is a power of
+    // two <= S, so a sampled page can only be the first page of a chunk.
+    const int w_req = (tile - (phase == 0 ? dsc.tile_start : dsc.tileb_start)) * kScoreWaves + wave;
+    const int cp = phase == 0 ? 1 : dsc.chunk_pages;
+    const int p_first = phase == 0 ? w_req * S : w_req * cp;
+    const int p_end = min(p_first + cp, dsc.n_pages);
+    const int p_begin = (phase == 1 && (p_first & (S - 1)) == 0) ? p_first + 1 : p_first;
+    if (PHASE == 1 && p_begin >= p_end) return;                  // whole wavefront; the main pass has no barriers
     const uint4 *qh = (const uint4 *)(qw + (size_t)rh0 * QW);    // wave-uniform address: scalar loads
 
     uint32_t tau[G];
@@ -147,8 +143,18 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
 #pragma unroll
     for (int g = 0; g < G; ++g) lmax[g] = -INFINITY;
 
-    for (int i = i_begin; i < i_end; ++i) {
-        const int p = phase_page(phase, i, S);
+    // The survivors of the wavefront's pages form ONE list per head.  It starts in the slot of the
+    // wavefront's first page and runs on through the slots of its other pages.  Small writes mixed
+    // into the read stream cost far more than their bytes, so with several pages per wavefront the
+    // survivors are staged in a ring of 64 entries per head held in registers (entry i in lane i) and
+    // leave as whole 512-byte blocks, plus one partial block when the wavefront is done.
+    uint32_t ring_s[G], ring_j[G]; // staged entries: score bits, token id
+    int pend[G], flushed[G];       // wave-uniform: entries staged / entries already written
+#pragma unroll
+    for (int g = 0; g < G; ++g) { ring_s[g] = 0u; ring_j[g] = 0u; pend[g] = 0; flushed[g] = 0; }
+    const size_t list0 = (size_t)dsc.score_off + (size_t)p_begin * kPageTokens; // + head * head_stride
+
+    for (int p = p_begin; p < p_end; ++p) {
         const int phys = page_table[dsc.pt_off + p];
         const uint4 *base = k_pool + ((size_t)phys * H_kv + kvh) * (size_t)(NC * 64) + lane;
         uint4 kc[NC];
@@ -186,13 +192,31 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
         for (int g = 0; g < G; ++g) {
             const bool keep = valid && ord_key(acc[g]) >= tau[g];
             const unsigned long long m = __ballot(keep);
-            if (keep) {
-                const size_t pos = (size_t)dsc.score_off + ((size_t)p * H_q + kvh * G + g) * kPageTokens +
-                                   (size_t)__popcll(m & lt_mask);
-                cand[pos] = make_uint2(__float_as_uint(acc[g]), (uint32_t)j); // one 8-byte store
+            const int c = __popcll(m);
+            if constexpr (!RING) { // one page per wavefront: its list goes straight out
+                if (keep)
+                    cand[list0 + (size_t)(kvh * G + g) * dsc.head_stride + __popcll(m & lt_mask)] =
+                        make_uint2(__float_as_uint(acc[g]), (uint32_t)j);
+                if (lane == g)
+                    page_cnt[(size_t)dsc.page_start * H_q + (size_t)(kvh * G + g) * dsc.n_pages + p] = c;
+            } else if (c) {
+                // Send the survivors, in lane order, to the ring positions pend .. pend + c - 1 (mod 64);
+                // the other lanes take the positions left over, so that the move is a permutation.
+                const int dst = keep ? pend[g] + __popcll(m & lt_mask) : pend[g] + c + __popcll(~m & lt_mask);
+                const uint32_t ts = (uint32_t)__builtin_amdgcn_ds_permute((dst & 63) << 2, (int)__float_as_uint(acc[g]));
+                const uint32_t tj = (uint32_t)__builtin_amdgcn_ds_permute((dst & 63) << 2, j);
+                const bool fresh = ((lane - pend[g]) & 63) < c; // this lane received a survivor
+                if (fresh && lane >= pend[g]) { ring_s[g] = ts; ring_j[g] = tj; }
+                if (pend[g] + c >= 64) { // the ring is full: one 512-byte block leaves
+                    cand[list0 + (size_t)(kvh * G + g) * dsc.head_stride + flushed[g] + lane] =
+                        make_uint2(ring_s[g], ring_j[g]);
+                    flushed[g] += 64;
+                    if (fresh && lane < pend[g]) { ring_s[g] = ts; ring_j[g] = tj; } // those that wrapped around
+                    pend[g] += c - 64;
+                } else {
+                    pend[g] += c;
+                }
             }
-            if (lane == g) // survivors of this page for head g
-                page_cnt[(size_t)dsc.page_start * H_q + (size_t)(kvh * G + g) * dsc.n_pages + p] = __popcll(m);
             if (PHASE == 0 && valid) {
                 lmax[g] = fmaxf(lmax[g], acc[g]);
                 if (sample_hist_on) {
@@ -201,6 +225,15 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
                 }
             }
         }
+    }
+    // the rest of each list; its length goes to the first page's count, zero to the other pages'
+#pragma unroll
+    for (int g = 0; RING && g < G; ++g) {
+        if (lane < pend[g])
+            cand[list0 + (size_t)(kvh * G + g) * dsc.head_stride + flushed[g] + lane] = make_uint2(ring_s[g], ring_j[g]);
+        if (lane < p_end - p_begin)
+            page_cnt[(size_t)dsc.page_start * H_q + (size_t)(kvh * G + g) * dsc.n_pages + p_begin + lane] =
+                lane == 0 ? flushed[g] + pend[g] : 0;
     }
     if (PHASE == 0) {
         // what the sample says about this head: bucket counts (top-k) or the maximum (DIPR)
@@ -240,16 +273,14 @@ static hipError_t launch_score_g(const Shape &sh, const DeviceViews &dv, int B, 
 {
     const int G = sh.n_q_heads / sh.n_kv_heads;
     const dim3 grid((unsigned)(total_tiles * sh.n_kv_heads)), block(256);
+#define ALAYA_SCORE_ARGS                                                                                       \
+    dv.desc, B, dv.page_table, (const uint32_t *)q, (const uint4 *)dv.k_pool, dv.cand, dv.page_cnt, dv.tau,   \
+        dv.hist, dv.sample_max, sh.n_kv_heads, ppw, mode
 #define ALAYA_SCORE(GG)                                                                                       \
     do {                                                                                                      \
-        if (phase == 0)                                                                                       \
-            score_kernel<DT, D, GG, 0><<<grid, block, 0, st>>>(                                               \
-                dv.desc, B, dv.page_table, (const uint32_t *)q, (const uint4 *)dv.k_pool, dv.cand, dv.page_cnt, \
-                dv.tau, dv.hist, dv.sample_max, sh.n_kv_heads, ppw, mode);                          \
-        else                                                                                                  \
-            score_kernel<DT, D, GG, 1><<<grid, block, 0, st>>>(                                               \
-                dv.desc, B, dv.page_table, (const uint32_t *)q, (const uint4 *)dv.k_pool, dv.cand, dv.page_cnt, \
-                dv.tau, dv.hist, dv.sample_max, sh.n_kv_heads, ppw, mode);                          \
+        if (phase == 0) score_kernel<DT, D, GG, 0, false><<<grid, block, 0, st>>>(ALAYA_SCORE_ARGS);          \
+        else if (ppw == 1) score_kernel<DT, D, GG, 1, false><<<grid, block, 0, st>>>(ALAYA_SCORE_ARGS);       \
+        else score_kernel<DT, D, GG, 1, true><<<grid, block, 0, st>>>(ALAYA_SCORE_ARGS);                      \
     } while (0)
     switch (G) {
     case 1: ALAYA_SCORE(1); break;
@@ -259,6 +290,7 @@ static hipError_t launch_score_g(const Shape &sh, const DeviceViews &dv, int B, 
     default: return hipErrorInvalidValue;
     }
 #undef ALAYA_SCORE
+#undef ALAYA_SCORE_ARGS
     return hipGetLastError();
 }
 

@@ -120,11 +120,13 @@ __device__ __forceinline__ SegId seg_of_block(const ReqDesc *desc, int B, int H_
     return {r, h, gs - desc[r].seg_start};
 }
 
-// The survivors of the pages [p_begin, p_end) of one head, addressed by a flat index.
+// The survivors of the pages [p_begin, p_end) of one head, addressed by a flat index.  A list may be
+// longer than its page's 64 slots (it then covers the slots of the pages behind it, whose own counts
+// are 0); no list crosses a segment boundary.
 struct SegView {
     int p_begin, np, total; // first page, pages, survivors
     size_t base;            // element offset of (page 0, this head) in the survivor arrays
-    size_t page_stride;     // elements between consecutive pages of this head (H_q * 64)
+    size_t page_stride;     // elements between the slots of consecutive pages
 };
 
 // Loads the pages' survivor counts (two pages per thread) ...
@@ -135,8 +137,8 @@ __device__ __forceinline__ SegView begin_segment(const ReqDesc &dsc, int H_q, in
     SegView v;
     v.p_begin = seg * dsc.seg_pages;
     v.np = min(dsc.n_pages, v.p_begin + dsc.seg_pages) - v.p_begin;
-    v.base = (size_t)dsc.score_off + (size_t)h * kPageTokens;
-    v.page_stride = (size_t)H_q * kPageTokens;
+    v.base = (size_t)dsc.score_off + (size_t)h * dsc.head_stride;
+    v.page_stride = kPageTokens;
     v.total = 0;
     const int32_t *cnt = page_cnt + (size_t)dsc.page_start * H_q + (size_t)h * dsc.n_pages + v.p_begin;
     const int i0 = 2 * tid, i1 = 2 * tid + 1;
