@@ -104,6 +104,24 @@ def test_dipr_beta_sweep():
     c.close()
 
 
+@pytest.mark.parametrize("ppw", [4, 16])
+def test_dense_survivor_lists_with_several_pages_per_wavefront(ppw):
+    """Wide margins keep a large share of every page's scores alive, so that the lists a wavefront
+    builds over its pages fill and wrap their staging ring at every fill level."""
+    w = wl.resized(wl.config("range_256k"), [40000 + 37])
+    g = wl.generate(w)
+    c = make_cache(w, g)
+    c.set_tuning(ppw, 0, 0)
+    fractions = []
+    for beta in (3.0, 6.0, 9.0, 14.0, float("inf")):
+        st = run_and_compare(c, w, g, A.ALAYA_DIPR, beta=[beta])
+        fractions.append(sum(st["counts"]) / (w.n_q_heads * w.lens[0]))
+    assert fractions == sorted(fractions) and fractions[-1] == 1.0
+    assert any(0.1 < f < 0.9 for f in fractions)          # the partly filled case really occurs
+    st = run_and_compare(c, w, g, A.ALAYA_TOPK, topk=[3000])
+    c.close()
+
+
 # ------------------------------------------------------------------------------------------ paging
 def test_permuted_pages_do_not_change_the_answer():
     """Physical page order is invisible: same ids, bit-identical output as with pages in order."""
