@@ -15,6 +15,7 @@ timed region.  Prints ONE JSON line:
               counted.  Duration = the kernel's average over a profiled repeat of the timed loop,
               taken with HIP events on the launch stream (events between kernels would lengthen the
               timed steps themselves).
+  cold_cache  per-kernel times of the same step when the last-level cache is flushed before it
   gather      the gather + attend kernel: one V row (256 B) per selected (head, token), same clock
   cpu_baseline  the CPU oracle on the same step, on this host's cores (a reported baseline only)
 """
@@ -42,6 +43,8 @@ def main() -> int:
                     choices=["llama8b_128k", "range_256k", "paged_1m", "batched_16"])
     ap.add_argument("--beta", type=float, default=2.0, help="DIPR margin for range_256k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cold-steps", type=int, default=40,
+                    help="extra steps with the last-level cache flushed before each (0 = skip)")
     ap.add_argument("--pages-per-wave", type=int, default=0)
     ap.add_argument("--attend-splits", type=int, default=0)
     ap.add_argument("--segment-pages", type=int, default=0)
@@ -70,7 +73,7 @@ def main() -> int:
     print(f"[bench] generated {w.name}: {w.total_tokens} tokens in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
 
     # Each step appends one token per request, so leave room for every step of both passes.
-    extra = 2 * (W + K_steps) + 8
+    extra = 2 * (W + K_steps) + args.cold_steps + 8
     n_phys = g["n_phys_pages"] + w.batch * ((extra + 63) // 64 + 1)
     order = g["page_order"]
     if len(order) < n_phys:
@@ -145,6 +148,27 @@ def main() -> int:
               "avg_us": attend_ms * 1e3, "achieved": gather_bytes / (attend_ms * 1e-3) / 1e9, "unit": "GB/s",
               "frac": gather_bytes / (attend_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
+    # The same steps with the last-level cache flushed before each one (a 1 GiB buffer is read, which
+    # leaves no dirty lines behind to be written back during the step):
+    # in a model with many layers every layer's keys arrive cold.  Only the per-kernel event times of
+    # this loop are used; its wall clock includes the flushes.
+    cold = None
+    if args.cold_steps > 0:
+        scratch = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+        c.set_profiling(True)
+        for _ in range(args.cold_steps):
+            scratch.sum()
+            step()
+        torch.cuda.synchronize()
+        ktc = c.kernel_times()
+        c.set_profiling(False)
+        del scratch
+        cold_ms = ktc["score"]["sum_ms"] / max(1, ktc["score"]["launches"])
+        cold_us = {k: round(v["sum_ms"] / v["launches"] * 1e3, 2) for k, v in ktc.items() if v["launches"]}
+        cold = {"steps": args.cold_steps, "kernels_us": cold_us, "step_kernel_sum_us": round(sum(cold_us.values()), 2),
+                "main_pass_achieved": bytes_per_launch / (cold_ms * 1e-3) / 1e9, "unit": "GB/s",
+                "main_pass_frac": bytes_per_launch / (cold_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
     # Dense attention over the same cache, for context (reads K and V once each).
     torch.cuda.synchronize()
     t = time.perf_counter()
@@ -179,8 +203,15 @@ def main() -> int:
             cpu_s = dt * int(res["threads"])
             if cpu_s >= 20.0 or dt >= 30.0:
                 break
+        # ... and once on a single thread, on the first KV head's group (the groups are independent, equal work)
+        G = w.n_q_heads // w.n_kv_heads
+        t1 = time.perf_counter()
+        oracle.sparse_attn(g["q"][0][:G], g["K"][0][:, :1], g["V"][0][:, :1],
+                           oracle.TOPK if w.mode == "topk" else oracle.DIPR,
+                           k=w.topk[0] if w.topk else 0, beta=args.beta, want_ids=False, threads=1)
+        dt1 = time.perf_counter() - t1
         cpu = {"value": w.n_q_heads * n * reps / dt, "unit": "keys/s", "cores": int(res["threads"]),
-               "kind": "oracle",
+               "kind": "oracle", "single_thread_value": G * n / dt1,
                "sample": f"{reps} full steps of request 0 ({n} tokens x {w.n_q_heads} heads each), "
                          f"{dt:.2f} s wall, about {cpu_s:.0f} s of CPU time"}
 
@@ -205,6 +236,7 @@ def main() -> int:
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "bytes_per_launch": bytes_per_launch, "avg_us": score_ms * 1e3},
         "gather": gather,
+        "cold_cache": cold,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))
