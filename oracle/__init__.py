@@ -49,7 +49,9 @@ def _load():
         lib.oracle_select_dipr.restype = i64
         lib.oracle_attend.argtypes = [vp, vp, i32, i32, i32, i32, vp, i64, f64, vp]
         lib.oracle_attend.restype = None
-        lib.oracle_sparse_attn.argtypes = [vp, vp, vp, i32, i64, i32, i32, i32, i32, i64, f64, f64,
+        lib.oracle_select_window.argtypes = [vp, i64, i64, i64, i32, i64, f64, vp]
+        lib.oracle_select_window.restype = i64
+        lib.oracle_sparse_attn.argtypes = [vp, vp, vp, i32, i64, i32, i32, i32, i32, i64, f64, f64, i64, i64,
                                            vp, vp, i64, vp, vp, i32]
         lib.oracle_sparse_attn.restype = i32
         _lib = lib
@@ -100,6 +102,16 @@ def select_dipr(s: np.ndarray, beta: float) -> np.ndarray:
     return ids[:cnt].copy()
 
 
+def select_window(s: np.ndarray, w0: int, w1: int, mode: int, k: int = 0, beta: float = 0.0) -> np.ndarray:
+    """Window tokens (first w0, last w1) plus the query's result among / beside them: ascending ids."""
+    s = _c(s.astype(np.float64, copy=False))
+    ids = np.empty(max(1, s.size), dtype=np.int32)
+    cnt = _load().oracle_select_window(_p(s), s.size, int(w0), int(w1), int(mode), int(k), float(beta), _p(ids))
+    if cnt < 0:
+        raise ValueError("invalid k, beta or window")
+    return ids[:cnt].copy()
+
+
 def attend(s: np.ndarray, V: np.ndarray, g: int, ids: np.ndarray, scale: Optional[float] = None) -> np.ndarray:
     """Softmax over the given token set and the weighted sum of its V rows: fp64 [d]."""
     s, V = _c(s.astype(np.float64, copy=False)), _c(V)
@@ -116,12 +128,19 @@ def attend(s: np.ndarray, V: np.ndarray, g: int, ids: np.ndarray, scale: Optiona
 
 def sparse_attn(q: np.ndarray, K: np.ndarray, V: np.ndarray, mode: int, k: int = 0, beta: float = 0.0,
                 scale: Optional[float] = None, want_ids: bool = True, want_scores: bool = False,
-                threads: int = 0) -> dict:
+                threads: int = 0, window: Tuple[int, int] = (0, 0), n_visible: Optional[int] = None) -> dict:
     """One request, all heads.  q [n_q_heads][d]; K, V [n][n_kv_heads][d].
+
+    window = (first, last) tokens that are always attended; n_visible: only that prefix of K, V exists
+    for the query (it is cut off here, the C code never sees the rest).
 
     Returns {"out": fp64 [Hq][d], "counts": int64 [Hq], "ids": list of int32 arrays (ascending),
              "scores": fp64 [Hq][n] or None, "threads": OpenMP threads used}.
     """
+    if n_visible is not None:
+        if not 0 < n_visible <= K.shape[0]:
+            raise ValueError("n_visible out of range")
+        K, V = K[:n_visible], V[:n_visible]
     q, K, V = _c(q), _c(K), _c(V)
     n, hk, d = K.shape
     hq = q.shape[0]
@@ -132,11 +151,11 @@ def sparse_attn(q: np.ndarray, K: np.ndarray, V: np.ndarray, mode: int, k: int =
     ids = np.empty((hq, stride), dtype=np.int32) if want_ids else None
     sc = np.empty((hq, n), dtype=np.float64) if want_scores else None
     rc = _load().oracle_sparse_attn(_p(q), _p(K), _p(V), _dt(K), n, hq, hk, d, int(mode), int(k),
-                                    float(beta), float(scale) if scale else 0.0,
+                                    float(beta), float(scale) if scale else 0.0, int(window[0]), int(window[1]),
                                     _p(out), _p(ids), stride, _p(counts), _p(sc), int(threads))
     if rc < 0:
         raise ValueError({-1: "bad shapes or n == 0", -2: "k must be positive",
-                          -3: "beta must be >= 0"}.get(rc, f"oracle error {rc}"))
+                          -3: "beta must be >= 0", -4: "window sizes must be >= 0"}.get(rc, f"oracle error {rc}"))
     id_list = [ids[h, :counts[h]].copy() for h in range(hq)] if want_ids else None
     return {"out": out, "counts": counts, "ids": id_list, "scores": sc, "threads": rc}
 

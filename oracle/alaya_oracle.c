@@ -14,6 +14,12 @@
  *            o = sum_j a_j v_{g,j}                    (Eq. 1 restricted to the critical tokens,
  *                                                      Sec. 2 "Sparse Attention")
  *   full     the same with every token selected       (Eq. 1)
+ *   window   (Sec. 7.1 "Window Caching Enhanced DIPR"; Table 3 counts "[initial + last] + retrieved"
+ *            tokens) the first w0 and the last w1 tokens are always attended; top-k retrieves its k
+ *            tokens among the others; DIPR keeps the others that are within beta of the maximum over
+ *            ALL tokens, the window's included
+ *   prefix   (Sec. 7.1 "Flexible Context Reuse") only the first n_visible tokens exist for the query:
+ *            the caller hands over that prefix of K and V, nothing else changes
  *
  * All arithmetic is fp64.  Inputs are the stored bytes (bf16 or fp32), widened
  * exactly.  K and V are token-major: element (j, g, c) sits at (j*n_kv_heads + g)*d + c.
@@ -103,6 +109,48 @@ int64_t oracle_select_dipr(const double *s, int64_t n, double beta, int32_t *ids
     return cnt;
 }
 
+/* Query with a window of always-attended tokens W = {j < w0} U {j >= n - w1}.
+ *   top-k: W plus the min(k, n - |W|) best tokens outside W (equal scores: smaller j first);
+ *   DIPR : W plus every token outside W with s_j >= max over all n tokens - beta.
+ * ids ascending.  Returns the count, or -1 on an invalid k / beta / window. */
+int64_t oracle_select_window(const double *s, int64_t n, int64_t w0, int64_t w1, int mode, int64_t k,
+                             double beta, int32_t *ids)
+{
+    if (w0 < 0 || w1 < 0) return -1;
+    if (mode == ORACLE_TOPK && k <= 0) return -1;
+    if (mode == ORACLE_DIPR && !(beta >= 0.0)) return -1;
+    if (n <= 0) return 0;
+    char *inwin = (char *)malloc((size_t)n);
+    int64_t n_out = 0;
+    for (int64_t j = 0; j < n; ++j) {
+        inwin[j] = (j < w0 || j >= n - w1) ? 1 : 0;
+        n_out += !inwin[j];
+    }
+    char *take = (char *)calloc((size_t)n, 1);
+    if (mode == ORACLE_TOPK) {
+        int32_t *order = (int32_t *)malloc((size_t)(n_out > 0 ? n_out : 1) * sizeof *order);
+        int64_t m = 0;
+        for (int64_t j = 0; j < n; ++j)
+            if (!inwin[j]) order[m++] = (int32_t)j;
+        qsort_r(order, (size_t)n_out, sizeof *order, by_score_desc_then_id, (void *)s);
+        int64_t kk = k < n_out ? k : n_out;
+        for (int64_t i = 0; i < kk; ++i) take[order[i]] = 1;
+        free(order);
+    } else {
+        double m = s[0];
+        for (int64_t j = 1; j < n; ++j)
+            if (s[j] > m) m = s[j];
+        for (int64_t j = 0; j < n; ++j)
+            if (!inwin[j] && s[j] >= m - beta) take[j] = 1;
+    }
+    int64_t cnt = 0;
+    for (int64_t j = 0; j < n; ++j)
+        if (inwin[j] || take[j]) ids[cnt++] = (int32_t)j;
+    free(take);
+    free(inwin);
+    return cnt;
+}
+
 /* Softmax over the selected set and the weighted sum of its value rows. */
 void oracle_attend(const double *s, const void *V, int dtype, int n_kv_heads, int g, int d,
                    const int32_t *ids, int64_t cnt, double scale, double *o)
@@ -130,6 +178,7 @@ void oracle_attend(const double *s, const void *V, int dtype, int n_kv_heads, in
  *   q        [n_q_heads][d]          storage dtype
  *   K, V     [n][n_kv_heads][d]      storage dtype
  *   mode     ORACLE_TOPK (uses k), ORACLE_DIPR (uses beta), ORACLE_FULL
+ *   w0, w1   window of always-attended first / last tokens (0, 0 = none)
  *   scale    softmax scale; <= 0 means 1/sqrt(d)
  *   out      [n_q_heads][d] fp64
  *   ids      optional [n_q_heads][ids_stride] ascending token ids (first min(count, stride))
@@ -140,10 +189,11 @@ void oracle_attend(const double *s, const void *V, int dtype, int n_kv_heads, in
  */
 int oracle_sparse_attn(const void *q, const void *K, const void *V, int dtype, int64_t n,
                        int n_q_heads, int n_kv_heads, int d, int mode, int64_t k, double beta,
-                       double scale, double *out, int32_t *ids, int64_t ids_stride,
+                       double scale, int64_t w0, int64_t w1, double *out, int32_t *ids, int64_t ids_stride,
                        int64_t *counts, double *scores, int n_threads)
 {
     if (n <= 0 || n_q_heads <= 0 || n_kv_heads <= 0 || d <= 0 || n_q_heads % n_kv_heads) return -1;
+    if (w0 < 0 || w1 < 0) return -4;
     if (mode == ORACLE_TOPK && k <= 0) return -2;
     if (mode == ORACLE_DIPR && !(beta >= 0.0)) return -3;
     if (!(scale > 0.0)) scale = 1.0 / sqrt((double)d);
@@ -162,7 +212,9 @@ int oracle_sparse_attn(const void *q, const void *K, const void *V, int dtype, i
         int32_t *sel = (int32_t *)malloc((size_t)n * sizeof(int32_t));
         oracle_scores((const char *)q + (size_t)h * (size_t)d * esz, K, dtype, n, n_kv_heads, g, d, s);
         int64_t cnt;
-        if (mode == ORACLE_TOPK) {
+        if (mode != ORACLE_FULL && (w0 > 0 || w1 > 0)) {
+            cnt = oracle_select_window(s, n, w0, w1, mode, k, beta, sel);
+        } else if (mode == ORACLE_TOPK) {
             cnt = oracle_select_topk(s, n, k, sel);
         } else if (mode == ORACLE_DIPR) {
             cnt = oracle_select_dipr(s, n, beta, sel);

@@ -312,3 +312,118 @@ def test_bf16_widening_is_exact():
     # round-to-nearest-even of the generator: 1 + 2^-8 is a tie and goes to the even mantissa (1.0)
     assert wl.to_bf16_bits(np.array([1.0 + 2.0 ** -8], dtype=np.float32))[0] == 0x3F80
     assert wl.to_bf16_bits(np.array([1.0 + 3 * 2.0 ** -8], dtype=np.float32))[0] == 0x3F82
+
+
+# ---------------------------------------------------------------- window and prefix (Sec. 7.1)
+def _merge_two(parts):
+    """Partial-attention merge (Sec. 6.2) of (m, l, o) triples computed from library routines."""
+    M = max(m for m, _, _ in parts)
+    num = sum(math.exp(m - M) * l * o for m, l, o in parts)
+    den = sum(math.exp(m - M) * l for m, l, _ in parts)
+    return num / den
+
+
+def _dense_part(s_h, V_g, ids, d):
+    """(max, sum of exponentials, normalised output) of one token set, numpy only."""
+    z = s_h[ids] / math.sqrt(d)
+    m = z.max()
+    e = np.exp(z - m)
+    return m, e.sum(), (e[:, None] * V_g[ids]).sum(axis=0) / e.sum()
+
+
+def test_window_closed_form_weights():
+    """Five tokens with softmax weights 1, 2, 4, 8, 16 (d = 4, q.k_j = 2 ln w_j).  Window = first 1 + last 1
+    (weights 1 and 16) is always attended; top-1 retrieves the best of the OTHERS (weight 8), so the
+    attended set is {0, 3, 4} with weights 1 : 8 : 16 (Table 3's "[initial + last] + retrieved")."""
+    w = np.array([1.0, 2.0, 4.0, 8.0, 16.0])
+    q = np.array([[1.0, 0.0, 0.0, 0.0]], dtype=np.float32)
+    K = np.zeros((5, 1, 4), dtype=np.float32)
+    K[:, 0, 0] = 2.0 * np.log(w)
+    V = np.arange(20, dtype=np.float32).reshape(5, 1, 4) - 7.0
+    r = oracle.sparse_attn(q, K, V, oracle.TOPK, k=1, window=(1, 1))
+    assert list(r["ids"][0]) == [0, 3, 4]
+    np.testing.assert_allclose(r["out"][0], (1 * V[0, 0] + 8 * V[3, 0] + 16 * V[4, 0]) / 25.0, rtol=0, atol=1e-5)
+    # DIPR: the maximum is the window's last token (score 2 ln 16 = 5.545); beta = 1.5 reaches weight 8
+    # (score 4.159) but not weight 4 (2.773): the threshold uses the maximum over window AND the rest
+    r = oracle.sparse_attn(q, K, V, oracle.DIPR, beta=1.5, window=(1, 1))
+    assert list(r["ids"][0]) == [0, 3, 4]
+    # without the window's maximum the same beta would have kept weight 4 as well: max of the others is 4.159
+    r = oracle.sparse_attn(q, K[:4], V[:4], oracle.DIPR, beta=1.5)
+    assert list(r["ids"][0]) == [2, 3]
+    # a window that covers everything is full attention (Eq. 1)
+    r = oracle.sparse_attn(q, K, V, oracle.TOPK, k=1, window=(3, 2))
+    np.testing.assert_allclose(r["out"][0], (w[:, None] * V[:, 0]).sum(axis=0) / w.sum(), rtol=0, atol=1e-5)
+    r = oracle.sparse_attn(q, K, V, oracle.DIPR, beta=0.0, window=(9, 9))
+    assert list(r["ids"][0]) == [0, 1, 2, 3, 4]
+
+
+@pytest.mark.parametrize("seed,w0,w1,k", [(0, 5, 7, 6), (1, 0, 9, 3), (2, 11, 0, 200), (3, 1, 1, 1)])
+def test_window_topk_is_window_plus_topk_of_the_rest(seed, w0, w1, k):
+    """The retrieved tokens are the windowless top-k of the cache with the window rows removed, and the
+    output is the merge (Sec. 6.2) of the window's attention and the retrieved tokens' attention."""
+    w, q, K, V = _small(seed)
+    n, d, G = K.shape[0], K.shape[2], w.n_q_heads // w.n_kv_heads
+    s, _, _ = _dense(q, K, V, "f32")
+    win = np.r_[np.arange(w0), np.arange(n - w1, n)]
+    rest = np.arange(w0, n - w1)
+    r = oracle.sparse_attn(q, K, V, oracle.TOPK, k=k, window=(w0, w1))
+    sub = oracle.sparse_attn(q, K[rest], V[rest], oracle.TOPK, k=k)          # windowless, already pinned
+    for h in range(w.n_q_heads):
+        retrieved = rest[sub["ids"][h]]
+        assert list(r["ids"][h]) == sorted(np.r_[win, retrieved])
+        assert r["counts"][h] == len(win) + min(k, len(rest))
+        Vg = V[:, h // G].astype(np.float64)
+        parts = [_dense_part(s[h], Vg, ids, d) for ids in (win, retrieved) if len(ids)]
+        np.testing.assert_allclose(r["out"][h], _merge_two(parts), rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("seed,w0,w1,beta", [(0, 4, 4, 0.0), (1, 8, 16, 1.0), (2, 0, 3, 2.5), (3, 30, 0, 0.7)])
+def test_window_dipr_is_windowless_dipr_united_with_the_window(seed, w0, w1, beta):
+    """DIPR's threshold hangs on the maximum over ALL tokens (Sec. 7.1: the window's maximum is taken
+    into consideration), so the result is the windowless DIPR set united with the window."""
+    w, q, K, V = _small(seed)
+    n, d, G = K.shape[0], K.shape[2], w.n_q_heads // w.n_kv_heads
+    s, _, _ = _dense(q, K, V, "f32")
+    win = np.r_[np.arange(w0), np.arange(n - w1, n)].astype(np.int64)
+    r = oracle.sparse_attn(q, K, V, oracle.DIPR, beta=beta, window=(w0, w1))
+    plain = oracle.sparse_attn(q, K, V, oracle.DIPR, beta=beta)               # windowless, already pinned
+    for h in range(w.n_q_heads):
+        want = np.union1d(win, plain["ids"][h])
+        assert list(r["ids"][h]) == list(want)
+        m, l, o = _dense_part(s[h], V[:, h // G].astype(np.float64), want, d)
+        np.testing.assert_allclose(r["out"][h], o, rtol=0, atol=1e-12)
+
+
+def test_window_select_function_alone_and_its_errors():
+    s = np.array([0.5, 3.0, 1.0, 2.0, 2.0, 0.0, 9.0])
+    assert list(oracle.select_window(s, 1, 1, oracle.TOPK, k=2)) == [0, 1, 3, 6]        # tie 2.0 / 2.0: smaller id
+    assert list(oracle.select_window(s, 1, 1, oracle.TOPK, k=99)) == [0, 1, 2, 3, 4, 5, 6]
+    assert list(oracle.select_window(s, 0, 0, oracle.TOPK, k=2)) == [1, 6]              # no window: plain top-k
+    assert list(oracle.select_window(s, 2, 0, oracle.DIPR, beta=7.0)) == [0, 1, 3, 4, 6]  # 9 - 7 = 2, inclusive
+    assert list(oracle.select_window(s, 0, 1, oracle.DIPR, beta=0.0)) == [6]
+    with pytest.raises(ValueError):
+        oracle.select_window(s, -1, 0, oracle.TOPK, k=1)
+    with pytest.raises(ValueError):
+        oracle.select_window(s, 0, 0, oracle.TOPK, k=0)
+    with pytest.raises(ValueError):
+        oracle.select_window(s, 0, 0, oracle.DIPR, beta=-1.0)
+
+
+@pytest.mark.parametrize("mode,kw", [(oracle.TOPK, dict(k=7)), (oracle.DIPR, dict(beta=1.5)),
+                                     (oracle.TOPK, dict(k=7, window=(3, 5)))])
+def test_prefix_sees_nothing_behind_it(mode, kw):
+    """Flexible context reuse (Sec. 7.1): a query on the first m tokens is the query on a cache that
+    holds only those tokens, whatever lies behind them; 'last' window tokens are the prefix's last."""
+    w, q, K, V = _small(5)
+    m = 41
+    ref = oracle.sparse_attn(q, K[:m].copy(), V[:m].copy(), mode, **kw)
+    K2, V2 = K.copy(), V.copy()
+    K2[m:], V2[m:] = np.nan, np.nan                                            # poison what must not be read
+    r = oracle.sparse_attn(q, K2, V2, mode, n_visible=m, **kw)
+    assert all(list(a) == list(b) for a, b in zip(r["ids"], ref["ids"]))
+    assert np.array_equal(r["out"], ref["out"]) and np.isfinite(r["out"]).all()
+    full = oracle.sparse_attn(q, K, V, mode, n_visible=K.shape[0], **kw)
+    plain = oracle.sparse_attn(q, K, V, mode, **kw)
+    assert np.array_equal(full["out"], plain["out"])
+    with pytest.raises(ValueError):
+        oracle.sparse_attn(q, K, V, mode, n_visible=0, **kw)
