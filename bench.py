@@ -42,6 +42,8 @@ def main() -> int:
     ap.add_argument("--workload", default="llama8b_128k",
                     choices=["llama8b_128k", "range_256k", "paged_1m", "batched_16"])
     ap.add_argument("--beta", type=float, default=2.0, help="DIPR margin for range_256k")
+    ap.add_argument("--window", default="0,0",
+                    help="INIT,LAST tokens that are always attended (the paper's tables use 128,512)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cold-steps", type=int, default=40,
                     help="extra steps with the last-level cache flushed before each (0 = skip)")
@@ -94,10 +96,11 @@ def main() -> int:
     new_v = [dev(g["V"][r][w.lens[r] - 1:]) for r in range(w.batch)]
     seqs = list(range(w.batch))
     out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    window = tuple(int(x) for x in args.window.split(","))
     if w.mode == "topk":
-        mode, kw = A.ALAYA_TOPK, dict(topk=list(w.topk))
+        mode, kw = A.ALAYA_TOPK, dict(topk=list(w.topk), window=window)
     else:
-        mode, kw = A.ALAYA_DIPR, dict(beta=[args.beta] * w.batch)
+        mode, kw = A.ALAYA_DIPR, dict(beta=[args.beta] * w.batch, window=window)
     c.set_tuning(args.pages_per_wave, args.attend_splits, args.segment_pages, args.write_all_scores)
     torch.cuda.synchronize()
 
@@ -197,7 +200,7 @@ def main() -> int:
         while True:
             res = oracle.sparse_attn(g["q"][0], g["K"][0], g["V"][0],
                                      oracle.TOPK if w.mode == "topk" else oracle.DIPR,
-                                     k=w.topk[0] if w.topk else 0, beta=args.beta, want_ids=False)
+                                     k=w.topk[0] if w.topk else 0, beta=args.beta, want_ids=False, window=window)
             reps += 1
             dt = time.perf_counter() - t0
             cpu_s = dt * int(res["threads"])
@@ -208,7 +211,7 @@ def main() -> int:
         t1 = time.perf_counter()
         oracle.sparse_attn(g["q"][0][:G], g["K"][0][:, :1], g["V"][0][:, :1],
                            oracle.TOPK if w.mode == "topk" else oracle.DIPR,
-                           k=w.topk[0] if w.topk else 0, beta=args.beta, want_ids=False, threads=1)
+                           k=w.topk[0] if w.topk else 0, beta=args.beta, want_ids=False, threads=1, window=window)
         dt1 = time.perf_counter() - t1
         cpu = {"value": w.n_q_heads * n * reps / dt, "unit": "keys/s", "cores": int(res["threads"]),
                "kind": "oracle", "single_thread_value": G * n / dt1,
@@ -225,7 +228,7 @@ def main() -> int:
                    "batch": w.batch, "tokens": total_n, "mode": w.mode,
                    "topk": list(w.topk) if w.topk else None, "beta": args.beta if w.mode == "dipr" else None,
                    "paged": "64-token pages" + (", randomly permuted" if w.permute_pages else ""),
-                   "accumulate": "fp32"},
+                   "accumulate": "fp32", "window": list(window)},
         "latency_us_per_layer": ms_per_step * 1e3,
         "k_rows_per_s": rows / secs,
         "kernels_us": kernels_us,

@@ -113,14 +113,16 @@ int alaya_reset_seq(alaya_cache *c, int seq);
 
 typedef struct {
     int32_t mode;          /* alaya_mode                                                        */
-    int32_t reserved;      /* 0                                                                 */
+    int32_t window_init;   /* >= 0: the first window_init visible tokens are always attended    */
     const int32_t *topk;   /* HOST [B], ALAYA_TOPK: per-request k > 0 (k > n means all n)       */
     const float *beta;     /* HOST [B], ALAYA_DIPR: per-request beta >= 0, +inf allowed         */
     float scale;           /* softmax scale; 0 means 1 / sqrt(head_dim)                         */
-    int32_t reserved2;     /* 0                                                                 */
+    int32_t window_last;   /* >= 0: the last window_last visible tokens are always attended     */
     int32_t *out_ids;      /* DEVICE, optional [B][n_q_heads][ids_stride]: selected token ids   */
     int32_t *out_counts;   /* DEVICE, optional [B][n_q_heads]: TRUE size of each selected set   */
     int64_t ids_stride;    /* capacity per head of out_ids                                      */
+    const int32_t *n_visible; /* HOST [B], optional: request b sees only its first n_visible[b]
+                                 cached tokens (1 .. cached length); NULL = all of them         */
 } alaya_sparse_params;
 
 /*
@@ -128,6 +130,13 @@ typedef struct {
  * cached keys, select (top-k or DIPR), and attend over the selected tokens.
  *   seqs  HOST [B], distinct or repeated sequence ids      q    DEVICE [B][n_q_heads][head_dim], cache dtype
  *   out   DEVICE [B][n_q_heads][head_dim], fp32
+ * Window (Sec. 7.1 "Window Caching Enhanced DIPR"; Table 3 counts "[initial + last] + retrieved"
+ * tokens): with window_init / window_last set, those tokens are always in the selected set; top-k
+ * retrieves its k tokens among the OTHER tokens (k more than there are means all of them); DIPR keeps
+ * the others that are within beta of the maximum over all visible tokens, the window's included.
+ * out_ids / out_counts cover window and retrieved tokens alike.
+ * Prefix (Sec. 7.1 "Flexible Context Reuse"): with n_visible set, the query runs as if the sequence
+ * ended after n_visible[b] tokens; "last" window tokens are then the last visible ones.
  * Selection runs on raw fp32 inner products (bf16 products are exact in fp32; accumulation is fp32).
  * Among equal scores at the k-th place the smaller token id is taken, so results are reproducible.
  * out_ids come back in an unspecified but deterministic order.  If a set is larger than ids_stride

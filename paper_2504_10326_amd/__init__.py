@@ -52,10 +52,11 @@ class CacheConfig(ctypes.Structure):
 
 class SparseParams(ctypes.Structure):
     _fields_ = [
-        ("mode", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("mode", ctypes.c_int32), ("window_init", ctypes.c_int32),
         ("topk", ctypes.POINTER(ctypes.c_int32)), ("beta", ctypes.POINTER(ctypes.c_float)),
-        ("scale", ctypes.c_float), ("reserved2", ctypes.c_int32),
+        ("scale", ctypes.c_float), ("window_last", ctypes.c_int32),
         ("out_ids", ctypes.c_void_p), ("out_counts", ctypes.c_void_p), ("ids_stride", ctypes.c_int64),
+        ("n_visible", ctypes.POINTER(ctypes.c_int32)),
     ]
 
 
@@ -179,9 +180,13 @@ def alaya_reset_seq(handle: int, seq: int) -> None:
 
 def alaya_sparse_attn(handle: int, seqs: Sequence[int], n_q_heads: int, q, mode: int,
                       topk: Optional[Sequence[int]], beta: Optional[Sequence[float]], scale: float, out,
-                      out_ids=None, out_counts=None, ids_stride: int = 0, stream=0) -> None:
+                      out_ids=None, out_counts=None, ids_stride: int = 0, stream=0,
+                      window: Tuple[int, int] = (0, 0), n_visible: Optional[Sequence[int]] = None) -> None:
     p = SparseParams()
     p.mode = mode
+    p.window_init, p.window_last = int(window[0]), int(window[1])
+    nv = _i32_array(n_visible)
+    p.n_visible = ctypes.cast(nv, ctypes.POINTER(ctypes.c_int32)) if nv is not None else None
     tk, bt = _i32_array(topk), _f32_array(beta)
     p.topk = ctypes.cast(tk, ctypes.POINTER(ctypes.c_int32)) if tk is not None else None
     p.beta = ctypes.cast(bt, ctypes.POINTER(ctypes.c_float)) if bt is not None else None
@@ -264,9 +269,11 @@ class Cache:
                                 device=self.device)
 
     def sparse_attn(self, seqs: Sequence[int], q, mode: int, topk=None, beta=None, scale: float = 0.0,
-                    ids_stride: int = 0, out=None, stream=None, want_counts: bool = False):
+                    ids_stride: int = 0, out=None, stream=None, want_counts: bool = False,
+                    window: Tuple[int, int] = (0, 0), n_visible: Optional[Sequence[int]] = None):
         """Returns out [B][Hq][d] fp32, or (out, ids [B][Hq][ids_stride] int32, counts [B][Hq] int32) when
-        ids_stride > 0, or (out, counts) when only want_counts is set."""
+        ids_stride > 0, or (out, counts) when only want_counts is set.  window = (first, last) tokens
+        that are always attended; n_visible[b] = the prefix of request b that the query sees."""
         if out is None:
             out = self._q_out(seqs, q)
         ids = counts = None
@@ -276,7 +283,7 @@ class Cache:
         if ids_stride > 0 or want_counts:
             counts = self.torch.zeros((len(seqs), self.cfg.n_q_heads), dtype=self.torch.int32, device=self.device)
         alaya_sparse_attn(self.handle, seqs, self.cfg.n_q_heads, q, mode, topk, beta, scale, out, ids, counts,
-                          ids_stride, _stream(stream))
+                          ids_stride, _stream(stream), window, n_visible)
         if ids is not None:
             return out, ids, counts
         return (out, counts) if want_counts else out

@@ -23,9 +23,9 @@ constexpr int kScorePad = 1088; // 17 * 256 bytes
 // Per-request descriptor, built on the host for every attention call and copied to the device.
 struct ReqDesc {
     int32_t pt_off;        // first entry of this sequence's row in the device page table
-    int32_t n;             // cached tokens
+    int32_t n;             // tokens the query sees (the cached ones, or a prefix of them)
     int32_t head_stride;   // elements between consecutive heads in the per-head arrays
-    int32_t k;             // top-k, already clamped to n (0 in DIPR mode)
+    int32_t k;             // top-k: tokens to retrieve outside the window, already clamped (0 in DIPR mode)
     float beta;            // DIPR margin (raw inner-product units)
     int32_t tile_start;    // first phase-A scoring tile / full-attention tile of this request (prefix sum)
     int64_t score_off;     // offset (elements) of this request's block in every per-token array
@@ -37,8 +37,14 @@ struct ReqDesc {
     int32_t tileb_start;   // first phase-B scoring tile of this request (prefix sum)
     int32_t sample_stride; // S: phase A scores pages 0, S, 2S, ... in full; 1 = no pruning
     int32_t chunk_pages;   // pages one wavefront of the main pass covers: a power of two, at most S
+    int32_t w0, w1;        // window: tokens j < w0 and j >= n - w1 are always selected
+    int32_t nwin;          // tokens in the window: min(n, w0 + w1)
+    int32_t reserved;
 };
-static_assert(sizeof(ReqDesc) == 64, "ReqDesc layout");
+static_assert(sizeof(ReqDesc) == 80, "ReqDesc layout");
+
+// A window token is always selected, and top-k neither counts nor ranks it.
+__device__ __forceinline__ bool in_window(const ReqDesc &d, int j) { return j < d.w0 || j >= d.n - d.w1; }
 
 // Device views handed to the launchers.  "per-token arrays" hold one element per (query head, token):
 // a request's block starts at score_off and spans n_q_heads * head_stride elements.

@@ -14,6 +14,8 @@
 
 using namespace alaya;
 
+static_assert(sizeof(alaya_cache_config) == 56 && sizeof(alaya_sparse_params) == 64, "C ABI struct layout");
+
 namespace {
 
 thread_local std::string g_err;
@@ -428,6 +430,13 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
             if (!(p->beta[b] >= 0.f)) return fail(ALAYA_E_INVAL, "request %d: beta must be >= 0", b);
     }
     if (p->out_ids && p->ids_stride <= 0) return fail(ALAYA_E_INVAL, "out_ids given with ids_stride <= 0");
+    if (p->window_init < 0 || p->window_last < 0)
+        return fail(ALAYA_E_INVAL, "window sizes %d + %d must be >= 0", p->window_init, p->window_last);
+    if (p->n_visible)
+        for (int b = 0; b < B; ++b)
+            if (p->n_visible[b] <= 0 || p->n_visible[b] > c->seq_len[(size_t)seqs[b]])
+                return fail(ALAYA_E_INVAL, "request %d: n_visible = %d outside 1..%lld", b, p->n_visible[b],
+                            (long long)c->seq_len[(size_t)seqs[b]]);
 
     hipStream_t st = (hipStream_t)stream;
     // pages per wavefront in the main scoring pass: aim at about 8192 workgroups
@@ -468,13 +477,19 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
     int64_t pages_a = 0;
     int64_t off = 0;
     for (int b = 0; b < B; ++b) {
-        const int64_t n = c->seq_len[(size_t)seqs[b]];
+        // the tokens this query sees: the whole sequence, or the prefix asked for
+        const int64_t n = p->n_visible ? (int64_t)p->n_visible[b] : c->seq_len[(size_t)seqs[b]];
         const int64_t pages = (n + kPageTokens - 1) / kPageTokens;
         ReqDesc &d = hd[b];
         d.pt_off = (int32_t)((int64_t)seqs[b] * c->L.mpps);
         d.n = (int32_t)n;
         d.head_stride = (int32_t)(pages * kPageTokens + kScorePad);
-        d.k = p->mode == ALAYA_TOPK ? (int32_t)((int64_t)p->topk[b] < n ? p->topk[b] : n) : 0;
+        d.w0 = (int32_t)((int64_t)p->window_init < n ? p->window_init : n);
+        d.w1 = (int32_t)((int64_t)p->window_last < n ? p->window_last : n);
+        d.nwin = (int32_t)((int64_t)d.w0 + d.w1 < n ? d.w0 + d.w1 : n);
+        d.reserved = 0;
+        const int64_t n_out = n - d.nwin; // tokens outside the window: what top-k ranks
+        d.k = p->mode == ALAYA_TOPK ? (int32_t)((int64_t)p->topk[b] < n_out ? p->topk[b] : n_out) : 0;
         d.beta = p->mode == ALAYA_DIPR ? p->beta[b] : 0.f;
         d.tile_start = tiles;
         d.score_off = off;
@@ -588,6 +603,7 @@ int alaya_full_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, c
         d.tileb_start = 0;
         d.sample_stride = 1;
         d.chunk_pages = 1;
+        d.w0 = d.w1 = d.nwin = d.reserved = 0;
         tiles += (int)((pages + ppt - 1) / ppt);
     }
     if (tiles > c->L.max_tiles) return fail(ALAYA_E_NOMEM, "partial-result workspace too small");

@@ -188,9 +188,10 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
         }
         const int j = p * kPageTokens + lane;
         const bool valid = j < dsc.n;
+        const bool win = in_window(dsc, j); // always a survivor; top-k's statistics leave it out
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const bool keep = valid && ord_key(acc[g]) >= tau[g];
+            const bool keep = valid && (win || ord_key(acc[g]) >= tau[g]);
             const unsigned long long m = __ballot(keep);
             const int c = __popcll(m);
             if constexpr (!RING) { // one page per wavefront: its list goes straight out
@@ -219,7 +220,7 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
             }
             if (PHASE == 0 && valid) {
                 lmax[g] = fmaxf(lmax[g], acc[g]);
-                if (sample_hist_on) {
+                if (sample_hist_on && !win) {
                     const uint32_t bin = ord_key(acc[g]) >> 21;
                     atomicAdd(&lhist[g][bin >> 1], 1u << ((bin & 1u) * 16u));
                 }

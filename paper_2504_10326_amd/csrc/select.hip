@@ -185,14 +185,15 @@ struct Rule {
     int topk;     // 1: bucket rule, 0: threshold rule
     uint32_t b1;  // bucket of the k-th score
     float thr;    // threshold rule: definite iff score >= thr
-    __device__ __forceinline__ void classify(float v, bool in, bool &definite, bool &candidate) const
+    // win: the token is in the window (always selected; top-k neither counts nor ranks it)
+    __device__ __forceinline__ void classify(float v, bool in, bool win, bool &definite, bool &candidate) const
     {
         if (topk) {
             const uint32_t bin = ord_key(v) >> 21;
-            definite = in && bin > b1;
-            candidate = in && bin == b1;
+            definite = in && (win || bin > b1);
+            candidate = in && !win && bin == b1;
         } else {
-            definite = in && v >= thr;
+            definite = in && (win || v >= thr);
             candidate = false;
         }
     }
@@ -215,7 +216,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_stats_kernel(
     // The sampled pages entered the histogram and the maximum when they were scored.
     const int S = dsc.sample_stride;
     if (S == 1) return; // whole workgroup: every page was a sampled page
-    const bool want_hist = mode == 0 && dsc.k < dsc.n;
+    const bool want_hist = mode == 0 && dsc.k < dsc.n - dsc.nwin;
     if (want_hist)
         for (int i = tid; i < kHistBins; i += kSelectThreads) lh[i] = 0u;
     int a0, a1;
@@ -227,15 +228,19 @@ __global__ __launch_bounds__(kSelectThreads) void select_stats_kernel(
     constexpr int U = 4; // independent loads per thread and step
     for (int t0 = tid; t0 < v.total; t0 += U * kSelectThreads) {
         float s[U];
+        bool ranked[U]; // a survivor outside the window: top-k's histogram counts only those
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int t = t0 + u * kSelectThreads;
-            s[u] = t < v.total ? __uint_as_float(cand[flat_to_offset(v, off, t)].x) : -INFINITY;
+            const bool in = t < v.total;
+            const uint2 pr = in ? cand[flat_to_offset(v, off, t)] : make_uint2(0u, 0u);
+            s[u] = in ? __uint_as_float(pr.x) : -INFINITY;
+            ranked[u] = in && !in_window(dsc, (int)pr.y);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            m = fmaxf(m, s[u]);
-            if (want_hist && s[u] > -INFINITY) atomicAdd(&lh[ord_key(s[u]) >> 21], 1u);
+            m = fmaxf(m, s[u]); // DIPR's maximum runs over the window's tokens too
+            if (want_hist && ranked[u]) atomicAdd(&lh[ord_key(s[u]) >> 21], 1u);
         }
     }
 #pragma unroll
@@ -275,7 +280,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_local_kernel(
     int a0, a1;
     SegView v = begin_segment(dsc, H_q, id.h, id.seg, page_cnt, a0, a1);
     const float M = ord_float(head_maxkey[rh]);
-    const bool bucket_rule = mode == 0 && dsc.k < dsc.n;
+    const bool bucket_rule = mode == 0 && dsc.k < dsc.n - dsc.nwin;
     if (bucket_rule) {
         for (int i = tid; i < kHistBins; i += kSelectThreads) lh[i] = hist[(size_t)rh * kHistBins + i];
         __syncthreads();
@@ -312,7 +317,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_local_kernel(
             const uint2 pr = in ? cand[o] : make_uint2(0u, 0u);
             sv[e] = __uint_as_float(pr.x);
             tok[e] = (int)pr.y;
-            rule.classify(sv[e], in, fa[e], fc[e]);
+            rule.classify(sv[e], in, in_window(dsc, tok[e]), fa[e], fc[e]);
         }
         int exA[kSelE], exC[kSelE], totA, totC;
         chunk_ranks(scan, parity, fa, fc, exA, exC, totA, totC);
@@ -405,7 +410,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
         // They are gathered once, refined from registers, and only the kept ones are written.
         const uint32_t b1 = (uint32_t)head_info[2 * rh];
         const int cb = totC;
-        int need = dsc.k - totA; // 1 <= need <= cb
+        int need = dsc.k + dsc.nwin - totA; // 1 <= need <= cb (totA counts the window's tokens too)
         float v[kSelE];
         int idv[kSelE];
         uint32_t key[kSelE];
@@ -462,7 +467,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
                 mx = fmaxf(mx, v[e]);
             }
         }
-        count = dsc.k;
+        count = dsc.k + dsc.nwin;
     } else if (bucket_rule) {
         for (int e = tid; e < totC; e += kSelectThreads) {
             const int s = find_seg(preC, e);
@@ -477,7 +482,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
         const uint32_t b1 = (uint32_t)head_info[2 * rh];
         const int above1 = totA; // == head_info[2 * rh + 1]: every token above bucket b1
         const int cb = totC;
-        int need = dsc.k - above1; // 1 <= need <= cb
+        int need = dsc.k + dsc.nwin - above1; // 1 <= need <= cb (above1 counts the window's tokens too)
         int parity = 0;
         if (need < cb) {
             // refine over the candidates: key bits [20:10], then bits [9:0]
@@ -532,7 +537,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
                 baseT += tB;
             }
         }
-        count = dsc.k;
+        count = dsc.k + dsc.nwin;
     }
 
 #pragma unroll

@@ -55,19 +55,24 @@ def make_cache(w: wl.Workload, g: dict, extra_tokens: int = 0, max_batch=None, c
 
 
 def compare_sparse(w, g, out, ids, counts, mode, topk=None, beta=None, scale=None, requests=None, heads=None,
-                   scores_gpu=None, threads=0):
+                   scores_gpu=None, threads=0, window=(0, 0), n_visible=None):
     """Compare one sparse call with the oracle. Returns a dict of summary numbers; asserts on failure."""
     out = out.cpu().numpy()
     ids = ids.cpu().numpy()
     counts = counts.cpu().numpy()
     stats = {"band_heads": 0, "max_out_err": 0.0, "max_score_err": 0.0, "counts": []}
     for r in (requests if requests is not None else range(w.batch)):
-        n = w.lens[r]
+        n = w.lens[r] if n_visible is None else int(n_visible[r])
         K, V, q = g["K"][r], g["V"][r], g["q"][r]
         k = int(topk[r]) if mode == A.ALAYA_TOPK else 0
         b = float(beta[r]) if mode == A.ALAYA_DIPR else 0.0
         orc = oracle.sparse_attn(q, K, V, oracle.TOPK if mode == A.ALAYA_TOPK else oracle.DIPR, k=k, beta=b,
-                                 scale=scale, want_scores=True, threads=threads)
+                                 scale=scale, want_scores=True, threads=threads, window=window, n_visible=n)
+        K, V = K[:n], V[:n]
+        w0, w1 = min(window[0], n), min(window[1], n)
+        outside = np.ones(n, dtype=bool)                       # tokens that the query ranks
+        outside[:w0] = False
+        outside[n - w1:] = False
         sg = scores_gpu[r].cpu().numpy() if scores_gpu is not None else None
         for h in (heads if heads is not None else range(w.n_q_heads)):
             s = orc["scores"][h]
@@ -82,12 +87,15 @@ def compare_sparse(w, g, out, ids, counts, mode, topk=None, beta=None, scale=Non
                 f"request {r} head {h}: ids not distinct or out of range"
             ora_ids = orc["ids"][h]
             if mode == A.ALAYA_TOPK:
-                assert cnt == min(k, n), f"request {r} head {h}: count {cnt} != min(k, n)"
-                boundary = s[ora_ids].min()
+                want = (n - int(outside.sum())) + min(k, int(outside.sum()))
+                assert cnt == want, f"request {r} head {h}: count {cnt} != window + min(k, rest) = {want}"
+                retrieved = ora_ids[outside[ora_ids]]
+                boundary = s[retrieved].min() if retrieved.size else np.inf
             else:
                 boundary = s.max() - b
             diff = np.setxor1d(gpu_ids, ora_ids)
             if diff.size:
+                assert outside[diff].all(), f"request {r} head {h}: a window token is missing or extra"
                 off = np.abs(s[diff] - boundary)
                 assert off.max() <= BAND, (f"request {r} head {h}: {diff.size} ids differ, farthest "
                                            f"{off.max():.3e} from the boundary (> {BAND})")
@@ -103,12 +111,14 @@ def compare_sparse(w, g, out, ids, counts, mode, topk=None, beta=None, scale=Non
 
 
 def run_and_compare(c: A.Cache, w, g, mode, topk=None, beta=None, scale=None, ids_stride=None, check_scores=True,
-                    threads=0):
+                    threads=0, window=(0, 0), n_visible=None):
     q = to_device(g["q"], w.dtype)
     seqs = list(range(w.batch))
     if ids_stride is None:
-        ids_stride = max(w.lens) if mode == A.ALAYA_DIPR else max(min(k, n) for k, n in zip(topk, w.lens))
-    out, ids, counts = c.sparse_attn(seqs, q, mode, topk=topk, beta=beta, scale=scale or 0.0, ids_stride=ids_stride)
+        ids_stride = max(w.lens) if mode == A.ALAYA_DIPR else \
+            max(min(k + window[0] + window[1], n) for k, n in zip(topk, w.lens))
+    out, ids, counts = c.sparse_attn(seqs, q, mode, topk=topk, beta=beta, scale=scale or 0.0, ids_stride=ids_stride,
+                                     window=window, n_visible=n_visible)
     torch.cuda.synchronize()
     assert c.poll_status() == A.ALAYA_OK
     sg = None
@@ -117,10 +127,11 @@ def run_and_compare(c: A.Cache, w, g, mode, topk=None, beta=None, scale=None, id
         # pruned run above must have produced bit-identical ids, counts and outputs.
         c.set_write_all_scores(True)
         out2, ids2, counts2 = c.sparse_attn(seqs, q, mode, topk=topk, beta=beta, scale=scale or 0.0,
-                                            ids_stride=ids_stride)
+                                            ids_stride=ids_stride, window=window, n_visible=n_visible)
         torch.cuda.synchronize()
-        sg = [s.clone() for s in c.debug_scores(w.lens)]
+        sg = [s.clone() for s in c.debug_scores(w.lens if n_visible is None else n_visible)]
         c.set_write_all_scores(False)
         assert torch.equal(counts, counts2) and torch.equal(ids, ids2), "pruned and unpruned selections differ"
         assert torch.equal(out, out2), "pruned and unpruned outputs differ"
-    return compare_sparse(w, g, out, ids, counts, mode, topk, beta, scale, scores_gpu=sg, threads=threads)
+    return compare_sparse(w, g, out, ids, counts, mode, topk, beta, scale, scores_gpu=sg, threads=threads,
+                          window=window, n_visible=n_visible)

@@ -36,6 +36,17 @@ def test_llama8b_128k_topk2048():
     st = run_and_compare(c, w, g, A.ALAYA_TOPK, topk=w.topk)
     _say(f"llama8b_128k: out err {st['max_out_err']:.2e}, score err {st['max_score_err']:.2e}, "
          f"heads with band ids {st['band_heads']}")
+    # the paper's own settings (Table 3): a window of [128 + 512] tokens plus 2000 / 100 retrieved ones,
+    # and the window-enhanced DIPR query; then the same on a 100000-token prefix of the context
+    for k in (2000, 100):
+        st = run_and_compare(c, w, g, A.ALAYA_TOPK, topk=[k], window=(128, 512), check_scores=False)
+        assert set(st["counts"]) == {640 + k}
+        _say(f"llama8b_128k [128+512]+{k}: out err {st['max_out_err']:.2e}, band heads {st['band_heads']}")
+    st = run_and_compare(c, w, g, A.ALAYA_DIPR, beta=[2.0], window=(128, 512), check_scores=False)
+    _say(f"llama8b_128k [128+512] DIPR beta=2: selected {min(st['counts'])}..{max(st['counts'])}, "
+         f"out err {st['max_out_err']:.2e}")
+    st = run_and_compare(c, w, g, A.ALAYA_TOPK, topk=[2000], window=(128, 512), n_visible=[100000], check_scores=False)
+    _say(f"llama8b_128k prefix 100000, [128+512]+2000: out err {st['max_out_err']:.2e}, band heads {st['band_heads']}")
     c.close()
 
 

@@ -122,6 +122,53 @@ def test_dense_survivor_lists_with_several_pages_per_wavefront(ppw):
     c.close()
 
 
+# ------------------------------------------------------------------------------------------ window, prefix
+@pytest.mark.parametrize("n,w0,w1", [(9000, 128, 512), (5000, 0, 70), (4100, 3, 0), (700, 400, 400), (64 * 30, 64, 64)])
+def test_window_tokens_are_always_attended(n, w0, w1):
+    """Sec. 7.1 window caching: [initial + last] tokens plus the retrieved ones (Table 3); top-k ranks only
+    the tokens outside the window, DIPR's threshold hangs on the maximum over all tokens."""
+    w = _llama([n], topk=[100])
+    g = wl.generate(w)
+    c = make_cache(w, g)
+    nwin = min(n, w0 + w1)
+    for k in (1, 100, 10 ** 6):
+        st = run_and_compare(c, w, g, A.ALAYA_TOPK, topk=[k], window=(w0, w1), ids_stride=n)
+        assert set(st["counts"]) == {nwin + min(k, n - nwin)}
+    for beta in (0.0, 1.5, 6.0):
+        st = run_and_compare(c, w, g, A.ALAYA_DIPR, beta=[beta], window=(w0, w1), ids_stride=n)
+        assert min(st["counts"]) >= nwin
+    c.close()
+
+
+def test_prefix_queries_ignore_what_lies_behind_the_prefix():
+    """Sec. 7.1 flexible context reuse: the query sees only the first n_visible tokens of each request."""
+    w = _llama([6000, 3000, 4500], topk=[64, 64, 64])
+    g = wl.generate(w)
+    c = make_cache(w, g)
+    vis = [4097, 1, 4500]
+    run_and_compare(c, w, g, A.ALAYA_TOPK, topk=[64, 64, 64], n_visible=vis, ids_stride=4500)
+    run_and_compare(c, w, g, A.ALAYA_DIPR, beta=[1.0, 1.0, 3.0], n_visible=vis, ids_stride=4500)
+    run_and_compare(c, w, g, A.ALAYA_TOPK, topk=[64, 64, 64], n_visible=vis, window=(16, 100), ids_stride=4500)
+    # the same answer, bit for bit, from a cache that never held the rest
+    q = to_device(g["q"], w.dtype)
+    out_a, ids_a, cnt_a = c.sparse_attn([0, 1, 2], q, A.ALAYA_TOPK, topk=[64] * 3, n_visible=vis, ids_stride=64)
+    w2 = _llama(vis, topk=[64, 64, 64])
+    g2 = {**g, "K": [g["K"][r][:vis[r]] for r in range(3)], "V": [g["V"][r][:vis[r]] for r in range(3)]}
+    c2 = make_cache(w2, g2)
+    out_b, ids_b, cnt_b = c2.sparse_attn([0, 1, 2], q, A.ALAYA_TOPK, topk=[64] * 3, ids_stride=64)
+    torch.cuda.synchronize()
+    assert torch.equal(out_a, out_b) and torch.equal(ids_a, ids_b) and torch.equal(cnt_a, cnt_b)
+    for bad in ([0, 1, 1], [6001, 1, 1], [1, 1, -5]):
+        with pytest.raises(A.AlayaError) as e:
+            c.sparse_attn([0, 1, 2], q, A.ALAYA_TOPK, topk=[64] * 3, n_visible=bad)
+        assert e.value.code == A.ALAYA_E_INVAL
+    with pytest.raises(A.AlayaError) as e:
+        c.sparse_attn([0, 1, 2], q, A.ALAYA_TOPK, topk=[64] * 3, window=(-1, 0))
+    assert e.value.code == A.ALAYA_E_INVAL
+    c.close()
+    c2.close()
+
+
 # ------------------------------------------------------------------------------------------ paging
 def test_permuted_pages_do_not_change_the_answer():
     """Physical page order is invisible: same ids, bit-identical output as with pages in order."""
