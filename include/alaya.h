@@ -177,6 +177,13 @@ int alaya_kernel_times(alaya_cache *c, double *sum_ms, int64_t *launches, int n_
 int alaya_set_tuning(alaya_cache *c, int score_pages_per_wave, int attend_splits, int select_segment_pages,
                      int write_all_scores);
 
+/* Test hook for the estimated threshold bound of large top-k calls.  Such calls filter the main
+ * scoring pass with a bound that is only very likely to be low enough, check it afterwards against
+ * the number of tokens that survived, and repair the heads where it was not (results are exact
+ * either way).  mode 0: the library decides (default); 1: estimate whenever the shapes allow;
+ * 2: as 1, and with an estimate so high that every head needs the repair; -1: never estimate. */
+int alaya_debug_estimate(alaya_cache *c, int mode);
+
 /* Inspection hook for tests: DEVICE pointer to the fp32 scores the last alaya_sparse_attn call left
  * in the workspace.  Meaningful only if that call ran with write_all_scores = 1.  Requests follow
  * each other, each block being n_q_heads * (n rounded up to a whole page + ALAYA_SCORE_PAD) pairs of

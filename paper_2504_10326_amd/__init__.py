@@ -29,7 +29,7 @@ EXPORTS = (
     "alaya_pool_bytes", "alaya_workspace_bytes", "alaya_create_cache", "alaya_destroy_cache",
     "alaya_append_kv", "alaya_seq_len", "alaya_reset_seq", "alaya_sparse_attn", "alaya_full_attn",
     "alaya_poll_status", "alaya_set_profiling", "alaya_kernel_times", "alaya_set_tuning", "alaya_debug_scores",
-    "alaya_debug_survivors", "alaya_debug_pages",
+    "alaya_debug_survivors", "alaya_debug_pages", "alaya_debug_estimate",
     "alaya_last_error",
 )
 
@@ -95,6 +95,7 @@ def lib() -> ctypes.CDLL:
         L.alaya_debug_survivors.argtypes = [vp, vp]; L.alaya_debug_survivors.restype = i64
         L.alaya_debug_pages.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64)]
         L.alaya_debug_pages.restype = i32
+        L.alaya_debug_estimate.argtypes = [vp, i32]; L.alaya_debug_estimate.restype = i32
         L.alaya_last_error.argtypes = []; L.alaya_last_error.restype = ctypes.c_char_p
         _lib = L
     return _lib
@@ -331,6 +332,10 @@ class Cache:
         a, b = ctypes.c_int64(0), ctypes.c_int64(0)
         _check(lib().alaya_debug_pages(self.handle, ctypes.byref(a), ctypes.byref(b)))
         return a.value, b.value
+
+    def debug_estimate(self, mode: int) -> None:
+        """0: library decides, 1: estimated bound whenever possible, 2: estimate that always needs repair, -1: never."""
+        _check(lib().alaya_debug_estimate(self.handle, mode))
 
     def set_tuning(self, score_pages_per_wave: int = 0, attend_splits: int = 0,
                    select_segment_pages: int = 0, write_all_scores: bool = False) -> None:

@@ -12,6 +12,7 @@ constexpr int kSelectThreads = 1024;
 constexpr int kAttendThreads = 256;
 constexpr int kMaxSplits = 64;
 constexpr int kHistBins = 2048;      // top 11 bits of the order-preserving score image
+constexpr int kRepairGrid = 2048;    // workgroups of the (normally idle) repair scoring pass
 constexpr int kMaxSlots = 64;        // addresses one head's sample-pass maxima are spread over
 constexpr int kMaxSegs = 64;         // selection segments per head
 constexpr int kMaxSegPages = 2048;   // pages per selection segment
@@ -39,7 +40,7 @@ struct ReqDesc {
     int32_t chunk_pages;   // pages one wavefront of the main pass covers: a power of two, at most S
     int32_t w0, w1;        // window: tokens j < w0 and j >= n - w1 are always selected
     int32_t nwin;          // tokens in the window: min(n, w0 + w1)
-    int32_t reserved;
+    int32_t k_est;         // top-k: rank in the sample that the ESTIMATED bound is read at; 0 = guaranteed bound only
 };
 static_assert(sizeof(ReqDesc) == 80, "ReqDesc layout");
 
@@ -72,7 +73,10 @@ struct DeviceViews {
     uint32_t *hist;            // [max_batch * n_q_heads][kHistBins]
     uint32_t *head_maxkey;     // [max_batch * n_q_heads]
     uint32_t *sample_max;      // [max_batch * n_q_heads][kMaxSlots] maxima of the sample pass (DIPR); zero between calls
-    uint32_t *tau;             // [max_batch * n_q_heads] lower bound of the selection threshold (ordered key)
+    uint32_t *fail;            // [max_batch * n_q_heads] 1: the estimated bound lost tokens, repair this head; zero between calls
+    uint32_t *any_fail;        // one word: some head of the call is marked; zero between calls
+    uint32_t *tau;             // [max_batch * n_q_heads] the bound the main pass filters with (ordered key)
+    uint32_t *tau_safe;        // [max_batch * n_q_heads] the guaranteed lower bound of the selection threshold
     int32_t *seg_counts;       // [max_batch * n_q_heads][kMaxSegs][2]
     float *head_M;             // [max_batch * n_q_heads]: maximum score per head
     int32_t *head_info;        // [max_batch * n_q_heads][2]: bucket of the k-th score (-1: threshold rule), tokens above it
@@ -92,15 +96,20 @@ struct Shape {
 hipError_t launch_append(const Shape &sh, const int32_t *page_table_row, void *k_pool, void *v_pool,
                          const void *k, const void *v, int64_t n_old, int64_t t, hipStream_t st);
 
-// phase 0 scores the sampled pages in full, phase 1 the other pages against dv.tau.
+// phase 0 scores the sampled pages in full, phase 1 the other pages against dv.tau, phase 2 (repair)
+// the other pages of the heads marked in dv.fail against dv.tau_safe.
 hipError_t launch_score(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles,
                         int pages_per_wave, int phase, int mode, hipStream_t st);
 // mode: 0 top-k, 1 DIPR
 hipError_t launch_tau(const Shape &sh, const DeviceViews &dv, int B, int mode, hipStream_t st);
 
-// stats -> local -> finish; total_segs = sum over requests of nseg
-hipError_t launch_select(const Shape &sh, const DeviceViews &dv, int B, int mode, int total_segs,
-                         int32_t *out_ids, int32_t *out_counts, int64_t ids_stride, hipStream_t st);
+// Selection, total_segs = sum over requests of nseg.  front: stats -> local (which marks the heads whose
+// estimated bound lost tokens in dv.fail); back: local again for the marked heads if `redo` (the repair
+// scoring pass must have run in between), then finish.
+hipError_t launch_select_front(const Shape &sh, const DeviceViews &dv, int B, int mode, int total_segs,
+                               hipStream_t st);
+hipError_t launch_select_back(const Shape &sh, const DeviceViews &dv, int B, int mode, int total_segs, bool redo,
+                              int32_t *out_ids, int32_t *out_counts, int64_t ids_stride, hipStream_t st);
 
 hipError_t launch_attend(const Shape &sh, const DeviceViews &dv, int B, float scale, int splits,
                          hipStream_t st);

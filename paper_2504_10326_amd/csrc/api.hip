@@ -61,7 +61,7 @@ bool cfg_ok(const alaya_cache_config *c)
 
 struct Layout {
     size_t page_table, desc, cand, loc_scores, loc_ids, sel_scores, sel_ids, page_cnt, hist,
-        head_maxkey, sample_max, tau, seg_counts, head_M, head_info, counts, partials, status, total;
+        head_maxkey, sample_max, fail, tau, tau_safe, seg_counts, head_M, head_info, counts, partials, status, total;
     int64_t mpps;        // max pages per sequence
     int64_t score_elems; // capacity of each per-token array
     int64_t max_tiles;   // full-attention tiles
@@ -88,7 +88,9 @@ Layout make_layout(const alaya_cache_config &c)
     L.hist = take((size_t)c.max_batch * c.n_q_heads * kHistBins * sizeof(uint32_t));
     L.head_maxkey = take((size_t)c.max_batch * c.n_q_heads * sizeof(uint32_t));
     L.sample_max = take((size_t)c.max_batch * c.n_q_heads * kMaxSlots * sizeof(uint32_t));
+    L.fail = take(((size_t)c.max_batch * c.n_q_heads + 1) * sizeof(uint32_t)); // + the any-head word
     L.tau = take((size_t)c.max_batch * c.n_q_heads * sizeof(uint32_t));
+    L.tau_safe = take((size_t)c.max_batch * c.n_q_heads * sizeof(uint32_t));
     L.seg_counts = take((size_t)c.max_batch * c.n_q_heads * kMaxSegs * 2 * sizeof(int32_t));
     L.head_M = take((size_t)c.max_batch * c.n_q_heads * sizeof(float));
     L.head_info = take((size_t)c.max_batch * c.n_q_heads * 2 * sizeof(int32_t));
@@ -120,6 +122,7 @@ struct alaya_cache {
     int ring_pos;
     bool dev_ready;
     int tune_ppw, tune_splits, tune_seg, tune_noprune;
+    int estimate_mode; // alaya_debug_estimate
     int last_ppw; // pages per wavefront of the last sparse call (layout of the survivor lists)
     int last_pages, last_heads;
     int64_t last_pages_a, last_pages_b; // pages of the last sparse call scored by the sample / the main pass
@@ -300,7 +303,10 @@ int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k
     c->dv.hist = (uint32_t *)(c->ws + L.hist);
     c->dv.head_maxkey = (uint32_t *)(c->ws + L.head_maxkey);
     c->dv.sample_max = (uint32_t *)(c->ws + L.sample_max);
+    c->dv.fail = (uint32_t *)(c->ws + L.fail);
+    c->dv.any_fail = c->dv.fail + (size_t)cfg->max_batch * cfg->n_q_heads;
     c->dv.tau = (uint32_t *)(c->ws + L.tau);
+    c->dv.tau_safe = (uint32_t *)(c->ws + L.tau_safe);
     c->dv.seg_counts = (int32_t *)(c->ws + L.seg_counts);
     c->dv.head_info = (int32_t *)(c->ws + L.head_info);
     c->dv.head_M = (float *)(c->ws + L.head_M);
@@ -331,6 +337,7 @@ int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k
     c->tune_splits = 0;
     c->tune_seg = 0;
     c->tune_noprune = 0;
+    c->estimate_mode = 0;
     c->last_ppw = 0;
     c->last_pages = c->last_heads = 0;
     c->last_pages_a = c->last_pages_b = 0;
@@ -474,6 +481,10 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
     rc = ring_acquire(c, &hd, &slot);
     if (rc != ALAYA_OK) return rc;
     int tiles = 0, tiles_b = 0, segs = 0, all_pages = 0;
+    // Large top-k calls filter with an estimated bound and pay two (normally idle) repair launches for
+    // it; below about half a million tokens in the call the guaranteed bound is as fast.
+    const bool estimate = c->estimate_mode > 0 || (c->estimate_mode == 0 && total_pages >= 8192);
+    bool any_est = false;
     int64_t pages_a = 0;
     int64_t off = 0;
     for (int b = 0; b < B; ++b) {
@@ -487,7 +498,6 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
         d.w0 = (int32_t)((int64_t)p->window_init < n ? p->window_init : n);
         d.w1 = (int32_t)((int64_t)p->window_last < n ? p->window_last : n);
         d.nwin = (int32_t)((int64_t)d.w0 + d.w1 < n ? d.w0 + d.w1 : n);
-        d.reserved = 0;
         const int64_t n_out = n - d.nwin; // tokens outside the window: what top-k ranks
         d.k = p->mode == ALAYA_TOPK ? (int32_t)((int64_t)p->topk[b] < n_out ? p->topk[b] : n_out) : 0;
         d.beta = p->mode == ALAYA_DIPR ? p->beta[b] : 0.f;
@@ -508,13 +518,27 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
         // Sample stride S: phase A writes n / S scores, phase B about k * S survivors; their sum is
         // smallest at S = sqrt(n / k).  Powers of two, at most 32, and the sample must hold 2k tokens.
         int S = 1;
+        d.k_est = 0;
         if (!c->tune_noprune && pages >= 4) {
-            if (p->mode == ALAYA_TOPK) {
+            if (p->mode == ALAYA_TOPK && estimate && d.k >= 512 && pages >= 64) {
+                // Estimated bound (large calls): a 1-in-S sample holds about mu = k / S of the k best
+                // scores, so its (mu + 6 sqrt(mu) + 8)-th largest score lies below the true threshold
+                // unless the sample is far from representative - which the selection detects and
+                // repairs.  The main pass then writes about k (1 + 6 / sqrt(mu)) survivors whatever S
+                // is, so S only has to keep mu at 64 or more.
+                while (S < 32 && d.k / (2 * S) >= 64) S *= 2;
+                while (S > 1 && pages / S < 2) S /= 2;
+                const double mu = (double)d.k / S;
+                d.k_est = c->estimate_mode == 2 ? 1 : (int32_t)(mu + 6.0 * std::sqrt(mu) + 8.0);
+                if (d.k_est > d.k) d.k_est = d.k;
+                if (S > 1) any_est = true; else d.k_est = 0;
+            } else if (p->mode == ALAYA_TOPK) {
                 while (S < 32 && (int64_t)(2 * S) * (2 * S) * d.k <= n && (int64_t)2 * S * d.k * 2 <= n) S *= 2;
+                while (S > 1 && pages / S < 2) S /= 2;
             } else {
                 S = 16;
+                while (S > 1 && pages / S < 2) S /= 2;
             }
-            while (S > 1 && pages / S < 2) S /= 2;
         }
         d.sample_stride = S;
         const int n_a = (int)((pages + S - 1) / S);
@@ -562,7 +586,14 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
         e = launch_score(sh, c->dv, B, q, tiles_b, ppw, 1, p->mode, st);
     }
     if (e != hipSuccess) { c->dev_ready = false; return fail_hip(e, "score launch"); }
-    { Timed tm(c, 1, st); e = launch_select(sh, c->dv, B, p->mode, segs, p->out_ids, p->out_counts, p->ids_stride, st); }
+    {
+        Timed tm(c, 1, st);
+        e = launch_select_front(sh, c->dv, B, p->mode, segs, st);
+        // repair of the heads whose estimated bound lost tokens (normally none: both launches are idle)
+        if (e == hipSuccess && any_est) e = launch_score(sh, c->dv, B, q, tiles_b, ppw, 2, p->mode, st);
+        if (e == hipSuccess)
+            e = launch_select_back(sh, c->dv, B, p->mode, segs, any_est, p->out_ids, p->out_counts, p->ids_stride, st);
+    }
     if (e != hipSuccess) { c->dev_ready = false; return fail_hip(e, "select launch"); }
     { Timed tm(c, 2, st); e = launch_attend(sh, c->dv, B, scale, splits, st); }
     if (e != hipSuccess) return fail_hip(e, "attend launch");
@@ -603,7 +634,7 @@ int alaya_full_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, c
         d.tileb_start = 0;
         d.sample_stride = 1;
         d.chunk_pages = 1;
-        d.w0 = d.w1 = d.nwin = d.reserved = 0;
+        d.w0 = d.w1 = d.nwin = d.k_est = 0;
         tiles += (int)((pages + ppt - 1) / ppt);
     }
     if (tiles > c->L.max_tiles) return fail(ALAYA_E_NOMEM, "partial-result workspace too small");
@@ -670,6 +701,14 @@ const float *alaya_debug_scores(const alaya_cache *c)
 {
     if (!c) { fail(ALAYA_E_INVAL, "null cache handle"); return nullptr; }
     return (const float *)c->dv.cand;
+}
+
+int alaya_debug_estimate(alaya_cache *c, int mode)
+{
+    if (!c) return fail(ALAYA_E_INVAL, "null cache handle");
+    if (mode < -1 || mode > 2) return fail(ALAYA_E_INVAL, "estimate mode %d outside -1..2", mode);
+    c->estimate_mode = mode;
+    return ALAYA_OK;
 }
 
 int alaya_debug_pages(const alaya_cache *c, int64_t *sampled, int64_t *main_pass)

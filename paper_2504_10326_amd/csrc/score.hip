@@ -68,6 +68,8 @@ hipError_t launch_append(const Shape &sh, const int32_t *pt_row, void *k_pool, v
 //   tau      (tau_kernel) top-k: the k-th largest score of a SUBSET is never above the k-th largest of
 //            the whole, so the lower edge of the histogram bucket holding the sample's k-th largest
 //            score is a valid tau; DIPR: tau = (sample max) - beta <= (true max) - beta;
+//            (large top-k calls filter with a tighter ESTIMATE instead, which the selection verifies:
+//            see tau_kernel and PHASE 2 below)
 //   phase B  scores the remaining pages against tau.
 // tau never exceeds the final threshold, so nothing that can be selected is ever dropped: the
 // selection that follows is exact.  It is also deterministic - the survivor lists depend on the
@@ -87,17 +89,23 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c)
 // kernel reads both right after this pass; the selection later adds only the survivors of the OTHER
 // pages to them.  Few workgroups run in phase 0 (a 1/S share of the pages), so these atomics are
 // cheap; the main pass (PHASE 1) has none.
+// PHASE 2 (repair pass): as the main pass, but only for the heads marked in `fail` - those whose
+// estimated bound turned out to lie above the true threshold - and against the guaranteed bound; it
+// rewrites those heads' lists and adds the scores between the two bounds to their histograms.  It
+// runs after every call that used an estimated bound and normally finds nothing to do.
 // RING: a wavefront may cover several pages; their survivors are staged and leave as one list.
+// `block` = tile * H_kv + KV head: what one 256-thread workgroup scores.
 template <int DT, int D, int G, int PHASE, bool RING>
-__global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ desc, int B,
-                                                     const int32_t *__restrict__ page_table,
-                                                     const uint32_t *__restrict__ qw, const uint4 *__restrict__ k_pool,
-                                                     uint2 *__restrict__ cand, int32_t *__restrict__ page_cnt,
-                                                     const uint32_t *__restrict__ tau_in,
-                                                     uint32_t *__restrict__ hist,
-                                                     uint32_t *__restrict__ sample_max, int H_kv, int ppw, int mode)
+__device__ __forceinline__ void score_block(const int block, const ReqDesc *__restrict__ desc, int B,
+                                            const int32_t *__restrict__ page_table,
+                                            const uint32_t *__restrict__ qw, const uint4 *__restrict__ k_pool,
+                                            uint2 *__restrict__ cand, int32_t *__restrict__ page_cnt,
+                                            const uint32_t *__restrict__ tau_in,
+                                            const uint32_t *__restrict__ tau_safe,
+                                            const uint32_t *__restrict__ fail, uint32_t *__restrict__ hist,
+                                            uint32_t *__restrict__ sample_max, int H_kv, int ppw, int mode)
 {
-    constexpr int phase = PHASE;
+    constexpr int phase = PHASE == 0 ? 0 : 1; // page mapping: the repair pass walks the main pass's pages
     constexpr int NC = D * (DT == 0 ? 2 : 4) / 16; // 16-byte chunks per key
     constexpr int QW = D * (DT == 0 ? 2 : 4) / 4;  // 32-bit words per query head
     // two 16-bit counters per word: a phase-0 workgroup scores 4 pages = 256 tokens per head
@@ -111,8 +119,8 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
         __syncthreads();
     }
 
-    const int kvh = blockIdx.x % H_kv;
-    const int tile = blockIdx.x / H_kv;
+    const int kvh = block % H_kv;
+    const int tile = block / H_kv;
     int r = 0;
     if (phase == 0) while (r + 1 < B && desc[r + 1].tile_start <= tile) ++r;
     else while (r + 1 < B && desc[r + 1].tileb_start <= tile) ++r;
@@ -134,9 +142,17 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
     if (PHASE == 1 && p_begin >= p_end) return;                  // whole wavefront; the main pass has no barriers
     const uint4 *qh = (const uint4 *)(qw + (size_t)rh0 * QW);    // wave-uniform address: scalar loads
 
-    uint32_t tau[G];
+    uint32_t tau[G], tau_hi[G]; // keep key >= tau; repair pass: count tau <= key < tau_hi
+    bool act[G];                // repair pass: this head is being repaired
+    bool any_act = PHASE != 2;
 #pragma unroll
-    for (int g = 0; g < G; ++g) tau[g] = phase == 0 ? 0u : tau_in[rh0 + g];
+    for (int g = 0; g < G; ++g) {
+        act[g] = PHASE != 2 || fail[rh0 + g] != 0u;
+        any_act |= act[g];
+        tau[g] = PHASE == 0 ? 0u : PHASE == 1 ? tau_in[rh0 + g] : tau_safe[rh0 + g];
+        tau_hi[g] = PHASE == 2 ? tau_in[rh0 + g] : 0u;
+    }
+    if (PHASE == 2 && !any_act) return; // whole workgroup: the usual case
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
 
     float lmax[G];
@@ -191,14 +207,17 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
         const bool win = in_window(dsc, j); // always a survivor; top-k's statistics leave it out
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const bool keep = valid && (win || ord_key(acc[g]) >= tau[g]);
+            const uint32_t key = ord_key(acc[g]);
+            const bool keep = act[g] && valid && (win || key >= tau[g]);
+            if (PHASE == 2 && keep && !win && key < tau_hi[g]) // a score the estimated bound had dropped
+                atomicAdd(&hist[(size_t)(rh0 + g) * kHistBins + (key >> 21)], 1u);
             const unsigned long long m = __ballot(keep);
             const int c = __popcll(m);
             if constexpr (!RING) { // one page per wavefront: its list goes straight out
                 if (keep)
                     cand[list0 + (size_t)(kvh * G + g) * dsc.head_stride + __popcll(m & lt_mask)] =
                         make_uint2(__float_as_uint(acc[g]), (uint32_t)j);
-                if (lane == g)
+                if (lane == g && act[g])
                     page_cnt[(size_t)dsc.page_start * H_q + (size_t)(kvh * G + g) * dsc.n_pages + p] = c;
             } else if (c) {
                 // Send the survivors, in lane order, to the ring positions pend .. pend + c - 1 (mod 64);
@@ -221,7 +240,7 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
             if (PHASE == 0 && valid) {
                 lmax[g] = fmaxf(lmax[g], acc[g]);
                 if (sample_hist_on && !win) {
-                    const uint32_t bin = ord_key(acc[g]) >> 21;
+                    const uint32_t bin = key >> 21;
                     atomicAdd(&lhist[g][bin >> 1], 1u << ((bin & 1u) * 16u));
                 }
             }
@@ -230,6 +249,7 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
     // the rest of each list; its length goes to the first page's count, zero to the other pages'
 #pragma unroll
     for (int g = 0; RING && g < G; ++g) {
+        if (!act[g]) continue;
         if (lane < pend[g])
             cand[list0 + (size_t)(kvh * G + g) * dsc.head_stride + flushed[g] + lane] = make_uint2(ring_s[g], ring_j[g]);
         if (lane < p_end - p_begin)
@@ -268,20 +288,50 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
     }
 }
 
+// Phases 0 and 1: one workgroup per block.  Phase 2 is launched with a small grid whose workgroups
+// leave at once unless some head was marked for repair, and otherwise share all blocks out.
+template <int DT, int D, int G, int PHASE, bool RING>
+__global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ desc, int B,
+                                                     const int32_t *__restrict__ page_table,
+                                                     const uint32_t *__restrict__ qw, const uint4 *__restrict__ k_pool,
+                                                     uint2 *__restrict__ cand, int32_t *__restrict__ page_cnt,
+                                                     const uint32_t *__restrict__ tau_in,
+                                                     const uint32_t *__restrict__ tau_safe,
+                                                     const uint32_t *__restrict__ fail,
+                                                     const uint32_t *__restrict__ any_fail,
+                                                     uint32_t *__restrict__ hist,
+                                                     uint32_t *__restrict__ sample_max, int H_kv, int ppw, int mode,
+                                                     int total_blocks)
+{
+    if (PHASE == 2) {
+        if (*any_fail == 0u) return;
+        for (int b = blockIdx.x; b < total_blocks; b += gridDim.x)
+            score_block<DT, D, G, PHASE, RING>(b, desc, B, page_table, qw, k_pool, cand, page_cnt, tau_in, tau_safe,
+                                               fail, hist, sample_max, H_kv, ppw, mode);
+    } else {
+        score_block<DT, D, G, PHASE, RING>(blockIdx.x, desc, B, page_table, qw, k_pool, cand, page_cnt, tau_in,
+                                           tau_safe, fail, hist, sample_max, H_kv, ppw, mode);
+    }
+}
+
 template <int DT, int D>
 static hipError_t launch_score_g(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles,
                                  int ppw, int phase, int mode, hipStream_t st)
 {
     const int G = sh.n_q_heads / sh.n_kv_heads;
-    const dim3 grid((unsigned)(total_tiles * sh.n_kv_heads)), block(256);
+    const int total_blocks = total_tiles * sh.n_kv_heads;
+    const dim3 grid((unsigned)(phase == 2 && total_blocks > kRepairGrid ? kRepairGrid : total_blocks)), block(256);
 #define ALAYA_SCORE_ARGS                                                                                       \
     dv.desc, B, dv.page_table, (const uint32_t *)q, (const uint4 *)dv.k_pool, dv.cand, dv.page_cnt, dv.tau,   \
-        dv.hist, dv.sample_max, sh.n_kv_heads, ppw, mode
+        dv.tau_safe, dv.fail, dv.any_fail, dv.hist, dv.sample_max, sh.n_kv_heads, ppw, mode, total_blocks
 #define ALAYA_SCORE(GG)                                                                                       \
     do {                                                                                                      \
         if (phase == 0) score_kernel<DT, D, GG, 0, false><<<grid, block, 0, st>>>(ALAYA_SCORE_ARGS);          \
-        else if (ppw == 1) score_kernel<DT, D, GG, 1, false><<<grid, block, 0, st>>>(ALAYA_SCORE_ARGS);       \
-        else score_kernel<DT, D, GG, 1, true><<<grid, block, 0, st>>>(ALAYA_SCORE_ARGS);                      \
+        else if (phase == 1 && ppw == 1)                                                                      \
+            score_kernel<DT, D, GG, 1, false><<<grid, block, 0, st>>>(ALAYA_SCORE_ARGS);                      \
+        else if (phase == 1) score_kernel<DT, D, GG, 1, true><<<grid, block, 0, st>>>(ALAYA_SCORE_ARGS);      \
+        else if (ppw == 1) score_kernel<DT, D, GG, 2, false><<<grid, block, 0, st>>>(ALAYA_SCORE_ARGS);       \
+        else score_kernel<DT, D, GG, 2, true><<<grid, block, 0, st>>>(ALAYA_SCORE_ARGS);                      \
     } while (0)
     switch (G) {
     case 1: ALAYA_SCORE(1); break;
@@ -317,10 +367,11 @@ __global__ __launch_bounds__(kSelectThreads) void tau_kernel(const ReqDesc *__re
                                                               const uint32_t *__restrict__ hist,
                                                               uint32_t *__restrict__ sample_max,
                                                               uint32_t *__restrict__ head_maxkey,
-                                                              uint32_t *__restrict__ tau)
+                                                              uint32_t *__restrict__ tau,
+                                                              uint32_t *__restrict__ tau_safe)
 {
     __shared__ int32_t wtot[kSelectThreads / 64];
-    __shared__ int32_t found;
+    __shared__ int32_t found, found_est;
 
     const int rh = blockIdx.x;
     const ReqDesc dsc = desc[rh / H_q];
@@ -335,7 +386,7 @@ __global__ __launch_bounds__(kSelectThreads) void tau_kernel(const ReqDesc *__re
             for (int o = 32; o > 0; o >>= 1) mk = max(mk, (uint32_t)__shfl_xor((int)mk, o));
             if (tid == 0) {
                 head_maxkey[rh] = mk; // the selection raises it further with the other pages' survivors
-                tau[rh] = mk ? ord_key(ord_float(mk) - dsc.beta) : 0u;
+                tau[rh] = tau_safe[rh] = mk ? ord_key(ord_float(mk) - dsc.beta) : 0u;
             }
         }
         return;
@@ -345,7 +396,7 @@ __global__ __launch_bounds__(kSelectThreads) void tau_kernel(const ReqDesc *__re
     const uint32_t *gh = hist + (size_t)rh * kHistBins;
     const int b0 = kHistBins - 1 - 2 * tid;
     const int c0 = (int)gh[b0], c1 = (int)gh[b0 - 1];
-    if (tid == 0) found = -1;
+    if (tid == 0) found = found_est = -1;
     int inc = c0 + c1;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
@@ -357,15 +408,23 @@ __global__ __launch_bounds__(kSelectThreads) void tau_kernel(const ReqDesc *__re
     int above = inc - (c0 + c1);
     for (int w = 0; w < wave; ++w) above += wtot[w];
     if (above < dsc.k && above + c0 + c1 >= dsc.k) found = above + c0 >= dsc.k ? b0 : b0 - 1;
+    // The estimated bound: the bucket of the sample's k_est-th largest score, k_est being the share
+    // of k that a 1-in-S sample is expected to hold plus a wide margin.  Nothing guarantees it; the
+    // selection checks the survivor count against k and has the head repaired if it fell short.
+    const int ke = dsc.k_est;
+    if (ke > 0 && above < ke && above + c0 + c1 >= ke) found_est = above + c0 >= ke ? b0 : b0 - 1;
     __syncthreads();
-    // fewer than k scores in the sample: no bound
-    if (tid == 0) tau[rh] = found >= 0 ? (uint32_t)found << 21 : 0u;
+    if (tid == 0) {
+        const uint32_t safe = found >= 0 ? (uint32_t)found << 21 : 0u; // fewer than k scores in the sample: no bound
+        tau_safe[rh] = safe;
+        tau[rh] = (ke > 0 && found_est >= 0) ? (uint32_t)found_est << 21 : safe;
+    }
 }
 
 hipError_t launch_tau(const Shape &sh, const DeviceViews &dv, int B, int mode, hipStream_t st)
 {
     tau_kernel<<<dim3((unsigned)(B * sh.n_q_heads)), dim3(kSelectThreads), 0, st>>>(
-        dv.desc, sh.n_q_heads, mode, dv.hist, dv.sample_max, dv.head_maxkey, dv.tau);
+        dv.desc, sh.n_q_heads, mode, dv.hist, dv.sample_max, dv.head_maxkey, dv.tau, dv.tau_safe);
     return hipGetLastError();
 }
 

@@ -263,7 +263,8 @@ __global__ __launch_bounds__(kSelectThreads) void select_local_kernel(
     const int32_t *__restrict__ page_cnt,
     const uint32_t *__restrict__ hist, const uint32_t *__restrict__ head_maxkey, float *__restrict__ head_M,
     int32_t *__restrict__ head_info, int32_t *__restrict__ seg_counts, float *__restrict__ loc_scores,
-    int32_t *__restrict__ loc_ids)
+    int32_t *__restrict__ loc_ids, const uint32_t *__restrict__ tau, uint32_t *__restrict__ fail,
+    uint32_t *__restrict__ any_fail, int redo)
 {
     __shared__ uint32_t lh[kHistBins];
     __shared__ int32_t off[kMaxSegPages + 1];
@@ -271,10 +272,12 @@ __global__ __launch_bounds__(kSelectThreads) void select_local_kernel(
     __shared__ int32_t wtot[kSelWaves];
     __shared__ int32_t res[2];
 
+    if (redo && *any_fail == 0u) return; // second run, and nothing was marked: the usual case
     const SegId id = seg_of_block(desc, B, H_q);
     const ReqDesc dsc = desc[id.r];
     const int rh = id.r * H_q + id.h;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (redo && fail[rh] == 0u) return; // second run: only the heads that the repair pass rewrote
 
     // issue every independent load first: the page counts, the maximum, the histogram
     int a0, a1;
@@ -283,8 +286,21 @@ __global__ __launch_bounds__(kSelectThreads) void select_local_kernel(
     const bool bucket_rule = mode == 0 && dsc.k < dsc.n - dsc.nwin;
     if (bucket_rule) {
         for (int i = tid; i < kHistBins; i += kSelectThreads) lh[i] = hist[(size_t)rh * kHistBins + i];
+        if (tid == 0) res[0] = -1;
         __syncthreads();
         block_find_bin(lh, kHistBins, dsc.k, wtot, res);
+        // The histogram is complete from the bucket of the main pass's bound upwards (below it only
+        // the sampled pages are counted).  If the k-th largest score does not lie in that part, the
+        // bound - an estimate then - was too high and tokens are missing: every workgroup of the
+        // head sees the same histogram, steps aside, and the head is marked for the repair pass.
+        const int b_bound = dsc.sample_stride > 1 ? (int)(tau[rh] >> 21) : 0;
+        if (!redo && (res[0] < 0 || res[0] < b_bound)) {
+            if (id.seg == 0 && tid == 0) {
+                fail[rh] = 1u;
+                *any_fail = 1u; // (several heads may write the same 1)
+            }
+            return;
+        }
     }
     Rule rule;
     rule.topk = bucket_rule;
@@ -343,7 +359,8 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
     const int32_t *__restrict__ loc_ids, uint32_t *__restrict__ hist, uint32_t *__restrict__ head_maxkey,
     int32_t *__restrict__ sel_ids, float *__restrict__ sel_scores, int32_t *__restrict__ counts,
     int32_t *__restrict__ out_ids, int32_t *__restrict__ out_counts, int64_t ids_stride,
-    int32_t *__restrict__ status, float *__restrict__ head_M)
+    int32_t *__restrict__ status, float *__restrict__ head_M, uint32_t *__restrict__ fail,
+    uint32_t *__restrict__ any_fail)
 {
     __shared__ uint32_t lh[kHistBins];
     __shared__ float wred[kSelWaves];
@@ -553,7 +570,9 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
         counts[rh] = count;
         if (out_counts) out_counts[rh] = count;
         if (out_ids && (int64_t)count > ids_stride) atomicOr(status, 1);
-        head_maxkey[rh] = 0u; // leave the running maximum and the histogram clean for the next call
+        head_maxkey[rh] = 0u; // leave the running maximum, the histogram and the repair mark clean for the next call
+        fail[rh] = 0u;
+        if (rh == 0) *any_fail = 0u;
     }
     if (out_ids) {
         const int m = (int)((int64_t)count < ids_stride ? (int64_t)count : ids_stride);
@@ -564,8 +583,8 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
         for (int i = tid; i < kHistBins; i += kSelectThreads) hist[(size_t)rh * kHistBins + i] = 0u;
 }
 
-hipError_t launch_select(const Shape &sh, const DeviceViews &dv, int B, int mode, int total_segs, int32_t *out_ids,
-                         int32_t *out_counts, int64_t ids_stride, hipStream_t st)
+hipError_t launch_select_front(const Shape &sh, const DeviceViews &dv, int B, int mode, int total_segs,
+                               hipStream_t st)
 {
     const dim3 block(kSelectThreads);
     const dim3 seg_grid((unsigned)(total_segs * sh.n_q_heads));
@@ -573,15 +592,29 @@ hipError_t launch_select(const Shape &sh, const DeviceViews &dv, int B, int mode
                                                     dv.hist, dv.head_maxkey);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    select_local_kernel<<<seg_grid, block, 0, st>>>(dv.desc, B, sh.n_q_heads, mode, dv.cand,
-                                                    dv.page_cnt, dv.hist, dv.head_maxkey, dv.head_M, dv.head_info,
-                                                    dv.seg_counts, dv.loc_scores, dv.loc_ids);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    select_local_kernel<<<seg_grid, block, 0, st>>>(dv.desc, B, sh.n_q_heads, mode, dv.cand, dv.page_cnt, dv.hist,
+                                                    dv.head_maxkey, dv.head_M, dv.head_info, dv.seg_counts,
+                                                    dv.loc_scores, dv.loc_ids, dv.tau, dv.fail, dv.any_fail, 0);
+    return hipGetLastError();
+}
+
+hipError_t launch_select_back(const Shape &sh, const DeviceViews &dv, int B, int mode, int total_segs, bool redo,
+                              int32_t *out_ids, int32_t *out_counts, int64_t ids_stride, hipStream_t st)
+{
+    const dim3 block(kSelectThreads);
+    if (redo) {
+        const dim3 seg_grid((unsigned)(total_segs * sh.n_q_heads));
+        select_local_kernel<<<seg_grid, block, 0, st>>>(dv.desc, B, sh.n_q_heads, mode, dv.cand, dv.page_cnt,
+                                                        dv.hist, dv.head_maxkey, dv.head_M, dv.head_info,
+                                                        dv.seg_counts, dv.loc_scores, dv.loc_ids, dv.tau, dv.fail, dv.any_fail,
+                                                        1);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     select_finish_kernel<<<dim3((unsigned)(B * sh.n_q_heads)), block, 0, st>>>(
         dv.desc, sh.n_q_heads, mode, dv.head_info, dv.seg_counts, dv.loc_scores, dv.loc_ids, dv.hist,
         dv.head_maxkey, dv.sel_ids, dv.sel_scores, dv.counts, out_ids, out_counts, ids_stride, dv.status,
-        dv.head_M);
+        dv.head_M, dv.fail, dv.any_fail);
     return hipGetLastError();
 }
 

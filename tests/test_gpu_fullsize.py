@@ -65,6 +65,11 @@ def test_paged_1m_topk4096_permuted_pages():
     st = run_and_compare(c, w, g, A.ALAYA_TOPK, topk=w.topk)
     _say(f"paged_1m: out err {st['max_out_err']:.2e}, score err {st['max_score_err']:.2e}, "
          f"band heads {st['band_heads']}")
+    # this call is large enough for the estimated threshold bound; make every head take the repair path too
+    c.debug_estimate(2)
+    st = run_and_compare(c, w, g, A.ALAYA_TOPK, topk=w.topk, check_scores=False)
+    _say(f"paged_1m with every head repaired: out err {st['max_out_err']:.2e}, band heads {st['band_heads']}")
+    c.debug_estimate(0)
     q = to_device(g["q"], w.dtype)
     full = c.full_attn([0], q).cpu().numpy()
     ref = oracle.full_attn(g["q"][0], g["K"][0], g["V"][0])

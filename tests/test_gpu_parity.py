@@ -169,6 +169,50 @@ def test_prefix_queries_ignore_what_lies_behind_the_prefix():
     c2.close()
 
 
+# ------------------------------------------------------------------------------------------ estimated bound
+@pytest.mark.parametrize("force", [1, 2])
+def test_estimated_bound_is_verified_and_repaired(force):
+    """Large top-k calls filter with an estimated threshold bound; the selection checks it and has the
+    heads repaired where it was too high.  force = 1: estimate on these (small) shapes too; force = 2:
+    an estimate that is always too high, so that every head takes the repair path."""
+    w = _llama([30000 + 21, 9000], topk=[2048, 600])
+    g = wl.generate(w)
+    c = make_cache(w, g)
+    c.debug_estimate(force)
+    for ppw in (0, 4):
+        c.set_tuning(ppw, 0, 0)
+        run_and_compare(c, w, g, A.ALAYA_TOPK, topk=[2048, 600])
+        run_and_compare(c, w, g, A.ALAYA_TOPK, topk=[700, 5000], window=(100, 300), check_scores=False)
+    run_and_compare(c, w, g, A.ALAYA_DIPR, beta=[2.0, 2.0], check_scores=False)   # DIPR never estimates
+    c.close()
+
+
+def test_estimate_that_fails_for_one_head_only():
+    """The sample is every S-th page.  Keys in exactly those pages are made to line up with ONE head's
+    query: that head's sample is far richer in high scores than the cache as a whole, its estimated
+    bound comes out too high, and it alone must be repaired (the other heads of its group share the
+    same keys and must be left as they are)."""
+    w = _llama([40000], topk=[2048])
+    g = wl.generate(w)
+    K = g["K"][0].copy()
+    q0 = wl.bf16_bits_to_f32(g["q"][0][0]).astype(np.float64)
+    rng = np.random.default_rng(5)
+    for S in (16,):                                        # the stride the library takes for k = 2048
+        pages = np.arange(0, (40000 + 63) // 64, S)
+        tok = (pages[:, None] * 64 + np.arange(64)[None, :]).ravel()
+        tok = tok[tok < 40000]
+        boost = (q0[None, :] / np.linalg.norm(q0)) * rng.uniform(3.0, 6.0, size=(tok.size, 1))
+        K[tok, 0, :] = wl.to_bf16_bits((wl.bf16_bits_to_f32(K[tok, 0, :]) * 0.3 + boost).astype(np.float32))
+    g = {**g, "K": [K]}
+    c = make_cache(w, g)
+    c.debug_estimate(1)
+    st = run_and_compare(c, w, g, A.ALAYA_TOPK, topk=[2048])
+    c.debug_estimate(-1)
+    st2 = run_and_compare(c, w, g, A.ALAYA_TOPK, topk=[2048], check_scores=False)
+    assert st["counts"] == st2["counts"]
+    c.close()
+
+
 # ------------------------------------------------------------------------------------------ paging
 def test_permuted_pages_do_not_change_the_answer():
     """Physical page order is invisible: same ids, bit-identical output as with pages in order."""
