@@ -482,8 +482,8 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
     if (rc != ALAYA_OK) return rc;
     int tiles = 0, tiles_b = 0, segs = 0, all_pages = 0;
     // Large top-k calls filter with an estimated bound and pay two (normally idle) repair launches for
-    // it; below about half a million tokens in the call the guaranteed bound is as fast.
-    const bool estimate = c->estimate_mode > 0 || (c->estimate_mode == 0 && total_pages >= 8192);
+    // it; below about a quarter of a million tokens in the call the guaranteed bound is as fast.
+    const bool estimate = c->estimate_mode > 0 || (c->estimate_mode == 0 && total_pages >= 4096);
     bool any_est = false;
     int64_t pages_a = 0;
     int64_t off = 0;
@@ -536,7 +536,7 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
                 while (S < 32 && (int64_t)(2 * S) * (2 * S) * d.k <= n && (int64_t)2 * S * d.k * 2 <= n) S *= 2;
                 while (S > 1 && pages / S < 2) S /= 2;
             } else {
-                S = 16;
+                S = pages >= 8192 ? 32 : 16; // the sample only has to come close to the maximum
                 while (S > 1 && pages / S < 2) S /= 2;
             }
         }
