@@ -446,14 +446,7 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
                             (long long)c->seq_len[(size_t)seqs[b]]);
 
     hipStream_t st = (hipStream_t)stream;
-    // pages per wavefront in the main scoring pass: aim at about 8192 workgroups
-    int ppw = c->tune_ppw;
-    if (ppw <= 0) {
-        ppw = (int)((total_pages * c->cfg.n_kv_heads + (int64_t)kScoreWaves * 8192 - 1) /
-                    ((int64_t)kScoreWaves * 8192));
-        if (ppw < 1) ppw = 1;
-        if (ppw > 8) ppw = 8;
-    }
+    int ppw = c->tune_ppw; // pages per wavefront in the main scoring pass; chosen below if not given
     // pages per selection segment: about 512 segment workgroups in all, 128 to 2048 pages each
     int64_t seg_pages_want = c->tune_seg;
     if (seg_pages_want <= 0) {
@@ -485,6 +478,7 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
     // it; below about a quarter of a million tokens in the call the guaranteed bound is as fast.
     const bool estimate = c->estimate_mode > 0 || (c->estimate_mode == 0 && total_pages >= 4096);
     bool any_est = false;
+    double survive = 0.0;
     int64_t pages_a = 0;
     int64_t off = 0;
     for (int b = 0; b < B; ++b) {
@@ -501,7 +495,6 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
         const int64_t n_out = n - d.nwin; // tokens outside the window: what top-k ranks
         d.k = p->mode == ALAYA_TOPK ? (int32_t)((int64_t)p->topk[b] < n_out ? p->topk[b] : n_out) : 0;
         d.beta = p->mode == ALAYA_DIPR ? p->beta[b] : 0.f;
-        d.tile_start = tiles;
         d.score_off = off;
         if (pages > (int64_t)kMaxSegs * kMaxSegPages)
             return fail(ALAYA_E_INVAL, "request %d: %lld tokens exceed the selection layout (%lld)", b, (long long)n,
@@ -541,17 +534,35 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
             }
         }
         d.sample_stride = S;
-        const int n_a = (int)((pages + S - 1) / S);
-        d.tileb_start = tiles_b;
+        // share of the main pass's scores that is expected to survive
+        const double f = p->mode == ALAYA_TOPK && S > 1 ? (double)(d.k_est > 0 ? d.k_est : d.k) * S / (double)n : 0.0;
+        if (f > survive) survive = f;
+        all_pages += (int)pages;
+        pages_a += (pages + S - 1) / S;
+        segs += d.nseg;
+        off += (int64_t)n_q_heads * d.head_stride;
+    }
+    // Several pages per wavefront (about 8192 workgroups, survivors staged in registers and written as
+    // one list) pay when many scores survive; with few survivors one page per wavefront is faster.
+    if (ppw <= 0) {
+        ppw = 1;
+        if (survive > 0.03)
+            ppw = (int)((total_pages * c->cfg.n_kv_heads + (int64_t)kScoreWaves * 8192 - 1) /
+                        ((int64_t)kScoreWaves * 8192));
+        if (ppw < 1) ppw = 1;
+        if (ppw > 8) ppw = 8;
+    }
+    for (int b = 0; b < B; ++b) {
+        ReqDesc &d = hd[b];
+        const int S = d.sample_stride;
+        const int n_a = (d.n_pages + S - 1) / S;
         int cp = 1; // pages per wavefront in the main pass: a power of two, at most min(ppw, S)
         while (2 * cp <= ppw && 2 * cp <= S) cp *= 2;
         d.chunk_pages = cp;
+        d.tile_start = tiles;
+        d.tileb_start = tiles_b;
         tiles += (n_a + kScoreWaves - 1) / kScoreWaves;                                  // one page per wavefront
-        if (S > 1) tiles_b += (int)((pages + (int64_t)kScoreWaves * cp - 1) / ((int64_t)kScoreWaves * cp));
-        all_pages += (int)pages;
-        pages_a += n_a;
-        segs += d.nseg;
-        off += (int64_t)n_q_heads * d.head_stride;
+        if (S > 1) tiles_b += (int)((d.n_pages + (int64_t)kScoreWaves * cp - 1) / ((int64_t)kScoreWaves * cp));
     }
     c->last_ppw = ppw;
     c->last_pages = all_pages;
