@@ -13,8 +13,9 @@ timed region.  Prints ONE JSON line:
               256 B (one bf16 K row, read once) x the K rows that launch scores (the pages that the
               sample pass did not take, x 64 tokens x KV heads); the few survivors it writes are not
               counted.  Duration = the kernel's average over a profiled repeat of the timed loop,
-              taken with HIP events on the launch stream (events between kernels would lengthen the
-              timed steps themselves).
+              taken with HIP events attached to the kernel's own dispatch on the launch stream (the
+              library's profiling mode; events between kernels would lengthen the timed steps
+              themselves, so the timed loop runs without them).
   cold_cache  per-kernel times of the same step when the last-level cache is flushed before it
   gather      the gather + attend kernel: one V row (256 B) per selected (head, token), same clock
   cpu_baseline  the CPU oracle on the same step, on this host's cores (a reported baseline only)

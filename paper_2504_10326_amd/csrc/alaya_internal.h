@@ -98,8 +98,10 @@ hipError_t launch_append(const Shape &sh, const int32_t *page_table_row, void *k
 
 // phase 0 scores the sampled pages in full, phase 1 the other pages against dv.tau, phase 2 (repair)
 // the other pages of the heads marked in dv.fail against dv.tau_safe.
+// ev0 / ev1: optional events that take the kernel's own begin and end times.
 hipError_t launch_score(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles,
-                        int pages_per_wave, int phase, int mode, hipStream_t st);
+                        int pages_per_wave, int phase, int mode, hipStream_t st, hipEvent_t ev0 = nullptr,
+                        hipEvent_t ev1 = nullptr);
 // mode: 0 top-k, 1 DIPR
 hipError_t launch_tau(const Shape &sh, const DeviceViews &dv, int B, int mode, hipStream_t st);
 

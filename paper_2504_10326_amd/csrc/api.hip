@@ -152,12 +152,16 @@ int harvest(alaya_cache *c)
     return ALAYA_OK;
 }
 
-// Brackets one launch with events when profiling is on.
+// Brackets one or more launches with events when profiling is on; with `attach` the events are not
+// recorded here but handed to ONE launch (begin() / end()), which attaches them to its dispatch.
 struct Timed {
     alaya_cache *c;
     hipStream_t st;
     int idx;
-    Timed(alaya_cache *c_, int slot, hipStream_t st_) : c(c_), st(st_), idx(-1)
+    bool attach;
+    hipEvent_t begin() const { return idx >= 0 ? c->ev[2 * idx] : nullptr; }
+    hipEvent_t end() const { return idx >= 0 ? c->ev[2 * idx + 1] : nullptr; }
+    Timed(alaya_cache *c_, int slot, hipStream_t st_, bool attach_ = false) : c(c_), st(st_), idx(-1), attach(attach_)
     {
         if (!c->prof) return;
         if (c->ev_n == kProfPairs && harvest(c) != ALAYA_OK) return;
@@ -168,11 +172,11 @@ struct Timed {
         }
         idx = c->ev_n++;
         c->ev_slot[idx] = slot;
-        (void)hipEventRecord(c->ev[2 * idx], st);
+        if (!attach) (void)hipEventRecord(c->ev[2 * idx], st);
     }
     ~Timed()
     {
-        if (idx >= 0) (void)hipEventRecord(c->ev[2 * idx + 1], st);
+        if (idx >= 0 && !attach) (void)hipEventRecord(c->ev[2 * idx + 1], st);
     }
 };
 
@@ -593,8 +597,8 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
     }
     if (e != hipSuccess) { c->dev_ready = false; return fail_hip(e, "sample scoring launch"); }
     if (tiles_b > 0) {
-        Timed tm(c, 0, st);
-        e = launch_score(sh, c->dv, B, q, tiles_b, ppw, 1, p->mode, st);
+        Timed tm(c, 0, st, true); // the roofline kernel: timed by its own dispatch
+        e = launch_score(sh, c->dv, B, q, tiles_b, ppw, 1, p->mode, st, tm.begin(), tm.end());
     }
     if (e != hipSuccess) { c->dev_ready = false; return fail_hip(e, "score launch"); }
     {

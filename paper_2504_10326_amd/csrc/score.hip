@@ -8,6 +8,7 @@
 // lane ends up with its own token's whole key, and the G query heads of the group are reduced in
 // registers with no cross-lane traffic.  One K read serves all G heads of the group (GQA, Sec. 6.2).
 #include "alaya_internal.h"
+#include <hip/hip_ext.h>
 
 namespace alaya {
 
@@ -314,24 +315,37 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
     }
 }
 
+// With events given, they are attached to the dispatch itself (hipExtLaunchKernelGGL): their
+// timestamps are then the kernel's own begin and end, without the gaps an event pair recorded
+// around a launch also sees.
+template <typename Kern, typename... Args>
+static void launch_maybe_timed(Kern kern, dim3 grid, dim3 block, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1,
+                               Args... args)
+{
+    if (ev0 && ev1) hipExtLaunchKernelGGL(kern, grid, block, 0, st, ev0, ev1, 0, args...);
+    else kern<<<grid, block, 0, st>>>(args...);
+}
+
 template <int DT, int D>
 static hipError_t launch_score_g(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles,
-                                 int ppw, int phase, int mode, hipStream_t st)
+                                 int ppw, int phase, int mode, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1)
 {
     const int G = sh.n_q_heads / sh.n_kv_heads;
     const int total_blocks = total_tiles * sh.n_kv_heads;
     const dim3 grid((unsigned)(phase == 2 && total_blocks > kRepairGrid ? kRepairGrid : total_blocks)), block(256);
-#define ALAYA_SCORE_ARGS                                                                                       \
-    dv.desc, B, dv.page_table, (const uint32_t *)q, (const uint4 *)dv.k_pool, dv.cand, dv.page_cnt, dv.tau,   \
-        dv.tau_safe, dv.fail, dv.any_fail, dv.hist, dv.sample_max, sh.n_kv_heads, ppw, mode, total_blocks
+#define ALAYA_SCORE_K(GG, PH, RG)                                                                             \
+    launch_maybe_timed(score_kernel<DT, D, GG, PH, RG>, grid, block, st, ev0, ev1, dv.desc, B, dv.page_table, \
+                       (const uint32_t *)q, (const uint4 *)dv.k_pool, dv.cand, dv.page_cnt,                   \
+                       (const uint32_t *)dv.tau, (const uint32_t *)dv.tau_safe, (const uint32_t *)dv.fail,    \
+                       (const uint32_t *)dv.any_fail, dv.hist, dv.sample_max, sh.n_kv_heads, ppw, mode,       \
+                       total_blocks)
 #define ALAYA_SCORE(GG)                                                                                       \
     do {                                                                                                      \
-        if (phase == 0) score_kernel<DT, D, GG, 0, false><<<grid, block, 0, st>>>(ALAYA_SCORE_ARGS);          \
-        else if (phase == 1 && ppw == 1)                                                                      \
-            score_kernel<DT, D, GG, 1, false><<<grid, block, 0, st>>>(ALAYA_SCORE_ARGS);                      \
-        else if (phase == 1) score_kernel<DT, D, GG, 1, true><<<grid, block, 0, st>>>(ALAYA_SCORE_ARGS);      \
-        else if (ppw == 1) score_kernel<DT, D, GG, 2, false><<<grid, block, 0, st>>>(ALAYA_SCORE_ARGS);       \
-        else score_kernel<DT, D, GG, 2, true><<<grid, block, 0, st>>>(ALAYA_SCORE_ARGS);                      \
+        if (phase == 0) ALAYA_SCORE_K(GG, 0, false);                                                          \
+        else if (phase == 1 && ppw == 1) ALAYA_SCORE_K(GG, 1, false);                                         \
+        else if (phase == 1) ALAYA_SCORE_K(GG, 1, true);                                                      \
+        else if (ppw == 1) ALAYA_SCORE_K(GG, 2, false);                                                       \
+        else ALAYA_SCORE_K(GG, 2, true);                                                                      \
     } while (0)
     switch (G) {
     case 1: ALAYA_SCORE(1); break;
@@ -341,20 +355,20 @@ static hipError_t launch_score_g(const Shape &sh, const DeviceViews &dv, int B, 
     default: return hipErrorInvalidValue;
     }
 #undef ALAYA_SCORE
-#undef ALAYA_SCORE_ARGS
+#undef ALAYA_SCORE_K
     return hipGetLastError();
 }
 
 hipError_t launch_score(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles, int ppw,
-                        int phase, int mode, hipStream_t st)
+                        int phase, int mode, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1)
 {
     if (total_tiles <= 0) return hipSuccess;
     if (sh.dtype == 0) {
-        if (sh.head_dim == 128) return launch_score_g<0, 128>(sh, dv, B, q, total_tiles, ppw, phase, mode, st);
-        if (sh.head_dim == 64) return launch_score_g<0, 64>(sh, dv, B, q, total_tiles, ppw, phase, mode, st);
+        if (sh.head_dim == 128) return launch_score_g<0, 128>(sh, dv, B, q, total_tiles, ppw, phase, mode, st, ev0, ev1);
+        if (sh.head_dim == 64) return launch_score_g<0, 64>(sh, dv, B, q, total_tiles, ppw, phase, mode, st, ev0, ev1);
     } else {
-        if (sh.head_dim == 128) return launch_score_g<1, 128>(sh, dv, B, q, total_tiles, ppw, phase, mode, st);
-        if (sh.head_dim == 64) return launch_score_g<1, 64>(sh, dv, B, q, total_tiles, ppw, phase, mode, st);
+        if (sh.head_dim == 128) return launch_score_g<1, 128>(sh, dv, B, q, total_tiles, ppw, phase, mode, st, ev0, ev1);
+        if (sh.head_dim == 64) return launch_score_g<1, 64>(sh, dv, B, q, total_tiles, ppw, phase, mode, st, ev0, ev1);
     }
     return hipErrorInvalidValue;
 }
