@@ -5,9 +5,10 @@
 //   to the critical tokens as in Sec. 2 "Sparse Attention").
 // Partial results carry (m, l, acc) = (reference max, sum of exp(z - m), sum of exp(z - m) v) and are
 // merged in a fixed order, as in the paper's data-centric engine (Sec. 6.2: partial attention computed
-// where the vectors sit, then aggregated the FlashAttention way).  The selected set always contains the
-// arg-max of all scores, so the sparse path knows its softmax reference before it starts: m is the
-// global maximum found by the scoring pass and no rescaling is needed on the way.
+// where the vectors sit, then aggregated the FlashAttention way).  The sparse path knows its softmax
+// reference before it starts: the selection leaves the maximum over the selected set in head_M (DIPR:
+// the maximum of all scores, which is always selected; top-k: the maximum of the finished list), so no
+// rescaling is needed on the way.
 #include "alaya_internal.h"
 
 namespace alaya {

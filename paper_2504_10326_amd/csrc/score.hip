@@ -52,29 +52,30 @@ hipError_t launch_append(const Shape &sh, const int32_t *pt_row, void *k_pool, v
 // ------------------------------------------------------------------------------------------------
 // Scoring.  Grid: one workgroup per (tile, KV head); KV head is the fastest index so that with
 // 8 KV heads each head's stream stays on one XCD (workgroups are dealt to XCDs round-robin).
-// A tile is four wavefronts' worth of pages; a wavefront scores pages_per_wave pages of one request.
+// A tile is four wavefronts' worth of pages; a wavefront scores one or a few pages of one request.
 //
 // bf16 uses the packed dot-product instruction (two bf16 products and the fp32 accumulate in one op,
 // both operands used as stored), the query streamed through scalar registers; fp32 uses fused
 // multiply-add.
 //
-// What is written.  Writing every fp32 score back costs far more than its 6 % share of the bytes (HBM
-// dislikes a write stream mixed into the read stream: a read-only scan of the same keys runs at
-// 6.3 TB/s, the same scan writing all scores at 5.3), and nearly all of those scores can never be
-// selected.  So a wavefront writes only the SURVIVORS of its pages - (score, token id) pairs,
-// compacted, ascending, plus their count - where a survivor is a score at or above `tau`, a lower
-// bound of the head's final selection threshold.  The bound comes from a sample, with no atomics and no feedback between
-// workgroups:
-//   phase A  scores every S-th page of each request and writes all of those scores (tau = 0);
-//   tau      (tau_kernel) top-k: the k-th largest score of a SUBSET is never above the k-th largest of
-//            the whole, so the lower edge of the histogram bucket holding the sample's k-th largest
-//            score is a valid tau; DIPR: tau = (sample max) - beta <= (true max) - beta;
-//            (large top-k calls filter with a tighter ESTIMATE instead, which the selection verifies:
-//            see tau_kernel and PHASE 2 below)
-//   phase B  scores the remaining pages against tau.
-// tau never exceeds the final threshold, so nothing that can be selected is ever dropped: the
-// selection that follows is exact.  It is also deterministic - the survivor lists depend on the
-// data only, not on timing.
+// What is written.  Writing every fp32 score back costs far more than its 6 % share of the bytes (a
+// read-only scan of the same keys runs at 6.3 TB/s, the same scan writing all scores at 5.3), and
+// nearly all of those scores can never be selected.  So a wavefront writes only the SURVIVORS of its
+// pages - (score, token id) pairs, compacted, ascending, plus their count - where a survivor is a
+// score at or above `tau`, a lower bound of the head's final selection threshold (window tokens
+// always survive).  The bound comes from a sample; the workgroups of one launch never wait for or
+// feed back to each other:
+//   sample pass  (phase 0) scores every S-th page of each request, writes all of those scores and
+//                enters them into the head's histogram (top-k) or maximum (DIPR);
+//   bound        (tau_kernel) top-k: the k-th largest score of a SUBSET is never above the k-th largest
+//                of the whole, so the lower edge of the histogram bucket holding the sample's k-th
+//                largest score is a valid tau; DIPR: tau = (sample max) - beta <= (true max) - beta.
+//                Large top-k calls filter with a tighter ESTIMATE instead, which the selection
+//                verifies afterwards (tau_kernel, phase 2);
+//   main pass    (phase 1) scores the remaining pages against tau.
+// A guaranteed tau never exceeds the final threshold, so nothing that can be selected is dropped;
+// an estimated one that does is detected and repaired.  Either way the selection that follows is
+// exact, and deterministic - the survivor lists depend on the data only, not on timing.
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 
 __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c)
@@ -85,11 +86,10 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c)
 
 // PHASE 0 (sample pass): the workgroup also enters its scores into the head's statistics: for DIPR it
 // raises one of the head's kMaxSlots sample maxima (many atomics on ONE address are slow: they are
-// carried out one after the other at the memory side), for top-k it counts them per bucket in LDS and
-// adds the non-empty buckets to the histogram.  The bound
-// kernel reads both right after this pass; the selection later adds only the survivors of the OTHER
-// pages to them.  Few workgroups run in phase 0 (a 1/S share of the pages), so these atomics are
-// cheap; the main pass (PHASE 1) has none.
+// carried out one after the other at the memory side), for top-k it counts them per bucket in LDS
+// and adds the non-empty buckets to the histogram.  The bound kernel reads both right after this
+// pass; the selection later adds only the survivors of the OTHER pages to them.  Few workgroups run
+// in phase 0 (a 1/S share of the pages), so these atomics are cheap; the main pass (PHASE 1) has none.
 // PHASE 2 (repair pass): as the main pass, but only for the heads marked in `fail` - those whose
 // estimated bound turned out to lie above the true threshold - and against the guaranteed bound; it
 // rewrites those heads' lists and adds the scores between the two bounds to their histograms.  It

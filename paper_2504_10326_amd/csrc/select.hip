@@ -1,7 +1,8 @@
 // Selection of the critical tokens of every (request, query head) from the survivors the scoring
-// pass wrote (every token that can possibly be selected is among them; each page's list is ascending).
+// passes wrote (every token that can possibly be selected is among them; each list is ascending).
 //   top-k (Sec. 5.1.1): the k largest scores; equal scores at the k-th place go to the smaller id.
 //   DIPR  (Def. 2, 3) : every token with score >= max - beta.
+//   window (Sec. 7.1) : window tokens are always selected; top-k neither counts nor ranks them.
 // Everything is exact and order-deterministic: counting is integer (radix select on the
 // order-preserving image of the score) and placement is an ordered compaction, so the selected list
 // is the same on every run.
@@ -10,18 +11,23 @@
 // survivors of a segment are addressed through a FLAT index: the pages' survivor counts are scanned
 // in LDS, and element t of the concatenation is found by a binary search over the prefix sums.  All
 // loads of a pass are therefore independent, and the flat order is ascending token order.
-//   stats   the head's maximum score (the arg-max always survives) and, for top-k, the bucket counts
-//           of the survivors (top 11 bits of the ordered key): LDS first, then at most kMaxSegs
-//           workgroups per head add to the same global counters
-//   local   classify each survivor: "definite" (top-k: its bucket lies above the bucket b of the k-th
-//           score, read off the histogram; DIPR: score >= max - beta), "candidate" (top-k only:
-//           bucket == b) or neither, and compact the segment into its own region: definite tokens
-//           first, candidates behind them, both in ascending token order
+//   stats   adds the survivors of the main pass's pages to what the sample pass already entered for
+//           its own pages: the bucket counts (top 11 bits of the ordered key) for top-k, the maximum
+//           for DIPR.  LDS first, then at most kMaxSegs workgroups per head add to the global counters.
+//   local   top-k: reads the bucket b of the k-th largest score off the histogram and checks that it
+//           lies in the part of the histogram that is complete (at or above the bucket of the bound
+//           the main pass filtered with); if not - possible only with an estimated bound - the head
+//           is marked for the repair pass and left alone until `local` runs a second time.
+//           Then classifies each survivor: "definite" (window token; top-k: bucket above b; DIPR:
+//           score >= max - beta), "candidate" (top-k only: bucket == b) or neither, and compacts the
+//           segment into its own region: definite tokens from the front, candidates from the back,
+//           both in ascending token order.
 //   finish  per head: gather the segments' definite lists into the head's final list (a binary search
 //           over the segment prefix sums finds each element's source), gather the candidates behind
-//           them, radix-refine the remaining 21 key bits over the candidates and compact them in
-//           place - keep key > T and the first `ties` tokens with key == T; publish the count, copy
-//           ids out if asked, and reset the head's histogram and maximum for the next call
+//           them, radix-refine the remaining 21 key bits over the candidates and keep key > T and the
+//           first `ties` tokens with key == T (from registers when they are at most 4096, in place
+//           otherwise); take top-k's head maximum from the finished list; publish the count, copy ids
+//           out if asked, and reset the head's histogram, maximum and repair mark for the next call.
 #include "alaya_internal.h"
 
 namespace alaya {
