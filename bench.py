@@ -105,9 +105,11 @@ def main() -> int:
     c.set_tuning(args.pages_per_wave, args.attend_splits, args.segment_pages, args.write_all_scores)
     torch.cuda.synchronize()
 
+    step_k = torch.cat(new_k, dim=0).contiguous()            # [batch][H_kv][d]: one new token per request
+    step_v = torch.cat(new_v, dim=0).contiguous()
+
     def step():
-        for r in range(w.batch):
-            c.append_kv(r, new_k[r], new_v[r])
+        c.append_step(seqs, step_k, step_v)                  # Session.update for the whole batch, one launch
         c.sparse_attn(seqs, q, mode, out=out, **kw)
 
     def run(n_steps):

@@ -104,6 +104,16 @@ int alaya_destroy_cache(alaya_cache *c);
  */
 int alaya_append_kv(alaya_cache *c, int seq, const void *k, const void *v, int64_t t, void *stream);
 
+/*
+ * Session.update for one decode step of a batch: appends ONE token to each of the B listed
+ * sequences with a single launch.
+ * seqs: HOST [B], distinct.  k, v: DEVICE, [B][n_kv_heads][head_dim] of the cache dtype; row b
+ * goes to sequence seqs[b].  Either every listed sequence grows by one token or, on an error
+ * (ALAYA_E_INVAL for a bad or repeated id, ALAYA_E_NOMEM when a length limit or the page pool is
+ * hit), none does.
+ */
+int alaya_append_kv_step(alaya_cache *c, const int32_t *seqs, int B, const void *k, const void *v, void *stream);
+
 /* Tokens cached for seq (host bookkeeping, includes appends still in flight); -1 on a bad argument. */
 int64_t alaya_seq_len(const alaya_cache *c, int seq);
 

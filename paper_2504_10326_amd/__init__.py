@@ -27,7 +27,7 @@ KERNEL_SLOTS = ("score", "select", "attend", "combine", "full_partial", "append"
 
 EXPORTS = (
     "alaya_pool_bytes", "alaya_workspace_bytes", "alaya_create_cache", "alaya_destroy_cache",
-    "alaya_append_kv", "alaya_seq_len", "alaya_reset_seq", "alaya_sparse_attn", "alaya_full_attn",
+    "alaya_append_kv", "alaya_append_kv_step", "alaya_seq_len", "alaya_reset_seq", "alaya_sparse_attn", "alaya_full_attn",
     "alaya_poll_status", "alaya_set_profiling", "alaya_kernel_times", "alaya_set_tuning", "alaya_debug_scores",
     "alaya_debug_survivors", "alaya_debug_pages", "alaya_debug_estimate",
     "alaya_last_error",
@@ -79,6 +79,8 @@ def lib() -> ctypes.CDLL:
         L.alaya_create_cache.restype = i32
         L.alaya_destroy_cache.argtypes = [vp]; L.alaya_destroy_cache.restype = i32
         L.alaya_append_kv.argtypes = [vp, i32, vp, vp, i64, vp]; L.alaya_append_kv.restype = i32
+        L.alaya_append_kv_step.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), i32, vp, vp, vp]
+        L.alaya_append_kv_step.restype = i32
         L.alaya_seq_len.argtypes = [vp, i32]; L.alaya_seq_len.restype = i64
         L.alaya_reset_seq.argtypes = [vp, i32]; L.alaya_reset_seq.restype = i32
         L.alaya_sparse_attn.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), i32, i32, vp,
@@ -171,6 +173,11 @@ def alaya_append_kv(handle: int, seq: int, k, v, t: int, stream=0) -> None:
     _check(lib().alaya_append_kv(handle, seq, _ptr(k), _ptr(v), t, stream or None))
 
 
+def alaya_append_kv_step(handle: int, seqs: Sequence[int], k, v, stream=0) -> None:
+    sq = _i32_array(seqs)
+    _check(lib().alaya_append_kv_step(handle, sq, len(seqs), _ptr(k), _ptr(v), stream or None))
+
+
 def alaya_seq_len(handle: int, seq: int) -> int:
     return lib().alaya_seq_len(handle, seq)
 
@@ -254,6 +261,13 @@ class Cache:
         assert k.dtype == self.torch_dtype and v.dtype == self.torch_dtype and k.shape == v.shape
         assert tuple(k.shape[1:]) == (self.cfg.n_kv_heads, self.cfg.head_dim)
         alaya_append_kv(self.handle, seq, k, v, k.shape[0], _stream(stream))
+
+    def append_step(self, seqs: Sequence[int], k, v, stream=None) -> None:
+        """One new token for each listed sequence, one launch: k, v [len(seqs)][n_kv_heads][head_dim]."""
+        assert k.is_cuda and v.is_cuda and k.is_contiguous() and v.is_contiguous()
+        assert k.dtype == self.torch_dtype and v.dtype == self.torch_dtype and k.shape == v.shape
+        assert tuple(k.shape) == (len(seqs), self.cfg.n_kv_heads, self.cfg.head_dim)
+        alaya_append_kv_step(self.handle, seqs, k, v, _stream(stream))
 
     def seq_len(self, seq: int) -> int:
         return alaya_seq_len(self.handle, seq)

@@ -96,6 +96,10 @@ struct Shape {
 hipError_t launch_append(const Shape &sh, const int32_t *page_table_row, void *k_pool, void *v_pool,
                          const void *k, const void *v, int64_t n_old, int64_t t, hipStream_t st);
 
+// one token for each of B sequences; dv.desc[b] holds the page-table row offset and the old length
+hipError_t launch_append_step(const Shape &sh, const DeviceViews &dv, void *k_pool, void *v_pool, const void *k,
+                              const void *v, int B, hipStream_t st);
+
 // phase 0 scores the sampled pages in full, phase 1 the other pages against dv.tau, phase 2 (repair)
 // the other pages of the heads marked in dv.fail against dv.tau_safe.
 // ev0 / ev1: optional events that take the kernel's own begin and end times.

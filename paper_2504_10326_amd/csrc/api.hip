@@ -422,6 +422,74 @@ int alaya_append_kv(alaya_cache *c, int seq, const void *k, const void *v, int64
     return ALAYA_OK;
 }
 
+int alaya_append_kv_step(alaya_cache *c, const int32_t *seqs, int B, const void *k, const void *v, void *stream)
+{
+    if (!c) return fail(ALAYA_E_INVAL, "null cache handle");
+    if (!seqs || !k || !v) return fail(ALAYA_E_INVAL, "null seqs, k or v");
+    if (B <= 0 || B > c->cfg.max_batch) return fail(ALAYA_E_INVAL, "batch %d outside 1..%d", B, c->cfg.max_batch);
+    if (B == 1) return alaya_append_kv(c, seqs[0], k, v, 1, stream); // needs no descriptor copy
+    size_t need = 0;
+    for (int b = 0; b < B; ++b) {
+        if (seqs[b] < 0 || seqs[b] >= c->cfg.max_seqs)
+            return fail(ALAYA_E_INVAL, "entry %d: sequence id %d outside 0..%d", b, seqs[b], c->cfg.max_seqs - 1);
+        for (int a = 0; a < b; ++a)
+            if (seqs[a] == seqs[b]) return fail(ALAYA_E_INVAL, "sequence %d is listed twice", seqs[b]);
+        const int64_t n_old = c->seq_len[(size_t)seqs[b]];
+        if (n_old + 1 > c->cfg.max_tokens_per_seq)
+            return fail(ALAYA_E_NOMEM, "sequence %d would hold %lld tokens, limit %lld", seqs[b],
+                        (long long)(n_old + 1), (long long)c->cfg.max_tokens_per_seq);
+        if (n_old % kPageTokens == 0) ++need;
+    }
+    if (need > c->free_pages.size())
+        return fail(ALAYA_E_NOMEM, "page pool exhausted: %zu pages needed, %zu free", need, c->free_pages.size());
+    hipStream_t st = (hipStream_t)stream;
+    ReqDesc *hd;
+    int slot;
+    int rc = ring_acquire(c, &hd, &slot);
+    if (rc != ALAYA_OK) return rc;
+    if (!c->ring_ev[slot]) {
+        hipError_t e = hipEventCreateWithFlags(&c->ring_ev[slot], hipEventDisableTiming);
+        if (e != hipSuccess) { c->ring_ev[slot] = nullptr; return fail_hip(e, "hipEventCreate"); }
+    }
+    rc = ensure_device(c, st);
+    if (rc != ALAYA_OK) return rc;
+    // From here on pages are taken; on a failure they go back and no length changes.
+    std::vector<int32_t> taken; // sequences that got a page, in order
+    auto rollback = [&]() {
+        for (size_t i = taken.size(); i-- > 0;) {
+            const int s = taken[i];
+            c->free_pages.push_back(c->h_page_table[(size_t)s * c->L.mpps + c->seq_len[(size_t)s] / kPageTokens]);
+        }
+    };
+    for (int b = 0; b < B; ++b) {
+        const int s = seqs[b];
+        const int64_t n_old = c->seq_len[(size_t)s];
+        std::memset(&hd[b], 0, sizeof(ReqDesc));
+        hd[b].pt_off = (int32_t)((int64_t)s * c->L.mpps);
+        hd[b].n = (int32_t)n_old;
+        if (n_old % kPageTokens == 0) {
+            int32_t *row = c->h_page_table + (size_t)s * c->L.mpps;
+            row[n_old / kPageTokens] = c->free_pages.back();
+            c->free_pages.pop_back();
+            taken.push_back(s);
+            hipError_t e = hipMemcpyAsync((int32_t *)c->dv.page_table + (size_t)s * c->L.mpps + n_old / kPageTokens,
+                                          row + n_old / kPageTokens, sizeof(int32_t), hipMemcpyHostToDevice, st);
+            if (e != hipSuccess) { rollback(); return fail_hip(e, "page table copy"); }
+        }
+    }
+    rc = ring_publish(c, slot, B, st);
+    if (rc != ALAYA_OK) { rollback(); return rc; }
+    const Shape sh{c->cfg.dtype, c->cfg.head_dim, c->cfg.n_q_heads, c->cfg.n_kv_heads};
+    hipError_t e;
+    {
+        Timed tm(c, 5, st);
+        e = launch_append_step(sh, c->dv, c->k_pool, c->v_pool, k, v, B, st);
+    }
+    if (e != hipSuccess) { rollback(); return fail_hip(e, "append launch"); }
+    for (int b = 0; b < B; ++b) c->seq_len[(size_t)seqs[b]] += 1;
+    return ALAYA_OK;
+}
+
 int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q,
                       const alaya_sparse_params *p, float *out, void *stream)
 {

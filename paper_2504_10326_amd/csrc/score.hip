@@ -49,6 +49,38 @@ hipError_t launch_append(const Shape &sh, const int32_t *pt_row, void *k_pool, v
     return hipGetLastError();
 }
 
+// One new token for each of B sequences (a decode step of a batch) in one launch.
+//   k, v   [B][H_kv][D]; desc[b].pt_off / desc[b].n = the sequence's page-table row / its length before
+__global__ __launch_bounds__(256) void append_step_kernel(const ReqDesc *__restrict__ desc,
+                                                           const int32_t *__restrict__ page_table,
+                                                           uint4 *__restrict__ k_pool, uint4 *__restrict__ v_pool,
+                                                           const uint4 *__restrict__ k, const uint4 *__restrict__ v,
+                                                           int B, int H_kv, int NC)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= B * H_kv * NC) return;
+    const int c = i % NC;
+    const int kvh = (i / NC) % H_kv;
+    const int b = i / (NC * H_kv);
+    const int tok = desc[b].n;
+    const int phys = page_table[desc[b].pt_off + (tok >> 6)];
+    const int slot = tok & 63;
+    const size_t tile = ((size_t)phys * H_kv + kvh) * (size_t)(NC * 64);
+    k_pool[tile + (size_t)c * 64 + slot] = k[i];
+    v_pool[tile + (size_t)slot * NC + c] = v[i];
+}
+
+hipError_t launch_append_step(const Shape &sh, const DeviceViews &dv, void *k_pool, void *v_pool, const void *k,
+                              const void *v, int B, hipStream_t st)
+{
+    const int NC = sh.head_dim * (sh.dtype == 0 ? 2 : 4) / 16;
+    const int total = B * sh.n_kv_heads * NC;
+    append_step_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(
+        dv.desc, dv.page_table, (uint4 *)k_pool, (uint4 *)v_pool, (const uint4 *)k, (const uint4 *)v, B,
+        sh.n_kv_heads, NC);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------------------
 // Scoring.  Grid: one workgroup per (tile, KV head); KV head is the fastest index so that with
 // 8 KV heads each head's stream stays on one XCD (workgroups are dealt to XCDs round-robin).

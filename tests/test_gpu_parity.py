@@ -122,6 +122,62 @@ def test_dense_survivor_lists_with_several_pages_per_wavefront(ppw):
     c.close()
 
 
+def test_decode_step_append_for_a_batch_matches_single_appends():
+    """alaya_append_kv_step (one launch for the new token of every request) leaves the pools exactly as
+    per-sequence appends do, across page boundaries, and is all-or-nothing on errors."""
+    w = _llama([130, 63, 64, 1], topk=[8, 8, 8, 1])
+    g = wl.generate(wl.resized(w, [200, 200, 200, 200]))
+    dev = lambda a: to_device(a, w.dtype)
+
+    def fresh():
+        c = A.Cache(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, max_seqs=5, max_batch=4, max_tokens_per_seq=256,
+                    max_batch_tokens=1024, n_phys_pages=16)
+        c.k_pool.fill_(0xFF); c.v_pool.fill_(0xFF)
+        for r, n in enumerate(w.lens):
+            c.append_kv(r, dev(g["K"][r][:n]), dev(g["V"][r][:n]))
+        return c
+    a, b = fresh(), fresh()
+    order = [2, 0, 3, 1]                                    # any order of distinct sequences
+    for step in range(70):                                  # every sequence crosses a page boundary
+        ks = np.stack([g["K"][r][w.lens[r] + step] for r in order])
+        vs = np.stack([g["V"][r][w.lens[r] + step] for r in order])
+        a.append_step(order, dev(ks), dev(vs))
+        for i, r in enumerate(order):
+            b.append_kv(r, dev(ks[i:i + 1]), dev(vs[i:i + 1]))
+    torch.cuda.synchronize()
+    assert [a.seq_len(r) for r in range(4)] == [b.seq_len(r) for r in range(4)] == [n + 70 for n in w.lens]
+    q = dev(g["q"])
+    oa = a.sparse_attn([0, 1, 2, 3], q, A.ALAYA_TOPK, topk=[8, 8, 8, 8])
+    ob = b.sparse_attn([0, 1, 2, 3], q, A.ALAYA_TOPK, topk=[8, 8, 8, 8])
+    ref = [oracle.sparse_attn(g["q"][r], g["K"][r][:w.lens[r] + 70], g["V"][r][:w.lens[r] + 70], oracle.TOPK, k=8)["out"]
+           for r in range(4)]
+    torch.cuda.synchronize()
+    assert torch.equal(oa, ob)
+    assert max(np.abs(oa[r].cpu().numpy() - ref[r]).max() for r in range(4)) <= OUT_TOL
+    one = dev(np.stack([g["K"][0][0]] * 2))
+    for seqs, code in [([0, 0], A.ALAYA_E_INVAL), ([0, 9], A.ALAYA_E_INVAL)]:
+        with pytest.raises(A.AlayaError) as e:
+            a.append_step(seqs, one, one)
+        assert e.value.code == code
+    a.close(); b.close()
+    # all or nothing: sequence 1 sits at its length limit, so sequence 0 must not grow either
+    c = A.Cache(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, max_seqs=3, max_batch=3, max_tokens_per_seq=128,
+                max_batch_tokens=384, n_phys_pages=3)
+    c.append_kv(0, dev(g["K"][0][:10]), dev(g["V"][0][:10]))
+    c.append_kv(1, dev(g["K"][1][:128]), dev(g["V"][1][:128]))
+    with pytest.raises(A.AlayaError) as e:
+        c.append_step([0, 1], one, one)
+    assert e.value.code == A.ALAYA_E_NOMEM and [c.seq_len(r) for r in range(3)] == [10, 128, 0]
+    # ... and the pool is empty (3 pages, all in use): the empty sequence 2 cannot get its first page
+    with pytest.raises(A.AlayaError) as e:
+        c.append_step([0, 2], one, one)
+    assert e.value.code == A.ALAYA_E_NOMEM and "exhausted" in str(e.value)
+    assert [c.seq_len(r) for r in range(3)] == [10, 128, 0]
+    c.append_step([0], one[:1], one[:1])                    # still usable
+    assert c.seq_len(0) == 11
+    c.close()
+
+
 # ------------------------------------------------------------------------------------------ window, prefix
 @pytest.mark.parametrize("n,w0,w1", [(9000, 128, 512), (5000, 0, 70), (4100, 3, 0), (700, 400, 400), (64 * 30, 64, 64)])
 def test_window_tokens_are_always_attended(n, w0, w1):
