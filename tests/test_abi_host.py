@@ -135,3 +135,23 @@ def test_null_handle():
     assert L.alaya_seq_len(None, 0) == -1
     assert L.alaya_set_tuning(None, 1, 1, 1, 0) == A.ALAYA_E_INVAL
     assert "null" in A.alaya_last_error()
+
+
+def test_step_append_and_estimate_hook_argument_checks():
+    h = _create()
+    try:
+        for seqs, code in [([0, 0], A.ALAYA_E_INVAL), ([0, 4], A.ALAYA_E_INVAL), ([-1, 0], A.ALAYA_E_INVAL),
+                           ([0, 1, 2, 3, 0], A.ALAYA_E_INVAL)]:          # repeated, out of range, above max_batch
+            with pytest.raises(A.AlayaError) as e:
+                A.alaya_append_kv_step(h, seqs, FAKE[3], FAKE[4])
+            assert e.value.code == code, seqs
+        with pytest.raises(A.AlayaError) as e:
+            A.alaya_append_kv_step(h, [0, 1], 0, FAKE[4])
+        assert e.value.code == A.ALAYA_E_INVAL
+        assert [A.alaya_seq_len(h, s) for s in range(4)] == [0, 0, 0, 0]
+        L = A.lib()
+        assert L.alaya_debug_estimate(h, 3) == A.ALAYA_E_INVAL and L.alaya_debug_estimate(h, -2) == A.ALAYA_E_INVAL
+        assert L.alaya_debug_estimate(h, 2) == A.ALAYA_OK and L.alaya_debug_estimate(h, 0) == A.ALAYA_OK
+        assert L.alaya_debug_estimate(None, 0) == A.ALAYA_E_INVAL
+    finally:
+        A.alaya_destroy_cache(h)
