@@ -35,6 +35,7 @@ namespace alaya {
 constexpr int kSelE = 4;                       // elements per thread per chunk
 constexpr int kSelWaves = kSelectThreads / 64; // 16
 constexpr int kSelChunk = kSelE * kSelectThreads;
+constexpr int kFinSets = 3;                    // chunks of tie-bucket tokens the finishing pass keeps in registers
 static_assert(kSelE * kSelWaves == 64, "the cross-wave scan maps one (e, wave) pair to one lane of wave 0");
 static_assert(kMaxSegPages == 2 * kSelectThreads, "the page-count scan takes two pages per thread");
 
@@ -428,26 +429,31 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
     const bool bucket_rule = head_info[2 * rh] >= 0;
     int count = totA;
 
-    if (bucket_rule && totC <= kSelChunk) {
-        // The usual case: the tie bucket's tokens fit in registers (four per thread, in token order).
-        // They are gathered once, refined from registers, and only the kept ones are written.
+    if (bucket_rule && totC <= kFinSets * kSelChunk) {
+        // The usual case: the tie bucket's tokens fit in registers (kFinSets sets of four per thread,
+        // in token order).  They are gathered once, refined from registers, and only the kept ones
+        // are written.
         const uint32_t b1 = (uint32_t)head_info[2 * rh];
         const int cb = totC;
         int need = dsc.k + dsc.nwin - totA; // 1 <= need <= cb (totA counts the window's tokens too)
-        float v[kSelE];
-        int idv[kSelE];
-        uint32_t key[kSelE];
-        bool in[kSelE];
+        float v[kFinSets][kSelE];
+        int idv[kFinSets][kSelE];
+        uint32_t key[kFinSets][kSelE];
+        bool in[kFinSets][kSelE];
 #pragma unroll
-        for (int e = 0; e < kSelE; ++e) {
-            const int i = e * kSelectThreads + tid;
-            in[e] = i < cb;
-            const int sgm = in[e] ? find_seg(preC, i) : 0;
-            const int np_s = min(dsc.n_pages, (sgm + 1) * dsc.seg_pages) - sgm * dsc.seg_pages;
-            const size_t src = (size_t)sgm * seg_region + (size_t)np_s * kPageTokens - 1 - (size_t)(i - preC[sgm]);
-            v[e] = in[e] ? ls[src] : 0.f;
-            idv[e] = in[e] ? li[src] : 0;
-            key[e] = ord_key(v[e]);
+        for (int s = 0; s < kFinSets; ++s) {
+#pragma unroll
+            for (int e = 0; e < kSelE; ++e) {
+                const int i = s * kSelChunk + e * kSelectThreads + tid;
+                in[s][e] = i < cb;
+                const int sgm = in[s][e] ? find_seg(preC, i) : 0;
+                const int np_s = min(dsc.n_pages, (sgm + 1) * dsc.seg_pages) - sgm * dsc.seg_pages;
+                const size_t src =
+                    (size_t)sgm * seg_region + (size_t)np_s * kPageTokens - 1 - (size_t)(i - preC[sgm]);
+                v[s][e] = in[s][e] ? ls[src] : 0.f;
+                idv[s][e] = in[s][e] ? li[src] : 0;
+                key[s][e] = ord_key(v[s][e]);
+            }
         }
         uint32_t T = 0u; // keep key > T, and the first `ties` tokens with key == T
         int ties = 0;
@@ -455,8 +461,10 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
             for (int i = tid; i < kHistBins; i += kSelectThreads) lh[i] = 0u;
             __syncthreads();
 #pragma unroll
-            for (int e = 0; e < kSelE; ++e)
-                if (in[e]) atomicAdd(&lh[(key[e] >> 10) & 0x7FFu], 1u);
+            for (int s = 0; s < kFinSets; ++s)
+#pragma unroll
+                for (int e = 0; e < kSelE; ++e)
+                    if (in[s][e]) atomicAdd(&lh[(key[s][e] >> 10) & 0x7FFu], 1u);
             __syncthreads();
             block_find_bin(lh, 2048, need, wtot, res);
             const uint32_t b2 = (uint32_t)res[0];
@@ -466,29 +474,39 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
             __syncthreads();
             const uint32_t pre = (b1 << 11) | b2; // key >> 10 of the threshold
 #pragma unroll
-            for (int e = 0; e < kSelE; ++e)
-                if (in[e] && (key[e] >> 10) == pre) atomicAdd(&lh[key[e] & 0x3FFu], 1u);
+            for (int s = 0; s < kFinSets; ++s)
+#pragma unroll
+                for (int e = 0; e < kSelE; ++e)
+                    if (in[s][e] && (key[s][e] >> 10) == pre) atomicAdd(&lh[key[s][e] & 0x3FFu], 1u);
             __syncthreads();
             block_find_bin(lh, 1024, need, wtot, res);
             T = (pre << 10) | (uint32_t)res[0];
             ties = need - res[1];
         }
-        bool fa[kSelE], fb[kSelE];
+        int baseG = 0, baseT = 0; // kept-above and tie tokens in the sets before this one
 #pragma unroll
-        for (int e = 0; e < kSelE; ++e) {
-            fa[e] = in[e] && key[e] > T;
-            fb[e] = in[e] && key[e] == T;
-        }
-        int exA[kSelE], exB[kSelE], tA, tB;
-        chunk_ranks(scan, 0, fa, fb, exA, exB, tA, tB);
+        for (int s = 0; s < kFinSets; ++s) {
+            if (s * kSelChunk >= cb) break; // (uniform)
+            bool fa[kSelE], fb[kSelE];
 #pragma unroll
-        for (int e = 0; e < kSelE; ++e) {
-            if (fa[e] || (fb[e] && exB[e] < ties)) {
-                const int pos = totA + exA[e] + min(exB[e], ties);
-                ids[pos] = idv[e];
-                ss[pos] = v[e];
-                mx = fmaxf(mx, v[e]);
+            for (int e = 0; e < kSelE; ++e) {
+                fa[e] = in[s][e] && key[s][e] > T;
+                fb[e] = in[s][e] && key[s][e] == T;
             }
+            int exA[kSelE], exB[kSelE], tA, tB;
+            chunk_ranks(scan, s & 1, fa, fb, exA, exB, tA, tB);
+#pragma unroll
+            for (int e = 0; e < kSelE; ++e) {
+                const int tb = baseT + exB[e]; // ties before this element
+                if (fa[e] || (fb[e] && tb < ties)) {
+                    const int pos = totA + baseG + exA[e] + min(tb, ties);
+                    ids[pos] = idv[s][e];
+                    ss[pos] = v[s][e];
+                    mx = fmaxf(mx, v[s][e]);
+                }
+            }
+            baseG += tA;
+            baseT += tB;
         }
         count = dsc.k + dsc.nwin;
     } else if (bucket_rule) {

@@ -411,6 +411,32 @@ def test_exact_ties_go_to_the_smaller_id_and_runs_are_identical():
     c.close()
 
 
+@pytest.mark.parametrize("spread", [0.0, 0.04])
+def test_huge_tie_bucket_takes_the_in_place_refinement(spread):
+    """All 30000 keys of a KV head are (nearly) the same vector, so every score falls into the bucket
+    of the k-th largest one: far more candidates than the finishing pass keeps in registers.
+    spread = 0: all scores equal, the k smallest ids must win; 0.04: distinct scores inside one bucket."""
+    n = 30000
+    w = _llama([n], topk=[500])
+    g = wl.generate(w)
+    rng = np.random.default_rng(11)
+    K = g["K"][0].copy()
+    for kvh in range(w.n_kv_heads):
+        u = wl.bf16_bits_to_f32(g["K"][0][7, kvh]).astype(np.float32)
+        scale = 1.0 + spread * rng.random((n, 1), dtype=np.float32)
+        K[:, kvh, :] = wl.to_bf16_bits(u[None, :] * scale)
+    g2 = dict(g, K=[K])
+    c = make_cache(w, g2)
+    for k in (500, 13000):
+        st = run_and_compare(c, w, g2, A.ALAYA_TOPK, topk=[k])
+        assert set(st["counts"]) == {k}
+    if spread == 0.0:
+        q = to_device(g["q"], w.dtype)
+        _, ids, _ = c.sparse_attn([0], q, A.ALAYA_TOPK, topk=[500], ids_stride=500)
+        assert (np.sort(ids.cpu().numpy()[0], axis=1) == np.arange(500)[None, :]).all()
+    c.close()
+
+
 def test_capacity_overflow_is_reported_not_truncated():
     w = _llama([3000], topk=[50])
     g = wl.generate(w)
