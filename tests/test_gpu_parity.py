@@ -231,15 +231,15 @@ def test_estimated_bound_is_verified_and_repaired(force):
     """Large top-k calls filter with an estimated threshold bound; the selection checks it and has the
     heads repaired where it was too high.  force = 1: estimate on these (small) shapes too; force = 2:
     an estimate that is always too high, so that every head takes the repair path."""
-    w = _llama([30000 + 21, 9000], topk=[2048, 600])
+    w = _llama([30000 + 21, 9000, 1500], topk=[2048, 600, 64])   # the third request is too small to estimate
     g = wl.generate(w)
     c = make_cache(w, g)
     c.debug_estimate(force)
     for ppw in (0, 4):
         c.set_tuning(ppw, 0, 0)
-        run_and_compare(c, w, g, A.ALAYA_TOPK, topk=[2048, 600])
-        run_and_compare(c, w, g, A.ALAYA_TOPK, topk=[700, 5000], window=(100, 300), check_scores=False)
-    run_and_compare(c, w, g, A.ALAYA_DIPR, beta=[2.0, 2.0], check_scores=False)   # DIPR never estimates
+        run_and_compare(c, w, g, A.ALAYA_TOPK, topk=[2048, 600, 64])
+        run_and_compare(c, w, g, A.ALAYA_TOPK, topk=[700, 5000, 1000], window=(100, 300), check_scores=False)
+    run_and_compare(c, w, g, A.ALAYA_DIPR, beta=[2.0, 2.0, 1.0], check_scores=False)   # DIPR never estimates
     c.close()
 
 
