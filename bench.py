@@ -216,7 +216,14 @@ def main() -> int:
                            oracle.TOPK if w.mode == "topk" else oracle.DIPR,
                            k=w.topk[0] if w.topk else 0, beta=args.beta, want_ids=False, threads=1, window=window)
         dt1 = time.perf_counter() - t1
+        model = ""
+        try:
+            with open("/proc/cpuinfo") as f:
+                model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), "")
+        except OSError:
+            pass
         cpu = {"value": w.n_q_heads * n * reps / dt, "unit": "keys/s", "cores": int(res["threads"]),
+               "cpu_model": model, "host_cpus": os.cpu_count(),
                "kind": "oracle", "single_thread_value": G * n / dt1,
                "sample": f"{reps} full steps of request 0 ({n} tokens x {w.n_q_heads} heads each), "
                          f"{dt:.2f} s wall, about {cpu_s:.0f} s of CPU time"}
