@@ -123,7 +123,6 @@ struct alaya_cache {
     bool dev_ready;
     int tune_ppw, tune_splits, tune_seg, tune_noprune;
     int estimate_mode; // alaya_debug_estimate
-    int last_ppw; // pages per wavefront of the last sparse call (layout of the survivor lists)
     int last_pages, last_heads;
     int64_t last_pages_a, last_pages_b; // pages of the last sparse call scored by the sample / the main pass
     // profiling
@@ -342,7 +341,6 @@ int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k
     c->tune_seg = 0;
     c->tune_noprune = 0;
     c->estimate_mode = 0;
-    c->last_ppw = 0;
     c->last_pages = c->last_heads = 0;
     c->last_pages_a = c->last_pages_b = 0;
     c->prof = false;
@@ -636,7 +634,6 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
         tiles += (n_a + kScoreWaves - 1) / kScoreWaves;                                  // one page per wavefront
         if (S > 1) tiles_b += (int)((d.n_pages + (int64_t)kScoreWaves * cp - 1) / ((int64_t)kScoreWaves * cp));
     }
-    c->last_ppw = ppw;
     c->last_pages = all_pages;
     c->last_pages_a = pages_a;
     c->last_pages_b = all_pages - pages_a;

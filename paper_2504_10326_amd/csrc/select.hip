@@ -521,7 +521,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
         }
         __syncthreads(); // candidates visible to the whole workgroup
         const uint32_t b1 = (uint32_t)head_info[2 * rh];
-        const int above1 = totA; // == head_info[2 * rh + 1]: every token above bucket b1
+        const int above1 = totA; // every window token and every token above bucket b1
         const int cb = totC;
         int need = dsc.k + dsc.nwin - above1; // 1 <= need <= cb (above1 counts the window's tokens too)
         int parity = 0;
