@@ -285,6 +285,32 @@ def test_permuted_pages_do_not_change_the_answer():
     c1.close(); c2.close()
 
 
+def test_pages_out_of_order_stay_right_while_the_sequence_grows():
+    """A sequence whose pages were handed out in shuffled order: decode steps across several page
+    boundaries, a prefix query and a reset-and-refill must all keep matching the oracle."""
+    base = wl.resized(wl.config("paged_1m"), [9000 + 200], topk=[300])
+    g = wl.generate(base)
+    w = wl.resized(base, [9000], topk=[300])
+    gw = dict(g, K=[g["K"][0][:9000]], V=[g["V"][0][:9000]])
+    c = make_cache(w, gw, extra_tokens=400)
+    assert w.permute_pages
+    run_and_compare(c, w, gw, A.ALAYA_TOPK, topk=[300])
+    for step in range(200):                                   # crosses three page boundaries
+        j = 9000 + step
+        c.append_kv(0, to_device(g["K"][0][j:j + 1], w.dtype), to_device(g["V"][0][j:j + 1], w.dtype))
+        if step in (0, 63, 64, 130, 199):
+            wj = wl.resized(base, [j + 1], topk=[300])
+            gj = dict(g, K=[g["K"][0][:j + 1]], V=[g["V"][0][:j + 1]])
+            run_and_compare(c, wj, gj, A.ALAYA_TOPK, topk=[300], check_scores=False)
+            run_and_compare(c, wj, gj, A.ALAYA_DIPR, beta=[1.5], check_scores=False)
+    run_and_compare(c, base, g, A.ALAYA_TOPK, topk=[300], n_visible=[5000], window=(10, 70), check_scores=False)
+    c.reset_seq(0)
+    c.append_kv(0, to_device(g["K"][0][:7000], w.dtype), to_device(g["V"][0][:7000], w.dtype))
+    w7 = wl.resized(base, [7000], topk=[300])
+    run_and_compare(c, w7, dict(g, K=[g["K"][0][:7000]], V=[g["V"][0][:7000]]), A.ALAYA_TOPK, topk=[300])
+    c.close()
+
+
 def test_token_permutation_invariance_on_gpu():
     """Permuting the cached tokens maps the selected set through the permutation and keeps the output."""
     w = _llama([4000], topk=[300])
