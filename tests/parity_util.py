@@ -1,7 +1,7 @@
 """Shared pieces of the GPU parity tests: load a workload into a Cache, run the HIP path, and compare
 with the CPU oracle to the stated bar.
 
-Bar (stated by the benchmark spec, derived in the design doc):
+Bar:
   * selected sets: identical, except for tokens whose ORACLE score lies within BAND = 1e-4 of the
     selection boundary (the oracle's k-th largest score for top-k, its max - beta for DIPR);
   * outputs: max-abs <= OUT_TOL = 2e-3 against the oracle on its own set; if the sets differ (only
