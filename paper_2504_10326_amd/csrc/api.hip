@@ -583,7 +583,8 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
         int S = 1;
         d.k_est = 0;
         if (!c->tune_noprune && pages >= 4) {
-            if (p->mode == ALAYA_TOPK && estimate && d.k >= 512 && pages >= 64) {
+            // (never when top-k takes every token outside the window: nothing checks the bound then)
+            if (p->mode == ALAYA_TOPK && estimate && d.k >= 512 && d.k < n_out && pages >= 64) {
                 // Estimated bound (large calls): a 1-in-S sample holds about mu = k / S of the k best
                 // scores, so its (mu + 6 sqrt(mu) + 8)-th largest score lies below the true threshold
                 // unless the sample is far from representative - which the selection detects and

@@ -508,3 +508,37 @@ def test_custom_scale_and_profiling_hooks():
     assert t["sample"]["launches"] == 6 and t["sample"]["sum_ms"] > 0 and t["combine"]["launches"] == 6
     assert 0 < t["score"]["launches"] <= 6        # the main scoring pass runs only when there is something to prune
     c.close()
+
+
+# ------------------------------------------------------------------------------------------ random sweep
+@pytest.mark.parametrize("seed", list(range(24)) + [63])   # 63: top-k of everything under a forced estimate
+def test_random_configurations_against_the_oracle(seed):
+    """Seeded random shapes and parameters: head counts, head dim, dtype, ragged batches, k, beta, window,
+    visible prefixes, launch knobs, estimate mode - each call checked against the oracle, pruned against
+    unpruned."""
+    rng = np.random.default_rng(1000 + seed)
+    hk = int(rng.choice([1, 2, 4, 8]))
+    G = int(rng.choice([1, 2, 4, 8]))
+    d = int(rng.choice([64, 128]))
+    dtype = str(rng.choice(["bf16", "f32"]))
+    B = int(rng.integers(1, 5))
+    lens = [int(rng.choice([1, 2, 63, 64, 65, int(rng.integers(100, 700)), int(rng.integers(700, 9000))])) for _ in range(B)]
+    w = wl.Workload(f"rnd{seed}", hk * G, hk, d, tuple(lens), dtype, 8, "topk", topk=tuple(1 for _ in lens),
+                    permute_pages=bool(rng.integers(0, 2)), seed=seed)
+    g = wl.generate(w, threads=1)
+    c = make_cache(w, g)
+    for it in range(4):
+        c.set_tuning(int(rng.choice([0, 1, 2, 8])), int(rng.choice([0, 1, 5])), int(rng.choice([0, 16, 300])))
+        c.debug_estimate(int(rng.choice([0, 1, 2, -1])))
+        window = (int(rng.choice([0, 0, 3, 64, 200])), int(rng.choice([0, 0, 1, 70, 500])))
+        vis = [int(rng.integers(1, n + 1)) for n in lens] if rng.integers(0, 2) else None
+        if rng.integers(0, 2):
+            ks = [int(rng.choice([1, 7, 64, 600, 5000])) for _ in lens]
+            run_and_compare(c, w, g, A.ALAYA_TOPK, topk=ks, window=window, n_visible=vis, ids_stride=max(lens))
+        else:
+            betas = [float(rng.choice([0.0, 0.3, 1.0, 3.0, 20.0])) for _ in lens]
+            run_and_compare(c, w, g, A.ALAYA_DIPR, beta=betas, window=window, n_visible=vis, ids_stride=max(lens))
+    full = c.full_attn(list(range(B)), to_device(g["q"], dtype)).cpu().numpy()
+    for r in range(B):
+        assert np.abs(full[r] - oracle.full_attn(g["q"][r], g["K"][r], g["V"][r])).max() <= OUT_TOL
+    c.close()
