@@ -155,3 +155,14 @@ def test_step_append_and_estimate_hook_argument_checks():
         assert L.alaya_debug_estimate(None, 0) == A.ALAYA_E_INVAL
     finally:
         A.alaya_destroy_cache(h)
+
+
+def test_bench_refuses_more_than_one_gpu_and_has_no_cpu_fallback():
+    import subprocess
+    import sys
+    import torch
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+    if not torch.cuda.is_available():
+        r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")], capture_output=True, text=True)
+        assert r.returncode != 0 and "no GPU" in r.stderr and r.stdout.strip() == ""
