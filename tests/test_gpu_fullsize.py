@@ -85,3 +85,58 @@ def test_batched_16_requests_one_launch():
     _say(f"batched_16: lens {w.lens}, out err {st['max_out_err']:.2e}, score err {st['max_score_err']:.2e}, "
          f"band heads {st['band_heads']}")
     c.close()
+
+
+def test_largest_context_the_selection_layout_takes():
+    """131072 pages = 8388608 tokens in one sequence (34 GB of pools): top-k, DIPR, window and dense
+    attention for the four heads of KV head 0 against the oracle; one page more is refused."""
+    n = 131072 * 64
+    c = A.Cache(32, 8, 128, "bf16", max_seqs=1, max_batch=1, max_tokens_per_seq=n + 128, max_batch_tokens=n + 128,
+                n_phys_pages=n // 64 + 4)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(0)
+    K0 = np.empty((n, 1, 128), dtype=np.uint16)
+    V0 = np.empty((n, 1, 128), dtype=np.uint16)
+    for a in range(0, n, 1 << 19):                             # keys and values drawn on the device, KV head 0 kept
+        m = min(1 << 19, n - a)
+        kk = torch.randn((m, 8, 128), device="cuda", generator=gen).to(torch.bfloat16)
+        vv = torch.randn((m, 8, 128), device="cuda", generator=gen).to(torch.bfloat16)
+        c.append_kv(0, kk, vv)
+        K0[a:a + m, 0] = kk[:, 0].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+        V0[a:a + m, 0] = vv[:, 0].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    q = (torch.randn((1, 32, 128), device="cuda", generator=gen) * 0.15).to(torch.bfloat16)
+    qh = q[0, :4].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    _say(f"largest context: {n} tokens loaded")
+    for mode, kw, okw in [(A.ALAYA_TOPK, dict(topk=[8192]), dict(k=8192)),
+                          (A.ALAYA_DIPR, dict(beta=[1.0]), dict(beta=1.0)),
+                          (A.ALAYA_TOPK, dict(topk=[8192], window=(128, 512)), dict(k=8192, window=(128, 512)))]:
+        out, ids, counts = c.sparse_attn([0], q, mode, ids_stride=20000, **kw)
+        torch.cuda.synchronize()
+        assert c.poll_status() == A.ALAYA_OK
+        ref = oracle.sparse_attn(qh, K0, V0, oracle.TOPK if mode == A.ALAYA_TOPK else oracle.DIPR, want_scores=True,
+                                 **okw)
+        out, ids, counts = out.cpu().numpy(), ids.cpu().numpy(), counts.cpu().numpy()
+        for h in range(4):
+            s = ref["scores"][h]
+            got = ids[0, h, :counts[0, h]]
+            if mode == A.ALAYA_TOPK:
+                w0, w1 = okw.get("window", (0, 0))
+                outside = np.ones(n, dtype=bool)
+                outside[:w0] = False
+                outside[n - w1:] = False
+                edge = s[ref["ids"][h][outside[ref["ids"][h]]]].min()
+            else:
+                edge = s.max() - 1.0
+            diff = np.setxor1d(got, ref["ids"][h])
+            assert diff.size == 0 or np.abs(s[diff] - edge).max() <= 1e-4
+            want = ref["out"][h] if diff.size == 0 else oracle.attend(s, V0, 0, np.sort(got))
+            assert np.abs(out[0, h] - want).max() <= OUT_TOL
+        _say(f"largest context, mode {mode} {kw}: selected {counts[0, :4].tolist()}")
+    full = c.full_attn([0], q).cpu().numpy()
+    assert np.abs(full[0, :4] - oracle.full_attn(qh, K0, V0)).max() <= OUT_TOL
+    c.append_kv(0, q.new_zeros((64, 8, 128)), q.new_zeros((64, 8, 128)))     # page 131073
+    with pytest.raises(A.AlayaError) as e:
+        c.sparse_attn([0], q, A.ALAYA_TOPK, topk=[8])
+    assert e.value.code == A.ALAYA_E_INVAL and "selection layout" in str(e.value)
+    assert np.isfinite(c.full_attn([0], q).cpu().numpy()).all()              # dense attention has no such limit
+    c.close()
