@@ -147,6 +147,8 @@ typedef struct {
  * out_ids / out_counts cover window and retrieved tokens alike.
  * Prefix (Sec. 7.1 "Flexible Context Reuse"): with n_visible set, the query runs as if the sequence
  * ended after n_visible[b] tokens; "last" window tokens are then the last visible ones.
+ * A request may see at most 131072 pages (8388608 tokens); a longer one is refused with
+ * ALAYA_E_INVAL (alaya_full_attn has no such limit).
  * Selection runs on raw fp32 inner products (bf16 products are exact in fp32; accumulation is fp32).
  * Among equal scores at the k-th place the smaller token id is taken, so results are reproducible.
  * out_ids come back in an unspecified but deterministic order.  If a set is larger than ids_stride
