@@ -542,3 +542,19 @@ def test_random_configurations_against_the_oracle(seed):
     for r in range(B):
         assert np.abs(full[r] - oracle.full_attn(g["q"][r], g["K"][r], g["V"][r])).max() <= OUT_TOL
     c.close()
+
+
+def test_many_small_requests_in_one_call():
+    """128 requests of 1 .. 3000 tokens in one call: top-k, DIPR with a window, dense attention."""
+    rng = np.random.default_rng(3)
+    B = 128
+    lens = [int(rng.integers(1, 3000)) for _ in range(B)]
+    w = wl.Workload("many", 8, 2, 128, tuple(lens), "bf16", 8, "topk", topk=tuple(1 for _ in lens), seed=1)
+    g = wl.generate(w, threads=8)
+    c = make_cache(w, g)
+    run_and_compare(c, w, g, A.ALAYA_TOPK, topk=[int(rng.integers(1, 400)) for _ in lens], ids_stride=3000)
+    run_and_compare(c, w, g, A.ALAYA_DIPR, beta=[float(rng.choice([0.0, 1.0, 4.0])) for _ in lens], ids_stride=3000,
+                    window=(2, 30), check_scores=False)
+    full = c.full_attn(list(range(B)), to_device(g["q"], w.dtype)).cpu().numpy()
+    assert max(np.abs(full[r] - oracle.full_attn(g["q"][r], g["K"][r], g["V"][r])).max() for r in range(B)) <= OUT_TOL
+    c.close()
