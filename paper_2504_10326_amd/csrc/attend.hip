@@ -177,8 +177,10 @@ __global__ __launch_bounds__(D) void combine_kernel(const ReqDesc *__restrict__ 
     }
     // loads are issued eight at a time so that their latencies overlap; the merge order stays fixed
     constexpr int U = 8;
+    // The splits of a sparse call all subtracted the same maximum (or hold nothing): no rescaling, and
+    // no need to look for the largest reference first.
     float M = -INFINITY;
-    for (int i0 = 0; i0 < np; i0 += U) {
+    for (int i0 = 0; per_request_tiles && i0 < np; i0 += U) {
         float mm[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) mm[u] = i0 + u < np ? partials[first + (size_t)(i0 + u) * stride] : -INFINITY;
@@ -198,7 +200,7 @@ __global__ __launch_bounds__(D) void combine_kernel(const ReqDesc *__restrict__ 
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const float w = mm[u] == -INFINITY ? 0.f : __expf(mm[u] - M);
+            const float w = mm[u] == -INFINITY ? 0.f : per_request_tiles ? __expf(mm[u] - M) : 1.f;
             L = fmaf(w, ll[u], L);
             o = fmaf(w, aa[u], o);
         }
