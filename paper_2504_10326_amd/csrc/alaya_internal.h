@@ -41,8 +41,17 @@ struct ReqDesc {
     int32_t w0, w1;        // window: tokens j < w0 and j >= n - w1 are always selected
     int32_t nwin;          // tokens in the window: min(n, w0 + w1)
     int32_t k_est;         // top-k: rank in the sample that the ESTIMATED bound is read at; 0 = guaranteed bound only
+    int32_t xf, xb;        // the sample pass also scores the pages [0, xf) and [xb, n_pages) in full: DIPR with a
+                           // window, whose tokens seed the maximum (Sec. 7.1); both are multiples of chunk_pages
+                           // (0 and n_pages otherwise)
 };
-static_assert(sizeof(ReqDesc) == 80, "ReqDesc layout");
+static_assert(sizeof(ReqDesc) == 88, "ReqDesc layout");
+
+// A page that the sample pass scored in full (the main pass and the statistics leave it out).
+__device__ __forceinline__ bool sampled_page(const ReqDesc &d, int p)
+{
+    return (p & (d.sample_stride - 1)) == 0 || p < d.xf || p >= d.xb;
+}
 
 // A window token is always selected, and top-k neither counts nor ranks it.
 __device__ __forceinline__ bool in_window(const ReqDesc &d, int j) { return j < d.w0 || j >= d.n - d.w1; }

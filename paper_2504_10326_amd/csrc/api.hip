@@ -3,6 +3,7 @@
 #include "../../include/alaya.h"
 #include "alaya_internal.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -609,7 +610,6 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
         const double f = p->mode == ALAYA_TOPK && S > 1 ? (double)(d.k_est > 0 ? d.k_est : d.k) * S / (double)n : 0.0;
         if (f > survive) survive = f;
         all_pages += (int)pages;
-        pages_a += (pages + S - 1) / S;
         segs += d.nseg;
         off += (int64_t)n_q_heads * d.head_stride;
     }
@@ -626,10 +626,24 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
     for (int b = 0; b < B; ++b) {
         ReqDesc &d = hd[b];
         const int S = d.sample_stride;
-        const int n_a = (d.n_pages + S - 1) / S;
         int cp = 1; // pages per wavefront in the main pass: a power of two, at most min(ppw, S)
         while (2 * cp <= ppw && 2 * cp <= S) cp *= 2;
         d.chunk_pages = cp;
+        // DIPR with a window (Sec. 7.1): the maximum mostly sits among the window's tokens, which are
+        // attended anyway, so the pages that hold them join the sample and seed the bound.  Whole
+        // main-pass chunks, so that a chunk never mixes the two kinds of page.
+        d.xf = 0;
+        d.xb = d.n_pages;
+        if (p->mode == ALAYA_DIPR && S > 1 && d.nwin > 0) {
+            const int wp0 = (d.w0 + kPageTokens - 1) / kPageTokens;
+            const int pb = d.w1 > 0 ? (d.n - d.w1) / kPageTokens : d.n_pages;
+            d.xf = std::min(d.n_pages, (wp0 + cp - 1) / cp * cp);
+            d.xb = std::max(d.xf, pb / cp * cp);
+        }
+        const int every = (d.n_pages + S - 1) / S;
+        auto not_every = [S](int a, int b) { return (b - a) - ((b + S - 1) / S - (a + S - 1) / S); }; // in [a, b)
+        pages_a += every + not_every(0, d.xf) + not_every(d.xb, d.n_pages);
+        const int n_a = every + d.xf + (d.n_pages - d.xb); // wavefronts of the sample pass
         d.tile_start = tiles;
         d.tileb_start = tiles_b;
         tiles += (n_a + kScoreWaves - 1) / kScoreWaves;                                  // one page per wavefront
@@ -716,6 +730,7 @@ int alaya_full_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, c
         d.sample_stride = 1;
         d.chunk_pages = 1;
         d.w0 = d.w1 = d.nwin = d.k_est = 0;
+        d.xf = d.xb = 0;
         tiles += (int)((pages + ppt - 1) / ppt);
     }
     if (tiles > c->L.max_tiles) return fail(ALAYA_E_NOMEM, "partial-result workspace too small");

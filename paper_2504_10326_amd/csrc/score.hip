@@ -164,15 +164,24 @@ __device__ __forceinline__ void score_block(const int block, const ReqDesc *__re
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int S = dsc.sample_stride;
-    // Phase 0: wavefront w of the request takes the sampled page w * S.  Phase 1: it takes the aligned
+    // Phase 0: wavefront w of the request takes the sampled page w * S; the wavefronts after those take
+    // the pages [0, xf) and [xb, n_pages) that hold a DIPR window (one of these may be an S-th page
+    // too: it is then scored twice, with the same result).  Phase 1: wavefront w takes the aligned
     // chunk of `cp` consecutive pages [w * cp, (w + 1) * cp) without the sampled ones; cp is a power of
-    // two <= S, so a sampled page can only be the first page of a chunk.
+    // two <= S and divides xf and xb, so a chunk is either all window pages or holds at most one
+    // sampled page, its first.
     const int w_req = (tile - (phase == 0 ? dsc.tile_start : dsc.tileb_start)) * kScoreWaves + wave;
     const int cp = phase == 0 ? 1 : dsc.chunk_pages;
-    const int p_first = phase == 0 ? w_req * S : w_req * cp;
+    int p_first = w_req * cp;
+    if (phase == 0) {
+        const int ns = (dsc.n_pages + S - 1) >> (__ffs(S) - 1); // every S-th page
+        const int x = w_req - ns;
+        p_first = x < 0 ? w_req * S : x < dsc.xf ? x : dsc.xb + (x - dsc.xf);
+    }
     const int p_end = min(p_first + cp, dsc.n_pages);
     const int p_begin = (phase == 1 && (p_first & (S - 1)) == 0) ? p_first + 1 : p_first;
     if (PHASE == 1 && p_begin >= p_end) return;                  // whole wavefront; the main pass has no barriers
+    if (phase == 1 && (p_first < dsc.xf || p_first >= dsc.xb)) return; // window pages: the sample pass had them
     const uint4 *qh = (const uint4 *)(qw + (size_t)rh0 * QW);    // wave-uniform address: scalar loads
 
     uint32_t tau[G], tau_hi[G]; // keep key >= tau; repair pass: count tau <= key < tau_hi

@@ -228,8 +228,8 @@ __global__ __launch_bounds__(kSelectThreads) void select_stats_kernel(
         for (int i = tid; i < kHistBins; i += kSelectThreads) lh[i] = 0u;
     int a0, a1;
     SegView v = begin_segment(dsc, H_q, id.h, id.seg, page_cnt, a0, a1);
-    if (((v.p_begin + 2 * tid) & (S - 1)) == 0) a0 = 0;
-    if (((v.p_begin + 2 * tid + 1) & (S - 1)) == 0) a1 = 0;
+    if (sampled_page(dsc, v.p_begin + 2 * tid)) a0 = 0;
+    if (sampled_page(dsc, v.p_begin + 2 * tid + 1)) a1 = 0;
     scan_segment(v, a0, a1, off, wtot); // barriers inside
     float m = -INFINITY;
     constexpr int U = 4; // independent loads per thread and step

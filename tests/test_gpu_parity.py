@@ -196,6 +196,33 @@ def test_window_tokens_are_always_attended(n, w0, w1):
     c.close()
 
 
+def test_dipr_bound_is_seeded_by_the_window():
+    """Sec. 7.1 (window caching enhanced DIPR): the key with the largest inner product mostly lies in the
+    window, so the window's pages are scored with the sample and seed the bound: hardly any score of
+    the other pages is then kept.  Here every head's best key is planted among the last 512 tokens, on
+    pages that the every-S-th-page sample does not take."""
+    n = 40000
+    w = _llama([n])
+    g = wl.generate(w)
+    q = wl.bf16_bits_to_f32(g["q"])[0].astype(np.float64)
+    for h in range(w.n_q_heads):
+        pos = n - 500 + 8 * h                                   # pages 617 .. 621: no multiple of 16
+        g["K"][0][pos, h // w.group, :] = wl.to_bf16_bits((30.0 / (q[h] @ q[h]) * q[h]).astype(np.float32))
+    c = make_cache(w, g)
+    kept = {}
+    for window in ((128, 512), (0, 0)):
+        for ppw in (0, 4):
+            c.set_tuning(ppw, 0, 0, False)
+            st = run_and_compare(c, w, g, A.ALAYA_DIPR, beta=[8.0], window=window, ids_stride=n)
+            assert min(st["counts"]) >= sum(window) + (window == (0, 0))
+            run_and_compare(c, w, g, A.ALAYA_DIPR, beta=[8.0], window=window, ids_stride=n, check_scores=False)
+            kept[window, ppw] = c.debug_survivors() / (n * w.n_q_heads)
+    c.close()
+    for ppw in (0, 4):
+        # with the window: the sampled pages (1 in 16, written in full), the window, and little else
+        assert kept[(128, 512), ppw] < 0.10 < 0.25 < kept[(0, 0), ppw], kept
+
+
 def test_prefix_queries_ignore_what_lies_behind_the_prefix():
     """Sec. 7.1 flexible context reuse: the query sees only the first n_visible tokens of each request."""
     w = _llama([6000, 3000, 4500], topk=[64, 64, 64])
