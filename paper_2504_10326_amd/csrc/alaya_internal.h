@@ -47,6 +47,23 @@ struct ReqDesc {
 };
 static_assert(sizeof(ReqDesc) == 88, "ReqDesc layout");
 
+// How the kernels get at the request descriptors.  A call of one request carries its descriptor in
+// the kernel arguments, which saves the host-to-device copy (a 4 us blit ahead of the first kernel of
+// every step); calls of more requests read the copy in the workspace.  (One only: indexing an array
+// in the arguments makes the compiler treat the descriptor as varying from lane to lane.)
+constexpr int kInlineDescs = 1;
+struct DescArgs { // host side: what the launchers hand to every kernel as (mem, in, n)
+    const ReqDesc *mem; // device copy, [n]; valid when n > 1
+    ReqDesc in;         // valid when n == 1
+    int32_t n;          // requests in this call
+};
+struct Descs { // device side, built from those three kernel arguments
+    const ReqDesc *__restrict__ mem;
+    const ReqDesc &in;
+    int n;
+    __device__ __forceinline__ ReqDesc operator[](int r) const { return n == 1 ? in : mem[r]; }
+};
+
 // A page that the sample pass scored in full (the main pass and the statistics leave it out).
 __device__ __forceinline__ bool sampled_page(const ReqDesc &d, int p)
 {
@@ -59,7 +76,7 @@ __device__ __forceinline__ bool in_window(const ReqDesc &d, int j) { return j < 
 // Device views handed to the launchers.  "per-token arrays" hold one element per (query head, token):
 // a request's block starts at score_off and spans n_q_heads * head_stride elements.
 struct DeviceViews {
-    const ReqDesc *desc;       // [B]
+    DescArgs desc;             // the call's request descriptors
     const int32_t *page_table; // [max_seqs][max_pages_per_seq]
     const void *k_pool;
     const void *v_pool;

@@ -205,9 +205,17 @@ int ring_acquire(alaya_cache *c, ReqDesc **slot, int *idx)
     return ALAYA_OK;
 }
 
+// Hands the descriptors in ring slot idx to the kernels launched after this: in their arguments for a
+// small call, through an asynchronous copy into the workspace otherwise.
 int ring_publish(alaya_cache *c, int idx, int B, hipStream_t st)
 {
-    hipError_t e = hipMemcpyAsync((void *)c->dv.desc, c->h_desc + (size_t)idx * c->cfg.max_batch,
+    const ReqDesc *src = c->h_desc + (size_t)idx * c->cfg.max_batch;
+    c->dv.desc.n = B;
+    if (B <= kInlineDescs) {
+        c->dv.desc.in = src[0];
+        return ALAYA_OK; // the slot is free again at once
+    }
+    hipError_t e = hipMemcpyAsync((void *)c->dv.desc.mem, src,
                                   (size_t)B * sizeof(ReqDesc), hipMemcpyHostToDevice, st);
     if (e != hipSuccess) return fail_hip(e, "descriptor copy");
     e = hipEventRecord(c->ring_ev[idx], st);
@@ -294,7 +302,8 @@ int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k
     c->ws = (char *)workspace;
     c->k_pool = k_pool;
     c->v_pool = v_pool;
-    c->dv.desc = (const ReqDesc *)(c->ws + L.desc);
+    c->dv.desc.mem = (const ReqDesc *)(c->ws + L.desc);
+    c->dv.desc.n = 0;
     c->dv.page_table = (const int32_t *)(c->ws + L.page_table);
     c->dv.k_pool = k_pool;
     c->dv.v_pool = v_pool;

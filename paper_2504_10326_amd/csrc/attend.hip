@@ -49,11 +49,12 @@ constexpr int kAttendU = 4;
 
 template <int DT, int D>
 __global__ __launch_bounds__(kAttendThreads) void attend_kernel(
-    const ReqDesc *__restrict__ desc, int H_q, int H_kv, const int32_t *__restrict__ page_table,
+    const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int H_q, int H_kv, const int32_t *__restrict__ page_table,
     const char *__restrict__ v_pool, const int32_t *__restrict__ sel_ids, const float *__restrict__ sel_scores,
     const int32_t *__restrict__ counts, const float *__restrict__ head_M, float scale, int splits,
     float *__restrict__ partials)
 {
+    const Descs desc{desc_mem, desc0, desc_n};
     using RS = RowSlice<DT, D>;
     constexpr int EPL = RS::EPL;
     constexpr size_t ROW_BYTES = (size_t)D * (DT == 0 ? 2 : 4);
@@ -140,7 +141,7 @@ hipError_t launch_attend(const Shape &sh, const DeviceViews &dv, int B, float sc
 {
     const dim3 grid((unsigned)(B * sh.n_q_heads * splits)), block(kAttendThreads);
 #define ALAYA_ATTEND(DT, D)                                                                                  \
-    attend_kernel<DT, D><<<grid, block, 0, st>>>(dv.desc, sh.n_q_heads, sh.n_kv_heads, dv.page_table,        \
+    attend_kernel<DT, D><<<grid, block, 0, st>>>(dv.desc.mem, dv.desc.in, dv.desc.n, sh.n_q_heads, sh.n_kv_heads, dv.page_table,        \
                                                  (const char *)dv.v_pool, dv.sel_ids, dv.sel_scores, dv.counts, \
                                                  dv.head_M, scale, splits, dv.partials)
     if (sh.dtype == 0 && sh.head_dim == 128) ALAYA_ATTEND(0, 128);
@@ -155,11 +156,12 @@ hipError_t launch_attend(const Shape &sh, const DeviceViews &dv, int B, float sc
 // ------------------------------------------------------------------------------------------------
 // Merge of partial results, fixed order.  Grid: (request, head); one thread per output channel.
 template <int D>
-__global__ __launch_bounds__(D) void combine_kernel(const ReqDesc *__restrict__ desc, int B, int H_q,
+__global__ __launch_bounds__(D) void combine_kernel(const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int B, int H_q,
                                                      const float *__restrict__ partials, int splits,
                                                      int per_request_tiles, int pages_per_tile,
                                                      float *__restrict__ out)
 {
+    const Descs desc{desc_mem, desc0, desc_n};
     const int rh = blockIdx.x;
     const int r = rh / H_q, h = rh % H_q;
     int np;
@@ -213,10 +215,10 @@ hipError_t launch_combine(const Shape &sh, const DeviceViews &dv, int B, int spl
 {
     const dim3 grid((unsigned)(B * sh.n_q_heads));
     if (sh.head_dim == 128)
-        combine_kernel<128><<<grid, dim3(128), 0, st>>>(dv.desc, B, sh.n_q_heads, dv.partials, splits,
+        combine_kernel<128><<<grid, dim3(128), 0, st>>>(dv.desc.mem, dv.desc.in, dv.desc.n, B, sh.n_q_heads, dv.partials, splits,
                                                         per_request_tiles, pages_per_tile, out);
     else if (sh.head_dim == 64)
-        combine_kernel<64><<<grid, dim3(64), 0, st>>>(dv.desc, B, sh.n_q_heads, dv.partials, splits,
+        combine_kernel<64><<<grid, dim3(64), 0, st>>>(dv.desc.mem, dv.desc.in, dv.desc.n, B, sh.n_q_heads, dv.partials, splits,
                                                       per_request_tiles, pages_per_tile, out);
     else
         return hipErrorInvalidValue;
@@ -229,13 +231,14 @@ hipError_t launch_combine(const Shape &sh, const DeviceViews &dv, int B, int spl
 // online softmax per head, probabilities through LDS, then the page's value rows with 16 lanes per
 // row.  The four wavefronts' results are merged before the partial is written.
 template <int DT, int D, int G>
-__global__ __launch_bounds__(256) void full_partial_kernel(const ReqDesc *__restrict__ desc, int B,
+__global__ __launch_bounds__(256) void full_partial_kernel(const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int B,
                                                             const int32_t *__restrict__ page_table,
                                                             const void *__restrict__ qv,
                                                             const uint4 *__restrict__ k_pool,
                                                             const char *__restrict__ v_pool, float scale, int H_kv,
                                                             int ppt, float *__restrict__ partials)
 {
+    const Descs desc{desc_mem, desc0, desc_n};
     using RS = RowSlice<DT, D>;
     constexpr int EPL = RS::EPL;
     constexpr int E = DT == 0 ? 8 : 4;
@@ -382,7 +385,7 @@ static hipError_t launch_full_g(const Shape &sh, const DeviceViews &dv, int B, c
     const int G = sh.n_q_heads / sh.n_kv_heads;
     const dim3 grid((unsigned)(total_tiles * sh.n_kv_heads)), block(256);
 #define ALAYA_FULL(GG)                                                                                     \
-    full_partial_kernel<DT, D, GG><<<grid, block, 0, st>>>(dv.desc, B, dv.page_table, q,                   \
+    full_partial_kernel<DT, D, GG><<<grid, block, 0, st>>>(dv.desc.mem, dv.desc.in, dv.desc.n, B, dv.page_table, q,                   \
                                                            (const uint4 *)dv.k_pool, (const char *)dv.v_pool, \
                                                            scale, sh.n_kv_heads, ppt, dv.partials)
     switch (G) {

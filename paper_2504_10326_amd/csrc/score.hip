@@ -51,12 +51,13 @@ hipError_t launch_append(const Shape &sh, const int32_t *pt_row, void *k_pool, v
 
 // One new token for each of B sequences (a decode step of a batch) in one launch.
 //   k, v   [B][H_kv][D]; desc[b].pt_off / desc[b].n = the sequence's page-table row / its length before
-__global__ __launch_bounds__(256) void append_step_kernel(const ReqDesc *__restrict__ desc,
+__global__ __launch_bounds__(256) void append_step_kernel(const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n,
                                                            const int32_t *__restrict__ page_table,
                                                            uint4 *__restrict__ k_pool, uint4 *__restrict__ v_pool,
                                                            const uint4 *__restrict__ k, const uint4 *__restrict__ v,
                                                            int B, int H_kv, int NC)
 {
+    const Descs desc{desc_mem, desc0, desc_n};
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= B * H_kv * NC) return;
     const int c = i % NC;
@@ -76,7 +77,7 @@ hipError_t launch_append_step(const Shape &sh, const DeviceViews &dv, void *k_po
     const int NC = sh.head_dim * (sh.dtype == 0 ? 2 : 4) / 16;
     const int total = B * sh.n_kv_heads * NC;
     append_step_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(
-        dv.desc, dv.page_table, (uint4 *)k_pool, (uint4 *)v_pool, (const uint4 *)k, (const uint4 *)v, B,
+        dv.desc.mem, dv.desc.in, dv.desc.n, dv.page_table, (uint4 *)k_pool, (uint4 *)v_pool, (const uint4 *)k, (const uint4 *)v, B,
         sh.n_kv_heads, NC);
     return hipGetLastError();
 }
@@ -129,7 +130,7 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c)
 // RING: a wavefront may cover several pages; their survivors are staged and leave as one list.
 // `block` = tile * H_kv + KV head: what one 256-thread workgroup scores.
 template <int DT, int D, int G, int PHASE, bool RING>
-__device__ __forceinline__ void score_block(const int block, const ReqDesc *__restrict__ desc, int B,
+__device__ __forceinline__ void score_block(const int block, const Descs &desc, int B,
                                             const int32_t *__restrict__ page_table,
                                             const uint32_t *__restrict__ qw, const uint4 *__restrict__ k_pool,
                                             uint2 *__restrict__ cand, int32_t *__restrict__ page_cnt,
@@ -333,7 +334,7 @@ __device__ __forceinline__ void score_block(const int block, const ReqDesc *__re
 // Phases 0 and 1: one workgroup per block.  Phase 2 is launched with a small grid whose workgroups
 // leave at once unless some head was marked for repair, and otherwise share all blocks out.
 template <int DT, int D, int G, int PHASE, bool RING>
-__global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ desc, int B,
+__global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int B,
                                                      const int32_t *__restrict__ page_table,
                                                      const uint32_t *__restrict__ qw, const uint4 *__restrict__ k_pool,
                                                      uint2 *__restrict__ cand, int32_t *__restrict__ page_cnt,
@@ -345,6 +346,7 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
                                                      uint32_t *__restrict__ sample_max, int H_kv, int ppw, int mode,
                                                      int total_blocks)
 {
+    const Descs desc{desc_mem, desc0, desc_n};
     if (PHASE == 2) {
         if (*any_fail == 0u) return;
         for (int b = blockIdx.x; b < total_blocks; b += gridDim.x)
@@ -375,7 +377,7 @@ static hipError_t launch_score_g(const Shape &sh, const DeviceViews &dv, int B, 
     const int total_blocks = total_tiles * sh.n_kv_heads;
     const dim3 grid((unsigned)(phase == 2 && total_blocks > kRepairGrid ? kRepairGrid : total_blocks)), block(256);
 #define ALAYA_SCORE_K(GG, PH, RG)                                                                             \
-    launch_maybe_timed(score_kernel<DT, D, GG, PH, RG>, grid, block, st, ev0, ev1, dv.desc, B, dv.page_table, \
+    launch_maybe_timed(score_kernel<DT, D, GG, PH, RG>, grid, block, st, ev0, ev1, dv.desc.mem, dv.desc.in, dv.desc.n, B, dv.page_table, \
                        (const uint32_t *)q, (const uint4 *)dv.k_pool, dv.cand, dv.page_cnt,                   \
                        (const uint32_t *)dv.tau, (const uint32_t *)dv.tau_safe, (const uint32_t *)dv.fail,    \
                        (const uint32_t *)dv.any_fail, dv.hist, dv.sample_max, sh.n_kv_heads, ppw, mode,       \
@@ -418,13 +420,14 @@ hipError_t launch_score(const Shape &sh, const DeviceViews &dv, int B, const voi
 // tau: the lower bound of each head's selection threshold, from what the sample pass accumulated.
 // One 1024-thread workgroup per (request, head); runs between the sample pass and the main pass, when
 // the histogram and the maximum hold the sampled pages only.
-__global__ __launch_bounds__(kSelectThreads) void tau_kernel(const ReqDesc *__restrict__ desc, int H_q, int mode,
+__global__ __launch_bounds__(kSelectThreads) void tau_kernel(const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int H_q, int mode,
                                                               const uint32_t *__restrict__ hist,
                                                               uint32_t *__restrict__ sample_max,
                                                               uint32_t *__restrict__ head_maxkey,
                                                               uint32_t *__restrict__ tau,
                                                               uint32_t *__restrict__ tau_safe)
 {
+    const Descs desc{desc_mem, desc0, desc_n};
     __shared__ int32_t wtot[kSelectThreads / 64];
     __shared__ int32_t found, found_est;
 
@@ -479,7 +482,7 @@ __global__ __launch_bounds__(kSelectThreads) void tau_kernel(const ReqDesc *__re
 hipError_t launch_tau(const Shape &sh, const DeviceViews &dv, int B, int mode, hipStream_t st)
 {
     tau_kernel<<<dim3((unsigned)(B * sh.n_q_heads)), dim3(kSelectThreads), 0, st>>>(
-        dv.desc, sh.n_q_heads, mode, dv.hist, dv.sample_max, dv.head_maxkey, dv.tau, dv.tau_safe);
+        dv.desc.mem, dv.desc.in, dv.desc.n, sh.n_q_heads, mode, dv.hist, dv.sample_max, dv.head_maxkey, dv.tau, dv.tau_safe);
     return hipGetLastError();
 }
 

@@ -118,7 +118,7 @@ __device__ __forceinline__ void block_find_bin(const uint32_t *hist, int nbins, 
 
 // blockIdx -> (request, head, segment).  Heads are the fastest index.
 struct SegId { int r, h, seg; };
-__device__ __forceinline__ SegId seg_of_block(const ReqDesc *desc, int B, int H_q)
+__device__ __forceinline__ SegId seg_of_block(const Descs &desc, int B, int H_q)
 {
     const int h = blockIdx.x % H_q;
     const int gs = blockIdx.x / H_q;
@@ -208,9 +208,10 @@ struct Rule {
 
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kSelectThreads) void select_stats_kernel(
-    const ReqDesc *__restrict__ desc, int B, int H_q, int mode, const uint2 *__restrict__ cand,
+    const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int B, int H_q, int mode, const uint2 *__restrict__ cand,
     const int32_t *__restrict__ page_cnt, uint32_t *__restrict__ hist, uint32_t *__restrict__ head_maxkey)
 {
+    const Descs desc{desc_mem, desc0, desc_n};
     __shared__ uint32_t lh[kHistBins];
     __shared__ int32_t off[kMaxSegPages + 1];
     __shared__ int32_t wtot[kSelWaves];
@@ -266,13 +267,14 @@ __global__ __launch_bounds__(kSelectThreads) void select_stats_kernel(
 
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kSelectThreads) void select_local_kernel(
-    const ReqDesc *__restrict__ desc, int B, int H_q, int mode, const uint2 *__restrict__ cand,
+    const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int B, int H_q, int mode, const uint2 *__restrict__ cand,
     const int32_t *__restrict__ page_cnt,
     const uint32_t *__restrict__ hist, const uint32_t *__restrict__ head_maxkey, float *__restrict__ head_M,
     int32_t *__restrict__ head_info, int32_t *__restrict__ seg_counts, float *__restrict__ loc_scores,
     int32_t *__restrict__ loc_ids, const uint32_t *__restrict__ tau, uint32_t *__restrict__ fail,
     uint32_t *__restrict__ any_fail, int redo)
 {
+    const Descs desc{desc_mem, desc0, desc_n};
     __shared__ uint32_t lh[kHistBins];
     __shared__ int32_t off[kMaxSegPages + 1];
     __shared__ ScanShared scan;
@@ -361,7 +363,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_local_kernel(
 
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
-    const ReqDesc *__restrict__ desc, int H_q, int mode, const int32_t *__restrict__ head_info,
+    const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int H_q, int mode, const int32_t *__restrict__ head_info,
     const int32_t *__restrict__ seg_counts, const float *__restrict__ loc_scores,
     const int32_t *__restrict__ loc_ids, uint32_t *__restrict__ hist, uint32_t *__restrict__ head_maxkey,
     int32_t *__restrict__ sel_ids, float *__restrict__ sel_scores, int32_t *__restrict__ counts,
@@ -369,6 +371,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
     int32_t *__restrict__ status, float *__restrict__ head_M, uint32_t *__restrict__ fail,
     uint32_t *__restrict__ any_fail)
 {
+    const Descs desc{desc_mem, desc0, desc_n};
     __shared__ uint32_t lh[kHistBins];
     __shared__ float wred[kSelWaves];
     __shared__ ScanShared scan;
@@ -612,11 +615,11 @@ hipError_t launch_select_front(const Shape &sh, const DeviceViews &dv, int B, in
 {
     const dim3 block(kSelectThreads);
     const dim3 seg_grid((unsigned)(total_segs * sh.n_q_heads));
-    select_stats_kernel<<<seg_grid, block, 0, st>>>(dv.desc, B, sh.n_q_heads, mode, dv.cand, dv.page_cnt,
+    select_stats_kernel<<<seg_grid, block, 0, st>>>(dv.desc.mem, dv.desc.in, dv.desc.n, B, sh.n_q_heads, mode, dv.cand, dv.page_cnt,
                                                     dv.hist, dv.head_maxkey);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    select_local_kernel<<<seg_grid, block, 0, st>>>(dv.desc, B, sh.n_q_heads, mode, dv.cand, dv.page_cnt, dv.hist,
+    select_local_kernel<<<seg_grid, block, 0, st>>>(dv.desc.mem, dv.desc.in, dv.desc.n, B, sh.n_q_heads, mode, dv.cand, dv.page_cnt, dv.hist,
                                                     dv.head_maxkey, dv.head_M, dv.head_info, dv.seg_counts,
                                                     dv.loc_scores, dv.loc_ids, dv.tau, dv.fail, dv.any_fail, 0);
     return hipGetLastError();
@@ -628,7 +631,7 @@ hipError_t launch_select_back(const Shape &sh, const DeviceViews &dv, int B, int
     const dim3 block(kSelectThreads);
     if (redo) {
         const dim3 seg_grid((unsigned)(total_segs * sh.n_q_heads));
-        select_local_kernel<<<seg_grid, block, 0, st>>>(dv.desc, B, sh.n_q_heads, mode, dv.cand, dv.page_cnt,
+        select_local_kernel<<<seg_grid, block, 0, st>>>(dv.desc.mem, dv.desc.in, dv.desc.n, B, sh.n_q_heads, mode, dv.cand, dv.page_cnt,
                                                         dv.hist, dv.head_maxkey, dv.head_M, dv.head_info,
                                                         dv.seg_counts, dv.loc_scores, dv.loc_ids, dv.tau, dv.fail, dv.any_fail,
                                                         1);
@@ -636,7 +639,7 @@ hipError_t launch_select_back(const Shape &sh, const DeviceViews &dv, int B, int
         if (e != hipSuccess) return e;
     }
     select_finish_kernel<<<dim3((unsigned)(B * sh.n_q_heads)), block, 0, st>>>(
-        dv.desc, sh.n_q_heads, mode, dv.head_info, dv.seg_counts, dv.loc_scores, dv.loc_ids, dv.hist,
+        dv.desc.mem, dv.desc.in, dv.desc.n, sh.n_q_heads, mode, dv.head_info, dv.seg_counts, dv.loc_scores, dv.loc_ids, dv.hist,
         dv.head_maxkey, dv.sel_ids, dv.sel_scores, dv.counts, out_ids, out_counts, ids_stride, dv.status,
         dv.head_M, dv.fail, dv.any_fail);
     return hipGetLastError();
