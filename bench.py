@@ -5,8 +5,9 @@
 
 One step = one decode step of one layer: append the new token's key/value (Session.update), then
 the sparse-attention query (Session.attention): score every cached key, select top-k (or DIPR),
-gather the selected value rows, softmax-weighted sum, merge.  Inputs are resident in HBM before the
-timed region.  Prints ONE JSON line:
+gather the selected value rows, softmax-weighted sum, merge.  Both through one alaya_decode_step
+call (--separate-append: through alaya_append_kv_step and alaya_sparse_attn, one launch more).
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line:
 
   value       keys scored per second over the whole step  (a key-score = one (query head, token) pair)
   roofline    the main scoring kernel against the 8 TB/s HBM peak.  Algorithmic bytes per launch =
@@ -45,6 +46,8 @@ def main() -> int:
     ap.add_argument("--beta", type=float, default=2.0, help="DIPR margin for range_256k")
     ap.add_argument("--window", default="0,0",
                     help="INIT,LAST tokens that are always attended (the paper's tables use 128,512)")
+    ap.add_argument("--separate-append", action="store_true",
+                    help="append and attend through two calls instead of one alaya_decode_step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cold-steps", type=int, default=40,
                     help="extra steps with the last-level cache flushed before each (0 = skip)")
@@ -108,9 +111,13 @@ def main() -> int:
     step_k = torch.cat(new_k, dim=0).contiguous()            # [batch][H_kv][d]: one new token per request
     step_v = torch.cat(new_v, dim=0).contiguous()
 
-    def step():
-        c.append_step(seqs, step_k, step_v)                  # Session.update for the whole batch, one launch
-        c.sparse_attn(seqs, q, mode, out=out, **kw)
+    if args.separate_append:
+        def step():
+            c.append_step(seqs, step_k, step_v)              # Session.update for the whole batch, one launch
+            c.sparse_attn(seqs, q, mode, out=out, **kw)      # Session.attention
+    else:
+        def step():                                          # both in one call: the first scoring kernel
+            c.decode_step(seqs, step_k, step_v, q, mode, out=out, **kw)   # writes the new rows itself
 
     def run(n_steps):
         """n_steps steps bracketed by synchronisation; returns (seconds, key-scores, K rows scored)."""
@@ -238,7 +245,9 @@ def main() -> int:
                    "batch": w.batch, "tokens": total_n, "mode": w.mode,
                    "topk": list(w.topk) if w.topk else None, "beta": args.beta if w.mode == "dipr" else None,
                    "paged": "64-token pages" + (", randomly permuted" if w.permute_pages else ""),
-                   "accumulate": "fp32", "window": list(window)},
+                   "accumulate": "fp32", "window": list(window),
+                   "calls_per_step": "alaya_append_kv_step + alaya_sparse_attn" if args.separate_append
+                   else "alaya_decode_step"},
         "latency_us_per_layer": ms_per_step * 1e3,
         "k_rows_per_s": rows / secs,
         "kernels_us": kernels_us,

@@ -158,6 +158,21 @@ typedef struct {
 int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q,
                       const alaya_sparse_params *p, float *out, void *stream);
 
+/*
+ * One decode step of one layer (Sec. 5 "User Interface": Session.update, then Session.attention):
+ * appends ONE token to each of the B listed sequences and runs alaya_sparse_attn over the grown
+ * sequences.  Results are those of alaya_append_kv_step(seqs, k, v) followed by
+ * alaya_sparse_attn(seqs, q, p, out); the difference is one launch less: the first scoring kernel
+ * writes the new key and value rows itself.
+ *   seqs  HOST [B], distinct          k, v  DEVICE [B][n_kv_heads][head_dim], cache dtype
+ *   q, p, out: as for alaya_sparse_attn (with p->n_visible set the two calls are simply made in turn)
+ * Errors: if the append is refused (bad or repeated id, a length limit, the page pool: see
+ * alaya_append_kv_step) nothing changes.  If only the attention part is refused (its arguments, its
+ * workspace), the tokens HAVE been appended, as after the two separate calls.
+ */
+int alaya_decode_step(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *k, const void *v,
+                      const void *q, const alaya_sparse_params *p, float *out, void *stream);
+
 /* Session.attention, dense: Eq. (1) over every cached token (same q / out layout as above). */
 int alaya_full_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q,
                     float scale, float *out, void *stream);

@@ -27,7 +27,8 @@ KERNEL_SLOTS = ("score", "select", "attend", "combine", "full_partial", "append"
 
 EXPORTS = (
     "alaya_pool_bytes", "alaya_workspace_bytes", "alaya_create_cache", "alaya_destroy_cache",
-    "alaya_append_kv", "alaya_append_kv_step", "alaya_seq_len", "alaya_reset_seq", "alaya_sparse_attn", "alaya_full_attn",
+    "alaya_append_kv", "alaya_append_kv_step", "alaya_seq_len", "alaya_reset_seq", "alaya_sparse_attn", "alaya_decode_step",
+    "alaya_full_attn",
     "alaya_poll_status", "alaya_set_profiling", "alaya_kernel_times", "alaya_set_tuning", "alaya_debug_scores",
     "alaya_debug_survivors", "alaya_debug_pages", "alaya_debug_estimate",
     "alaya_last_error",
@@ -86,6 +87,9 @@ def lib() -> ctypes.CDLL:
         L.alaya_sparse_attn.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), i32, i32, vp,
                                         ctypes.POINTER(SparseParams), vp, vp]
         L.alaya_sparse_attn.restype = i32
+        L.alaya_decode_step.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), i32, i32, vp, vp, vp,
+                                        ctypes.POINTER(SparseParams), vp, vp]
+        L.alaya_decode_step.restype = i32
         L.alaya_full_attn.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), i32, i32, vp, ctypes.c_float, vp, vp]
         L.alaya_full_attn.restype = i32
         L.alaya_poll_status.argtypes = [vp, vp]; L.alaya_poll_status.restype = i32
@@ -189,7 +193,9 @@ def alaya_reset_seq(handle: int, seq: int) -> None:
 def alaya_sparse_attn(handle: int, seqs: Sequence[int], n_q_heads: int, q, mode: int,
                       topk: Optional[Sequence[int]], beta: Optional[Sequence[float]], scale: float, out,
                       out_ids=None, out_counts=None, ids_stride: int = 0, stream=0,
-                      window: Tuple[int, int] = (0, 0), n_visible: Optional[Sequence[int]] = None) -> None:
+                      window: Tuple[int, int] = (0, 0), n_visible: Optional[Sequence[int]] = None,
+                      step_kv=None) -> None:
+    """step_kv = (k, v): make the call an alaya_decode_step that first appends one token per sequence."""
     p = SparseParams()
     p.mode = mode
     p.window_init, p.window_last = int(window[0]), int(window[1])
@@ -203,8 +209,20 @@ def alaya_sparse_attn(handle: int, seqs: Sequence[int], n_q_heads: int, q, mode:
     p.out_counts = _ptr(out_counts)
     p.ids_stride = ids_stride
     sq = _i32_array(seqs)
+    if step_kv is not None:
+        _check(lib().alaya_decode_step(handle, sq, len(seqs), n_q_heads, _ptr(step_kv[0]), _ptr(step_kv[1]), _ptr(q),
+                                       ctypes.byref(p), _ptr(out), stream or None))
+        return
     _check(lib().alaya_sparse_attn(handle, sq, len(seqs), n_q_heads, _ptr(q), ctypes.byref(p), _ptr(out),
                                    stream or None))
+
+
+def alaya_decode_step(handle: int, seqs: Sequence[int], n_q_heads: int, k, v, q, mode: int,
+                      topk: Optional[Sequence[int]], beta: Optional[Sequence[float]], scale: float, out,
+                      out_ids=None, out_counts=None, ids_stride: int = 0, stream=0,
+                      window: Tuple[int, int] = (0, 0), n_visible: Optional[Sequence[int]] = None) -> None:
+    alaya_sparse_attn(handle, seqs, n_q_heads, q, mode, topk, beta, scale, out, out_ids, out_counts, ids_stride,
+                      stream, window, n_visible, step_kv=(k, v))
 
 
 def alaya_full_attn(handle: int, seqs: Sequence[int], n_q_heads: int, q, scale: float, out, stream=0) -> None:
@@ -283,9 +301,18 @@ class Cache:
         return self.torch.empty((B, self.cfg.n_q_heads, self.cfg.head_dim), dtype=self.torch.float32,
                                 device=self.device)
 
+    def decode_step(self, seqs: Sequence[int], k, v, q, mode: int, **kw):
+        """One token (k, v [len(seqs)][n_kv_heads][head_dim]) appended to each listed sequence, then
+        sparse_attn over the grown sequences, in one call (alaya_decode_step); arguments and result as
+        for sparse_attn."""
+        assert k.is_cuda and v.is_cuda and k.is_contiguous() and v.is_contiguous()
+        assert k.dtype == self.torch_dtype and v.dtype == self.torch_dtype and k.shape == v.shape
+        assert tuple(k.shape) == (len(seqs), self.cfg.n_kv_heads, self.cfg.head_dim)
+        return self.sparse_attn(seqs, q, mode, _step_kv=(k, v), **kw)
+
     def sparse_attn(self, seqs: Sequence[int], q, mode: int, topk=None, beta=None, scale: float = 0.0,
                     ids_stride: int = 0, out=None, stream=None, want_counts: bool = False,
-                    window: Tuple[int, int] = (0, 0), n_visible: Optional[Sequence[int]] = None):
+                    window: Tuple[int, int] = (0, 0), n_visible: Optional[Sequence[int]] = None, _step_kv=None):
         """Returns out [B][Hq][d] fp32, or (out, ids [B][Hq][ids_stride] int32, counts [B][Hq] int32) when
         ids_stride > 0, or (out, counts) when only want_counts is set.  window = (first, last) tokens
         that are always attended; n_visible[b] = the prefix of request b that the query sees."""
@@ -298,7 +325,7 @@ class Cache:
         if ids_stride > 0 or want_counts:
             counts = self.torch.zeros((len(seqs), self.cfg.n_q_heads), dtype=self.torch.int32, device=self.device)
         alaya_sparse_attn(self.handle, seqs, self.cfg.n_q_heads, q, mode, topk, beta, scale, out, ids, counts,
-                          ids_stride, _stream(stream), window, n_visible)
+                          ids_stride, _stream(stream), window, n_visible, step_kv=_step_kv)
         if ids is not None:
             return out, ids, counts
         return (out, counts) if want_counts else out

@@ -41,9 +41,11 @@ struct ReqDesc {
     int32_t w0, w1;        // window: tokens j < w0 and j >= n - w1 are always selected
     int32_t nwin;          // tokens in the window: min(n, w0 + w1)
     int32_t k_est;         // top-k: rank in the sample that the ESTIMATED bound is read at; 0 = guaranteed bound only
-    int32_t xf, xb;        // the sample pass also scores the pages [0, xf) and [xb, n_pages) in full: DIPR with a
-                           // window, whose tokens seed the maximum (Sec. 7.1); both are multiples of chunk_pages
-                           // (0 and n_pages otherwise)
+    int32_t xf, xb;        // the sample pass also scores the pages [0, xf) and [xb, n_pages) in full, and the main
+                           // pass leaves them out: DIPR with a window, whose tokens seed the maximum (Sec. 7.1);
+                           // a decode step, whose newest token that pass writes.  Multiples of chunk_pages
+                           // (0 and n_pages otherwise).  Only the every-S-th pages count as the sample in
+                           // top-k's histogram; the statistics kernel treats these pages like any other.
 };
 static_assert(sizeof(ReqDesc) == 88, "ReqDesc layout");
 
@@ -64,11 +66,14 @@ struct Descs { // device side, built from those three kernel arguments
     __device__ __forceinline__ ReqDesc operator[](int r) const { return n == 1 ? in : mem[r]; }
 };
 
-// A page that the sample pass scored in full (the main pass and the statistics leave it out).
-__device__ __forceinline__ bool sampled_page(const ReqDesc &d, int p)
-{
-    return (p & (d.sample_stride - 1)) == 0 || p < d.xf || p >= d.xb;
-}
+// The decode step's append, carried out by the sample pass (alaya_decode_step): the wavefront that
+// scores the page holding a request's newest token first writes that token's key and value rows.
+struct FusedAppend {
+    uint4 *k_pool, *v_pool; // the pools, writable
+    const uint4 *k, *v;     // [B][H_kv][D] new rows; k == nullptr: nothing to append
+};
+
+
 
 // A window token is always selected, and top-k neither counts nor ranks it.
 __device__ __forceinline__ bool in_window(const ReqDesc &d, int j) { return j < d.w0 || j >= d.n - d.w1; }
@@ -77,6 +82,7 @@ __device__ __forceinline__ bool in_window(const ReqDesc &d, int j) { return j < 
 // a request's block starts at score_off and spans n_q_heads * head_stride elements.
 struct DeviceViews {
     DescArgs desc;             // the call's request descriptors
+    FusedAppend fused;         // set for the duration of a decode-step call, all null otherwise
     const int32_t *page_table; // [max_seqs][max_pages_per_seq]
     const void *k_pool;
     const void *v_pool;

@@ -304,6 +304,7 @@ int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k
     c->v_pool = v_pool;
     c->dv.desc.mem = (const ReqDesc *)(c->ws + L.desc);
     c->dv.desc.n = 0;
+    c->dv.fused = FusedAppend{nullptr, nullptr, nullptr, nullptr};
     c->dv.page_table = (const int32_t *)(c->ws + L.page_table);
     c->dv.k_pool = k_pool;
     c->dv.v_pool = v_pool;
@@ -430,12 +431,13 @@ int alaya_append_kv(alaya_cache *c, int seq, const void *k, const void *v, int64
     return ALAYA_OK;
 }
 
-int alaya_append_kv_step(alaya_cache *c, const int32_t *seqs, int B, const void *k, const void *v, void *stream)
+namespace {
+
+// Host side of a decode step's append: checks, then takes a page for every listed sequence that starts
+// a new one and sends the new page-table entries.  Lengths are left as they are; `taken` lists the
+// sequences that got a page, for step_rollback.
+int step_reserve(alaya_cache *c, const int32_t *seqs, int B, hipStream_t st, std::vector<int32_t> &taken)
 {
-    if (!c) return fail(ALAYA_E_INVAL, "null cache handle");
-    if (!seqs || !k || !v) return fail(ALAYA_E_INVAL, "null seqs, k or v");
-    if (B <= 0 || B > c->cfg.max_batch) return fail(ALAYA_E_INVAL, "batch %d outside 1..%d", B, c->cfg.max_batch);
-    if (B == 1) return alaya_append_kv(c, seqs[0], k, v, 1, stream); // needs no descriptor copy
     size_t need = 0;
     for (int b = 0; b < B; ++b) {
         if (seqs[b] < 0 || seqs[b] >= c->cfg.max_seqs)
@@ -450,7 +452,36 @@ int alaya_append_kv_step(alaya_cache *c, const int32_t *seqs, int B, const void 
     }
     if (need > c->free_pages.size())
         return fail(ALAYA_E_NOMEM, "page pool exhausted: %zu pages needed, %zu free", need, c->free_pages.size());
-    hipStream_t st = (hipStream_t)stream;
+    int rc = ensure_device(c, st);
+    if (rc != ALAYA_OK) return rc;
+    for (int b = 0; b < B; ++b) {
+        const int s = seqs[b];
+        const int64_t n_old = c->seq_len[(size_t)s];
+        if (n_old % kPageTokens != 0) continue;
+        int32_t *row = c->h_page_table + (size_t)s * c->L.mpps;
+        row[n_old / kPageTokens] = c->free_pages.back();
+        c->free_pages.pop_back();
+        taken.push_back(s);
+        hipError_t e = hipMemcpyAsync((int32_t *)c->dv.page_table + (size_t)s * c->L.mpps + n_old / kPageTokens,
+                                      row + n_old / kPageTokens, sizeof(int32_t), hipMemcpyHostToDevice, st);
+        if (e != hipSuccess) return fail_hip(e, "page table copy");
+    }
+    return ALAYA_OK;
+}
+
+// Gives the pages of a failed step back; `back` = 1 if the lengths already count the new token.
+void step_rollback(alaya_cache *c, const std::vector<int32_t> &taken, int back)
+{
+    for (size_t i = taken.size(); i-- > 0;) {
+        const int s = taken[i];
+        c->free_pages.push_back(c->h_page_table[(size_t)s * c->L.mpps + (c->seq_len[(size_t)s] - back) / kPageTokens]);
+    }
+}
+
+// The append kernel for one new token per listed sequence; `back` as above.
+int step_launch_append(alaya_cache *c, const int32_t *seqs, int B, const void *k, const void *v, int back,
+                       hipStream_t st)
+{
     ReqDesc *hd;
     int slot;
     int rc = ring_acquire(c, &hd, &slot);
@@ -459,47 +490,90 @@ int alaya_append_kv_step(alaya_cache *c, const int32_t *seqs, int B, const void 
         hipError_t e = hipEventCreateWithFlags(&c->ring_ev[slot], hipEventDisableTiming);
         if (e != hipSuccess) { c->ring_ev[slot] = nullptr; return fail_hip(e, "hipEventCreate"); }
     }
-    rc = ensure_device(c, st);
-    if (rc != ALAYA_OK) return rc;
-    // From here on pages are taken; on a failure they go back and no length changes.
-    std::vector<int32_t> taken; // sequences that got a page, in order
-    auto rollback = [&]() {
-        for (size_t i = taken.size(); i-- > 0;) {
-            const int s = taken[i];
-            c->free_pages.push_back(c->h_page_table[(size_t)s * c->L.mpps + c->seq_len[(size_t)s] / kPageTokens]);
-        }
-    };
     for (int b = 0; b < B; ++b) {
-        const int s = seqs[b];
-        const int64_t n_old = c->seq_len[(size_t)s];
         std::memset(&hd[b], 0, sizeof(ReqDesc));
-        hd[b].pt_off = (int32_t)((int64_t)s * c->L.mpps);
-        hd[b].n = (int32_t)n_old;
-        if (n_old % kPageTokens == 0) {
-            int32_t *row = c->h_page_table + (size_t)s * c->L.mpps;
-            row[n_old / kPageTokens] = c->free_pages.back();
-            c->free_pages.pop_back();
-            taken.push_back(s);
-            hipError_t e = hipMemcpyAsync((int32_t *)c->dv.page_table + (size_t)s * c->L.mpps + n_old / kPageTokens,
-                                          row + n_old / kPageTokens, sizeof(int32_t), hipMemcpyHostToDevice, st);
-            if (e != hipSuccess) { rollback(); return fail_hip(e, "page table copy"); }
-        }
+        hd[b].pt_off = (int32_t)((int64_t)seqs[b] * c->L.mpps);
+        hd[b].n = (int32_t)(c->seq_len[(size_t)seqs[b]] - back);
     }
     rc = ring_publish(c, slot, B, st);
-    if (rc != ALAYA_OK) { rollback(); return rc; }
+    if (rc != ALAYA_OK) return rc;
     const Shape sh{c->cfg.dtype, c->cfg.head_dim, c->cfg.n_q_heads, c->cfg.n_kv_heads};
     hipError_t e;
     {
         Timed tm(c, 5, st);
         e = launch_append_step(sh, c->dv, c->k_pool, c->v_pool, k, v, B, st);
     }
-    if (e != hipSuccess) { rollback(); return fail_hip(e, "append launch"); }
+    if (e != hipSuccess) return fail_hip(e, "append launch");
+    return ALAYA_OK;
+}
+
+int sparse_attn_impl(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q,
+                     const alaya_sparse_params *p, float *out, void *stream, const void *fused_k,
+                     const void *fused_v, bool *appended);
+
+} // namespace
+
+int alaya_append_kv_step(alaya_cache *c, const int32_t *seqs, int B, const void *k, const void *v, void *stream)
+{
+    if (!c) return fail(ALAYA_E_INVAL, "null cache handle");
+    if (!seqs || !k || !v) return fail(ALAYA_E_INVAL, "null seqs, k or v");
+    if (B <= 0 || B > c->cfg.max_batch) return fail(ALAYA_E_INVAL, "batch %d outside 1..%d", B, c->cfg.max_batch);
+    if (B == 1) return alaya_append_kv(c, seqs[0], k, v, 1, stream);
+    hipStream_t st = (hipStream_t)stream;
+    // From step_reserve on pages are taken; on a failure they go back and no length changes.
+    std::vector<int32_t> taken;
+    int rc = step_reserve(c, seqs, B, st, taken);
+    if (rc == ALAYA_OK) rc = step_launch_append(c, seqs, B, k, v, 0, st);
+    if (rc != ALAYA_OK) { step_rollback(c, taken, 0); return rc; }
     for (int b = 0; b < B; ++b) c->seq_len[(size_t)seqs[b]] += 1;
     return ALAYA_OK;
 }
 
+int alaya_decode_step(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *k, const void *v,
+                      const void *q, const alaya_sparse_params *p, float *out, void *stream)
+{
+    if (!c) return fail(ALAYA_E_INVAL, "null cache handle");
+    if (!seqs || !k || !v) return fail(ALAYA_E_INVAL, "null seqs, k or v");
+    if (B <= 0 || B > c->cfg.max_batch) return fail(ALAYA_E_INVAL, "batch %d outside 1..%d", B, c->cfg.max_batch);
+    if (p && p->n_visible) { // the new token may lie outside what the query sees: nothing to fuse
+        const int rc = alaya_append_kv_step(c, seqs, B, k, v, stream);
+        return rc != ALAYA_OK ? rc : alaya_sparse_attn(c, seqs, B, n_q_heads, q, p, out, stream);
+    }
+    hipStream_t st = (hipStream_t)stream;
+    std::vector<int32_t> taken;
+    int rc = step_reserve(c, seqs, B, st, taken);
+    if (rc != ALAYA_OK) { step_rollback(c, taken, 0); return rc; }
+    for (int b = 0; b < B; ++b) c->seq_len[(size_t)seqs[b]] += 1;
+    // The attention call's sample pass writes the new rows.  If the call is turned down before that
+    // launch, the plain append kernel writes them: the token is appended either way.
+    bool appended = false;
+    rc = sparse_attn_impl(c, seqs, B, n_q_heads, q, p, out, stream, k, v, &appended);
+    if (!appended) {
+        const int rc2 = step_launch_append(c, seqs, B, k, v, 1, st);
+        if (rc2 != ALAYA_OK) { // nothing was written: undo the step
+            step_rollback(c, taken, 1);
+            for (int b = 0; b < B; ++b) c->seq_len[(size_t)seqs[b]] -= 1;
+            return rc2;
+        }
+    }
+    return rc;
+}
+
 int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q,
                       const alaya_sparse_params *p, float *out, void *stream)
+{
+    bool appended = false;
+    return sparse_attn_impl(c, seqs, B, n_q_heads, q, p, out, stream, nullptr, nullptr, &appended);
+}
+
+namespace {
+
+// alaya_sparse_attn; with fused_k / fused_v (a decode step whose lengths already count the new token)
+// the sample pass also writes each request's newest key and value rows.  *appended is set once that
+// launch is out.
+int sparse_attn_impl(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q,
+                     const alaya_sparse_params *p, float *out, void *stream, const void *fused_k,
+                     const void *fused_v, bool *appended)
 {
     int64_t total_pages = 0, total_tokens = 0;
     int rc = check_call(c, seqs, B, n_q_heads, q, out, &total_pages, &total_tokens);
@@ -649,6 +723,8 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
             d.xf = std::min(d.n_pages, (wp0 + cp - 1) / cp * cp);
             d.xb = std::max(d.xf, pb / cp * cp);
         }
+        // a decode step: the page of the newest token belongs to the sample pass, which writes that token
+        if (fused_k && S > 1) d.xb = std::max(d.xf, std::min(d.xb, (d.n - 1) / kPageTokens / cp * cp));
         const int every = (d.n_pages + S - 1) / S;
         auto not_every = [S](int a, int b) { return (b - a) - ((b + S - 1) / S - (a + S - 1) / S); }; // in [a, b)
         pages_a += every + not_every(0, d.xf) + not_every(d.xb, d.n_pages);
@@ -680,7 +756,10 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
     hipError_t e;
     {
         Timed tm(c, 6, st);
+        if (fused_k) c->dv.fused = FusedAppend{(uint4 *)c->k_pool, (uint4 *)c->v_pool, (const uint4 *)fused_k, (const uint4 *)fused_v};
         e = launch_score(sh, c->dv, B, q, tiles, 1, 0, p->mode, st);
+        c->dv.fused = FusedAppend{nullptr, nullptr, nullptr, nullptr};
+        if (e == hipSuccess) *appended = fused_k != nullptr;
         // (DIPR: the bound kernel also gathers the sample pass's maxima, so it runs even with no main pass)
         if (e == hipSuccess && (tiles_b > 0 || p->mode == ALAYA_DIPR)) e = launch_tau(sh, c->dv, B, p->mode, st);
     }
@@ -705,6 +784,8 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
     if (e != hipSuccess) return fail_hip(e, "combine launch");
     return ALAYA_OK;
 }
+
+} // namespace
 
 int alaya_full_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q, float scale_in,
                     float *out, void *stream)

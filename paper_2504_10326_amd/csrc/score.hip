@@ -137,7 +137,8 @@ __device__ __forceinline__ void score_block(const int block, const Descs &desc, 
                                             const uint32_t *__restrict__ tau_in,
                                             const uint32_t *__restrict__ tau_safe,
                                             const uint32_t *__restrict__ fail, uint32_t *__restrict__ hist,
-                                            uint32_t *__restrict__ sample_max, int H_kv, int ppw, int mode)
+                                            uint32_t *__restrict__ sample_max, int H_kv, int ppw, int mode,
+                                            const FusedAppend &fa)
 {
     constexpr int phase = PHASE == 0 ? 0 : 1; // page mapping: the repair pass walks the main pass's pages
     constexpr int NC = D * (DT == 0 ? 2 : 4) / 16; // 16-byte chunks per key
@@ -166,18 +167,21 @@ __device__ __forceinline__ void score_block(const int block, const Descs &desc, 
     const int lane = threadIdx.x & 63;
     const int S = dsc.sample_stride;
     // Phase 0: wavefront w of the request takes the sampled page w * S; the wavefronts after those take
-    // the pages [0, xf) and [xb, n_pages) that hold a DIPR window (one of these may be an S-th page
-    // too: it is then scored twice, with the same result).  Phase 1: wavefront w takes the aligned
+    // the pages [0, xf) and [xb, n_pages) that are sampled on top (a DIPR window, the page of a token
+    // that this pass appends), leaving out the S-th pages among them.  Phase 1: wavefront w takes the aligned
     // chunk of `cp` consecutive pages [w * cp, (w + 1) * cp) without the sampled ones; cp is a power of
     // two <= S and divides xf and xb, so a chunk is either all window pages or holds at most one
     // sampled page, its first.
     const int w_req = (tile - (phase == 0 ? dsc.tile_start : dsc.tileb_start)) * kScoreWaves + wave;
     const int cp = phase == 0 ? 1 : dsc.chunk_pages;
     int p_first = w_req * cp;
+    bool every_sth = true; // phase 0: this wavefront's page is one of the every-S-th sample
     if (phase == 0) {
         const int ns = (dsc.n_pages + S - 1) >> (__ffs(S) - 1); // every S-th page
         const int x = w_req - ns;
+        every_sth = x < 0;
         p_first = x < 0 ? w_req * S : x < dsc.xf ? x : dsc.xb + (x - dsc.xf);
+        if (x >= 0 && (p_first & (S - 1)) == 0) p_first = dsc.n_pages; // an S-th page: not this wavefront's
     }
     const int p_end = min(p_first + cp, dsc.n_pages);
     const int p_begin = (phase == 1 && (p_first & (S - 1)) == 0) ? p_first + 1 : p_first;
@@ -215,7 +219,24 @@ __device__ __forceinline__ void score_block(const int block, const Descs &desc, 
 
     for (int p = p_begin; p < p_end; ++p) {
         const int phys = page_table[dsc.pt_off + p];
-        const uint4 *base = k_pool + ((size_t)phys * H_kv + kvh) * (size_t)(NC * 64) + lane;
+        const uint4 *kp = k_pool;
+        if (PHASE == 0 && fa.k) {
+            // A decode step: the newest token's rows are not in the pools yet.  The wavefront that scores
+            // its page writes them (this KV head's), waits for the writes, and reads the page through
+            // the same pointer; the value row is read by later kernels only.
+            kp = fa.k_pool;
+            if (p == (dsc.n - 1) >> 6) {
+                const int slot = (dsc.n - 1) & 63;
+                const size_t tile = ((size_t)phys * H_kv + kvh) * (size_t)(NC * 64);
+                const size_t src = ((size_t)r * H_kv + kvh) * NC;
+                for (int c = lane; c < NC; c += 64) {
+                    fa.k_pool[tile + (size_t)c * 64 + slot] = fa.k[src + c];
+                    fa.v_pool[tile + (size_t)slot * NC + c] = fa.v[src + c];
+                }
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
+        }
+        const uint4 *base = kp + ((size_t)phys * H_kv + kvh) * (size_t)(NC * 64) + lane;
         uint4 kc[NC];
 #pragma unroll
         for (int c = 0; c < NC; ++c) kc[c] = base[c * 64];
@@ -282,7 +303,9 @@ __device__ __forceinline__ void score_block(const int block, const Descs &desc, 
             }
             if (PHASE == 0 && valid) {
                 lmax[g] = fmaxf(lmax[g], acc[g]);
-                if (sample_hist_on && !win) {
+                // (the pages sampled on top are no uniform sample of the request: top-k's estimate must
+                // not see them; the statistics kernel counts them with the other pages' survivors)
+                if (sample_hist_on && !win && every_sth) {
                     const uint32_t bin = key >> 21;
                     atomicAdd(&lhist[g][bin >> 1], 1u << ((bin & 1u) * 16u));
                 }
@@ -344,17 +367,17 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
                                                      const uint32_t *__restrict__ any_fail,
                                                      uint32_t *__restrict__ hist,
                                                      uint32_t *__restrict__ sample_max, int H_kv, int ppw, int mode,
-                                                     int total_blocks)
+                                                     int total_blocks, const FusedAppend fa)
 {
     const Descs desc{desc_mem, desc0, desc_n};
     if (PHASE == 2) {
         if (*any_fail == 0u) return;
         for (int b = blockIdx.x; b < total_blocks; b += gridDim.x)
             score_block<DT, D, G, PHASE, RING>(b, desc, B, page_table, qw, k_pool, cand, page_cnt, tau_in, tau_safe,
-                                               fail, hist, sample_max, H_kv, ppw, mode);
+                                               fail, hist, sample_max, H_kv, ppw, mode, fa);
     } else {
         score_block<DT, D, G, PHASE, RING>(blockIdx.x, desc, B, page_table, qw, k_pool, cand, page_cnt, tau_in,
-                                           tau_safe, fail, hist, sample_max, H_kv, ppw, mode);
+                                           tau_safe, fail, hist, sample_max, H_kv, ppw, mode, fa);
     }
 }
 
@@ -381,7 +404,7 @@ static hipError_t launch_score_g(const Shape &sh, const DeviceViews &dv, int B, 
                        (const uint32_t *)q, (const uint4 *)dv.k_pool, dv.cand, dv.page_cnt,                   \
                        (const uint32_t *)dv.tau, (const uint32_t *)dv.tau_safe, (const uint32_t *)dv.fail,    \
                        (const uint32_t *)dv.any_fail, dv.hist, dv.sample_max, sh.n_kv_heads, ppw, mode,       \
-                       total_blocks)
+                       total_blocks, PH == 0 ? dv.fused : FusedAppend{nullptr, nullptr, nullptr, nullptr})
 #define ALAYA_SCORE(GG)                                                                                       \
     do {                                                                                                      \
         if (phase == 0) ALAYA_SCORE_K(GG, 0, false);                                                          \

@@ -221,7 +221,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_stats_kernel(
     const ReqDesc dsc = desc[id.r];
     const int rh = id.r * H_q + id.h;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // The sampled pages entered the histogram and the maximum when they were scored.
+    // The every-S-th pages entered the histogram and the maximum when they were scored.
     const int S = dsc.sample_stride;
     if (S == 1) return; // whole workgroup: every page was a sampled page
     const bool want_hist = mode == 0 && dsc.k < dsc.n - dsc.nwin;
@@ -229,8 +229,8 @@ __global__ __launch_bounds__(kSelectThreads) void select_stats_kernel(
         for (int i = tid; i < kHistBins; i += kSelectThreads) lh[i] = 0u;
     int a0, a1;
     SegView v = begin_segment(dsc, H_q, id.h, id.seg, page_cnt, a0, a1);
-    if (sampled_page(dsc, v.p_begin + 2 * tid)) a0 = 0;
-    if (sampled_page(dsc, v.p_begin + 2 * tid + 1)) a1 = 0;
+    if (((v.p_begin + 2 * tid) & (S - 1)) == 0) a0 = 0;
+    if (((v.p_begin + 2 * tid + 1) & (S - 1)) == 0) a1 = 0;
     scan_segment(v, a0, a1, off, wtot); // barriers inside
     float m = -INFINITY;
     constexpr int U = 4; // independent loads per thread and step

@@ -148,6 +148,10 @@ def test_step_append_and_estimate_hook_argument_checks():
         with pytest.raises(A.AlayaError) as e:
             A.alaya_append_kv_step(h, [0, 1], 0, FAKE[4])
         assert e.value.code == A.ALAYA_E_INVAL
+        for seqs, kv in [([0, 0], FAKE[3]), ([0, 9], FAKE[3]), ([0, 1], 0)]:  # the decode step checks its append first
+            with pytest.raises(A.AlayaError) as e:
+                A.alaya_decode_step(h, seqs, 32, kv, FAKE[4], FAKE[3], A.ALAYA_TOPK, [4, 4], None, 0.0, FAKE[4])
+            assert e.value.code == A.ALAYA_E_INVAL, seqs
         assert [A.alaya_seq_len(h, s) for s in range(4)] == [0, 0, 0, 0]
         L = A.lib()
         assert L.alaya_debug_estimate(h, 3) == A.ALAYA_E_INVAL and L.alaya_debug_estimate(h, -2) == A.ALAYA_E_INVAL

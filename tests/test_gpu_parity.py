@@ -178,6 +178,75 @@ def test_decode_step_append_for_a_batch_matches_single_appends():
     c.close()
 
 
+@pytest.mark.parametrize("lens,mode,kw", [
+    ([5000, 8190, 130, 3], A.ALAYA_TOPK, dict(topk=[100, 300, 20, 2])),
+    ([5000, 8190, 130, 3], A.ALAYA_DIPR, dict(beta=[1.0, 2.0, 0.5, 3.0], window=(70, 130))),
+    ([40000], A.ALAYA_TOPK, dict(topk=[600], window=(128, 512))),
+    ([40000], A.ALAYA_DIPR, dict(beta=[2.0])),
+])
+def test_decode_step_in_one_call_equals_append_then_attend(lens, mode, kw):
+    """alaya_decode_step (the first scoring kernel writes the new token's rows) against the two separate
+    calls on a twin cache: identical pools, ids, counts and outputs at every step, across page
+    boundaries, whether the new token's page is one the sample takes anyway or not; the last step
+    also against the oracle."""
+    steps = 70
+    B = len(lens)
+    w = _llama(lens, topk=kw.get("topk"))
+    g = wl.generate(wl.resized(w, [n + steps for n in lens]))
+    dev = lambda a: to_device(a, w.dtype)
+
+    def fresh():
+        c = make_cache(wl.resized(w, [n + steps for n in lens]), dict(g, K=[g["K"][r][:0] for r in range(B)],
+                                                                     V=[g["V"][r][:0] for r in range(B)]))
+        for r, n in enumerate(lens):
+            c.append_kv(r, dev(g["K"][r][:n]), dev(g["V"][r][:n]))
+        return c
+    a, b = fresh(), fresh()
+    q = dev(g["q"])
+    seqs = list(range(B))
+    stride = max(lens) + steps
+    for step in range(steps):
+        ks = dev(np.stack([g["K"][r][lens[r] + step] for r in seqs]))
+        vs = dev(np.stack([g["V"][r][lens[r] + step] for r in seqs]))
+        ra = a.decode_step(seqs, ks, vs, q, mode, ids_stride=stride, **kw)
+        b.append_step(seqs, ks, vs)
+        rb = b.sparse_attn(seqs, q, mode, ids_stride=stride, **kw)
+        for x, y in zip(ra, rb):
+            assert torch.equal(x, y), step
+    torch.cuda.synchronize()
+    assert [a.seq_len(r) for r in seqs] == [b.seq_len(r) for r in seqs] == [n + steps for n in lens]
+    assert torch.equal(a.k_pool, b.k_pool) and torch.equal(a.v_pool, b.v_pool)
+    assert a.poll_status() == A.ALAYA_OK
+    w2 = wl.resized(w, [n + steps for n in lens], topk=kw.get("topk"))
+    compare_sparse(w2, g, ra[0], ra[1], ra[2], mode, kw.get("topk"), kw.get("beta"), window=kw.get("window", (0, 0)))
+    a.close(); b.close()
+
+
+def test_decode_step_errors_and_prefix():
+    """A refused append changes nothing; a refused attention part leaves the token appended, as the two
+    separate calls would; with a visible prefix the call is simply the two calls in turn."""
+    w = _llama([200, 100], topk=[8, 8])
+    g = wl.generate(w)
+    c = make_cache(w, g, extra_tokens=64)
+    q = to_device(g["q"], w.dtype)
+    one = to_device(np.stack([g["K"][0][0], g["K"][1][0]]), w.dtype)
+    with pytest.raises(A.AlayaError) as e:
+        c.decode_step([0, 0], one, one, q, A.ALAYA_TOPK, topk=[8, 8])
+    assert e.value.code == A.ALAYA_E_INVAL and [c.seq_len(0), c.seq_len(1)] == [200, 100]
+    with pytest.raises(A.AlayaError) as e:
+        c.decode_step([0, 1], one, one, q, A.ALAYA_TOPK, topk=[8, 0])         # k = 0: attention refused
+    assert e.value.code == A.ALAYA_E_INVAL and [c.seq_len(0), c.seq_len(1)] == [201, 101]
+    g2 = dict(g, K=[np.concatenate([g["K"][r], g["K"][r][:1]]) for r in range(2)],      # k = v = the sequence's row 0
+              V=[np.concatenate([g["V"][r], g["K"][r][:1]]) for r in range(2)])
+    w2 = wl.resized(w, [201, 101], topk=[8, 8])
+    out, ids, counts = c.sparse_attn([0, 1], q, A.ALAYA_TOPK, topk=[8, 8], ids_stride=8)
+    compare_sparse(w2, g2, out, ids, counts, A.ALAYA_TOPK, topk=[8, 8])         # the refused step's rows are there
+    out, ids, counts = c.decode_step([0, 1], one, one, q, A.ALAYA_TOPK, topk=[8, 8], ids_stride=8, n_visible=[150, 60])
+    assert [c.seq_len(0), c.seq_len(1)] == [202, 102]
+    compare_sparse(w2, g2, out, ids, counts, A.ALAYA_TOPK, topk=[8, 8], n_visible=[150, 60])
+    c.close()
+
+
 # ------------------------------------------------------------------------------------------ window, prefix
 @pytest.mark.parametrize("n,w0,w1", [(9000, 128, 512), (5000, 0, 70), (4100, 3, 0), (700, 400, 400), (64 * 30, 64, 64)])
 def test_window_tokens_are_always_attended(n, w0, w1):
