@@ -138,7 +138,7 @@ __device__ __forceinline__ void score_block(const int block, const Descs &desc, 
                                             const uint32_t *__restrict__ tau_safe,
                                             const uint32_t *__restrict__ fail, uint32_t *__restrict__ hist,
                                             uint32_t *__restrict__ sample_max, int H_kv, int ppw, int mode,
-                                            const FusedAppend &fa)
+                                            const FusedAppend &fa, uint32_t *head_maxkey)
 {
     constexpr int phase = PHASE == 0 ? 0 : 1; // page mapping: the repair pass walks the main pass's pages
     constexpr int NC = D * (DT == 0 ? 2 : 4) / 16; // 16-byte chunks per key
@@ -190,6 +190,7 @@ __device__ __forceinline__ void score_block(const int block, const Descs &desc, 
     const uint4 *qh = (const uint4 *)(qw + (size_t)rh0 * QW);    // wave-uniform address: scalar loads
 
     uint32_t tau[G], tau_hi[G]; // keep key >= tau; repair pass: count tau <= key < tau_hi
+    uint32_t smax[G];           // main pass of a DIPR call: the head's maximum as the sample knows it
     bool act[G];                // repair pass: this head is being repaired
     bool any_act = PHASE != 2;
 #pragma unroll
@@ -198,6 +199,7 @@ __device__ __forceinline__ void score_block(const int block, const Descs &desc, 
         any_act |= act[g];
         tau[g] = PHASE == 0 ? 0u : PHASE == 1 ? tau_in[rh0 + g] : tau_safe[rh0 + g];
         tau_hi[g] = PHASE == 2 ? tau_in[rh0 + g] : 0u;
+        smax[g] = PHASE == 1 && mode == 1 ? head_maxkey[rh0 + g] : 0xFFFFFFFFu;
     }
     if (PHASE == 2 && !any_act) return; // whole workgroup: the usual case
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
@@ -273,6 +275,10 @@ __device__ __forceinline__ void score_block(const int block, const Descs &desc, 
         for (int g = 0; g < G; ++g) {
             const uint32_t key = ord_key(acc[g]);
             const bool keep = act[g] && valid && (win || key >= tau[g]);
+            // DIPR: a score above the sample's maximum raises the head's maximum.  About S - 1 scores
+            // per head do (the expected number of tokens ahead of the best of a 1-in-S sample), so
+            // these atomics on one address are few; they replace a statistics kernel.
+            if (PHASE == 1 && valid && key > smax[g]) atomicMax(&head_maxkey[rh0 + g], key);
             if (PHASE == 2 && keep && !win && key < tau_hi[g]) // a score the estimated bound had dropped
                 atomicAdd(&hist[(size_t)(rh0 + g) * kHistBins + (key >> 21)], 1u);
             const unsigned long long m = __ballot(keep);
@@ -367,17 +373,18 @@ __global__ __launch_bounds__(256) void score_kernel(const ReqDesc *__restrict__ 
                                                      const uint32_t *__restrict__ any_fail,
                                                      uint32_t *__restrict__ hist,
                                                      uint32_t *__restrict__ sample_max, int H_kv, int ppw, int mode,
-                                                     int total_blocks, const FusedAppend fa)
+                                                     int total_blocks, const FusedAppend fa,
+                                                     uint32_t *head_maxkey)
 {
     const Descs desc{desc_mem, desc0, desc_n};
     if (PHASE == 2) {
         if (*any_fail == 0u) return;
         for (int b = blockIdx.x; b < total_blocks; b += gridDim.x)
             score_block<DT, D, G, PHASE, RING>(b, desc, B, page_table, qw, k_pool, cand, page_cnt, tau_in, tau_safe,
-                                               fail, hist, sample_max, H_kv, ppw, mode, fa);
+                                               fail, hist, sample_max, H_kv, ppw, mode, fa, head_maxkey);
     } else {
         score_block<DT, D, G, PHASE, RING>(blockIdx.x, desc, B, page_table, qw, k_pool, cand, page_cnt, tau_in,
-                                           tau_safe, fail, hist, sample_max, H_kv, ppw, mode, fa);
+                                           tau_safe, fail, hist, sample_max, H_kv, ppw, mode, fa, head_maxkey);
     }
 }
 
@@ -404,7 +411,8 @@ static hipError_t launch_score_g(const Shape &sh, const DeviceViews &dv, int B, 
                        (const uint32_t *)q, (const uint4 *)dv.k_pool, dv.cand, dv.page_cnt,                   \
                        (const uint32_t *)dv.tau, (const uint32_t *)dv.tau_safe, (const uint32_t *)dv.fail,    \
                        (const uint32_t *)dv.any_fail, dv.hist, dv.sample_max, sh.n_kv_heads, ppw, mode,       \
-                       total_blocks, PH == 0 ? dv.fused : FusedAppend{nullptr, nullptr, nullptr, nullptr})
+                       total_blocks, PH == 0 ? dv.fused : FusedAppend{nullptr, nullptr, nullptr, nullptr},       \
+                       dv.head_maxkey)
 #define ALAYA_SCORE(GG)                                                                                       \
     do {                                                                                                      \
         if (phase == 0) ALAYA_SCORE_K(GG, 0, false);                                                          \

@@ -11,9 +11,11 @@
 // survivors of a segment are addressed through a FLAT index: the pages' survivor counts are scanned
 // in LDS, and element t of the concatenation is found by a binary search over the prefix sums.  All
 // loads of a pass are therefore independent, and the flat order is ascending token order.
-//   stats   adds the survivors of the main pass's pages to what the sample pass already entered for
-//           its own pages: the bucket counts (top 11 bits of the ordered key) for top-k, the maximum
-//           for DIPR.  LDS first, then at most kMaxSegs workgroups per head add to the global counters.
+//   stats   (top-k only) adds the survivors of the main pass's pages to what the sample pass already
+//           entered for its own pages: the bucket counts (top 11 bits of the ordered key).  LDS first,
+//           then at most kMaxSegs workgroups per head add to the global counters.  A DIPR call needs
+//           no such pass: its main pass raises the head's maximum itself, with the few scores that
+//           lie above the sample's maximum.
 //   local   top-k: reads the bucket b of the k-th largest score off the histogram and checks that it
 //           lies in the part of the histogram that is complete (at or above the bucket of the bound
 //           the main pass filtered with); if not - possible only with an estimated bound - the head
@@ -208,61 +210,47 @@ struct Rule {
 
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kSelectThreads) void select_stats_kernel(
-    const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int B, int H_q, int mode, const uint2 *__restrict__ cand,
-    const int32_t *__restrict__ page_cnt, uint32_t *__restrict__ hist, uint32_t *__restrict__ head_maxkey)
+    const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int B, int H_q, const uint2 *__restrict__ cand,
+    const int32_t *__restrict__ page_cnt, uint32_t *__restrict__ hist)
 {
     const Descs desc{desc_mem, desc0, desc_n};
     __shared__ uint32_t lh[kHistBins];
     __shared__ int32_t off[kMaxSegPages + 1];
     __shared__ int32_t wtot[kSelWaves];
-    __shared__ float wred[kSelWaves];
 
     const SegId id = seg_of_block(desc, B, H_q);
     const ReqDesc dsc = desc[id.r];
     const int rh = id.r * H_q + id.h;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // The every-S-th pages entered the histogram and the maximum when they were scored.
+    const int tid = threadIdx.x;
+    // The every-S-th pages entered the histogram when they were scored.
     const int S = dsc.sample_stride;
-    if (S == 1) return; // whole workgroup: every page was a sampled page
-    const bool want_hist = mode == 0 && dsc.k < dsc.n - dsc.nwin;
-    if (want_hist)
-        for (int i = tid; i < kHistBins; i += kSelectThreads) lh[i] = 0u;
+    if (S == 1) return;                        // whole workgroup: every page was a sampled page
+    if (dsc.k >= dsc.n - dsc.nwin) return;     // every token is taken: nothing to rank
+    for (int i = tid; i < kHistBins; i += kSelectThreads) lh[i] = 0u;
     int a0, a1;
     SegView v = begin_segment(dsc, H_q, id.h, id.seg, page_cnt, a0, a1);
     if (((v.p_begin + 2 * tid) & (S - 1)) == 0) a0 = 0;
     if (((v.p_begin + 2 * tid + 1) & (S - 1)) == 0) a1 = 0;
     scan_segment(v, a0, a1, off, wtot); // barriers inside
-    float m = -INFINITY;
     constexpr int U = 4; // independent loads per thread and step
     for (int t0 = tid; t0 < v.total; t0 += U * kSelectThreads) {
         float s[U];
-        bool ranked[U]; // a survivor outside the window: top-k's histogram counts only those
+        bool ranked[U]; // a survivor outside the window: the histogram counts only those
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int t = t0 + u * kSelectThreads;
             const bool in = t < v.total;
             const uint2 pr = in ? cand[flat_to_offset(v, off, t)] : make_uint2(0u, 0u);
-            s[u] = in ? __uint_as_float(pr.x) : -INFINITY;
+            s[u] = __uint_as_float(pr.x);
             ranked[u] = in && !in_window(dsc, (int)pr.y);
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            m = fmaxf(m, s[u]); // DIPR's maximum runs over the window's tokens too
-            if (want_hist && ranked[u]) atomicAdd(&lh[ord_key(s[u]) >> 21], 1u);
-        }
+        for (int u = 0; u < U; ++u)
+            if (ranked[u]) atomicAdd(&lh[ord_key(s[u]) >> 21], 1u);
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-    if (lane == 0) wred[wave] = m;
     __syncthreads();
-    if (tid == 0 && mode == 1) { // top-k takes its maximum from the finished set instead
-        float M = wred[0];
-        for (int w = 1; w < kSelWaves; ++w) M = fmaxf(M, wred[w]);
-        if (M > -INFINITY) atomicMax(&head_maxkey[rh], ord_key(M));
-    }
-    if (want_hist)
-        for (int i = tid; i < kHistBins; i += kSelectThreads)
-            if (lh[i]) atomicAdd(&hist[(size_t)rh * kHistBins + i], lh[i]);
+    for (int i = tid; i < kHistBins; i += kSelectThreads)
+        if (lh[i]) atomicAdd(&hist[(size_t)rh * kHistBins + i], lh[i]);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -615,8 +603,10 @@ hipError_t launch_select_front(const Shape &sh, const DeviceViews &dv, int B, in
 {
     const dim3 block(kSelectThreads);
     const dim3 seg_grid((unsigned)(total_segs * sh.n_q_heads));
-    select_stats_kernel<<<seg_grid, block, 0, st>>>(dv.desc.mem, dv.desc.in, dv.desc.n, B, sh.n_q_heads, mode, dv.cand, dv.page_cnt,
-                                                    dv.hist, dv.head_maxkey);
+    // (a DIPR call needs no statistics: its main pass raises the maximum itself)
+    if (mode == 0)
+        select_stats_kernel<<<seg_grid, block, 0, st>>>(dv.desc.mem, dv.desc.in, dv.desc.n, B, sh.n_q_heads, dv.cand,
+                                                        dv.page_cnt, dv.hist);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     select_local_kernel<<<seg_grid, block, 0, st>>>(dv.desc.mem, dv.desc.in, dv.desc.n, B, sh.n_q_heads, mode, dv.cand, dv.page_cnt, dv.hist,
