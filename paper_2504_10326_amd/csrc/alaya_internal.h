@@ -149,8 +149,8 @@ hipError_t launch_select_front(const Shape &sh, const DeviceViews &dv, int B, in
 hipError_t launch_select_back(const Shape &sh, const DeviceViews &dv, int B, int mode, int total_segs, bool redo,
                               int32_t *out_ids, int32_t *out_counts, int64_t ids_stride, hipStream_t st);
 
-hipError_t launch_attend(const Shape &sh, const DeviceViews &dv, int B, float scale, int splits,
-                         hipStream_t st);
+hipError_t launch_attend(const Shape &sh, const DeviceViews &dv, int B, float scale, int splits, bool segmented,
+                         int32_t *out_ids, int32_t *out_counts, int64_t ids_stride, hipStream_t st);
 
 // partial layout: [slot][head_dim + 2] = {m (already times scale), l, acc[head_dim]}
 // sparse: slot = (b * n_q_heads + h) * splits + s           (per_request_tiles == 0)

@@ -774,11 +774,15 @@ int sparse_attn_impl(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, 
         e = launch_select_front(sh, c->dv, B, p->mode, segs, st);
         // repair of the heads whose estimated bound lost tokens (normally none: both launches are idle)
         if (e == hipSuccess && any_est) e = launch_score(sh, c->dv, B, q, tiles_b, ppw, 2, p->mode, st);
-        if (e == hipSuccess)
+        if (e == hipSuccess && p->mode == ALAYA_TOPK)
             e = launch_select_back(sh, c->dv, B, p->mode, segs, any_est, p->out_ids, p->out_counts, p->ids_stride, st);
     }
     if (e != hipSuccess) { c->dev_ready = false; return fail_hip(e, "select launch"); }
-    { Timed tm(c, 2, st); e = launch_attend(sh, c->dv, B, scale, splits, st); }
+    {
+        // (a DIPR call has no finishing pass: the gather reads select_local's lists and reports the ids)
+        Timed tm(c, 2, st);
+        e = launch_attend(sh, c->dv, B, scale, splits, p->mode == ALAYA_DIPR, p->out_ids, p->out_counts, p->ids_stride, st);
+    }
     if (e != hipSuccess) return fail_hip(e, "attend launch");
     { Timed tm(c, 3, st); e = launch_combine(sh, c->dv, B, splits, 0, 0, out, st); }
     if (e != hipSuccess) return fail_hip(e, "combine launch");

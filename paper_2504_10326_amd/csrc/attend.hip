@@ -45,20 +45,35 @@ template <int DT, int D> struct RowSlice {
 // ------------------------------------------------------------------------------------------------
 // Sparse attend.  Grid: (request, head, split).  A wavefront takes 4 selected rows per step
 // (16 lanes per 256-byte row), kAttendU steps in flight.
+// SEG = false: the head's selected tokens are one list (sel_ids / sel_scores, `counts` long), as the
+// finishing pass of a top-k call leaves them.
+// SEG = true (DIPR): there is no finishing pass; the selected tokens are still where select_local put
+// them, one list per selection segment (`ids_in` / `scores_in` = its arrays, seg_counts = the lengths).
+// The kernel reads the concatenation of those lists through the segments' prefix sums, and does what
+// is left of the finishing pass on the way: the true count, the ids for the caller, the overflow
+// status, and the reset of the head's running maximum for the next call.
 constexpr int kAttendU = 4;
 
-template <int DT, int D>
+struct AttendOut { // SEG only: what the caller asked to get back
+    int32_t *out_ids, *out_counts;
+    int64_t ids_stride;
+    int32_t *status;
+};
+
+template <int DT, int D, bool SEG>
 __global__ __launch_bounds__(kAttendThreads) void attend_kernel(
     const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int H_q, int H_kv, const int32_t *__restrict__ page_table,
-    const char *__restrict__ v_pool, const int32_t *__restrict__ sel_ids, const float *__restrict__ sel_scores,
-    const int32_t *__restrict__ counts, const float *__restrict__ head_M, float scale, int splits,
-    float *__restrict__ partials)
+    const char *__restrict__ v_pool, const int32_t *__restrict__ ids_in, const float *__restrict__ scores_in,
+    int32_t *__restrict__ counts, const float *__restrict__ head_M, float scale, int splits,
+    float *__restrict__ partials, const int32_t *__restrict__ seg_counts, uint32_t *__restrict__ head_maxkey,
+    const AttendOut ao)
 {
     const Descs desc{desc_mem, desc0, desc_n};
     using RS = RowSlice<DT, D>;
     constexpr int EPL = RS::EPL;
     constexpr size_t ROW_BYTES = (size_t)D * (DT == 0 ? 2 : 4);
     __shared__ float red[4][D + 1];
+    __shared__ int32_t pre[SEG ? kMaxSegs + 1 : 1]; // exclusive prefix sums of the segments' list lengths
 
     const int sp = blockIdx.x % splits;
     const int rh = blockIdx.x / splits;
@@ -66,15 +81,55 @@ __global__ __launch_bounds__(kAttendThreads) void attend_kernel(
     const int kvh = h / (H_q / H_kv);
     const ReqDesc dsc = desc[r];
     const size_t off = (size_t)dsc.score_off + (size_t)h * dsc.head_stride;
-    const int32_t *ids = sel_ids + off;
-    const float *ss = sel_scores + off;
-    const int cnt = counts[rh];
+    const int32_t *ids = ids_in + off;
+    const float *ss = scores_in + off;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int nseg = dsc.nseg;
+    if (SEG) {
+        static_assert(kMaxSegs == 64, "one segment per lane");
+        if (threadIdx.x < 64) {
+            const int a = lane < nseg ? seg_counts[((size_t)rh * kMaxSegs + lane) * 2] : 0;
+            int ia = a;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_up(ia, o);
+                if (lane >= o) ia += t;
+            }
+            pre[lane] = ia - a;
+            if (lane == 63) pre[64] = ia;
+        }
+        __syncthreads();
+    }
+    const size_t seg_region = (size_t)dsc.seg_pages * kPageTokens;
+    // position of element i of the head's list in ids / ss
+    auto at = [&](int i) -> size_t {
+        if (!SEG) return (size_t)i;
+        int lo = 0, hi = nseg; // the last segment whose prefix is <= i
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (pre[mid] <= i) lo = mid; else hi = mid;
+        }
+        return (size_t)lo * seg_region + (size_t)(i - pre[lo]);
+    };
+    const int cnt = SEG ? pre[kMaxSegs] : counts[rh];
     int per = (cnt + splits - 1) / splits;
     per = (per + 15) & ~15;
     const int begin = min(cnt, sp * per), end = min(cnt, begin + per);
     const float M = head_M[rh];
+    if (SEG) {
+        if (ao.out_ids) {
+            const int m = (int)((int64_t)end < ao.ids_stride ? (int64_t)end : ao.ids_stride);
+            int32_t *dst = ao.out_ids + (size_t)rh * (size_t)ao.ids_stride;
+            for (int i = begin + (int)threadIdx.x; i < m; i += kAttendThreads) dst[i] = ids[at(i)];
+        }
+        if (sp == 0 && threadIdx.x == 0) {
+            counts[rh] = cnt;
+            if (ao.out_counts) ao.out_counts[rh] = cnt;
+            if (ao.out_ids && (int64_t)cnt > ao.ids_stride) atomicOr(ao.status, 1);
+            head_maxkey[rh] = 0u; // clean for the next call (select_local, the last reader, is done)
+        }
+    }
 
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int sub = lane & 15, grp = lane >> 4;
     float acc[EPL];
 #pragma unroll
@@ -88,8 +143,9 @@ __global__ __launch_bounds__(kAttendThreads) void attend_kernel(
         for (int u = 0; u < kAttendU; ++u) {
             const int i = i0 + u * 16;
             const bool ok = i < end;
-            id[u] = ok ? ids[i] : -1;
-            p[u] = ok ? __expf((ss[i] - M) * scale) : 0.f;
+            const size_t src = ok ? at(i) : 0;
+            id[u] = ok ? ids[src] : -1;
+            p[u] = ok ? __expf((ss[src] - M) * scale) : 0.f;
         }
         const char *row[kAttendU];
 #pragma unroll
@@ -137,13 +193,24 @@ __global__ __launch_bounds__(kAttendThreads) void attend_kernel(
     }
 }
 
-hipError_t launch_attend(const Shape &sh, const DeviceViews &dv, int B, float scale, int splits, hipStream_t st)
+hipError_t launch_attend(const Shape &sh, const DeviceViews &dv, int B, float scale, int splits, bool segmented,
+                         int32_t *out_ids, int32_t *out_counts, int64_t ids_stride, hipStream_t st)
 {
     const dim3 grid((unsigned)(B * sh.n_q_heads * splits)), block(kAttendThreads);
+    const AttendOut ao{out_ids, out_counts, ids_stride, dv.status};
 #define ALAYA_ATTEND(DT, D)                                                                                  \
-    attend_kernel<DT, D><<<grid, block, 0, st>>>(dv.desc.mem, dv.desc.in, dv.desc.n, sh.n_q_heads, sh.n_kv_heads, dv.page_table,        \
-                                                 (const char *)dv.v_pool, dv.sel_ids, dv.sel_scores, dv.counts, \
-                                                 dv.head_M, scale, splits, dv.partials)
+    do {                                                                                                     \
+        if (segmented)                                                                                       \
+            attend_kernel<DT, D, true><<<grid, block, 0, st>>>(                                              \
+                dv.desc.mem, dv.desc.in, dv.desc.n, sh.n_q_heads, sh.n_kv_heads, dv.page_table,              \
+                (const char *)dv.v_pool, dv.loc_ids, dv.loc_scores, dv.counts, dv.head_M, scale, splits,     \
+                dv.partials, dv.seg_counts, dv.head_maxkey, ao);                                             \
+        else                                                                                                 \
+            attend_kernel<DT, D, false><<<grid, block, 0, st>>>(                                             \
+                dv.desc.mem, dv.desc.in, dv.desc.n, sh.n_q_heads, sh.n_kv_heads, dv.page_table,              \
+                (const char *)dv.v_pool, dv.sel_ids, dv.sel_scores, dv.counts, dv.head_M, scale, splits,     \
+                dv.partials, dv.seg_counts, dv.head_maxkey, ao);                                             \
+    } while (0)
     if (sh.dtype == 0 && sh.head_dim == 128) ALAYA_ATTEND(0, 128);
     else if (sh.dtype == 0 && sh.head_dim == 64) ALAYA_ATTEND(0, 64);
     else if (sh.dtype == 1 && sh.head_dim == 128) ALAYA_ATTEND(1, 128);

@@ -24,11 +24,12 @@
 //           score >= max - beta), "candidate" (top-k only: bucket == b) or neither, and compacts the
 //           segment into its own region: definite tokens from the front, candidates from the back,
 //           both in ascending token order.
-//   finish  per head: gather the segments' definite lists into the head's final list (a binary search
+//   finish  (top-k only; the gather kernel of a DIPR call reads the segments' lists as they are)
+//           per head: gather the segments' definite lists into the head's final list (a binary search
 //           over the segment prefix sums finds each element's source), gather the candidates behind
 //           them, radix-refine the remaining 21 key bits over the candidates and keep key > T and the
 //           first `ties` tokens with key == T (from registers when they are at most 4096, in place
-//           otherwise); take top-k's head maximum from the finished list; publish the count, copy ids
+//           otherwise); take the head maximum from the finished list; publish the count, copy ids
 //           out if asked, and reset the head's histogram, maximum and repair mark for the next call.
 #include "alaya_internal.h"
 
@@ -304,7 +305,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_local_kernel(
     rule.b1 = bucket_rule ? (uint32_t)res[0] : 0u;
     rule.thr = mode == 1 ? M - dsc.beta : -INFINITY; // top-k with k >= n: every token
     if (id.seg == 0 && tid == 0) {
-        if (mode == 1) head_M[rh] = M; // top-k: written by the finishing pass
+        if (mode == 1) head_M[rh] = M; // top-k: written by the finishing pass (a DIPR call has none)
         head_info[2 * rh] = bucket_rule ? res[0] : -1;
         head_info[2 * rh + 1] = bucket_rule ? res[1] : 0;
     }
@@ -351,7 +352,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_local_kernel(
 
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
-    const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int H_q, int mode, const int32_t *__restrict__ head_info,
+    const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int H_q, const int32_t *__restrict__ head_info,
     const int32_t *__restrict__ seg_counts, const float *__restrict__ loc_scores,
     const int32_t *__restrict__ loc_ids, uint32_t *__restrict__ hist, uint32_t *__restrict__ head_maxkey,
     int32_t *__restrict__ sel_ids, float *__restrict__ sel_scores, int32_t *__restrict__ counts,
@@ -577,11 +578,9 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
     if (lane == 0) wred[tid >> 6] = mx;
     __syncthreads(); // list complete and visible to the whole workgroup
     if (tid == 0) {
-        if (mode == 0) { // top-k: the largest score overall is the largest selected one
-            float M = wred[0];
-            for (int w = 1; w < kSelWaves; ++w) M = fmaxf(M, wred[w]);
-            head_M[rh] = M;
-        }
+        float M = wred[0]; // the largest score overall is the largest selected one
+        for (int w = 1; w < kSelWaves; ++w) M = fmaxf(M, wred[w]);
+        head_M[rh] = M;
         counts[rh] = count;
         if (out_counts) out_counts[rh] = count;
         if (out_ids && (int64_t)count > ids_stride) atomicOr(status, 1);
@@ -594,8 +593,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
         int32_t *dst = out_ids + (size_t)rh * (size_t)ids_stride;
         for (int i = tid; i < m; i += kSelectThreads) dst[i] = ids[i];
     }
-    if (mode == 0)
-        for (int i = tid; i < kHistBins; i += kSelectThreads) hist[(size_t)rh * kHistBins + i] = 0u;
+    for (int i = tid; i < kHistBins; i += kSelectThreads) hist[(size_t)rh * kHistBins + i] = 0u;
 }
 
 hipError_t launch_select_front(const Shape &sh, const DeviceViews &dv, int B, int mode, int total_segs,
@@ -629,7 +627,7 @@ hipError_t launch_select_back(const Shape &sh, const DeviceViews &dv, int B, int
         if (e != hipSuccess) return e;
     }
     select_finish_kernel<<<dim3((unsigned)(B * sh.n_q_heads)), block, 0, st>>>(
-        dv.desc.mem, dv.desc.in, dv.desc.n, sh.n_q_heads, mode, dv.head_info, dv.seg_counts, dv.loc_scores, dv.loc_ids, dv.hist,
+        dv.desc.mem, dv.desc.in, dv.desc.n, sh.n_q_heads, dv.head_info, dv.seg_counts, dv.loc_scores, dv.loc_ids, dv.hist,
         dv.head_maxkey, dv.sel_ids, dv.sel_scores, dv.counts, out_ids, out_counts, ids_stride, dv.status,
         dv.head_M, dv.fail, dv.any_fail);
     return hipGetLastError();
