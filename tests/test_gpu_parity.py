@@ -222,6 +222,39 @@ def test_decode_step_in_one_call_equals_append_then_attend(lens, mode, kw):
     a.close(); b.close()
 
 
+def test_decode_steps_from_an_empty_cache_until_the_pool_is_empty():
+    """Every token of two sequences arrives through alaya_decode_step, from the first one on; checked
+    against the oracle around page boundaries.  A step that the page pool cannot serve changes nothing."""
+    n = 300
+    w = _llama([n, n], topk=[4, 4])
+    g = wl.generate(w)
+    c = A.Cache(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, max_seqs=2, max_batch=2, max_tokens_per_seq=512,
+                max_batch_tokens=1024, n_phys_pages=12)
+    c.k_pool.fill_(0xFF); c.v_pool.fill_(0xFF); c.workspace.fill_(0xFF)
+    q = to_device(g["q"], w.dtype)
+    for mode, kw in [(A.ALAYA_TOPK, dict(topk=[4, 4])), (A.ALAYA_DIPR, dict(beta=[1.0, 1.0]))]:
+        for r in (0, 1):
+            c.reset_seq(r)
+        for s in range(n):
+            ks = to_device(np.stack([g["K"][r][s] for r in range(2)]), w.dtype)
+            vs = to_device(np.stack([g["V"][r][s] for r in range(2)]), w.dtype)
+            out, ids, counts = c.decode_step([0, 1], ks, vs, q, mode, ids_stride=n, **kw)
+            if s in (0, 1, 62, 63, 64, 65, 127, 128, 255, 256, n - 1):
+                ws = wl.resized(w, [s + 1, s + 1], topk=[4, 4])
+                gs = dict(g, K=[g["K"][r][:s + 1] for r in range(2)], V=[g["V"][r][:s + 1] for r in range(2)])
+                torch.cuda.synchronize()
+                assert c.poll_status() == A.ALAYA_OK
+                compare_sparse(ws, gs, out, ids, counts, mode, topk=kw.get("topk"), beta=kw.get("beta"))
+    one = to_device(np.stack([g["K"][r][0] for r in range(2)]), w.dtype)
+    for _ in range(384 - n):                     # 12 pages: both sequences can fill their sixth page
+        c.decode_step([0, 1], one, one, q, A.ALAYA_TOPK, topk=[4, 4])
+    with pytest.raises(A.AlayaError) as e:
+        c.decode_step([0, 1], one, one, q, A.ALAYA_TOPK, topk=[4, 4])
+    assert e.value.code == A.ALAYA_E_NOMEM and "exhausted" in str(e.value)
+    assert [c.seq_len(0), c.seq_len(1)] == [384, 384]
+    c.close()
+
+
 def test_decode_step_errors_and_prefix():
     """A refused append changes nothing; a refused attention part leaves the token appended, as the two
     separate calls would; with a visible prefix the call is simply the two calls in turn."""
