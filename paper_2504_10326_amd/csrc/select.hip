@@ -28,7 +28,7 @@
 //           per head: gather the segments' definite lists into the head's final list (a binary search
 //           over the segment prefix sums finds each element's source), gather the candidates behind
 //           them, radix-refine the remaining 21 key bits over the candidates and keep key > T and the
-//           first `ties` tokens with key == T (from registers when they are at most 4096, in place
+//           first `ties` tokens with key == T (from registers when they are at most 16384, in place
 //           otherwise); take the head maximum from the finished list; publish the count, copy ids
 //           out if asked, and reset the head's histogram, maximum and repair mark for the next call.
 #include "alaya_internal.h"
@@ -38,7 +38,7 @@ namespace alaya {
 constexpr int kSelE = 4;                       // elements per thread per chunk
 constexpr int kSelWaves = kSelectThreads / 64; // 16
 constexpr int kSelChunk = kSelE * kSelectThreads;
-constexpr int kFinSets = 3;                    // chunks of tie-bucket tokens the finishing pass keeps in registers
+constexpr int kFinSets = 4;                    // chunks of tie-bucket tokens the finishing pass keeps in registers
 static_assert(kSelE * kSelWaves == 64, "the cross-wave scan maps one (e, wave) pair to one lane of wave 0");
 static_assert(kMaxSegPages == 2 * kSelectThreads, "the page-count scan takes two pages per thread");
 
@@ -436,6 +436,17 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
         for (int s = 0; s < kFinSets; ++s) {
 #pragma unroll
             for (int e = 0; e < kSelE; ++e) {
+                in[s][e] = false;
+                v[s][e] = 0.f;
+                idv[s][e] = 0;
+                key[s][e] = 0u;
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < kFinSets; ++s) {
+            if (s * kSelChunk >= cb) break; // (uniform) the sets behind the last candidate stay empty
+#pragma unroll
+            for (int e = 0; e < kSelE; ++e) {
                 const int i = s * kSelChunk + e * kSelectThreads + tid;
                 in[s][e] = i < cb;
                 const int sgm = in[s][e] ? find_seg(preC, i) : 0;
@@ -453,10 +464,12 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
             for (int i = tid; i < kHistBins; i += kSelectThreads) lh[i] = 0u;
             __syncthreads();
 #pragma unroll
-            for (int s = 0; s < kFinSets; ++s)
+            for (int s = 0; s < kFinSets; ++s) {
+                if (s * kSelChunk >= cb) break;
 #pragma unroll
                 for (int e = 0; e < kSelE; ++e)
                     if (in[s][e]) atomicAdd(&lh[(key[s][e] >> 10) & 0x7FFu], 1u);
+            }
             __syncthreads();
             block_find_bin(lh, 2048, need, wtot, res);
             const uint32_t b2 = (uint32_t)res[0];
@@ -466,10 +479,12 @@ __global__ __launch_bounds__(kSelectThreads) void select_finish_kernel(
             __syncthreads();
             const uint32_t pre = (b1 << 11) | b2; // key >> 10 of the threshold
 #pragma unroll
-            for (int s = 0; s < kFinSets; ++s)
+            for (int s = 0; s < kFinSets; ++s) {
+                if (s * kSelChunk >= cb) break;
 #pragma unroll
                 for (int e = 0; e < kSelE; ++e)
                     if (in[s][e] && (key[s][e] >> 10) == pre) atomicAdd(&lh[key[s][e] & 0x3FFu], 1u);
+            }
             __syncthreads();
             block_find_bin(lh, 1024, need, wtot, res);
             T = (pre << 10) | (uint32_t)res[0];
