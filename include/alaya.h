@@ -187,9 +187,10 @@ int alaya_poll_status(alaya_cache *c, void *stream);
  * alaya_kernel_times synchronises them and returns, per kernel slot, the summed duration in
  * milliseconds and the number of launches since profiling was (re)enabled.
  * Slots: 0 score (the main scoring pass; its events are attached to the kernel's dispatch, so the
- * figure is the kernel's own run time), 1 select (statistics, local selection, the repair launches
- * of the estimated bound, finish), 2 attend, 3 combine, 4 full-attention partial, 5 append,
- * 6 sample (scoring of the sampled pages + the threshold bound).  Slots other than 0 span from an
+ * figure is the kernel's own run time), 1 select (local selection; for top-k also the statistics,
+ * the repair launches of the estimated bound and the finishing pass), 2 attend, 3 combine,
+ * 4 full-attention partial, 5 append (the append kernel; an alaya_decode_step has none: its sample
+ * pass writes the new rows), 6 sample (scoring of the sampled pages + the threshold bound).  Slots other than 0 span from an
  * event before their first launch to one after their last, dispatch gaps included.
  * sum_ms, launches: HOST arrays of n_slots entries (n_slots <= ALAYA_N_KERNEL_SLOTS).
  */
