@@ -11,7 +11,7 @@ import torch
 import oracle
 import paper_2504_10326_amd as A
 import workloads as wl
-from parity_util import OUT_TOL, make_cache, run_and_compare, to_device
+from parity_util import OUT_TOL, compare_sparse, make_cache, run_and_compare, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -26,9 +26,29 @@ def _case(name, seed=0):
     _say(f"{name}: generating {w.total_tokens} tokens x {w.n_kv_heads} KV heads")
     g = wl.generate(w)
     _say(f"{name}: generated in {time.time() - t0:.1f}s, loading the cache")
-    c = make_cache(w, g)
+    c = make_cache(w, g, extra_tokens=64)          # room for the decode steps at the end of each test
     _say(f"{name}: cache loaded")
     return w, g, c
+
+
+def _decode_step(name, c, w, g, mode, **kw):
+    """What bench.py times: one alaya_decode_step (a new token for every request, then the query over
+    the grown sequences), every head against the oracle.  Returns the grown workload and inputs."""
+    B = w.batch
+    knew = np.stack([g["K"][r][w.lens[r] // 3] for r in range(B)])       # any rows will do
+    vnew = np.stack([g["V"][r][w.lens[r] // 5] for r in range(B)])
+    q = to_device(g["q"], w.dtype)
+    stride = max(w.lens) + 1 if mode == A.ALAYA_DIPR else max(kw["topk"]) + sum(kw.get("window", (0, 0)))
+    out, ids, counts = c.decode_step(list(range(B)), to_device(knew, w.dtype), to_device(vnew, w.dtype), q, mode,
+                                     ids_stride=stride, **kw)
+    torch.cuda.synchronize()
+    assert c.poll_status() == A.ALAYA_OK
+    w2 = wl.resized(w, [n + 1 for n in w.lens], topk=kw.get("topk"))
+    g2 = dict(g, K=[np.concatenate([g["K"][r], knew[r:r + 1]]) for r in range(B)],
+              V=[np.concatenate([g["V"][r], vnew[r:r + 1]]) for r in range(B)])
+    st = compare_sparse(w2, g2, out, ids, counts, mode, kw.get("topk"), kw.get("beta"), window=kw.get("window", (0, 0)))
+    _say(f"{name}: decode step in one call, out err {st['max_out_err']:.2e}, band heads {st['band_heads']}")
+    return w2, g2
 
 
 def test_llama8b_128k_topk2048():
@@ -47,6 +67,8 @@ def test_llama8b_128k_topk2048():
          f"out err {st['max_out_err']:.2e}")
     st = run_and_compare(c, w, g, A.ALAYA_TOPK, topk=[2000], window=(128, 512), n_visible=[100000], check_scores=False)
     _say(f"llama8b_128k prefix 100000, [128+512]+2000: out err {st['max_out_err']:.2e}, band heads {st['band_heads']}")
+    w, g = _decode_step("llama8b_128k", c, w, g, A.ALAYA_TOPK, topk=list(w.topk))
+    _decode_step("llama8b_128k [128+512] DIPR", c, w, g, A.ALAYA_DIPR, beta=[2.0], window=(128, 512))
     c.close()
 
 
@@ -57,6 +79,7 @@ def test_range_256k_dipr_betas():
         cnt = np.array(st["counts"])
         _say(f"range_256k beta={beta}: selected per head min/median/max = {cnt.min()}/{int(np.median(cnt))}/"
              f"{cnt.max()}, out err {st['max_out_err']:.2e}, band heads {st['band_heads']}")
+    _decode_step("range_256k", c, w, g, A.ALAYA_DIPR, beta=[2.0])
     c.close()
 
 
@@ -76,6 +99,7 @@ def test_paged_1m_topk4096_permuted_pages():
     err = float(np.abs(full[0] - ref).max())
     _say(f"paged_1m: full attention err {err:.2e}")
     assert err <= OUT_TOL
+    _decode_step("paged_1m", c, w, g, A.ALAYA_TOPK, topk=list(w.topk))
     c.close()
 
 
@@ -84,6 +108,7 @@ def test_batched_16_requests_one_launch():
     st = run_and_compare(c, w, g, A.ALAYA_TOPK, topk=w.topk)
     _say(f"batched_16: lens {w.lens}, out err {st['max_out_err']:.2e}, score err {st['max_score_err']:.2e}, "
          f"band heads {st['band_heads']}")
+    _decode_step("batched_16", c, w, g, A.ALAYA_TOPK, topk=list(w.topk))
     c.close()
 
 
