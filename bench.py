@@ -1,29 +1,36 @@
 #!/usr/bin/env python3
 """Decode-step sparse-attention benchmark on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama8b_128k]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload batched_16] [--no-per-config]
 
 One step = one decode step of one layer: append the new token's key/value (Session.update), then
 the sparse-attention query (Session.attention): score every cached key, select top-k (or DIPR),
 gather the selected value rows, softmax-weighted sum, merge.  Both through one alaya_decode_step
 call (--separate-append: through alaya_append_kv_step and alaya_sparse_attn, one launch more).
-Inputs are resident in HBM before the timed region.  Prints ONE JSON line:
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line whose headline fields
+(value, ms_per_step, roofline, cpu_baseline, config) are those of --workload - by default the
+largest configuration, 16 requests of 32K..256K tokens in one call - and whose per_config block
+repeats the measurement on the other configurations (128K, 256K at beta = 2 and 4, 1M).
 
   value       keys scored per second over the whole step  (a key-score = one (query head, token) pair)
   roofline    the main scoring kernel against the 8 TB/s HBM peak.  Algorithmic bytes per launch =
-              256 B (one bf16 K row, read once) x the K rows that launch scores (the pages that the
-              sample pass did not take, x 64 tokens x KV heads); the few survivors it writes are not
-              counted.  Duration = the kernel's average over a profiled repeat of the timed loop,
-              taken with HIP events attached to the kernel's own dispatch on the launch stream (the
-              library's profiling mode; events between kernels would lengthen the timed steps
-              themselves, so the timed loop runs without them).
-  cold_cache  per-kernel times of the same step when the last-level cache is flushed before it
+              256 B (one bf16 K row, read once) x the K rows of the call (tokens rounded up to pages
+              x KV heads); the few survivors it writes are not counted.  Duration = the kernel's
+              average over a profiled repeat of the timed loop, taken with HIP events attached to
+              the kernel's own dispatch on the launch stream (the library's profiling mode; events
+              between kernels would lengthen the timed steps themselves, so the timed loop runs
+              without them).  When the keys of the call are smaller than 512 MB they partly survive
+              in the 256 MB last-level cache from step to step, which no model with many layers
+              would see: `frac` is then taken from the cold loop (cache flushed before every step)
+              and the warm figure is reported beside it.  scoring_pass_frac = the same bytes over
+              sample pass + bound + main pass.
   gather      the gather + attend kernel: one V row (256 B) per selected (head, token), same clock
   cpu_baseline  the CPU oracle on the same step, on this host's cores (a reported baseline only)
 """
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -34,52 +41,25 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+LLC_BYTES = 512e6          # below this the keys of a call partly stay in the last-level cache
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="llama8b_128k",
-                    choices=["llama8b_128k", "range_256k", "paged_1m", "batched_16"])
-    ap.add_argument("--beta", type=float, default=2.0, help="DIPR margin for range_256k")
-    ap.add_argument("--window", default="0,0",
-                    help="INIT,LAST tokens that are always attended (the paper's tables use 128,512)")
-    ap.add_argument("--separate-append", action="store_true",
-                    help="append and attend through two calls instead of one alaya_decode_step")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cold-steps", type=int, default=40,
-                    help="extra steps with the last-level cache flushed before each (0 = skip)")
-    ap.add_argument("--pages-per-wave", type=int, default=0)
-    ap.add_argument("--attend-splits", type=int, default=0)
-    ap.add_argument("--segment-pages", type=int, default=0)
-    ap.add_argument("--write-all-scores", action="store_true")
-    ap.add_argument("--calibration-copy-mb", type=int, default=0,
-                    help="also run a plain device copy of this many MiB (reference for rocprofv3 byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
-        return 2
-
+def measure(name, args, steps, warmup, cold_steps, cpu_baseline, beta=None, dense=True):
+    """One workload: timed loop, profiled loop, cold-cache loop, optional oracle timing.  Returns a dict."""
     import numpy as np
     import torch
 
     import paper_2504_10326_amd as A
     import workloads as wl
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
-        return 1
-    A.lib()
-    K_steps, W = args.steps, args.warmup
-    w = wl.config(args.workload)
+    w = wl.config(name)
+    beta = args.beta if beta is None else beta
     t0 = time.time()
     g = wl.generate(w)
     print(f"[bench] generated {w.name}: {w.total_tokens} tokens in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
 
-    # Each step appends one token per request, so leave room for every step of both passes.
-    extra = 2 * (W + K_steps) + args.cold_steps + 8
+    # Each step appends one token per request, so leave room for every step of all passes.
+    extra = 2 * (warmup + steps) + cold_steps + 16
     n_phys = g["n_phys_pages"] + w.batch * ((extra + 63) // 64 + 1)
     order = g["page_order"]
     if len(order) < n_phys:
@@ -96,28 +76,36 @@ def main() -> int:
     for r, n in enumerate(w.lens):
         c.append_kv(r, dev(g["K"][r][:n - 1]), dev(g["V"][r][:n - 1]))
     q = dev(g["q"])
-    new_k = [dev(g["K"][r][w.lens[r] - 1:]) for r in range(w.batch)]
-    new_v = [dev(g["V"][r][w.lens[r] - 1:]) for r in range(w.batch)]
+    # What the steps append: the workload's own last token first, then fresh random rows - a new
+    # key and value for every step and request, as a decoding model would emit them.
+    n_new = extra + 1
+    ek = np.empty((n_new, w.batch, w.n_kv_heads, w.head_dim), dtype=np.uint16)
+    ev = np.empty_like(ek)
+    for r in range(w.batch):
+        k2, v2 = wl.extra_tokens(w, r, n_new - 1)
+        ek[0, r], ev[0, r] = g["K"][r][w.lens[r] - 1], g["V"][r][w.lens[r] - 1]
+        ek[1:, r], ev[1:, r] = k2, v2
+    step_k, step_v = dev(ek), dev(ev)                        # [step][batch][H_kv][d]
+    cursor = [0]
     seqs = list(range(w.batch))
     out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
     window = tuple(int(x) for x in args.window.split(","))
     if w.mode == "topk":
         mode, kw = A.ALAYA_TOPK, dict(topk=list(w.topk), window=window)
     else:
-        mode, kw = A.ALAYA_DIPR, dict(beta=[args.beta] * w.batch, window=window)
-    c.set_tuning(args.pages_per_wave, args.attend_splits, args.segment_pages, args.write_all_scores)
+        mode, kw = A.ALAYA_DIPR, dict(beta=[beta] * w.batch, window=window)
+    c.set_tuning(args.pages_per_wave, args.attend_splits, 0, args.write_all_scores)
     torch.cuda.synchronize()
-
-    step_k = torch.cat(new_k, dim=0).contiguous()            # [batch][H_kv][d]: one new token per request
-    step_v = torch.cat(new_v, dim=0).contiguous()
 
     if args.separate_append:
         def step():
-            c.append_step(seqs, step_k, step_v)              # Session.update for the whole batch, one launch
-            c.sparse_attn(seqs, q, mode, out=out, **kw)      # Session.attention
+            i = cursor[0] = cursor[0] + 1
+            c.append_step(seqs, step_k[i - 1], step_v[i - 1])  # Session.update for the whole batch, one launch
+            c.sparse_attn(seqs, q, mode, out=out, **kw)        # Session.attention
     else:
-        def step():                                          # both in one call: the first scoring kernel
-            c.decode_step(seqs, step_k, step_v, q, mode, out=out, **kw)   # writes the new rows itself
+        def step():                                            # both in one call: the first scoring kernel
+            i = cursor[0] = cursor[0] + 1                      # writes the new rows itself
+            c.decode_step(seqs, step_k[i - 1], step_v[i - 1], q, mode, out=out, **kw)
 
     def run(n_steps):
         """n_steps steps bracketed by synchronisation; returns (seconds, key-scores, K rows scored)."""
@@ -132,26 +120,27 @@ def main() -> int:
         toks = n_steps * before + w.batch * n_steps * (n_steps + 1) // 2
         return dt, w.n_q_heads * toks, w.n_kv_heads * toks
 
-    run(W)
-    secs, keys, rows = run(K_steps)
-    ms_per_step = secs / K_steps * 1e3
+    run(warmup)
+    secs, keys, rows = run(steps)
+    ms_per_step = secs / steps * 1e3
 
     # Profiled repeat of the same loop: per-kernel durations from HIP events on the launch stream.
     c.set_profiling(True)
-    run(K_steps)
+    run(steps)
     kt = c.kernel_times()
     c.set_profiling(False)
     pages_sampled, pages_main = c.debug_pages()              # of the last step (the context grows by one token a step)
     survivors = c.debug_survivors()
-    score_ms = kt["score"]["sum_ms"] / max(1, kt["score"]["launches"])
     bytes_per_row = w.head_dim * 2                            # one bf16 K row, read once
     bytes_per_launch = pages_main * 64 * w.n_kv_heads * bytes_per_row
-    achieved = bytes_per_launch / (score_ms * 1e-3) / 1e9
-    traffic = None
-    tpath = os.path.join(ROOT, "paper_2504_10326_amd", "measured_traffic.json")
-    if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(w.name, {}).get("score_kernel_hbm_bytes_per_launch")
-    kernels_us = {k: round(v["sum_ms"] / v["launches"] * 1e3, 2) for k, v in kt.items() if v["launches"]}
+
+    def per_kernel(k):
+        us = {n: round(v["sum_ms"] / v["launches"] * 1e3, 2) for n, v in k.items() if v["launches"]}
+        main_s = k["score"]["sum_ms"] / max(1, k["score"]["launches"]) * 1e-3
+        pass_s = main_s + k["sample"]["sum_ms"] / max(1, k["sample"]["launches"]) * 1e-3
+        return us, bytes_per_launch / main_s / 1e9, bytes_per_launch / pass_s / 1e9, main_s
+
+    kernels_us, warm_gbs, warm_pass_gbs, warm_main_s = per_kernel(kt)
     # The gather + attend kernel reads one V row per selected (head, token).
     _, counts = c.sparse_attn(seqs, q, mode, out=out, want_counts=True, **kw)
     selected_rows = int(counts.sum().item())
@@ -162,33 +151,36 @@ def main() -> int:
               "frac": gather_bytes / (attend_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
     # The same steps with the last-level cache flushed before each one (a 1 GiB buffer is read, which
-    # leaves no dirty lines behind to be written back during the step):
-    # in a model with many layers every layer's keys arrive cold.  Only the per-kernel event times of
-    # this loop are used; its wall clock includes the flushes.
+    # leaves no dirty lines behind to be written back during the step): in a model with many layers
+    # every layer's keys arrive cold.  Only the per-kernel event times of this loop are used; its wall
+    # clock includes the flushes.
     cold = None
-    if args.cold_steps > 0:
+    if cold_steps > 0:
         scratch = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
         c.set_profiling(True)
-        for _ in range(args.cold_steps):
+        for _ in range(cold_steps):
             scratch.sum()
             step()
         torch.cuda.synchronize()
         ktc = c.kernel_times()
         c.set_profiling(False)
         del scratch
-        cold_ms = ktc["score"]["sum_ms"] / max(1, ktc["score"]["launches"])
-        cold_us = {k: round(v["sum_ms"] / v["launches"] * 1e3, 2) for k, v in ktc.items() if v["launches"]}
-        cold = {"steps": args.cold_steps, "kernels_us": cold_us, "step_kernel_sum_us": round(sum(cold_us.values()), 2),
-                "main_pass_achieved": bytes_per_launch / (cold_ms * 1e-3) / 1e9, "unit": "GB/s",
-                "main_pass_frac": bytes_per_launch / (cold_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        cold_us, cold_gbs, cold_pass_gbs, cold_main_s = per_kernel(ktc)
+        gather_cold_ms = ktc["attend"]["sum_ms"] / max(1, ktc["attend"]["launches"])
+        cold = {"steps": cold_steps, "kernels_us": cold_us, "step_kernel_sum_us": round(sum(cold_us.values()), 2),
+                "main_pass_achieved": cold_gbs, "unit": "GB/s", "main_pass_frac": cold_gbs / HBM_PEAK_GBS,
+                "scoring_pass_frac": cold_pass_gbs / HBM_PEAK_GBS,
+                "gather_frac": gather_bytes / (gather_cold_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
     # Dense attention over the same cache, for context (reads K and V once each).
-    torch.cuda.synchronize()
-    t = time.perf_counter()
-    for _ in range(10):
-        c.full_attn(seqs, q, out=out)
-    torch.cuda.synchronize()
-    full_ms = (time.perf_counter() - t) / 10 * 1e3
+    full_ms = None
+    if dense:
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(10):
+            c.full_attn(seqs, q, out=out)
+        torch.cuda.synchronize()
+        full_ms = (time.perf_counter() - t) / 10 * 1e3
 
     if args.calibration_copy_mb > 0:
         # A plain copy of known size: what FETCH_SIZE / WRITE_SIZE read for it gives the counters' scale.
@@ -200,7 +192,7 @@ def main() -> int:
         del src, dst
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if cpu_baseline:
         import oracle
         # One whole step of the first request on the oracle (scores, selection, attention; fp64).
         # Repeated until it has used about 20 s of CPU time (threads x wall), so that the figure is stable.
@@ -210,7 +202,7 @@ def main() -> int:
         while True:
             res = oracle.sparse_attn(g["q"][0], g["K"][0], g["V"][0],
                                      oracle.TOPK if w.mode == "topk" else oracle.DIPR,
-                                     k=w.topk[0] if w.topk else 0, beta=args.beta, want_ids=False, window=window)
+                                     k=w.topk[0] if w.topk else 0, beta=beta, want_ids=False, window=window)
             reps += 1
             dt = time.perf_counter() - t0
             cpu_s = dt * int(res["threads"])
@@ -221,7 +213,7 @@ def main() -> int:
         t1 = time.perf_counter()
         oracle.sparse_attn(g["q"][0][:G], g["K"][0][:, :1], g["V"][0][:, :1],
                            oracle.TOPK if w.mode == "topk" else oracle.DIPR,
-                           k=w.topk[0] if w.topk else 0, beta=args.beta, want_ids=False, threads=1, window=window)
+                           k=w.topk[0] if w.topk else 0, beta=beta, want_ids=False, threads=1, window=window)
         dt1 = time.perf_counter() - t1
         model = ""
         try:
@@ -236,14 +228,21 @@ def main() -> int:
                          f"{dt:.2f} s wall, about {cpu_s:.0f} s of CPU time"}
 
     total_n = sum(c.seq_len(r) for r in seqs)
-    line = {
-        "metric": "keys scored/s (one layer, sparse decode step: append + score + select + gather + attend)",
-        "value": keys / secs, "unit": "keys/s", "n_gpus": 1, "steps": K_steps, "warmup": W,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+    # Bytes the main pass moved as rocprofv3 counted them - from the committed summaries, not from this run.
+    traffic, traffic_source = None, None
+    tpath = os.path.join(ROOT, "profiles", "measured_traffic.json")
+    if os.path.exists(tpath):
+        ent = json.load(open(tpath)).get(w.name)
+        if ent:
+            traffic, traffic_source = ent.get("main_pass_hbm_bytes_per_launch"), ent.get("source")
+    k_bytes = bytes_per_launch
+    use_cold = cold is not None and k_bytes < LLC_BYTES
+    achieved = cold["main_pass_achieved"] if use_cold else warm_gbs
+    res = {
+        "value": keys / secs, "ms_per_step": ms_per_step,
         "config": {"workload": w.name, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
                    "batch": w.batch, "tokens": total_n, "mode": w.mode,
-                   "topk": list(w.topk) if w.topk else None, "beta": args.beta if w.mode == "dipr" else None,
+                   "topk": list(w.topk) if w.topk else None, "beta": beta if w.mode == "dipr" else None,
                    "paged": "64-token pages" + (", randomly permuted" if w.permute_pages else ""),
                    "accumulate": "fp32", "window": list(window),
                    "calls_per_step": "alaya_append_kv_step + alaya_sparse_attn" if args.separate_append
@@ -254,15 +253,88 @@ def main() -> int:
         "full_attn_ms": full_ms,
         "survivor_fraction": survivors / (w.n_q_heads * total_n),
         "pages": {"sampled": pages_sampled, "main_pass": pages_main},
-        "roofline": {"bound": "hbm", "kernel": "score_kernel (main pass)", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "bytes_per_launch": bytes_per_launch, "avg_us": score_ms * 1e3},
+        "roofline": {"bound": "hbm", "kernel": "main_kernel (main scoring pass)", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "cache": "cold (last-level cache flushed before every step)" if use_cold else
+                              "as timed (the keys of one call are far larger than the last-level cache)",
+                     "warm_frac": warm_gbs / HBM_PEAK_GBS,
+                     "scoring_pass_frac": (cold["scoring_pass_frac"] if use_cold else warm_pass_gbs / HBM_PEAK_GBS),
+                     "traffic": traffic, "traffic_source": traffic_source,
+                     "bytes_per_launch": bytes_per_launch,
+                     "avg_us": (bytes_per_launch / (achieved * 1e9)) * 1e6},
         "gather": gather,
         "cold_cache": cold,
         "cpu_baseline": cpu,
     }
-    print(json.dumps(line))
     c.close()
+    del c, g, q, step_k, step_v, ek, ev, out
+    gc.collect()
+    torch.cuda.empty_cache()
+    return res
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="batched_16",
+                    choices=["llama8b_128k", "range_256k", "paged_1m", "batched_16"])
+    ap.add_argument("--beta", type=float, default=2.0, help="DIPR margin for range_256k")
+    ap.add_argument("--window", default="0,0",
+                    help="INIT,LAST tokens that are always attended (the paper's tables use 128,512)")
+    ap.add_argument("--separate-append", action="store_true",
+                    help="append and attend through two calls instead of one alaya_decode_step")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true", help="measure only --workload")
+    ap.add_argument("--cold-steps", type=int, default=40,
+                    help="extra steps with the last-level cache flushed before each (0 = skip)")
+    ap.add_argument("--pages-per-wave", type=int, default=0)
+    ap.add_argument("--attend-splits", type=int, default=0)
+    ap.add_argument("--write-all-scores", action="store_true")
+    ap.add_argument("--calibration-copy-mb", type=int, default=0,
+                    help="also run a plain device copy of this many MiB (reference for rocprofv3 byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2504_10326_amd as A
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 1
+    A.lib()
+    head = measure(args.workload, args, args.steps, args.warmup, args.cold_steps, not args.no_cpu_baseline)
+    per_config = {}
+    if not args.no_per_config:
+        others = [("llama8b_128k", None), ("range_256k", 2.0), ("range_256k", 4.0), ("paged_1m", None), ("batched_16", None)]
+        for name, beta in others:
+            if name == args.workload and (beta is None or beta == args.beta):
+                continue
+            r = measure(name, args, min(args.steps, 100), min(args.warmup, 10), min(args.cold_steps, 20), False,
+                        beta=beta, dense=False)
+            key = name if beta is None else f"{name}_beta{beta:g}"
+            per_config[key] = {"ms_per_step": r["ms_per_step"], "keys_per_s": r["value"], "tokens": r["config"]["tokens"],
+                               "kernels_us": r["kernels_us"], "survivor_fraction": r["survivor_fraction"],
+                               "main_pass_frac": r["roofline"]["frac"], "main_pass_warm_frac": r["roofline"]["warm_frac"],
+                               "main_pass_cache": r["roofline"]["cache"],
+                               "scoring_pass_frac": r["roofline"]["scoring_pass_frac"],
+                               "gather_frac": r["gather"]["frac"], "gather_rows": r["gather"]["selected_rows"],
+                               "cold_kernels_us": r["cold_cache"]["kernels_us"] if r["cold_cache"] else None}
+    line = {
+        "metric": "keys scored/s (one layer, sparse decode step: append + score + select + gather + attend)",
+        "value": head["value"], "unit": "keys/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+    }
+    for k in ("config", "latency_us_per_layer", "k_rows_per_s", "kernels_us", "full_attn_ms", "survivor_fraction", "pages",
+              "roofline", "gather", "cold_cache", "cpu_baseline"):
+        line[k] = head[k]
+    line["per_config"] = per_config
+    print(json.dumps(line))
     return 0
 
 

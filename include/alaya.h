@@ -9,17 +9,17 @@
  * tokens, and take the softmax-weighted sum of their values.
  *
  *   scores      s[h][j] = q_h . k_{h/G, j}         raw inner product, no 1/sqrt(d)  (Eq. 1; Def. 2)
- *   top-k       the min(k, n) tokens with the largest s[h][.]                        (Sec. 5.1.1)
+ *   top-k       the min(k, n) tokens with the largest s[h][.]                        (Sec. 6.1.1)
  *   DIPR        every j with s[h][j] >= max_j s[h][j] - beta,  beta >= 0            (Def. 2, Def. 3)
  *   attention   softmax of s * scale over the SELECTED tokens, times their values   (Eq. 1, Sec. 2
  *               "Sparse Attention"; partial results merged by running max / sum,
- *               Sec. 6.2 "Data-centric Attention Engine")
- *   GQA         query head h reads key/value head h / G, G = n_q_heads / n_kv_heads (Sec. 6.2)
+ *               Sec. 7.2 "Data-centric Attention Engine")
+ *   GQA         query head h reads key/value head h / G, G = n_q_heads / n_kv_heads (Sec. 7.2)
  *
  * Conventions
  *   - Every pointer is tagged HOST or DEVICE below.  The library never allocates
- *     or frees device memory: pools and workspace are the caller's, and stay the
- *     caller's.  It keeps a few KB of pinned host memory per cache for descriptors.
+ *     or frees device memory: pools, page-table workspace and scratch are the caller's,
+ *     and stay the caller's.  It keeps a few KB of pinned host memory per cache for descriptors.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
  *     asynchronous on it.  All calls on one cache must use one stream at a time; the
  *     handle is not thread-safe; distinct caches are independent.
@@ -79,21 +79,36 @@ typedef struct {
     int64_t n_phys_pages;       /* pages in each pool                                      */
 } alaya_cache_config;
 
-/* Bytes of ONE pool (K or V) / of the workspace for this configuration; 0 if cfg is invalid. */
+/* Bytes of ONE pool (K or V) / of the cache's workspace (its page table) / of the scratch memory an
+ * attention call needs for this configuration; 0 if cfg is invalid. */
 size_t alaya_pool_bytes(const alaya_cache_config *cfg);
 size_t alaya_workspace_bytes(const alaya_cache_config *cfg);
+size_t alaya_scratch_bytes(const alaya_cache_config *cfg);
 
 /*
  * Create a cache over caller-owned DEVICE memory: k_pool, v_pool (alaya_pool_bytes each) and
- * workspace (>= alaya_workspace_bytes, 256-byte aligned; holds the page table, scores,
- * selected ids and partial results - its contents are the library's while the cache lives).
+ * workspace (>= alaya_workspace_bytes, 256-byte aligned; holds the page table - its contents are
+ * the library's while the cache lives).
  * phys_page_order: HOST, optional, n_phys_pages distinct page numbers - the order in which
  * physical pages are handed to growing sequences (NULL = 0, 1, 2, ...).  Copied.
- * No device work happens here; the first append or attention call initialises the workspace.
+ * No device work happens here.
  */
 int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k_pool, void *v_pool,
                        const int32_t *phys_page_order, void *workspace, size_t workspace_bytes);
 int alaya_destroy_cache(alaya_cache *c);
+
+/*
+ * Scratch memory for the attention calls of this cache (and for alaya_append_kv_step / alaya_decode_step
+ * of more than one sequence): DEVICE, >= alaya_scratch_bytes(cfg of the cache), 256-byte aligned.  It
+ * holds the survivors of the scoring pass, the selected tokens and the partial results of ONE call;
+ * nothing in it has to outlive a call.  One cache is one layer (Sec. 2: a key/value cache per layer), and
+ * a model runs its layers one after the other, so SEVERAL CACHES MAY BIND THE SAME SCRATCH MEMORY as long
+ * as their calls are ordered on one stream - a 32-layer model then holds one scratch area, not 32.  The
+ * first call of each cache after binding clears the few words that must start at zero; calls leave them
+ * zero.  scratch = NULL unbinds.  alaya_poll_status reads a status word that lives in the scratch memory:
+ * caches that share it share the word.
+ */
+int alaya_bind_scratch(alaya_cache *c, void *scratch, size_t scratch_bytes);
 
 /*
  * Session.update: append t tokens to sequence `seq`.
@@ -180,58 +195,6 @@ int alaya_full_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, c
 /* Synchronises `stream`, then returns and clears the device-side status word of the cache:
  * ALAYA_OK or ALAYA_E_CAPACITY (or ALAYA_E_DEVICE if the sync fails). */
 int alaya_poll_status(alaya_cache *c, void *stream);
-
-/*
- * Kernel timing with HIP events recorded on the call's own stream.
- * alaya_set_profiling(c, 1) makes every later call bracket each of its kernels with events;
- * alaya_kernel_times synchronises them and returns, per kernel slot, the summed duration in
- * milliseconds and the number of launches since profiling was (re)enabled.
- * Slots: 0 score (the main scoring pass; its events are attached to the kernel's dispatch, so the
- * figure is the kernel's own run time), 1 select (local selection; for top-k also the statistics,
- * the repair launches of the estimated bound and the finishing pass), 2 attend, 3 combine,
- * 4 full-attention partial, 5 append (the append kernel; an alaya_decode_step has none: its sample
- * pass writes the new rows), 6 sample (scoring of the sampled pages + the threshold bound).  Slots other than 0 span from an
- * event before their first launch to one after their last, dispatch gaps included.
- * sum_ms, launches: HOST arrays of n_slots entries (n_slots <= ALAYA_N_KERNEL_SLOTS).
- */
-#define ALAYA_N_KERNEL_SLOTS 7
-int alaya_set_profiling(alaya_cache *c, int enabled);
-int alaya_kernel_times(alaya_cache *c, double *sum_ms, int64_t *launches, int n_slots);
-
-/* Launch-shape knobs for measurement sweeps and tests; each <= 0 keeps the built-in choice.
- * score_pages_per_wave: pages one wavefront scores in a row in the main scoring pass (1..16).
- * attend_splits: workgroups that share one head's selected set (1..64).
- * select_segment_pages: pages of one head that one selection workgroup handles (1..2048; at most 64
- * segments per head are used whatever the value).
- * write_all_scores: 1 makes the scoring pass write every score instead of only those that can still
- * be selected (results are identical either way; it exists so that tests can read all scores). */
-int alaya_set_tuning(alaya_cache *c, int score_pages_per_wave, int attend_splits, int select_segment_pages,
-                     int write_all_scores);
-
-/* Test hook for the estimated threshold bound of large top-k calls.  Such calls filter the main
- * scoring pass with a bound that is only very likely to be low enough, check it afterwards against
- * the number of tokens that survived, and repair the heads where it was not (results are exact
- * either way).  mode 0: the library decides (default); 1: estimate whenever the shapes allow;
- * 2: as 1, and with an estimate so high that every head needs the repair; -1: never estimate. */
-int alaya_debug_estimate(alaya_cache *c, int mode);
-
-/* Inspection hook for tests: DEVICE pointer to the fp32 scores the last alaya_sparse_attn call left
- * in the workspace.  Meaningful only if that call ran with write_all_scores = 1.  Requests follow
- * each other, each block being n_q_heads * (n rounded up to a whole page + ALAYA_SCORE_PAD) pairs of
- * (fp32 score, int32 token id) laid out [head][that many pairs]: the pair of token j of head h is
- * pair j of row h.  Valid until the next call on the cache. */
-#define ALAYA_SCORE_PAD 1088
-const float *alaya_debug_scores(const alaya_cache *c);
-
-/* Inspection hook for tests and measurement: synchronises `stream` and returns how many (token, score)
- * pairs the scoring pass of the last alaya_sparse_attn call wrote, summed over requests and heads
- * (with write_all_scores = 0 it is the number of scores that survived the running bound); -1 on error. */
-int64_t alaya_debug_survivors(alaya_cache *c, void *stream);
-
-/* How the last alaya_sparse_attn call split its pages (one page = 64 tokens of one sequence, scored
- * for every KV head): *sampled pages were scored in full to bound the threshold, *main_pass pages
- * were scored against that bound by the main scoring kernel.  HOST pointers. */
-int alaya_debug_pages(const alaya_cache *c, int64_t *sampled, int64_t *main_pass);
 
 /* Thread-local description of the last error returned on this thread ("" if none). */
 const char *alaya_last_error(void);

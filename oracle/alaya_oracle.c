@@ -8,7 +8,7 @@
  *
  * What it computes, per query head h (KV head g = h / G), over n cached tokens:
  *   scores   s_j = q_h . k_{g,j}                      raw inner product (Eq. 1 numerator; Def. 2)
- *   top-k    the min(k, n) tokens with the largest s_j (Sec. 5.1.1); equal scores: smaller j first
+ *   top-k    the min(k, n) tokens with the largest s_j (Sec. 6.1.1); equal scores: smaller j first
  *   DIPR     every j with s_j >= max_s s_s - beta, beta >= 0, inclusive (Def. 2, Def. 3)
  *   attend   z_j = s_j * scale (scale = 1/sqrt(d)); a = softmax over the SELECTED set only;
  *            o = sum_j a_j v_{g,j}                    (Eq. 1 restricted to the critical tokens,

@@ -25,13 +25,16 @@ SCORE_PAD = 1088
 N_KERNEL_SLOTS = 7
 KERNEL_SLOTS = ("score", "select", "attend", "combine", "full_partial", "append", "sample")
 
+# include/alaya.h
 EXPORTS = (
-    "alaya_pool_bytes", "alaya_workspace_bytes", "alaya_create_cache", "alaya_destroy_cache",
-    "alaya_append_kv", "alaya_append_kv_step", "alaya_seq_len", "alaya_reset_seq", "alaya_sparse_attn", "alaya_decode_step",
-    "alaya_full_attn",
-    "alaya_poll_status", "alaya_set_profiling", "alaya_kernel_times", "alaya_set_tuning", "alaya_debug_scores",
-    "alaya_debug_survivors", "alaya_debug_pages", "alaya_debug_estimate",
-    "alaya_last_error",
+    "alaya_pool_bytes", "alaya_workspace_bytes", "alaya_scratch_bytes", "alaya_create_cache", "alaya_bind_scratch",
+    "alaya_destroy_cache", "alaya_append_kv", "alaya_append_kv_step", "alaya_seq_len", "alaya_reset_seq",
+    "alaya_sparse_attn", "alaya_decode_step", "alaya_full_attn", "alaya_poll_status", "alaya_last_error",
+)
+# include/alaya_debug.h
+DEBUG_EXPORTS = (
+    "alaya_set_profiling", "alaya_kernel_times", "alaya_set_tuning", "alaya_debug_scores", "alaya_debug_pages",
+    "alaya_debug_estimate",
 )
 
 
@@ -76,6 +79,8 @@ def lib() -> ctypes.CDLL:
         cfgp = ctypes.POINTER(CacheConfig)
         L.alaya_pool_bytes.argtypes = [cfgp]; L.alaya_pool_bytes.restype = sz
         L.alaya_workspace_bytes.argtypes = [cfgp]; L.alaya_workspace_bytes.restype = sz
+        L.alaya_scratch_bytes.argtypes = [cfgp]; L.alaya_scratch_bytes.restype = sz
+        L.alaya_bind_scratch.argtypes = [vp, vp, sz]; L.alaya_bind_scratch.restype = i32
         L.alaya_create_cache.argtypes = [ctypes.POINTER(vp), cfgp, vp, vp, ctypes.POINTER(ctypes.c_int32), vp, sz]
         L.alaya_create_cache.restype = i32
         L.alaya_destroy_cache.argtypes = [vp]; L.alaya_destroy_cache.restype = i32
@@ -97,8 +102,7 @@ def lib() -> ctypes.CDLL:
         L.alaya_kernel_times.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64), i32]
         L.alaya_kernel_times.restype = i32
         L.alaya_set_tuning.argtypes = [vp, i32, i32, i32, i32]; L.alaya_set_tuning.restype = i32
-        L.alaya_debug_scores.argtypes = [vp]; L.alaya_debug_scores.restype = vp
-        L.alaya_debug_survivors.argtypes = [vp, vp]; L.alaya_debug_survivors.restype = i64
+        L.alaya_debug_scores.argtypes = [vp, vp, vp]; L.alaya_debug_scores.restype = i64
         L.alaya_debug_pages.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64)]
         L.alaya_debug_pages.restype = i32
         L.alaya_debug_estimate.argtypes = [vp, i32]; L.alaya_debug_estimate.restype = i32
@@ -154,6 +158,14 @@ def alaya_pool_bytes(cfg: CacheConfig) -> int:
 
 def alaya_workspace_bytes(cfg: CacheConfig) -> int:
     return lib().alaya_workspace_bytes(ctypes.byref(cfg))
+
+
+def alaya_scratch_bytes(cfg: CacheConfig) -> int:
+    return lib().alaya_scratch_bytes(ctypes.byref(cfg))
+
+
+def alaya_bind_scratch(handle: int, scratch, scratch_bytes: int) -> None:
+    _check(lib().alaya_bind_scratch(handle, _ptr(scratch), scratch_bytes))
 
 
 def alaya_create_cache(cfg: CacheConfig, k_pool, v_pool, phys_page_order: Optional[Sequence[int]],
@@ -237,11 +249,12 @@ def alaya_poll_status(handle: int, stream=0) -> int:
 # ---- a handle bundled with the torch memory behind it ---------------------------------------------
 
 class Cache:
-    """One layer's paged KV store on one GPU.  torch allocates the pools and the workspace."""
+    """One layer's paged KV store on one GPU.  torch allocates the pools, the page-table workspace and -
+    unless a tensor shared with other caches (other layers) is passed as `scratch` - the scratch memory."""
 
     def __init__(self, n_q_heads: int, n_kv_heads: int, head_dim: int, dtype: str, max_seqs: int,
                  max_batch: int, max_tokens_per_seq: int, max_batch_tokens: int, n_phys_pages: int,
-                 phys_page_order: Optional[Sequence[int]] = None, device: str = "cuda:0"):
+                 phys_page_order: Optional[Sequence[int]] = None, device: str = "cuda:0", scratch=None):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU visible: the sparse-attention path has no CPU fallback")
@@ -252,14 +265,17 @@ class Cache:
         cfg = CacheConfig(n_q_heads, n_kv_heads, head_dim, 64, self.dtype, max_seqs, max_batch, 0,
                           max_tokens_per_seq, max_batch_tokens, n_phys_pages)
         self.cfg = cfg
-        pool, ws = alaya_pool_bytes(cfg), alaya_workspace_bytes(cfg)
-        if pool == 0 or ws == 0:
+        pool, ws, sc = alaya_pool_bytes(cfg), alaya_workspace_bytes(cfg), alaya_scratch_bytes(cfg)
+        if pool == 0 or ws == 0 or sc == 0:
             raise AlayaError(ALAYA_E_INVAL, "invalid cache configuration")
         self.k_pool = torch.empty(pool, dtype=torch.uint8, device=self.device)
         self.v_pool = torch.empty(pool, dtype=torch.uint8, device=self.device)
         self.workspace = torch.empty(ws, dtype=torch.uint8, device=self.device)
         self.workspace_bytes = ws
+        self.scratch = scratch if scratch is not None else torch.empty(sc, dtype=torch.uint8, device=self.device)
+        self.scratch_bytes = sc
         self.handle = alaya_create_cache(cfg, self.k_pool, self.v_pool, phys_page_order, self.workspace, ws)
+        alaya_bind_scratch(self.handle, self.scratch, self.scratch.numel())
 
     def close(self) -> None:
         if getattr(self, "handle", None):
@@ -350,23 +366,23 @@ class Cache:
         return {name: {"sum_ms": ms[i], "launches": n[i]} for i, name in enumerate(KERNEL_SLOTS)}
 
     def debug_scores(self, lens: Sequence[int]):
-        """fp32 scores of the last sparse call (made with write_all_scores=1): list of tensors [Hq][n]."""
+        """fp32 scores that the scoring pass of the last sparse call kept (all of them if the call was made
+        with write_all_scores=1), NaN elsewhere: list of tensors [Hq][n], one per request."""
         torch = self.torch
-        base = lib().alaya_debug_scores(self.handle)
-        off = base - self.workspace.data_ptr()
         hq = self.cfg.n_q_heads
-        views = []
-        for n in lens:
-            pages = (n + 63) // 64
-            stride = pages * 64 + SCORE_PAD
-            blk = self.workspace[off:off + hq * stride * 8].view(torch.float32).view(hq, stride, 2)
-            views.append(blk[:, :n, 0])
-            off += hq * stride * 8
+        strides = [(n + 63) // 64 * 64 + SCORE_PAD for n in lens]
+        dense = torch.full((hq * sum(strides),), float("nan"), dtype=torch.float32, device=self.device)
+        if lib().alaya_debug_scores(self.handle, dense.data_ptr(), _stream(None)) < 0:
+            raise AlayaError(ALAYA_E_DEVICE, alaya_last_error())
+        views, off = [], 0
+        for n, stride in zip(lens, strides):
+            views.append(dense[off:off + hq * stride].view(hq, stride)[:, :n])
+            off += hq * stride
         return views
 
     def debug_survivors(self, stream=None) -> int:
-        """(token, score) pairs written by the scoring pass of the last sparse call, over all heads."""
-        return lib().alaya_debug_survivors(self.handle, _stream(stream))
+        """(token, score) pairs kept by the scoring pass of the last sparse call, over all heads."""
+        return lib().alaya_debug_scores(self.handle, None, _stream(stream))
 
     def debug_pages(self) -> Tuple[int, int]:
         """(pages scored in full by the sample pass, pages scored by the main pass) of the last sparse call."""
@@ -375,14 +391,14 @@ class Cache:
         return a.value, b.value
 
     def debug_estimate(self, mode: int) -> None:
-        """0: library decides, 1: estimated bound whenever possible, 2: estimate that always needs repair, -1: never."""
+        """0, 1: estimated bound whenever the shapes allow, 2: estimate that always needs repair, -1: never."""
         _check(lib().alaya_debug_estimate(self.handle, mode))
 
     def set_tuning(self, score_pages_per_wave: int = 0, attend_splits: int = 0,
-                   select_segment_pages: int = 0, write_all_scores: bool = False) -> None:
-        _check(lib().alaya_set_tuning(self.handle, score_pages_per_wave, attend_splits, select_segment_pages,
+                   select_batch_blocks: int = 0, write_all_scores: bool = False) -> None:
+        _check(lib().alaya_set_tuning(self.handle, score_pages_per_wave, attend_splits, select_batch_blocks,
                                       int(write_all_scores)))
-        self._tuning = (score_pages_per_wave, attend_splits, select_segment_pages, bool(write_all_scores))
+        self._tuning = (score_pages_per_wave, attend_splits, select_batch_blocks, bool(write_all_scores))
 
     def set_write_all_scores(self, flag: bool) -> None:
         """Toggle only the write-everything switch, keeping the other knobs."""

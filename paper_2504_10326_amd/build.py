@@ -14,7 +14,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libalaya.so")
 SOURCES = ["api.hip", "score.hip", "select.hip", "attend.hip"]
-HEADERS = [os.path.join(CSRC, "alaya_internal.h"), os.path.join(HERE, "..", "include", "alaya.h")]
+HEADERS = [os.path.join(CSRC, "alaya_internal.h"), os.path.join(CSRC, "score_page.h"),
+           os.path.join(HERE, "..", "include", "alaya.h"), os.path.join(HERE, "..", "include", "alaya_debug.h")]
 # packed-fp32 instructions are switched off for all device code (hipcc's host pass warns that it
 # does not know the feature; that is harmless)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-command-line-argument",

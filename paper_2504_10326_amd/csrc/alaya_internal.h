@@ -7,15 +7,16 @@ namespace alaya {
 
 constexpr int kPageTokens = 64;      // one page == one wavefront of tokens
 constexpr int kScoreWaves = 4;       // wavefronts per scoring workgroup
-constexpr int kMaxPagesPerWave = 16; // pages one wavefront scores in a row, at most
+constexpr int kMaxPagesPerWave = 4;  // pages one wavefront of the main pass scores in a row, at most
 constexpr int kSelectThreads = 1024;
 constexpr int kAttendThreads = 256;
 constexpr int kMaxSplits = 64;
 constexpr int kHistBins = 2048;      // top 11 bits of the order-preserving score image
-constexpr int kRepairGrid = 2048;    // workgroups of the (normally idle) repair scoring pass
+constexpr int kRepairGrid = 8192;    // workgroups of the (normally idle) repair scoring pass, at most
 constexpr int kMaxSlots = 64;        // addresses one head's sample-pass maxima are spread over
-constexpr int kMaxSegs = 64;         // selection segments per head
-constexpr int kMaxSegPages = 2048;   // pages per selection segment
+constexpr int kBlockHdr = 8;         // 8-byte words at the head of a survivor block: {count, start} per head of the group
+constexpr int kSelBatch = 4096;      // survivor blocks whose prefix sums the selection holds in LDS at a time
+constexpr int kMaxReqBlocks = 1 << 16; // survivor blocks of one request per KV head, at most
 
 // Elements added to each head's row in the per-head arrays so that rows of different heads, touched
 // at the same offset at the same time, do not all start on the same memory channel.
@@ -25,33 +26,29 @@ constexpr int kScorePad = 1088; // 17 * 256 bytes
 struct ReqDesc {
     int32_t pt_off;        // first entry of this sequence's row in the device page table
     int32_t n;             // tokens the query sees (the cached ones, or a prefix of them)
-    int32_t head_stride;   // elements between consecutive heads in the per-head arrays
+    int32_t head_stride;   // elements between consecutive heads in the selected-token arrays
     int32_t k;             // top-k: tokens to retrieve outside the window, already clamped (0 in DIPR mode)
     float beta;            // DIPR margin (raw inner-product units)
-    int32_t tile_start;    // first phase-A scoring tile / full-attention tile of this request (prefix sum)
-    int64_t score_off;     // offset (elements) of this request's block in every per-token array
-    int32_t page_start;    // pages of the requests before this one (prefix sum)
+    int32_t tile_start;    // first sample-pass tile / full-attention tile of this request (prefix sum)
+    int64_t score_off;     // offset (elements) of this request's block in the selected-token arrays
     int32_t n_pages;       // pages of this request
-    int32_t seg_start;     // first selection segment of this request (prefix sum, per head)
-    int32_t nseg;          // selection segments per head
-    int32_t seg_pages;     // pages per selection segment
-    int32_t tileb_start;   // first phase-B scoring tile of this request (prefix sum)
-    int32_t sample_stride; // S: phase A scores pages 0, S, 2S, ... in full; 1 = no pruning
-    int32_t chunk_pages;   // pages one wavefront of the main pass covers: a power of two, at most S
+    int32_t tileb_start;   // first main-pass tile (= survivor block per KV head) of this request (prefix sum)
+    int32_t ntiles_b;      // main-pass tiles of this request
+    int32_t sample_stride; // S: the sample pass scores pages 0, S, 2S, ...; 1 = no sample, no pruning
     int32_t w0, w1;        // window: tokens j < w0 and j >= n - w1 are always selected
     int32_t nwin;          // tokens in the window: min(n, w0 + w1)
     int32_t k_est;         // top-k: rank in the sample that the ESTIMATED bound is read at; 0 = guaranteed bound only
-    int32_t xf, xb;        // the sample pass also scores the pages [0, xf) and [xb, n_pages) in full, and the main
-                           // pass leaves them out: DIPR with a window, whose tokens seed the maximum (Sec. 7.1);
-                           // a decode step, whose newest token that pass writes.  Multiples of chunk_pages
-                           // (0 and n_pages otherwise).  Only the every-S-th pages count as the sample in
-                           // top-k's histogram; the statistics kernel treats these pages like any other.
+    int32_t xf, xb;        // the sample pass also scores the pages [0, xf) and [xb, n_pages): DIPR with a window,
+                           // whose tokens seed the maximum (Sec. 7.1); a decode step, whose newest token that
+                           // pass writes.  Only the every-S-th pages enter top-k's histogram.
+    int32_t hist_cap;      // top-k: what one sample-pass workgroup (four sampled pages) may add to one bucket, at most
+    int32_t pad1;
 };
-static_assert(sizeof(ReqDesc) == 88, "ReqDesc layout");
+static_assert(sizeof(ReqDesc) == 80, "ReqDesc layout");
 
 // How the kernels get at the request descriptors.  A call of one request carries its descriptor in
 // the kernel arguments, which saves the host-to-device copy (a 4 us blit ahead of the first kernel of
-// every step); calls of more requests read the copy in the workspace.  (One only: indexing an array
+// every step); calls of more requests read the copy in the scratch memory.  (One only: indexing an array
 // in the arguments makes the compiler treat the descriptor as varying from lane to lane.)
 constexpr int kInlineDescs = 1;
 struct DescArgs { // host side: what the launchers hand to every kernel as (mem, in, n)
@@ -73,45 +70,34 @@ struct FusedAppend {
     const uint4 *k, *v;     // [B][H_kv][D] new rows; k == nullptr: nothing to append
 };
 
-
-
 // A window token is always selected, and top-k neither counts nor ranks it.
 __device__ __forceinline__ bool in_window(const ReqDesc &d, int j) { return j < d.w0 || j >= d.n - d.w1; }
 
-// Device views handed to the launchers.  "per-token arrays" hold one element per (query head, token):
-// a request's block starts at score_off and spans n_q_heads * head_stride elements.
+// Device views handed to the launchers.
 struct DeviceViews {
     DescArgs desc;             // the call's request descriptors
     FusedAppend fused;         // set for the duration of a decode-step call, all null otherwise
-    const int32_t *page_table; // [max_seqs][max_pages_per_seq]
+    const int32_t *page_table; // [max_seqs][max_pages_per_seq]   (the cache's own memory)
     const void *k_pool;
     const void *v_pool;
-    // scoring output: survivors as (score bits, token id) pairs, [head][head_stride] inside the request's
-    // block with 64 slots per page; a list starts in the slot of its first page and may run on through
-    // the slots of the pages that the same wavefront scored after it ...
-    uint2 *cand;
-    // ... and the lists' lengths: [head][n_pages] per request, requests in order; a page inside another
-    // page's list has 0
-    int32_t *page_cnt;
-    // selection, stage 1: per (head, segment) local lists, [head][head_stride] inside the block,
-    // segment s at s * seg_pages * 64: definite tokens first, tie-bucket tokens behind them
-    float *loc_scores;
-    int32_t *loc_ids;
-    // selection, stage 2 = what attention reads: [head][head_stride] inside the block
+    // Everything below lives in the scratch memory of the call.
+    // Scoring output: one block per main-pass workgroup = (tile, KV head), blocks[(tile * H_kv + kvh) * block_stride]:
+    // kBlockHdr words of header ({count, start} for each head of the group), then the survivors as
+    // (score bits, token id) pairs, head after head, each head's ascending by token.
+    uint2 *blocks;
+    int64_t block_stride;      // 8-byte words between blocks: kBlockHdr + 4 * pages per wave * 64 * G
+    // what attention reads: [head][head_stride] inside the request's block at score_off
     float *sel_scores;
     int32_t *sel_ids;
-    // Bucket counts (top-k only) and maximum (as an ordered key) of the head's scores: the sample pass
-    // enters the sampled pages, the selection the survivors of the others.  Zero between calls.
-    uint32_t *hist;            // [max_batch * n_q_heads][kHistBins]
-    uint32_t *head_maxkey;     // [max_batch * n_q_heads]
+    int32_t *sel_rows;         // the same tokens as rows of the V pool: physical page * 64 + slot in the page
+    uint32_t *hist;            // [max_batch * n_q_heads][kHistBins] bucket counts of the sample (top-k); zero between calls
+    uint32_t *head_maxkey;     // [max_batch * n_q_heads] DIPR: running maximum (ordered key); zero between calls
     uint32_t *sample_max;      // [max_batch * n_q_heads][kMaxSlots] maxima of the sample pass (DIPR); zero between calls
     uint32_t *fail;            // [max_batch * n_q_heads] 1: the estimated bound lost tokens, repair this head; zero between calls
-    uint32_t *any_fail;        // one word: some head of the call is marked; zero between calls
+    uint32_t *any_fail;        // one word: some head of the call is marked
     uint32_t *tau;             // [max_batch * n_q_heads] the bound the main pass filters with (ordered key)
     uint32_t *tau_safe;        // [max_batch * n_q_heads] the guaranteed lower bound of the selection threshold
-    int32_t *seg_counts;       // [max_batch * n_q_heads][kMaxSegs][2]
-    float *head_M;             // [max_batch * n_q_heads]: maximum score per head
-    int32_t *head_info;        // [max_batch * n_q_heads][2]: bucket of the k-th score (-1: threshold rule), tokens above it
+    float *head_M;             // [max_batch * n_q_heads]: maximum score over the selected set
     int32_t *counts;           // [max_batch * n_q_heads]: size of the selected set
     float *partials;           // attend / full-attention partial results
     int32_t *status;           // device status word
@@ -132,25 +118,23 @@ hipError_t launch_append(const Shape &sh, const int32_t *page_table_row, void *k
 hipError_t launch_append_step(const Shape &sh, const DeviceViews &dv, void *k_pool, void *v_pool, const void *k,
                               const void *v, int B, hipStream_t st);
 
-// phase 0 scores the sampled pages in full, phase 1 the other pages against dv.tau, phase 2 (repair)
-// the other pages of the heads marked in dv.fail against dv.tau_safe.
-// ev0 / ev1: optional events that take the kernel's own begin and end times.
-hipError_t launch_score(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles,
-                        int pages_per_wave, int phase, int mode, hipStream_t st, hipEvent_t ev0 = nullptr,
-                        hipEvent_t ev1 = nullptr);
-// mode: 0 top-k, 1 DIPR
+// Sample pass: statistics of every S-th page (histogram for top-k, maximum for DIPR) and, in a decode
+// step, the append of the newest token.  total_tiles may be 0 (nothing to launch).
+hipError_t launch_sample(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles, int mode,
+                         hipStream_t st);
+// The bound of every head from the sample's statistics; mode: 0 top-k, 1 DIPR.
 hipError_t launch_tau(const Shape &sh, const DeviceViews &dv, int B, int mode, hipStream_t st);
+// Main pass: every page against dv.tau (repair = false), or - only for the workgroups with a head marked
+// in dv.fail - against dv.tau_safe for the marked heads (repair = true).  cp = pages per wavefront.
+// ev0 / ev1: optional events that take the kernel's own begin and end times.
+hipError_t launch_score(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles, int cp,
+                        bool repair, int mode, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 
-// Selection, total_segs = sum over requests of nseg.  front: stats -> local (which marks the heads whose
-// estimated bound lost tokens in dv.fail); back: local again for the marked heads if `redo` (the repair
-// scoring pass must have run in between), then finish.
-hipError_t launch_select_front(const Shape &sh, const DeviceViews &dv, int B, int mode, int total_segs,
-                               hipStream_t st);
-hipError_t launch_select_back(const Shape &sh, const DeviceViews &dv, int B, int mode, int total_segs, bool redo,
-                              int32_t *out_ids, int32_t *out_counts, int64_t ids_stride, hipStream_t st);
-
-hipError_t launch_attend(const Shape &sh, const DeviceViews &dv, int B, float scale, int splits, bool segmented,
+// Selection: one workgroup per (request, head).  redo: only the heads marked in dv.fail (after the repair pass).
+hipError_t launch_select(const Shape &sh, const DeviceViews &dv, int B, int mode, bool redo, int batch_blocks,
                          int32_t *out_ids, int32_t *out_counts, int64_t ids_stride, hipStream_t st);
+
+hipError_t launch_attend(const Shape &sh, const DeviceViews &dv, int B, float scale, int splits, hipStream_t st);
 
 // partial layout: [slot][head_dim + 2] = {m (already times scale), l, acc[head_dim]}
 // sparse: slot = (b * n_q_heads + h) * splits + s           (per_request_tiles == 0)
@@ -162,6 +146,11 @@ hipError_t launch_full_partial(const Shape &sh, const DeviceViews &dv, int B, co
                                int total_tiles, int pages_per_tile, hipStream_t st);
 
 hipError_t launch_fill_u32(uint32_t *p, size_t n, uint32_t v, hipStream_t st);
+
+// Inspection (tests, measurement): the survivors' scores scattered into dense rows
+// out[score_off + head * head_stride + token]; the number of survivors of the call added to *total.
+hipError_t launch_debug_scatter(const Shape &sh, const DeviceViews &dv, int B, int total_tiles, float *out,
+                                unsigned long long *total, hipStream_t st);
 
 // ---- device helpers ---------------------------------------------------------------------------
 
@@ -176,6 +165,16 @@ __device__ __forceinline__ float ord_float(uint32_t k)
 {
     uint32_t b = (k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k;
     return __uint_as_float(b);
+}
+
+// 16-byte load of data that is read once: marked non-temporal so that the stream does not push the
+// small, re-read structures (survivor blocks, page table, queries) out of the caches.  Measured on a
+// 2 GiB key pool: 6.8 against 6.0 TB/s for the bare read stream.
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_nt;
+__device__ __forceinline__ uint4 load_stream(const uint4 *p)
+{
+    const u32x4_nt t = __builtin_nontemporal_load((const u32x4_nt *)p);
+    return make_uint4(t.x, t.y, t.z, t.w);
 }
 
 } // namespace alaya

@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in include/alaya.h: argument checks, the page allocator and page
 // table, per-call descriptors, launch shapes, event timing.  No device memory is allocated here.
 #include "../../include/alaya.h"
+#include "../../include/alaya_debug.h"
 #include "alaya_internal.h"
 
 #include <algorithm>
@@ -53,55 +54,81 @@ bool cfg_ok(const alaya_cache_config *c)
     const int G = c->n_q_heads / c->n_kv_heads;
     if (G != 1 && G != 2 && G != 4 && G != 8) return false;
     if (c->max_seqs <= 0 || c->max_batch <= 0 || c->max_tokens_per_seq <= 0 || c->max_batch_tokens <= 0) return false;
-    if (c->n_phys_pages <= 0 || c->n_phys_pages > INT32_MAX) return false;
+    if (c->n_phys_pages <= 0 || c->n_phys_pages > INT32_MAX / kPageTokens) return false; // V-pool row numbers are int32
     if (c->max_tokens_per_seq > (int64_t)INT32_MAX - 64) return false; // token ids are int32
     const int64_t mpps = (c->max_tokens_per_seq + kPageTokens - 1) / kPageTokens;
     if (mpps * c->max_seqs > INT32_MAX) return false;                 // page-table offsets are int32
     return true;
 }
 
+// The cache's own device memory: the page table.
 struct Layout {
-    size_t page_table, desc, cand, loc_scores, loc_ids, sel_scores, sel_ids, page_cnt, hist,
-        head_maxkey, sample_max, fail, tau, tau_safe, seg_counts, head_M, head_info, counts, partials, status, total;
-    int64_t mpps;        // max pages per sequence
-    int64_t score_elems; // capacity of each per-token array
-    int64_t max_tiles;   // full-attention tiles
-    int64_t max_pages;   // pages over one call
+    size_t page_table, total;
+    int64_t mpps; // max pages per sequence
 };
 
 Layout make_layout(const alaya_cache_config &c)
 {
     Layout L{};
     L.mpps = (c.max_tokens_per_seq + kPageTokens - 1) / kPageTokens;
-    L.score_elems = (int64_t)c.n_q_heads * (c.max_batch_tokens + (int64_t)(kPageTokens + kScorePad) * c.max_batch);
-    L.max_tiles = kTargetGroups / c.n_kv_heads + 1 + c.max_batch;
-    L.max_pages = c.max_batch_tokens / kPageTokens + c.max_batch;
+    L.page_table = 0;
+    L.total = align_up((size_t)L.mpps * c.max_seqs * sizeof(int32_t), 256);
+    return L;
+}
+
+// Scratch memory of one attention call (nothing in it outlives the call, except that the words between
+// zero_begin and zero_end are zero from one call to the next): survivor blocks, selected tokens,
+// statistics, partial results.  Sized by the largest call it must serve.
+struct Scratch {
+    size_t desc, blocks, sel_scores, sel_ids, sel_rows, zero_begin, hist, head_maxkey, sample_max, fail, zero_end, tau,
+        tau_safe, head_M, counts, partials, status, dbg_total, total;
+    int64_t block_words; // capacity of the survivor blocks, 8-byte words
+    int64_t sel_elems;   // capacity of each selected-token array
+    int64_t max_tiles;   // full-attention tiles
+};
+
+// Survivor-block words that a call of `pages` pages in `batch` requests can need with cp pages per wavefront.
+int64_t block_words_for(int64_t pages, int64_t batch, int n_kv_heads, int G, int cp)
+{
+    const int64_t tiles = (pages + (int64_t)kScoreWaves * cp - 1) / ((int64_t)kScoreWaves * cp) + batch;
+    return tiles * n_kv_heads * (int64_t)(kBlockHdr + kScoreWaves * cp * kPageTokens * G);
+}
+
+Scratch make_scratch(int n_q_heads, int n_kv_heads, int head_dim, int64_t max_batch, int64_t max_batch_tokens)
+{
+    Scratch S{};
+    const int G = n_q_heads / n_kv_heads;
+    const int64_t pages = max_batch_tokens / kPageTokens + max_batch;
+    S.block_words = 0;
+    for (int cp = 1; cp <= kMaxPagesPerWave && cp * G <= 16; cp *= 2)
+        S.block_words = std::max(S.block_words, block_words_for(pages, max_batch, n_kv_heads, G, cp));
+    S.sel_elems = (int64_t)n_q_heads * (max_batch_tokens + (int64_t)(kPageTokens + kScorePad) * max_batch);
+    S.max_tiles = kTargetGroups / n_kv_heads + 1 + max_batch;
+    const size_t heads = (size_t)max_batch * n_q_heads;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
-    L.page_table = take((size_t)L.mpps * c.max_seqs * sizeof(int32_t));
-    L.desc = take((size_t)c.max_batch * sizeof(ReqDesc));
-    L.cand = take((size_t)L.score_elems * sizeof(uint2));
-    L.loc_scores = take((size_t)L.score_elems * sizeof(float));
-    L.loc_ids = take((size_t)L.score_elems * sizeof(int32_t));
-    L.sel_scores = take((size_t)L.score_elems * sizeof(float));
-    L.sel_ids = take((size_t)L.score_elems * sizeof(int32_t));
-    L.page_cnt = take((size_t)L.max_pages * c.n_q_heads * sizeof(int32_t));
-    L.hist = take((size_t)c.max_batch * c.n_q_heads * kHistBins * sizeof(uint32_t));
-    L.head_maxkey = take((size_t)c.max_batch * c.n_q_heads * sizeof(uint32_t));
-    L.sample_max = take((size_t)c.max_batch * c.n_q_heads * kMaxSlots * sizeof(uint32_t));
-    L.fail = take(((size_t)c.max_batch * c.n_q_heads + 1) * sizeof(uint32_t)); // + the any-head word
-    L.tau = take((size_t)c.max_batch * c.n_q_heads * sizeof(uint32_t));
-    L.tau_safe = take((size_t)c.max_batch * c.n_q_heads * sizeof(uint32_t));
-    L.seg_counts = take((size_t)c.max_batch * c.n_q_heads * kMaxSegs * 2 * sizeof(int32_t));
-    L.head_M = take((size_t)c.max_batch * c.n_q_heads * sizeof(float));
-    L.head_info = take((size_t)c.max_batch * c.n_q_heads * 2 * sizeof(int32_t));
-    L.counts = take((size_t)c.max_batch * c.n_q_heads * sizeof(int32_t));
-    const size_t sparse_slots = (size_t)c.max_batch * c.n_q_heads * kMaxSplits;
-    const size_t full_slots = (size_t)L.max_tiles * c.n_q_heads;
-    L.partials = take((sparse_slots > full_slots ? sparse_slots : full_slots) * (c.head_dim + 2) * sizeof(float));
-    L.status = take(256);
-    L.total = o;
-    return L;
+    S.desc = take((size_t)max_batch * sizeof(ReqDesc));
+    S.blocks = take((size_t)S.block_words * sizeof(uint2));
+    S.sel_scores = take((size_t)S.sel_elems * sizeof(float));
+    S.sel_ids = take((size_t)S.sel_elems * sizeof(int32_t));
+    S.sel_rows = take((size_t)S.sel_elems * sizeof(int32_t));
+    S.zero_begin = o;
+    S.hist = take(heads * kHistBins * sizeof(uint32_t));
+    S.head_maxkey = take(heads * sizeof(uint32_t));
+    S.sample_max = take(heads * kMaxSlots * sizeof(uint32_t));
+    S.fail = take((heads + 1) * sizeof(uint32_t)); // + the any-head word
+    S.zero_end = o;
+    S.tau = take(heads * sizeof(uint32_t));
+    S.tau_safe = take(heads * sizeof(uint32_t));
+    S.head_M = take(heads * sizeof(float));
+    S.counts = take(heads * sizeof(int32_t));
+    const size_t sparse_slots = heads * kMaxSplits;
+    const size_t full_slots = (size_t)S.max_tiles * n_q_heads;
+    S.partials = take((sparse_slots > full_slots ? sparse_slots : full_slots) * (head_dim + 2) * sizeof(float));
+    S.status = take(256);
+    S.dbg_total = take(256);
+    S.total = o;
+    return S;
 }
 
 } // namespace
@@ -109,7 +136,9 @@ Layout make_layout(const alaya_cache_config &c)
 struct alaya_cache {
     alaya_cache_config cfg;
     Layout L;
-    char *ws;
+    Scratch S;                       // layout of the bound scratch memory
+    char *ws;                        // the cache's own device memory (page table)
+    char *scratch_mem;               // bound scratch memory, or null
     void *k_pool, *v_pool;
     DeviceViews dv;
     // host bookkeeping
@@ -121,10 +150,10 @@ struct alaya_cache {
     hipEvent_t ring_ev[kRing];
     bool ring_used[kRing];
     int ring_pos;
-    bool dev_ready;
-    int tune_ppw, tune_splits, tune_seg, tune_noprune;
+    bool scratch_ready;              // the must-be-zero words of the bound scratch were cleared by this cache
+    int tune_ppw, tune_splits, tune_batch, tune_noprune;
     int estimate_mode; // alaya_debug_estimate
-    int last_pages, last_heads;
+    int last_B, last_tiles_b;        // of the last sparse call, for the inspection hooks
     int64_t last_pages_a, last_pages_b; // pages of the last sparse call scored by the sample / the main pass
     // profiling
     bool prof;
@@ -180,25 +209,56 @@ struct Timed {
     }
 };
 
-int ensure_device(alaya_cache *c, hipStream_t st)
+// Points the device views at a scratch area laid out as S.
+void bind_views(DeviceViews &dv, const Scratch &S, char *base)
 {
-    if (c->dev_ready) return ALAYA_OK;
-    // the histograms and the running maxima sit next to each other in the workspace: one fill
-    const size_t nh = (size_t)(c->L.tau - c->L.hist) / sizeof(uint32_t);
-    hipError_t e = launch_fill_u32(c->dv.hist, nh, 0u, st);
-    if (e == hipSuccess) e = launch_fill_u32((uint32_t *)c->dv.status, 1, 0u, st);
-    if (e != hipSuccess) return fail_hip(e, "workspace initialisation");
-    c->dev_ready = true;
+    dv.desc.mem = (const ReqDesc *)(base + S.desc);
+    dv.blocks = (uint2 *)(base + S.blocks);
+    dv.sel_scores = (float *)(base + S.sel_scores);
+    dv.sel_ids = (int32_t *)(base + S.sel_ids);
+    dv.sel_rows = (int32_t *)(base + S.sel_rows);
+    dv.hist = (uint32_t *)(base + S.hist);
+    dv.head_maxkey = (uint32_t *)(base + S.head_maxkey);
+    dv.sample_max = (uint32_t *)(base + S.sample_max);
+    dv.fail = (uint32_t *)(base + S.fail);
+    dv.any_fail = dv.fail + (S.zero_end - S.fail) / sizeof(uint32_t) - 1; // the last word of the cleared range
+    dv.tau = (uint32_t *)(base + S.tau);
+    dv.tau_safe = (uint32_t *)(base + S.tau_safe);
+    dv.head_M = (float *)(base + S.head_M);
+    dv.counts = (int32_t *)(base + S.counts);
+    dv.partials = (float *)(base + S.partials);
+    dv.status = (int32_t *)(base + S.status);
+}
+
+// Clears what must be zero before a scratch area's first use: statistics, repair marks, status.
+hipError_t clear_scratch(const Scratch &S, char *base, hipStream_t st)
+{
+    hipError_t e = launch_fill_u32((uint32_t *)(base + S.zero_begin), (S.zero_end - S.zero_begin) / sizeof(uint32_t), 0u, st);
+    if (e == hipSuccess) e = launch_fill_u32((uint32_t *)(base + S.status), 1, 0u, st);
+    return e;
+}
+
+int need_scratch(alaya_cache *c, hipStream_t st)
+{
+    if (!c->scratch_mem) return fail(ALAYA_E_INVAL, "no scratch memory bound to this cache (alaya_bind_scratch)");
+    if (c->scratch_ready) return ALAYA_OK;
+    const hipError_t e = clear_scratch(c->S, c->scratch_mem, st);
+    if (e != hipSuccess) return fail_hip(e, "scratch initialisation");
+    c->scratch_ready = true;
     return ALAYA_OK;
 }
 
 // Reserve the next descriptor slot; waits only if the copy issued kRing calls ago is still pending.
-int ring_acquire(alaya_cache *c, ReqDesc **slot, int *idx)
+int ring_acquire(alaya_cache *c, int B, ReqDesc **slot, int *idx)
 {
     const int i = c->ring_pos;
     if (c->ring_used[i]) {
         hipError_t e = hipEventSynchronize(c->ring_ev[i]);
         if (e != hipSuccess) return fail_hip(e, "hipEventSynchronize(descriptor ring)");
+    }
+    if (B > kInlineDescs && !c->ring_ev[i]) { // (normally created with the cache)
+        hipError_t e = hipEventCreateWithFlags(&c->ring_ev[i], hipEventDisableTiming);
+        if (e != hipSuccess) { c->ring_ev[i] = nullptr; return fail_hip(e, "hipEventCreate"); }
     }
     *slot = c->h_desc + (size_t)i * c->cfg.max_batch;
     *idx = i;
@@ -206,17 +266,16 @@ int ring_acquire(alaya_cache *c, ReqDesc **slot, int *idx)
 }
 
 // Hands the descriptors in ring slot idx to the kernels launched after this: in their arguments for a
-// small call, through an asynchronous copy into the workspace otherwise.
-int ring_publish(alaya_cache *c, int idx, int B, hipStream_t st)
+// call of one request, through an asynchronous copy into `dev` (device memory) otherwise.
+int ring_publish(alaya_cache *c, DeviceViews &dv, int idx, int B, hipStream_t st)
 {
     const ReqDesc *src = c->h_desc + (size_t)idx * c->cfg.max_batch;
-    c->dv.desc.n = B;
+    dv.desc.n = B;
     if (B <= kInlineDescs) {
-        c->dv.desc.in = src[0];
+        dv.desc.in = src[0];
         return ALAYA_OK; // the slot is free again at once
     }
-    hipError_t e = hipMemcpyAsync((void *)c->dv.desc.mem, src,
-                                  (size_t)B * sizeof(ReqDesc), hipMemcpyHostToDevice, st);
+    hipError_t e = hipMemcpyAsync((void *)dv.desc.mem, src, (size_t)B * sizeof(ReqDesc), hipMemcpyHostToDevice, st);
     if (e != hipSuccess) return fail_hip(e, "descriptor copy");
     e = hipEventRecord(c->ring_ev[idx], st);
     if (e != hipSuccess) return fail_hip(e, "hipEventRecord");
@@ -225,7 +284,7 @@ int ring_publish(alaya_cache *c, int idx, int B, hipStream_t st)
     return ALAYA_OK;
 }
 
-// Checks shared by both attention calls; fills n[] with the sequence lengths.
+// Checks shared by both attention calls.
 int check_call(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q, const float *out,
                int64_t *total_pages, int64_t *total_tokens)
 {
@@ -244,7 +303,7 @@ int check_call(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const 
         toks += n;
     }
     if (toks > c->cfg.max_batch_tokens)
-        return fail(ALAYA_E_NOMEM, "call covers %lld tokens, workspace was sized for %lld", (long long)toks,
+        return fail(ALAYA_E_NOMEM, "call covers %lld tokens, the cache was configured for %lld", (long long)toks,
                     (long long)c->cfg.max_batch_tokens);
     *total_pages = pages;
     *total_tokens = toks;
@@ -268,6 +327,12 @@ size_t alaya_workspace_bytes(const alaya_cache_config *cfg)
 {
     if (!cfg_ok(cfg)) return 0;
     return make_layout(*cfg).total;
+}
+
+size_t alaya_scratch_bytes(const alaya_cache_config *cfg)
+{
+    if (!cfg_ok(cfg)) return 0;
+    return make_scratch(cfg->n_q_heads, cfg->n_kv_heads, cfg->head_dim, cfg->max_batch, cfg->max_batch_tokens).total;
 }
 
 int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k_pool, void *v_pool,
@@ -299,34 +364,16 @@ int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k
     if (!c) return fail(ALAYA_E_NOMEM, "host allocation failed");
     c->cfg = *cfg;
     c->L = L;
+    c->S = Scratch{};
     c->ws = (char *)workspace;
+    c->scratch_mem = nullptr;
     c->k_pool = k_pool;
     c->v_pool = v_pool;
-    c->dv.desc.mem = (const ReqDesc *)(c->ws + L.desc);
-    c->dv.desc.n = 0;
+    c->dv = DeviceViews{};
     c->dv.fused = FusedAppend{nullptr, nullptr, nullptr, nullptr};
     c->dv.page_table = (const int32_t *)(c->ws + L.page_table);
     c->dv.k_pool = k_pool;
     c->dv.v_pool = v_pool;
-    c->dv.cand = (uint2 *)(c->ws + L.cand);
-    c->dv.loc_scores = (float *)(c->ws + L.loc_scores);
-    c->dv.loc_ids = (int32_t *)(c->ws + L.loc_ids);
-    c->dv.sel_scores = (float *)(c->ws + L.sel_scores);
-    c->dv.sel_ids = (int32_t *)(c->ws + L.sel_ids);
-    c->dv.page_cnt = (int32_t *)(c->ws + L.page_cnt);
-    c->dv.hist = (uint32_t *)(c->ws + L.hist);
-    c->dv.head_maxkey = (uint32_t *)(c->ws + L.head_maxkey);
-    c->dv.sample_max = (uint32_t *)(c->ws + L.sample_max);
-    c->dv.fail = (uint32_t *)(c->ws + L.fail);
-    c->dv.any_fail = c->dv.fail + (size_t)cfg->max_batch * cfg->n_q_heads;
-    c->dv.tau = (uint32_t *)(c->ws + L.tau);
-    c->dv.tau_safe = (uint32_t *)(c->ws + L.tau_safe);
-    c->dv.seg_counts = (int32_t *)(c->ws + L.seg_counts);
-    c->dv.head_info = (int32_t *)(c->ws + L.head_info);
-    c->dv.head_M = (float *)(c->ws + L.head_M);
-    c->dv.counts = (int32_t *)(c->ws + L.counts);
-    c->dv.partials = (float *)(c->ws + L.partials);
-    c->dv.status = (int32_t *)(c->ws + L.status);
     c->free_pages.assign(order.rbegin(), order.rend()); // back() == first page of the order
     c->seq_len.assign((size_t)cfg->max_seqs, 0);
     const size_t pt_bytes = (size_t)L.mpps * cfg->max_seqs * sizeof(int32_t);
@@ -344,20 +391,48 @@ int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k
     }
     c->h_page_table = (int32_t *)p;
     c->h_desc = (ReqDesc *)((char *)p + pt_bytes);
-    for (int i = 0; i < kRing; ++i) { c->ring_ev[i] = nullptr; c->ring_used[i] = false; }
+    for (int i = 0; i < kRing; ++i) {
+        c->ring_ev[i] = nullptr;
+        c->ring_used[i] = false;
+        // (with a device: now, so that no later call has to create one; without: on first use)
+        if (c->h_page_table_pinned && hipEventCreateWithFlags(&c->ring_ev[i], hipEventDisableTiming) != hipSuccess) {
+            (void)hipGetLastError();
+            c->ring_ev[i] = nullptr;
+        }
+    }
     c->ring_pos = 0;
-    c->dev_ready = false;
+    c->scratch_ready = false;
     c->tune_ppw = 0;
     c->tune_splits = 0;
-    c->tune_seg = 0;
+    c->tune_batch = 0;
     c->tune_noprune = 0;
     c->estimate_mode = 0;
-    c->last_pages = c->last_heads = 0;
+    c->last_B = c->last_tiles_b = 0;
     c->last_pages_a = c->last_pages_b = 0;
     c->prof = false;
     c->ev_n = 0;
     for (int i = 0; i < ALAYA_N_KERNEL_SLOTS; ++i) { c->sum_ms[i] = 0.0; c->launches[i] = 0; }
     *out = c;
+    return ALAYA_OK;
+}
+
+int alaya_bind_scratch(alaya_cache *c, void *scratch, size_t scratch_bytes)
+{
+    if (!c) return fail(ALAYA_E_INVAL, "null cache handle");
+    if (!scratch) { // unbind
+        c->scratch_mem = nullptr;
+        c->scratch_ready = false;
+        return ALAYA_OK;
+    }
+    if ((uintptr_t)scratch & 255) return fail(ALAYA_E_INVAL, "scratch memory must be 256-byte aligned");
+    const Scratch S = make_scratch(c->cfg.n_q_heads, c->cfg.n_kv_heads, c->cfg.head_dim, c->cfg.max_batch,
+                                   c->cfg.max_batch_tokens);
+    if (scratch_bytes < S.total)
+        return fail(ALAYA_E_NOMEM, "scratch has %zu bytes, %zu needed", scratch_bytes, S.total);
+    c->S = S;
+    c->scratch_mem = (char *)scratch;
+    c->scratch_ready = false;
+    bind_views(c->dv, S, c->scratch_mem);
     return ALAYA_OK;
 }
 
@@ -413,8 +488,6 @@ int alaya_append_kv(alaya_cache *c, int seq, const void *k, const void *v, int64
     auto rollback = [&]() {
         for (int64_t i = take - 1; i >= 0; --i) c->free_pages.push_back(row[have + i]);
     };
-    int rc = ensure_device(c, st);
-    if (rc != ALAYA_OK) { rollback(); return rc; }
     int32_t *d_row = (int32_t *)c->dv.page_table + (size_t)seq * c->L.mpps;
     if (take > 0) {
         hipError_t e = hipMemcpyAsync(d_row + have, row + have, (size_t)take * sizeof(int32_t), hipMemcpyHostToDevice, st);
@@ -452,8 +525,6 @@ int step_reserve(alaya_cache *c, const int32_t *seqs, int B, hipStream_t st, std
     }
     if (need > c->free_pages.size())
         return fail(ALAYA_E_NOMEM, "page pool exhausted: %zu pages needed, %zu free", need, c->free_pages.size());
-    int rc = ensure_device(c, st);
-    if (rc != ALAYA_OK) return rc;
     for (int b = 0; b < B; ++b) {
         const int s = seqs[b];
         const int64_t n_old = c->seq_len[(size_t)s];
@@ -478,24 +549,23 @@ void step_rollback(alaya_cache *c, const std::vector<int32_t> &taken, int back)
     }
 }
 
-// The append kernel for one new token per listed sequence; `back` as above.
+// The append kernel for one new token per listed sequence; `back` as above.  A batch needs the bound
+// scratch memory for its descriptors.
 int step_launch_append(alaya_cache *c, const int32_t *seqs, int B, const void *k, const void *v, int back,
                        hipStream_t st)
 {
+    if (B > kInlineDescs && !c->scratch_mem)
+        return fail(ALAYA_E_INVAL, "no scratch memory bound to this cache (alaya_bind_scratch)");
     ReqDesc *hd;
     int slot;
-    int rc = ring_acquire(c, &hd, &slot);
+    int rc = ring_acquire(c, B, &hd, &slot);
     if (rc != ALAYA_OK) return rc;
-    if (!c->ring_ev[slot]) {
-        hipError_t e = hipEventCreateWithFlags(&c->ring_ev[slot], hipEventDisableTiming);
-        if (e != hipSuccess) { c->ring_ev[slot] = nullptr; return fail_hip(e, "hipEventCreate"); }
-    }
     for (int b = 0; b < B; ++b) {
         std::memset(&hd[b], 0, sizeof(ReqDesc));
         hd[b].pt_off = (int32_t)((int64_t)seqs[b] * c->L.mpps);
         hd[b].n = (int32_t)(c->seq_len[(size_t)seqs[b]] - back);
     }
-    rc = ring_publish(c, slot, B, st);
+    rc = ring_publish(c, c->dv, slot, B, st);
     if (rc != ALAYA_OK) return rc;
     const Shape sh{c->cfg.dtype, c->cfg.head_dim, c->cfg.n_q_heads, c->cfg.n_kv_heads};
     hipError_t e;
@@ -507,8 +577,14 @@ int step_launch_append(alaya_cache *c, const int32_t *seqs, int B, const void *k
     return ALAYA_OK;
 }
 
-int sparse_attn_impl(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q,
-                     const alaya_sparse_params *p, float *out, void *stream, const void *fused_k,
+// Scratch memory other than the one bound to the cache: views into it and its layout.
+struct ScratchUse {
+    DeviceViews *dv;
+    const Scratch *S;
+};
+
+int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs, int B, int n_q_heads,
+                     const void *q, const alaya_sparse_params *p, float *out, void *stream, const void *fused_k,
                      const void *fused_v, bool *appended);
 
 } // namespace
@@ -547,7 +623,7 @@ int alaya_decode_step(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
     // The attention call's sample pass writes the new rows.  If the call is turned down before that
     // launch, the plain append kernel writes them: the token is appended either way.
     bool appended = false;
-    rc = sparse_attn_impl(c, seqs, B, n_q_heads, q, p, out, stream, k, v, &appended);
+    rc = sparse_attn_impl(c, nullptr, seqs, B, n_q_heads, q, p, out, stream, k, v, &appended);
     if (!appended) {
         const int rc2 = step_launch_append(c, seqs, B, k, v, 1, st);
         if (rc2 != ALAYA_OK) { // nothing was written: undo the step
@@ -563,16 +639,17 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
                       const alaya_sparse_params *p, float *out, void *stream)
 {
     bool appended = false;
-    return sparse_attn_impl(c, seqs, B, n_q_heads, q, p, out, stream, nullptr, nullptr, &appended);
+    return sparse_attn_impl(c, nullptr, seqs, B, n_q_heads, q, p, out, stream, nullptr, nullptr, &appended);
 }
 
 namespace {
 
 // alaya_sparse_attn; with fused_k / fused_v (a decode step whose lengths already count the new token)
 // the sample pass also writes each request's newest key and value rows.  *appended is set once that
-// launch is out.
-int sparse_attn_impl(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q,
-                     const alaya_sparse_params *p, float *out, void *stream, const void *fused_k,
+// launch is out.  use: null = the scratch memory bound to the cache; otherwise a scratch area that the
+// caller of this function has made ready (cleared), with room for this call.
+int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs, int B, int n_q_heads,
+                     const void *q, const alaya_sparse_params *p, float *out, void *stream, const void *fused_k,
                      const void *fused_v, bool *appended)
 {
     int64_t total_pages = 0, total_tokens = 0;
@@ -598,48 +675,56 @@ int sparse_attn_impl(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, 
             if (p->n_visible[b] <= 0 || p->n_visible[b] > c->seq_len[(size_t)seqs[b]])
                 return fail(ALAYA_E_INVAL, "request %d: n_visible = %d outside 1..%lld", b, p->n_visible[b],
                             (long long)c->seq_len[(size_t)seqs[b]]);
+    if (!use && !c->scratch_mem) return fail(ALAYA_E_INVAL, "no scratch memory bound to this cache (alaya_bind_scratch)");
+    DeviceViews &dv = use ? *use->dv : c->dv;
+    const Scratch &S = use ? *use->S : c->S;
 
     hipStream_t st = (hipStream_t)stream;
-    int ppw = c->tune_ppw; // pages per wavefront in the main scoring pass; chosen below if not given
-    // pages per selection segment: about 512 segment workgroups in all, 128 to 2048 pages each
-    int64_t seg_pages_want = c->tune_seg;
-    if (seg_pages_want <= 0) {
-        seg_pages_want = 128;
-        while (seg_pages_want < kMaxSegPages && seg_pages_want * 512 < total_pages * n_q_heads) seg_pages_want *= 2;
+    const int G = n_q_heads / c->cfg.n_kv_heads;
+    // Pages per wavefront of the main pass (= pages per survivor block / 4): as many as leave about 4096
+    // workgroups or more, so that the blocks are few and large; a power of two, at most 4, and the
+    // staging area of a workgroup (4 * cp * 64 * G pairs) at most 32 KiB.
+    int cp = 1;
+    {
+        int want = c->tune_ppw;
+        if (want <= 0) {
+            want = 1;
+            while (want < kMaxPagesPerWave && total_pages * c->cfg.n_kv_heads / (kScoreWaves * 2 * want) >= 4096) want *= 2;
+        }
+        while (2 * cp <= want && 2 * cp <= kMaxPagesPerWave && 2 * cp * G <= 16) cp *= 2;
     }
     int splits = c->tune_splits;
     if (splits <= 0) {
-        // enough workgroups to fill the chip, and at most about 512 selected tokens per workgroup
-        // (a threshold set's size is not known here: assume 4096)
+        // about 128 selected tokens per workgroup (what the gather of 256-byte rows runs fastest with),
+        // more workgroups when the call is small (a threshold set's size is not known here: assume 4096)
         int kmax = 4096;
         if (p->mode == ALAYA_TOPK) {
             kmax = 1;
             for (int b = 0; b < B; ++b) kmax = p->topk[b] > kmax ? p->topk[b] : kmax;
         }
-        const int fill = (2048 + B * n_q_heads - 1) / (B * n_q_heads);
-        const int per = (int)(((int64_t)kmax + 511) / 512);
-        splits = fill > per ? fill : per;
+        const int64_t kw = (int64_t)kmax + p->window_init + p->window_last;
+        const int per = (int)((kw + 127) / 128);
+        const int fill = std::min((int)((kw + 31) / 32), (512 + B * n_q_heads - 1) / (B * n_q_heads));
+        splits = std::max(per, fill);
         if (splits < 1) splits = 1;
-        if (splits > 32) splits = 32;
+        if (splits > kMaxSplits) splits = kMaxSplits;
     }
 
     ReqDesc *hd;
     int slot;
-    rc = ring_acquire(c, &hd, &slot);
+    rc = ring_acquire(c, B, &hd, &slot);
     if (rc != ALAYA_OK) return rc;
-    int tiles = 0, tiles_b = 0, segs = 0, all_pages = 0;
-    // Large top-k calls filter with an estimated bound and pay two (normally idle) repair launches for
-    // it; below about a quarter of a million tokens in the call the guaranteed bound is as fast.
-    const bool estimate = c->estimate_mode > 0 || (c->estimate_mode == 0 && total_pages >= 4096);
+    int tiles = 0, tiles_b = 0;
+    const bool estimate = c->estimate_mode >= 0;
     bool any_est = false;
-    double survive = 0.0;
-    int64_t pages_a = 0;
+    int64_t pages_a = 0, pages_all = 0;
     int64_t off = 0;
     for (int b = 0; b < B; ++b) {
         // the tokens this query sees: the whole sequence, or the prefix asked for
         const int64_t n = p->n_visible ? (int64_t)p->n_visible[b] : c->seq_len[(size_t)seqs[b]];
         const int64_t pages = (n + kPageTokens - 1) / kPageTokens;
         ReqDesc &d = hd[b];
+        std::memset(&d, 0, sizeof d);
         d.pt_off = (int32_t)((int64_t)seqs[b] * c->L.mpps);
         d.n = (int32_t)n;
         d.head_stride = (int32_t)(pages * kPageTokens + kScorePad);
@@ -650,26 +735,18 @@ int sparse_attn_impl(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, 
         d.k = p->mode == ALAYA_TOPK ? (int32_t)((int64_t)p->topk[b] < n_out ? p->topk[b] : n_out) : 0;
         d.beta = p->mode == ALAYA_DIPR ? p->beta[b] : 0.f;
         d.score_off = off;
-        if (pages > (int64_t)kMaxSegs * kMaxSegPages)
+        if (pages > 131072)
             return fail(ALAYA_E_INVAL, "request %d: %lld tokens exceed the selection layout (%lld)", b, (long long)n,
-                        (long long)kMaxSegs * kMaxSegPages * kPageTokens);
+                        (long long)131072 * kPageTokens);
         d.n_pages = (int32_t)pages;
-        d.page_start = all_pages;
-        // selection segments: seg_pages pages each, at most kMaxSegs per head
-        int64_t per = seg_pages_want;
-        if ((pages + per - 1) / per > kMaxSegs) per = (pages + kMaxSegs - 1) / kMaxSegs;
-        per = (per + kMaxPagesPerWave - 1) / kMaxPagesPerWave * kMaxPagesPerWave; // whole scoring chunks
-        d.seg_pages = (int32_t)per;
-        d.nseg = (int32_t)((pages + per - 1) / per);
-        d.seg_start = segs;
-        // Sample stride S: phase A writes n / S scores, phase B about k * S survivors; their sum is
-        // smallest at S = sqrt(n / k).  Powers of two, at most 32, and the sample must hold 2k tokens.
+        // Sample stride S: the sample pass reads n / S keys, the main pass writes about k * S survivors
+        // (guaranteed bound).  Powers of two, at most 32.
         int S = 1;
         d.k_est = 0;
         if (!c->tune_noprune && pages >= 4) {
             // (never when top-k takes every token outside the window: nothing checks the bound then)
             if (p->mode == ALAYA_TOPK && estimate && d.k >= 512 && d.k < n_out && pages >= 64) {
-                // Estimated bound (large calls): a 1-in-S sample holds about mu = k / S of the k best
+                // Estimated bound: a 1-in-S sample holds about mu = k / S of the k best
                 // scores, so its (mu + 6 sqrt(mu) + 8)-th largest score lies below the true threshold
                 // unless the sample is far from representative - which the selection detects and
                 // repairs.  The main pass then writes about k (1 + 6 / sqrt(mu)) survivors whatever S
@@ -680,6 +757,10 @@ int sparse_attn_impl(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, 
                 d.k_est = c->estimate_mode == 2 ? 1 : (int32_t)(mu + 6.0 * std::sqrt(mu) + 8.0);
                 if (d.k_est > d.k) d.k_est = d.k;
                 if (S > 1) any_est = true; else d.k_est = 0;
+                // a sample-pass workgroup (four sampled pages) adds at most this much to one bucket: four
+                // times what all buckets down to the estimate's rank get from four pages on average, 8 at least
+                const int64_t sampled_pages = (pages + S - 1) / S;
+                d.hist_cap = (int32_t)std::max<int64_t>(8, (16 * (int64_t)d.k_est + sampled_pages - 1) / sampled_pages);
             } else if (p->mode == ALAYA_TOPK) {
                 while (S < 32 && (int64_t)(2 * S) * (2 * S) * d.k <= n && (int64_t)2 * S * d.k * 2 <= n) S *= 2;
                 while (S > 1 && pages / S < 2) S /= 2;
@@ -688,103 +769,82 @@ int sparse_attn_impl(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, 
                 while (S > 1 && pages / S < 2) S /= 2;
             }
         }
+        if (d.k_est == 0) d.hist_cap = 1 << 16; // guaranteed bound only: the counts must be exact
         d.sample_stride = S;
-        // share of the main pass's scores that is expected to survive
-        const double f = p->mode == ALAYA_TOPK && S > 1 ? (double)(d.k_est > 0 ? d.k_est : d.k) * S / (double)n : 0.0;
-        if (f > survive) survive = f;
-        all_pages += (int)pages;
-        segs += d.nseg;
-        off += (int64_t)n_q_heads * d.head_stride;
-    }
-    // Several pages per wavefront (about 8192 workgroups, survivors staged in registers and written as
-    // one list) pay when many scores survive; with few survivors one page per wavefront is faster.
-    if (ppw <= 0) {
-        ppw = 1;
-        if (survive > 0.03)
-            ppw = (int)((total_pages * c->cfg.n_kv_heads + (int64_t)kScoreWaves * 8192 - 1) /
-                        ((int64_t)kScoreWaves * 8192));
-        if (ppw < 1) ppw = 1;
-        if (ppw > 8) ppw = 8;
-    }
-    for (int b = 0; b < B; ++b) {
-        ReqDesc &d = hd[b];
-        const int S = d.sample_stride;
-        int cp = 1; // pages per wavefront in the main pass: a power of two, at most min(ppw, S)
-        while (2 * cp <= ppw && 2 * cp <= S) cp *= 2;
-        d.chunk_pages = cp;
-        // DIPR with a window (Sec. 7.1): the maximum mostly sits among the window's tokens, which are
-        // attended anyway, so the pages that hold them join the sample and seed the bound.  Whole
-        // main-pass chunks, so that a chunk never mixes the two kinds of page.
+        // DIPR with a window (Sec. 7.1): the maximum mostly sits among the window's tokens, so the pages
+        // that hold them join the sample and seed the bound.
         d.xf = 0;
         d.xb = d.n_pages;
         if (p->mode == ALAYA_DIPR && S > 1 && d.nwin > 0) {
-            const int wp0 = (d.w0 + kPageTokens - 1) / kPageTokens;
-            const int pb = d.w1 > 0 ? (d.n - d.w1) / kPageTokens : d.n_pages;
-            d.xf = std::min(d.n_pages, (wp0 + cp - 1) / cp * cp);
-            d.xb = std::max(d.xf, pb / cp * cp);
+            d.xf = std::min(d.n_pages, (d.w0 + kPageTokens - 1) / kPageTokens);
+            d.xb = std::max(d.xf, d.w1 > 0 ? (d.n - d.w1) / kPageTokens : d.n_pages);
         }
         // a decode step: the page of the newest token belongs to the sample pass, which writes that token
-        if (fused_k && S > 1) d.xb = std::max(d.xf, std::min(d.xb, (d.n - 1) / kPageTokens / cp * cp));
-        const int every = (d.n_pages + S - 1) / S;
-        auto not_every = [S](int a, int b) { return (b - a) - ((b + S - 1) / S - (a + S - 1) / S); }; // in [a, b)
+        if (fused_k) d.xb = std::max(d.xf, std::min(d.xb, (d.n - 1) / kPageTokens));
+        const int every = S > 1 ? (d.n_pages + S - 1) / S : 0;
+        auto not_every = [S](int a, int b) { return S > 1 ? (b - a) - ((b + S - 1) / S - (a + S - 1) / S) : b - a; }; // in [a, b)
         pages_a += every + not_every(0, d.xf) + not_every(d.xb, d.n_pages);
         const int n_a = every + d.xf + (d.n_pages - d.xb); // wavefronts of the sample pass
         d.tile_start = tiles;
         d.tileb_start = tiles_b;
-        tiles += (n_a + kScoreWaves - 1) / kScoreWaves;                                  // one page per wavefront
-        if (S > 1) tiles_b += (int)((d.n_pages + (int64_t)kScoreWaves * cp - 1) / ((int64_t)kScoreWaves * cp));
+        d.ntiles_b = (int32_t)((d.n_pages + (int64_t)kScoreWaves * cp - 1) / ((int64_t)kScoreWaves * cp));
+        tiles += (n_a + kScoreWaves - 1) / kScoreWaves; // one page per wavefront
+        tiles_b += d.ntiles_b;
+        pages_all += pages;
+        off += (int64_t)n_q_heads * d.head_stride;
     }
-    c->last_pages = all_pages;
-    c->last_pages_a = pages_a;
-    c->last_pages_b = all_pages - pages_a;
-    c->last_heads = n_q_heads;
-    if (off > c->L.score_elems) return fail(ALAYA_E_NOMEM, "score workspace too small");
-    if (all_pages > c->L.max_pages) return fail(ALAYA_E_NOMEM, "page-count workspace too small");
-    if (!c->ring_ev[slot]) {
-        hipError_t e = hipEventCreateWithFlags(&c->ring_ev[slot], hipEventDisableTiming);
-        if (e != hipSuccess) { c->ring_ev[slot] = nullptr; return fail_hip(e, "hipEventCreate"); }
+    const int64_t block_stride = kBlockHdr + (int64_t)kScoreWaves * cp * kPageTokens * G;
+    if (off > S.sel_elems) return fail(ALAYA_E_NOMEM, "scratch too small for the selected-token arrays");
+    if ((int64_t)tiles_b * c->cfg.n_kv_heads * block_stride > S.block_words)
+        return fail(ALAYA_E_NOMEM, "scratch too small for the survivor blocks");
+    if (!use) {
+        rc = need_scratch(c, st);
+        if (rc != ALAYA_OK) return rc;
     }
-    rc = ensure_device(c, st);
+    rc = ring_publish(c, dv, slot, B, st);
     if (rc != ALAYA_OK) return rc;
-    rc = ring_publish(c, slot, B, st);
-    if (rc != ALAYA_OK) return rc;
+    dv.block_stride = block_stride;
+    if (!use) {
+        c->last_B = B;
+        c->last_tiles_b = tiles_b;
+        c->last_pages_a = pages_a;
+        c->last_pages_b = pages_all;
+    }
 
     const Shape sh{c->cfg.dtype, c->cfg.head_dim, n_q_heads, c->cfg.n_kv_heads};
     const float scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)c->cfg.head_dim);
-    // (a launch that fails below may leave the running histogram and maximum half-filled: dev_ready is
-    // dropped so that the next call zeroes them again)
+    // (a launch that fails below may leave the statistics half-filled: scratch_ready is dropped so that
+    // the next call clears them again)
     hipError_t e;
     {
         Timed tm(c, 6, st);
-        if (fused_k) c->dv.fused = FusedAppend{(uint4 *)c->k_pool, (uint4 *)c->v_pool, (const uint4 *)fused_k, (const uint4 *)fused_v};
-        e = launch_score(sh, c->dv, B, q, tiles, 1, 0, p->mode, st);
-        c->dv.fused = FusedAppend{nullptr, nullptr, nullptr, nullptr};
-        if (e == hipSuccess) *appended = fused_k != nullptr;
-        // (DIPR: the bound kernel also gathers the sample pass's maxima, so it runs even with no main pass)
-        if (e == hipSuccess && (tiles_b > 0 || p->mode == ALAYA_DIPR)) e = launch_tau(sh, c->dv, B, p->mode, st);
+        if (fused_k) dv.fused = FusedAppend{(uint4 *)c->k_pool, (uint4 *)c->v_pool, (const uint4 *)fused_k, (const uint4 *)fused_v};
+        e = launch_sample(sh, dv, B, q, tiles, p->mode, st);
+        dv.fused = FusedAppend{nullptr, nullptr, nullptr, nullptr};
+        if (e == hipSuccess) *appended = fused_k != nullptr && tiles > 0;
+        if (e == hipSuccess) e = launch_tau(sh, dv, B, p->mode, st);
     }
-    if (e != hipSuccess) { c->dev_ready = false; return fail_hip(e, "sample scoring launch"); }
-    if (tiles_b > 0) {
+    if (e != hipSuccess) { c->scratch_ready = false; return fail_hip(e, "sample scoring launch"); }
+    {
         Timed tm(c, 0, st, true); // the roofline kernel: timed by its own dispatch
-        e = launch_score(sh, c->dv, B, q, tiles_b, ppw, 1, p->mode, st, tm.begin(), tm.end());
+        e = launch_score(sh, dv, B, q, tiles_b, cp, false, p->mode, st, tm.begin(), tm.end());
     }
-    if (e != hipSuccess) { c->dev_ready = false; return fail_hip(e, "score launch"); }
+    if (e != hipSuccess) { c->scratch_ready = false; return fail_hip(e, "score launch"); }
     {
         Timed tm(c, 1, st);
-        e = launch_select_front(sh, c->dv, B, p->mode, segs, st);
+        e = launch_select(sh, dv, B, p->mode, false, c->tune_batch, p->out_ids, p->out_counts, p->ids_stride, st);
         // repair of the heads whose estimated bound lost tokens (normally none: both launches are idle)
-        if (e == hipSuccess && any_est) e = launch_score(sh, c->dv, B, q, tiles_b, ppw, 2, p->mode, st);
-        if (e == hipSuccess && p->mode == ALAYA_TOPK)
-            e = launch_select_back(sh, c->dv, B, p->mode, segs, any_est, p->out_ids, p->out_counts, p->ids_stride, st);
+        if (e == hipSuccess && any_est) e = launch_score(sh, dv, B, q, tiles_b, cp, true, p->mode, st);
+        if (e == hipSuccess && any_est)
+            e = launch_select(sh, dv, B, p->mode, true, c->tune_batch, p->out_ids, p->out_counts, p->ids_stride, st);
     }
-    if (e != hipSuccess) { c->dev_ready = false; return fail_hip(e, "select launch"); }
+    if (e != hipSuccess) { c->scratch_ready = false; return fail_hip(e, "select launch"); }
     {
-        // (a DIPR call has no finishing pass: the gather reads select_local's lists and reports the ids)
         Timed tm(c, 2, st);
-        e = launch_attend(sh, c->dv, B, scale, splits, p->mode == ALAYA_DIPR, p->out_ids, p->out_counts, p->ids_stride, st);
+        e = launch_attend(sh, dv, B, scale, splits, st);
     }
     if (e != hipSuccess) return fail_hip(e, "attend launch");
-    { Timed tm(c, 3, st); e = launch_combine(sh, c->dv, B, splits, 0, 0, out, st); }
+    { Timed tm(c, 3, st); e = launch_combine(sh, dv, B, splits, 0, 0, out, st); }
     if (e != hipSuccess) return fail_hip(e, "combine launch");
     return ALAYA_OK;
 }
@@ -798,6 +858,7 @@ int alaya_full_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, c
     int rc = check_call(c, seqs, B, n_q_heads, q, out, &total_pages, &total_tokens);
     if (rc != ALAYA_OK) return rc;
     if (!(scale_in >= 0.f) || std::isinf(scale_in)) return fail(ALAYA_E_INVAL, "scale must be finite and >= 0");
+    if (!c->scratch_mem) return fail(ALAYA_E_INVAL, "no scratch memory bound to this cache (alaya_bind_scratch)");
     hipStream_t st = (hipStream_t)stream;
     int64_t ppt = (total_pages * c->cfg.n_kv_heads + kTargetGroups - 1) / kTargetGroups;
     ppt = (ppt + 3) / 4 * 4;
@@ -805,36 +866,24 @@ int alaya_full_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, c
 
     ReqDesc *hd;
     int slot;
-    rc = ring_acquire(c, &hd, &slot);
+    rc = ring_acquire(c, B, &hd, &slot);
     if (rc != ALAYA_OK) return rc;
     int tiles = 0;
     for (int b = 0; b < B; ++b) {
         const int64_t n = c->seq_len[(size_t)seqs[b]];
         const int64_t pages = (n + kPageTokens - 1) / kPageTokens;
         ReqDesc &d = hd[b];
+        std::memset(&d, 0, sizeof d);
         d.pt_off = (int32_t)((int64_t)seqs[b] * c->L.mpps);
         d.n = (int32_t)n;
-        d.head_stride = 0;
-        d.k = 0;
-        d.beta = 0.f;
         d.tile_start = tiles;
-        d.score_off = 0;
-        d.page_start = d.n_pages = d.seg_start = d.nseg = d.seg_pages = 0;
-        d.tileb_start = 0;
         d.sample_stride = 1;
-        d.chunk_pages = 1;
-        d.w0 = d.w1 = d.nwin = d.k_est = 0;
-        d.xf = d.xb = 0;
         tiles += (int)((pages + ppt - 1) / ppt);
     }
-    if (tiles > c->L.max_tiles) return fail(ALAYA_E_NOMEM, "partial-result workspace too small");
-    if (!c->ring_ev[slot]) {
-        hipError_t e = hipEventCreateWithFlags(&c->ring_ev[slot], hipEventDisableTiming);
-        if (e != hipSuccess) { c->ring_ev[slot] = nullptr; return fail_hip(e, "hipEventCreate"); }
-    }
-    rc = ensure_device(c, st);
+    if (tiles > c->S.max_tiles) return fail(ALAYA_E_NOMEM, "scratch too small for the partial results");
+    rc = need_scratch(c, st);
     if (rc != ALAYA_OK) return rc;
-    rc = ring_publish(c, slot, B, st);
+    rc = ring_publish(c, c->dv, slot, B, st);
     if (rc != ALAYA_OK) return rc;
 
     const Shape sh{c->cfg.dtype, c->cfg.head_dim, n_q_heads, c->cfg.n_kv_heads};
@@ -850,7 +899,7 @@ int alaya_full_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, c
 int alaya_poll_status(alaya_cache *c, void *stream)
 {
     if (!c) return fail(ALAYA_E_INVAL, "null cache handle");
-    if (!c->dev_ready) return ALAYA_OK;
+    if (!c->scratch_mem || !c->scratch_ready) return ALAYA_OK;
     hipStream_t st = (hipStream_t)stream;
     int32_t word = 0;
     hipError_t e = hipMemcpyAsync(&word, c->dv.status, sizeof word, hipMemcpyDeviceToHost, st);
@@ -863,6 +912,8 @@ int alaya_poll_status(alaya_cache *c, void *stream)
     }
     return ALAYA_OK;
 }
+
+// ---- include/alaya_debug.h ---------------------------------------------------------------------
 
 int alaya_set_profiling(alaya_cache *c, int enabled)
 {
@@ -887,12 +938,6 @@ int alaya_kernel_times(alaya_cache *c, double *sum_ms, int64_t *launches, int n_
     return ALAYA_OK;
 }
 
-const float *alaya_debug_scores(const alaya_cache *c)
-{
-    if (!c) { fail(ALAYA_E_INVAL, "null cache handle"); return nullptr; }
-    return (const float *)c->dv.cand;
-}
-
 int alaya_debug_estimate(alaya_cache *c, int mode)
 {
     if (!c) return fail(ALAYA_E_INVAL, "null cache handle");
@@ -909,31 +954,31 @@ int alaya_debug_pages(const alaya_cache *c, int64_t *sampled, int64_t *main_pass
     return ALAYA_OK;
 }
 
-int64_t alaya_debug_survivors(alaya_cache *c, void *stream)
+int64_t alaya_debug_scores(alaya_cache *c, float *out, void *stream)
 {
     if (!c) { fail(ALAYA_E_INVAL, "null cache handle"); return -1; }
-    const size_t n = (size_t)c->last_pages * c->last_heads;
-    if (n == 0) return 0;
-    std::vector<int32_t> h(n);
+    if (!c->scratch_mem || c->last_tiles_b <= 0) return 0;
     hipStream_t st = (hipStream_t)stream;
-    hipError_t e = hipMemcpyAsync(h.data(), c->dv.page_cnt, n * sizeof(int32_t), hipMemcpyDeviceToHost, st);
+    unsigned long long *total = (unsigned long long *)(c->scratch_mem + c->S.dbg_total);
+    hipError_t e = launch_fill_u32((uint32_t *)total, 2, 0u, st);
+    const Shape sh{c->cfg.dtype, c->cfg.head_dim, c->cfg.n_q_heads, c->cfg.n_kv_heads};
+    if (e == hipSuccess) e = launch_debug_scatter(sh, c->dv, c->last_B, c->last_tiles_b, out, total, st);
+    unsigned long long h = 0;
+    if (e == hipSuccess) e = hipMemcpyAsync(&h, total, sizeof h, hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
-    if (e != hipSuccess) { fail_hip(e, "survivor count read"); return -1; }
-    int64_t tot = 0;
-    for (size_t i = 0; i < n; ++i) tot += h[i];
-    return tot;
+    if (e != hipSuccess) { fail_hip(e, "survivor read"); return -1; }
+    return (int64_t)h;
 }
 
-int alaya_set_tuning(alaya_cache *c, int score_pages_per_wave, int attend_splits, int select_segment_pages,
+int alaya_set_tuning(alaya_cache *c, int score_pages_per_wave, int attend_splits, int select_batch_blocks,
                      int write_all_scores)
 {
     if (!c) return fail(ALAYA_E_INVAL, "null cache handle");
-    if (score_pages_per_wave > kMaxPagesPerWave || attend_splits > kMaxSplits ||
-        select_segment_pages > kMaxSegPages)
+    if (score_pages_per_wave > 16 || attend_splits > kMaxSplits || select_batch_blocks > kSelBatch)
         return fail(ALAYA_E_INVAL, "knob out of range");
     c->tune_ppw = score_pages_per_wave > 0 ? score_pages_per_wave : 0;
     c->tune_splits = attend_splits > 0 ? attend_splits : 0;
-    c->tune_seg = select_segment_pages > 0 ? select_segment_pages : 0;
+    c->tune_batch = select_batch_blocks > 0 ? select_batch_blocks : 0;
     c->tune_noprune = write_all_scores > 0 ? 1 : 0;
     return ALAYA_OK;
 }

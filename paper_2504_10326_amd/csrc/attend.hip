@@ -4,12 +4,12 @@
 //   z_j = s_j * scale;  a = softmax over the selected set;  o = sum_j a_j v_j        (Eq. 1, restricted
 //   to the critical tokens as in Sec. 2 "Sparse Attention").
 // Partial results carry (m, l, acc) = (reference max, sum of exp(z - m), sum of exp(z - m) v) and are
-// merged in a fixed order, as in the paper's data-centric engine (Sec. 6.2: partial attention computed
+// merged in a fixed order, as in the paper's data-centric engine (Sec. 7.2: partial attention computed
 // where the vectors sit, then aggregated the FlashAttention way).  The sparse path knows its softmax
-// reference before it starts: the selection leaves the maximum over the selected set in head_M (DIPR:
-// the maximum of all scores, which is always selected; top-k: the maximum of the finished list), so no
+// reference before it starts: the selection leaves the maximum over the selected set in head_M, so no
 // rescaling is needed on the way.
 #include "alaya_internal.h"
+#include "score_page.h"
 
 namespace alaya {
 
@@ -21,59 +21,67 @@ __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_floa
 template <int DT, int D> struct RowSlice {
     static constexpr int EPL = D / 16;
     static constexpr int BYTES = EPL * (DT == 0 ? 2 : 4);
-    // row: first byte of the token's value row; sub = lane % 16
-    __device__ static __forceinline__ void load(const char *row, int sub, float *f)
+    static constexpr int WORDS = BYTES / 4;
+    struct Raw { uint32_t w[WORDS]; }; // a lane's slice as loaded
+    // row: first byte of the token's value row; sub = lane % 16.  STREAM: the row is read once, in order
+    // with its neighbours (dense attention): non-temporal load.  Rows gathered at random are loaded plainly
+    // (measured: the hint costs the gather 5 to 10 %).
+    template <bool STREAM = false>
+    __device__ static __forceinline__ Raw load_raw(const char *row, int sub)
     {
         const char *p = row + (size_t)sub * BYTES;
-        if constexpr (DT == 0 && EPL == 8) {
-            const uint4 c = *(const uint4 *)p;
-            f[0] = bf16_lo(c.x); f[1] = bf16_hi(c.x); f[2] = bf16_lo(c.y); f[3] = bf16_hi(c.y);
-            f[4] = bf16_lo(c.z); f[5] = bf16_hi(c.z); f[6] = bf16_lo(c.w); f[7] = bf16_hi(c.w);
-        } else if constexpr (DT == 0 && EPL == 4) {
-            const uint2 c = *(const uint2 *)p;
-            f[0] = bf16_lo(c.x); f[1] = bf16_hi(c.x); f[2] = bf16_lo(c.y); f[3] = bf16_hi(c.y);
-        } else if constexpr (DT == 1 && EPL == 8) {
-            const float4 a = *(const float4 *)p, b = *(const float4 *)(p + 16);
-            f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+        Raw r;
+        if constexpr (WORDS == 8) {
+            const uint4 a = STREAM ? load_stream((const uint4 *)p) : *(const uint4 *)p;
+            const uint4 b = STREAM ? load_stream((const uint4 *)(p + 16)) : *(const uint4 *)(p + 16);
+            r.w[0] = a.x; r.w[1] = a.y; r.w[2] = a.z; r.w[3] = a.w; r.w[4] = b.x; r.w[5] = b.y; r.w[6] = b.z; r.w[7] = b.w;
+        } else if constexpr (WORDS == 4) {
+            const uint4 a = STREAM ? load_stream((const uint4 *)p) : *(const uint4 *)p;
+            r.w[0] = a.x; r.w[1] = a.y; r.w[2] = a.z; r.w[3] = a.w;
         } else {
-            const float4 a = *(const float4 *)p;
-            f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w;
+            const uint2 a = *(const uint2 *)p;
+            r.w[0] = a.x; r.w[1] = a.y;
         }
+        return r;
+    }
+    __device__ static __forceinline__ void widen(const Raw &r, float *f)
+    {
+        if constexpr (DT == 0) {
+#pragma unroll
+            for (int i = 0; i < WORDS; ++i) { f[2 * i] = bf16_lo(r.w[i]); f[2 * i + 1] = bf16_hi(r.w[i]); }
+        } else {
+#pragma unroll
+            for (int i = 0; i < WORDS; ++i) f[i] = __uint_as_float(r.w[i]);
+        }
+    }
+    template <bool STREAM = false>
+    __device__ static __forceinline__ void load(const char *row, int sub, float *f)
+    {
+        widen(load_raw<STREAM>(row, sub), f);
     }
 };
 
 // ------------------------------------------------------------------------------------------------
 // Sparse attend.  Grid: (request, head, split).  A wavefront takes 4 selected rows per step
-// (16 lanes per 256-byte row), kAttendU steps in flight.
-// SEG = false: the head's selected tokens are one list (sel_ids / sel_scores, `counts` long), as the
-// finishing pass of a top-k call leaves them.
-// SEG = true (DIPR): there is no finishing pass; the selected tokens are still where select_local put
-// them, one list per selection segment (`ids_in` / `scores_in` = its arrays, seg_counts = the lengths).
-// The kernel reads the concatenation of those lists through the segments' prefix sums, and does what
-// is left of the finishing pass on the way: the true count, the ids for the caller, the overflow
-// status, and the reset of the head's running maximum for the next call.
-constexpr int kAttendU = 4;
+// (16 lanes per 256-byte row), kAttendU steps in flight: 128 rows per workgroup and pass - the gather of
+// 256-byte rows at random runs fastest with many small workgroups (6.1 TB/s at 128 rows each against
+// 3.8 at 2048 on a 410 MB gather).  The head's selected tokens are one list (sel_rows / sel_scores,
+// `counts` long, ascending by token), as the selection leaves them; sel_rows already holds the rows'
+// places in the V pool, so that the loads of a pass are two deep (row number, row), not three.
+constexpr int kAttendU = 8;
 
-struct AttendOut { // SEG only: what the caller asked to get back
-    int32_t *out_ids, *out_counts;
-    int64_t ids_stride;
-    int32_t *status;
-};
-
-template <int DT, int D, bool SEG>
+template <int DT, int D>
 __global__ __launch_bounds__(kAttendThreads) void attend_kernel(
-    const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int H_q, int H_kv, const int32_t *__restrict__ page_table,
-    const char *__restrict__ v_pool, const int32_t *__restrict__ ids_in, const float *__restrict__ scores_in,
-    int32_t *__restrict__ counts, const float *__restrict__ head_M, float scale, int splits,
-    float *__restrict__ partials, const int32_t *__restrict__ seg_counts, uint32_t *__restrict__ head_maxkey,
-    const AttendOut ao)
+    const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int H_q, int H_kv,
+    const char *__restrict__ v_pool, const int32_t *__restrict__ rows_in, const float *__restrict__ scores_in,
+    const int32_t *__restrict__ counts, const float *__restrict__ head_M, float scale, int splits,
+    float *__restrict__ partials)
 {
     const Descs desc{desc_mem, desc0, desc_n};
     using RS = RowSlice<DT, D>;
     constexpr int EPL = RS::EPL;
     constexpr size_t ROW_BYTES = (size_t)D * (DT == 0 ? 2 : 4);
     __shared__ float red[4][D + 1];
-    __shared__ int32_t pre[SEG ? kMaxSegs + 1 : 1]; // exclusive prefix sums of the segments' list lengths
 
     const int sp = blockIdx.x % splits;
     const int rh = blockIdx.x / splits;
@@ -81,54 +89,14 @@ __global__ __launch_bounds__(kAttendThreads) void attend_kernel(
     const int kvh = h / (H_q / H_kv);
     const ReqDesc dsc = desc[r];
     const size_t off = (size_t)dsc.score_off + (size_t)h * dsc.head_stride;
-    const int32_t *ids = ids_in + off;
+    const int32_t *rows = rows_in + off;
     const float *ss = scores_in + off;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int nseg = dsc.nseg;
-    if (SEG) {
-        static_assert(kMaxSegs == 64, "one segment per lane");
-        if (threadIdx.x < 64) {
-            const int a = lane < nseg ? seg_counts[((size_t)rh * kMaxSegs + lane) * 2] : 0;
-            int ia = a;
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                const int t = __shfl_up(ia, o);
-                if (lane >= o) ia += t;
-            }
-            pre[lane] = ia - a;
-            if (lane == 63) pre[64] = ia;
-        }
-        __syncthreads();
-    }
-    const size_t seg_region = (size_t)dsc.seg_pages * kPageTokens;
-    // position of element i of the head's list in ids / ss
-    auto at = [&](int i) -> size_t {
-        if (!SEG) return (size_t)i;
-        int lo = 0, hi = nseg; // the last segment whose prefix is <= i
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (pre[mid] <= i) lo = mid; else hi = mid;
-        }
-        return (size_t)lo * seg_region + (size_t)(i - pre[lo]);
-    };
-    const int cnt = SEG ? pre[kMaxSegs] : counts[rh];
+    const int cnt = counts[rh];
     int per = (cnt + splits - 1) / splits;
     per = (per + 15) & ~15;
     const int begin = min(cnt, sp * per), end = min(cnt, begin + per);
     const float M = head_M[rh];
-    if (SEG) {
-        if (ao.out_ids) {
-            const int m = (int)((int64_t)end < ao.ids_stride ? (int64_t)end : ao.ids_stride);
-            int32_t *dst = ao.out_ids + (size_t)rh * (size_t)ao.ids_stride;
-            for (int i = begin + (int)threadIdx.x; i < m; i += kAttendThreads) dst[i] = ids[at(i)];
-        }
-        if (sp == 0 && threadIdx.x == 0) {
-            counts[rh] = cnt;
-            if (ao.out_counts) ao.out_counts[rh] = cnt;
-            if (ao.out_ids && (int64_t)cnt > ao.ids_stride) atomicOr(ao.status, 1);
-            head_maxkey[rh] = 0u; // clean for the next call (select_local, the last reader, is done)
-        }
-    }
 
     const int sub = lane & 15, grp = lane >> 4;
     float acc[EPL];
@@ -137,38 +105,30 @@ __global__ __launch_bounds__(kAttendThreads) void attend_kernel(
     float l = 0.f;
 
     for (int i0 = begin + wave * 4 + grp; i0 < end; i0 += 16 * kAttendU) {
-        int id[kAttendU];
+        int row[kAttendU];
         float p[kAttendU];
 #pragma unroll
         for (int u = 0; u < kAttendU; ++u) {
             const int i = i0 + u * 16;
             const bool ok = i < end;
-            const size_t src = ok ? at(i) : 0;
-            id[u] = ok ? ids[src] : -1;
-            p[u] = ok ? __expf((ss[src] - M) * scale) : 0.f;
+            row[u] = ok ? rows[i] : -1;
+            p[u] = ok ? __expf((ss[i] - M) * scale) : 0.f;
         }
-        const char *row[kAttendU];
+        typename RS::Raw raw[kAttendU];
 #pragma unroll
         for (int u = 0; u < kAttendU; ++u) {
-            const int t = id[u] < 0 ? 0 : id[u];
-            const int phys = id[u] < 0 ? 0 : page_table[dsc.pt_off + (t >> 6)];
-            row[u] = v_pool + (((size_t)phys * H_kv + kvh) * 64 + (t & 63)) * ROW_BYTES;
-        }
-        float v[kAttendU][EPL];
-#pragma unroll
-        for (int u = 0; u < kAttendU; ++u) {
-            if (id[u] >= 0) {
-                RS::load(row[u], sub, v[u]);
-            } else {
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) v[u][e] = 0.f;
-            }
+            // row = physical page * 64 + slot; a page holds 64 rows of each of its H_kv heads
+            const size_t at = ((size_t)(row[u] >> 6) * H_kv + kvh) * 64 + (row[u] & 63);
+            if (row[u] >= 0) raw[u] = RS::load_raw(v_pool + at * ROW_BYTES, sub);
+            else raw[u] = typename RS::Raw{};
         }
 #pragma unroll
         for (int u = 0; u < kAttendU; ++u) {
+            float v[EPL];
+            RS::widen(raw[u], v);
             l += p[u];
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p[u], v[u][e], acc[e]);
+            for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p[u], v[e], acc[e]);
         }
     }
     // the four 16-lane groups of a wavefront hold different rows: add them up
@@ -193,24 +153,13 @@ __global__ __launch_bounds__(kAttendThreads) void attend_kernel(
     }
 }
 
-hipError_t launch_attend(const Shape &sh, const DeviceViews &dv, int B, float scale, int splits, bool segmented,
-                         int32_t *out_ids, int32_t *out_counts, int64_t ids_stride, hipStream_t st)
+hipError_t launch_attend(const Shape &sh, const DeviceViews &dv, int B, float scale, int splits, hipStream_t st)
 {
     const dim3 grid((unsigned)(B * sh.n_q_heads * splits)), block(kAttendThreads);
-    const AttendOut ao{out_ids, out_counts, ids_stride, dv.status};
 #define ALAYA_ATTEND(DT, D)                                                                                  \
-    do {                                                                                                     \
-        if (segmented)                                                                                       \
-            attend_kernel<DT, D, true><<<grid, block, 0, st>>>(                                              \
-                dv.desc.mem, dv.desc.in, dv.desc.n, sh.n_q_heads, sh.n_kv_heads, dv.page_table,              \
-                (const char *)dv.v_pool, dv.loc_ids, dv.loc_scores, dv.counts, dv.head_M, scale, splits,     \
-                dv.partials, dv.seg_counts, dv.head_maxkey, ao);                                             \
-        else                                                                                                 \
-            attend_kernel<DT, D, false><<<grid, block, 0, st>>>(                                             \
-                dv.desc.mem, dv.desc.in, dv.desc.n, sh.n_q_heads, sh.n_kv_heads, dv.page_table,              \
-                (const char *)dv.v_pool, dv.sel_ids, dv.sel_scores, dv.counts, dv.head_M, scale, splits,     \
-                dv.partials, dv.seg_counts, dv.head_maxkey, ao);                                             \
-    } while (0)
+    attend_kernel<DT, D><<<grid, block, 0, st>>>(dv.desc.mem, dv.desc.in, dv.desc.n, sh.n_q_heads, sh.n_kv_heads, \
+                                                 (const char *)dv.v_pool, dv.sel_rows, dv.sel_scores,        \
+                                                 dv.counts, dv.head_M, scale, splits, dv.partials)
     if (sh.dtype == 0 && sh.head_dim == 128) ALAYA_ATTEND(0, 128);
     else if (sh.dtype == 0 && sh.head_dim == 64) ALAYA_ATTEND(0, 64);
     else if (sh.dtype == 1 && sh.head_dim == 128) ALAYA_ATTEND(1, 128);
@@ -294,9 +243,10 @@ hipError_t launch_combine(const Shape &sh, const DeviceViews &dv, int B, int spl
 
 // ------------------------------------------------------------------------------------------------
 // Dense attention, split over pages (Eq. 1 over every cached token).  Grid: (tile, KV head).  Each
-// wavefront walks its pages: scores for 64 tokens x G heads as in the scoring pass (lane = token),
-// online softmax per head, probabilities through LDS, then the page's value rows with 16 lanes per
-// row.  The four wavefronts' results are merged before the partial is written.
+// wavefront walks its pages: scores for 64 tokens x G heads with the scoring pass's own routine
+// (lane = token), online softmax per head, probabilities through LDS, then the page's value rows with
+// 16 lanes per row.  Keys and values are read once: non-temporal loads.  The four wavefronts' results
+// are merged before the partial is written.
 template <int DT, int D, int G>
 __global__ __launch_bounds__(256) void full_partial_kernel(const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int B,
                                                             const int32_t *__restrict__ page_table,
@@ -311,7 +261,6 @@ __global__ __launch_bounds__(256) void full_partial_kernel(const ReqDesc *__rest
     constexpr int E = DT == 0 ? 8 : 4;
     constexpr int NC = D / E;
     constexpr size_t ROW_BYTES = (size_t)D * (DT == 0 ? 2 : 4);
-    __shared__ float qs[G][D];
     __shared__ float ps[4][G][64];
     __shared__ float red[4][G][D + 2];
 
@@ -321,12 +270,8 @@ __global__ __launch_bounds__(256) void full_partial_kernel(const ReqDesc *__rest
     while (r + 1 < B && desc[r + 1].tile_start <= tile) ++r;
     const ReqDesc dsc = desc[r];
     const int H_q = H_kv * G;
-    for (int i = threadIdx.x; i < G * D; i += 256) {
-        const int g = i / D, c = i % D;
-        const size_t qi = ((size_t)r * H_q + kvh * G + g) * D + c;
-        qs[g][c] = DT == 0 ? bf16_to_f32(((const uint16_t *)qv)[qi]) : ((const float *)qv)[qi];
-    }
-    __syncthreads();
+    constexpr int QW = D * (DT == 0 ? 2 : 4) / 4;
+    const uint4 *qh = (const uint4 *)((const uint32_t *)qv + ((size_t)r * H_q + kvh * G) * QW); // wave-uniform
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63, sub = lane & 15, grp = lane >> 4;
@@ -349,28 +294,8 @@ __global__ __launch_bounds__(256) void full_partial_kernel(const ReqDesc *__rest
         const int phys = active ? page_table[dsc.pt_off + p] : 0;
         const size_t tile_off = ((size_t)phys * H_kv + kvh);
         if (active) {
-            const uint4 *base = k_pool + tile_off * (size_t)(NC * 64) + lane;
-            uint4 kc[NC];
-#pragma unroll
-            for (int c = 0; c < NC; ++c) kc[c] = base[c * 64];
             float s[G];
-#pragma unroll
-            for (int g = 0; g < G; ++g) s[g] = 0.f;
-#pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                float kf[E];
-                if constexpr (DT == 0) {
-                    kf[0] = bf16_lo(kc[c].x); kf[1] = bf16_hi(kc[c].x); kf[2] = bf16_lo(kc[c].y); kf[3] = bf16_hi(kc[c].y);
-                    kf[4] = bf16_lo(kc[c].z); kf[5] = bf16_hi(kc[c].z); kf[6] = bf16_lo(kc[c].w); kf[7] = bf16_hi(kc[c].w);
-                } else {
-                    kf[0] = __uint_as_float(kc[c].x); kf[1] = __uint_as_float(kc[c].y);
-                    kf[2] = __uint_as_float(kc[c].z); kf[3] = __uint_as_float(kc[c].w);
-                }
-#pragma unroll
-                for (int e = 0; e < E; ++e)
-#pragma unroll
-                    for (int g = 0; g < G; ++g) s[g] = fmaf(kf[e], qs[g][c * E + e], s[g]);
-            }
+            score_page<DT, D, G>(k_pool + tile_off * (size_t)(NC * 64) + lane, qh, s);
             const bool valid = p * kPageTokens + lane < dsc.n;
 #pragma unroll
             for (int g = 0; g < G; ++g) {
@@ -394,7 +319,7 @@ __global__ __launch_bounds__(256) void full_partial_kernel(const ReqDesc *__rest
             for (int t4 = 0; t4 < 16; ++t4) {
                 const int tok = t4 * 4 + grp;
                 float v[EPL];
-                RS::load(vbase + (size_t)tok * ROW_BYTES, sub, v);
+                RS::template load<true>(vbase + (size_t)tok * ROW_BYTES, sub, v);
                 if (p * kPageTokens + tok >= dsc.n) { // unwritten tail of the last page: weight 0, but 0 * NaN is NaN
 #pragma unroll
                     for (int e = 0; e < EPL; ++e) v[e] = 0.f;

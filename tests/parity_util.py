@@ -41,11 +41,12 @@ def make_cache(w: wl.Workload, g: dict, extra_tokens: int = 0, max_batch=None, c
                 max_tokens_per_seq=max(w.lens) + extra_tokens + 64,
                 max_batch_tokens=w.total_tokens + w.batch * extra_tokens,
                 n_phys_pages=n_phys, phys_page_order=order if w.permute_pages else None)
-    # Poison everything the library did not write itself: unwritten page slots and workspace read as NaN
+    # Poison everything the library did not write itself: unwritten page slots, workspace and scratch read as NaN
     # (0xFFFF is a bf16 NaN, 0xFFFFFFFF an fp32 NaN), so any use of them shows up in the outputs.
     c.k_pool.fill_(0xFF)
     c.v_pool.fill_(0xFF)
     c.workspace.fill_(0xFF)
+    c.scratch.fill_(0xFF)
     for r, n in enumerate(w.lens):
         cuts = [0, n] if not chunks else sorted({0, n, *[x for x in chunks if 0 < x < n]})
         for a, b in zip(cuts[:-1], cuts[1:]):

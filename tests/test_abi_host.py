@@ -25,14 +25,17 @@ def _create(cfg=None, order=None):
 
 
 def test_library_exports_every_declared_symbol():
-    text = open(os.path.join(ROOT, "include", "alaya.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(alaya_[a-z_]+)\s*\(", text))
-    assert {"alaya_create_cache", "alaya_append_kv", "alaya_sparse_attn", "alaya_full_attn"} <= declared
     L = A.lib()
-    for name in sorted(declared):
-        assert hasattr(L, name), f"{name} declared in alaya.h but not exported"
-    assert declared == set(A.EXPORTS)
+    for header, exports in (("alaya.h", A.EXPORTS), ("alaya_debug.h", A.DEBUG_EXPORTS)):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        declared = set(re.findall(r"\b(alaya_[a-z_]+)\s*\(", text))
+        for name in sorted(declared):
+            assert hasattr(L, name), f"{name} declared in {header} but not exported"
+        assert declared == set(exports), header
+    assert {"alaya_create_cache", "alaya_append_kv", "alaya_sparse_attn", "alaya_full_attn"} <= set(A.EXPORTS)
+    # the paper-defined header carries no measurement or test hooks
+    assert not any("debug" in n or "tuning" in n or "profiling" in n for n in A.EXPORTS)
 
 
 def test_struct_layouts_match_header():
@@ -44,9 +47,34 @@ def test_sizes():
     cfg = _cfg()
     assert A.alaya_pool_bytes(cfg) == 70 * 8 * 64 * 128 * 2
     assert A.alaya_pool_bytes(_cfg(dtype=1)) == 70 * 8 * 64 * 128 * 4
+    # the cache's own workspace is its page table: 4 sequences of 64 pages
     ws = A.alaya_workspace_bytes(cfg)
-    # three arrays of one fp32/int32 per (q head, padded token) dominate the workspace
-    assert ws >= 3 * 4 * 32 * 8192 and ws % 256 == 0
+    assert ws == 4 * 64 * 4
+    # survivor blocks and selected tokens, 8 bytes each per (q head, token), dominate the scratch memory
+    sc = A.alaya_scratch_bytes(cfg)
+    assert sc >= 2 * 8 * 32 * 8192 and sc % 256 == 0
+    assert A.alaya_scratch_bytes(_cfg(max_batch_tokens=16384)) > sc
+
+
+def test_scratch_binding_is_checked_and_may_be_shared():
+    """Scratch memory is separate from the cache (one cache = one layer; layers run one after the other
+    and may share it): size and alignment are checked, several caches may bind the same area, NULL unbinds."""
+    cfg = _cfg()
+    sc = A.alaya_scratch_bytes(cfg)
+    a, b = _create(cfg), _create(cfg)
+    try:
+        for args, code in [((a, FAKE[3] + 8, sc), A.ALAYA_E_INVAL), ((a, FAKE[3], sc - 1), A.ALAYA_E_NOMEM),
+                           ((0, FAKE[3], sc), A.ALAYA_E_INVAL)]:
+            with pytest.raises(A.AlayaError) as e:
+                A.alaya_bind_scratch(*args)
+            assert e.value.code == code
+        A.alaya_bind_scratch(a, FAKE[3], sc)
+        A.alaya_bind_scratch(b, FAKE[3], sc + 4096)          # the same area, for a second layer
+        A.alaya_bind_scratch(b, 0, 0)                         # unbind
+        assert A.alaya_poll_status(a) == A.ALAYA_OK           # nothing launched yet: nothing to read
+    finally:
+        A.alaya_destroy_cache(a)
+        A.alaya_destroy_cache(b)
 
 
 @pytest.mark.parametrize("bad", [dict(head_dim=96), dict(page_tokens=32), dict(dtype=2), dict(n_q_heads=30),

@@ -230,7 +230,7 @@ def test_decode_steps_from_an_empty_cache_until_the_pool_is_empty():
     g = wl.generate(w)
     c = A.Cache(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, max_seqs=2, max_batch=2, max_tokens_per_seq=512,
                 max_batch_tokens=1024, n_phys_pages=12)
-    c.k_pool.fill_(0xFF); c.v_pool.fill_(0xFF); c.workspace.fill_(0xFF)
+    c.k_pool.fill_(0xFF); c.v_pool.fill_(0xFF); c.workspace.fill_(0xFF); c.scratch.fill_(0xFF)
     q = to_device(g["q"], w.dtype)
     for mode, kw in [(A.ALAYA_TOPK, dict(topk=[4, 4])), (A.ALAYA_DIPR, dict(beta=[1.0, 1.0]))]:
         for r in (0, 1):
@@ -321,8 +321,8 @@ def test_dipr_bound_is_seeded_by_the_window():
             kept[window, ppw] = c.debug_survivors() / (n * w.n_q_heads)
     c.close()
     for ppw in (0, 4):
-        # with the window: the sampled pages (1 in 16, written in full), the window, and little else
-        assert kept[(128, 512), ppw] < 0.10 < 0.25 < kept[(0, 0), ppw], kept
+        # with the window: the window's tokens and little else
+        assert kept[(128, 512), ppw] < 0.05 < 0.2 < kept[(0, 0), ppw], kept
 
 
 def test_prefix_queries_ignore_what_lies_behind_the_prefix():
@@ -635,8 +635,51 @@ def test_custom_scale_and_profiling_hooks():
     t = c.kernel_times()
     # every run_and_compare makes two calls: one pruned, one with all scores written
     assert t["sample"]["launches"] == 6 and t["sample"]["sum_ms"] > 0 and t["combine"]["launches"] == 6
-    assert 0 < t["score"]["launches"] <= 6        # the main scoring pass runs only when there is something to prune
+    assert t["score"]["launches"] == 6 and t["score"]["sum_ms"] > 0
     c.close()
+
+
+def test_caches_of_several_layers_share_one_scratch_area():
+    """One cache is one layer; layers run one after the other and may bind the same scratch memory.  Three
+    caches with different contents take turns on one scratch area (top-k with an estimated bound, DIPR,
+    dense attention, a decode step of two sequences) and must answer exactly as caches with scratch
+    memory of their own."""
+    lens = [9000, 700]
+    ws = [_llama(lens, seed=s, topk=[600, 30]) for s in (0, 1, 2)]
+    gs = [wl.generate(w) for w in ws]
+    own = [make_cache(w, g, extra_tokens=64) for w, g in zip(ws, gs)]
+    shared_mem = torch.empty_like(own[0].scratch)
+    shared_mem.fill_(0xFF)
+    shared = []
+    for w, g in zip(ws, gs):
+        c = A.Cache(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, max_seqs=2, max_batch=2,
+                    max_tokens_per_seq=max(lens) + 128, max_batch_tokens=sum(lens) + 128,
+                    n_phys_pages=g["n_phys_pages"] + 2, scratch=shared_mem)
+        for r, n in enumerate(lens):
+            c.append_kv(r, to_device(g["K"][r], w.dtype), to_device(g["V"][r], w.dtype))
+        shared.append(c)
+    qs = [to_device(g["q"], "bf16") for g in gs]
+    for rnd in range(2):
+        for i in (0, 1, 2, 1, 0):
+            for mode, kw in [(A.ALAYA_TOPK, dict(topk=[600, 30], ids_stride=700)),
+                             (A.ALAYA_DIPR, dict(beta=[2.0, 1.0], ids_stride=9100, window=(16, 64)))]:
+                ra = own[i].sparse_attn([0, 1], qs[i], mode, **kw)
+                rb = shared[i].sparse_attn([0, 1], qs[i], mode, **kw)
+                for x, y in zip(ra, rb):
+                    assert torch.equal(x, y), (rnd, i, mode)
+            assert torch.equal(own[i].full_attn([0, 1], qs[i]), shared[i].full_attn([0, 1], qs[i]))
+        # every layer appends a token (two sequences: the descriptors travel through the scratch memory) and attends
+        for i in (0, 1, 2):
+            ks = to_device(np.stack([gs[i]["K"][r][rnd] for r in range(2)]), "bf16")
+            vs = to_device(np.stack([gs[i]["V"][r][rnd] for r in range(2)]), "bf16")
+            ra = own[i].decode_step([0, 1], ks, vs, qs[i], A.ALAYA_TOPK, topk=[600, 30], ids_stride=700)
+            rb = shared[i].decode_step([0, 1], ks, vs, qs[i], A.ALAYA_TOPK, topk=[600, 30], ids_stride=700)
+            for x, y in zip(ra, rb):
+                assert torch.equal(x, y), (rnd, i)
+    torch.cuda.synchronize()
+    assert shared[0].poll_status() == A.ALAYA_OK
+    for c in own + shared:
+        c.close()
 
 
 # ------------------------------------------------------------------------------------------ random sweep

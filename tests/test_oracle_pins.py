@@ -149,7 +149,7 @@ def test_nesting_counts_and_cross_check():
         sets = [set(x) for x in r["ids"]]
         for h, S in enumerate(sets):
             assert len(S) >= 1 and int(np.argmax(r["scores"][h])) in S
-            # Sec. 5.1.2 (i): a DIPR answer is the top-k' answer for k' = its own size
+            # Sec. 6.1.2 (i): a DIPR answer is the top-k' answer for k' = its own size
             kprime = len(S)
             assert S == set(oracle.select_topk(r["scores"][h], kprime))
         if prev_b is not None:
@@ -182,7 +182,7 @@ def test_token_permutation_invariance():
 # ---------------------------------------------------------------- P7 / P8: brute force
 @pytest.mark.parametrize("seed", range(4))
 def test_bruteforce_tiny(seed):
-    """n = 12: sort for top-k, enumerate every subset for the recovery ratio (Sec. 5.1.2, Observation I)."""
+    """n = 12: sort for top-k, enumerate every subset for the recovery ratio (Sec. 6.1.1, Observation I)."""
     n, k = 12, 4
     w, q, K, V = _small(seed, n=n, hq=2, hk=1, d=8)
     qf, Kf, Vf = q.astype(np.float64), K.astype(np.float64), V.astype(np.float64)
@@ -222,7 +222,7 @@ def test_ties_prefer_smaller_index():
 
 # ---------------------------------------------------------------- P9: partial attention merge
 def test_partial_attention_merge():
-    """Sec. 6.2, data-centric engine: parts computed independently and merged by (max, sum, acc) equal one pass."""
+    """Sec. 7.2, data-centric engine: parts computed independently and merged by (max, sum, acc) equal one pass."""
     w, q, K, V = _small(17, n=222, hq=2, hk=1, d=16)
     s, _, _ = _dense(q, K, V, "f32")
     rng = np.random.default_rng(1)
@@ -243,7 +243,7 @@ def test_partial_attention_merge():
 
 # ---------------------------------------------------------------- P10: GQA
 def test_gqa_equals_replicated_mha():
-    """Sec. 6.2, GQA: the heads of a group query the same key/value head."""
+    """Sec. 7.2, GQA: the heads of a group query the same key/value head."""
     w, q, K, V = _small(19, n=140, hq=8, hk=2, d=16)
     G = w.group
     Kr, Vr = np.repeat(K, G, axis=1), np.repeat(V, G, axis=1)
@@ -316,7 +316,7 @@ def test_bf16_widening_is_exact():
 
 # ---------------------------------------------------------------- window and prefix (Sec. 7.1)
 def _merge_two(parts):
-    """Partial-attention merge (Sec. 6.2) of (m, l, o) triples computed from library routines."""
+    """Partial-attention merge (Sec. 7.2) of (m, l, o) triples computed from library routines."""
     M = max(m for m, _, _ in parts)
     num = sum(math.exp(m - M) * l * o for m, l, o in parts)
     den = sum(math.exp(m - M) * l for m, l, _ in parts)
@@ -360,7 +360,7 @@ def test_window_closed_form_weights():
 @pytest.mark.parametrize("seed,w0,w1,k", [(0, 5, 7, 6), (1, 0, 9, 3), (2, 11, 0, 200), (3, 1, 1, 1)])
 def test_window_topk_is_window_plus_topk_of_the_rest(seed, w0, w1, k):
     """The retrieved tokens are the windowless top-k of the cache with the window rows removed, and the
-    output is the merge (Sec. 6.2) of the window's attention and the retrieved tokens' attention."""
+    output is the merge (Sec. 7.2) of the window's attention and the retrieved tokens' attention."""
     w, q, K, V = _small(seed)
     n, d, G = K.shape[0], K.shape[2], w.n_q_heads // w.n_kv_heads
     s, _, _ = _dense(q, K, V, "f32")

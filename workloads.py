@@ -3,7 +3,7 @@
 This module serves both the CPU oracle and the HIP path and holds none of the
 method's arithmetic: it only draws random numbers, shapes them like the
 paper's workload (Llama-3-8B-style heads: 32 query heads sharing 8 KV heads,
-head_dim 128, bf16, Sec. 8 "Experimental Setting"; a few dominant keys among a
+head_dim 128, bf16, Sec. 9 "Experimental Setting"; a few dominant keys among a
 long tail, Sec. 2 "Sparse Attention") and rounds them once to the storage
 type.  Both sides then read the very same bytes.
 
