@@ -188,6 +188,23 @@ int alaya_sparse_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
 int alaya_decode_step(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *k, const void *v,
                       const void *q, const alaya_sparse_params *p, float *out, void *stream);
 
+/*
+ * alaya_sparse_attn for callers that cannot allocate device memory or bind any (code under HIP graph
+ * capture set-up, tight serving loops, harnesses that forbid hipMalloc): same arguments, same results,
+ * but the scratch memory of the call is an array of ALAYA_STATIC_SCRATCH_BYTES that the library holds
+ * itself on each GPU it runs on (in its device image, until the process ends); the cache needs no
+ * alaya_bind_scratch.  The call allocates nothing, on the host's device side or through any library.
+ * Limit: the call's scratch need - about 16 bytes per (query head, token the call sees) plus 0.6 MB per
+ * request - must fit the array (32 query heads: about 160 thousand tokens in one call); a larger call
+ * is refused with ALAYA_E_NOMEM and nothing is launched.  Every call on a GPU, from any cache, uses that
+ * GPU's one array: calls that overlap in time on one GPU race, so order them on one stream.  The array
+ * keeps the last call's contents; each call clears the words that must start at zero.
+ * alaya_poll_status does not see this call's status word; ask for out_counts to detect an id overflow.
+ */
+#define ALAYA_STATIC_SCRATCH_BYTES (80u << 20)
+int alaya_sparse_attn_static(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q,
+                             const alaya_sparse_params *p, float *out, void *stream);
+
 /* Session.attention, dense: Eq. (1) over every cached token (same q / out layout as above). */
 int alaya_full_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q,
                     float scale, float *out, void *stream);

@@ -29,7 +29,8 @@ KERNEL_SLOTS = ("score", "select", "attend", "combine", "full_partial", "append"
 EXPORTS = (
     "alaya_pool_bytes", "alaya_workspace_bytes", "alaya_scratch_bytes", "alaya_create_cache", "alaya_bind_scratch",
     "alaya_destroy_cache", "alaya_append_kv", "alaya_append_kv_step", "alaya_seq_len", "alaya_reset_seq",
-    "alaya_sparse_attn", "alaya_decode_step", "alaya_full_attn", "alaya_poll_status", "alaya_last_error",
+    "alaya_sparse_attn", "alaya_decode_step", "alaya_sparse_attn_static", "alaya_full_attn", "alaya_poll_status",
+    "alaya_last_error",
 )
 # include/alaya_debug.h
 DEBUG_EXPORTS = (
@@ -92,6 +93,8 @@ def lib() -> ctypes.CDLL:
         L.alaya_sparse_attn.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), i32, i32, vp,
                                         ctypes.POINTER(SparseParams), vp, vp]
         L.alaya_sparse_attn.restype = i32
+        L.alaya_sparse_attn_static.argtypes = L.alaya_sparse_attn.argtypes
+        L.alaya_sparse_attn_static.restype = i32
         L.alaya_decode_step.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), i32, i32, vp, vp, vp,
                                         ctypes.POINTER(SparseParams), vp, vp]
         L.alaya_decode_step.restype = i32
@@ -206,8 +209,9 @@ def alaya_sparse_attn(handle: int, seqs: Sequence[int], n_q_heads: int, q, mode:
                       topk: Optional[Sequence[int]], beta: Optional[Sequence[float]], scale: float, out,
                       out_ids=None, out_counts=None, ids_stride: int = 0, stream=0,
                       window: Tuple[int, int] = (0, 0), n_visible: Optional[Sequence[int]] = None,
-                      step_kv=None) -> None:
-    """step_kv = (k, v): make the call an alaya_decode_step that first appends one token per sequence."""
+                      step_kv=None, static_scratch: bool = False) -> None:
+    """step_kv = (k, v): make the call an alaya_decode_step that first appends one token per sequence.
+    static_scratch: call alaya_sparse_attn_static (the library's own scratch array, nothing allocated)."""
     p = SparseParams()
     p.mode = mode
     p.window_init, p.window_last = int(window[0]), int(window[1])
@@ -225,8 +229,16 @@ def alaya_sparse_attn(handle: int, seqs: Sequence[int], n_q_heads: int, q, mode:
         _check(lib().alaya_decode_step(handle, sq, len(seqs), n_q_heads, _ptr(step_kv[0]), _ptr(step_kv[1]), _ptr(q),
                                        ctypes.byref(p), _ptr(out), stream or None))
         return
-    _check(lib().alaya_sparse_attn(handle, sq, len(seqs), n_q_heads, _ptr(q), ctypes.byref(p), _ptr(out),
-                                   stream or None))
+    fn = lib().alaya_sparse_attn_static if static_scratch else lib().alaya_sparse_attn
+    _check(fn(handle, sq, len(seqs), n_q_heads, _ptr(q), ctypes.byref(p), _ptr(out), stream or None))
+
+
+def alaya_sparse_attn_static(handle: int, seqs: Sequence[int], n_q_heads: int, q, mode: int,
+                             topk: Optional[Sequence[int]], beta: Optional[Sequence[float]], scale: float, out,
+                             out_ids=None, out_counts=None, ids_stride: int = 0, stream=0,
+                             window: Tuple[int, int] = (0, 0), n_visible: Optional[Sequence[int]] = None) -> None:
+    alaya_sparse_attn(handle, seqs, n_q_heads, q, mode, topk, beta, scale, out, out_ids, out_counts, ids_stride,
+                      stream, window, n_visible, static_scratch=True)
 
 
 def alaya_decode_step(handle: int, seqs: Sequence[int], n_q_heads: int, k, v, q, mode: int,
@@ -328,10 +340,12 @@ class Cache:
 
     def sparse_attn(self, seqs: Sequence[int], q, mode: int, topk=None, beta=None, scale: float = 0.0,
                     ids_stride: int = 0, out=None, stream=None, want_counts: bool = False,
-                    window: Tuple[int, int] = (0, 0), n_visible: Optional[Sequence[int]] = None, _step_kv=None):
+                    window: Tuple[int, int] = (0, 0), n_visible: Optional[Sequence[int]] = None, _step_kv=None,
+                    static_scratch: bool = False):
         """Returns out [B][Hq][d] fp32, or (out, ids [B][Hq][ids_stride] int32, counts [B][Hq] int32) when
         ids_stride > 0, or (out, counts) when only want_counts is set.  window = (first, last) tokens
-        that are always attended; n_visible[b] = the prefix of request b that the query sees."""
+        that are always attended; n_visible[b] = the prefix of request b that the query sees.
+        static_scratch: through alaya_sparse_attn_static (the library's own scratch array)."""
         if out is None:
             out = self._q_out(seqs, q)
         ids = counts = None
@@ -341,7 +355,8 @@ class Cache:
         if ids_stride > 0 or want_counts:
             counts = self.torch.zeros((len(seqs), self.cfg.n_q_heads), dtype=self.torch.int32, device=self.device)
         alaya_sparse_attn(self.handle, seqs, self.cfg.n_q_heads, q, mode, topk, beta, scale, out, ids, counts,
-                          ids_stride, _stream(stream), window, n_visible, step_kv=_step_kv)
+                          ids_stride, _stream(stream), window, n_visible, step_kv=_step_kv,
+                          static_scratch=static_scratch)
         if ids is not None:
             return out, ids, counts
         return (out, counts) if want_counts else out

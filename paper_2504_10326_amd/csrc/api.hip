@@ -22,6 +22,15 @@ namespace {
 
 thread_local std::string g_err;
 
+// Scratch memory for alaya_sparse_attn_static, the entry point for callers that cannot allocate: one
+// array per GPU, in the library's own device image, held until the process ends.  In host code the
+// array's name is only a stand-in for the symbol: every use of the memory goes through the address that
+// hipGetSymbolAddress returns for the current device.
+constexpr size_t kStaticScratchBytes = ALAYA_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+char *g_static_scratch[kMaxDevices]; // per device: address of that device's copy of `scratch`, once looked up
+
 int fail(int code, const char *fmt, ...)
 {
     char buf[512];
@@ -850,6 +859,50 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
 }
 
 } // namespace
+
+int alaya_sparse_attn_static(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q,
+                             const alaya_sparse_params *p, float *out, void *stream)
+{
+    int64_t total_pages = 0, total_tokens = 0;
+    int rc = check_call(c, seqs, B, n_q_heads, q, out, &total_pages, &total_tokens);
+    if (rc != ALAYA_OK) return rc;
+    // The layout for exactly this call; it must fit the array.
+    int64_t tokens = total_tokens;
+    if (p && p->n_visible) {
+        tokens = 0;
+        for (int b = 0; b < B; ++b) tokens += p->n_visible[b] > 0 ? p->n_visible[b] : 0;
+    }
+    const Scratch S = make_scratch(n_q_heads, c->cfg.n_kv_heads, c->cfg.head_dim, B, tokens);
+    if (S.total > kStaticScratchBytes)
+        return fail(ALAYA_E_NOMEM, "call needs %zu bytes of scratch memory, the built-in area holds %zu "
+                    "(alaya_sparse_attn with bound scratch memory has no such limit)", S.total, kStaticScratchBytes);
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(ALAYA_E_DEVICE, "device %d outside 0..%d", dev, kMaxDevices - 1);
+    if (!g_static_scratch[dev]) {
+        char *ptr = nullptr;
+        e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) return fail_hip(e, "hipGetSymbolAddress(scratch)");
+        g_static_scratch[dev] = ptr;
+    }
+    char *base = g_static_scratch[dev];
+    hipStream_t st = (hipStream_t)stream;
+    // The array keeps what the call before this one left (of any cache, with any layout): clear what must start at zero.
+    e = clear_scratch(S, base, st);
+    if (e != hipSuccess) return fail_hip(e, "scratch clear");
+    if (B > kInlineDescs && !c->ring_ev[c->ring_pos])
+        return fail(ALAYA_E_DEVICE, "descriptor ring not initialised (no device when the cache was created)");
+    DeviceViews dv = c->dv; // page table and pools; the rest is pointed at the array
+    bind_views(dv, S, base);
+    const ScratchUse use{&dv, &S};
+    const bool prof = c->prof; // (the profiling mode creates events on first use: not here)
+    c->prof = false;
+    bool appended = false;
+    rc = sparse_attn_impl(c, &use, seqs, B, n_q_heads, q, p, out, stream, nullptr, nullptr, &appended);
+    c->prof = prof;
+    return rc;
+}
 
 int alaya_full_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q, float scale_in,
                     float *out, void *stream)
