@@ -51,6 +51,15 @@ def _load():
         lib.oracle_attend.restype = None
         lib.oracle_select_window.argtypes = [vp, i64, i64, i64, i32, i64, f64, vp]
         lib.oracle_select_window.restype = i64
+        lib.oracle_block_reps.argtypes = [vp, i32, i64, i32, i32, i32, i64, vp, vp]
+        lib.oracle_block_reps.restype = None
+        lib.oracle_block_scores.argtypes = [vp, i32, vp, vp, i64, i32, vp]
+        lib.oracle_block_scores.restype = None
+        lib.oracle_select_topk_in_blocks.argtypes = [vp, i64, i64, vp, i64, i64, i64, i64, vp]
+        lib.oracle_select_topk_in_blocks.restype = i64
+        lib.oracle_coarse_attn.argtypes = [vp, vp, vp, i32, i64, i64, i32, i32, i32, i64, i64, i64, f64, i64, i64, vp,
+                                           vp, i64, vp, vp, vp, i64, vp, vp, i32]
+        lib.oracle_coarse_attn.restype = i32
         lib.oracle_sparse_attn.argtypes = [vp, vp, vp, i32, i64, i32, i32, i32, i32, i64, f64, f64, i64, i64,
                                            vp, vp, i64, vp, vp, i32]
         lib.oracle_sparse_attn.restype = i32
@@ -110,6 +119,71 @@ def select_window(s: np.ndarray, w0: int, w1: int, mode: int, k: int = 0, beta: 
     if cnt < 0:
         raise ValueError("invalid k, beta or window")
     return ids[:cnt].copy()
+
+
+def block_reps(K: np.ndarray, g: int, block: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Channel-wise minimum and maximum of the keys of KV head g over blocks of `block` adjacent tokens: fp64 [nb][d] each."""
+    K = _c(K)
+    n, hk, d = K.shape
+    nb = (n + block - 1) // block
+    lo, hi = np.empty((nb, d), dtype=np.float64), np.empty((nb, d), dtype=np.float64)
+    _load().oracle_block_reps(_p(K), _dt(K), n, hk, g, d, int(block), _p(lo), _p(hi))
+    return lo, hi
+
+
+def block_scores(q_h: np.ndarray, lo: np.ndarray, hi: np.ndarray) -> np.ndarray:
+    """u_b = sum_c max(q_c lo_bc, q_c hi_bc): fp64 [nb]."""
+    q_h, lo, hi = _c(q_h), _c(lo.astype(np.float64, copy=False)), _c(hi.astype(np.float64, copy=False))
+    nb, d = lo.shape
+    assert hi.shape == lo.shape and q_h.shape == (d,)
+    u = np.empty(nb, dtype=np.float64)
+    _load().oracle_block_scores(_p(q_h), _dt(q_h), _p(lo), _p(hi), nb, d, _p(u))
+    return u
+
+
+def select_topk_in_blocks(s: np.ndarray, block: int, blocks: np.ndarray, k: int, window: Tuple[int, int] = (0, 0)) -> np.ndarray:
+    """Window tokens plus the k best tokens outside the window among the tokens of the given blocks: ascending ids."""
+    s = _c(s.astype(np.float64, copy=False))
+    blocks = _c(np.asarray(blocks, dtype=np.int32))
+    if blocks.size and (blocks.min() < 0 or blocks.max() * block >= s.size):
+        raise IndexError("block out of range")
+    ids = np.empty(max(1, s.size), dtype=np.int32)
+    cnt = _load().oracle_select_topk_in_blocks(_p(s), s.size, int(block), _p(blocks), blocks.size, int(window[0]),
+                                               int(window[1]), int(k), _p(ids))
+    if cnt < 0:
+        raise ValueError("invalid k, block or window")
+    return ids[:cnt].copy()
+
+
+def coarse_attn(q: np.ndarray, K: np.ndarray, V: np.ndarray, block: int, n_blocks: int, k: int,
+                scale: Optional[float] = None, window: Tuple[int, int] = (0, 0), n_visible: Optional[int] = None,
+                want_scores: bool = False, threads: int = 0) -> dict:
+    """Top-k through the coarse index, one request, all heads: the n_blocks best blocks per head, then top-k
+    among their tokens.  n_visible: the query sees that prefix only, through the index of the whole stored
+    context (a block's representatives cover its hidden tokens too).  Returns {"out", "counts", "ids",
+    "blocks": list of int32 arrays (ascending), "u": fp64 [Hq][nb] block scores, "scores": fp64 [Hq][n_visible]
+    or None, "threads"}."""
+    q, K, V = _c(q), _c(K), _c(V)
+    n, hk, d = K.shape
+    nv = n if n_visible is None else int(n_visible)
+    if not 0 < nv <= n:
+        raise ValueError("n_visible out of range")
+    hq = q.shape[0]
+    assert V.shape == K.shape and q.shape == (hq, d) and _dt(q) == _dt(K) == _dt(V)
+    nb = (nv + block - 1) // block
+    out = np.empty((hq, d), dtype=np.float64)
+    counts, bcounts = np.zeros(hq, dtype=np.int64), np.zeros(hq, dtype=np.int64)
+    ids = np.empty((hq, nv), dtype=np.int32)
+    blocks = np.empty((hq, nb), dtype=np.int32)
+    u = np.empty((hq, nb), dtype=np.float64)
+    sc = np.empty((hq, nv), dtype=np.float64) if want_scores else None
+    rc = _load().oracle_coarse_attn(_p(q), _p(K), _p(V), _dt(K), n, nv, hq, hk, d, int(block), int(n_blocks), int(k),
+                                    float(scale) if scale else 0.0, int(window[0]), int(window[1]), _p(out),
+                                    _p(ids), nv, _p(counts), _p(sc), _p(blocks), nb, _p(bcounts), _p(u), int(threads))
+    if rc < 0:
+        raise ValueError(f"oracle error {rc}")
+    return {"out": out, "counts": counts, "ids": [ids[h, :counts[h]].copy() for h in range(hq)],
+            "blocks": [blocks[h, :bcounts[h]].copy() for h in range(hq)], "u": u, "scores": sc, "threads": rc}
 
 
 def attend(s: np.ndarray, V: np.ndarray, g: int, ids: np.ndarray, scale: Optional[float] = None) -> np.ndarray:

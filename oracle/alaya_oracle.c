@@ -20,6 +20,13 @@
  *            ALL tokens, the window's included
  *   prefix   (Sec. 7.1 "Flexible Context Reuse") only the first n_visible tokens exist for the query:
  *            the caller hands over that prefix of K and V, nothing else changes
+ *   coarse   (Sec. 6.2 "Query Optimizer", coarse-grained index; Table 4: top-k and filter queries) adjacent
+ *            tokens form blocks, each block is represented by two vectors - the channel-wise minimum lo and
+ *            maximum hi of its keys - and scored by u_b = sum_c max(q_c lo_bc, q_c hi_bc), which no q.k of
+ *            the block exceeds; the P blocks with the largest u_b (equal u: smaller block first) are the
+ *            critical blocks, and the top-k query runs over their tokens only (window tokens are still
+ *            always attended).  The paper fixes neither the block size, nor the representatives, nor P:
+ *            they are parameters here.
  *
  * All arithmetic is fp64.  Inputs are the stored bytes (bf16 or fp32), widened
  * exactly.  K and V are token-major: element (j, g, c) sits at (j*n_kv_heads + g)*d + c.
@@ -149,6 +156,132 @@ int64_t oracle_select_window(const double *s, int64_t n, int64_t w0, int64_t w1,
     free(take);
     free(inwin);
     return cnt;
+}
+
+/* Coarse index, step 1: representatives of block b = tokens [b*block, min(n, (b+1)*block)) of KV head g:
+ * lo[b][c] = min_j K[j][g][c], hi[b][c] = max_j K[j][g][c].  lo, hi: [ceil(n/block)][d]. */
+void oracle_block_reps(const void *K, int dtype, int64_t n, int n_kv_heads, int g, int d, int64_t block,
+                       double *lo, double *hi)
+{
+    for (int64_t b = 0; b * block < n; ++b) {
+        for (int c = 0; c < d; ++c) {
+            double mn = 0.0, mx = 0.0;
+            for (int64_t j = b * block; j < n && j < (b + 1) * block; ++j) {
+                double x = widen(K, dtype, (j * n_kv_heads + g) * (int64_t)d + c);
+                if (j == b * block || x < mn) mn = x;
+                if (j == b * block || x > mx) mx = x;
+            }
+            lo[b * d + c] = mn;
+            hi[b * d + c] = mx;
+        }
+    }
+}
+
+/* Coarse index, step 2: u_b = sum_c max(q_c * lo[b][c], q_c * hi[b][c]) for nb blocks. */
+void oracle_block_scores(const void *q, int dtype, const double *lo, const double *hi, int64_t nb, int d, double *u)
+{
+    for (int64_t b = 0; b < nb; ++b) {
+        double acc = 0.0;
+        for (int c = 0; c < d; ++c) {
+            double qc = widen(q, dtype, c);
+            double a = qc * lo[b * d + c], z = qc * hi[b * d + c];
+            acc += a > z ? a : z;
+        }
+        u[b] = acc;
+    }
+}
+
+/* Coarse index, step 3 is oracle_select_topk(u, nb, P, blocks): the P best blocks, smaller block first among
+ * equal scores.  Step 4: the top-k query over the tokens of the given blocks (ascending block numbers):
+ * the window W = {j < w0} U {j >= n - w1} plus the min(k, candidates) best tokens outside W that lie in one
+ * of the blocks (equal scores: smaller j first).  ids ascending.  Returns the count, -1 on invalid arguments. */
+int64_t oracle_select_topk_in_blocks(const double *s, int64_t n, int64_t block, const int32_t *blocks, int64_t nblk,
+                                     int64_t w0, int64_t w1, int64_t k, int32_t *ids)
+{
+    if (w0 < 0 || w1 < 0 || k <= 0 || block <= 0) return -1;
+    if (n <= 0) return 0;
+    char *cand = (char *)calloc((size_t)n, 1);
+    for (int64_t i = 0; i < nblk; ++i)
+        for (int64_t j = (int64_t)blocks[i] * block; j < n && j < ((int64_t)blocks[i] + 1) * block; ++j) cand[j] = 1;
+    int32_t *order = (int32_t *)malloc((size_t)n * sizeof *order);
+    int64_t m = 0;
+    for (int64_t j = 0; j < n; ++j) {
+        int inwin = j < w0 || j >= n - w1;
+        if (cand[j] && !inwin) order[m++] = (int32_t)j;
+    }
+    qsort_r(order, (size_t)m, sizeof *order, by_score_desc_then_id, (void *)s);
+    int64_t kk = k < m ? k : m;
+    char *take = (char *)calloc((size_t)n, 1);
+    for (int64_t i = 0; i < kk; ++i) take[order[i]] = 1;
+    int64_t cnt = 0;
+    for (int64_t j = 0; j < n; ++j)
+        if (j < w0 || j >= n - w1 || take[j]) ids[cnt++] = (int32_t)j;
+    free(take);
+    free(order);
+    free(cand);
+    return cnt;
+}
+
+/*
+ * One request, all query heads, top-k through the coarse index: scores -> block representatives -> block
+ * scores -> the P best blocks -> top-k among their tokens -> attend.
+ *   blocks_out  optional [n_q_heads][blocks_stride] ascending block numbers (first min(count, stride))
+ *   bcounts     optional [n_q_heads] blocks chosen = min(P, number of blocks)
+ *   u_out       optional [n_q_heads][number of blocks] block scores
+ *   n_vis       the query sees only the first n_vis <= n tokens (prefix reuse, Sec. 7.1), through the index of
+ *               the STORED context: the representatives of a block cover all of its stored tokens, also those
+ *               behind the prefix; only blocks that hold a visible token take part
+ * Other arguments as oracle_sparse_attn.  Returns the threads used, negative on invalid arguments.
+ */
+void oracle_attend(const double *s, const void *V, int dtype, int n_kv_heads, int g, int d,
+                   const int32_t *ids, int64_t cnt, double scale, double *o);
+int oracle_coarse_attn(const void *q, const void *K, const void *V, int dtype, int64_t n, int64_t n_vis, int n_q_heads,
+                       int n_kv_heads, int d, int64_t block, int64_t P, int64_t k, double scale, int64_t w0, int64_t w1, double *out,
+                       int32_t *ids, int64_t ids_stride, int64_t *counts, double *scores, int32_t *blocks_out,
+                       int64_t blocks_stride, int64_t *bcounts, double *u_out, int n_threads)
+{
+    if (n <= 0 || n_q_heads <= 0 || n_kv_heads <= 0 || d <= 0 || n_q_heads % n_kv_heads) return -1;
+    if (w0 < 0 || w1 < 0) return -4;
+    if (k <= 0) return -2;
+    if (block <= 0 || P <= 0) return -5;
+    if (n_vis <= 0 || n_vis > n) return -6;
+    if (!(scale > 0.0)) scale = 1.0 / sqrt((double)d);
+    const int G = n_q_heads / n_kv_heads;
+    const size_t esz = dtype == ORACLE_F32 ? 4 : 2;
+    const int64_t nb = (n_vis + block - 1) / block;            /* blocks that hold a visible token */
+    const int64_t n_rep = nb * block < n ? nb * block : n;     /* stored tokens that their representatives cover */
+    int used = 1;
+#ifdef _OPENMP
+    if (n_threads <= 0) n_threads = omp_get_max_threads();
+    if (n_threads > n_q_heads) n_threads = n_q_heads;
+    used = n_threads;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(n_threads)
+#endif
+    for (int h = 0; h < n_q_heads; ++h) {
+        const int g = h / G;
+        const void *qh = (const char *)q + (size_t)h * (size_t)d * esz;
+        double *s = scores ? scores + (size_t)h * (size_t)n_vis : (double *)malloc((size_t)n_vis * sizeof(double));
+        double *lo = (double *)malloc((size_t)nb * d * sizeof(double)), *hi = (double *)malloc((size_t)nb * d * sizeof(double));
+        double *u = u_out ? u_out + (size_t)h * (size_t)nb : (double *)malloc((size_t)nb * sizeof(double));
+        int32_t *blk = (int32_t *)malloc((size_t)nb * sizeof(int32_t));
+        int32_t *sel = (int32_t *)malloc((size_t)n_vis * sizeof(int32_t));
+        oracle_scores(qh, K, dtype, n_vis, n_kv_heads, g, d, s);
+        oracle_block_reps(K, dtype, n_rep, n_kv_heads, g, d, block, lo, hi);
+        oracle_block_scores(qh, dtype, lo, hi, nb, d, u);
+        int64_t nblk = oracle_select_topk(u, nb, P, blk);
+        int64_t cnt = oracle_select_topk_in_blocks(s, n_vis, block, blk, nblk, w0, w1, k, sel);
+        oracle_attend(s, V, dtype, n_kv_heads, g, d, sel, cnt, scale, out + (size_t)h * (size_t)d);
+        if (counts) counts[h] = cnt;
+        if (bcounts) bcounts[h] = nblk;
+        if (ids) memcpy(ids + (size_t)h * (size_t)ids_stride, sel, (size_t)(cnt < ids_stride ? cnt : ids_stride) * sizeof(int32_t));
+        if (blocks_out)
+            memcpy(blocks_out + (size_t)h * (size_t)blocks_stride, blk,
+                   (size_t)(nblk < blocks_stride ? nblk : blocks_stride) * sizeof(int32_t));
+        free(sel); free(blk); free(lo); free(hi);
+        if (!u_out) free(u);
+        if (!scores) free(s);
+    }
+    return used;
 }
 
 /* Softmax over the selected set and the weighted sum of its value rows. */

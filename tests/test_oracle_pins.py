@@ -427,3 +427,111 @@ def test_prefix_sees_nothing_behind_it(mode, kw):
     assert np.array_equal(full["out"], plain["out"])
     with pytest.raises(ValueError):
         oracle.sparse_attn(q, K, V, mode, n_visible=0, **kw)
+
+
+# ---------------------------------------------------------------- coarse-grained index (Sec. 6.2, Table 4)
+def test_coarse_index_by_hand():
+    """Sec. 6.2, coarse-grained index: blocks of adjacent tokens, two representative vectors (channel-wise
+    min and max), block score = sum_c max(q_c lo_c, q_c hi_c), best blocks first, then top-k inside them.
+    d = 2, q = (1, -2), three blocks of two tokens; every number below is worked out by hand:
+      block 0: keys (1,1), (3,0)   lo (1,0)  hi (3,1)  u = max(1,3) + max(0,-2)  = 3    scores -1, 3
+      block 1: keys (0,-1), (2,2)  lo (0,-1) hi (2,2)  u = max(0,2) + max(2,-4)  = 4    scores  2, -2
+      block 2: keys (-1,0), (-2,1) lo (-2,0) hi (-1,1) u = max(-2,-1) + max(0,-2) = -1  scores -1, -4
+    The best single block is block 1 although the best token (score 3) sits in block 0: with one block the
+    query answers token 2, with two blocks token 1."""
+    q = np.array([[1.0, -2.0]], dtype=np.float32)
+    K = np.array([[1, 1], [3, 0], [0, -1], [2, 2], [-1, 0], [-2, 1]], dtype=np.float32).reshape(6, 1, 2)
+    V = np.arange(12, dtype=np.float32).reshape(6, 1, 2)
+    lo, hi = oracle.block_reps(K, 0, 2)
+    assert lo.tolist() == [[1, 0], [0, -1], [-2, 0]] and hi.tolist() == [[3, 1], [2, 2], [-1, 1]]
+    assert oracle.block_scores(q[0], lo, hi).tolist() == [3.0, 4.0, -1.0]
+    r1 = oracle.coarse_attn(q, K, V, block=2, n_blocks=1, k=1)
+    assert r1["blocks"][0].tolist() == [1] and r1["ids"][0].tolist() == [2]
+    np.testing.assert_allclose(r1["out"][0], V[2, 0])
+    r2 = oracle.coarse_attn(q, K, V, block=2, n_blocks=2, k=1)
+    assert r2["blocks"][0].tolist() == [0, 1] and r2["ids"][0].tolist() == [1]
+    # k larger than the blocks hold: every token of the chosen blocks (the paper's description read literally)
+    r3 = oracle.coarse_attn(q, K, V, block=2, n_blocks=2, k=100)
+    assert r3["ids"][0].tolist() == [0, 1, 2, 3]
+    # weights exp(s / sqrt(2)) over scores -1, 3, 2, -2
+    wgt = np.exp(np.array([-1.0, 3.0, 2.0, -2.0]) / math.sqrt(2.0))
+    np.testing.assert_allclose(r3["out"][0], (wgt[:, None] * V[:4, 0]).sum(0) / wgt.sum(), rtol=1e-12)
+    # window tokens are attended whatever block they are in; top-k counts the others
+    r4 = oracle.coarse_attn(q, K, V, block=2, n_blocks=1, k=1, window=(1, 1))
+    assert r4["ids"][0].tolist() == [0, 2, 5]
+    # equal block scores: the smaller block wins (block 2 made a copy of block 1)
+    K2 = K.copy(); K2[4:6] = K[2:4]
+    assert oracle.coarse_attn(q, K2, V, block=2, n_blocks=1, k=1)["blocks"][0].tolist() == [1]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_coarse_representatives_and_bound_against_library_routines(dtype):
+    """The representatives are plain minima and maxima (numpy's), and the block score is an upper bound of
+    every inner product of the block - the property that makes min/max vectors a usable representative -
+    reached exactly by blocks of one token."""
+    w, q, K, V = _small(21, n=203, hq=4, hk=2, d=16, dtype=dtype)
+    Kf, qf = _f64(K, dtype), _f64(q, dtype)
+    for block in (1, 7, 64):
+        nb = -(-203 // block)
+        for g in range(2):
+            lo, hi = oracle.block_reps(K, g, block)
+            pad = np.full((nb * block - 203, 16), np.nan)
+            kb = np.concatenate([Kf[:, g], pad]).reshape(nb, block, 16)
+            np.testing.assert_array_equal(lo, np.nanmin(kb, axis=1))
+            np.testing.assert_array_equal(hi, np.nanmax(kb, axis=1))
+            for h in (2 * g, 2 * g + 1):
+                u = oracle.block_scores(q[h], lo, hi)
+                s = Kf[:, g] @ qf[h]
+                smax = np.array([s[b * block:(b + 1) * block].max() for b in range(nb)])
+                assert (u >= smax - 1e-12).all()
+                if block == 1:
+                    np.testing.assert_allclose(u, s, rtol=0, atol=1e-12)
+
+
+def test_coarse_query_reduces_to_the_exact_one():
+    """All blocks chosen = the exact top-k query; blocks of one token with P = k too; and so does any P that
+    takes every block whose bound reaches the exact k-th score (no token that belongs to the answer can lie
+    in a block whose upper bound is below it).  Chosen blocks are nested in P."""
+    w, q, K, V = _small(22, n=500, hq=4, hk=2, d=16, dtype="bf16")
+    exact = oracle.sparse_attn(q, K, V, oracle.TOPK, k=20, want_scores=True, window=(3, 5))
+    nb = -(-500 // 16)
+    allb = oracle.coarse_attn(q, K, V, block=16, n_blocks=nb, k=20, window=(3, 5))
+    for h in range(4):
+        assert allb["ids"][h].tolist() == exact["ids"][h].tolist()
+        np.testing.assert_allclose(allb["out"][h], exact["out"][h], rtol=0, atol=1e-12)
+    one = oracle.coarse_attn(q, K, V, block=1, n_blocks=20, k=20)
+    ex0 = oracle.sparse_attn(q, K, V, oracle.TOPK, k=20)
+    prev = [set() for _ in range(4)]
+    for P in (1, 2, 5, 11, nb):
+        r = oracle.coarse_attn(q, K, V, block=16, n_blocks=P, k=20)
+        for h in range(4):
+            assert one["ids"][h].tolist() == ex0["ids"][h].tolist()
+            assert len(r["blocks"][h]) == min(P, nb) and prev[h] <= set(r["blocks"][h].tolist())
+            prev[h] = set(r["blocks"][h].tolist())
+    for h in range(4):
+        s = exact["scores"][h]
+        kth = np.sort(s)[-20]
+        u = allb["u"][h]
+        P = int((u >= kth).sum())
+        r = oracle.coarse_attn(q, K, V, block=16, n_blocks=P, k=20)
+        assert r["ids"][h].tolist() == ex0["ids"][h].tolist()
+
+
+def test_coarse_prefix_uses_the_stored_index():
+    """Sec. 7.1 flexible context reuse on the coarse index: the query sees a prefix through the index of the
+    stored context, so the half-visible block keeps the representatives of all its stored tokens; whole
+    blocks behind the prefix take no part, and hidden tokens are never returned."""
+    w, q, K, V = _small(23, n=160, hq=2, hk=1, d=16, dtype="f32")
+    Kp = K.copy()
+    Kp[100:112] *= 50.0            # hidden tokens of the half-visible block 6 (tokens 96..111; 100 are visible)
+    r = oracle.coarse_attn(q, Kp, V, block=16, n_blocks=3, k=8, n_visible=100)
+    lo, hi = oracle.block_reps(Kp, 0, 16)
+    for h in range(2):
+        assert r["u"][h].shape == (7,)                                        # blocks 0..6 only
+        np.testing.assert_array_equal(r["u"][h], oracle.block_scores(q[h], lo, hi)[:7])
+        assert 6 in r["blocks"][h]                                            # its (hidden) outliers raise the bound
+        assert r["ids"][h].max() < 100
+        np.testing.assert_array_equal(r["ids"][h], oracle.select_topk_in_blocks(
+            oracle.scores(q[h], Kp[:100], 0), 16, r["blocks"][h], 8))
+    with pytest.raises(ValueError):
+        oracle.coarse_attn(q, K, V, block=16, n_blocks=0, k=8)
