@@ -111,6 +111,17 @@ int alaya_destroy_cache(alaya_cache *c);
 int alaya_bind_scratch(alaya_cache *c, void *scratch, size_t scratch_bytes);
 
 /*
+ * The coarse-grained index (Sec. 6.2 "Query Optimizer", index types; Table 4): every page of 64 adjacent
+ * tokens is represented, per KV head, by two vectors - the channel-wise minimum and maximum of its keys.
+ * rep_pool: DEVICE, >= alaya_rep_bytes(cfg), 256-byte aligned, laid out [phys_page][kv_head][2][head_dim]
+ * in the cache dtype; the library's while the cache lives.  Bind it while every sequence is empty: from
+ * then on each append also brings the representatives of the pages it touches up to date, and
+ * alaya_sparse_attn accepts coarse_pages.  A cache without it answers exact queries only.
+ */
+size_t alaya_rep_bytes(const alaya_cache_config *cfg);
+int alaya_bind_reps(alaya_cache *c, void *rep_pool, size_t rep_bytes);
+
+/*
  * Session.update: append t tokens to sequence `seq`.
  * k, v: DEVICE, [t][n_kv_heads][head_dim] of the cache dtype (token-major, as a model emits them).
  * Pages are taken from the pool as needed; if it runs out: ALAYA_E_NOMEM and nothing changes.
@@ -148,6 +159,11 @@ typedef struct {
     int64_t ids_stride;    /* capacity per head of out_ids                                      */
     const int32_t *n_visible; /* HOST [B], optional: request b sees only its first n_visible[b]
                                  cached tokens (1 .. cached length); NULL = all of them         */
+    const int32_t *coarse_pages; /* HOST [B], optional, ALAYA_TOPK only: answer through the coarse index -
+                                 request b's query runs over the tokens of its coarse_pages[b] >= 1
+                                 best pages only (see alaya_bind_reps); NULL = the exact query   */
+    int32_t *out_pages;    /* DEVICE, optional [B][n_q_heads][pages_stride]: the chosen pages    */
+    int64_t pages_stride;  /* capacity per head of out_pages                                     */
 } alaya_sparse_params;
 
 /*
@@ -162,6 +178,12 @@ typedef struct {
  * out_ids / out_counts cover window and retrieved tokens alike.
  * Prefix (Sec. 7.1 "Flexible Context Reuse"): with n_visible set, the query runs as if the sequence
  * ended after n_visible[b] tokens; "last" window tokens are then the last visible ones.
+ * Coarse index (Sec. 6.2; Table 4: top-k and filter queries): with coarse_pages set, each query head first
+ * scores every page by u = sum_c max(q_c * lo_c, q_c * hi_c) over the page's two representative vectors - an
+ * upper bound of every inner product in the page -, keeps the coarse_pages[b] pages with the largest u (equal
+ * u: the smaller page) and runs the top-k query over their tokens only (k larger than they hold means all of
+ * them; window tokens are attended wherever they are).  Only those pages' keys are read.  With n_visible the
+ * pages that hold a visible token take part, each with the representatives of all its cached tokens.
  * A request may see at most 131072 pages (8388608 tokens); a longer one is refused with
  * ALAYA_E_INVAL (alaya_full_attn has no such limit).
  * Selection runs on raw fp32 inner products (bf16 products are exact in fp32; accumulation is fp32).

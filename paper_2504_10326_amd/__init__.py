@@ -27,7 +27,8 @@ KERNEL_SLOTS = ("score", "select", "attend", "combine", "full_partial", "append"
 
 # include/alaya.h
 EXPORTS = (
-    "alaya_pool_bytes", "alaya_workspace_bytes", "alaya_scratch_bytes", "alaya_create_cache", "alaya_bind_scratch",
+    "alaya_pool_bytes", "alaya_workspace_bytes", "alaya_scratch_bytes", "alaya_rep_bytes", "alaya_create_cache",
+    "alaya_bind_scratch", "alaya_bind_reps",
     "alaya_destroy_cache", "alaya_append_kv", "alaya_append_kv_step", "alaya_seq_len", "alaya_reset_seq",
     "alaya_sparse_attn", "alaya_decode_step", "alaya_sparse_attn_static", "alaya_full_attn", "alaya_poll_status",
     "alaya_last_error",
@@ -62,6 +63,8 @@ class SparseParams(ctypes.Structure):
         ("scale", ctypes.c_float), ("window_last", ctypes.c_int32),
         ("out_ids", ctypes.c_void_p), ("out_counts", ctypes.c_void_p), ("ids_stride", ctypes.c_int64),
         ("n_visible", ctypes.POINTER(ctypes.c_int32)),
+        ("coarse_pages", ctypes.POINTER(ctypes.c_int32)), ("out_pages", ctypes.c_void_p),
+        ("pages_stride", ctypes.c_int64),
     ]
 
 
@@ -82,6 +85,8 @@ def lib() -> ctypes.CDLL:
         L.alaya_workspace_bytes.argtypes = [cfgp]; L.alaya_workspace_bytes.restype = sz
         L.alaya_scratch_bytes.argtypes = [cfgp]; L.alaya_scratch_bytes.restype = sz
         L.alaya_bind_scratch.argtypes = [vp, vp, sz]; L.alaya_bind_scratch.restype = i32
+        L.alaya_rep_bytes.argtypes = [cfgp]; L.alaya_rep_bytes.restype = sz
+        L.alaya_bind_reps.argtypes = [vp, vp, sz]; L.alaya_bind_reps.restype = i32
         L.alaya_create_cache.argtypes = [ctypes.POINTER(vp), cfgp, vp, vp, ctypes.POINTER(ctypes.c_int32), vp, sz]
         L.alaya_create_cache.restype = i32
         L.alaya_destroy_cache.argtypes = [vp]; L.alaya_destroy_cache.restype = i32
@@ -171,6 +176,14 @@ def alaya_bind_scratch(handle: int, scratch, scratch_bytes: int) -> None:
     _check(lib().alaya_bind_scratch(handle, _ptr(scratch), scratch_bytes))
 
 
+def alaya_rep_bytes(cfg: CacheConfig) -> int:
+    return lib().alaya_rep_bytes(ctypes.byref(cfg))
+
+
+def alaya_bind_reps(handle: int, rep_pool, rep_bytes: int) -> None:
+    _check(lib().alaya_bind_reps(handle, _ptr(rep_pool), rep_bytes))
+
+
 def alaya_create_cache(cfg: CacheConfig, k_pool, v_pool, phys_page_order: Optional[Sequence[int]],
                        workspace, workspace_bytes: int) -> int:
     h = ctypes.c_void_p()
@@ -209,7 +222,8 @@ def alaya_sparse_attn(handle: int, seqs: Sequence[int], n_q_heads: int, q, mode:
                       topk: Optional[Sequence[int]], beta: Optional[Sequence[float]], scale: float, out,
                       out_ids=None, out_counts=None, ids_stride: int = 0, stream=0,
                       window: Tuple[int, int] = (0, 0), n_visible: Optional[Sequence[int]] = None,
-                      step_kv=None, static_scratch: bool = False) -> None:
+                      step_kv=None, static_scratch: bool = False, coarse_pages: Optional[Sequence[int]] = None,
+                      out_pages=None, pages_stride: int = 0) -> None:
     """step_kv = (k, v): make the call an alaya_decode_step that first appends one token per sequence.
     static_scratch: call alaya_sparse_attn_static (the library's own scratch array, nothing allocated)."""
     p = SparseParams()
@@ -224,6 +238,10 @@ def alaya_sparse_attn(handle: int, seqs: Sequence[int], n_q_heads: int, q, mode:
     p.out_ids = _ptr(out_ids)
     p.out_counts = _ptr(out_counts)
     p.ids_stride = ids_stride
+    cpg = _i32_array(coarse_pages)
+    p.coarse_pages = ctypes.cast(cpg, ctypes.POINTER(ctypes.c_int32)) if cpg is not None else None
+    p.out_pages = _ptr(out_pages)
+    p.pages_stride = pages_stride
     sq = _i32_array(seqs)
     if step_kv is not None:
         _check(lib().alaya_decode_step(handle, sq, len(seqs), n_q_heads, _ptr(step_kv[0]), _ptr(step_kv[1]), _ptr(q),
@@ -266,7 +284,8 @@ class Cache:
 
     def __init__(self, n_q_heads: int, n_kv_heads: int, head_dim: int, dtype: str, max_seqs: int,
                  max_batch: int, max_tokens_per_seq: int, max_batch_tokens: int, n_phys_pages: int,
-                 phys_page_order: Optional[Sequence[int]] = None, device: str = "cuda:0", scratch=None):
+                 phys_page_order: Optional[Sequence[int]] = None, device: str = "cuda:0", scratch=None,
+                 coarse_index: bool = False):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU visible: the sparse-attention path has no CPU fallback")
@@ -288,6 +307,10 @@ class Cache:
         self.scratch_bytes = sc
         self.handle = alaya_create_cache(cfg, self.k_pool, self.v_pool, phys_page_order, self.workspace, ws)
         alaya_bind_scratch(self.handle, self.scratch, self.scratch.numel())
+        self.rep_pool = None
+        if coarse_index:      # block representatives (Sec. 6.2, coarse-grained index), kept up to date by every append
+            self.rep_pool = torch.empty(alaya_rep_bytes(cfg), dtype=torch.uint8, device=self.device)
+            alaya_bind_reps(self.handle, self.rep_pool, self.rep_pool.numel())
 
     def close(self) -> None:
         if getattr(self, "handle", None):
@@ -341,11 +364,13 @@ class Cache:
     def sparse_attn(self, seqs: Sequence[int], q, mode: int, topk=None, beta=None, scale: float = 0.0,
                     ids_stride: int = 0, out=None, stream=None, want_counts: bool = False,
                     window: Tuple[int, int] = (0, 0), n_visible: Optional[Sequence[int]] = None, _step_kv=None,
-                    static_scratch: bool = False):
+                    static_scratch: bool = False, coarse_pages: Optional[Sequence[int]] = None, pages_stride: int = 0):
         """Returns out [B][Hq][d] fp32, or (out, ids [B][Hq][ids_stride] int32, counts [B][Hq] int32) when
         ids_stride > 0, or (out, counts) when only want_counts is set.  window = (first, last) tokens
         that are always attended; n_visible[b] = the prefix of request b that the query sees.
-        static_scratch: through alaya_sparse_attn_static (the library's own scratch array)."""
+        static_scratch: through alaya_sparse_attn_static (the library's own scratch array).
+        coarse_pages[b]: answer through the coarse index, over the tokens of that many best pages per head;
+        with pages_stride > 0 the chosen pages come back too: (out, ids, counts, pages [B][Hq][pages_stride])."""
         if out is None:
             out = self._q_out(seqs, q)
         ids = counts = None
@@ -354,9 +379,16 @@ class Cache:
                                   device=self.device)
         if ids_stride > 0 or want_counts:
             counts = self.torch.zeros((len(seqs), self.cfg.n_q_heads), dtype=self.torch.int32, device=self.device)
+        pages = None
+        if pages_stride > 0:
+            pages = self.torch.full((len(seqs), self.cfg.n_q_heads, pages_stride), -1, dtype=self.torch.int32,
+                                    device=self.device)
         alaya_sparse_attn(self.handle, seqs, self.cfg.n_q_heads, q, mode, topk, beta, scale, out, ids, counts,
                           ids_stride, _stream(stream), window, n_visible, step_kv=_step_kv,
-                          static_scratch=static_scratch)
+                          static_scratch=static_scratch, coarse_pages=coarse_pages, out_pages=pages,
+                          pages_stride=pages_stride)
+        if pages is not None:
+            return out, ids, counts, pages
         if ids is not None:
             return out, ids, counts
         return (out, counts) if want_counts else out

@@ -42,9 +42,10 @@ struct ReqDesc {
                            // whose tokens seed the maximum (Sec. 7.1); a decode step, whose newest token that
                            // pass writes.  Only the every-S-th pages enter top-k's histogram.
     int32_t hist_cap;      // top-k: what one sample-pass workgroup (four sampled pages) may add to one bucket, at most
-    int32_t pad1;
+    int32_t pm_stride;     // coarse index: bytes between the KV heads' rows of this request's page mask
+    int64_t pm_off;        // coarse index: first byte of this request's page mask
 };
-static_assert(sizeof(ReqDesc) == 80, "ReqDesc layout");
+static_assert(sizeof(ReqDesc) == 88, "ReqDesc layout");
 
 // How the kernels get at the request descriptors.  A call of one request carries its descriptor in
 // the kernel arguments, which saves the host-to-device copy (a 4 us blit ahead of the first kernel of
@@ -101,6 +102,7 @@ struct DeviceViews {
     int32_t *counts;           // [max_batch * n_q_heads]: size of the selected set
     float *partials;           // attend / full-attention partial results
     int32_t *status;           // device status word
+    const uint8_t *pmask;      // coarse index: one byte per (KV head, page), bit g = head g of the group chose the page
 };
 
 struct Shape {
@@ -127,12 +129,37 @@ hipError_t launch_tau(const Shape &sh, const DeviceViews &dv, int B, int mode, h
 // Main pass: every page against dv.tau (repair = false), or - only for the workgroups with a head marked
 // in dv.fail - against dv.tau_safe for the marked heads (repair = true).  cp = pages per wavefront.
 // ev0 / ev1: optional events that take the kernel's own begin and end times.
+// coarse: only the pages marked in dv.pmask (and those that hold window tokens) are read, and a head keeps
+// only tokens of pages it chose itself.
 hipError_t launch_score(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles, int cp,
-                        bool repair, int mode, hipStream_t st, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
+                        bool repair, int mode, bool coarse, hipStream_t st, hipEvent_t ev0 = nullptr,
+                        hipEvent_t ev1 = nullptr);
 
 // Selection: one workgroup per (request, head).  redo: only the heads marked in dv.fail (after the repair pass).
-hipError_t launch_select(const Shape &sh, const DeviceViews &dv, int B, int mode, bool redo, int batch_blocks,
-                         int32_t *out_ids, int32_t *out_counts, int64_t ids_stride, hipStream_t st);
+// What is selected from, and where the result goes, may differ from the views' own (the page level of the
+// coarse index runs the same kernel over block scores).
+struct SelectIO {
+    DescArgs desc;          // descriptors of this level
+    const uint2 *blocks;    // survivor blocks
+    int64_t block_stride;
+    int32_t *ids;           // selected ids, [head][head_stride] at score_off
+    float *scores;          // their scores
+    int32_t *rows;          // their V-pool rows, or null (not wanted)
+    int32_t *counts;        // [request * head]
+    float *head_M;          // [request * head]
+    bool short_ok;          // top-k: fewer than k candidates is no failure, all of them are taken
+};
+hipError_t launch_select(const Shape &sh, const DeviceViews &dv, const SelectIO &io, int B, int mode, bool redo,
+                         int batch_blocks, int32_t *out_ids, int32_t *out_counts, int64_t ids_stride, hipStream_t st);
+
+// Coarse-grained index (coarse.hip).
+hipError_t launch_reps_range(const Shape &sh, const int32_t *pt_row, const void *k_pool, void *rep_pool, int first,
+                             int count, int64_t n_new, hipStream_t st);
+hipError_t launch_reps_step(const Shape &sh, const DeviceViews &dv, void *rep_pool, int B, hipStream_t st);
+hipError_t launch_coarse_score(const Shape &sh, const DeviceViews &dv, const DescArgs &pdesc, int B, const void *q,
+                               const void *rep_pool, int total_tiles, int64_t block_stride, hipStream_t st);
+hipError_t launch_page_mask(const Shape &sh, const DeviceViews &dv, const DescArgs &pdesc, int B, const int32_t *pg_ids,
+                            const int32_t *pg_counts, uint32_t *pmask, hipStream_t st);
 
 hipError_t launch_attend(const Shape &sh, const DeviceViews &dv, int B, float scale, int splits, hipStream_t st);
 

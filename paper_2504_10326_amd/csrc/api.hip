@@ -16,7 +16,7 @@
 
 using namespace alaya;
 
-static_assert(sizeof(alaya_cache_config) == 56 && sizeof(alaya_sparse_params) == 64, "C ABI struct layout");
+static_assert(sizeof(alaya_cache_config) == 56 && sizeof(alaya_sparse_params) == 88, "C ABI struct layout");
 
 namespace {
 
@@ -90,7 +90,9 @@ Layout make_layout(const alaya_cache_config &c)
 // statistics, partial results.  Sized by the largest call it must serve.
 struct Scratch {
     size_t desc, blocks, sel_scores, sel_ids, sel_rows, zero_begin, hist, head_maxkey, sample_max, fail, zero_end, tau,
-        tau_safe, head_M, counts, partials, status, dbg_total, total;
+        tau_safe, head_M, counts, partials, status, dbg_total, pg_ids, pg_scores, pg_counts, pg_M, pmask, total;
+    int64_t pg_elems;    // capacity of the chosen-page arrays of the coarse index
+    int64_t pmask_bytes; // capacity of its page mask
     int64_t block_words; // capacity of the survivor blocks, 8-byte words
     int64_t sel_elems;   // capacity of each selected-token array
     int64_t max_tiles;   // full-attention tiles
@@ -116,7 +118,7 @@ Scratch make_scratch(int n_q_heads, int n_kv_heads, int head_dim, int64_t max_ba
     const size_t heads = (size_t)max_batch * n_q_heads;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
-    S.desc = take((size_t)max_batch * sizeof(ReqDesc));
+    S.desc = take((size_t)max_batch * 2 * sizeof(ReqDesc)); // token-level and page-level descriptors
     S.blocks = take((size_t)S.block_words * sizeof(uint2));
     S.sel_scores = take((size_t)S.sel_elems * sizeof(float));
     S.sel_ids = take((size_t)S.sel_elems * sizeof(int32_t));
@@ -136,6 +138,14 @@ Scratch make_scratch(int n_q_heads, int n_kv_heads, int head_dim, int64_t max_ba
     S.partials = take((sparse_slots > full_slots ? sparse_slots : full_slots) * (head_dim + 2) * sizeof(float));
     S.status = take(256);
     S.dbg_total = take(256);
+    // coarse index: the chosen pages of every head, and one byte per (KV head, page)
+    S.pg_elems = (int64_t)n_q_heads * (pages + (int64_t)kPageTokens * max_batch);
+    S.pg_ids = take((size_t)S.pg_elems * sizeof(int32_t));
+    S.pg_scores = take((size_t)S.pg_elems * sizeof(float));
+    S.pg_counts = take(heads * sizeof(int32_t));
+    S.pg_M = take(heads * sizeof(float));
+    S.pmask_bytes = (int64_t)n_kv_heads * (pages + 4 * max_batch);
+    S.pmask = take((size_t)S.pmask_bytes);
     S.total = o;
     return S;
 }
@@ -149,6 +159,7 @@ struct alaya_cache {
     char *ws;                        // the cache's own device memory (page table)
     char *scratch_mem;               // bound scratch memory, or null
     void *k_pool, *v_pool;
+    void *rep_pool;                  // block representatives of the coarse index, or null
     DeviceViews dv;
     // host bookkeeping
     std::vector<int32_t> free_pages; // stack: back() is handed out next
@@ -237,6 +248,7 @@ void bind_views(DeviceViews &dv, const Scratch &S, char *base)
     dv.counts = (int32_t *)(base + S.counts);
     dv.partials = (float *)(base + S.partials);
     dv.status = (int32_t *)(base + S.status);
+    dv.pmask = (const uint8_t *)(base + S.pmask);
 }
 
 // Clears what must be zero before a scratch area's first use: statistics, repair marks, status.
@@ -269,22 +281,23 @@ int ring_acquire(alaya_cache *c, int B, ReqDesc **slot, int *idx)
         hipError_t e = hipEventCreateWithFlags(&c->ring_ev[i], hipEventDisableTiming);
         if (e != hipSuccess) { c->ring_ev[i] = nullptr; return fail_hip(e, "hipEventCreate"); }
     }
-    *slot = c->h_desc + (size_t)i * c->cfg.max_batch;
+    *slot = c->h_desc + (size_t)i * 2 * c->cfg.max_batch; // room for two sets of descriptors
     *idx = i;
     return ALAYA_OK;
 }
 
 // Hands the descriptors in ring slot idx to the kernels launched after this: in their arguments for a
 // call of one request, through an asynchronous copy into `dev` (device memory) otherwise.
-int ring_publish(alaya_cache *c, DeviceViews &dv, int idx, int B, hipStream_t st)
+int ring_publish(alaya_cache *c, DeviceViews &dv, int idx, int B, hipStream_t st, bool two_sets = false)
 {
-    const ReqDesc *src = c->h_desc + (size_t)idx * c->cfg.max_batch;
+    const ReqDesc *src = c->h_desc + (size_t)idx * 2 * c->cfg.max_batch;
     dv.desc.n = B;
     if (B <= kInlineDescs) {
         dv.desc.in = src[0];
         return ALAYA_OK; // the slot is free again at once
     }
-    hipError_t e = hipMemcpyAsync((void *)dv.desc.mem, src, (size_t)B * sizeof(ReqDesc), hipMemcpyHostToDevice, st);
+    hipError_t e = hipMemcpyAsync((void *)dv.desc.mem, src, (size_t)B * (two_sets ? 2 : 1) * sizeof(ReqDesc),
+                                  hipMemcpyHostToDevice, st);
     if (e != hipSuccess) return fail_hip(e, "descriptor copy");
     e = hipEventRecord(c->ring_ev[idx], st);
     if (e != hipSuccess) return fail_hip(e, "hipEventRecord");
@@ -378,6 +391,7 @@ int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k
     c->scratch_mem = nullptr;
     c->k_pool = k_pool;
     c->v_pool = v_pool;
+    c->rep_pool = nullptr;
     c->dv = DeviceViews{};
     c->dv.fused = FusedAppend{nullptr, nullptr, nullptr, nullptr};
     c->dv.page_table = (const int32_t *)(c->ws + L.page_table);
@@ -386,7 +400,7 @@ int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k
     c->free_pages.assign(order.rbegin(), order.rend()); // back() == first page of the order
     c->seq_len.assign((size_t)cfg->max_seqs, 0);
     const size_t pt_bytes = (size_t)L.mpps * cfg->max_seqs * sizeof(int32_t);
-    const size_t ring_bytes = (size_t)kRing * cfg->max_batch * sizeof(ReqDesc);
+    const size_t ring_bytes = (size_t)kRing * 2 * cfg->max_batch * sizeof(ReqDesc);
     // Pinned host memory lets the table and descriptor copies run asynchronously.  Without a device
     // (host-only use: argument and allocator checks) plain memory serves.
     void *p = nullptr;
@@ -442,6 +456,25 @@ int alaya_bind_scratch(alaya_cache *c, void *scratch, size_t scratch_bytes)
     c->scratch_mem = (char *)scratch;
     c->scratch_ready = false;
     bind_views(c->dv, S, c->scratch_mem);
+    return ALAYA_OK;
+}
+
+size_t alaya_rep_bytes(const alaya_cache_config *cfg)
+{
+    if (!cfg_ok(cfg)) return 0;
+    return (size_t)cfg->n_phys_pages * cfg->n_kv_heads * 2 * cfg->head_dim * (cfg->dtype == ALAYA_BF16 ? 2 : 4);
+}
+
+int alaya_bind_reps(alaya_cache *c, void *rep_pool, size_t rep_bytes)
+{
+    if (!c) return fail(ALAYA_E_INVAL, "null cache handle");
+    if (!rep_pool) return fail(ALAYA_E_INVAL, "null representative pool");
+    if ((uintptr_t)rep_pool & 255) return fail(ALAYA_E_INVAL, "representative pool must be 256-byte aligned");
+    if (rep_bytes < alaya_rep_bytes(&c->cfg))
+        return fail(ALAYA_E_NOMEM, "representative pool has %zu bytes, %zu needed", rep_bytes, alaya_rep_bytes(&c->cfg));
+    for (int64_t n : c->seq_len)
+        if (n > 0) return fail(ALAYA_E_INVAL, "bind the representative pool while every sequence is empty");
+    c->rep_pool = rep_pool;
     return ALAYA_OK;
 }
 
@@ -509,6 +542,11 @@ int alaya_append_kv(alaya_cache *c, int seq, const void *k, const void *v, int64
         e = launch_append(sh, d_row, c->k_pool, c->v_pool, k, v, n_old, t, st);
     }
     if (e != hipSuccess) { rollback(); return fail_hip(e, "append launch"); }
+    if (c->rep_pool) { // coarse index: the representatives of the pages this append touched
+        const int first = (int)(n_old / kPageTokens);
+        e = launch_reps_range(sh, d_row, c->k_pool, c->rep_pool, first, (int)(want - first), n_new, st);
+        if (e != hipSuccess) { rollback(); return fail_hip(e, "representative update launch"); }
+    }
     c->seq_len[(size_t)seq] = n_new;
     return ALAYA_OK;
 }
@@ -581,6 +619,7 @@ int step_launch_append(alaya_cache *c, const int32_t *seqs, int B, const void *k
     {
         Timed tm(c, 5, st);
         e = launch_append_step(sh, c->dv, c->k_pool, c->v_pool, k, v, B, st);
+        if (e == hipSuccess && c->rep_pool) e = launch_reps_step(sh, c->dv, c->rep_pool, B, st);
     }
     if (e != hipSuccess) return fail_hip(e, "append launch");
     return ALAYA_OK;
@@ -620,7 +659,9 @@ int alaya_decode_step(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
     if (!c) return fail(ALAYA_E_INVAL, "null cache handle");
     if (!seqs || !k || !v) return fail(ALAYA_E_INVAL, "null seqs, k or v");
     if (B <= 0 || B > c->cfg.max_batch) return fail(ALAYA_E_INVAL, "batch %d outside 1..%d", B, c->cfg.max_batch);
-    if (p && p->n_visible) { // the new token may lie outside what the query sees: nothing to fuse
+    // (with a visible prefix the new token may lie outside what the query sees; with a coarse index the
+    // append also updates the page's representatives: nothing to fuse, the two calls are made in turn)
+    if ((p && p->n_visible) || c->rep_pool) {
         const int rc = alaya_append_kv_step(c, seqs, B, k, v, stream);
         return rc != ALAYA_OK ? rc : alaya_sparse_attn(c, seqs, B, n_q_heads, q, p, out, stream);
     }
@@ -684,6 +725,16 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
             if (p->n_visible[b] <= 0 || p->n_visible[b] > c->seq_len[(size_t)seqs[b]])
                 return fail(ALAYA_E_INVAL, "request %d: n_visible = %d outside 1..%lld", b, p->n_visible[b],
                             (long long)c->seq_len[(size_t)seqs[b]]);
+    const bool coarse = p->coarse_pages != nullptr;
+    if (coarse) {
+        if (p->mode != ALAYA_TOPK) return fail(ALAYA_E_INVAL, "the coarse index answers top-k queries only");
+        if (!c->rep_pool) return fail(ALAYA_E_INVAL, "no representative pool bound to this cache (alaya_bind_reps)");
+        for (int b = 0; b < B; ++b)
+            if (p->coarse_pages[b] <= 0)
+                return fail(ALAYA_E_INVAL, "request %d: coarse_pages = %d must be positive", b, p->coarse_pages[b]);
+        if (p->out_pages && p->pages_stride <= 0) return fail(ALAYA_E_INVAL, "out_pages given with pages_stride <= 0");
+        if (fused_k) return fail(ALAYA_E_INVAL, "internal: a fused append cannot go with the coarse index");
+    }
     if (!use && !c->scratch_mem) return fail(ALAYA_E_INVAL, "no scratch memory bound to this cache (alaya_bind_scratch)");
     DeviceViews &dv = use ? *use->dv : c->dv;
     const Scratch &S = use ? *use->S : c->S;
@@ -723,7 +774,9 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
     int slot;
     rc = ring_acquire(c, B, &hd, &slot);
     if (rc != ALAYA_OK) return rc;
-    int tiles = 0, tiles_b = 0;
+    int tiles = 0, tiles_b = 0, tiles_p = 0;
+    int64_t pg_off = 0, pm_off = 0;
+    ReqDesc *hp = hd + B; // page-level descriptors of the coarse index (the ring slot holds max_batch >= B more)
     const bool estimate = c->estimate_mode >= 0;
     bool any_est = false;
     int64_t pages_a = 0, pages_all = 0;
@@ -752,7 +805,7 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
         // (guaranteed bound).  Powers of two, at most 32.
         int S = 1;
         d.k_est = 0;
-        if (!c->tune_noprune && pages >= 4) {
+        if (!c->tune_noprune && pages >= 4 && !coarse) { // (the coarse index cuts the candidates down itself)
             // (never when top-k takes every token outside the window: nothing checks the bound then)
             if (p->mode == ALAYA_TOPK && estimate && d.k >= 512 && d.k < n_out && pages >= 64) {
                 // Estimated bound: a 1-in-S sample holds about mu = k / S of the k best
@@ -799,6 +852,24 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
         d.ntiles_b = (int32_t)((d.n_pages + (int64_t)kScoreWaves * cp - 1) / ((int64_t)kScoreWaves * cp));
         tiles += (n_a + kScoreWaves - 1) / kScoreWaves; // one page per wavefront
         tiles_b += d.ntiles_b;
+        if (coarse) {
+            d.pm_off = pm_off;
+            d.pm_stride = (int32_t)((pages + 3) / 4 * 4);
+            pm_off += (int64_t)c->cfg.n_kv_heads * d.pm_stride;
+            ReqDesc &e = hp[b]; // the same request seen as a sequence of pages: n, k count pages
+            std::memset(&e, 0, sizeof e);
+            e.pt_off = d.pt_off;
+            e.n = (int32_t)pages;
+            e.n_pages = (int32_t)((pages + kPageTokens - 1) / kPageTokens);
+            e.k = (int32_t)((int64_t)p->coarse_pages[b] < pages ? p->coarse_pages[b] : pages);
+            e.head_stride = (int32_t)(pages + kPageTokens);
+            e.score_off = pg_off;
+            e.sample_stride = 1;
+            e.tileb_start = tiles_p;
+            e.ntiles_b = (int32_t)((pages + 255) / 256);
+            tiles_p += e.ntiles_b;
+            pg_off += (int64_t)n_q_heads * e.head_stride;
+        }
         pages_all += pages;
         off += (int64_t)n_q_heads * d.head_stride;
     }
@@ -806,11 +877,15 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
     if (off > S.sel_elems) return fail(ALAYA_E_NOMEM, "scratch too small for the selected-token arrays");
     if ((int64_t)tiles_b * c->cfg.n_kv_heads * block_stride > S.block_words)
         return fail(ALAYA_E_NOMEM, "scratch too small for the survivor blocks");
+    const int64_t block_stride_p = kBlockHdr + (int64_t)256 * G; // page level: a block holds the scores of 256 pages
+    if (coarse && ((int64_t)tiles_p * c->cfg.n_kv_heads * block_stride_p > S.block_words || pg_off > S.pg_elems ||
+                   pm_off > S.pmask_bytes))
+        return fail(ALAYA_E_NOMEM, "scratch too small for the coarse index");
     if (!use) {
         rc = need_scratch(c, st);
         if (rc != ALAYA_OK) return rc;
     }
-    rc = ring_publish(c, dv, slot, B, st);
+    rc = ring_publish(c, dv, slot, B, st, coarse);
     if (rc != ALAYA_OK) return rc;
     dv.block_stride = block_stride;
     if (!use) {
@@ -825,6 +900,24 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
     // (a launch that fails below may leave the statistics half-filled: scratch_ready is dropped so that
     // the next call clears them again)
     hipError_t e;
+    char *sbase = (char *)dv.sel_scores - S.sel_scores; // the scratch area the views point into
+    if (coarse) {
+        // Coarse index: block scores of every page -> the best pages of every head (the selection kernel,
+        // over pages) -> one byte per (KV head, page) for the main pass.
+        Timed tm(c, 6, st);
+        DescArgs pd = dv.desc;
+        pd.mem = dv.desc.mem + B;
+        pd.in = hp[0];
+        int32_t *pg_ids = (int32_t *)(sbase + S.pg_ids), *pg_counts = (int32_t *)(sbase + S.pg_counts);
+        e = launch_fill_u32((uint32_t *)(sbase + S.pmask), (size_t)((pm_off + 3) / 4), 0u, st);
+        if (e == hipSuccess) e = launch_coarse_score(sh, dv, pd, B, q, c->rep_pool, tiles_p, block_stride_p, st);
+        const SelectIO pio{pd, dv.blocks, block_stride_p, pg_ids, (float *)(sbase + S.pg_scores), nullptr, pg_counts,
+                           (float *)(sbase + S.pg_M), false};
+        if (e == hipSuccess)
+            e = launch_select(sh, dv, pio, B, ALAYA_TOPK, false, c->tune_batch, p->out_pages, nullptr, p->pages_stride, st);
+        if (e == hipSuccess) e = launch_page_mask(sh, dv, pd, B, pg_ids, pg_counts, (uint32_t *)(sbase + S.pmask), st);
+        if (e != hipSuccess) { c->scratch_ready = false; return fail_hip(e, "coarse index launch"); }
+    }
     {
         Timed tm(c, 6, st);
         if (fused_k) dv.fused = FusedAppend{(uint4 *)c->k_pool, (uint4 *)c->v_pool, (const uint4 *)fused_k, (const uint4 *)fused_v};
@@ -836,16 +929,18 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
     if (e != hipSuccess) { c->scratch_ready = false; return fail_hip(e, "sample scoring launch"); }
     {
         Timed tm(c, 0, st, true); // the roofline kernel: timed by its own dispatch
-        e = launch_score(sh, dv, B, q, tiles_b, cp, false, p->mode, st, tm.begin(), tm.end());
+        e = launch_score(sh, dv, B, q, tiles_b, cp, false, p->mode, coarse, st, tm.begin(), tm.end());
     }
     if (e != hipSuccess) { c->scratch_ready = false; return fail_hip(e, "score launch"); }
     {
         Timed tm(c, 1, st);
-        e = launch_select(sh, dv, B, p->mode, false, c->tune_batch, p->out_ids, p->out_counts, p->ids_stride, st);
+        const SelectIO io{dv.desc, dv.blocks, block_stride, dv.sel_ids, dv.sel_scores, dv.sel_rows, dv.counts, dv.head_M,
+                          coarse};
+        e = launch_select(sh, dv, io, B, p->mode, false, c->tune_batch, p->out_ids, p->out_counts, p->ids_stride, st);
         // repair of the heads whose estimated bound lost tokens (normally none: both launches are idle)
-        if (e == hipSuccess && any_est) e = launch_score(sh, dv, B, q, tiles_b, cp, true, p->mode, st);
+        if (e == hipSuccess && any_est) e = launch_score(sh, dv, B, q, tiles_b, cp, true, p->mode, false, st);
         if (e == hipSuccess && any_est)
-            e = launch_select(sh, dv, B, p->mode, true, c->tune_batch, p->out_ids, p->out_counts, p->ids_stride, st);
+            e = launch_select(sh, dv, io, B, p->mode, true, c->tune_batch, p->out_ids, p->out_counts, p->ids_stride, st);
     }
     if (e != hipSuccess) { c->scratch_ready = false; return fail_hip(e, "select launch"); }
     {

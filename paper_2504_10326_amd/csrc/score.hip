@@ -385,7 +385,9 @@ hipError_t launch_tau(const Shape &sh, const DeviceViews &dv, int B, int mode, h
 // REPAIR: only for the groups with a head marked in `fail` - those whose estimated bound turned out to
 // lie above the true threshold - and for those heads against the guaranteed bound; the whole block is
 // written again (the other heads' parts come out as before).
-template <int DT, int D, int G, int CP, bool REPAIR>
+// COARSE (coarse-grained index): only the pages that some head of the group chose (dv.pmask), and the pages
+// that hold window tokens, are read; a head keeps a token only if it chose the token's page itself.
+template <int DT, int D, int G, int CP, bool REPAIR, bool COARSE>
 __device__ __forceinline__ void main_block(const int block, const Descs &desc, int B,
                                            const int32_t *__restrict__ page_table,
                                            const uint32_t *__restrict__ qw, const uint4 *__restrict__ k_pool,
@@ -393,7 +395,7 @@ __device__ __forceinline__ void main_block(const int block, const Descs &desc, i
                                            const uint32_t *__restrict__ tau_in,
                                            const uint32_t *__restrict__ tau_safe,
                                            const uint32_t *__restrict__ fail, int H_kv, int mode,
-                                           uint32_t *head_maxkey)
+                                           uint32_t *head_maxkey, const uint8_t *__restrict__ pmask)
 {
     constexpr int NC = D * (DT == 0 ? 2 : 4) / 16;
     constexpr int QW = D * (DT == 0 ? 2 : 4) / 4;
@@ -433,6 +435,12 @@ __device__ __forceinline__ void main_block(const int block, const Descs &desc, i
     for (int i = 0; i < CP; ++i) {
         const int p = p0 + i;
         if (p >= dsc.n_pages) break;
+        uint32_t chosen = 0xFFu; // bit g: head g takes tokens of this page
+        if (COARSE) {
+            chosen = pmask[(size_t)dsc.pm_off + (size_t)kvh * dsc.pm_stride + p];
+            const bool holds_window = p * kPageTokens < dsc.w0 || (dsc.w1 > 0 && (p + 1) * kPageTokens > dsc.n - dsc.w1);
+            if (chosen == 0u && !holds_window) continue; // (wave-uniform) the page's keys are not read
+        }
         const int phys = page_table[dsc.pt_off + p];
         const uint4 *base = k_pool + ((size_t)phys * H_kv + kvh) * (size_t)(NC * 64) + lane;
         float acc[G];
@@ -443,7 +451,7 @@ __device__ __forceinline__ void main_block(const int block, const Descs &desc, i
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const uint32_t key = ord_key(acc[g]);
-            const bool keep = valid && (win || key >= tau[g]);
+            const bool keep = valid && (win || (((chosen >> g) & 1u) != 0u && key >= tau[g]));
             // DIPR: a score above the sample's maximum raises the head's maximum.  About S - 1 scores
             // per head do (the expected number of tokens ahead of the best of a 1-in-S sample), so
             // these atomics on one address are few; one per wavefront and page at most.
@@ -484,7 +492,7 @@ __device__ __forceinline__ void main_block(const int block, const Descs &desc, i
     }
 }
 
-template <int DT, int D, int G, int CP, bool REPAIR>
+template <int DT, int D, int G, int CP, bool REPAIR, bool COARSE>
 __global__ __launch_bounds__(256) void main_kernel(const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int B,
                                                     const int32_t *__restrict__ page_table,
                                                     const uint32_t *__restrict__ qw, const uint4 *__restrict__ k_pool,
@@ -493,20 +501,21 @@ __global__ __launch_bounds__(256) void main_kernel(const ReqDesc *__restrict__ d
                                                     const uint32_t *__restrict__ tau_safe,
                                                     const uint32_t *__restrict__ fail,
                                                     const uint32_t *__restrict__ any_fail, int H_kv, int mode,
-                                                    int total_blocks, uint32_t *head_maxkey)
+                                                    int total_blocks, uint32_t *head_maxkey,
+                                                    const uint8_t *__restrict__ pmask)
 {
     const Descs desc{desc_mem, desc0, desc_n};
     if (REPAIR) {
         // launched with a small grid whose workgroups leave at once unless some head was marked
         if (*any_fail == 0u) return;
         for (int b = blockIdx.x; b < total_blocks; b += gridDim.x) {
-            main_block<DT, D, G, CP, REPAIR>(b, desc, B, page_table, qw, k_pool, blocks, block_stride, tau_in, tau_safe,
-                                             fail, H_kv, mode, head_maxkey);
+            main_block<DT, D, G, CP, REPAIR, COARSE>(b, desc, B, page_table, qw, k_pool, blocks, block_stride, tau_in,
+                                                     tau_safe, fail, H_kv, mode, head_maxkey, pmask);
             __syncthreads(); // the staging area is reused
         }
     } else {
-        main_block<DT, D, G, CP, REPAIR>(blockIdx.x, desc, B, page_table, qw, k_pool, blocks, block_stride, tau_in,
-                                         tau_safe, fail, H_kv, mode, head_maxkey);
+        main_block<DT, D, G, CP, REPAIR, COARSE>(blockIdx.x, desc, B, page_table, qw, k_pool, blocks, block_stride,
+                                                 tau_in, tau_safe, fail, H_kv, mode, head_maxkey, pmask);
     }
 }
 
@@ -523,20 +532,22 @@ static void launch_maybe_timed(Kern kern, dim3 grid, dim3 block, hipStream_t st,
 
 template <int DT, int D, int G>
 static hipError_t launch_score_cp(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles,
-                                  int cp, bool repair, int mode, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1)
+                                  int cp, bool repair, int mode, bool coarse, hipStream_t st, hipEvent_t ev0,
+                                  hipEvent_t ev1)
 {
     const int total_blocks = total_tiles * sh.n_kv_heads;
     const dim3 grid((unsigned)(repair && total_blocks > kRepairGrid ? kRepairGrid : total_blocks)), block(256);
-#define ALAYA_MAIN_K(CPP, RP)                                                                                 \
-    launch_maybe_timed(main_kernel<DT, D, G, CPP, RP>, grid, block, st, ev0, ev1, dv.desc.mem, dv.desc.in,    \
+#define ALAYA_MAIN_K(CPP, RP, CO)                                                                             \
+    launch_maybe_timed(main_kernel<DT, D, G, CPP, RP, CO>, grid, block, st, ev0, ev1, dv.desc.mem, dv.desc.in, \
                        dv.desc.n, B, dv.page_table, (const uint32_t *)q, (const uint4 *)dv.k_pool, dv.blocks, \
                        dv.block_stride, (const uint32_t *)dv.tau, (const uint32_t *)dv.tau_safe,              \
                        (const uint32_t *)dv.fail, (const uint32_t *)dv.any_fail, sh.n_kv_heads, mode,         \
-                       total_blocks, dv.head_maxkey)
+                       total_blocks, dv.head_maxkey, dv.pmask)
 #define ALAYA_MAIN(CPP)                                                                                       \
     do {                                                                                                      \
-        if (repair) ALAYA_MAIN_K(CPP, true);                                                                  \
-        else ALAYA_MAIN_K(CPP, false);                                                                        \
+        if (coarse) ALAYA_MAIN_K(CPP, false, true);                                                           \
+        else if (repair) ALAYA_MAIN_K(CPP, true, false);                                                      \
+        else ALAYA_MAIN_K(CPP, false, false);                                                                 \
     } while (0)
     // (the staging area holds 4 * G * 64 * CP pairs: at most 32 KiB)
     if (cp == 1) ALAYA_MAIN(1);
@@ -551,27 +562,28 @@ static hipError_t launch_score_cp(const Shape &sh, const DeviceViews &dv, int B,
 
 template <int DT, int D>
 static hipError_t launch_score_g(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles,
-                                 int cp, bool repair, int mode, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1)
+                                 int cp, bool repair, int mode, bool coarse, hipStream_t st, hipEvent_t ev0,
+                                 hipEvent_t ev1)
 {
     switch (sh.n_q_heads / sh.n_kv_heads) {
-    case 1: return launch_score_cp<DT, D, 1>(sh, dv, B, q, total_tiles, cp, repair, mode, st, ev0, ev1);
-    case 2: return launch_score_cp<DT, D, 2>(sh, dv, B, q, total_tiles, cp, repair, mode, st, ev0, ev1);
-    case 4: return launch_score_cp<DT, D, 4>(sh, dv, B, q, total_tiles, cp, repair, mode, st, ev0, ev1);
-    case 8: return launch_score_cp<DT, D, 8>(sh, dv, B, q, total_tiles, cp, repair, mode, st, ev0, ev1);
+    case 1: return launch_score_cp<DT, D, 1>(sh, dv, B, q, total_tiles, cp, repair, mode, coarse, st, ev0, ev1);
+    case 2: return launch_score_cp<DT, D, 2>(sh, dv, B, q, total_tiles, cp, repair, mode, coarse, st, ev0, ev1);
+    case 4: return launch_score_cp<DT, D, 4>(sh, dv, B, q, total_tiles, cp, repair, mode, coarse, st, ev0, ev1);
+    case 8: return launch_score_cp<DT, D, 8>(sh, dv, B, q, total_tiles, cp, repair, mode, coarse, st, ev0, ev1);
     default: return hipErrorInvalidValue;
     }
 }
 
 hipError_t launch_score(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles, int cp,
-                        bool repair, int mode, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1)
+                        bool repair, int mode, bool coarse, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1)
 {
     if (total_tiles <= 0) return hipSuccess;
     if (sh.dtype == 0) {
-        if (sh.head_dim == 128) return launch_score_g<0, 128>(sh, dv, B, q, total_tiles, cp, repair, mode, st, ev0, ev1);
-        if (sh.head_dim == 64) return launch_score_g<0, 64>(sh, dv, B, q, total_tiles, cp, repair, mode, st, ev0, ev1);
+        if (sh.head_dim == 128) return launch_score_g<0, 128>(sh, dv, B, q, total_tiles, cp, repair, mode, coarse, st, ev0, ev1);
+        if (sh.head_dim == 64) return launch_score_g<0, 64>(sh, dv, B, q, total_tiles, cp, repair, mode, coarse, st, ev0, ev1);
     } else {
-        if (sh.head_dim == 128) return launch_score_g<1, 128>(sh, dv, B, q, total_tiles, cp, repair, mode, st, ev0, ev1);
-        if (sh.head_dim == 64) return launch_score_g<1, 64>(sh, dv, B, q, total_tiles, cp, repair, mode, st, ev0, ev1);
+        if (sh.head_dim == 128) return launch_score_g<1, 128>(sh, dv, B, q, total_tiles, cp, repair, mode, coarse, st, ev0, ev1);
+        if (sh.head_dim == 64) return launch_score_g<1, 64>(sh, dv, B, q, total_tiles, cp, repair, mode, coarse, st, ev0, ev1);
     }
     return hipErrorInvalidValue;
 }

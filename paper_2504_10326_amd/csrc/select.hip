@@ -223,7 +223,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
     const uint2 *__restrict__ blocks, int64_t block_stride, uint32_t *__restrict__ head_maxkey,
     uint32_t *__restrict__ fail, uint32_t *__restrict__ any_fail, int redo, int batch_blocks,
     const int32_t *__restrict__ page_table, int32_t *__restrict__ sel_ids, int32_t *__restrict__ sel_rows,
-    float *__restrict__ sel_scores, int32_t *__restrict__ counts,
+    int short_ok, float *__restrict__ sel_scores, int32_t *__restrict__ counts,
     float *__restrict__ head_M, int32_t *__restrict__ out_ids, int32_t *__restrict__ out_counts, int64_t ids_stride,
     int32_t *__restrict__ status)
 {
@@ -249,7 +249,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
     int32_t *rows = sel_rows + (size_t)dsc.score_off + (size_t)h * dsc.head_stride;
     const int nb_all = dsc.ntiles_b;
     const int n_batches = (nb_all + batch_blocks - 1) / batch_blocks;
-    const bool bucket_rule = mode == 0 && dsc.k < dsc.n - dsc.nwin;
+    bool bucket_rule = mode == 0 && dsc.k < dsc.n - dsc.nwin;
     const float M_dipr = mode == 1 ? ord_float(head_maxkey[rh]) : 0.f;
     const float thr = mode == 1 ? M_dipr - dsc.beta : -INFINITY; // top-k with k >= n: every token
 
@@ -336,7 +336,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
         count_pass(21, 0x7FFu, 32, 0u);
         __syncthreads();
         block_find_bin(lh, kHistBins, need, wtot, res);
-        if (res[0] < 0) {
+        if (res[0] < 0 && !short_ok) {
             // Fewer than k ranked tokens survived: the bound - an estimate then - was too high.  Every
             // thread sees the same histogram; the head is marked for the repair pass and left alone.
             if (tid == 0) {
@@ -345,8 +345,12 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
             }
             return;
         }
+        // (short_ok: the candidates were cut down on purpose - the coarse index - and all of them are taken)
+        if (res[0] < 0) bucket_rule = false;
+    }
+    if (bucket_rule) {
         const uint32_t b1 = (uint32_t)res[0];
-        need -= res[1];
+        int need = dsc.k - res[1];
         __syncthreads();
         for (int i = tid; i < kHistBins; i += kSelectThreads) lh[i] = 0u;
         __syncthreads();
@@ -395,7 +399,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
                 ids[pos] = tok[e];
                 ss[pos] = v;
                 // where the gather finds the token's value row: physical page * 64 + slot
-                rows[pos] = page_table[dsc.pt_off + (tok[e] >> 6)] * kPageTokens + (tok[e] & 63);
+                if (sel_rows) rows[pos] = page_table[dsc.pt_off + (tok[e] >> 6)] * kPageTokens + (tok[e] & 63);
                 if (out_ids && (int64_t)pos < ids_stride) out_ids[(size_t)rh * (size_t)ids_stride + pos] = tok[e];
                 mx = fmaxf(mx, v);
             }
@@ -450,15 +454,14 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
     }
 }
 
-hipError_t launch_select(const Shape &sh, const DeviceViews &dv, int B, int mode, bool redo, int batch_blocks,
-                         int32_t *out_ids, int32_t *out_counts, int64_t ids_stride, hipStream_t st)
+hipError_t launch_select(const Shape &sh, const DeviceViews &dv, const SelectIO &io, int B, int mode, bool redo,
+                         int batch_blocks, int32_t *out_ids, int32_t *out_counts, int64_t ids_stride, hipStream_t st)
 {
     if (batch_blocks <= 0 || batch_blocks > kSelBatch) batch_blocks = kSelBatch;
     select_kernel<<<dim3((unsigned)(B * sh.n_q_heads)), dim3(kSelectThreads), 0, st>>>(
-        dv.desc.mem, dv.desc.in, dv.desc.n, sh.n_q_heads, sh.n_kv_heads, mode, dv.blocks, dv.block_stride,
-        dv.head_maxkey, dv.fail, dv.any_fail, redo ? 1 : 0, batch_blocks, dv.page_table, dv.sel_ids, dv.sel_rows,
-        dv.sel_scores, dv.counts,
-        dv.head_M, out_ids, out_counts, ids_stride, dv.status);
+        io.desc.mem, io.desc.in, io.desc.n, sh.n_q_heads, sh.n_kv_heads, mode, io.blocks, io.block_stride,
+        dv.head_maxkey, dv.fail, dv.any_fail, redo ? 1 : 0, batch_blocks, dv.page_table, io.ids, io.rows,
+        io.short_ok ? 1 : 0, io.scores, io.counts, io.head_M, out_ids, out_counts, ids_stride, dv.status);
     return hipGetLastError();
 }
 

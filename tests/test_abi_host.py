@@ -40,7 +40,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layouts_match_header():
     assert ctypes.sizeof(A.CacheConfig) == 56
-    assert ctypes.sizeof(A.SparseParams) == 64
+    assert ctypes.sizeof(A.SparseParams) == 88
 
 
 def test_sizes():

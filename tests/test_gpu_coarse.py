@@ -1,0 +1,224 @@
+"""GPU parity of the coarse-grained index (Sec. 6.2 "Query Optimizer", index types; Table 4) against the oracle:
+block representatives kept up to date by every kind of append, the chosen pages, the tokens selected among
+them, and the attention output.
+
+Bar: pages identical to the oracle's except for pages whose ORACLE block score lies within BAND_U of the
+score of the last chosen page (block scores are sums of 128 fp32 terms of magnitude up to a few units, about
+40 in all: the fp32 accumulation error is a few 1e-5, the band 1e-3); given the pages (the oracle's if they
+agree, else the GPU's own, handed to the oracle), tokens and outputs to the bar of the exact query."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2504_10326_amd as A
+import workloads as wl
+from parity_util import BAND, OUT_TOL, to_device
+
+pytestmark = pytest.mark.gpu
+BAND_U = 1e-3
+
+
+def _llama(lens, seed=0, **kw):
+    return wl.resized(wl.config("llama8b_128k", seed), lens, **kw)
+
+
+def _cache(w, g, extra=0, load=True):
+    n_phys = g["n_phys_pages"] + (extra + 63) // 64 * w.batch
+    order = g["page_order"]
+    if n_phys != len(order):
+        order = np.concatenate([order, np.arange(len(order), n_phys, dtype=np.int32)])
+    c = A.Cache(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, max_seqs=w.batch, max_batch=w.batch,
+                max_tokens_per_seq=max(w.lens) + extra + 64, max_batch_tokens=w.total_tokens + w.batch * extra,
+                n_phys_pages=n_phys, phys_page_order=order if w.permute_pages else None, coarse_index=True)
+    for t in (c.k_pool, c.v_pool, c.workspace, c.scratch, c.rep_pool):
+        t.fill_(0xFF)
+    if load:
+        for r, n in enumerate(w.lens):
+            c.append_kv(r, to_device(g["K"][r], w.dtype), to_device(g["V"][r], w.dtype))
+    torch.cuda.synchronize()
+    return c
+
+
+def compare_coarse(w, g, res, P, topk, window=(0, 0), n_visible=None, scale=None):
+    """One coarse call against the oracle, every request and head.  Returns recall of the exact top-k."""
+    out, ids, counts, pages = [t.cpu().numpy() for t in res]
+    stats = {"band_pages": 0, "band_heads": 0, "max_out_err": 0.0, "recall": []}
+    for r in range(w.batch):
+        nv = w.lens[r] if n_visible is None else int(n_visible[r])
+        K, V, q = g["K"][r], g["V"][r], g["q"][r]
+        orc = oracle.coarse_attn(q, K, V, 64, int(P[r]), int(topk[r]), scale=scale, window=window, n_visible=nv,
+                                 want_scores=True)
+        exact = oracle.sparse_attn(q, K, V, oracle.TOPK, k=int(topk[r]), window=window, n_visible=nv, scale=scale)
+        npg = (nv + 63) // 64
+        for h in range(w.n_q_heads):
+            want_pages = orc["blocks"][h]
+            got_pages = pages[r, h, :min(int(P[r]), npg)]
+            assert (pages[r, h, min(int(P[r]), npg):] == -1).all()
+            assert len(np.unique(got_pages)) == len(got_pages) and got_pages.min() >= 0 and got_pages.max() < npg
+            s = orc["scores"][h]
+            diff = np.setxor1d(got_pages, want_pages)
+            if diff.size:
+                u = orc["u"][h]
+                edge = u[want_pages].min()
+                assert np.abs(u[diff] - edge).max() <= BAND_U, \
+                    f"request {r} head {h}: pages {diff} differ, {np.abs(u[diff] - edge).max():.2e} from the boundary"
+                stats["band_pages"] += 1
+                want_ids = oracle.select_topk_in_blocks(s, 64, np.sort(got_pages), int(topk[r]), window)
+            else:
+                want_ids = orc["ids"][h]
+            cnt = int(counts[r, h])
+            assert cnt == len(want_ids), f"request {r} head {h}: count {cnt} != {len(want_ids)}"
+            got_ids = ids[r, h, :cnt]
+            d2 = np.setxor1d(got_ids, want_ids)
+            ref = None
+            if d2.size:
+                w0, w1 = min(window[0], nv), min(window[1], nv)
+                ranked = want_ids[(want_ids >= w0) & (want_ids < nv - w1)]
+                assert np.abs(s[d2] - s[ranked].min()).max() <= BAND, f"request {r} head {h}: ids {d2} differ"
+                stats["band_heads"] += 1
+            if d2.size or diff.size:
+                ref = oracle.attend(s, V[:nv], h // w.group, np.sort(got_ids), scale)
+            else:
+                ref = orc["out"][h]
+            err = float(np.abs(out[r, h] - ref).max())
+            stats["max_out_err"] = max(stats["max_out_err"], err)
+            assert err <= OUT_TOL, f"request {r} head {h}: output error {err}"
+            stats["recall"].append(len(np.intersect1d(got_ids, exact["ids"][h])) / len(exact["ids"][h]))
+    return stats
+
+
+def run_coarse(c, w, g, P, topk, window=(0, 0), n_visible=None, scale=None):
+    q = to_device(g["q"], w.dtype)
+    nv = w.lens if n_visible is None else n_visible
+    stride = max(min(k + sum(window), n) for k, n in zip(topk, nv))
+    pstride = max(min(p, (n + 63) // 64) for p, n in zip(P, nv))
+    res = c.sparse_attn(list(range(w.batch)), q, A.ALAYA_TOPK, topk=list(topk), coarse_pages=list(P), ids_stride=stride,
+                        pages_stride=pstride, window=window, n_visible=n_visible, scale=scale or 0.0)
+    torch.cuda.synchronize()
+    assert c.poll_status() == A.ALAYA_OK
+    return compare_coarse(w, g, res, P, topk, window, n_visible, scale)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_representatives_follow_every_kind_of_append(dtype):
+    """Bulk appends in ragged pieces, single-token appends, batch steps and decode steps, on permuted pages:
+    after each the representatives of every page equal the channel-wise minima and maxima of its keys."""
+    w = wl.Workload("reps", 8, 2, 128, (300, 130), dtype, 4, "topk", topk=(8, 8), permute_pages=True, seed=3)
+    g = wl.generate(wl.resized(w, [300 + 140, 130 + 140]), threads=1)
+    c = _cache(wl.resized(w, [440, 270]), g, load=False)
+    dev = lambda a: to_device(a, dtype)
+    lens = [0, 0]
+
+    def check():
+        torch.cuda.synchronize()
+        tdt = torch.int16 if dtype == "bf16" else torch.float32
+        reps = c.rep_pool.view(tdt).view(-1, 2, 2, 128).cpu().numpy()
+        mpps = (c.cfg.max_tokens_per_seq + 63) // 64                 # the workspace is the page table [seq][mpps]
+        pt = c.workspace.view(torch.int32)[:2 * mpps].view(2, mpps).cpu().numpy()
+        for r in range(2):
+            for kvh in range(2):
+                lo, hi = oracle.block_reps(g["K"][r][:lens[r]], kvh, 64)
+                for b in range(lo.shape[0]):
+                    got = reps[pt[r, b], kvh]
+                    got = wl.bf16_bits_to_f32(got.view(np.uint16)) if dtype == "bf16" else got
+                    assert (got[0] == lo[b]).all() and (got[1] == hi[b]).all(), (r, kvh, b)
+
+    for r, cuts in ((0, [0, 100, 101, 128, 300]), (1, [0, 64, 130])):
+        for a, b in zip(cuts[:-1], cuts[1:]):
+            c.append_kv(r, dev(g["K"][r][a:b]), dev(g["V"][r][a:b]))
+        lens[r] = cuts[-1]
+    check()
+    q = dev(g["q"])
+    for step in range(140):                                   # both sequences cross two page boundaries
+        ks = dev(np.stack([g["K"][r][lens[r]] for r in range(2)]))
+        vs = dev(np.stack([g["V"][r][lens[r]] for r in range(2)]))
+        if step % 3 == 0:
+            c.append_step([0, 1], ks, vs)
+        elif step % 3 == 1:
+            c.decode_step([0, 1], ks, vs, q, A.ALAYA_TOPK, topk=[8, 8])
+        else:
+            c.append_kv(0, ks[0:1], vs[0:1])
+            c.append_kv(1, ks[1:2], vs[1:2])
+        lens = [n + 1 for n in lens]
+        if step in (0, 1, 2, 62, 63, 64, 65, 139):
+            check()
+    c.close()
+
+
+@pytest.mark.parametrize("n,P,k,window,vis", [(9000, 20, 100, (0, 0), None), (5000 + 7, 3, 500, (0, 0), None),
+                                               (12345, 40, 64, (128, 512), None), (64 * 37, 1, 1, (0, 0), None),
+                                               (8191, 127, 8190, (3, 70), None), (20000, 60, 300, (0, 0), 13000 + 5),
+                                               (4000, 10 ** 6, 50, (0, 0), None)])
+def test_coarse_topk_llama_shape(n, P, k, window, vis):
+    """32 query heads / 8 KV heads: pages, tokens and outputs against the oracle; k from 1 to more than the
+    chosen pages hold; with a window; through a visible prefix; P larger than the context."""
+    w = _llama([n], topk=[k])
+    g = wl.generate(w)
+    c = _cache(w, g)
+    st = run_coarse(c, w, g, [P], [k], window, None if vis is None else [vis])
+    if P >= (n + 63) // 64:      # every page chosen: the exact query, bit for bit
+        q = to_device(g["q"], w.dtype)
+        a = c.sparse_attn([0], q, A.ALAYA_TOPK, topk=[k], ids_stride=k, window=window)
+        b = c.sparse_attn([0], q, A.ALAYA_TOPK, topk=[k], ids_stride=k, window=window, coarse_pages=[P])
+        for x, y in zip(a, b):
+            assert torch.equal(x, y)
+        assert min(st["recall"]) == 1.0
+    c.close()
+
+
+def test_coarse_batch_other_shapes_and_errors():
+    """Ragged batch with a different P per request on permuted pages; other group sizes, head dims and fp32;
+    refused calls."""
+    lens = [1, 63, 64, 65, 3000, 8191, 517]
+    w = wl.resized(wl.config("paged_1m"), lens, topk=[1, 5, 5, 5, 100, 300, 20])
+    g = wl.generate(w)
+    c = _cache(w, g)
+    run_coarse(c, w, g, [1, 1, 1, 2, 10, 33, 4], list(w.topk))
+    run_coarse(c, w, g, [5, 1, 1, 1, 47, 2, 9], [70, 5, 5, 5, 3000, 64, 20], window=(2, 30))
+    q = to_device(g["q"], w.dtype)
+    with pytest.raises(A.AlayaError) as e:
+        c.sparse_attn(list(range(7)), q, A.ALAYA_DIPR, beta=[1.0] * 7, coarse_pages=[1] * 7)
+    assert e.value.code == A.ALAYA_E_INVAL and "top-k" in str(e.value)
+    with pytest.raises(A.AlayaError) as e:
+        c.sparse_attn(list(range(7)), q, A.ALAYA_TOPK, topk=[1] * 7, coarse_pages=[1, 1, 0, 1, 1, 1, 1])
+    assert e.value.code == A.ALAYA_E_INVAL
+    with pytest.raises(A.AlayaError) as e:                      # tokens are cached: too late for an index
+        A.alaya_bind_reps(c.handle, c.rep_pool, c.rep_pool.numel())
+    assert e.value.code == A.ALAYA_E_INVAL and "empty" in str(e.value)
+    c.close()
+    plain = A.Cache(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, max_seqs=1, max_batch=1, max_tokens_per_seq=256,
+                    max_batch_tokens=256, n_phys_pages=4)
+    plain.append_kv(0, to_device(g["K"][4][:100], w.dtype), to_device(g["V"][4][:100], w.dtype))
+    with pytest.raises(A.AlayaError) as e:
+        plain.sparse_attn([0], q[:1].contiguous(), A.ALAYA_TOPK, topk=[4], coarse_pages=[1])
+    assert e.value.code == A.ALAYA_E_INVAL and "representative" in str(e.value)
+    plain.close()
+    for hq, hk, d, dtype in [(4, 4, 128, "bf16"), (8, 4, 64, "bf16"), (16, 2, 128, "bf16"), (4, 2, 64, "f32"), (8, 1, 128, "f32")]:
+        w2 = wl.Workload("shape", hq, hk, d, (2500, 700), dtype, 8, "topk", topk=(200, 33), seed=9)
+        g2 = wl.generate(w2)
+        c2 = _cache(w2, g2)
+        run_coarse(c2, w2, g2, [6, 3], [200, 33])
+        run_coarse(c2, w2, g2, [40, 1], [10, 100], window=(1, 1))
+        c2.close()
+
+
+def test_coarse_index_finds_clustered_keys():
+    """What the index is for: keys of adjacent tokens are alike, so the keys that matter to a query sit
+    together.  Here two pages per head are shifted as a whole towards the head's query; their minima and
+    maxima move with them, a handful of pages per head recovers the exact top-k, and the call reads a
+    fraction of the keys.  (Single outlier keys inside otherwise ordinary pages do not move the minima and
+    maxima of 64 tokens in 128 channels, and the index cannot see them: that is its price.)"""
+    n = 64 * 400
+    w = _llama([n], topk=[32])
+    g = wl.generate(w)
+    q = wl.bf16_bits_to_f32(g["q"])[0].astype(np.float64)
+    K = wl.bf16_bits_to_f32(g["K"][0]).astype(np.float64)
+    for h in range(w.n_q_heads):
+        for page in (37 + 9 * h, 111 + 7 * h):
+            K[page * 64:(page + 1) * 64, h // w.group, :] += 12.0 * q[h] / np.linalg.norm(q[h])
+    g2 = dict(g, K=[wl.to_bf16_bits(K.astype(np.float32))])
+    c = _cache(w, g2)
+    st = run_coarse(c, w, g2, [8], [32])
+    assert min(st["recall"]) >= 0.9 and np.mean(st["recall"]) >= 0.98, st["recall"]
+    c.close()
