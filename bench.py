@@ -44,8 +44,10 @@ HBM_PEAK_GBS = 8000.0
 LLC_BYTES = 512e6          # below this the keys of a call partly stay in the last-level cache
 
 
-def measure(name, args, steps, warmup, cold_steps, cpu_baseline, beta=None, dense=True):
-    """One workload: timed loop, profiled loop, cold-cache loop, optional oracle timing.  Returns a dict."""
+def measure(name, args, steps, warmup, cold_steps, cpu_baseline, beta=None, dense=True, coarse_div=0):
+    """One workload: timed loop, profiled loop, cold-cache loop, optional oracle timing.  Returns a dict.
+    coarse_div > 0: the top-k query goes through the coarse index with 1 / coarse_div of each request's pages
+    per head (the cache then keeps block representatives, and the append is not fused into the query)."""
     import numpy as np
     import torch
 
@@ -66,7 +68,7 @@ def measure(name, args, steps, warmup, cold_steps, cpu_baseline, beta=None, dens
         order = np.concatenate([order, np.arange(len(order), n_phys, dtype=np.int32)])
     c = A.Cache(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, max_seqs=w.batch, max_batch=w.batch,
                 max_tokens_per_seq=max(w.lens) + extra, max_batch_tokens=w.total_tokens + w.batch * extra,
-                n_phys_pages=n_phys, phys_page_order=order if w.permute_pages else None)
+                n_phys_pages=n_phys, phys_page_order=order if w.permute_pages else None, coarse_index=coarse_div > 0)
     tdt = torch.bfloat16
 
     def dev(a):
@@ -92,6 +94,8 @@ def measure(name, args, steps, warmup, cold_steps, cpu_baseline, beta=None, dens
     window = tuple(int(x) for x in args.window.split(","))
     if w.mode == "topk":
         mode, kw = A.ALAYA_TOPK, dict(topk=list(w.topk), window=window)
+        if coarse_div > 0:
+            kw["coarse_pages"] = [max(1, (n + 63) // 64 // coarse_div) for n in w.lens]
     else:
         mode, kw = A.ALAYA_DIPR, dict(beta=[beta] * w.batch, window=window)
     c.set_tuning(args.pages_per_wave, args.attend_splits, 0, args.write_all_scores)
@@ -121,8 +125,19 @@ def measure(name, args, steps, warmup, cold_steps, cpu_baseline, beta=None, dens
         return dt, w.n_q_heads * toks, w.n_kv_heads * toks
 
     run(warmup)
+    c.debug_repairs()
     secs, keys, rows = run(steps)
     ms_per_step = secs / steps * 1e3
+    repairs = c.debug_repairs()
+    recall = None
+    if coarse_div > 0:
+        # what the approximation costs: the share of the exact query's tokens that the coarse query returns
+        kmax = max(w.topk) + sum(window)
+        ex = c.sparse_attn(seqs, q, mode, topk=list(w.topk), window=window, ids_stride=kmax)
+        co = c.sparse_attn(seqs, q, mode, ids_stride=kmax, **kw)
+        e_ids, c_ids, cnts = ex[1].cpu().numpy(), co[1].cpu().numpy(), ex[2].cpu().numpy()
+        hits = sum(len(np.intersect1d(e_ids[r, h, :cnts[r, h]], c_ids[r, h])) for r in range(w.batch) for h in range(w.n_q_heads))
+        recall = hits / float(cnts.sum())
 
     # Profiled repeat of the same loop: per-kernel durations from HIP events on the launch stream.
     c.set_profiling(True)
@@ -252,6 +267,8 @@ def measure(name, args, steps, warmup, cold_steps, cpu_baseline, beta=None, dens
         "kernels_us": kernels_us,
         "full_attn_ms": full_ms,
         "survivor_fraction": survivors / (w.n_q_heads * total_n),
+        "repaired_heads_per_step": repairs / steps,
+        "coarse": None if coarse_div <= 0 else {"pages_per_head": kw["coarse_pages"], "recall_of_exact_topk": recall},
         "pages": {"sampled": pages_sampled, "main_pass": pages_main},
         "roofline": {"bound": "hbm", "kernel": "main_kernel (main scoring pass)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
@@ -279,7 +296,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="batched_16",
-                    choices=["llama8b_128k", "range_256k", "paged_1m", "batched_16"])
+                    choices=["llama8b_128k", "range_256k", "paged_1m", "batched_16", "clustered_128k"])
+    ap.add_argument("--coarse-div", type=int, default=0,
+                    help="answer --workload through the coarse index with 1 / this of the pages per head (0 = exact)")
     ap.add_argument("--beta", type=float, default=2.0, help="DIPR margin for range_256k")
     ap.add_argument("--window", default="0,0",
                     help="INIT,LAST tokens that are always attended (the paper's tables use 128,512)")
@@ -307,18 +326,24 @@ def main() -> int:
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         return 1
     A.lib()
-    head = measure(args.workload, args, args.steps, args.warmup, args.cold_steps, not args.no_cpu_baseline)
+    head = measure(args.workload, args, args.steps, args.warmup, args.cold_steps, not args.no_cpu_baseline,
+                   coarse_div=args.coarse_div)
     per_config = {}
     if not args.no_per_config:
-        others = [("llama8b_128k", None), ("range_256k", 2.0), ("range_256k", 4.0), ("paged_1m", None), ("batched_16", None)]
-        for name, beta in others:
-            if name == args.workload and (beta is None or beta == args.beta):
+        # (workload, DIPR margin, share of the pages that the coarse index keeps per head: 1 / that)
+        others = [("llama8b_128k", None, 0), ("range_256k", 2.0, 0), ("range_256k", 4.0, 0), ("paged_1m", None, 0),
+                  ("batched_16", None, 0), ("clustered_128k", None, 0), ("clustered_128k", None, 16), ("paged_1m", None, 16)]
+        for name, beta, cdiv in others:
+            if name == args.workload and cdiv == 0 and (beta is None or beta == args.beta):
                 continue
             r = measure(name, args, min(args.steps, 100), min(args.warmup, 10), min(args.cold_steps, 20), False,
-                        beta=beta, dense=False)
+                        beta=beta, dense=False, coarse_div=cdiv)
             key = name if beta is None else f"{name}_beta{beta:g}"
+            if cdiv:
+                key += f"_coarse_1_in_{cdiv}"
             per_config[key] = {"ms_per_step": r["ms_per_step"], "keys_per_s": r["value"], "tokens": r["config"]["tokens"],
                                "kernels_us": r["kernels_us"], "survivor_fraction": r["survivor_fraction"],
+                               "repaired_heads_per_step": r["repaired_heads_per_step"], "coarse": r["coarse"],
                                "main_pass_frac": r["roofline"]["frac"], "main_pass_warm_frac": r["roofline"]["warm_frac"],
                                "main_pass_cache": r["roofline"]["cache"],
                                "scoring_pass_frac": r["roofline"]["scoring_pass_frac"],
@@ -330,8 +355,8 @@ def main() -> int:
         "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
     }
-    for k in ("config", "latency_us_per_layer", "k_rows_per_s", "kernels_us", "full_attn_ms", "survivor_fraction", "pages",
-              "roofline", "gather", "cold_cache", "cpu_baseline"):
+    for k in ("config", "latency_us_per_layer", "k_rows_per_s", "kernels_us", "full_attn_ms", "survivor_fraction",
+              "repaired_heads_per_step", "coarse", "pages", "roofline", "gather", "cold_cache", "cpu_baseline"):
         line[k] = head[k]
     line["per_config"] = per_config
     print(json.dumps(line))

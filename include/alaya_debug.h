@@ -57,6 +57,11 @@ int alaya_debug_estimate(alaya_cache *c, int mode);
 #define ALAYA_SCORE_PAD 1088
 int64_t alaya_debug_scores(alaya_cache *c, float *out, void *stream);
 
+/* Inspection hook: synchronises `stream` and returns how many (request, head) selections took the repair path
+ * of the estimated bound since the counter was last read (it lives in the scratch memory), then clears it;
+ * -1 on error. */
+int64_t alaya_debug_repairs(alaya_cache *c, void *stream);
+
 /* How the last alaya_sparse_attn call split its pages (one page = 64 tokens of one sequence, scored
  * for every KV head): *sampled pages were scored by the sample pass for the threshold bound,
  * *main_pass pages by the main scoring kernel (all of them).  HOST pointers. */

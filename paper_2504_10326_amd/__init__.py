@@ -36,7 +36,7 @@ EXPORTS = (
 # include/alaya_debug.h
 DEBUG_EXPORTS = (
     "alaya_set_profiling", "alaya_kernel_times", "alaya_set_tuning", "alaya_debug_scores", "alaya_debug_pages",
-    "alaya_debug_estimate",
+    "alaya_debug_estimate", "alaya_debug_repairs",
 )
 
 
@@ -111,6 +111,7 @@ def lib() -> ctypes.CDLL:
         L.alaya_kernel_times.restype = i32
         L.alaya_set_tuning.argtypes = [vp, i32, i32, i32, i32]; L.alaya_set_tuning.restype = i32
         L.alaya_debug_scores.argtypes = [vp, vp, vp]; L.alaya_debug_scores.restype = i64
+        L.alaya_debug_repairs.argtypes = [vp, vp]; L.alaya_debug_repairs.restype = i64
         L.alaya_debug_pages.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64)]
         L.alaya_debug_pages.restype = i32
         L.alaya_debug_estimate.argtypes = [vp, i32]; L.alaya_debug_estimate.restype = i32
@@ -430,6 +431,10 @@ class Cache:
     def debug_survivors(self, stream=None) -> int:
         """(token, score) pairs kept by the scoring pass of the last sparse call, over all heads."""
         return lib().alaya_debug_scores(self.handle, None, _stream(stream))
+
+    def debug_repairs(self, stream=None) -> int:
+        """(request, head) selections that took the repair path of the estimated bound since the last read."""
+        return lib().alaya_debug_repairs(self.handle, _stream(stream))
 
     def debug_pages(self) -> Tuple[int, int]:
         """(pages scored in full by the sample pass, pages scored by the main pass) of the last sparse call."""

@@ -102,6 +102,7 @@ struct DeviceViews {
     int32_t *counts;           // [max_batch * n_q_heads]: size of the selected set
     float *partials;           // attend / full-attention partial results
     int32_t *status;           // device status word
+    uint32_t *repairs;         // heads that took the repair path since the counter was last read (inspection)
     const uint8_t *pmask;      // coarse index: one byte per (KV head, page), bit g = head g of the group chose the page
 };
 

@@ -249,6 +249,7 @@ void bind_views(DeviceViews &dv, const Scratch &S, char *base)
     dv.partials = (float *)(base + S.partials);
     dv.status = (int32_t *)(base + S.status);
     dv.pmask = (const uint8_t *)(base + S.pmask);
+    dv.repairs = (uint32_t *)(base + S.dbg_total + 8);
 }
 
 // Clears what must be zero before a scratch area's first use: statistics, repair marks, status.
@@ -256,6 +257,7 @@ hipError_t clear_scratch(const Scratch &S, char *base, hipStream_t st)
 {
     hipError_t e = launch_fill_u32((uint32_t *)(base + S.zero_begin), (S.zero_end - S.zero_begin) / sizeof(uint32_t), 0u, st);
     if (e == hipSuccess) e = launch_fill_u32((uint32_t *)(base + S.status), 1, 0u, st);
+    if (e == hipSuccess) e = launch_fill_u32((uint32_t *)(base + S.dbg_total), 4, 0u, st);
     return e;
 }
 
@@ -1115,6 +1117,19 @@ int64_t alaya_debug_scores(alaya_cache *c, float *out, void *stream)
     if (e == hipSuccess) e = hipMemcpyAsync(&h, total, sizeof h, hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e != hipSuccess) { fail_hip(e, "survivor read"); return -1; }
+    return (int64_t)h;
+}
+
+int64_t alaya_debug_repairs(alaya_cache *c, void *stream)
+{
+    if (!c) { fail(ALAYA_E_INVAL, "null cache handle"); return -1; }
+    if (!c->scratch_mem || !c->scratch_ready) return 0;
+    hipStream_t st = (hipStream_t)stream;
+    uint32_t h = 0;
+    hipError_t e = hipMemcpyAsync(&h, c->dv.repairs, sizeof h, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e == hipSuccess) e = launch_fill_u32(c->dv.repairs, 1, 0u, st);
+    if (e != hipSuccess) { fail_hip(e, "repair counter read"); return -1; }
     return (int64_t)h;
 }
 

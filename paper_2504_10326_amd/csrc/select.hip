@@ -225,7 +225,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
     const int32_t *__restrict__ page_table, int32_t *__restrict__ sel_ids, int32_t *__restrict__ sel_rows,
     int short_ok, float *__restrict__ sel_scores, int32_t *__restrict__ counts,
     float *__restrict__ head_M, int32_t *__restrict__ out_ids, int32_t *__restrict__ out_counts, int64_t ids_stride,
-    int32_t *__restrict__ status)
+    int32_t *__restrict__ status, uint32_t *__restrict__ repairs)
 {
     const Descs desc{desc_mem, desc0, desc_n};
     __shared__ uint32_t lh[kHistBins];
@@ -451,6 +451,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
         if (out_ids && (int64_t)count > ids_stride) atomicOr(status, 1);
         head_maxkey[rh] = 0u; // leave the running maximum and the repair mark clean for the next call
         fail[rh] = 0u;
+        if (redo) atomicAdd(repairs, 1u);
     }
 }
 
@@ -461,7 +462,7 @@ hipError_t launch_select(const Shape &sh, const DeviceViews &dv, const SelectIO 
     select_kernel<<<dim3((unsigned)(B * sh.n_q_heads)), dim3(kSelectThreads), 0, st>>>(
         io.desc.mem, io.desc.in, io.desc.n, sh.n_q_heads, sh.n_kv_heads, mode, io.blocks, io.block_stride,
         dv.head_maxkey, dv.fail, dv.any_fail, redo ? 1 : 0, batch_blocks, dv.page_table, io.ids, io.rows,
-        io.short_ok ? 1 : 0, io.scores, io.counts, io.head_M, out_ids, out_counts, ids_stride, dv.status);
+        io.short_ok ? 1 : 0, io.scores, io.counts, io.head_M, out_ids, out_counts, ids_stride, dv.status, dv.repairs);
     return hipGetLastError();
 }
 

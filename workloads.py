@@ -51,6 +51,9 @@ class Workload:
     permute_pages: bool = False        # physical pages handed out in a seeded random order
     seed: int = 0
     q_scale: float = 1.0               # knob on the planted direction of q (1.0 = the stated recipe)
+    cluster_runs: int = 0              # per query head: runs of two adjacent pages whose keys all lean towards the query
+    cluster_last: int = 0              # ... and that many last tokens of the request lean towards every query of the group
+    cluster_shift: float = 0.0         # how far they lean (added along the unit query, raw inner-product units / |q|)
     page_tokens: int = PAGE_TOKENS
 
     @property
@@ -92,6 +95,13 @@ def config(name: str, seed: int = 0) -> Workload:
     if name == "paged_1m":
         return Workload("paged_1m", 32, 8, 128, (1048576,), "bf16", 32, "topk", topk=(4096,),
                         permute_pages=True, seed=seed)
+    if name == "clustered_128k":
+        # The recipe above scatters the keys that matter uniformly over the context.  In a real cache the keys of
+        # adjacent tokens are alike and the recent tokens matter most (Sec. 7.1: a window of the last tokens holds
+        # the best key almost always): here each head's high-affinity keys sit in four runs of two pages and in
+        # the last 512 tokens.  Same shapes as llama8b_128k; a robustness measurement, not a parity bar.
+        return Workload("clustered_128k", 32, 8, 128, (131072,), "bf16", 32, "topk", topk=(2048,), seed=seed,
+                        cluster_runs=4, cluster_last=512, cluster_shift=6.0)
     if name == "batched_16":
         lens = batched_lens(seed)
         return Workload("batched_16", 32, 8, 128, lens, "bf16", 32, "topk",
@@ -178,6 +188,8 @@ def generate(w: Workload, threads: Optional[int] = None) -> Dict[str, object]:
             unit = ksum / max(np.linalg.norm(ksum), 1e-30)
             noise = 0.1 * _rng(w.seed, "qnoise", r, h).standard_normal(d)
             q[r, h, :] = (w.q_scale * unit + noise).astype(np.float32)
+    if w.cluster_runs or w.cluster_last:
+        _cluster(w, Ks, q)
     qs = _store(q, w.dtype)
 
     n_phys = w.pages_needed() + w.batch
@@ -185,6 +197,27 @@ def generate(w: Workload, threads: Optional[int] = None) -> Dict[str, object]:
     if w.permute_pages:
         order = _rng(w.seed, "pages").permutation(n_phys).astype(np.int32)
     return {"K": Ks, "V": Vs, "q": qs, "planted": planted, "page_order": order, "n_phys_pages": n_phys}
+
+
+def _cluster(w: Workload, Ks: List[np.ndarray], q: np.ndarray) -> None:
+    """Make the keys of a few page runs (per query head) and of the last tokens (per KV group) lean towards the
+    queries: k += shift * q / |q| for every key of the run.  In place, after the queries are drawn."""
+    G, T = w.group, w.page_tokens
+    for r, n in enumerate(w.lens):
+        pages = n // T
+        for h in range(w.n_q_heads):
+            g = h // G
+            unit = (q[r, h] / max(np.linalg.norm(q[r, h]), 1e-30)).astype(np.float32)
+            starts = _rng(w.seed, "pages", r + 1, h).choice(max(1, pages - 2), size=min(w.cluster_runs, max(1, pages - 2)),
+                                                            replace=False)
+            for p0 in starts:
+                a, b = int(p0) * T, min(n, (int(p0) + 2) * T)
+                Ks[r][a:b, g, :] = _store(_as_f32(Ks[r][a:b, g, :], w.dtype) + w.cluster_shift * unit, w.dtype)
+        if w.cluster_last:
+            a = max(0, n - w.cluster_last)
+            for g in range(w.n_kv_heads):
+                lean = sum(q[r, h] / max(np.linalg.norm(q[r, h]), 1e-30) for h in range(g * G, (g + 1) * G)).astype(np.float32)
+                Ks[r][a:, g, :] = _store(_as_f32(Ks[r][a:, g, :], w.dtype) + 0.5 * w.cluster_shift * lean, w.dtype)
 
 
 def extra_tokens(w: Workload, r: int, t: int, step: int = 0) -> Tuple[np.ndarray, np.ndarray]:
