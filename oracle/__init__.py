@@ -60,6 +60,12 @@ def _load():
         lib.oracle_coarse_attn.argtypes = [vp, vp, vp, i32, i64, i64, i32, i32, i32, i64, i64, i64, f64, i64, i64, vp,
                                            vp, i64, vp, vp, vp, i64, vp, vp, i32]
         lib.oracle_coarse_attn.restype = i32
+        lib.oracle_scores_f32.argtypes = [vp, vp, i32, i64, i32, i32, i32, vp]
+        lib.oracle_scores_f32.restype = None
+        lib.oracle_knn_graph.argtypes = [vp, i32, i64, i32, i32, i32, i32, vp]
+        lib.oracle_knn_graph.restype = None
+        lib.oracle_diprs.argtypes = [vp, i64, i32, vp, i32, i64, ctypes.c_float, i64, i64, vp, vp, vp]
+        lib.oracle_diprs.restype = i64
         lib.oracle_sparse_attn.argtypes = [vp, vp, vp, i32, i64, i32, i32, i32, i32, i64, f64, f64, i64, i64,
                                            vp, vp, i64, vp, vp, i32]
         lib.oracle_sparse_attn.restype = i32
@@ -184,6 +190,41 @@ def coarse_attn(q: np.ndarray, K: np.ndarray, V: np.ndarray, block: int, n_block
         raise ValueError(f"oracle error {rc}")
     return {"out": out, "counts": counts, "ids": [ids[h, :counts[h]].copy() for h in range(hq)],
             "blocks": [blocks[h, :bcounts[h]].copy() for h in range(hq)], "u": u, "scores": sc, "threads": rc}
+
+
+def scores_f32(q_h: np.ndarray, K: np.ndarray, g: int) -> np.ndarray:
+    """Inner products in the arithmetic DIPRS decides in: fp32, one fused multiply-add per channel in order."""
+    q_h, K = _c(q_h), _c(K)
+    n, hk, d = K.shape
+    assert q_h.shape == (d,) and _dt(q_h) == _dt(K)
+    s = np.empty(n, dtype=np.float32)
+    _load().oracle_scores_f32(_p(q_h), _p(K), _dt(K), n, hk, g, d, _p(s))
+    return s
+
+
+def knn_graph(K: np.ndarray, g: int, M: int) -> np.ndarray:
+    """Exact M-nearest-neighbour graph of KV head g's keys under the inner product: int32 [n][M], best first, -1 padded."""
+    K = _c(K)
+    n, hk, d = K.shape
+    nbr = np.empty((n, M), dtype=np.int32)
+    _load().oracle_knn_graph(_p(K), _dt(K), n, hk, g, d, int(M), _p(nbr))
+    return nbr
+
+
+def diprs(nbr: np.ndarray, s: np.ndarray, k0: int, l0: int, beta: float, window: Tuple[int, int] = (0, 0)):
+    """Algorithm 1 on the graph nbr [n][M] with fp32 scores s: returns (ids ascending, C in the order it grew)."""
+    nbr = _c(np.asarray(nbr, dtype=np.int32))
+    s = _c(np.asarray(s, dtype=np.float32))
+    n, M = nbr.shape
+    assert s.shape == (n,)
+    C = np.empty(n, dtype=np.int32)
+    ids = np.empty(n, dtype=np.int32)
+    clen = ctypes.c_int64(0)
+    cnt = _load().oracle_diprs(_p(nbr), n, M, _p(s), int(k0), int(l0), float(beta), int(window[0]), int(window[1]),
+                               _p(C), ctypes.byref(clen), _p(ids))
+    if cnt < 0:
+        raise ValueError("invalid DIPRS arguments")
+    return ids[:cnt].copy(), C[:clen.value].copy()
 
 
 def attend(s: np.ndarray, V: np.ndarray, g: int, ids: np.ndarray, scale: Optional[float] = None) -> np.ndarray:

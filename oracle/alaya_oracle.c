@@ -28,7 +28,18 @@
  *            always attended).  The paper fixes neither the block size, nor the representatives, nor P:
  *            they are parameters here.
  *
- * All arithmetic is fp64.  Inputs are the stored bytes (bf16 or fp32), widened
+ *   DIPRS    (Sec. 6.1.3 "DIPR Query Processing", Algorithm 1) the approximate DIPR query on a graph index: a
+ *            list C starts with the start key; its entries are visited in order, and every unvisited
+ *            neighbour k of the visited entry is appended if C holds at most l0 entries or q.k is within beta
+ *            of the best inner product in C so far; the answer is every c in C within beta of the best of C.
+ *            With a window (Sec. 7.1 "Window Caching Enhanced DIPR") the best so far also counts the window's
+ *            tokens, which are always attended and take no part in the walk.  The graph here is the exact
+ *            M-nearest-neighbour graph of the keys under the inner product (the paper builds RoarGraph; any
+ *            graph index serves Algorithm 1).  Which neighbours are appended depends on comparisons of
+ *            scores, so DIPRS - alone in this file - takes its scores in the GPU kernel's arithmetic: fp32,
+ *            one fused multiply-add per channel in channel order (oracle_scores_f32).
+ *
+ * All other arithmetic is fp64.  Inputs are the stored bytes (bf16 or fp32), widened
  * exactly.  K and V are token-major: element (j, g, c) sits at (j*n_kv_heads + g)*d + c.
  *
  * Every function here is pinned by tests/test_oracle_pins.py against facts that
@@ -282,6 +293,106 @@ int oracle_coarse_attn(const void *q, const void *K, const void *V, int dtype, i
         if (!scores) free(s);
     }
     return used;
+}
+
+/* Scores in the arithmetic DIPRS decides in: fp32, acc = fma(q_c, k_c, acc) for c = 0 .. d-1 in order. */
+void oracle_scores_f32(const void *q, const void *K, int dtype, int64_t n, int n_kv_heads, int g, int d, float *s)
+{
+    for (int64_t j = 0; j < n; ++j) {
+        float acc = 0.0f;
+        int64_t row = (j * n_kv_heads + g) * (int64_t)d;
+        for (int c = 0; c < d; ++c)
+            acc = fmaf((float)widen(q, dtype, c), (float)widen(K, dtype, row + c), acc);
+        s[j] = acc;
+    }
+}
+
+static int by_sim_desc_then_id(const void *a, const void *b, void *ctx)
+{
+    const double *sim = (const double *)ctx;
+    int32_t ia = *(const int32_t *)a, ib = *(const int32_t *)b;
+    if (sim[ia] > sim[ib]) return -1;
+    if (sim[ia] < sim[ib]) return 1;
+    return (ia > ib) - (ia < ib);
+}
+
+/* The exact M-nearest-neighbour graph of the first n keys of KV head g under the inner product: nbr[j][0..M)
+ * = the M keys i != j with the largest k_i . k_j, best first (equal products: smaller i first); -1 where
+ * fewer than M other keys exist.  Brute force, fp64. */
+void oracle_knn_graph(const void *K, int dtype, int64_t n, int n_kv_heads, int g, int d, int M, int32_t *nbr)
+{
+#ifdef _OPENMP
+#pragma omp parallel
+#endif
+    {
+        double *sim = (double *)malloc((size_t)n * sizeof(double));
+        int32_t *order = (int32_t *)malloc((size_t)n * sizeof(int32_t));
+#ifdef _OPENMP
+#pragma omp for schedule(dynamic, 16)
+#endif
+        for (int64_t j = 0; j < n; ++j) {
+            int64_t m = 0;
+            for (int64_t i = 0; i < n; ++i) {
+                double acc = 0.0;
+                for (int c = 0; c < d; ++c)
+                    acc += widen(K, dtype, (i * n_kv_heads + g) * (int64_t)d + c) *
+                           widen(K, dtype, (j * n_kv_heads + g) * (int64_t)d + c);
+                sim[i] = acc;
+                if (i != j) order[m++] = (int32_t)i;
+            }
+            qsort_r(order, (size_t)m, sizeof *order, by_sim_desc_then_id, sim);
+            for (int t = 0; t < M; ++t) nbr[j * M + t] = t < m ? order[t] : -1;
+        }
+        free(order);
+        free(sim);
+    }
+}
+
+/* Algorithm 1, DIPRS(G, q, k0, l0, beta), on the graph nbr[n][M] (-1 = no neighbour) with the scores s[n].
+ * Window tokens W = {j < w0} U {j >= n - w1} are always attended, count as visited from the start and seed
+ * the best-so-far; k0 must lie outside W.
+ *   C, c_len   the list C in the order in which it grew (C[0] = k0)
+ *   ids        the answer, ascending: W plus every c in C with s_c >= best - beta, best = max over C and W
+ * Returns the size of the answer, -1 on invalid arguments. */
+int64_t oracle_diprs(const int32_t *nbr, int64_t n, int M, const float *s, int32_t k0, int64_t l0, float beta,
+                     int64_t w0, int64_t w1, int32_t *C, int64_t *c_len, int32_t *ids)
+{
+    if (n <= 0 || M <= 0 || !(beta >= 0.0f) || l0 < 0 || w0 < 0 || w1 < 0) return -1;
+    if (k0 < 0 || k0 >= n || k0 < w0 || k0 >= n - w1) return -1;
+    char *visited = (char *)calloc((size_t)n, 1);
+    int have_best = 0;
+    float best = 0.0f;
+    for (int64_t j = 0; j < n; ++j)
+        if (j < w0 || j >= n - w1) {
+            visited[j] = 1;
+            if (!have_best || s[j] > best) { best = s[j]; have_best = 1; }
+        }
+    int64_t len = 0;
+    C[len++] = k0;
+    visited[k0] = 1;
+    if (!have_best || s[k0] > best) { best = s[k0]; have_best = 1; }
+    for (int64_t i = 0; i < len; ++i) {
+        const int32_t c = C[i];
+        for (int t = 0; t < M; ++t) {
+            const int32_t k = nbr[(int64_t)c * M + t];
+            if (k < 0 || k >= n || visited[k]) continue;
+            visited[k] = 1;                                   /* tryAppend(q, k, beta, C, l0) */
+            if (len <= l0 || s[k] >= best - beta) {
+                C[len++] = k;
+                if (s[k] > best) best = s[k];
+            }
+        }
+    }
+    *c_len = len;
+    char *take = (char *)calloc((size_t)n, 1);
+    for (int64_t i = 0; i < len; ++i)
+        if (s[C[i]] >= best - beta) take[C[i]] = 1;
+    int64_t cnt = 0;
+    for (int64_t j = 0; j < n; ++j)
+        if (j < w0 || j >= n - w1 || take[j]) ids[cnt++] = (int32_t)j;
+    free(take);
+    free(visited);
+    return cnt;
 }
 
 /* Softmax over the selected set and the weighted sum of its value rows. */

@@ -535,3 +535,109 @@ def test_coarse_prefix_uses_the_stored_index():
             oracle.scores(q[h], Kp[:100], 0), 16, r["blocks"][h], 8))
     with pytest.raises(ValueError):
         oracle.coarse_attn(q, K, V, block=16, n_blocks=0, k=8)
+
+
+# ---------------------------------------------------------------- DIPRS (Sec. 6.1.3, Algorithm 1)
+_G7 = np.array([[1, 2], [3, 4], [5, 4], [6, 0], [6, 5], [3, 6], [0, 1]], dtype=np.int32)   # neighbours of nodes 0..6
+
+
+def test_diprs_by_hand_three_cases_of_try_append():
+    """Algorithm 1 walked by hand on a 7-node graph (neighbour lists above), start key 0, beta = 1.
+    Scores 5, 1, 9, 8.5, 3, 8.9, 0.
+    l0 = 1: node 1 is appended although it is not critical (|C| <= l0, case a of the paper's figure); node 2
+    (9 >= 5 - 1) is appended by the threshold (case c) and raises the best to 9; node 3 (8.5 >= 8) and
+    node 5 (8.9 >= 8) follow; nodes 4 (3) and 6 (0) are pruned (case b).  C = 0, 1, 2, 3, 5; answer 2, 3, 5.
+    l0 = 0: node 1 is pruned at once; C grows 0, 2, 5, 3; the same answer."""
+    s = np.array([5.0, 1.0, 9.0, 8.5, 3.0, 8.9, 0.0], dtype=np.float32)
+    ids, C = oracle.diprs(_G7, s, 0, 1, 1.0)
+    assert C.tolist() == [0, 1, 2, 3, 5] and ids.tolist() == [2, 3, 5]
+    ids, C = oracle.diprs(_G7, s, 0, 0, 1.0)
+    assert C.tolist() == [0, 2, 5, 3] and ids.tolist() == [2, 3, 5]
+    # the threshold moves with the best so far: node 2 at 5.2 enters under the early threshold (4.5) and is
+    # dropped from the answer once 8.9 has been found; beta = 0.5
+    s2 = s.copy(); s2[2] = 5.2
+    ids, C = oracle.diprs(_G7, s2, 0, 0, 0.5)
+    assert C.tolist() == [0, 2, 5, 3] and ids.tolist() == [3, 5]
+    # inclusive comparison: a neighbour exactly beta below the best is appended and answered
+    s3 = np.array([5.0, 4.0, 4.0, 0.0, 0.0, 0.0, 0.0], dtype=np.float32)
+    ids, C = oracle.diprs(_G7, s3, 0, 0, 1.0)
+    assert C.tolist() == [0, 1, 2] and ids.tolist() == [0, 1, 2]
+
+
+def test_diprs_is_approximate_and_l0_buys_exploration():
+    """The best key (node 3, score 9) hangs behind node 1 (score 1).  With l0 = 0 node 1 is pruned and the
+    walk ends at once: the answer is the start key, not the true range.  With l0 = 1 node 1 is kept, node 3 is
+    reached, and the answer is the exact DIPR set {3}: principle (i) of Sec. 6.1.3."""
+    s = np.array([5.0, 1.0, 2.0, 9.0, 3.0, 0.5, 0.0], dtype=np.float32)
+    ids, C = oracle.diprs(_G7, s, 0, 0, 1.0)
+    assert C.tolist() == [0] and ids.tolist() == [0]
+    ids, C = oracle.diprs(_G7, s, 0, 1, 1.0)
+    assert C.tolist() == [0, 1, 3] and ids.tolist() == [3]
+    assert oracle.select_dipr(s, 1.0).tolist() == [3]
+
+
+def test_diprs_window_seeds_the_best_and_is_always_answered():
+    """Sec. 7.1: the best so far also counts the cached window.  Token 6 (last one) scores 9.5: from the start
+    the threshold is 8.5, so node 2 (9) is appended, node 1 (1) is not - even with l0 = 0 the walk goes straight
+    for the critical tokens - and the answer holds the window whatever it scores."""
+    s = np.array([5.0, 1.0, 9.0, 8.5, 3.0, 8.9, 9.5], dtype=np.float32)
+    ids, C = oracle.diprs(_G7, s, 0, 0, 1.0, window=(0, 1))
+    assert C.tolist() == [0, 2, 5, 3] and ids.tolist() == [2, 3, 5, 6]
+    s[6] = -4.0
+    ids, C = oracle.diprs(_G7, s, 0, 0, 1.0, window=(0, 1))
+    assert ids.tolist() == [2, 3, 5, 6]
+    # with node 2 at 6.0 the seeded threshold (9.5 - 1) prunes it and the walk never leaves the start key, whose
+    # own 5.0 is not within beta of the window's 9.5; unseeded, 6.0 >= 5 - 1 would have been appended
+    s2 = np.array([5.0, 1.0, 6.0, 8.5, 3.0, 8.9, 9.5], dtype=np.float32)
+    ids, C = oracle.diprs(_G7, s2, 0, 0, 1.0, window=(0, 1))
+    assert C.tolist() == [0] and ids.tolist() == [6]
+    with pytest.raises(ValueError):
+        oracle.diprs(_G7, s, 6, 0, 1.0, window=(0, 1))      # the start key may not be a window token
+
+
+def test_diprs_on_a_complete_graph_is_the_exact_range_query():
+    """If every key neighbours every other and l0 >= n nothing is ever pruned before it is scored: C holds
+    every key and the answer is Def. 2's set; and the nearest-neighbour graph itself against a library sort."""
+    w, q, K, V = _small(31, n=60, hq=2, hk=1, d=16, dtype="bf16")
+    full = oracle.knn_graph(K, 0, 59)
+    Kf = _f64(K, "bf16")[:, 0]
+    sim = Kf @ Kf.T
+    for j in range(60):
+        order = sorted((i for i in range(60) if i != j), key=lambda i: (-sim[i, j], i))
+        assert full[j].tolist() == order
+    assert (oracle.knn_graph(K, 0, 5) == full[:, :5]).all()
+    assert (oracle.knn_graph(K[:4], 0, 5)[:, 3:] == -1).all()
+    for h in range(2):
+        s32 = oracle.scores_f32(q[h], K, 0)
+        np.testing.assert_allclose(s32, oracle.scores(q[h], K, 0), rtol=0, atol=2e-5)
+        for beta in (0.0, 0.7, 3.0):
+            ids, C = oracle.diprs(full, s32, 7, 60, beta)
+            assert sorted(C.tolist()) == list(range(60))
+            assert ids.tolist() == oracle.select_dipr(s32.astype(np.float64), beta).tolist()
+    # the fp32 score is a chain of fused multiply-adds in channel order: on small integers it is exact
+    qi = np.arange(1, 17, dtype=np.float32)
+    Ki = (np.arange(32, dtype=np.float32).reshape(2, 1, 16) % 7) - 3
+    assert oracle.scores_f32(qi, Ki, 0).tolist() == (Ki[:, 0] @ qi).tolist()
+
+
+def test_diprs_invariants_on_a_sparse_graph():
+    """On a 6-nearest-neighbour graph: C starts with the start key, holds no key twice, every entry but the
+    first is a neighbour of an earlier entry, the answer is exactly the part of C within beta of C's best,
+    and a larger l0 never returns fewer keys of the exact range set when it finds the same best."""
+    w, q, K, V = _small(32, n=400, hq=2, hk=1, d=16, dtype="bf16")
+    nbr = oracle.knn_graph(K, 0, 6)
+    norms = (_f64(K, "bf16")[:, 0] ** 2).sum(1)
+    k0 = int(norms.argmax())
+    for h in range(2):
+        s = oracle.scores_f32(q[h], K, 0)
+        exact = set(oracle.select_dipr(s.astype(np.float64), 2.0).tolist())
+        for l0 in (0, 8, 64, 400):
+            ids, C = oracle.diprs(nbr, s, k0, l0, 2.0)
+            assert C[0] == k0 and len(set(C.tolist())) == len(C)
+            pos = {int(c): i for i, c in enumerate(C)}
+            for i, c in enumerate(C[1:], 1):
+                assert any(int(c) in nbr[int(p)] for p in C[:i])
+            best = s[C].max()
+            assert ids.tolist() == sorted(int(c) for c in C if s[c] >= best - np.float32(2.0))
+            if best == s.max():
+                assert set(ids.tolist()) <= exact
