@@ -227,6 +227,43 @@ int alaya_decode_step(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads,
 int alaya_sparse_attn_static(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q,
                              const alaya_sparse_params *p, float *out, void *stream);
 
+/*
+ * The fine-grained index (Sec. 6.2 "Query Optimizer", index types: a graph over the key vectors) and the
+ * approximate DIPR query on it, DIPRS (Sec. 6.1.3 "DIPR Query Processing", Algorithm 1).
+ *
+ * alaya_graph_build indexes the tokens that sequence `seq` holds now: for every KV head the exact
+ * degree-nearest-neighbour graph of its keys under the inner product (best neighbour first; equal products:
+ * smaller token), shared by the query heads of the group (Sec. 7.2 "GQA-based index sharing"), and as entry
+ * point the key of largest norm.  (The paper builds RoarGraph; Algorithm 1 runs on any graph index.)
+ * bf16 caches of head_dim 128, degree 1..64.  index_mem (>= alaya_graph_bytes) holds the graph and stays
+ * the library's while the handle lives; build_mem (>= alaya_graph_build_bytes) is scratch for the build only.
+ * Both DEVICE, 256-byte aligned.  The call synchronises `stream` before it returns.
+ *
+ * alaya_diprs_attn runs Algorithm 1 for every query head on its KV head's graph - start key = the entry
+ * point, capacity threshold l0, margin beta - in the paper's order, and attends over the answer: every key of
+ * the list C whose inner product is within beta of the best one met.  Inner products are fp32, one fused
+ * multiply-add per channel in channel order (the answer depends on comparisons of them).
+ *   q, out              as for alaya_sparse_attn with B = 1 (the graph's sequence)
+ *   p                   optional: window_init / window_last (Sec. 7.1 "Window Caching Enhanced DIPR": the
+ *                       window's tokens are always attended, take no part in the walk, and their best inner
+ *                       product seeds the walk's threshold), scale, out_ids / out_counts / ids_stride;
+ *                       the other fields are ignored
+ * Tokens appended after the build are not in the graph (Sec. 7.2 "Late Materialization for Index
+ * Updating"): they are treated as part of the window of last tokens.
+ */
+typedef struct alaya_graph alaya_graph;
+size_t alaya_graph_bytes(const alaya_cache *c, int seq, int degree);
+size_t alaya_graph_build_bytes(const alaya_cache *c, int seq, int degree);
+int alaya_graph_build(alaya_graph **out, alaya_cache *c, int seq, int degree, void *index_mem, size_t index_bytes,
+                      void *build_mem, size_t build_bytes, void *stream);
+int alaya_graph_destroy(alaya_graph *g);
+/* n_indexed, degree: HOST, optional; neighbours: DEVICE pointer to [n_kv_heads][n_indexed][degree] int32
+ * (-1 = none), optional; entry: HOST [n_kv_heads], optional. */
+int alaya_graph_info(const alaya_graph *g, int64_t *n_indexed, int32_t *degree, const int32_t **neighbours,
+                     int32_t *entry);
+int alaya_diprs_attn(alaya_cache *c, const alaya_graph *g, int n_q_heads, const void *q, float beta, int32_t l0,
+                     const alaya_sparse_params *p, float *out, void *stream);
+
 /* Session.attention, dense: Eq. (1) over every cached token (same q / out layout as above). */
 int alaya_full_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q,
                     float scale, float *out, void *stream);

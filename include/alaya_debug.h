@@ -62,6 +62,11 @@ int64_t alaya_debug_scores(alaya_cache *c, float *out, void *stream);
  * -1 on error. */
 int64_t alaya_debug_repairs(alaya_cache *c, void *stream);
 
+/* Inspection hook: the list C that the last alaya_diprs_attn call grew for query head `head`, in the order in
+ * which it grew: synchronises `stream`, copies the first min(length, cap) tokens to ids (HOST, optional) and
+ * returns the length; -1 on error.  Valid until the next call on the cache or its scratch memory. */
+int64_t alaya_debug_diprs_list(alaya_cache *c, int head, int32_t *ids, int64_t cap, void *stream);
+
 /* How the last alaya_sparse_attn call split its pages (one page = 64 tokens of one sequence, scored
  * for every KV head): *sampled pages were scored by the sample pass for the threshold bound,
  * *main_pass pages by the main scoring kernel (all of them).  HOST pointers. */

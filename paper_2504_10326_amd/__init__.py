@@ -32,11 +32,13 @@ EXPORTS = (
     "alaya_destroy_cache", "alaya_append_kv", "alaya_append_kv_step", "alaya_seq_len", "alaya_reset_seq",
     "alaya_sparse_attn", "alaya_decode_step", "alaya_sparse_attn_static", "alaya_full_attn", "alaya_poll_status",
     "alaya_last_error",
+    "alaya_graph_bytes", "alaya_graph_build_bytes", "alaya_graph_build", "alaya_graph_destroy", "alaya_graph_info",
+    "alaya_diprs_attn",
 )
 # include/alaya_debug.h
 DEBUG_EXPORTS = (
     "alaya_set_profiling", "alaya_kernel_times", "alaya_set_tuning", "alaya_debug_scores", "alaya_debug_pages",
-    "alaya_debug_estimate", "alaya_debug_repairs",
+    "alaya_debug_estimate", "alaya_debug_repairs", "alaya_debug_diprs_list",
 )
 
 
@@ -116,6 +118,17 @@ def lib() -> ctypes.CDLL:
         L.alaya_debug_pages.restype = i32
         L.alaya_debug_estimate.argtypes = [vp, i32]; L.alaya_debug_estimate.restype = i32
         L.alaya_last_error.argtypes = []; L.alaya_last_error.restype = ctypes.c_char_p
+        L.alaya_graph_bytes.argtypes = [vp, i32, i32]; L.alaya_graph_bytes.restype = sz
+        L.alaya_graph_build_bytes.argtypes = [vp, i32, i32]; L.alaya_graph_build_bytes.restype = sz
+        L.alaya_graph_build.argtypes = [ctypes.POINTER(vp), vp, i32, i32, vp, sz, vp, sz, vp]
+        L.alaya_graph_build.restype = i32
+        L.alaya_graph_destroy.argtypes = [vp]; L.alaya_graph_destroy.restype = i32
+        L.alaya_graph_info.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(vp),
+                                       ctypes.POINTER(ctypes.c_int32)]
+        L.alaya_graph_info.restype = i32
+        L.alaya_diprs_attn.argtypes = [vp, vp, i32, vp, ctypes.c_float, i32, ctypes.POINTER(SparseParams), vp, vp]
+        L.alaya_diprs_attn.restype = i32
+        L.alaya_debug_diprs_list.argtypes = [vp, i32, vp, i64, vp]; L.alaya_debug_diprs_list.restype = i64
         _lib = L
     return _lib
 
@@ -273,11 +286,86 @@ def alaya_full_attn(handle: int, seqs: Sequence[int], n_q_heads: int, q, scale: 
     _check(lib().alaya_full_attn(handle, sq, len(seqs), n_q_heads, _ptr(q), scale, _ptr(out), stream or None))
 
 
+def alaya_graph_bytes(handle: int, seq: int, degree: int) -> int:
+    return lib().alaya_graph_bytes(handle, seq, degree)
+
+
+def alaya_graph_build_bytes(handle: int, seq: int, degree: int) -> int:
+    return lib().alaya_graph_build_bytes(handle, seq, degree)
+
+
+def alaya_graph_build(handle: int, seq: int, degree: int, index_mem, index_bytes: int, build_mem, build_bytes: int,
+                      stream=0) -> int:
+    g = ctypes.c_void_p()
+    _check(lib().alaya_graph_build(ctypes.byref(g), handle, seq, degree, _ptr(index_mem), index_bytes,
+                                   _ptr(build_mem), build_bytes, stream or None))
+    return g.value
+
+
+def alaya_graph_destroy(graph: int) -> None:
+    _check(lib().alaya_graph_destroy(graph))
+
+
+def alaya_graph_info(graph: int, n_kv_heads: int) -> Tuple[int, int, int, list]:
+    """(n_indexed, degree, device address of the neighbour lists, entry point of every KV head)"""
+    n, m, nb = ctypes.c_int64(0), ctypes.c_int32(0), ctypes.c_void_p()
+    entry = (ctypes.c_int32 * n_kv_heads)()
+    _check(lib().alaya_graph_info(graph, ctypes.byref(n), ctypes.byref(m), ctypes.byref(nb), entry))
+    return n.value, m.value, nb.value, list(entry)
+
+
+def alaya_diprs_attn(handle: int, graph: int, n_q_heads: int, q, beta: float, l0: int, scale: float, out,
+                     out_ids=None, out_counts=None, ids_stride: int = 0, stream=0,
+                     window: Tuple[int, int] = (0, 0)) -> None:
+    p = SparseParams()
+    p.mode = ALAYA_DIPR
+    p.window_init, p.window_last = int(window[0]), int(window[1])
+    p.scale = scale
+    p.out_ids = _ptr(out_ids)
+    p.out_counts = _ptr(out_counts)
+    p.ids_stride = ids_stride
+    _check(lib().alaya_diprs_attn(handle, graph, n_q_heads, _ptr(q), beta, l0, ctypes.byref(p), _ptr(out),
+                                  stream or None))
+
+
 def alaya_poll_status(handle: int, stream=0) -> int:
     return lib().alaya_poll_status(handle, stream or None)
 
 
 # ---- a handle bundled with the torch memory behind it ---------------------------------------------
+
+class Graph:
+    """The exact nearest-neighbour graph of one sequence's keys (one per KV head), built on the GPU."""
+
+    def __init__(self, cache: "Cache", seq: int, degree: int, stream=None):
+        torch = cache.torch
+        self.cache, self.seq, self.handle = cache, seq, None
+        ib = alaya_graph_bytes(cache.handle, seq, degree)
+        bb = alaya_graph_build_bytes(cache.handle, seq, degree)
+        if ib == 0 or bb == 0:
+            raise AlayaError(ALAYA_E_INVAL, alaya_last_error())
+        self.index_mem = torch.empty(ib, dtype=torch.uint8, device=cache.device)
+        build_mem = torch.empty(bb, dtype=torch.uint8, device=cache.device)
+        self.handle = alaya_graph_build(cache.handle, seq, degree, self.index_mem, ib, build_mem, bb, _stream(stream))
+        self.n_indexed, self.degree, self._nbr_addr, self.entry = alaya_graph_info(self.handle, cache.cfg.n_kv_heads)
+
+    def neighbours(self):
+        """int32 tensor [n_kv_heads][n_indexed][degree] viewing the index memory"""
+        n = self.cache.cfg.n_kv_heads * self.n_indexed * self.degree
+        return self.index_mem[: 4 * n].view(self.cache.torch.int32).view(self.cache.cfg.n_kv_heads, self.n_indexed, self.degree)
+
+    def close(self) -> None:
+        if self.handle:
+            self.cache.torch.cuda.synchronize(self.cache.device)
+            alaya_graph_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
 
 class Cache:
     """One layer's paged KV store on one GPU.  torch allocates the pools, the page-table workspace and -
@@ -393,6 +481,35 @@ class Cache:
         if ids is not None:
             return out, ids, counts
         return (out, counts) if want_counts else out
+
+    # -- fine-grained index (Sec. 6.2) and DIPRS (Sec. 6.1.3, Algorithm 1)
+    def build_graph(self, seq: int, degree: int, stream=None) -> "Graph":
+        return Graph(self, seq, degree, stream)
+
+    def diprs_attn(self, graph: "Graph", q, beta: float, l0: int, scale: float = 0.0, ids_stride: int = 0, out=None,
+                   stream=None, window: Tuple[int, int] = (0, 0)):
+        """Algorithm 1 on the graph of its sequence for the query q [1][Hq][d]; returns out [1][Hq][d] fp32, or
+        (out, ids [1][Hq][ids_stride], counts [1][Hq]) when ids_stride > 0: the window's tokens, then the answer
+        in the order in which the walk met it."""
+        if out is None:
+            out = self._q_out([graph.seq], q)
+        ids = counts = None
+        if ids_stride > 0:
+            ids = self.torch.full((1, self.cfg.n_q_heads, ids_stride), -1, dtype=self.torch.int32, device=self.device)
+            counts = self.torch.zeros((1, self.cfg.n_q_heads), dtype=self.torch.int32, device=self.device)
+        alaya_diprs_attn(self.handle, graph.handle, self.cfg.n_q_heads, q, beta, l0, scale, out, ids, counts, ids_stride,
+                         _stream(stream), window)
+        return (out, ids, counts) if ids is not None else out
+
+    def debug_diprs_list(self, head: int, stream=None):
+        """The list C of the last diprs_attn call for one query head, as a numpy int32 array."""
+        import numpy as np
+        n = lib().alaya_debug_diprs_list(self.handle, head, None, 0, _stream(stream) or None)
+        if n < 0:
+            raise AlayaError(ALAYA_E_INVAL, alaya_last_error())
+        ids = np.empty(max(n, 1), dtype=np.int32)
+        lib().alaya_debug_diprs_list(self.handle, head, ids.ctypes.data, n, _stream(stream) or None)
+        return ids[:n]
 
     def full_attn(self, seqs: Sequence[int], q, scale: float = 0.0, out=None, stream=None):
         if out is None:

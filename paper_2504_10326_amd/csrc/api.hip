@@ -90,7 +90,8 @@ Layout make_layout(const alaya_cache_config &c)
 // statistics, partial results.  Sized by the largest call it must serve.
 struct Scratch {
     size_t desc, blocks, sel_scores, sel_ids, sel_rows, zero_begin, hist, head_maxkey, sample_max, fail, zero_end, tau,
-        tau_safe, head_M, counts, partials, status, dbg_total, pg_ids, pg_scores, pg_counts, pg_M, pmask, total;
+        tau_safe, head_M, counts, partials, status, dbg_total, pg_ids, pg_scores, pg_counts, pg_M, pmask, visited, total;
+    int64_t visited_words; // capacity of the DIPRS visited bits, 32-bit words
     int64_t pg_elems;    // capacity of the chosen-page arrays of the coarse index
     int64_t pmask_bytes; // capacity of its page mask
     int64_t block_words; // capacity of the survivor blocks, 8-byte words
@@ -146,6 +147,9 @@ Scratch make_scratch(int n_q_heads, int n_kv_heads, int head_dim, int64_t max_ba
     S.pg_M = take(heads * sizeof(float));
     S.pmask_bytes = (int64_t)n_kv_heads * (pages + 4 * max_batch);
     S.pmask = take((size_t)S.pmask_bytes);
+    // DIPRS: one visited bit per (query head, token)
+    S.visited_words = (int64_t)n_q_heads * ((max_batch_tokens + 31) / 32 + 8 * max_batch);
+    S.visited = take((size_t)S.visited_words * sizeof(uint32_t));
     S.total = o;
     return S;
 }
@@ -999,6 +1003,212 @@ int alaya_sparse_attn_static(alaya_cache *c, const int32_t *seqs, int B, int n_q
     rc = sparse_attn_impl(c, &use, seqs, B, n_q_heads, q, p, out, stream, nullptr, nullptr, &appended);
     c->prof = prof;
     return rc;
+}
+
+// ---- fine-grained index and DIPRS ------------------------------------------------------------------
+
+struct alaya_graph {
+    alaya_cache *cache;
+    int seq;
+    int64_t n_idx;           // tokens of the sequence that the graph covers
+    int degree;              // neighbours per key
+    int32_t *nbr;            // DEVICE [n_kv_heads][n_idx][degree]
+    unsigned long long *best; // DEVICE [n_kv_heads] (ordered norm << 32 | ~token) of the entry points
+    int32_t *entry_dev;      // DEVICE [n_kv_heads]
+    std::vector<int32_t> entry; // HOST copy
+};
+
+namespace {
+
+constexpr int64_t kGraphChunkBytes = (int64_t)256 << 20; // similarity rows held at a time
+
+int64_t graph_pad(int64_t n) { return (n + 127) / 128 * 128; }
+int64_t graph_chunk_rows(int64_t n)
+{
+    int64_t rows = kGraphChunkBytes / (graph_pad(n) * (int64_t)sizeof(float)) / 64 * 64;
+    if (rows < 64) rows = 64;
+    const int64_t all = (n + 63) / 64 * 64;
+    return rows < all ? rows : all;
+}
+
+int graph_args_ok(const alaya_cache *c, int seq, int degree)
+{
+    if (!c) return fail(ALAYA_E_INVAL, "null cache handle");
+    if (seq < 0 || seq >= c->cfg.max_seqs) return fail(ALAYA_E_INVAL, "sequence id %d outside 0..%d", seq, c->cfg.max_seqs - 1);
+    if (degree < 1 || degree > 64) return fail(ALAYA_E_INVAL, "degree %d outside 1..64", degree);
+    if (c->cfg.dtype != ALAYA_BF16 || c->cfg.head_dim != 128)
+        return fail(ALAYA_E_INVAL, "the graph index is built for bf16 caches of head_dim 128 only");
+    if (c->seq_len[(size_t)seq] <= 0) return fail(ALAYA_E_EMPTY, "sequence %d holds no tokens", seq);
+    return ALAYA_OK;
+}
+
+} // namespace
+
+size_t alaya_graph_bytes(const alaya_cache *c, int seq, int degree)
+{
+    if (graph_args_ok(c, seq, degree) != ALAYA_OK) return 0;
+    const int64_t n = c->seq_len[(size_t)seq];
+    return align_up((size_t)c->cfg.n_kv_heads * (size_t)n * degree * sizeof(int32_t), 256) + 512;
+}
+
+size_t alaya_graph_build_bytes(const alaya_cache *c, int seq, int degree)
+{
+    if (graph_args_ok(c, seq, degree) != ALAYA_OK) return 0;
+    const int64_t n = c->seq_len[(size_t)seq];
+    return (size_t)(graph_chunk_rows(n) * graph_pad(n)) * sizeof(float);
+}
+
+int alaya_graph_build(alaya_graph **out, alaya_cache *c, int seq, int degree, void *index_mem, size_t index_bytes,
+                      void *build_mem, size_t build_bytes, void *stream)
+{
+    if (!out) return fail(ALAYA_E_INVAL, "null out pointer");
+    *out = nullptr;
+    int rc = graph_args_ok(c, seq, degree);
+    if (rc != ALAYA_OK) return rc;
+    if (!index_mem || !build_mem || (((uintptr_t)index_mem | (uintptr_t)build_mem) & 255))
+        return fail(ALAYA_E_INVAL, "index and build memory must be given and 256-byte aligned");
+    if (index_bytes < alaya_graph_bytes(c, seq, degree) || build_bytes < alaya_graph_build_bytes(c, seq, degree))
+        return fail(ALAYA_E_NOMEM, "index or build memory too small");
+    const int64_t n = c->seq_len[(size_t)seq];
+    const int64_t n_pad = graph_pad(n), chunk = graph_chunk_rows(n);
+    hipStream_t st = (hipStream_t)stream;
+    alaya_graph *g = new (std::nothrow) alaya_graph();
+    if (!g) return fail(ALAYA_E_NOMEM, "host allocation failed");
+    g->cache = c;
+    g->seq = seq;
+    g->n_idx = n;
+    g->degree = degree;
+    g->nbr = (int32_t *)index_mem;
+    char *tail = (char *)index_mem + align_up((size_t)c->cfg.n_kv_heads * (size_t)n * degree * sizeof(int32_t), 256);
+    g->best = (unsigned long long *)tail;
+    g->entry_dev = (int32_t *)(tail + 256);
+    const Shape sh{c->cfg.dtype, c->cfg.head_dim, c->cfg.n_q_heads, c->cfg.n_kv_heads};
+    const int32_t *pt_row = c->dv.page_table + (size_t)seq * c->L.mpps;
+    hipError_t e = hipSuccess;
+    for (int kvh = 0; kvh < c->cfg.n_kv_heads && e == hipSuccess; ++kvh) {
+        int32_t *nbr = g->nbr + (size_t)kvh * (size_t)n * degree;
+        for (int64_t row0 = 0; row0 < n && e == hipSuccess; row0 += chunk) {
+            const int64_t rows = std::min(chunk, n - row0);
+            e = launch_graph_sim(sh, c->k_pool, pt_row, kvh, (int)row0, (int)((rows + 63) / 64 * 64), (int)n, (int)n_pad,
+                                 (float *)build_mem, st);
+            if (e == hipSuccess) e = launch_graph_topm((const float *)build_mem, (int)n_pad, (int)n, (int)row0, (int)rows, degree, nbr, st);
+        }
+    }
+    if (e == hipSuccess) e = launch_graph_norm(sh, c->k_pool, pt_row, (int)n, g->best, st);
+    std::vector<unsigned long long> best((size_t)c->cfg.n_kv_heads);
+    if (e == hipSuccess) e = hipMemcpyAsync(best.data(), g->best, best.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) { delete g; return fail_hip(e, "graph build"); }
+    g->entry.resize(best.size());
+    for (size_t i = 0; i < best.size(); ++i) g->entry[i] = (int32_t)(0xFFFFFFFFu - (uint32_t)(best[i] & 0xFFFFFFFFull));
+    e = hipMemcpyAsync(g->entry_dev, g->entry.data(), g->entry.size() * sizeof(int32_t), hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) { delete g; return fail_hip(e, "graph build"); }
+    *out = g;
+    return ALAYA_OK;
+}
+
+int alaya_graph_destroy(alaya_graph *g)
+{
+    if (!g) return fail(ALAYA_E_INVAL, "null graph handle");
+    delete g;
+    return ALAYA_OK;
+}
+
+int alaya_graph_info(const alaya_graph *g, int64_t *n_indexed, int32_t *degree, const int32_t **neighbours, int32_t *entry)
+{
+    if (!g) return fail(ALAYA_E_INVAL, "null graph handle");
+    if (n_indexed) *n_indexed = g->n_idx;
+    if (degree) *degree = g->degree;
+    if (neighbours) *neighbours = g->nbr;
+    if (entry) std::memcpy(entry, g->entry.data(), g->entry.size() * sizeof(int32_t));
+    return ALAYA_OK;
+}
+
+int alaya_diprs_attn(alaya_cache *c, const alaya_graph *g, int n_q_heads, const void *q, float beta, int32_t l0,
+                     const alaya_sparse_params *p, float *out, void *stream)
+{
+    if (!c || !g) return fail(ALAYA_E_INVAL, "null cache or graph handle");
+    if (g->cache != c) return fail(ALAYA_E_INVAL, "the graph belongs to another cache");
+    const int32_t seq = g->seq;
+    int64_t total_pages = 0, total_tokens = 0;
+    int rc = check_call(c, &seq, 1, n_q_heads, q, out, &total_pages, &total_tokens);
+    if (rc != ALAYA_OK) return rc;
+    if (!(beta >= 0.f)) return fail(ALAYA_E_INVAL, "beta must be >= 0");
+    if (l0 < 0) return fail(ALAYA_E_INVAL, "capacity threshold l0 = %d must be >= 0", l0);
+    if (p && (p->window_init < 0 || p->window_last < 0))
+        return fail(ALAYA_E_INVAL, "window sizes %d + %d must be >= 0", p->window_init, p->window_last);
+    if (p && (!(p->scale >= 0.f) || std::isinf(p->scale))) return fail(ALAYA_E_INVAL, "scale must be finite and >= 0");
+    if (p && p->out_ids && p->ids_stride <= 0) return fail(ALAYA_E_INVAL, "out_ids given with ids_stride <= 0");
+    if (!c->scratch_mem) return fail(ALAYA_E_INVAL, "no scratch memory bound to this cache (alaya_bind_scratch)");
+    const int64_t n = c->seq_len[(size_t)seq];
+    if (n < g->n_idx) return fail(ALAYA_E_INVAL, "the sequence is shorter (%lld) than its graph (%lld): it was reset", (long long)n, (long long)g->n_idx);
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t pages = (n + kPageTokens - 1) / kPageTokens;
+    ReqDesc d;
+    std::memset(&d, 0, sizeof d);
+    d.pt_off = (int32_t)((int64_t)seq * c->L.mpps);
+    d.n = (int32_t)n;
+    d.n_pages = (int32_t)pages;
+    d.head_stride = (int32_t)(pages * kPageTokens + kScorePad);
+    d.beta = beta;
+    d.sample_stride = 1;
+    // Tokens appended after the graph was built are not in it (Sec. 7.2 "Late Materialization for Index
+    // Updating"): they belong to the window of last tokens, which is attended as it is.
+    const int64_t w0 = p ? p->window_init : 0, w1 = std::max<int64_t>(p ? p->window_last : 0, n - g->n_idx);
+    d.w0 = (int32_t)std::min(w0, n);
+    d.w1 = (int32_t)std::min(w1, n);
+    d.nwin = (int32_t)std::min<int64_t>((int64_t)d.w0 + d.w1, n);
+    const int64_t cap = pages * kPageTokens, vis_words = (n + 31) / 32 + 8;
+    if ((int64_t)n_q_heads * cap > c->S.block_words || (int64_t)n_q_heads * vis_words > c->S.visited_words ||
+        (int64_t)n_q_heads * d.head_stride > c->S.sel_elems)
+        return fail(ALAYA_E_NOMEM, "scratch too small for the DIPRS walk");
+    rc = need_scratch(c, st);
+    if (rc != ALAYA_OK) return rc;
+    c->dv.desc.n = 1;
+    c->dv.desc.in = d;
+    const Shape sh{c->cfg.dtype, c->cfg.head_dim, n_q_heads, c->cfg.n_kv_heads};
+    const float scale = p && p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)c->cfg.head_dim);
+    uint32_t *visited = (uint32_t *)(c->scratch_mem + c->S.visited);
+    int32_t *c_lens = (int32_t *)(c->scratch_mem + c->S.pg_counts);
+    hipError_t e;
+    {
+        Timed tm(c, 1, st);
+        e = launch_fill_u32(visited, (size_t)n_q_heads * vis_words, 0u, st);
+        if (e == hipSuccess)
+            e = launch_diprs(sh, c->dv, q, g->nbr, (int)g->n_idx, g->degree, g->entry_dev, l0, beta, c->dv.blocks, cap, visited,
+                             vis_words, c_lens, p ? p->out_ids : nullptr, p ? p->out_counts : nullptr, p ? p->ids_stride : 0, st);
+    }
+    if (e != hipSuccess) return fail_hip(e, "DIPRS launch");
+    int splits = c->tune_splits > 0 ? c->tune_splits : 16;
+    { Timed tm(c, 2, st); e = launch_attend(sh, c->dv, 1, scale, splits, st); }
+    if (e != hipSuccess) return fail_hip(e, "attend launch");
+    { Timed tm(c, 3, st); e = launch_combine(sh, c->dv, 1, splits, 0, 0, out, st); }
+    if (e != hipSuccess) return fail_hip(e, "combine launch");
+    c->last_B = 0; // (no survivor blocks to inspect after this call)
+    c->last_tiles_b = 0;
+    return ALAYA_OK;
+}
+
+int64_t alaya_debug_diprs_list(alaya_cache *c, int head, int32_t *ids, int64_t cap, void *stream)
+{
+    if (!c || !c->scratch_mem || head < 0 || head >= c->cfg.n_q_heads) { fail(ALAYA_E_INVAL, "bad arguments"); return -1; }
+    hipStream_t st = (hipStream_t)stream;
+    const ReqDesc &d = c->dv.desc.in;
+    int32_t len = 0;
+    hipError_t e = hipMemcpyAsync(&len, (int32_t *)(c->scratch_mem + c->S.pg_counts) + head, sizeof len, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) { fail_hip(e, "list length read"); return -1; }
+    const int64_t m = len < cap ? len : cap;
+    if (ids && m > 0) {
+        std::vector<uint2> tmp((size_t)m);
+        const int64_t stride = (int64_t)d.n_pages * kPageTokens;
+        e = hipMemcpyAsync(tmp.data(), c->dv.blocks + (size_t)head * stride, (size_t)m * sizeof(uint2), hipMemcpyDeviceToHost, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        if (e != hipSuccess) { fail_hip(e, "list read"); return -1; }
+        for (int64_t i = 0; i < m; ++i) ids[i] = (int32_t)tmp[(size_t)i].y;
+    }
+    return len;
 }
 
 int alaya_full_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q, float scale_in,

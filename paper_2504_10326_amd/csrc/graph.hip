@@ -1,0 +1,358 @@
+// The fine-grained index (Sec. 6.2 "Query Optimizer", index types) and the DIPRS query on it (Sec. 6.1.3
+// "DIPR Query Processing", Algorithm 1).
+//
+// Index: the exact M-nearest-neighbour graph of a sequence's keys under the inner product, one graph per
+// KV head (shared by the query heads of the group, as Sec. 7.2 "GQA-based index sharing" shares one graph
+// among a query group).  The paper builds RoarGraph with a GPU nearest-neighbour stage; any graph index
+// serves Algorithm 1, and the exact graph needs nothing but the keys:
+//   sim_kernel    S = K K^T for a chunk of rows, bf16 operands straight from the paged K pool (its layout
+//                 keeps 8 consecutive channels of a token in one 16-byte word: the operand of the matrix
+//                 instruction as it is), fp32 accumulation in v_mfma_f32_32x32x16_bf16
+//   topm_kernel   per row, the M largest entries other than the row's own key, best first (equal
+//                 similarity: smaller token), by chunk-wise merging into a sorted list
+//   norm_kernel   the entry point of each KV head's graph: its key of largest norm
+// Query: diprs_kernel, one wavefront per query head, walks Algorithm 1 in the paper's order - the list C
+// is visited entry by entry, the neighbours of an entry are examined in the order of its list - so that the
+// list C and the answer are the ones the sequential algorithm gives.  The neighbours of one entry are scored
+// by the lanes side by side (lane = neighbour); what the sequential order decides (who is still under the
+// capacity threshold l0, what the best inner product was when a neighbour's turn came) is recovered with a
+// prefix count and a prefix maximum over the lanes.  Scores are fp32, one fused multiply-add per channel in
+// channel order.
+#include "alaya_internal.h"
+#include "row_slice.h"
+
+namespace alaya {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_g;
+typedef __attribute__((ext_vector_type(16))) float f32x16_g;
+
+// 16-byte word holding channels [8c, 8c + 8) of token j of KV head kvh (bf16 pool, D = 128: 16 words per token)
+__device__ __forceinline__ const uint4 *key_word(const uint4 *__restrict__ k_pool, const int32_t *__restrict__ pt_row,
+                                                 int H_kv, int kvh, int NC, int j, int c)
+{
+    const int phys = pt_row[j >> 6];
+    return k_pool + ((size_t)phys * H_kv + kvh) * (size_t)(NC * 64) + (size_t)c * 64 + (j & 63);
+}
+
+// ------------------------------------------------------------------------------------------------
+// S[r][j] = k_{row0 + r} . k_j for r < 64 * gridDim.y, j < n_pad (n_pad a multiple of 128; entries beyond n
+// hold whatever the unwritten page slots give and are ignored downstream).  Grid: (n_pad / 128, rows / 64);
+// a workgroup computes a 64 x 128 tile, wavefront w its columns [32 w, 32 w + 32) for both row halves.
+// Operand layout of v_mfma_f32_32x32x16_bf16: lane l supplies, for A, row l % 32 and channels 8 (l / 32) .. + 8
+// of the 16-channel step; for B, column l % 32 and the same channels; it receives, in register i, row
+// 8 (i / 4) + 4 (l / 32) + i % 4 of column l % 32.
+template <int D>
+__global__ __launch_bounds__(256) void sim_kernel(const uint4 *__restrict__ k_pool, const int32_t *__restrict__ pt_row,
+                                                  int H_kv, int kvh, int row0, int n, int n_pad, float *__restrict__ S)
+{
+    constexpr int NC = D / 8, STEPS = D / 16;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int col = blockIdx.x * 128 + wave * 32 + l32;
+    const int r_base = blockIdx.y * 64;
+    uint4 b[STEPS], a0[STEPS], a1[STEPS];
+    const bool col_ok = col < n;
+    const int ra = row0 + r_base + l32, rb = ra + 32;
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+        b[s] = col_ok ? *key_word(k_pool, pt_row, H_kv, kvh, NC, col, 2 * s + half) : make_uint4(0, 0, 0, 0);
+        a0[s] = ra < n ? *key_word(k_pool, pt_row, H_kv, kvh, NC, ra, 2 * s + half) : make_uint4(0, 0, 0, 0);
+        a1[s] = rb < n ? *key_word(k_pool, pt_row, H_kv, kvh, NC, rb, 2 * s + half) : make_uint4(0, 0, 0, 0);
+    }
+    f32x16_g c0 = {0.f}, c1 = {0.f};
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_g, a0[s]), __builtin_bit_cast(bf16x8_g, b[s]), c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_g, a1[s]), __builtin_bit_cast(bf16x8_g, b[s]), c1, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int r = 8 * (i >> 2) + 4 * half + (i & 3);
+        S[(size_t)(r_base + r) * n_pad + col] = c0[i];
+        S[(size_t)(r_base + 32 + r) * n_pad + col] = c1[i];
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// The M best columns of one row of S (the row's own key and columns >= n left out), best first; equal
+// similarity: smaller column first.  One 256-thread workgroup per row.  The row is read in chunks of 2048
+// columns; a sorted list of the M best so far is kept, the entries of a chunk that beat its last one are
+// appended, and list + newcomers are sorted again (bitonic, in LDS, as wide as needed).  Keys are composite:
+// (ordered similarity, ~column), so that the order is total and the result does not depend on timing.
+constexpr int kTopChunk = 2048;
+__global__ __launch_bounds__(256) void topm_kernel(const float *__restrict__ S, int n_pad, int n, int row0, int M,
+                                                   int32_t *__restrict__ nbr /* [n][M] of this KV head */)
+{
+    __shared__ unsigned long long buf[2 * kTopChunk]; // [0, M): the best so far, descending; then the newcomers
+    __shared__ int32_t cnt;
+    const int tid = threadIdx.x;
+    const int row = row0 + blockIdx.x;
+    if (row >= n) return;
+    const float *s = S + (size_t)blockIdx.x * n_pad;
+    for (int i = tid; i < M; i += 256) buf[i] = 0ull; // below every real key (ordered keys of floats are > 0)
+    if (tid == 0) cnt = M;
+    __syncthreads();
+    for (int c0 = 0; c0 < n; c0 += kTopChunk) {
+        const unsigned long long worst = buf[M - 1];
+#pragma unroll
+        for (int u = 0; u < kTopChunk / 256; ++u) {
+            const int col = c0 + u * 256 + tid;
+            if (col < n && col != row) {
+                const unsigned long long key = ((unsigned long long)ord_key(s[col]) << 32) | (0xFFFFFFFFu - (uint32_t)col);
+                if (key > worst) buf[atomicAdd(&cnt, 1)] = key;
+            }
+        }
+        __syncthreads();
+        const int total = cnt;
+        if (total > M) { // (uniform) sort list + newcomers, keep the first M
+            int width = 64;
+            while (width < total) width <<= 1;
+            for (int i = total + tid; i < width; i += 256) buf[i] = 0ull;
+            __syncthreads();
+            for (int k = 2; k <= width; k <<= 1) {
+                for (int j = k >> 1; j > 0; j >>= 1) {
+                    for (int i = tid; i < width; i += 256) {
+                        const int p = i ^ j;
+                        if (p > i) {
+                            const unsigned long long x = buf[i], y = buf[p];
+                            const bool desc = (i & k) == 0; // descending runs first: the final order is descending
+                            if (desc ? x < y : x > y) { buf[i] = y; buf[p] = x; }
+                        }
+                    }
+                    __syncthreads();
+                }
+            }
+            if (tid == 0) cnt = M;
+            __syncthreads();
+        }
+    }
+    for (int i = tid; i < M; i += 256) {
+        const unsigned long long key = buf[i];
+        nbr[(size_t)row * M + i] = key == 0ull ? -1 : (int32_t)(0xFFFFFFFFu - (uint32_t)(key & 0xFFFFFFFFull));
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Entry point of a KV head's graph: the key of largest squared norm (equal norms: smaller token).  One
+// workgroup per KV head; best[kvh] = (ordered norm << 32) | ~token.
+template <int D>
+__global__ __launch_bounds__(256) void norm_kernel(const uint4 *__restrict__ k_pool, const int32_t *__restrict__ pt_row,
+                                                   int H_kv, int n, unsigned long long *__restrict__ best)
+{
+    constexpr int NC = D / 8;
+    __shared__ unsigned long long red[256];
+    const int kvh = blockIdx.x;
+    unsigned long long mine = 0ull;
+    for (int j = threadIdx.x; j < n; j += 256) {
+        float acc = 0.f;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const uint4 w = *key_word(k_pool, pt_row, H_kv, kvh, NC, j, c);
+            const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float lo = bf16_lo(ww[e]), hi = bf16_hi(ww[e]);
+                acc = fmaf(lo, lo, acc);
+                acc = fmaf(hi, hi, acc);
+            }
+        }
+        const unsigned long long key = ((unsigned long long)ord_key(acc) << 32) | (0xFFFFFFFFu - (uint32_t)j);
+        mine = key > mine ? key : mine;
+    }
+    red[threadIdx.x] = mine;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o && red[threadIdx.x + o] > red[threadIdx.x]) red[threadIdx.x] = red[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) best[kvh] = red[0];
+}
+
+hipError_t launch_graph_sim(const Shape &sh, const void *k_pool, const int32_t *pt_row, int kvh, int row0, int rows,
+                            int n, int n_pad, float *S, hipStream_t st)
+{
+    if (sh.dtype != 0 || sh.head_dim != 128 || rows % 64 || n_pad % 128) return hipErrorInvalidValue;
+    sim_kernel<128><<<dim3((unsigned)(n_pad / 128), (unsigned)(rows / 64)), dim3(256), 0, st>>>(
+        (const uint4 *)k_pool, pt_row, sh.n_kv_heads, kvh, row0, n, n_pad, S);
+    return hipGetLastError();
+}
+
+hipError_t launch_graph_topm(const float *S, int n_pad, int n, int row0, int rows, int M, int32_t *nbr, hipStream_t st)
+{
+    if (M < 1 || M > 64) return hipErrorInvalidValue;
+    topm_kernel<<<dim3((unsigned)rows), dim3(256), 0, st>>>(S, n_pad, n, row0, M, nbr);
+    return hipGetLastError();
+}
+
+hipError_t launch_graph_norm(const Shape &sh, const void *k_pool, const int32_t *pt_row, int n, unsigned long long *best,
+                             hipStream_t st)
+{
+    if (sh.dtype != 0 || sh.head_dim != 128) return hipErrorInvalidValue;
+    norm_kernel<128><<<dim3((unsigned)sh.n_kv_heads), dim3(256), 0, st>>>((const uint4 *)k_pool, pt_row, sh.n_kv_heads, n, best);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// DIPRS.  Grid: one 64-thread workgroup (one wavefront) per query head.
+//   nbr       [H_kv][n_idx][M] neighbour lists (-1 = none)
+//   k0s       [H_kv] entry point of each KV head's graph
+//   clist     [H_q][cap] the list C as (score bits, token) pairs, in the order in which it grew
+//   visited   [H_q][words] one bit per token, zero on entry
+// The answer - the window's tokens, then every entry of C within beta of the best - goes to the
+// selected-token arrays that the gather kernel reads.
+template <int D>
+__global__ __launch_bounds__(64) void diprs_kernel(const ReqDesc dsc, int H_q, int H_kv, const uint4 *__restrict__ k_pool,
+                                                   const int32_t *__restrict__ page_table, const uint32_t *__restrict__ qw,
+                                                   const int32_t *__restrict__ nbr, int n_idx, int M,
+                                                   const int32_t *__restrict__ k0s, int l0, float beta,
+                                                   uint2 *__restrict__ clist, int64_t cap, uint32_t *__restrict__ visited,
+                                                   int64_t vis_words, int32_t *__restrict__ sel_ids,
+                                                   float *__restrict__ sel_scores, int32_t *__restrict__ sel_rows,
+                                                   int32_t *__restrict__ counts, float *__restrict__ head_M,
+                                                   int32_t *__restrict__ c_lens, int32_t *__restrict__ out_ids,
+                                                   int32_t *__restrict__ out_counts, int64_t ids_stride,
+                                                   int32_t *__restrict__ status)
+{
+    constexpr int NC = D / 8;
+    const int h = blockIdx.x, lane = threadIdx.x;
+    const int G = H_q / H_kv, kvh = h / G;
+    const int32_t *pt_row = page_table + dsc.pt_off;
+    const uint32_t *q = qw + (size_t)h * (D / 2);
+    uint2 *C = clist + (size_t)h * cap;
+    uint32_t *vis = visited + (size_t)h * vis_words;
+    int32_t *ids = sel_ids + (size_t)dsc.score_off + (size_t)h * dsc.head_stride;
+    float *ss = sel_scores + (size_t)dsc.score_off + (size_t)h * dsc.head_stride;
+    int32_t *rows = sel_rows + (size_t)dsc.score_off + (size_t)h * dsc.head_stride;
+    const int32_t *adj = nbr + (size_t)kvh * n_idx * M;
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+
+    // q . k_j in fp32: one fused multiply-add per channel, channels in order
+    auto score = [&](int j) {
+        float acc = 0.f;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const uint4 w = *key_word(k_pool, pt_row, H_kv, kvh, NC, j, c);
+            const uint32_t kw[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t qq = q[c * 4 + e];
+                acc = fmaf(bf16_lo(qq), bf16_lo(kw[e]), acc);
+                acc = fmaf(bf16_hi(qq), bf16_hi(kw[e]), acc);
+            }
+        }
+        return acc;
+    };
+    auto row_of = [&](int j) { return pt_row[j >> 6] * kPageTokens + (j & 63); };
+    auto wave_max = [&](float x) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+        return x;
+    };
+
+    // The window (Sec. 7.1): always attended, seeds the best so far, takes no part in the walk.
+    float best = -INFINITY;
+    int n_sel = 0;
+    for (int t0 = 0; t0 < dsc.nwin; t0 += 64) {
+        const int t = t0 + lane;
+        const bool on = t < dsc.nwin;
+        const int j = t < dsc.w0 ? t : dsc.n - dsc.nwin + t; // first w0 tokens, then the last ones
+        float s = -INFINITY;
+        if (on) {
+            s = score(j);
+            ids[t] = j;
+            ss[t] = s;
+            rows[t] = row_of(j);
+            if (out_ids && (int64_t)t < ids_stride) out_ids[(size_t)h * ids_stride + t] = j;
+        }
+        best = fmaxf(best, wave_max(s));
+    }
+    n_sel = dsc.nwin;
+
+    // start key: the graph's entry point, or - if that is a window token - the first token behind the initial window
+    int len = 0;
+    int k0 = k0s[kvh];
+    if (in_window(dsc, k0)) k0 = dsc.w0 < min(dsc.n - dsc.w1, n_idx) ? dsc.w0 : -1;
+    if (k0 >= 0) {
+        const float s0 = score(k0); // (every lane the same)
+        if (lane == 0) {
+            C[0] = make_uint2(__float_as_uint(s0), (uint32_t)k0);
+            atomicOr(&vis[k0 >> 5], 1u << (k0 & 31));
+        }
+        best = fmaxf(best, s0);
+        len = 1;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    for (int i = 0; i < len; ++i) { // len never exceeds the number of indexed tokens: every key enters C at most once
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        // (the list and the visited bits were written by this wavefront a moment ago, the bits with atomics
+        // that are carried out in the L2: both are read back past the L1)
+        const int c = (int)(__hip_atomic_load((const unsigned long long *)&C[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32);
+        const int k = lane < M ? adj[(size_t)c * M + lane] : -1;
+        bool fresh = k >= 0 && k < n_idx && !in_window(dsc, k);
+        if (fresh) fresh = (__hip_atomic_load(&vis[k >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & (1u << (k & 31))) == 0u;
+        if (fresh) atomicOr(&vis[k >> 5], 1u << (k & 31)); // mark k as visited (tryAppend)
+        const float s = fresh ? score(k) : -INFINITY;
+        const unsigned long long U = __ballot(fresh);
+        if (U == 0ull) continue;
+        // what the sequential order decides: the best inner product when this neighbour's turn comes ...
+        float pm = s;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const float t = __shfl_up(pm, o);
+            if (lane >= o) pm = fmaxf(pm, t);
+        }
+        float before = __shfl_up(pm, 1);
+        before = lane == 0 ? best : fmaxf(best, before);
+        // ... and whether the list is still at or under the capacity threshold
+        const int r = __popcll(U & lt_mask);
+        const bool app = fresh && (len + r <= l0 || s >= before - beta);
+        const unsigned long long A = __ballot(app);
+        const int at = len + __popcll(A & lt_mask);
+        if (app && at < cap) C[at] = make_uint2(__float_as_uint(s), (uint32_t)k); // (at < cap always: a key enters C once)
+        len = min(len + __popcll(A), (int)cap);
+        best = fmaxf(best, wave_max(app ? s : -INFINITY));
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    // the answer: every c in C with q.c >= best - beta
+    const float thr = best - beta;
+    for (int i0 = 0; i0 < len; i0 += 64) {
+        const int i = i0 + lane;
+        const unsigned long long raw =
+            i < len ? __hip_atomic_load((const unsigned long long *)&C[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
+        const uint2 pr = make_uint2((uint32_t)raw, (uint32_t)(raw >> 32)); // .x = score bits (low word), .y = token
+        const float s = __uint_as_float(pr.x);
+        const bool take = i < len && s >= thr;
+        const unsigned long long T = __ballot(take);
+        if (take) {
+            const int pos = n_sel + __popcll(T & lt_mask);
+            ids[pos] = (int)pr.y;
+            ss[pos] = s;
+            rows[pos] = row_of((int)pr.y);
+            if (out_ids && (int64_t)pos < ids_stride) out_ids[(size_t)h * ids_stride + pos] = (int)pr.y;
+        }
+        n_sel += __popcll(T);
+    }
+    if (lane == 0) {
+        counts[h] = n_sel;
+        head_M[h] = best;
+        c_lens[h] = len;
+        if (out_counts) out_counts[h] = n_sel;
+        if (out_ids && (int64_t)n_sel > ids_stride) atomicOr(status, 1);
+    }
+}
+
+hipError_t launch_diprs(const Shape &sh, const DeviceViews &dv, const void *q, const int32_t *nbr, int n_idx, int M,
+                        const int32_t *k0s, int l0, float beta, uint2 *clist, int64_t cap, uint32_t *visited,
+                        int64_t vis_words, int32_t *c_lens, int32_t *out_ids, int32_t *out_counts, int64_t ids_stride,
+                        hipStream_t st)
+{
+    if (sh.dtype != 0 || sh.head_dim != 128 || M < 1 || M > 64) return hipErrorInvalidValue;
+    diprs_kernel<128><<<dim3((unsigned)sh.n_q_heads), dim3(64), 0, st>>>(
+        dv.desc.in, sh.n_q_heads, sh.n_kv_heads, (const uint4 *)dv.k_pool, dv.page_table, (const uint32_t *)q, nbr, n_idx, M,
+        k0s, l0, beta, clist, cap, visited, vis_words, dv.sel_ids, dv.sel_scores, dv.sel_rows, dv.counts, dv.head_M, c_lens,
+        out_ids, out_counts, ids_stride, dv.status);
+    return hipGetLastError();
+}
+
+} // namespace alaya
