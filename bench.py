@@ -290,6 +290,62 @@ def measure(name, args, steps, warmup, cold_steps, cpu_baseline, beta=None, dens
     return res
 
 
+def measure_diprs(args, name="range_256k", degree=32, beta=2.0, l0s=(64, 1024), reps=20):
+    """The approximate DIPR query on the graph index (Algorithm 1) beside the exact DIPR scan, same cache, same
+    query, no append: build time and size of the index, time per query, length of the list C, size of the
+    answer and the share of the exact answer that it holds."""
+    import numpy as np
+    import torch
+
+    import paper_2504_10326_amd as A
+    import workloads as wl
+
+    w = wl.config(name)
+    g = wl.generate(w)
+    n = w.lens[0]
+    c = A.Cache(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, max_seqs=1, max_batch=1, max_tokens_per_seq=n + 64,
+                max_batch_tokens=n + 64, n_phys_pages=g["n_phys_pages"],
+                phys_page_order=g["page_order"] if w.permute_pages else None)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda().view(torch.bfloat16)
+    c.append_kv(0, dev(g["K"][0]), dev(g["V"][0]))
+    q = dev(g["q"])
+    torch.cuda.synchronize()
+    t = time.perf_counter()
+    gr = c.build_graph(0, degree)
+    torch.cuda.synchronize()
+    build_ms = (time.perf_counter() - t) * 1e3
+    print(f"[bench] graph over {n} keys x {w.n_kv_heads} KV heads, degree {degree}: {build_ms:.0f} ms", file=sys.stderr, flush=True)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / reps * 1e6
+
+    out = torch.empty((1, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    scan_us = timed(lambda: c.sparse_attn([0], q, A.ALAYA_DIPR, beta=[beta], out=out))
+    ex = c.sparse_attn([0], q, A.ALAYA_DIPR, beta=[beta], ids_stride=n)
+    e_ids, e_cnt = ex[1].cpu().numpy()[0], ex[2].cpu().numpy()[0]
+    res = {"workload": name, "tokens": n, "degree": degree, "beta": beta, "graph_build_ms": build_ms,
+           "index_bytes": int(gr.index_mem.numel()), "exact_scan_us": scan_us,
+           "exact_answer_mean": float(e_cnt.mean()), "walks": []}
+    for l0 in l0s:
+        us = timed(lambda: c.diprs_attn(gr, q, beta, l0, out=out))
+        _, ids, cnt = c.diprs_attn(gr, q, beta, l0, ids_stride=n)
+        ids, cnt = ids.cpu().numpy()[0], cnt.cpu().numpy()[0]
+        lens = [len(c.debug_diprs_list(h)) for h in range(w.n_q_heads)]
+        rec = [len(np.intersect1d(ids[h, :cnt[h]], e_ids[h, :e_cnt[h]])) / max(1, int(e_cnt[h])) for h in range(w.n_q_heads)]
+        res["walks"].append({"l0": l0, "us_per_query": us, "list_len_mean": float(np.mean(lens)), "list_len_max": int(max(lens)),
+                             "answer_mean": float(cnt.mean()), "recall_of_exact_dipr": float(np.mean(rec)),
+                             "neighbours_examined_mean": float(np.mean(lens)) * degree})
+    gr.close()
+    c.close()
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -359,6 +415,7 @@ def main() -> int:
               "repaired_heads_per_step", "coarse", "pages", "roofline", "gather", "cold_cache", "cpu_baseline"):
         line[k] = head[k]
     line["per_config"] = per_config
+    line["diprs_vs_scan"] = None if args.no_per_config else measure_diprs(args)
     print(json.dumps(line))
     return 0
 

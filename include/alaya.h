@@ -264,6 +264,39 @@ int alaya_graph_info(const alaya_graph *g, int64_t *n_indexed, int32_t *degree, 
 int alaya_diprs_attn(alaya_cache *c, const alaya_graph *g, int n_q_heads, const void *q, float beta, int32_t l0,
                      const alaya_sparse_params *p, float *out, void *stream);
 
+/*
+ * The rule-based query optimizer (Sec. 6.2 "Query Optimizer", the workflow of its figure): which query type
+ * on which index type answers one layer's attention query.  Host code, no GPU work, no state.  The rules, in
+ * the paper's order:
+ *   1. context_len <= short_context                 -> full attention, no index
+ *   2. 0 < reused_prefix < context_len              -> the query carries the filter predicate
+ *                                                      "token position < reused_prefix" (n_visible)
+ *   3. gpu_budget_bytes >= coarse_bytes             -> top-k on the coarse-grained index
+ *   4. otherwise DIPR: the flat index (a scan) for layer 0, the fine-grained index (DIPRS on the graph) for
+ *      every other layer
+ * The paper fixes neither the short-context length nor what the coarse index needs on the GPU: both are the
+ * caller's (coarse_bytes = what keeping the blocks and their representatives on the GPU takes: for this
+ * library alaya_pool_bytes twice plus alaya_rep_bytes).  out->n_visible = context_len when no filter applies.
+ * Returns ALAYA_E_INVAL for null pointers, context_len <= 0 or a negative field.
+ */
+enum { ALAYA_QUERY_FULL = 0, ALAYA_QUERY_TOPK = 1, ALAYA_QUERY_DIPR = 2 };
+enum { ALAYA_INDEX_NONE = 0, ALAYA_INDEX_COARSE = 1, ALAYA_INDEX_FLAT = 2, ALAYA_INDEX_FINE = 3 };
+typedef struct alaya_plan_input {
+    int64_t context_len;      /* tokens of the stored context */
+    int64_t short_context;    /* contexts up to this length are attended in full */
+    int64_t reused_prefix;    /* tokens of the context that this request reuses; 0 or >= context_len: all */
+    int64_t gpu_budget_bytes; /* GPU memory the session may use */
+    int64_t coarse_bytes;     /* GPU memory the coarse-grained plan needs */
+    int32_t layer_id;         /* 0 = the first layer */
+    int32_t reserved;
+} alaya_plan_input;
+typedef struct alaya_plan {
+    int32_t query; /* ALAYA_QUERY_* */
+    int32_t index; /* ALAYA_INDEX_* */
+    int64_t n_visible;
+} alaya_plan;
+int alaya_plan_query(const alaya_plan_input *in, alaya_plan *out);
+
 /* Session.attention, dense: Eq. (1) over every cached token (same q / out layout as above). */
 int alaya_full_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, const void *q,
                     float scale, float *out, void *stream);

@@ -275,6 +275,20 @@ def sparse_attn(q: np.ndarray, K: np.ndarray, V: np.ndarray, mode: int, k: int =
     return {"out": out, "counts": counts, "ids": id_list, "scores": sc, "threads": rc}
 
 
+def plan(context_len: int, short_context: int, reused_prefix: int, gpu_budget: int, coarse_need: int, layer_id: int):
+    """The rule-based optimizer's workflow (Sec. 6.2 "Query Optimizer"): (query type, index type, visible prefix).
+
+    Short contexts get full attention.  A long context that is only partly reused is queried under the filter
+    "position < reused prefix".  With enough GPU memory for the blocks the plan is top-k on the coarse-grained
+    index; otherwise DIPR, on the flat index for the first layer and on the graph for every other layer."""
+    if context_len <= short_context:
+        return ("full", "none", context_len)
+    visible = reused_prefix if 0 < reused_prefix < context_len else context_len
+    if gpu_budget >= coarse_need:
+        return ("topk", "coarse", visible)
+    return ("dipr", "flat" if layer_id == 0 else "fine", visible)
+
+
 def full_attn(q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: Optional[float] = None,
               threads: int = 0) -> np.ndarray:
     return sparse_attn(q, K, V, FULL, scale=scale, want_ids=False, threads=threads)["out"]

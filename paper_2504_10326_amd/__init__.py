@@ -33,7 +33,7 @@ EXPORTS = (
     "alaya_sparse_attn", "alaya_decode_step", "alaya_sparse_attn_static", "alaya_full_attn", "alaya_poll_status",
     "alaya_last_error",
     "alaya_graph_bytes", "alaya_graph_build_bytes", "alaya_graph_build", "alaya_graph_destroy", "alaya_graph_info",
-    "alaya_diprs_attn",
+    "alaya_diprs_attn", "alaya_plan_query",
 )
 # include/alaya_debug.h
 DEBUG_EXPORTS = (
@@ -71,6 +71,20 @@ class SparseParams(ctypes.Structure):
 
 
 _lib = None
+
+
+class PlanInput(ctypes.Structure):
+    _fields_ = [("context_len", ctypes.c_int64), ("short_context", ctypes.c_int64), ("reused_prefix", ctypes.c_int64),
+                ("gpu_budget_bytes", ctypes.c_int64), ("coarse_bytes", ctypes.c_int64), ("layer_id", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
+
+
+class Plan(ctypes.Structure):
+    _fields_ = [("query", ctypes.c_int32), ("index", ctypes.c_int32), ("n_visible", ctypes.c_int64)]
+
+
+QUERY_FULL, QUERY_TOPK, QUERY_DIPR = 0, 1, 2
+INDEX_NONE, INDEX_COARSE, INDEX_FLAT, INDEX_FINE = 0, 1, 2, 3
 
 
 def lib() -> ctypes.CDLL:
@@ -128,6 +142,7 @@ def lib() -> ctypes.CDLL:
         L.alaya_graph_info.restype = i32
         L.alaya_diprs_attn.argtypes = [vp, vp, i32, vp, ctypes.c_float, i32, ctypes.POINTER(SparseParams), vp, vp]
         L.alaya_diprs_attn.restype = i32
+        L.alaya_plan_query.argtypes = [ctypes.POINTER(PlanInput), ctypes.POINTER(Plan)]; L.alaya_plan_query.restype = i32
         L.alaya_debug_diprs_list.argtypes = [vp, i32, vp, i64, vp]; L.alaya_debug_diprs_list.restype = i64
         _lib = L
     return _lib
@@ -326,6 +341,16 @@ def alaya_diprs_attn(handle: int, graph: int, n_q_heads: int, q, beta: float, l0
     p.ids_stride = ids_stride
     _check(lib().alaya_diprs_attn(handle, graph, n_q_heads, _ptr(q), beta, l0, ctypes.byref(p), _ptr(out),
                                   stream or None))
+
+
+def alaya_plan_query(context_len: int, short_context: int, reused_prefix: int, gpu_budget_bytes: int, coarse_bytes: int,
+                     layer_id: int) -> Tuple[int, int, int]:
+    """(query type, index type, n_visible) by the rule-based optimizer of Sec. 6.2."""
+    i, o = PlanInput(context_len, short_context, reused_prefix, gpu_budget_bytes, coarse_bytes, layer_id, 0), Plan()
+    rc = lib().alaya_plan_query(ctypes.byref(i), ctypes.byref(o))
+    if rc != 0:
+        raise AlayaError(rc, "invalid plan input")
+    return o.query, o.index, o.n_visible
 
 
 def alaya_poll_status(handle: int, stream=0) -> int:

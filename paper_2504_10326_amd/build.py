@@ -13,7 +13,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libalaya.so")
-SOURCES = ["api.hip", "score.hip", "select.hip", "attend.hip", "coarse.hip", "graph.hip"]
+SOURCES = ["api.hip", "score.hip", "select.hip", "attend.hip", "coarse.hip", "graph.hip", "plan.hip"]
 HEADERS = [os.path.join(CSRC, "alaya_internal.h"), os.path.join(CSRC, "score_page.h"), os.path.join(CSRC, "row_slice.h"),
            os.path.join(HERE, "..", "include", "alaya.h"), os.path.join(HERE, "..", "include", "alaya_debug.h")]
 # packed-fp32 instructions are switched off for all device code (hipcc's host pass warns that it

@@ -198,3 +198,22 @@ def test_bench_refuses_more_than_one_gpu_and_has_no_cpu_fallback():
     if not torch.cuda.is_available():
         r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")], capture_output=True, text=True)
         assert r.returncode != 0 and "no GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_plan_query_matches_the_oracle_on_a_grid():
+    """The optimizer is host code: the whole decision table is compared here, no GPU needed."""
+    import itertools
+
+    import oracle
+    qn = {A.QUERY_FULL: "full", A.QUERY_TOPK: "topk", A.QUERY_DIPR: "dipr"}
+    xn = {A.INDEX_NONE: "none", A.INDEX_COARSE: "coarse", A.INDEX_FLAT: "flat", A.INDEX_FINE: "fine"}
+    grid = itertools.product([1, 4096, 4097, 1 << 20], [0, 4096], [0, 1, 4096, 1 << 19, 1 << 20, 1 << 21],
+                             [0, 999, 1000, 1 << 40], [0, 1000], [0, 1, 31])
+    for n, short, prefix, budget, need, layer in grid:
+        q, x, vis = A.alaya_plan_query(n, short, prefix, budget, need, layer)
+        assert (qn[q], xn[x], vis) == oracle.plan(n, short, prefix, budget, need, layer), (n, short, prefix, budget, need, layer)
+    for bad in [(0, 1, 0, 0, 0, 0), (10, -1, 0, 0, 0, 0), (10, 1, -1, 0, 0, 0), (10, 1, 0, -1, 0, 0), (10, 1, 0, 0, -1, 0),
+                (10, 1, 0, 0, 0, -1)]:
+        with pytest.raises(A.AlayaError):
+            A.alaya_plan_query(*bad)
+    assert ctypes.sizeof(A.PlanInput) == 48 and ctypes.sizeof(A.Plan) == 16

@@ -641,3 +641,18 @@ def test_diprs_invariants_on_a_sparse_graph():
             assert ids.tolist() == sorted(int(c) for c in C if s[c] >= best - np.float32(2.0))
             if best == s.max():
                 assert set(ids.tolist()) <= exact
+
+
+def test_plan_follows_the_optimizer_workflow():
+    """Sec. 6.2 "Query Optimizer": the outcomes the text states, one per branch of the workflow."""
+    GB = 1 << 30
+    assert oracle.plan(2000, 4096, 0, 80 * GB, 10 * GB, 3) == ("full", "none", 2000)          # short: full attention
+    assert oracle.plan(2000, 4096, 500, 0, 10 * GB, 0) == ("full", "none", 2000)              # ... whatever else holds
+    assert oracle.plan(200000, 4096, 0, 80 * GB, 10 * GB, 3) == ("topk", "coarse", 200000)    # budget is enough
+    assert oracle.plan(200000, 4096, 0, 10 * GB, 10 * GB, 0) == ("topk", "coarse", 200000)
+    assert oracle.plan(200000, 4096, 0, 4 * GB, 10 * GB, 0) == ("dipr", "flat", 200000)       # limited: first layer scans
+    assert oracle.plan(200000, 4096, 0, 4 * GB, 10 * GB, 1) == ("dipr", "fine", 200000)       # ... the others walk the graph
+    assert oracle.plan(200000, 4096, 0, 4 * GB, 10 * GB, 31) == ("dipr", "fine", 200000)
+    assert oracle.plan(200000, 4096, 150000, 4 * GB, 10 * GB, 7) == ("dipr", "fine", 150000)  # partial reuse: filter
+    assert oracle.plan(200000, 4096, 150000, 40 * GB, 10 * GB, 7) == ("topk", "coarse", 150000)
+    assert oracle.plan(200000, 4096, 200000, 4 * GB, 10 * GB, 7)[2] == 200000                 # whole context reused: no filter
