@@ -157,11 +157,23 @@ def measure(name, args, steps, warmup, cold_steps, cpu_baseline, beta=None, dens
 
     kernels_us, warm_gbs, warm_pass_gbs, warm_main_s = per_kernel(kt)
     # The gather + attend kernel reads one V row per selected (head, token).
-    _, counts = c.sparse_attn(seqs, q, mode, out=out, want_counts=True, **kw)
+    stride = int(max(w.topk) + sum(window)) if w.mode == "topk" else 0
+    if stride:
+        _, sel, counts = c.sparse_attn(seqs, q, mode, out=out, ids_stride=stride, **kw)
+    else:
+        _, counts = c.sparse_attn(seqs, q, mode, out=out, want_counts=True, **kw)
     selected_rows = int(counts.sum().item())
+    # How many of those rows the G query heads of a KV group share (they read the same V rows): the heads
+    # select on their own, so a row that two heads of a group pick is fetched twice.
+    distinct_rows = None
+    if stride:
+        sel_h, cnt_h, G = sel.cpu().numpy(), counts.cpu().numpy(), w.n_q_heads // w.n_kv_heads
+        distinct_rows = sum(len(np.unique(np.concatenate([sel_h[r, h, :cnt_h[r, h]] for h in range(g0, g0 + G)])))
+                            for r in range(w.batch) for g0 in range(0, w.n_q_heads, G))
     attend_ms = kt["attend"]["sum_ms"] / max(1, kt["attend"]["launches"])
     gather_bytes = selected_rows * bytes_per_row
-    gather = {"kernel": "attend_kernel", "selected_rows": selected_rows, "bytes_per_launch": gather_bytes,
+    gather = {"kernel": "attend_kernel", "selected_rows": selected_rows, "distinct_rows_per_kv_group": distinct_rows,
+              "bytes_per_launch": gather_bytes,
               "avg_us": attend_ms * 1e3, "achieved": gather_bytes / (attend_ms * 1e-3) / 1e9, "unit": "GB/s",
               "frac": gather_bytes / (attend_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
