@@ -62,6 +62,11 @@ int64_t alaya_debug_scores(alaya_cache *c, float *out, void *stream);
  * -1 on error. */
 int64_t alaya_debug_repairs(alaya_cache *c, void *stream);
 
+/* Test hook: the walk of alaya_diprs_attn keeps its visited bits, the page-table row and the head of the list C
+ * in on-chip memory as far as they fit; `bytes` > 0 lowers what it may use (so that small tests reach the
+ * paths that large contexts take), 0 restores the default.  Results do not depend on it. */
+int alaya_debug_diprs_lds(alaya_cache *c, int bytes);
+
 /* Inspection hook: the list C that the last alaya_diprs_attn call grew for query head `head`, in the order in
  * which it grew: synchronises `stream`, copies the first min(length, cap) tokens to ids (HOST, optional) and
  * returns the length; -1 on error.  Valid until the next call on the cache or its scratch memory. */

@@ -38,7 +38,7 @@ EXPORTS = (
 # include/alaya_debug.h
 DEBUG_EXPORTS = (
     "alaya_set_profiling", "alaya_kernel_times", "alaya_set_tuning", "alaya_debug_scores", "alaya_debug_pages",
-    "alaya_debug_estimate", "alaya_debug_repairs", "alaya_debug_diprs_list",
+    "alaya_debug_estimate", "alaya_debug_repairs", "alaya_debug_diprs_list", "alaya_debug_diprs_lds",
 )
 
 
@@ -143,6 +143,7 @@ def lib() -> ctypes.CDLL:
         L.alaya_diprs_attn.argtypes = [vp, vp, i32, vp, ctypes.c_float, i32, ctypes.POINTER(SparseParams), vp, vp]
         L.alaya_diprs_attn.restype = i32
         L.alaya_plan_query.argtypes = [ctypes.POINTER(PlanInput), ctypes.POINTER(Plan)]; L.alaya_plan_query.restype = i32
+        L.alaya_debug_diprs_lds.argtypes = [vp, i32]; L.alaya_debug_diprs_lds.restype = i32
         L.alaya_debug_diprs_list.argtypes = [vp, i32, vp, i64, vp]; L.alaya_debug_diprs_list.restype = i64
         _lib = L
     return _lib
@@ -525,6 +526,9 @@ class Cache:
         alaya_diprs_attn(self.handle, graph.handle, self.cfg.n_q_heads, q, beta, l0, scale, out, ids, counts, ids_stride,
                          _stream(stream), window)
         return (out, ids, counts) if ids is not None else out
+
+    def debug_diprs_lds(self, nbytes: int) -> None:
+        _check(lib().alaya_debug_diprs_lds(self.handle, nbytes))
 
     def debug_diprs_list(self, head: int, stream=None):
         """The list C of the last diprs_attn call for one query head, as a numpy int32 array."""

@@ -184,7 +184,7 @@ hipError_t launch_graph_norm(const Shape &sh, const void *k_pool, const int32_t 
 hipError_t launch_diprs(const Shape &sh, const DeviceViews &dv, const void *q, const int32_t *nbr, int n_idx, int M,
                         const int32_t *k0s, int l0, float beta, uint2 *clist, int64_t cap, uint32_t *visited,
                         int64_t vis_words, int32_t *c_lens, int32_t *out_ids, int32_t *out_counts, int64_t ids_stride,
-                        hipStream_t st);
+                        int lds_limit, hipStream_t st);
 
 // Inspection (tests, measurement): the survivors' scores scattered into dense rows
 // out[score_off + head * head_stride + token]; the number of survivors of the call added to *total.

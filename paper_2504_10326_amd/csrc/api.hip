@@ -177,6 +177,7 @@ struct alaya_cache {
     bool scratch_ready;              // the must-be-zero words of the bound scratch were cleared by this cache
     int tune_ppw, tune_splits, tune_batch, tune_noprune;
     int estimate_mode; // alaya_debug_estimate
+    int diprs_lds_limit; // alaya_debug_diprs_lds
     int last_B, last_tiles_b;        // of the last sparse call, for the inspection hooks
     int64_t last_pages_a, last_pages_b; // pages of the last sparse call scored by the sample / the main pass
     // profiling
@@ -436,6 +437,7 @@ int alaya_create_cache(alaya_cache **out, const alaya_cache_config *cfg, void *k
     c->tune_batch = 0;
     c->tune_noprune = 0;
     c->estimate_mode = 0;
+    c->diprs_lds_limit = 0;
     c->last_B = c->last_tiles_b = 0;
     c->last_pages_a = c->last_pages_b = 0;
     c->prof = false;
@@ -1174,10 +1176,9 @@ int alaya_diprs_attn(alaya_cache *c, const alaya_graph *g, int n_q_heads, const 
     hipError_t e;
     {
         Timed tm(c, 1, st);
-        e = launch_fill_u32(visited, (size_t)n_q_heads * vis_words, 0u, st);
-        if (e == hipSuccess)
-            e = launch_diprs(sh, c->dv, q, g->nbr, (int)g->n_idx, g->degree, g->entry_dev, l0, beta, c->dv.blocks, cap, visited,
-                             vis_words, c_lens, p ? p->out_ids : nullptr, p ? p->out_counts : nullptr, p ? p->ids_stride : 0, st);
+        e = launch_diprs(sh, c->dv, q, g->nbr, (int)g->n_idx, g->degree, g->entry_dev, l0, beta, c->dv.blocks, cap, visited,
+                             vis_words, c_lens, p ? p->out_ids : nullptr, p ? p->out_counts : nullptr, p ? p->ids_stride : 0,
+                             c->diprs_lds_limit, st);
     }
     if (e != hipSuccess) return fail_hip(e, "DIPRS launch");
     int splits = c->tune_splits > 0 ? c->tune_splits : 16;
@@ -1187,6 +1188,13 @@ int alaya_diprs_attn(alaya_cache *c, const alaya_graph *g, int n_q_heads, const 
     if (e != hipSuccess) return fail_hip(e, "combine launch");
     c->last_B = 0; // (no survivor blocks to inspect after this call)
     c->last_tiles_b = 0;
+    return ALAYA_OK;
+}
+
+int alaya_debug_diprs_lds(alaya_cache *c, int bytes)
+{
+    if (!c || bytes < 0) return fail(ALAYA_E_INVAL, "bad arguments");
+    c->diprs_lds_limit = bytes;
     return ALAYA_OK;
 }
 

@@ -21,6 +21,8 @@
 #include "alaya_internal.h"
 #include "row_slice.h"
 
+#include <algorithm>
+
 namespace alaya {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_g;
@@ -197,23 +199,44 @@ hipError_t launch_graph_norm(const Shape &sh, const void *k_pool, const int32_t 
 //   nbr       [H_kv][n_idx][M] neighbour lists (-1 = none)
 //   k0s       [H_kv] entry point of each KV head's graph
 //   clist     [H_q][cap] the list C as (score bits, token) pairs, in the order in which it grew
-//   visited   [H_q][words] one bit per token, zero on entry
+//   visited   [H_q][words] one bit per token, zero on entry; used only when the bits do not fit the LDS
+//   Mp        M rounded up to a power of two: 64 / Mp entries of C are visited side by side
+//   lds       how the workgroup's dynamic LDS is divided (DiprsLds, chosen by the launcher)
 // The answer - the window's tokens, then every entry of C within beta of the best - goes to the
 // selected-token arrays that the gather kernel reads.
+//
+// A visit is a chain of dependent reads (list entry -> neighbour list -> visited bits -> key rows), so the
+// walk is bound by latency, and everything that can be kept close is: the visited bits, the sequence's row
+// of the page table and the first tokens of C sit in LDS (as far as they fit: gfx950 has 160 KB), the
+// neighbour lists of the next entries are fetched while this visit's keys are scored, and with M <= 32
+// several consecutive entries of C are visited at once (lane = (entry, neighbour), which is the sequential
+// order; a key that two of those entries share goes to the earlier one, as it would one after the other).
+struct DiprsLds {
+    int vis_words; // visited bits kept in LDS (0: in global memory)
+    int pt_pages;  // page-table entries kept in LDS (0: read from global memory)
+    int list;      // leading entries of C mirrored in LDS
+};
+
 template <int D>
-__global__ __launch_bounds__(64) void diprs_kernel(const ReqDesc dsc, int H_q, int H_kv, const uint4 *__restrict__ k_pool,
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 2))) void diprs_kernel(const ReqDesc dsc, int H_q, int H_kv, const uint4 *__restrict__ k_pool,
                                                    const int32_t *__restrict__ page_table, const uint32_t *__restrict__ qw,
-                                                   const int32_t *__restrict__ nbr, int n_idx, int M,
+                                                   const int32_t *__restrict__ nbr, int n_idx, int M, int Mp,
                                                    const int32_t *__restrict__ k0s, int l0, float beta,
-                                                   uint2 *__restrict__ clist, int64_t cap, uint32_t *__restrict__ visited,
+                                                   uint2 *clist, int64_t cap, uint32_t *visited,
                                                    int64_t vis_words, int32_t *__restrict__ sel_ids,
                                                    float *__restrict__ sel_scores, int32_t *__restrict__ sel_rows,
                                                    int32_t *__restrict__ counts, float *__restrict__ head_M,
                                                    int32_t *__restrict__ c_lens, int32_t *__restrict__ out_ids,
                                                    int32_t *__restrict__ out_counts, int64_t ids_stride,
-                                                   int32_t *__restrict__ status)
+                                                   int32_t *__restrict__ status, const DiprsLds lds)
 {
     constexpr int NC = D / 8;
+    extern __shared__ __attribute__((aligned(16))) uint32_t dyn_lds[];
+    __shared__ __attribute__((aligned(16))) int32_t kk[64];
+    uint32_t *vis_lds = dyn_lds;
+    int32_t *pt_lds = (int32_t *)(dyn_lds + lds.vis_words);
+    int32_t *c_lds = pt_lds + lds.pt_pages;
+    const int kListLds = lds.list;
     const int h = blockIdx.x, lane = threadIdx.x;
     const int G = H_q / H_kv, kvh = h / G;
     const int32_t *pt_row = page_table + dsc.pt_off;
@@ -225,14 +248,24 @@ __global__ __launch_bounds__(64) void diprs_kernel(const ReqDesc dsc, int H_q, i
     int32_t *rows = sel_rows + (size_t)dsc.score_off + (size_t)h * dsc.head_stride;
     const int32_t *adj = nbr + (size_t)kvh * n_idx * M;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    const bool lds_bits = lds.vis_words > 0, lds_pt = lds.pt_pages > 0; // (uniform)
+    for (int i = lane; i < lds.vis_words; i += 64) vis_lds[i] = 0u;
+    for (int i = lane; i < lds.pt_pages; i += 64) pt_lds[i] = pt_row[i];
+    auto page_of = [&](int j) { return lds_pt ? pt_lds[j >> 6] : pt_row[j >> 6]; };
 
     // q . k_j in fp32: one fused multiply-add per channel, channels in order
     auto score = [&](int j) {
+        // all sixteen loads of the key first (a barrier for the instruction scheduler keeps them together:
+        // issued one by one, each behind the use of the one before, they cost sixteen memory latencies)
+        uint4 w[NC];
+        const uint4 *kp = k_pool + ((size_t)page_of(j) * H_kv + kvh) * (size_t)(NC * 64) + (j & 63);
+#pragma unroll
+        for (int c = 0; c < NC; ++c) w[c] = kp[(size_t)c * 64];
+        __builtin_amdgcn_sched_barrier(0);
         float acc = 0.f;
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-            const uint4 w = *key_word(k_pool, pt_row, H_kv, kvh, NC, j, c);
-            const uint32_t kw[4] = {w.x, w.y, w.z, w.w};
+            const uint32_t kw[4] = {w[c].x, w[c].y, w[c].z, w[c].w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const uint32_t qq = q[c * 4 + e];
@@ -242,11 +275,25 @@ __global__ __launch_bounds__(64) void diprs_kernel(const ReqDesc dsc, int H_q, i
         }
         return acc;
     };
-    auto row_of = [&](int j) { return pt_row[j >> 6] * kPageTokens + (j & 63); };
+    auto row_of = [&](int j) { return page_of(j) * kPageTokens + (j & 63); };
     auto wave_max = [&](float x) {
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
         return x;
+    };
+    // The list and the global visited bits were written by this wavefront a moment ago (the bits with atomics
+    // that are carried out in the L2): they are read back past the L1.
+    auto c_token = [&](int i) {
+        return i < kListLds ? c_lds[i]
+                            : (int)(__hip_atomic_load((const unsigned long long *)&C[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32);
+    };
+    auto seen = [&](int k) {
+        const uint32_t w = lds_bits ? vis_lds[k >> 5] : __hip_atomic_load(&vis[k >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return (w & (1u << (k & 31))) != 0u;
+    };
+    auto mark = [&](int k) { // (tryAppend marks k as visited whether or not it appends it)
+        if (lds_bits) atomicOr(&vis_lds[k >> 5], 1u << (k & 31));
+        else atomicOr(&vis[k >> 5], 1u << (k & 31));
     };
 
     // The window (Sec. 7.1): always attended, seeds the best so far, takes no part in the walk.
@@ -276,43 +323,76 @@ __global__ __launch_bounds__(64) void diprs_kernel(const ReqDesc dsc, int H_q, i
         const float s0 = score(k0); // (every lane the same)
         if (lane == 0) {
             C[0] = make_uint2(__float_as_uint(s0), (uint32_t)k0);
-            atomicOr(&vis[k0 >> 5], 1u << (k0 & 31));
+            c_lds[0] = k0;
+            mark(k0);
         }
         best = fmaxf(best, s0);
         len = 1;
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    for (int i = 0; i < len; ++i) { // len never exceeds the number of indexed tokens: every key enters C at most once
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-        // (the list and the visited bits were written by this wavefront a moment ago, the bits with atomics
-        // that are carried out in the L2: both are read back past the L1)
-        const int c = (int)(__hip_atomic_load((const unsigned long long *)&C[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32);
-        const int k = lane < M ? adj[(size_t)c * M + lane] : -1;
+
+    const int E = 64 / Mp;                       // entries of C visited side by side
+    const int ent = lane / Mp, t = lane % Mp;    // this lane's entry among them, and its neighbour
+    auto neighbour = [&](int idx) { return adj[(size_t)c_token(idx) * M + t]; };
+    int nb = ent < len && t < M ? neighbour(ent) : -1;
+    int cnt = 0;
+    for (int i = 0; i < len; i += cnt) { // len never exceeds the number of indexed tokens: every key enters C at most once
+        const int len0 = len;
+        cnt = min(E, len0 - i); // this round visits the entries i .. i + cnt - 1
+        const int k = nb;
+        // the neighbour lists of the entries after these, as far as the list is known already
+        const int idx_next = i + cnt + ent;
+        nb = idx_next < len0 && t < M ? neighbour(idx_next) : -1;
         bool fresh = k >= 0 && k < n_idx && !in_window(dsc, k);
-        if (fresh) fresh = (__hip_atomic_load(&vis[k >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & (1u << (k & 31))) == 0u;
-        if (fresh) atomicOr(&vis[k >> 5], 1u << (k & 31)); // mark k as visited (tryAppend)
+        if (fresh) fresh = !seen(k);
+        if (E > 1) { // a key shared with an earlier entry of this round is that entry's
+            kk[lane] = fresh ? k : -1;
+            const int lim = ent * Mp; // lanes below this one's entry
+            bool dup = false;
+            // (all sixteen 16-byte reads are issued at once: a loop of dependent LDS reads would cost more
+            // than the round's memory latency)
+            int4 v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) v[u] = ((const int4 *)kk)[u];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                dup |= (4 * u + 0 < lim && v[u].x == k) | (4 * u + 1 < lim && v[u].y == k) | (4 * u + 2 < lim && v[u].z == k) |
+                       (4 * u + 3 < lim && v[u].w == k);
+            }
+            fresh = fresh && !dup;
+        }
+        if (fresh) mark(k);
         const float s = fresh ? score(k) : -INFINITY;
         const unsigned long long U = __ballot(fresh);
-        if (U == 0ull) continue;
-        // what the sequential order decides: the best inner product when this neighbour's turn comes ...
-        float pm = s;
+        if (U != 0ull) {
+            // what the sequential order decides: the best inner product when this neighbour's turn comes ...
+            float pm = s;
 #pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const float t = __shfl_up(pm, o);
-            if (lane >= o) pm = fmaxf(pm, t);
+            for (int o = 1; o < 64; o <<= 1) {
+                const float x = __shfl_up(pm, o);
+                if (lane >= o) pm = fmaxf(pm, x);
+            }
+            float before = __shfl_up(pm, 1);
+            before = lane == 0 ? best : fmaxf(best, before);
+            // ... and whether the list is still at or under the capacity threshold
+            const int r = __popcll(U & lt_mask);
+            const bool app = fresh && (len + r <= l0 || s >= before - beta);
+            const unsigned long long A = __ballot(app);
+            const int at = len + __popcll(A & lt_mask);
+            if (app && at < cap) { // (at < cap always: a key enters C once)
+                C[at] = make_uint2(__float_as_uint(s), (uint32_t)k);
+                if (at < kListLds) c_lds[at] = k;
+            }
+            len = min(len + __popcll(A), (int)cap);
+            best = fmaxf(best, wave_max(app ? s : -INFINITY));
+            // (entries beyond the LDS mirror are read back from global memory: their stores must have arrived)
+            if (len > kListLds) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            // entries of the next round that this round appended
+            if (idx_next >= len0 && idx_next < len && t < M) nb = neighbour(idx_next);
         }
-        float before = __shfl_up(pm, 1);
-        before = lane == 0 ? best : fmaxf(best, before);
-        // ... and whether the list is still at or under the capacity threshold
-        const int r = __popcll(U & lt_mask);
-        const bool app = fresh && (len + r <= l0 || s >= before - beta);
-        const unsigned long long A = __ballot(app);
-        const int at = len + __popcll(A & lt_mask);
-        if (app && at < cap) C[at] = make_uint2(__float_as_uint(s), (uint32_t)k); // (at < cap always: a key enters C once)
-        len = min(len + __popcll(A), (int)cap);
-        best = fmaxf(best, wave_max(app ? s : -INFINITY));
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     // the answer: every c in C with q.c >= best - beta
     const float thr = best - beta;
@@ -345,13 +425,41 @@ __global__ __launch_bounds__(64) void diprs_kernel(const ReqDesc dsc, int H_q, i
 hipError_t launch_diprs(const Shape &sh, const DeviceViews &dv, const void *q, const int32_t *nbr, int n_idx, int M,
                         const int32_t *k0s, int l0, float beta, uint2 *clist, int64_t cap, uint32_t *visited,
                         int64_t vis_words, int32_t *c_lens, int32_t *out_ids, int32_t *out_counts, int64_t ids_stride,
-                        hipStream_t st)
+                        int lds_limit, hipStream_t st)
 {
     if (sh.dtype != 0 || sh.head_dim != 128 || M < 1 || M > 64) return hipErrorInvalidValue;
-    diprs_kernel<128><<<dim3((unsigned)sh.n_q_heads), dim3(64), 0, st>>>(
-        dv.desc.in, sh.n_q_heads, sh.n_kv_heads, (const uint4 *)dv.k_pool, dv.page_table, (const uint32_t *)q, nbr, n_idx, M,
+    int Mp = 1;
+    while (Mp < M) Mp <<= 1;
+    // Divide the workgroup's LDS: the visited bits first, then the page-table row, the rest mirrors the list.
+    static int max_lds = 0; // what a workgroup of this kernel may have, asked for once
+    if (max_lds == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess)
+            v = 64 << 10;
+        if (v > (64 << 10) &&
+            hipFuncSetAttribute((const void *)diprs_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, v - 1024) != hipSuccess) {
+            (void)hipGetLastError();
+            v = 64 << 10;
+        }
+        max_lds = v;
+    }
+    int64_t budget = (lds_limit > 0 && lds_limit < max_lds ? lds_limit : max_lds) - 1024; // (the static part and slack)
+    const ReqDesc &d = dv.desc.in;
+    DiprsLds lds{0, 0, 0};
+    const int64_t bits = ((int64_t)n_idx + 31) / 32 * 4;
+    if (bits + 8192 <= budget) { lds.vis_words = (int)(bits / 4); budget -= bits; }
+    if ((int64_t)d.n_pages * 4 + 4096 <= budget) { lds.pt_pages = d.n_pages; budget -= (int64_t)d.n_pages * 4; }
+    lds.list = (int)std::min<int64_t>(budget / 4, (int64_t)n_idx + 1);
+    if (lds.list < 1) lds.list = 1; // (entry 0 is always mirrored)
+    const size_t dyn = ((size_t)lds.vis_words + lds.pt_pages + lds.list) * 4;
+    if (lds.vis_words == 0) {
+        const hipError_t e = launch_fill_u32(visited, (size_t)sh.n_q_heads * vis_words, 0u, st);
+        if (e != hipSuccess) return e;
+    }
+    diprs_kernel<128><<<dim3((unsigned)sh.n_q_heads), dim3(64), dyn, st>>>(
+        dv.desc.in, sh.n_q_heads, sh.n_kv_heads, (const uint4 *)dv.k_pool, dv.page_table, (const uint32_t *)q, nbr, n_idx, M, Mp,
         k0s, l0, beta, clist, cap, visited, vis_words, dv.sel_ids, dv.sel_scores, dv.sel_rows, dv.counts, dv.head_M, c_lens,
-        out_ids, out_counts, ids_stride, dv.status);
+        out_ids, out_counts, ids_stride, dv.status, lds);
     return hipGetLastError();
 }
 

@@ -247,7 +247,7 @@ hipError_t launch_graph_norm(const Shape &sh, const void *, const int32_t *, int
 }
 hipError_t launch_diprs(const Shape &sh, const DeviceViews &dv, const void *q, const int32_t *nbr, int n_idx, int M,
                         const int32_t *k0s, int l0, float beta, uint2 *clist, int64_t cap, uint32_t *visited, int64_t vis_words,
-                        int32_t *c_lens, int32_t *, int32_t *, int64_t, hipStream_t)
+                        int32_t *c_lens, int32_t *, int32_t *, int64_t, int, hipStream_t)
 {
     ++g_launches;
     const ReqDesc d = dv.desc.in;

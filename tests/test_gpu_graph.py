@@ -133,7 +133,8 @@ def _check_walk(w, g, c, gr, l0, beta, window=(0, 0), scale=0.0):
 
 
 @pytest.mark.parametrize("n,M,l0,beta", [(64, 8, 0, 1.0), (700, 16, 32, 2.0), (4133, 32, 64, 2.0), (4133, 32, 0, 4.0),
-                                         (2500, 64, 500, 0.0), (4133, 8, 4133, 3.0)])
+                                         (2500, 64, 500, 0.0), (4133, 8, 4133, 3.0), (3000, 5, 200, 2.0), (3000, 1, 50, 8.0),
+                                         (3000, 33, 100, 2.0), (9000, 4, 9000, 2.0)])
 def test_diprs_list_and_answer_match_oracle(n, M, l0, beta):
     w, g, c = _setup(n, seed=100 + n)
     gr = c.build_graph(0, M)
@@ -141,6 +142,23 @@ def test_diprs_list_and_answer_match_oracle(n, M, l0, beta):
     print(f"|C| {lens.min()}..{lens.max()}, answers {sizes.min()}..{sizes.max()}", flush=True)
     assert lens.max() > 1 or n == 1
     gr.close()
+    c.close()
+
+
+@pytest.mark.parametrize("lds_bytes", [3072, 16384, 40000])
+def test_diprs_with_less_on_chip_memory(lds_bytes):
+    """What a walk over a very long context does - visited bits and page table in global memory, a list far
+    longer than its on-chip mirror - reached on a small one by lowering the on-chip budget: same list, same answer."""
+    w, g, c = _setup(9000, seed=13)
+    c.debug_diprs_lds(lds_bytes)
+    for M in (4, 32):
+        gr = c.build_graph(0, M)
+        lens, _ = _check_walk(w, g, c, gr, 9000, 2.0, window=(4, 100))
+        print(f"M={M}: |C| {lens.min()}..{lens.max()}", flush=True)
+        assert lens.max() > 1500
+        _check_walk(w, g, c, gr, 64, 2.0)
+        gr.close()
+    c.debug_diprs_lds(0)
     c.close()
 
 
