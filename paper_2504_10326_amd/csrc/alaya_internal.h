@@ -44,8 +44,11 @@ struct ReqDesc {
     int32_t hist_cap;      // top-k: what one sample-pass workgroup (four sampled pages) may add to one bucket, at most
     int32_t pm_stride;     // coarse index: bytes between the KV heads' rows of this request's page mask
     int64_t pm_off;        // coarse index: first byte of this request's page mask
+    int32_t short_ok;      // top-k: fewer than k candidates is no failure, all of them are taken (coarse index without a bound)
+    int32_t est_cand;      // coarse index: tokens in the pages a head chose (64 P); > 0: the rank that the estimated bound is
+                           // read at follows the share of them that the head's sample really holds
 };
-static_assert(sizeof(ReqDesc) == 88, "ReqDesc layout");
+static_assert(sizeof(ReqDesc) == 96, "ReqDesc layout");
 
 // How the kernels get at the request descriptors.  A call of one request carries its descriptor in
 // the kernel arguments, which saves the host-to-device copy (a 4 us blit ahead of the first kernel of
@@ -123,8 +126,9 @@ hipError_t launch_append_step(const Shape &sh, const DeviceViews &dv, void *k_po
 
 // Sample pass: statistics of every S-th page (histogram for top-k, maximum for DIPR) and, in a decode
 // step, the append of the newest token.  total_tiles may be 0 (nothing to launch).
+// coarse: only the pages marked in dv.pmask are scored, and a head counts only tokens of pages it chose itself.
 hipError_t launch_sample(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles, int mode,
-                         hipStream_t st);
+                         bool coarse, hipStream_t st);
 // The bound of every head from the sample's statistics; mode: 0 top-k, 1 DIPR.
 hipError_t launch_tau(const Shape &sh, const DeviceViews &dv, int B, int mode, hipStream_t st);
 // Main pass: every page against dv.tau (repair = false), or - only for the workgroups with a head marked
@@ -148,7 +152,6 @@ struct SelectIO {
     int32_t *rows;          // their V-pool rows, or null (not wanted)
     int32_t *counts;        // [request * head]
     float *head_M;          // [request * head]
-    bool short_ok;          // top-k: fewer than k candidates is no failure, all of them are taken
 };
 hipError_t launch_select(const Shape &sh, const DeviceViews &dv, const SelectIO &io, int B, int mode, bool redo,
                          int batch_blocks, int32_t *out_ids, int32_t *out_counts, int64_t ids_stride, hipStream_t st);

@@ -813,24 +813,41 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
         // (guaranteed bound).  Powers of two, at most 32.
         int S = 1;
         d.k_est = 0;
-        if (!c->tune_noprune && pages >= 4 && !coarse) { // (the coarse index cuts the candidates down itself)
+        // Through the coarse index top-k ranks the tokens of the P pages a head chose: at least cand of them,
+        // whichever pages those are.  With fewer than k such tokens possible, everything found is taken and
+        // nothing is pruned; otherwise the estimated bound works as it does on the whole sequence, with the
+        // chosen pages in the place of all pages.
+        int64_t rank_pages = pages, rank_tokens = n_out;
+        if (coarse) {
+            rank_pages = std::min<int64_t>(p->coarse_pages[b], pages);
+            rank_tokens = kPageTokens * (rank_pages - 1) + 1 - d.nwin;
+            d.short_ok = 1;
+        }
+        if (!c->tune_noprune && pages >= 4) {
             // (never when top-k takes every token outside the window: nothing checks the bound then)
-            if (p->mode == ALAYA_TOPK && estimate && d.k >= 512 && d.k < n_out && pages >= 64) {
+            // (through the coarse index only when the chosen pages hold more tokens than the selection keeps in
+            // registers: below that a bound saves the selection nothing and costs a sample pass)
+            if (p->mode == ALAYA_TOPK && estimate && d.k >= 512 && d.k < rank_tokens && rank_pages >= 64 &&
+                (!coarse || rank_pages * kPageTokens > 16384)) {
+                d.short_ok = 0; // at least k tokens can be ranked: fewer survivors means that the bound was too high
+                if (coarse) d.est_cand = (int32_t)(rank_pages * kPageTokens);
                 // Estimated bound: a 1-in-S sample holds about mu = k / S of the k best
                 // scores, so its (mu + 6 sqrt(mu) + 8)-th largest score lies below the true threshold
                 // unless the sample is far from representative - which the selection detects and
                 // repairs.  The main pass then writes about k (1 + 6 / sqrt(mu)) survivors whatever S
                 // is, so S only has to keep mu at 64 or more.
                 while (S < 32 && d.k / (2 * S) >= 64) S *= 2;
-                while (S > 1 && pages / S < 2) S /= 2;
+                while (S > 1 && rank_pages / S < 2) S /= 2;
                 const double mu = (double)d.k / S;
                 d.k_est = c->estimate_mode == 2 ? 1 : (int32_t)(mu + 6.0 * std::sqrt(mu) + 8.0);
                 if (d.k_est > d.k) d.k_est = d.k;
                 if (S > 1) any_est = true; else d.k_est = 0;
                 // a sample-pass workgroup (four sampled pages) adds at most this much to one bucket: four
                 // times what all buckets down to the estimate's rank get from four pages on average, 8 at least
-                const int64_t sampled_pages = (pages + S - 1) / S;
+                const int64_t sampled_pages = (rank_pages + S - 1) / S;
                 d.hist_cap = (int32_t)std::max<int64_t>(8, (16 * (int64_t)d.k_est + sampled_pages - 1) / sampled_pages);
+            } else if (coarse) {
+                // (no bound: every token of a chosen page survives)
             } else if (p->mode == ALAYA_TOPK) {
                 while (S < 32 && (int64_t)(2 * S) * (2 * S) * d.k <= n && (int64_t)2 * S * d.k * 2 <= n) S *= 2;
                 while (S > 1 && pages / S < 2) S /= 2;
@@ -920,7 +937,7 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
         e = launch_fill_u32((uint32_t *)(sbase + S.pmask), (size_t)((pm_off + 3) / 4), 0u, st);
         if (e == hipSuccess) e = launch_coarse_score(sh, dv, pd, B, q, c->rep_pool, tiles_p, block_stride_p, st);
         const SelectIO pio{pd, dv.blocks, block_stride_p, pg_ids, (float *)(sbase + S.pg_scores), nullptr, pg_counts,
-                           (float *)(sbase + S.pg_M), false};
+                           (float *)(sbase + S.pg_M)};
         if (e == hipSuccess)
             e = launch_select(sh, dv, pio, B, ALAYA_TOPK, false, c->tune_batch, p->out_pages, nullptr, p->pages_stride, st);
         if (e == hipSuccess) e = launch_page_mask(sh, dv, pd, B, pg_ids, pg_counts, (uint32_t *)(sbase + S.pmask), st);
@@ -929,7 +946,7 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
     {
         Timed tm(c, 6, st);
         if (fused_k) dv.fused = FusedAppend{(uint4 *)c->k_pool, (uint4 *)c->v_pool, (const uint4 *)fused_k, (const uint4 *)fused_v};
-        e = launch_sample(sh, dv, B, q, tiles, p->mode, st);
+        e = launch_sample(sh, dv, B, q, tiles, p->mode, coarse, st);
         dv.fused = FusedAppend{nullptr, nullptr, nullptr, nullptr};
         if (e == hipSuccess) *appended = fused_k != nullptr && tiles > 0;
         if (e == hipSuccess) e = launch_tau(sh, dv, B, p->mode, st);
@@ -942,11 +959,10 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
     if (e != hipSuccess) { c->scratch_ready = false; return fail_hip(e, "score launch"); }
     {
         Timed tm(c, 1, st);
-        const SelectIO io{dv.desc, dv.blocks, block_stride, dv.sel_ids, dv.sel_scores, dv.sel_rows, dv.counts, dv.head_M,
-                          coarse};
+        const SelectIO io{dv.desc, dv.blocks, block_stride, dv.sel_ids, dv.sel_scores, dv.sel_rows, dv.counts, dv.head_M};
         e = launch_select(sh, dv, io, B, p->mode, false, c->tune_batch, p->out_ids, p->out_counts, p->ids_stride, st);
         // repair of the heads whose estimated bound lost tokens (normally none: both launches are idle)
-        if (e == hipSuccess && any_est) e = launch_score(sh, dv, B, q, tiles_b, cp, true, p->mode, false, st);
+        if (e == hipSuccess && any_est) e = launch_score(sh, dv, B, q, tiles_b, cp, true, p->mode, coarse, st);
         if (e == hipSuccess && any_est)
             e = launch_select(sh, dv, io, B, p->mode, true, c->tune_batch, p->out_ids, p->out_counts, p->ids_stride, st);
     }

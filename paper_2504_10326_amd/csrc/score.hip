@@ -128,7 +128,8 @@ __global__ __launch_bounds__(256) void sample_kernel(const ReqDesc *__restrict__
                                                       int B, const int32_t *__restrict__ page_table,
                                                       const uint32_t *__restrict__ qw, const uint4 *__restrict__ k_pool,
                                                       uint32_t *__restrict__ hist, uint32_t *__restrict__ sample_max,
-                                                      int H_kv, int mode, const FusedAppend fa)
+                                                      int H_kv, int mode, const FusedAppend fa,
+                                                      const uint8_t *__restrict__ pmask)
 {
     const Descs desc{desc_mem, desc0, desc_n};
     constexpr int NC = D * (DT == 0 ? 2 : 4) / 16;
@@ -162,6 +163,13 @@ __global__ __launch_bounds__(256) void sample_kernel(const ReqDesc *__restrict__
 #pragma unroll
     for (int g = 0; g < G; ++g) lmax[g] = -INFINITY;
 
+    // Coarse index: a page that no head of the group chose is not read, and a head counts only the tokens of
+    // pages it chose itself (the sample then is 1-in-S of every head's own candidates).
+    uint32_t chosen = 0xFFu;
+    if (pmask && p < dsc.n_pages) {
+        chosen = pmask[(size_t)dsc.pm_off + (size_t)kvh * dsc.pm_stride + p];
+        if (chosen == 0u) p = dsc.n_pages;
+    }
     if (p < dsc.n_pages) {
         const int phys = page_table[dsc.pt_off + p];
         const uint4 *kp = k_pool;
@@ -191,7 +199,7 @@ __global__ __launch_bounds__(256) void sample_kernel(const ReqDesc *__restrict__
         for (int g = 0; g < G; ++g) {
             if (!valid) continue;
             lmax[g] = acc[g];
-            if (hist_on && every_sth && !win) {
+            if (hist_on && every_sth && !win && ((chosen >> g) & 1u)) {
                 const uint32_t bin = ord_key(acc[g]) >> 21;
                 atomicAdd(&lhist[g][bin >> 1], 1u << ((bin & 1u) * 16u));
             }
@@ -233,14 +241,15 @@ __global__ __launch_bounds__(256) void sample_kernel(const ReqDesc *__restrict__
 
 template <int DT, int D>
 static hipError_t launch_sample_g(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles,
-                                  int mode, hipStream_t st)
+                                  int mode, bool coarse, hipStream_t st)
 {
     const int G = sh.n_q_heads / sh.n_kv_heads;
     const dim3 grid((unsigned)(total_tiles * sh.n_kv_heads)), block(256);
 #define ALAYA_SAMPLE(GG)                                                                                      \
     sample_kernel<DT, D, GG><<<grid, block, 0, st>>>(dv.desc.mem, dv.desc.in, dv.desc.n, B, dv.page_table,     \
                                                      (const uint32_t *)q, (const uint4 *)dv.k_pool, dv.hist,  \
-                                                     dv.sample_max, sh.n_kv_heads, mode, dv.fused)
+                                                     dv.sample_max, sh.n_kv_heads, mode, dv.fused,           \
+                                                     coarse ? dv.pmask : nullptr)
     switch (G) {
     case 1: ALAYA_SAMPLE(1); break;
     case 2: ALAYA_SAMPLE(2); break;
@@ -253,15 +262,15 @@ static hipError_t launch_sample_g(const Shape &sh, const DeviceViews &dv, int B,
 }
 
 hipError_t launch_sample(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles, int mode,
-                         hipStream_t st)
+                         bool coarse, hipStream_t st)
 {
     if (total_tiles <= 0) return hipSuccess;
     if (sh.dtype == 0) {
-        if (sh.head_dim == 128) return launch_sample_g<0, 128>(sh, dv, B, q, total_tiles, mode, st);
-        if (sh.head_dim == 64) return launch_sample_g<0, 64>(sh, dv, B, q, total_tiles, mode, st);
+        if (sh.head_dim == 128) return launch_sample_g<0, 128>(sh, dv, B, q, total_tiles, mode, coarse, st);
+        if (sh.head_dim == 64) return launch_sample_g<0, 64>(sh, dv, B, q, total_tiles, mode, coarse, st);
     } else {
-        if (sh.head_dim == 128) return launch_sample_g<1, 128>(sh, dv, B, q, total_tiles, mode, st);
-        if (sh.head_dim == 64) return launch_sample_g<1, 64>(sh, dv, B, q, total_tiles, mode, st);
+        if (sh.head_dim == 128) return launch_sample_g<1, 128>(sh, dv, B, q, total_tiles, mode, coarse, st);
+        if (sh.head_dim == 64) return launch_sample_g<1, 64>(sh, dv, B, q, total_tiles, mode, coarse, st);
     }
     return hipErrorInvalidValue;
 }
@@ -328,7 +337,16 @@ __global__ __launch_bounds__(kSelectThreads) void tau_kernel(const ReqDesc *__re
     // The estimated bound: the sample's k_est-th largest score, k_est being the share of k that a
     // 1-in-S sample is expected to hold plus a wide margin.  Nothing guarantees it; the selection
     // checks the survivor count against k and has the head repaired if it fell short.
-    const int ke = dsc.k_est;
+    int ke = dsc.k_est;
+    if (dsc.est_cand > 0 && ke > 1) {
+        // Through the coarse index the sample is every S-th page among the pages the head chose - about P / S of
+        // them, but the number varies from head to head, and with it the share of the k best that the sample
+        // holds.  The histogram's total says how large the sample is.
+        int total = 0;
+        for (int w = 0; w < kSelectThreads / 64; ++w) total += wtot[w];
+        const float mu = (float)dsc.k * (float)total / (float)dsc.est_cand;
+        ke = min(dsc.k, (int)(mu + 6.f * sqrtf(mu) + 8.f));
+    }
     if (ke > 0 && above < ke && above + c0 + c1 >= ke) {
         const bool first = above + c0 >= ke;
         found_est = first ? b0 : b0 - 1;
@@ -545,7 +563,8 @@ static hipError_t launch_score_cp(const Shape &sh, const DeviceViews &dv, int B,
                        total_blocks, dv.head_maxkey, dv.pmask)
 #define ALAYA_MAIN(CPP)                                                                                       \
     do {                                                                                                      \
-        if (coarse) ALAYA_MAIN_K(CPP, false, true);                                                           \
+        if (coarse && repair) ALAYA_MAIN_K(CPP, true, true);                                                  \
+        else if (coarse) ALAYA_MAIN_K(CPP, false, true);                                                      \
         else if (repair) ALAYA_MAIN_K(CPP, true, false);                                                      \
         else ALAYA_MAIN_K(CPP, false, false);                                                                 \
     } while (0)

@@ -223,7 +223,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
     const uint2 *__restrict__ blocks, int64_t block_stride, uint32_t *__restrict__ head_maxkey,
     uint32_t *__restrict__ fail, uint32_t *__restrict__ any_fail, int redo, int batch_blocks,
     const int32_t *__restrict__ page_table, int32_t *__restrict__ sel_ids, int32_t *__restrict__ sel_rows,
-    int short_ok, float *__restrict__ sel_scores, int32_t *__restrict__ counts,
+    float *__restrict__ sel_scores, int32_t *__restrict__ counts,
     float *__restrict__ head_M, int32_t *__restrict__ out_ids, int32_t *__restrict__ out_counts, int64_t ids_stride,
     int32_t *__restrict__ status, uint32_t *__restrict__ repairs)
 {
@@ -336,7 +336,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
         count_pass(21, 0x7FFu, 32, 0u);
         __syncthreads();
         block_find_bin(lh, kHistBins, need, wtot, res);
-        if (res[0] < 0 && !short_ok) {
+        if (res[0] < 0 && !dsc.short_ok) {
             // Fewer than k ranked tokens survived: the bound - an estimate then - was too high.  Every
             // thread sees the same histogram; the head is marked for the repair pass and left alone.
             if (tid == 0) {
@@ -462,7 +462,7 @@ hipError_t launch_select(const Shape &sh, const DeviceViews &dv, const SelectIO 
     select_kernel<<<dim3((unsigned)(B * sh.n_q_heads)), dim3(kSelectThreads), 0, st>>>(
         io.desc.mem, io.desc.in, io.desc.n, sh.n_q_heads, sh.n_kv_heads, mode, io.blocks, io.block_stride,
         dv.head_maxkey, dv.fail, dv.any_fail, redo ? 1 : 0, batch_blocks, dv.page_table, io.ids, io.rows,
-        io.short_ok ? 1 : 0, io.scores, io.counts, io.head_M, out_ids, out_counts, ids_stride, dv.status, dv.repairs);
+        io.scores, io.counts, io.head_M, out_ids, out_counts, ids_stride, dv.status, dv.repairs);
     return hipGetLastError();
 }
 

@@ -91,12 +91,13 @@ hipError_t launch_append_step(const Shape &sh, const DeviceViews &dv, void *, vo
     (void)sh;
     return hipSuccess;
 }
-hipError_t launch_sample(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles, int mode, hipStream_t)
+hipError_t launch_sample(const Shape &sh, const DeviceViews &dv, int B, const void *q, int total_tiles, int mode, bool coarse,
+                         hipStream_t)
 {
     ++g_launches;
     if (total_tiles <= 0) return hipSuccess;
     check_descs(sh, dv.desc, B);
-    EXPECT(q && (mode == 0 || mode == 1));
+    EXPECT(q && (mode == 0 || mode == 1) && (!coarse || (mode == 0 && dv.pmask)));
     int prev = 0;
     for (int r = 0; r < B; ++r) {
         const ReqDesc d = desc_of(dv.desc, r);

@@ -167,6 +167,34 @@ def test_coarse_topk_llama_shape(n, P, k, window, vis):
     c.close()
 
 
+@pytest.mark.parametrize("n,P,k,window,vis", [(40000, 300, 1024, (0, 0), None), (40000, 400, 2048, (128, 512), 33333),
+                                               (70000, 280, 600, (0, 0), None)])
+def test_coarse_topk_with_the_estimated_bound(n, P, k, window, vis):
+    """More tokens in the chosen pages than the selection keeps in registers, and a large enough k: the main pass filters the chosen pages' tokens with the bound
+    estimated from a sample of them, and the selection checks it.  Same pages, tokens and outputs as the oracle,
+    with the estimate as it comes, with one so high that every head goes through the repair pass, and with
+    no estimate at all."""
+    w = _llama([n], topk=[k])
+    g = wl.generate(w)
+    c = _cache(w, g)
+    nv = None if vis is None else [vis]
+    c.debug_repairs()
+    run_coarse(c, w, g, [P], [k], window, nv)
+    assert c.debug_repairs() == 0
+    kept = c.debug_survivors()
+    c.debug_estimate(2)
+    run_coarse(c, w, g, [P], [k], window, nv)
+    assert c.debug_repairs() == w.n_q_heads
+    c.debug_estimate(-1)
+    run_coarse(c, w, g, [P], [k], window, nv)
+    assert c.debug_repairs() == 0
+    everything = c.debug_survivors()
+    c.debug_estimate(0)
+    print(f"survivors with the bound {kept}, without {everything}", flush=True)
+    assert kept < everything / 2
+    c.close()
+
+
 def test_coarse_batch_other_shapes_and_errors():
     """Ragged batch with a different P per request on permuted pages; other group sizes, head dims and fp32;
     refused calls."""
