@@ -250,3 +250,28 @@ def test_coarse_index_finds_clustered_keys():
     st = run_coarse(c, w, g2, [8], [32])
     assert min(st["recall"]) >= 0.9 and np.mean(st["recall"]) >= 0.98, st["recall"]
     c.close()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_coarse_random_configurations_against_the_oracle(seed):
+    """Random shapes, batches, page budgets, k, windows, prefixes and bound modes."""
+    rng = np.random.default_rng(9000 + seed)
+    hk, G, d = int(rng.choice([1, 2, 8])), int(rng.choice([1, 2, 4])), int(rng.choice([64, 128]))
+    dtype = str(rng.choice(["bf16", "bf16", "f32"]))
+    B = int(rng.integers(1, 4))
+    lens = [int(rng.choice([int(rng.integers(1, 300)), int(rng.integers(3000, 9000)), int(rng.integers(20000, 60000))]))
+            for _ in range(B)]
+    w = wl.Workload(f"cz{seed}", hk * G, hk, d, tuple(lens), dtype, 16, "topk", topk=tuple(1 for _ in lens),
+                    permute_pages=bool(rng.integers(0, 2)), seed=seed)
+    g = wl.generate(w, threads=4)
+    c = _cache(w, g)
+    for _ in range(3):
+        c.debug_estimate(int(rng.choice([0, 0, 2, -1])))
+        c.set_tuning(int(rng.choice([0, 1, 2, 4])), int(rng.choice([0, 1, 32])), int(rng.choice([0, 64])), 0)
+        window = (int(rng.choice([0, 0, 1, 128])), int(rng.choice([0, 0, 64, 512])))
+        vis = [int(rng.integers(1, n + 1)) for n in lens] if rng.integers(0, 3) == 0 else None
+        P = [int(rng.choice([1, 3, max(1, n // 64 // 8), max(1, n // 64 // 2), 300, 10 ** 6])) for n in lens]
+        ks = [int(rng.choice([1, 64, 512, 600, 2048, max(1, n // 5)])) for n in lens]
+        print("coarse", seed, lens, hk, G, d, dtype, window, vis, P, ks, flush=True)
+        run_coarse(c, w, g, P, ks, window, vis)
+    c.close()

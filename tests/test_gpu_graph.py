@@ -221,6 +221,24 @@ def test_diprs_recall_against_exact_range_query():
     c.close()
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_diprs_random_configurations_against_the_oracle(seed):
+    """Random context lengths, degrees, capacities, margins, windows and on-chip budgets."""
+    rng = np.random.default_rng(7000 + seed)
+    n = int(rng.choice([int(rng.integers(2, 200)), int(rng.integers(1000, 6000)), int(rng.integers(10000, 30000))]))
+    M = int(rng.choice([1, 3, 8, 16, 17, 32, 64]))
+    w, g, c = _setup(n, seed=seed, extra=100)
+    gr = c.build_graph(0, M)
+    for _ in range(3):
+        c.debug_diprs_lds(int(rng.choice([0, 0, 2048, 9000, 30000])))
+        l0 = int(rng.choice([0, 1, 16, 64, 500, n]))
+        beta = float(rng.choice([0.0, 0.5, 2.0, 5.0]))
+        window = (int(rng.choice([0, 0, 3, 128])), int(rng.choice([0, 0, 64, 512])))
+        _check_walk(w, g, c, gr, l0, beta, window=window)
+    gr.close()
+    c.close()
+
+
 def test_graph_and_diprs_argument_errors():
     w, g, c = _setup(300, seed=1)
     with pytest.raises(A.AlayaError):
