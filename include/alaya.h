@@ -236,7 +236,8 @@ int alaya_sparse_attn_static(alaya_cache *c, const int32_t *seqs, int B, int n_q
  * smaller token), shared by the query heads of the group (Sec. 7.2 "GQA-based index sharing"), and as entry
  * point the key of largest norm.  (The paper builds RoarGraph; Algorithm 1 runs on any graph index.)
  * bf16 caches of head_dim 128, degree 1..64.  index_mem (>= alaya_graph_bytes) holds the graph and stays
- * the library's while the handle lives; build_mem (>= alaya_graph_build_bytes) is scratch for the build only.
+ * the library's while the handle lives; build_mem (>= alaya_graph_build_bytes, a few hundred bytes today:
+ * the builder keeps its working lists on chip) is scratch for the build only.
  * Both DEVICE, 256-byte aligned.  The call synchronises `stream` before it returns.
  *
  * alaya_diprs_attn runs Algorithm 1 for every query head on its KV head's graph - start key = the entry

@@ -179,9 +179,7 @@ hipError_t launch_full_partial(const Shape &sh, const DeviceViews &dv, int B, co
 hipError_t launch_fill_u32(uint32_t *p, size_t n, uint32_t v, hipStream_t st);
 
 // Fine-grained index and DIPRS (graph.hip).
-hipError_t launch_graph_sim(const Shape &sh, const void *k_pool, const int32_t *pt_row, int kvh, int row0, int rows,
-                            int n, int n_pad, float *S, hipStream_t st);
-hipError_t launch_graph_topm(const float *S, int n_pad, int n, int row0, int rows, int M, int32_t *nbr, hipStream_t st);
+hipError_t launch_graph_knn(const Shape &sh, const void *k_pool, const int32_t *pt_row, int n, int M, int32_t *nbr, hipStream_t st);
 hipError_t launch_graph_norm(const Shape &sh, const void *k_pool, const int32_t *pt_row, int n, unsigned long long *best,
                              hipStream_t st);
 hipError_t launch_diprs(const Shape &sh, const DeviceViews &dv, const void *q, const int32_t *nbr, int n_idx, int M,

@@ -1038,17 +1038,6 @@ struct alaya_graph {
 
 namespace {
 
-constexpr int64_t kGraphChunkBytes = (int64_t)256 << 20; // similarity rows held at a time
-
-int64_t graph_pad(int64_t n) { return (n + 127) / 128 * 128; }
-int64_t graph_chunk_rows(int64_t n)
-{
-    int64_t rows = kGraphChunkBytes / (graph_pad(n) * (int64_t)sizeof(float)) / 64 * 64;
-    if (rows < 64) rows = 64;
-    const int64_t all = (n + 63) / 64 * 64;
-    return rows < all ? rows : all;
-}
-
 int graph_args_ok(const alaya_cache *c, int seq, int degree)
 {
     if (!c) return fail(ALAYA_E_INVAL, "null cache handle");
@@ -1072,8 +1061,7 @@ size_t alaya_graph_bytes(const alaya_cache *c, int seq, int degree)
 size_t alaya_graph_build_bytes(const alaya_cache *c, int seq, int degree)
 {
     if (graph_args_ok(c, seq, degree) != ALAYA_OK) return 0;
-    const int64_t n = c->seq_len[(size_t)seq];
-    return (size_t)(graph_chunk_rows(n) * graph_pad(n)) * sizeof(float);
+    return 256; // (the build keeps its working lists on chip; the argument is kept for builders that do not)
 }
 
 int alaya_graph_build(alaya_graph **out, alaya_cache *c, int seq, int degree, void *index_mem, size_t index_bytes,
@@ -1088,7 +1076,6 @@ int alaya_graph_build(alaya_graph **out, alaya_cache *c, int seq, int degree, vo
     if (index_bytes < alaya_graph_bytes(c, seq, degree) || build_bytes < alaya_graph_build_bytes(c, seq, degree))
         return fail(ALAYA_E_NOMEM, "index or build memory too small");
     const int64_t n = c->seq_len[(size_t)seq];
-    const int64_t n_pad = graph_pad(n), chunk = graph_chunk_rows(n);
     hipStream_t st = (hipStream_t)stream;
     alaya_graph *g = new (std::nothrow) alaya_graph();
     if (!g) return fail(ALAYA_E_NOMEM, "host allocation failed");
@@ -1102,16 +1089,7 @@ int alaya_graph_build(alaya_graph **out, alaya_cache *c, int seq, int degree, vo
     g->entry_dev = (int32_t *)(tail + 256);
     const Shape sh{c->cfg.dtype, c->cfg.head_dim, c->cfg.n_q_heads, c->cfg.n_kv_heads};
     const int32_t *pt_row = c->dv.page_table + (size_t)seq * c->L.mpps;
-    hipError_t e = hipSuccess;
-    for (int kvh = 0; kvh < c->cfg.n_kv_heads && e == hipSuccess; ++kvh) {
-        int32_t *nbr = g->nbr + (size_t)kvh * (size_t)n * degree;
-        for (int64_t row0 = 0; row0 < n && e == hipSuccess; row0 += chunk) {
-            const int64_t rows = std::min(chunk, n - row0);
-            e = launch_graph_sim(sh, c->k_pool, pt_row, kvh, (int)row0, (int)((rows + 63) / 64 * 64), (int)n, (int)n_pad,
-                                 (float *)build_mem, st);
-            if (e == hipSuccess) e = launch_graph_topm((const float *)build_mem, (int)n_pad, (int)n, (int)row0, (int)rows, degree, nbr, st);
-        }
-    }
+    hipError_t e = launch_graph_knn(sh, c->k_pool, pt_row, (int)n, degree, g->nbr, st);
     if (e == hipSuccess) e = launch_graph_norm(sh, c->k_pool, pt_row, (int)n, g->best, st);
     std::vector<unsigned long long> best((size_t)c->cfg.n_kv_heads);
     if (e == hipSuccess) e = hipMemcpyAsync(best.data(), g->best, best.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost, st);

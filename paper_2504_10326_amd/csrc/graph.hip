@@ -3,13 +3,11 @@
 //
 // Index: the exact M-nearest-neighbour graph of a sequence's keys under the inner product, one graph per
 // KV head (shared by the query heads of the group, as Sec. 7.2 "GQA-based index sharing" shares one graph
-// among a query group).  The paper builds RoarGraph with a GPU nearest-neighbour stage; any graph index
-// serves Algorithm 1, and the exact graph needs nothing but the keys:
-//   sim_kernel    S = K K^T for a chunk of rows, bf16 operands straight from the paged K pool (its layout
-//                 keeps 8 consecutive channels of a token in one 16-byte word: the operand of the matrix
-//                 instruction as it is), fp32 accumulation in v_mfma_f32_32x32x16_bf16
-//   topm_kernel   per row, the M largest entries other than the row's own key, best first (equal
-//                 similarity: smaller token), by chunk-wise merging into a sorted list
+// among a query group).  The paper builds RoarGraph with a GPU nearest-neighbour stage (Sec. 7.2 "Index
+// Construction Acceleration"); any graph index serves Algorithm 1, and the exact graph needs nothing but the keys:
+//   knn_kernel    K K^T on the matrix cores (v_mfma_f32_32x32x16_bf16; the K pool keeps 8 consecutive
+//                 channels of a token in one 16-byte word: the operand of the instruction as it is), the M
+//                 best of every row kept on the way (equal product: smaller token first)
 //   norm_kernel   the entry point of each KV head's graph: its key of largest norm
 // Query: diprs_kernel, one wavefront per query head, walks Algorithm 1 in the paper's order - the list C
 // is visited entry by entry, the neighbours of an entry are examined in the order of its list - so that the
@@ -27,6 +25,7 @@ namespace alaya {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_g;
 typedef __attribute__((ext_vector_type(16))) float f32x16_g;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_g;
 
 // 16-byte word holding channels [8c, 8c + 8) of token j of KV head kvh (bf16 pool, D = 128: 16 words per token)
 __device__ __forceinline__ const uint4 *key_word(const uint4 *__restrict__ k_pool, const int32_t *__restrict__ pt_row,
@@ -34,104 +33,6 @@ __device__ __forceinline__ const uint4 *key_word(const uint4 *__restrict__ k_poo
 {
     const int phys = pt_row[j >> 6];
     return k_pool + ((size_t)phys * H_kv + kvh) * (size_t)(NC * 64) + (size_t)c * 64 + (j & 63);
-}
-
-// ------------------------------------------------------------------------------------------------
-// S[r][j] = k_{row0 + r} . k_j for r < 64 * gridDim.y, j < n_pad (n_pad a multiple of 128; entries beyond n
-// hold whatever the unwritten page slots give and are ignored downstream).  Grid: (n_pad / 128, rows / 64);
-// a workgroup computes a 64 x 128 tile, wavefront w its columns [32 w, 32 w + 32) for both row halves.
-// Operand layout of v_mfma_f32_32x32x16_bf16: lane l supplies, for A, row l % 32 and channels 8 (l / 32) .. + 8
-// of the 16-channel step; for B, column l % 32 and the same channels; it receives, in register i, row
-// 8 (i / 4) + 4 (l / 32) + i % 4 of column l % 32.
-template <int D>
-__global__ __launch_bounds__(256) void sim_kernel(const uint4 *__restrict__ k_pool, const int32_t *__restrict__ pt_row,
-                                                  int H_kv, int kvh, int row0, int n, int n_pad, float *__restrict__ S)
-{
-    constexpr int NC = D / 8, STEPS = D / 16;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int half = lane >> 5, l32 = lane & 31;
-    const int col = blockIdx.x * 128 + wave * 32 + l32;
-    const int r_base = blockIdx.y * 64;
-    uint4 b[STEPS], a0[STEPS], a1[STEPS];
-    const bool col_ok = col < n;
-    const int ra = row0 + r_base + l32, rb = ra + 32;
-#pragma unroll
-    for (int s = 0; s < STEPS; ++s) {
-        b[s] = col_ok ? *key_word(k_pool, pt_row, H_kv, kvh, NC, col, 2 * s + half) : make_uint4(0, 0, 0, 0);
-        a0[s] = ra < n ? *key_word(k_pool, pt_row, H_kv, kvh, NC, ra, 2 * s + half) : make_uint4(0, 0, 0, 0);
-        a1[s] = rb < n ? *key_word(k_pool, pt_row, H_kv, kvh, NC, rb, 2 * s + half) : make_uint4(0, 0, 0, 0);
-    }
-    f32x16_g c0 = {0.f}, c1 = {0.f};
-#pragma unroll
-    for (int s = 0; s < STEPS; ++s) {
-        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_g, a0[s]), __builtin_bit_cast(bf16x8_g, b[s]), c0, 0, 0, 0);
-        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_g, a1[s]), __builtin_bit_cast(bf16x8_g, b[s]), c1, 0, 0, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int r = 8 * (i >> 2) + 4 * half + (i & 3);
-        S[(size_t)(r_base + r) * n_pad + col] = c0[i];
-        S[(size_t)(r_base + 32 + r) * n_pad + col] = c1[i];
-    }
-}
-
-// ------------------------------------------------------------------------------------------------
-// The M best columns of one row of S (the row's own key and columns >= n left out), best first; equal
-// similarity: smaller column first.  One 256-thread workgroup per row.  The row is read in chunks of 2048
-// columns; a sorted list of the M best so far is kept, the entries of a chunk that beat its last one are
-// appended, and list + newcomers are sorted again (bitonic, in LDS, as wide as needed).  Keys are composite:
-// (ordered similarity, ~column), so that the order is total and the result does not depend on timing.
-constexpr int kTopChunk = 2048;
-__global__ __launch_bounds__(256) void topm_kernel(const float *__restrict__ S, int n_pad, int n, int row0, int M,
-                                                   int32_t *__restrict__ nbr /* [n][M] of this KV head */)
-{
-    __shared__ unsigned long long buf[2 * kTopChunk]; // [0, M): the best so far, descending; then the newcomers
-    __shared__ int32_t cnt;
-    const int tid = threadIdx.x;
-    const int row = row0 + blockIdx.x;
-    if (row >= n) return;
-    const float *s = S + (size_t)blockIdx.x * n_pad;
-    for (int i = tid; i < M; i += 256) buf[i] = 0ull; // below every real key (ordered keys of floats are > 0)
-    if (tid == 0) cnt = M;
-    __syncthreads();
-    for (int c0 = 0; c0 < n; c0 += kTopChunk) {
-        const unsigned long long worst = buf[M - 1];
-#pragma unroll
-        for (int u = 0; u < kTopChunk / 256; ++u) {
-            const int col = c0 + u * 256 + tid;
-            if (col < n && col != row) {
-                const unsigned long long key = ((unsigned long long)ord_key(s[col]) << 32) | (0xFFFFFFFFu - (uint32_t)col);
-                if (key > worst) buf[atomicAdd(&cnt, 1)] = key;
-            }
-        }
-        __syncthreads();
-        const int total = cnt;
-        if (total > M) { // (uniform) sort list + newcomers, keep the first M
-            int width = 64;
-            while (width < total) width <<= 1;
-            for (int i = total + tid; i < width; i += 256) buf[i] = 0ull;
-            __syncthreads();
-            for (int k = 2; k <= width; k <<= 1) {
-                for (int j = k >> 1; j > 0; j >>= 1) {
-                    for (int i = tid; i < width; i += 256) {
-                        const int p = i ^ j;
-                        if (p > i) {
-                            const unsigned long long x = buf[i], y = buf[p];
-                            const bool desc = (i & k) == 0; // descending runs first: the final order is descending
-                            if (desc ? x < y : x > y) { buf[i] = y; buf[p] = x; }
-                        }
-                    }
-                    __syncthreads();
-                }
-            }
-            if (tid == 0) cnt = M;
-            __syncthreads();
-        }
-    }
-    for (int i = tid; i < M; i += 256) {
-        const unsigned long long key = buf[i];
-        nbr[(size_t)row * M + i] = key == 0ull ? -1 : (int32_t)(0xFFFFFFFFu - (uint32_t)(key & 0xFFFFFFFFull));
-    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -170,19 +71,191 @@ __global__ __launch_bounds__(256) void norm_kernel(const uint4 *__restrict__ k_p
     if (threadIdx.x == 0) best[kvh] = red[0];
 }
 
-hipError_t launch_graph_sim(const Shape &sh, const void *k_pool, const int32_t *pt_row, int kvh, int row0, int rows,
-                            int n, int n_pad, float *S, hipStream_t st)
+// ------------------------------------------------------------------------------------------------
+// The exact M-nearest-neighbour graph in one pass: K K^T on the matrix cores, the M best of every row kept on
+// the way, no similarity matrix in memory.  Grid: (strips of 128 rows, KV heads).  Wavefront w of a workgroup
+// owns rows [32 w, 32 w + 32) of the strip: their keys stay in its registers as the A operand, and it walks all
+// columns 32 at a time (the 32 keys of a step are staged in LDS once for the four wavefronts).  A lane gets 16
+// products of one column (rows 8 (i / 4) + 4 (l / 32) + i % 4); a product above its row's bar - the M-th best
+// of the row when its list was last tidied - is appended to the row's list in LDS.  Columns come in ascending
+// order, so a later key with the same product as the M-th best loses the tie: the test is a strict "greater".
+// When a list cannot take another step's worth it is tidied: sorted (bitonic, the wavefront's 64 lanes hold two
+// entries each; keys are (ordered product, ~column), a total order), cut to M, the bar raised.  A row is tidied
+// about log(n) times in all: the bar rises fast, and what passes it thins out.
+constexpr int kKnnRows = 128;  // rows per workgroup
+constexpr int kKnnList = 128;  // entries per row's list in LDS
+static_assert(kKnnList == 128, "a wavefront sorts a list as two entries per lane");
+
+__device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v, int m)
 {
-    if (sh.dtype != 0 || sh.head_dim != 128 || rows % 64 || n_pad % 128) return hipErrorInvalidValue;
-    sim_kernel<128><<<dim3((unsigned)(n_pad / 128), (unsigned)(rows / 64)), dim3(256), 0, st>>>(
-        (const uint4 *)k_pool, pt_row, sh.n_kv_heads, kvh, row0, n, n_pad, S);
-    return hipGetLastError();
+    const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)v, m), hi = (uint32_t)__shfl_xor((int)(uint32_t)(v >> 32), m);
+    return ((unsigned long long)hi << 32) | lo;
 }
 
-hipError_t launch_graph_topm(const float *S, int n_pad, int n, int row0, int rows, int M, int32_t *nbr, hipStream_t st)
+// Sorts the 128 keys held two per lane (element lane + 64 * slot) into descending order.
+__device__ __forceinline__ void sort128_desc(unsigned long long &k0, unsigned long long &k1, int lane)
 {
-    if (M < 1 || M > 64) return hipErrorInvalidValue;
-    topm_kernel<<<dim3((unsigned)rows), dim3(256), 0, st>>>(S, n_pad, n, row0, M, nbr);
+#pragma unroll
+    for (int k = 2; k <= 128; k <<= 1) {
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            if (j == 64) { // partner: the lane's own other slot; k == 128, descending throughout
+                const unsigned long long hi = k0 > k1 ? k0 : k1, lo = k0 > k1 ? k1 : k0;
+                k0 = hi;
+                k1 = lo;
+            } else {
+                const unsigned long long p0 = shfl_xor_u64(k0, j), p1 = shfl_xor_u64(k1, j);
+                const bool first = (lane & j) == 0;                  // this element is the lower index of the pair
+                const bool desc0 = (lane & k) == 0;                  // element index = lane (slot 0): direction of its run
+                const bool desc1 = ((lane + 64) & k) == 0;           // element index = lane + 64 (slot 1)
+                const bool take_max0 = first == desc0, take_max1 = first == desc1;
+                k0 = take_max0 ? (k0 > p0 ? k0 : p0) : (k0 < p0 ? k0 : p0);
+                k1 = take_max1 ? (k1 > p1 ? k1 : p1) : (k1 < p1 ? k1 : p1);
+            }
+        }
+    }
+}
+
+constexpr int kKnnAhead = 8;      // steps per round: a round's keys are loaded during the round before
+constexpr int kKnnPtLds = 3584;   // page-table entries that fit beside the lists (229 thousand tokens)
+
+// A workgroup barrier that orders LDS traffic only.  (__syncthreads also waits for every global load in
+// flight - here the keys fetched several steps ahead - which would undo the prefetch.)
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+template <int D>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void knn_kernel(const uint4 *__restrict__ k_pool, const int32_t *__restrict__ pt_row,
+                                                  int H_kv, int n, int M, int32_t *__restrict__ nbr_all)
+{
+    constexpr int NC = D / 8, STEPS = D / 16, LA = kKnnAhead;
+    extern __shared__ __attribute__((aligned(16))) unsigned long long knn_lds[];
+    unsigned long long *lists = knn_lds;                                     // [kKnnRows][kKnnList]
+    u32x4_g *stage = (u32x4_g *)(lists + (size_t)kKnnRows * kKnnList);           // [2][NC][32]
+    int32_t *cnt = (int32_t *)(stage + 2 * NC * 32);                         // [kKnnRows]
+    float *bar = (float *)(cnt + kKnnRows);                                  // [kKnnRows]
+    int32_t *pt_lds = (int32_t *)(bar + kKnnRows);                           // [kKnnPtLds]
+
+    const int kvh = blockIdx.y;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int r0 = blockIdx.x * kKnnRows;          // first row of the strip
+    int32_t *nbr = nbr_all + (size_t)kvh * (size_t)n * M;
+    const int n_pages = (n + kPageTokens - 1) / kPageTokens;
+    const bool pt_near = n_pages <= kKnnPtLds; // (uniform) the page table is read from LDS: one latency less per key
+
+    for (int i = tid; i < kKnnRows; i += 256) { cnt[i] = 0; bar[i] = -INFINITY; }
+    if (pt_near)
+        for (int i = tid; i < n_pages; i += 256) pt_lds[i] = pt_row[i];
+    // A operand: this wavefront's 32 rows
+    u32x4_g a[STEPS];
+    const int arow = r0 + wave * 32 + l32;
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s)
+        a[s] = arow < n ? *(const u32x4_g *)key_word(k_pool, pt_row, H_kv, kvh, NC, arow, 2 * s + half) : u32x4_g{0u, 0u, 0u, 0u};
+    __syncthreads();
+    // staging: thread t brings the words (t / 32) and (t / 32 + 8) of column t % 32 of a step
+    const int scol = tid & 31, sw = tid >> 5;
+    // (columns beyond n are not skipped but clamped, and never selected: straight-line loads keep the count of
+    // loads in flight exact, so that a step waits only for the keys it needs)
+    auto fetch = [&](int cb, u32x4_g &x, u32x4_g &y) {
+        const int col = min(cb * 32 + scol, n - 1);
+        const int phys = pt_near ? pt_lds[col >> 6] : pt_row[col >> 6];
+        const u32x4_g *kp = (const u32x4_g *)k_pool + ((size_t)phys * H_kv + kvh) * (size_t)(NC * 64) + (col & 63);
+        x = kp[(size_t)sw * 64];
+        y = kp[(size_t)(sw + 8) * 64];
+    };
+    const int steps = ((n + 31) / 32 + LA - 1) / LA * LA; // (whole rounds of LA steps; the extra ones find no column < n)
+    // A round is LA steps.  Its keys were asked for a round ago and are awaited once, at its start; the next
+    // round's are asked for at once and travel while this round computes.  (A ring of loads that wraps around
+    // the loop would do with fewer registers, but the compiler cannot tell how old a load is once the loop has
+    // turned, and waits for all of them at every step.)
+    u32x4_g cx[LA], cy[LA], nx[LA], ny[LA];
+#pragma unroll
+    for (int u = 0; u < LA; ++u) fetch(u, nx[u], ny[u]);
+    float mybar[16]; // the bars of this lane's 16 rows
+#pragma unroll
+    for (int i = 0; i < 16; ++i) mybar[i] = -INFINITY;
+
+    for (int cb0 = 0; cb0 < steps; cb0 += LA) {
+#pragma unroll
+        for (int u = 0; u < LA; ++u) { cx[u] = nx[u]; cy[u] = ny[u]; }
+#pragma unroll
+        for (int u = 0; u < LA; ++u) fetch(cb0 + LA + u, nx[u], ny[u]);
+        stage[sw * 32 + scol] = cx[0]; // (the round's first step; the last round's barrier has passed)
+        stage[(sw + 8) * 32 + scol] = cy[0];
+        lds_barrier();
+#pragma unroll
+        for (int u = 0; u < LA; ++u) {
+            const int cb = cb0 + u;
+            const u32x4_g *cur = stage + (size_t)(u & 1) * NC * 32;
+            f32x16_g c = {0.f};
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
+                const u32x4_g b = cur[(2 * s + half) * 32 + l32];
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_g, a[s]), __builtin_bit_cast(bf16x8_g, b), c, 0, 0, 0);
+            }
+            if (u + 1 < LA) { // the next step's keys go to the other half of the staging area
+                u32x4_g *nxt = stage + (size_t)((u + 1) & 1) * NC * 32;
+                nxt[sw * 32 + scol] = cx[u + 1 < LA ? u + 1 : 0];
+                nxt[(sw + 8) * 32 + scol] = cy[u + 1 < LA ? u + 1 : 0];
+            }
+            const int col = cb * 32 + l32;
+            const bool col_ok = col < n;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int rl = wave * 32 + 8 * (i >> 2) + 4 * half + (i & 3); // row within the strip
+                const int row = r0 + rl;
+                if (col_ok && row < n && col != row && c[i] > mybar[i]) {
+                    const int slot = atomicAdd(&cnt[rl], 1);
+                    lists[(size_t)rl * kKnnList + slot] = ((unsigned long long)ord_key(c[i]) << 32) | (0xFFFFFFFFu - (uint32_t)col);
+                }
+            }
+            // tidy the lists that could not take another step (32 entries at most per row and step)
+            const int mine = l32 == lane ? cnt[wave * 32 + l32] : 0; // (lanes 0..31: one row each)
+            unsigned long long full = __ballot(lane < 32 && mine > kKnnList - 32);
+            const bool any = full != 0ull;
+            while (full) {
+                const int rl = wave * 32 + (__ffsll((long long)full) - 1);
+                full &= full - 1;
+                const int m = cnt[rl];
+                unsigned long long k0 = lane < m ? lists[(size_t)rl * kKnnList + lane] : 0ull;
+                unsigned long long k1 = lane + 64 < m ? lists[(size_t)rl * kKnnList + lane + 64] : 0ull;
+                sort128_desc(k0, k1, lane);
+                if (lane < M) lists[(size_t)rl * kKnnList + lane] = k0; // (M <= 64: the best M sit in slot 0)
+                if (lane == M - 1) bar[rl] = k0 == 0ull ? -INFINITY : ord_float((uint32_t)(k0 >> 32));
+                if (lane == 0) cnt[rl] = m < M ? m : M;
+            }
+            if (any) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) mybar[i] = bar[wave * 32 + 8 * (i >> 2) + 4 * half + (i & 3)];
+            }
+            lds_barrier(); // the next step's keys are staged; everyone is done with this step's
+        }
+    }
+    // what is left: sort every row's list and write its first M entries
+    for (int r = 0; r < 32; ++r) {
+        const int rl = wave * 32 + r, row = r0 + rl;
+        if (row >= n) break;
+        const int m = cnt[rl];
+        unsigned long long k0 = lane < m ? lists[(size_t)rl * kKnnList + lane] : 0ull;
+        unsigned long long k1 = lane + 64 < m ? lists[(size_t)rl * kKnnList + lane + 64] : 0ull;
+        sort128_desc(k0, k1, lane);
+        if (lane < M) nbr[(size_t)row * M + lane] = k0 == 0ull ? -1 : (int32_t)(0xFFFFFFFFu - (uint32_t)(k0 & 0xFFFFFFFFull));
+    }
+}
+
+hipError_t launch_graph_knn(const Shape &sh, const void *k_pool, const int32_t *pt_row, int n, int M, int32_t *nbr, hipStream_t st)
+{
+    if (sh.dtype != 0 || sh.head_dim != 128 || M < 1 || M > 64 || n < 1) return hipErrorInvalidValue;
+    const size_t lds = (size_t)kKnnRows * kKnnList * 8 + 2 * 16 * 32 * 16 + kKnnRows * 8 + kKnnPtLds * 4;
+    static bool prepared = false;
+    if (!prepared) {
+        const hipError_t e = hipFuncSetAttribute((const void *)knn_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        prepared = true;
+    }
+    knn_kernel<128><<<dim3((unsigned)((n + kKnnRows - 1) / kKnnRows), (unsigned)sh.n_kv_heads), dim3(256), lds, st>>>(
+        (const uint4 *)k_pool, pt_row, sh.n_kv_heads, n, M, nbr);
     return hipGetLastError();
 }
 

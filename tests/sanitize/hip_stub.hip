@@ -222,22 +222,14 @@ hipError_t launch_page_mask(const Shape &, const DeviceViews &, const DescArgs &
     EXPECT(pd.n == B && pg_ids && pg_counts && pmask);
     return hipSuccess;
 }
-hipError_t launch_graph_sim(const Shape &, const void *k_pool, const int32_t *pt_row, int kvh, int row0, int rows, int n,
-                            int n_pad, float *S, hipStream_t)
+hipError_t launch_graph_knn(const Shape &sh, const void *k_pool, const int32_t *pt_row, int n, int M, int32_t *nbr, hipStream_t)
 {
     ++g_launches;
-    EXPECT(k_pool && pt_row && S && kvh >= 0 && rows % 64 == 0 && n_pad % 128 == 0 && n_pad >= n && row0 >= 0 && row0 < n);
-    // the chunk that the kernel writes lies inside the build memory: touch its first and last element
-    S[0] = 0.f;
-    S[(size_t)rows * n_pad - 1] = 0.f;
-    return hipSuccess;
-}
-hipError_t launch_graph_topm(const float *S, int n_pad, int n, int row0, int rows, int M, int32_t *nbr, hipStream_t)
-{
-    ++g_launches;
-    EXPECT(S && n_pad >= n && row0 + rows <= n && M >= 1 && M <= 64);
-    for (int r = row0; r < row0 + rows; ++r)
-        for (int m = 0; m < M; ++m) nbr[(size_t)r * M + m] = -1; // inside the index memory
+    EXPECT(k_pool && pt_row && nbr && n >= 1 && M >= 1 && M <= 64);
+    for (int p = 0; p < (n + kPageTokens - 1) / kPageTokens; ++p) EXPECT(pt_row[p] >= 0);
+    // the lists that the kernel writes lie inside the index memory: touch their first and last element
+    nbr[0] = -1;
+    nbr[(size_t)sh.n_kv_heads * n * M - 1] = -1;
     return hipSuccess;
 }
 hipError_t launch_graph_norm(const Shape &sh, const void *, const int32_t *, int n, unsigned long long *best, hipStream_t)
