@@ -379,6 +379,8 @@ def main() -> int:
     ap.add_argument("--pages-per-wave", type=int, default=0)
     ap.add_argument("--attend-splits", type=int, default=0)
     ap.add_argument("--write-all-scores", action="store_true")
+    ap.add_argument("--diprs-only", action="store_true",
+                    help="run only the graph-index leg (build, walks, exact scan beside them) and print its block")
     ap.add_argument("--calibration-copy-mb", type=int, default=0,
                     help="also run a plain device copy of this many MiB (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -394,6 +396,9 @@ def main() -> int:
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         return 1
     A.lib()
+    if args.diprs_only:
+        print(json.dumps({"diprs_vs_scan": measure_diprs(args)}))
+        return 0
     head = measure(args.workload, args, args.steps, args.warmup, args.cold_steps, not args.no_cpu_baseline,
                    coarse_div=args.coarse_div)
     per_config = {}

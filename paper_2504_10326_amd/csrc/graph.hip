@@ -36,8 +36,9 @@ __device__ __forceinline__ const uint4 *key_word(const uint4 *__restrict__ k_poo
 }
 
 // ------------------------------------------------------------------------------------------------
-// Entry point of a KV head's graph: the key of largest squared norm (equal norms: smaller token).  One
-// workgroup per KV head; best[kvh] = (ordered norm << 32) | ~token.
+// Entry point of a KV head's graph: the key of largest squared norm (equal norms: smaller token).  Grid:
+// (KV heads, slices of the sequence); best[kvh] = (ordered norm << 32) | ~token, zero on entry, raised with
+// a 64-bit atomic maximum (one per workgroup).
 template <int D>
 __global__ __launch_bounds__(256) void norm_kernel(const uint4 *__restrict__ k_pool, const int32_t *__restrict__ pt_row,
                                                    int H_kv, int n, unsigned long long *__restrict__ best)
@@ -46,7 +47,7 @@ __global__ __launch_bounds__(256) void norm_kernel(const uint4 *__restrict__ k_p
     __shared__ unsigned long long red[256];
     const int kvh = blockIdx.x;
     unsigned long long mine = 0ull;
-    for (int j = threadIdx.x; j < n; j += 256) {
+    for (int j = blockIdx.y * 256 + threadIdx.x; j < n; j += 256 * gridDim.y) {
         float acc = 0.f;
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
@@ -68,7 +69,7 @@ __global__ __launch_bounds__(256) void norm_kernel(const uint4 *__restrict__ k_p
         if ((int)threadIdx.x < o && red[threadIdx.x + o] > red[threadIdx.x]) red[threadIdx.x] = red[threadIdx.x + o];
         __syncthreads();
     }
-    if (threadIdx.x == 0) best[kvh] = red[0];
+    if (threadIdx.x == 0 && red[0] != 0ull) atomicMax(best + kvh, red[0]);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -263,7 +264,10 @@ hipError_t launch_graph_norm(const Shape &sh, const void *k_pool, const int32_t 
                              hipStream_t st)
 {
     if (sh.dtype != 0 || sh.head_dim != 128) return hipErrorInvalidValue;
-    norm_kernel<128><<<dim3((unsigned)sh.n_kv_heads), dim3(256), 0, st>>>((const uint4 *)k_pool, pt_row, sh.n_kv_heads, n, best);
+    const hipError_t e = launch_fill_u32((uint32_t *)best, 2 * (size_t)sh.n_kv_heads, 0u, st);
+    if (e != hipSuccess) return e;
+    const unsigned slices = (unsigned)std::max(1, std::min(256, n / 1024));
+    norm_kernel<128><<<dim3((unsigned)sh.n_kv_heads, slices), dim3(256), 0, st>>>((const uint4 *)k_pool, pt_row, sh.n_kv_heads, n, best);
     return hipGetLastError();
 }
 
