@@ -12,7 +12,7 @@ constexpr int kSelectThreads = 1024;
 constexpr int kAttendThreads = 256;
 constexpr int kMaxSplits = 64;
 constexpr int kHistBins = 2048;      // top 11 bits of the order-preserving score image
-constexpr int kRepairGrid = 2048;    // workgroups of the (normally idle) repair scoring pass, at most
+constexpr int kRepairGrid = 512;     // workgroups of the (normally idle) repair scoring pass, at most
 constexpr int kMaxSlots = 64;        // addresses one head's sample-pass maxima are spread over
 constexpr int kBlockHdr = 8;         // 8-byte words at the head of a survivor block: {count, start} per head of the group
 constexpr int kSelBatch = 4096;      // survivor blocks whose prefix sums the selection holds in LDS at a time

@@ -76,16 +76,18 @@ __global__ __launch_bounds__(256) void norm_kernel(const uint4 *__restrict__ k_p
 // The exact M-nearest-neighbour graph in one pass: K K^T on the matrix cores, the M best of every row kept on
 // the way, no similarity matrix in memory.  Grid: (strips of 128 rows, KV heads).  Wavefront w of a workgroup
 // owns rows [32 w, 32 w + 32) of the strip: their keys stay in its registers as the A operand, and it walks all
-// columns 32 at a time (the 32 keys of a step are staged in LDS once for the four wavefronts).  A lane gets 16
-// products of one column (rows 8 (i / 4) + 4 (l / 32) + i % 4); a product above its row's bar - the M-th best
-// of the row when its list was last tidied - is appended to the row's list in LDS.  Columns come in ascending
-// order, so a later key with the same product as the M-th best loses the tie: the test is a strict "greater".
-// When a list cannot take another step's worth it is tidied: sorted (bitonic, the wavefront's 64 lanes hold two
-// entries each; keys are (ordered product, ~column), a total order), cut to M, the bar raised.  A row is tidied
-// about log(n) times in all: the bar rises fast, and what passes it thins out.
-constexpr int kKnnRows = 128;  // rows per workgroup
-constexpr int kKnnList = 128;  // entries per row's list in LDS
-static_assert(kKnnList == 128, "a wavefront sorts a list as two entries per lane");
+// columns 32 at a time (the 32 keys of a step are staged in LDS once for the four wavefronts).  The matrix
+// instruction leaves a lane 16 entries of one column of its result; the step's keys go in as its first operand
+// and the wavefront's rows as the second, so that this column is a ROW of K K^T: lanes l and l + 32 own row l
+// of the wavefront, 16 of the step's 32 columns each (in groups of four, alternating), with a list of their
+// own for it in LDS, its length and the row's bar in registers - no atomics, no lane depends on another.  A product above the bar - the M-th best of the row when its lists were last
+// tidied - is appended.  Columns come in ascending order, so a later key with the same product as the M-th
+// best loses the tie: the test is a strict "greater".  When one of a row's two lists cannot take another
+// step's worth, the wavefront tidies the row: both lists sorted together (bitonic, two entries per lane; keys
+// are (ordered product, ~column), a total order), cut to M, dealt back to the two lists, the bar raised.
+constexpr int kKnnRows = 128; // rows per workgroup
+constexpr int kKnnSub = 64;   // entries per list; a row has two
+static_assert(kKnnSub <= 64 && kKnnSub >= 32 + 16, "a list is sorted as one entry per lane, and holds M / 2 entries plus a step's 16");
 
 __device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v, int m)
 {
@@ -130,11 +132,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 {
     constexpr int NC = D / 8, STEPS = D / 16, LA = kKnnAhead;
     extern __shared__ __attribute__((aligned(16))) unsigned long long knn_lds[];
-    unsigned long long *lists = knn_lds;                                     // [kKnnRows][kKnnList]
-    u32x4_g *stage = (u32x4_g *)(lists + (size_t)kKnnRows * kKnnList);           // [2][NC][32]
-    int32_t *cnt = (int32_t *)(stage + 2 * NC * 32);                         // [kKnnRows]
-    float *bar = (float *)(cnt + kKnnRows);                                  // [kKnnRows]
-    int32_t *pt_lds = (int32_t *)(bar + kKnnRows);                           // [kKnnPtLds]
+    unsigned long long *lists = knn_lds;                                     // [kKnnRows][2][kKnnSub]
+    u32x4_g *stage = (u32x4_g *)(lists + (size_t)kKnnRows * 2 * kKnnSub);    // [2][NC][32]
+    int32_t *pt_lds = (int32_t *)(stage + 2 * NC * 32);                      // [kKnnPtLds]
 
     const int kvh = blockIdx.y;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -144,7 +144,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int n_pages = (n + kPageTokens - 1) / kPageTokens;
     const bool pt_near = n_pages <= kKnnPtLds; // (uniform) the page table is read from LDS: one latency less per key
 
-    for (int i = tid; i < kKnnRows; i += 256) { cnt[i] = 0; bar[i] = -INFINITY; }
     if (pt_near)
         for (int i = tid; i < n_pages; i += 256) pt_lds[i] = pt_row[i];
     // A operand: this wavefront's 32 rows
@@ -173,9 +172,60 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     u32x4_g cx[LA], cy[LA], nx[LA], ny[LA];
 #pragma unroll
     for (int u = 0; u < LA; ++u) fetch(u, nx[u], ny[u]);
-    float mybar[16]; // the bars of this lane's 16 rows
-#pragma unroll
-    for (int i = 0; i < 16; ++i) mybar[i] = -INFINITY;
+
+    // this lane's row, its list, and what it knows of the row
+    const int myrow = r0 + wave * 32 + l32;
+    unsigned long long *mylist = lists + ((size_t)(wave * 32 + l32) * 2 + half) * kKnnSub;
+    int cnt = 0;
+    float bar = -INFINITY;
+
+    // Tidying a row: of the entries of its two lists the M best stay, dealt back to the two lists (in no
+    // particular order: only the final pass sorts), and the bar becomes the M-th best product.  That product is
+    // found bit by bit from the top - ballots and counts, no sorting network, no shuffles; equal products at the
+    // bar (they differ in their columns) are settled the same way on the low halves of the keys.  Returns what
+    // the row's two lanes keep: their new lengths and the new bar.
+    auto tidy = [&](int r, int &len_a, int &len_b, float &new_bar) {
+        const int ca = __shfl(cnt, r), cb = __shfl(cnt, 32 + r);
+        unsigned long long *la = lists + (size_t)(wave * 32 + r) * 2 * kKnnSub;
+        const unsigned long long k0 = lane < ca ? la[lane] : 0ull, k1 = lane < cb ? la[kKnnSub + lane] : 0ull;
+        const uint32_t s0 = (uint32_t)(k0 >> 32), s1 = (uint32_t)(k1 >> 32); // (0: no entry; below every product)
+        bool keep0 = k0 != 0ull, keep1 = k1 != 0ull;
+        new_bar = -INFINITY;
+        if (ca + cb > M) { // (uniform)
+            uint32_t T = 0u;
+            int need = M;
+#pragma unroll 1
+            for (int bit = 31; bit >= 0; --bit) {
+                const uint32_t cand = T | (1u << bit), top = ~((1u << bit) - 1u);
+                const int c = __popcll(__ballot((s0 & top) == cand)) + __popcll(__ballot((s1 & top) == cand));
+                if (c >= need) T = cand; else need -= c;
+            }
+            // T: the M-th best product; `need` of the entries equal to it stay: those with the smallest columns
+            const bool eq0 = s0 == T, eq1 = s1 == T;
+            const int n_eq = __popcll(__ballot(eq0)) + __popcll(__ballot(eq1));
+            uint32_t L = 0u; // of the entries at T, those with low half >= L stay
+            if (n_eq != need) {
+                const uint32_t l0 = (uint32_t)k0, l1 = (uint32_t)k1;
+#pragma unroll 1
+                for (int bit = 31; bit >= 0; --bit) {
+                    const uint32_t cand = L | (1u << bit), top = ~((1u << bit) - 1u);
+                    const int c = __popcll(__ballot(eq0 && (l0 & top) == cand)) + __popcll(__ballot(eq1 && (l1 & top) == cand));
+                    if (c >= need) L = cand; else need -= c;
+                }
+            }
+            keep0 = s0 > T || (eq0 && (uint32_t)k0 >= L);
+            keep1 = s1 > T || (eq1 && (uint32_t)k1 >= L);
+            new_bar = ord_float(T);
+        }
+        const unsigned long long b0 = __ballot(keep0), b1 = __ballot(keep1);
+        const unsigned long long lt = (1ull << lane) - 1ull;
+        const int n0 = __popcll(b0), p0 = __popcll(b0 & lt), p1 = n0 + __popcll(b1 & lt);
+        if (keep0) la[(size_t)(p0 & 1) * kKnnSub + (p0 >> 1)] = k0;
+        if (keep1) la[(size_t)(p1 & 1) * kKnnSub + (p1 >> 1)] = k1;
+        const int kept = n0 + __popcll(b1);
+        len_a = (kept + 1) >> 1;
+        len_b = kept >> 1;
+    };
 
     for (int cb0 = 0; cb0 < steps; cb0 += LA) {
 #pragma unroll
@@ -193,53 +243,59 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
             for (int s = 0; s < STEPS; ++s) {
                 const u32x4_g b = cur[(2 * s + half) * 32 + l32];
-                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_g, a[s]), __builtin_bit_cast(bf16x8_g, b), c, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_g, b), __builtin_bit_cast(bf16x8_g, a[s]), c, 0, 0, 0);
             }
             if (u + 1 < LA) { // the next step's keys go to the other half of the staging area
                 u32x4_g *nxt = stage + (size_t)((u + 1) & 1) * NC * 32;
                 nxt[sw * 32 + scol] = cx[u + 1 < LA ? u + 1 : 0];
                 nxt[(sw + 8) * 32 + scol] = cy[u + 1 < LA ? u + 1 : 0];
             }
-            const int col = cb * 32 + l32;
-            const bool col_ok = col < n;
+            // c[i]: the product of this lane's row with the step's column 8 (i / 4) + 4 (lane / 32) + i % 4.
+            // Which of the 16 pass: compares only; the appends - rare once the bars have risen - are done in
+            // a loop of their own, which most steps skip or leave after one turn.
+            const int col0 = cb * 32 + 4 * half;
+            uint32_t pass = 0u;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int rl = wave * 32 + 8 * (i >> 2) + 4 * half + (i & 3); // row within the strip
-                const int row = r0 + rl;
-                if (col_ok && row < n && col != row && c[i] > mybar[i]) {
-                    const int slot = atomicAdd(&cnt[rl], 1);
-                    lists[(size_t)rl * kKnnList + slot] = ((unsigned long long)ord_key(c[i]) << 32) | (0xFFFFFFFFu - (uint32_t)col);
+                const int col = col0 + 8 * (i >> 2) + (i & 3);
+                pass |= (c[i] > bar && col < n && col != myrow ? 1u : 0u) << i;
+            }
+            if (myrow >= n) pass = 0u;
+            while (__ballot(pass != 0u) != 0ull) {
+                if (pass != 0u) {
+                    const int i = __ffs(pass) - 1;
+                    pass &= pass - 1u;
+                    float ci = c[0];
+#pragma unroll
+                    for (int t = 1; t < 16; ++t) ci = i == t ? c[t] : ci;
+                    mylist[cnt] = ((unsigned long long)ord_key(ci) << 32) | (0xFFFFFFFFu - (uint32_t)(col0 + 8 * (i >> 2) + (i & 3)));
+                    ++cnt;
                 }
             }
-            // tidy the lists that could not take another step (32 entries at most per row and step)
-            const int mine = l32 == lane ? cnt[wave * 32 + l32] : 0; // (lanes 0..31: one row each)
-            unsigned long long full = __ballot(lane < 32 && mine > kKnnList - 32);
-            const bool any = full != 0ull;
+            // tidy the rows one of whose lists could not take another step (16 entries at most per list and step)
+            unsigned long long full = __ballot(cnt > kKnnSub - 16);
+            full = (full | (full >> 32)) & 0xFFFFFFFFull;
             while (full) {
-                const int rl = wave * 32 + (__ffsll((long long)full) - 1);
+                const int r = __ffsll((long long)full) - 1;
                 full &= full - 1;
-                const int m = cnt[rl];
-                unsigned long long k0 = lane < m ? lists[(size_t)rl * kKnnList + lane] : 0ull;
-                unsigned long long k1 = lane + 64 < m ? lists[(size_t)rl * kKnnList + lane + 64] : 0ull;
-                sort128_desc(k0, k1, lane);
-                if (lane < M) lists[(size_t)rl * kKnnList + lane] = k0; // (M <= 64: the best M sit in slot 0)
-                if (lane == M - 1) bar[rl] = k0 == 0ull ? -INFINITY : ord_float((uint32_t)(k0 >> 32));
-                if (lane == 0) cnt[rl] = m < M ? m : M;
-            }
-            if (any) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) mybar[i] = bar[wave * 32 + 8 * (i >> 2) + 4 * half + (i & 3)];
+                int len_a, len_b;
+                float new_bar;
+                tidy(r, len_a, len_b, new_bar);
+                if (l32 == r) {
+                    cnt = half ? len_b : len_a;
+                    bar = new_bar;
+                }
             }
             lds_barrier(); // the next step's keys are staged; everyone is done with this step's
         }
     }
-    // what is left: sort every row's list and write its first M entries
+    // what is left: sort every row's two lists together and write the first M entries
     for (int r = 0; r < 32; ++r) {
-        const int rl = wave * 32 + r, row = r0 + rl;
+        const int row = r0 + wave * 32 + r;
         if (row >= n) break;
-        const int m = cnt[rl];
-        unsigned long long k0 = lane < m ? lists[(size_t)rl * kKnnList + lane] : 0ull;
-        unsigned long long k1 = lane + 64 < m ? lists[(size_t)rl * kKnnList + lane + 64] : 0ull;
+        const int ca = __shfl(cnt, r), cb = __shfl(cnt, 32 + r);
+        const unsigned long long *la = lists + (size_t)(wave * 32 + r) * 2 * kKnnSub;
+        unsigned long long k0 = lane < ca ? la[lane] : 0ull, k1 = lane < cb ? la[kKnnSub + lane] : 0ull;
         sort128_desc(k0, k1, lane);
         if (lane < M) nbr[(size_t)row * M + lane] = k0 == 0ull ? -1 : (int32_t)(0xFFFFFFFFu - (uint32_t)(k0 & 0xFFFFFFFFull));
     }
@@ -248,7 +304,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 hipError_t launch_graph_knn(const Shape &sh, const void *k_pool, const int32_t *pt_row, int n, int M, int32_t *nbr, hipStream_t st)
 {
     if (sh.dtype != 0 || sh.head_dim != 128 || M < 1 || M > 64 || n < 1) return hipErrorInvalidValue;
-    const size_t lds = (size_t)kKnnRows * kKnnList * 8 + 2 * 16 * 32 * 16 + kKnnRows * 8 + kKnnPtLds * 4;
+    const size_t lds = (size_t)kKnnRows * 2 * kKnnSub * 8 + 2 * 16 * 32 * 16 + kKnnPtLds * 4;
     static bool prepared = false;
     if (!prepared) {
         const hipError_t e = hipFuncSetAttribute((const void *)knn_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
