@@ -165,3 +165,50 @@ def test_largest_context_the_selection_layout_takes():
     assert e.value.code == A.ALAYA_E_INVAL and "selection layout" in str(e.value)
     assert np.isfinite(c.full_attn([0], q).cpu().numpy()).all()              # dense attention has no such limit
     c.close()
+
+
+def test_paged_1m_through_the_coarse_index():
+    """The coarse plan as bench.py times it at 1M tokens (one page in sixteen per head, permuted pages, the
+    candidates filtered with the estimated bound): chosen pages, tokens and outputs against the oracle."""
+    import test_gpu_coarse as TC
+    w = wl.config("paged_1m")
+    _say(f"paged_1m coarse: generating {w.total_tokens} tokens")
+    g = wl.generate(w)
+    c = TC._cache(w, g)
+    P = [w.lens[0] // 64 // 16]
+    c.debug_repairs()
+    t0 = time.time()
+    st = TC.run_coarse(c, w, g, P, list(w.topk))
+    _say(f"paged_1m coarse: compared in {time.time() - t0:.1f}s, out err {st['max_out_err']:.2e}, band pages {st['band_pages']}, "
+         f"band heads {st['band_heads']}, repaired heads {c.debug_repairs()}, recall {np.mean(st['recall']):.3f}")
+    c.close()
+
+
+def test_llama8b_128k_graph_and_diprs():
+    """The fine-grained index at 128K tokens: sampled rows of the graph against brute force, then Algorithm 1
+    (list C, answer, output) for every query head against the oracle on the same graph, with the paper's window."""
+    import test_gpu_graph as TG
+    w, g, c = _case("llama8b_128k")
+    t0 = time.time()
+    gr = c.build_graph(0, 32)
+    torch.cuda.synchronize()
+    _say(f"llama8b_128k graph: built in {time.time() - t0:.2f}s")
+    n = w.lens[0]
+    nbr = gr.neighbours().cpu().numpy()
+    rows = np.unique(np.concatenate([np.arange(8), np.arange(n - 8, n), np.random.default_rng(0).integers(0, n, 48)]))
+    for kvh in (0, w.n_kv_heads - 1):
+        Kf = wl.bf16_bits_to_f32(g["K"][0][:, kvh, :]).astype(np.float64)
+        for j in rows:
+            sim = Kf @ Kf[j]
+            sim[j] = -np.inf
+            want = np.lexsort((np.arange(n), -sim))[:32]
+            got = nbr[kvh, j]
+            diff = np.setxor1d(got, want)
+            assert diff.size == 0 or np.abs(sim[diff] - sim[want[-1]]).max() <= TG.BAND_SIM, (kvh, j, diff)
+            assert (np.diff(sim[got]) <= TG.BAND_SIM).all()
+    lens, sizes = TG._check_walk(w, g, c, gr, 64, 2.0, window=(128, 512))
+    _say(f"llama8b_128k DIPRS l0=64: |C| {lens.min()}..{lens.max()}, answers {sizes.min()}..{sizes.max()}")
+    lens, sizes = TG._check_walk(w, g, c, gr, 1024, 2.0)
+    _say(f"llama8b_128k DIPRS l0=1024: |C| {lens.min()}..{lens.max()}, answers {sizes.min()}..{sizes.max()}")
+    gr.close()
+    c.close()
