@@ -185,7 +185,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // bar (they differ in their columns) are settled the same way on the low halves of the keys.  Returns what
     // the row's two lanes keep: their new lengths and the new bar.
     auto tidy = [&](int r, int &len_a, int &len_b, float &new_bar) {
-        const int ca = __shfl(cnt, r), cb = __shfl(cnt, 32 + r);
+        const int ca = __builtin_amdgcn_readlane(cnt, r), cb = __builtin_amdgcn_readlane(cnt, 32 + r);
         unsigned long long *la = lists + (size_t)(wave * 32 + r) * 2 * kKnnSub;
         const unsigned long long k0 = lane < ca ? la[lane] : 0ull, k1 = lane < cb ? la[kKnnSub + lane] : 0ull;
         const uint32_t s0 = (uint32_t)(k0 >> 32), s1 = (uint32_t)(k1 >> 32); // (0: no entry; below every product)
@@ -293,7 +293,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     for (int r = 0; r < 32; ++r) {
         const int row = r0 + wave * 32 + r;
         if (row >= n) break;
-        const int ca = __shfl(cnt, r), cb = __shfl(cnt, 32 + r);
+        const int ca = __builtin_amdgcn_readlane(cnt, r), cb = __builtin_amdgcn_readlane(cnt, 32 + r);
         const unsigned long long *la = lists + (size_t)(wave * 32 + r) * 2 * kKnnSub;
         unsigned long long k0 = lane < ca ? la[lane] : 0ull, k1 = lane < cb ? la[kKnnSub + lane] : 0ull;
         sort128_desc(k0, k1, lane);

@@ -119,7 +119,7 @@ __device__ __forceinline__ void hist_add(uint32_t *lh, uint32_t bin, bool on)
         const unsigned long long act = __ballot(on);
         if (act == 0ull) return;
         const int leader = __ffsll((long long)act) - 1;
-        const uint32_t lb = (uint32_t)__shfl((int)bin, leader);
+        const uint32_t lb = (uint32_t)__builtin_amdgcn_readlane((int)bin, leader); // (leader is wave-uniform: no trip through LDS)
         const unsigned long long same = __ballot(on && bin == lb);
         if (lane == leader) atomicAdd(&lh[lb], (uint32_t)__popcll(same));
         on = on && bin != lb;
