@@ -749,19 +749,21 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
 
     hipStream_t st = (hipStream_t)stream;
     const int G = n_q_heads / c->cfg.n_kv_heads;
-    // Pages per wavefront of the main pass (= pages per survivor block / 4): as many as leave about 8192
-    // workgroups or more (measured: 256K tokens run faster with 8192 workgroups of one page per wavefront
-    // than with 4096 of two, 1M tokens faster with 8192 of four than with 32768 of one), so that the blocks
-    // are few and large; a power of two, at most 4, and the
-    // staging area of a workgroup (4 * cp * 64 * G pairs) at most 32 KiB.
+    // Pages per wavefront of the main pass (= pages per survivor block / 4): one, or four where that still
+    // leaves about 3072 workgroups or more (from 384K tokens of 8 KV heads on), so that the blocks are few and
+    // large.  Measured, main pass in us with 1 / 2 / 4 pages per wavefront: 256K tokens 86 / 89 / 93, 384K 132 /
+    // 144 / 128, 512K 175 / 191 / 169, 768K 259 / 282 / 251, 1M 344 / 371 / 332: two is never the best.  The
+    // staging area of a workgroup (4 * cp * 64 * G pairs) stays within 32 KiB.
     int cp = 1;
     {
         int want = c->tune_ppw;
-        if (want <= 0) {
-            want = 1;
-            while (want < kMaxPagesPerWave && total_pages * c->cfg.n_kv_heads / (kScoreWaves * 2 * want) >= 8192) want *= 2;
+        if (want <= 0) want = total_pages * c->cfg.n_kv_heads / (kScoreWaves * kMaxPagesPerWave) >= 3072 ? kMaxPagesPerWave : 1;
+        if (want > kMaxPagesPerWave) want = kMaxPagesPerWave;
+        if (c->tune_ppw > 0) { // (the tests ask for every value)
+            while (2 * cp <= want && 2 * cp * G <= 16) cp *= 2;
+        } else if (want * G <= 16) {
+            cp = want;
         }
-        while (2 * cp <= want && 2 * cp <= kMaxPagesPerWave && 2 * cp * G <= 16) cp *= 2;
     }
     int splits = c->tune_splits;
     if (splits <= 0) {
