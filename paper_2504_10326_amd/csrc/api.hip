@@ -825,7 +825,7 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
         if (coarse) {
             rank_pages = std::min<int64_t>(p->coarse_pages[b], pages);
             rank_tokens = kPageTokens * (rank_pages - 1) + 1 - d.nwin;
-            d.short_ok = 1;
+            d.flags = 1;
         }
         if (!c->tune_noprune && pages >= 4) {
             // (never when top-k takes every token outside the window: nothing checks the bound then)
@@ -833,7 +833,7 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
             // registers: below that a bound saves the selection nothing and costs a sample pass)
             if (p->mode == ALAYA_TOPK && estimate && d.k >= 512 && d.k < rank_tokens && rank_pages >= 64 &&
                 (!coarse || rank_pages * kPageTokens > 16384)) {
-                d.short_ok = 0; // at least k tokens can be ranked: fewer survivors means that the bound was too high
+                d.flags = 0; // at least k tokens can be ranked: fewer survivors means that the bound was too high
                 if (coarse) d.est_cand = (int32_t)(rank_pages * kPageTokens);
                 // Estimated bound: a 1-in-S sample holds about mu = k / S of the k best
                 // scores, so its (mu + 6 sqrt(mu) + 8)-th largest score lies below the true threshold
@@ -901,6 +901,16 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
         }
         pages_all += pages;
         off += (int64_t)n_q_heads * d.head_stride;
+    }
+    {
+        // selection workgroups take the requests in descending order of what they have to go through
+        std::vector<int> order((size_t)B);
+        for (int b = 0; b < B; ++b) order[(size_t)b] = b;
+        std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return hd[x].n_pages > hd[y].n_pages; });
+        for (int b = 0; b < B; ++b) {
+            hd[b].flags = (hd[b].flags & 1) | (order[(size_t)b] << 8);
+            if (coarse) hp[b].flags = (hp[b].flags & 1) | (order[(size_t)b] << 8);
+        }
     }
     const int64_t block_stride = kBlockHdr + (int64_t)kScoreWaves * cp * kPageTokens * G;
     if (off > S.sel_elems) return fail(ALAYA_E_NOMEM, "scratch too small for the selected-token arrays");

@@ -237,9 +237,11 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
     __shared__ int32_t res[2];
     __shared__ int32_t gfirst[kRegSets * kSelChunk / 64 + 1]; // register path: block of every 64th survivor
 
-    const int rh = blockIdx.x;
-    if (redo && (*any_fail == 0u || fail[rh] == 0u)) return; // second run: only the heads that the repair pass rewrote
-    const int r = rh / H_q, h = rh % H_q;
+    if (redo && *any_fail == 0u) return; // second run: only the heads that the repair pass rewrote
+    const int h = blockIdx.x % H_q;
+    const int r = desc_n > 1 ? desc[blockIdx.x / H_q].flags >> 8 : 0; // (the largest requests first)
+    const int rh = r * H_q + h;
+    if (redo && fail[rh] == 0u) return;
     const int G = H_q / H_kv;
     const HeadBlocks hb{blocks, block_stride, H_kv, h / G, h % G};
     const ReqDesc dsc = desc[r];
@@ -336,7 +338,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
         count_pass(21, 0x7FFu, 32, 0u);
         __syncthreads();
         block_find_bin(lh, kHistBins, need, wtot, res);
-        if (res[0] < 0 && !dsc.short_ok) {
+        if (res[0] < 0 && !(dsc.flags & 1)) {
             // Fewer than k ranked tokens survived: the bound - an estimate then - was too high.  Every
             // thread sees the same histogram; the head is marked for the repair pass and left alone.
             if (tid == 0) {
