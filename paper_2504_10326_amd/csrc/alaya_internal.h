@@ -170,13 +170,15 @@ hipError_t launch_coarse_score(const Shape &sh, const DeviceViews &dv, const Des
 hipError_t launch_page_mask(const Shape &sh, const DeviceViews &dv, const DescArgs &pdesc, int B, const int32_t *pg_ids,
                             const int32_t *pg_counts, uint32_t *pmask, hipStream_t st);
 
-hipError_t launch_attend(const Shape &sh, const DeviceViews &dv, int B, float scale, int splits, hipStream_t st);
+hipError_t launch_attend(const Shape &sh, const DeviceViews &dv, int B, float scale, int splits, int min_splits,
+                         hipStream_t st);
 
 // partial layout: [slot][head_dim + 2] = {m (already times scale), l, acc[head_dim]}
 // sparse: slot = (b * n_q_heads + h) * splits + s           (per_request_tiles == 0)
 // full  : slot = (tile_start[b] + t) * n_q_heads + h        (per_request_tiles == 1)
-hipError_t launch_combine(const Shape &sh, const DeviceViews &dv, int B, int splits, int per_request_tiles,
-                          int pages_per_tile, float *out, hipStream_t st);
+// sparse: a head's first head_splits(count) slots hold partials (min_splits <= that <= splits), as in the attend pass
+hipError_t launch_combine(const Shape &sh, const DeviceViews &dv, int B, int splits, int min_splits,
+                          int per_request_tiles, int pages_per_tile, float *out, hipStream_t st);
 
 hipError_t launch_full_partial(const Shape &sh, const DeviceViews &dv, int B, const void *q, float scale,
                                int total_tiles, int pages_per_tile, hipStream_t st);

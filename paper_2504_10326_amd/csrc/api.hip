@@ -765,21 +765,23 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
             cp = want;
         }
     }
-    int splits = c->tune_splits;
+    // The attend pass: `splits` workgroups per head in the grid, of which a head with `count` selected tokens
+    // uses clamp(count / 128, min_splits, splits) - about 128 tokens per workgroup (what the gather of 256-byte
+    // rows runs fastest with), more workgroups when the call is small.  The grid is sized for the longest
+    // list the call can have (a threshold set's size is not known here: 4096 is assumed, and a longer list
+    // gets more tokens per workgroup).
+    int splits = c->tune_splits, min_splits = c->tune_splits;
     if (splits <= 0) {
-        // about 128 selected tokens per workgroup (what the gather of 256-byte rows runs fastest with),
-        // more workgroups when the call is small (a threshold set's size is not known here: assume 4096)
         int kmax = 4096;
         if (p->mode == ALAYA_TOPK) {
             kmax = 1;
             for (int b = 0; b < B; ++b) kmax = p->topk[b] > kmax ? p->topk[b] : kmax;
         }
         const int64_t kw = (int64_t)kmax + p->window_init + p->window_last;
-        const int per = (int)((kw + 127) / 128);
-        const int fill = std::min((int)((kw + 31) / 32), (512 + B * n_q_heads - 1) / (B * n_q_heads));
-        splits = std::max(per, fill);
-        if (splits < 1) splits = 1;
-        if (splits > kMaxSplits) splits = kMaxSplits;
+        const int per = (int)std::min<int64_t>((kw + 127) / 128, kMaxSplits);
+        const int fill = (int)std::min<int64_t>((kw + 31) / 32, (512 + B * n_q_heads - 1) / (B * n_q_heads));
+        splits = std::min(std::max(std::max(per, fill), 1), kMaxSplits);
+        min_splits = std::min(std::max(fill, 1), splits);
     }
 
     ReqDesc *hd;
@@ -983,10 +985,10 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
     if (e != hipSuccess) { c->scratch_ready = false; return fail_hip(e, "select launch"); }
     {
         Timed tm(c, 2, st);
-        e = launch_attend(sh, dv, B, scale, splits, st);
+        e = launch_attend(sh, dv, B, scale, splits, min_splits, st);
     }
     if (e != hipSuccess) return fail_hip(e, "attend launch");
-    { Timed tm(c, 3, st); e = launch_combine(sh, dv, B, splits, 0, 0, out, st); }
+    { Timed tm(c, 3, st); e = launch_combine(sh, dv, B, splits, min_splits, 0, 0, out, st); }
     if (e != hipSuccess) return fail_hip(e, "combine launch");
     return ALAYA_OK;
 }
@@ -1190,9 +1192,9 @@ int alaya_diprs_attn(alaya_cache *c, const alaya_graph *g, int n_q_heads, const 
     }
     if (e != hipSuccess) return fail_hip(e, "DIPRS launch");
     int splits = c->tune_splits > 0 ? c->tune_splits : 16;
-    { Timed tm(c, 2, st); e = launch_attend(sh, c->dv, 1, scale, splits, st); }
+    { Timed tm(c, 2, st); e = launch_attend(sh, c->dv, 1, scale, splits, splits, st); }
     if (e != hipSuccess) return fail_hip(e, "attend launch");
-    { Timed tm(c, 3, st); e = launch_combine(sh, c->dv, 1, splits, 0, 0, out, st); }
+    { Timed tm(c, 3, st); e = launch_combine(sh, c->dv, 1, splits, splits, 0, 0, out, st); }
     if (e != hipSuccess) return fail_hip(e, "combine launch");
     c->last_B = 0; // (no survivor blocks to inspect after this call)
     c->last_tiles_b = 0;
@@ -1267,7 +1269,7 @@ int alaya_full_attn(alaya_cache *c, const int32_t *seqs, int B, int n_q_heads, c
     hipError_t e;
     { Timed tm(c, 4, st); e = launch_full_partial(sh, c->dv, B, q, scale, tiles, (int)ppt, st); }
     if (e != hipSuccess) return fail_hip(e, "full-attention launch");
-    { Timed tm(c, 3, st); e = launch_combine(sh, c->dv, B, 0, 1, (int)ppt, out, st); }
+    { Timed tm(c, 3, st); e = launch_combine(sh, c->dv, B, 0, 0, 1, (int)ppt, out, st); }
     if (e != hipSuccess) return fail_hip(e, "combine launch");
     return ALAYA_OK;
 }

@@ -21,13 +21,20 @@ namespace alaya {
 // 3.8 at 2048 on a 410 MB gather).  The head's selected tokens are one list (sel_rows / sel_scores,
 // `counts` long, ascending by token), as the selection leaves them; sel_rows already holds the rows'
 // places in the V pool, so that the loads of a pass are two deep (row number, row), not three.
+// The grid has `splits` workgroups per head, sized for the longest list of the call; a head uses as many
+// of them as give each about 128 rows (head_splits), the others leave at once.
 constexpr int kAttendU = 8;
+
+__device__ __forceinline__ int head_splits(int cnt, int splits, int min_splits)
+{
+    return min(splits, max(min_splits, (cnt + 127) >> 7));
+}
 
 template <int DT, int D>
 __global__ __launch_bounds__(kAttendThreads) void attend_kernel(
     const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int H_q, int H_kv,
     const char *__restrict__ v_pool, const int32_t *__restrict__ rows_in, const float *__restrict__ scores_in,
-    const int32_t *__restrict__ counts, const float *__restrict__ head_M, float scale, int splits,
+    const int32_t *__restrict__ counts, const float *__restrict__ head_M, float scale, int splits, int min_splits,
     float *__restrict__ partials)
 {
     const Descs desc{desc_mem, desc0, desc_n};
@@ -46,10 +53,12 @@ __global__ __launch_bounds__(kAttendThreads) void attend_kernel(
     const float *ss = scores_in + off;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int cnt = counts[rh];
-    int per = (cnt + splits - 1) / splits;
+    const float M = head_M[rh]; // (asked for before the early exit: one trip to memory, not two)
+    const int eff = head_splits(cnt, splits, min_splits);
+    if (sp >= eff) return;
+    int per = (cnt + eff - 1) / eff;
     per = (per + 15) & ~15;
     const int begin = min(cnt, sp * per), end = min(cnt, begin + per);
-    const float M = head_M[rh];
 
     const int sub = lane & 15, grp = lane >> 4;
     float acc[EPL];
@@ -106,13 +115,14 @@ __global__ __launch_bounds__(kAttendThreads) void attend_kernel(
     }
 }
 
-hipError_t launch_attend(const Shape &sh, const DeviceViews &dv, int B, float scale, int splits, hipStream_t st)
+hipError_t launch_attend(const Shape &sh, const DeviceViews &dv, int B, float scale, int splits, int min_splits,
+                         hipStream_t st)
 {
     const dim3 grid((unsigned)(B * sh.n_q_heads * splits)), block(kAttendThreads);
 #define ALAYA_ATTEND(DT, D)                                                                                  \
     attend_kernel<DT, D><<<grid, block, 0, st>>>(dv.desc.mem, dv.desc.in, dv.desc.n, sh.n_q_heads, sh.n_kv_heads, \
                                                  (const char *)dv.v_pool, dv.sel_rows, dv.sel_scores,        \
-                                                 dv.counts, dv.head_M, scale, splits, dv.partials)
+                                                 dv.counts, dv.head_M, scale, splits, min_splits, dv.partials)
     if (sh.dtype == 0 && sh.head_dim == 128) ALAYA_ATTEND(0, 128);
     else if (sh.dtype == 0 && sh.head_dim == 64) ALAYA_ATTEND(0, 64);
     else if (sh.dtype == 1 && sh.head_dim == 128) ALAYA_ATTEND(1, 128);
@@ -128,6 +138,7 @@ template <int D>
 __global__ __launch_bounds__(D) void combine_kernel(const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int B, int H_q,
                                                      const float *__restrict__ partials, int splits,
                                                      int per_request_tiles, int pages_per_tile,
+                                                     const int32_t *__restrict__ counts, int min_splits,
                                                      float *__restrict__ out)
 {
     const Descs desc{desc_mem, desc0, desc_n};
@@ -142,7 +153,7 @@ __global__ __launch_bounds__(D) void combine_kernel(const ReqDesc *__restrict__ 
         first = ((size_t)dsc.tile_start * H_q + h) * (D + 2);
         stride = (size_t)H_q * (D + 2);
     } else {
-        np = splits;
+        np = head_splits(counts[rh], splits, min_splits); // what the attend pass used of the head's slots
         first = (size_t)rh * splits * (D + 2);
         stride = D + 2;
     }
@@ -179,16 +190,16 @@ __global__ __launch_bounds__(D) void combine_kernel(const ReqDesc *__restrict__ 
     out[(size_t)rh * D + threadIdx.x] = o / L;
 }
 
-hipError_t launch_combine(const Shape &sh, const DeviceViews &dv, int B, int splits, int per_request_tiles,
-                          int pages_per_tile, float *out, hipStream_t st)
+hipError_t launch_combine(const Shape &sh, const DeviceViews &dv, int B, int splits, int min_splits,
+                          int per_request_tiles, int pages_per_tile, float *out, hipStream_t st)
 {
     const dim3 grid((unsigned)(B * sh.n_q_heads));
     if (sh.head_dim == 128)
         combine_kernel<128><<<grid, dim3(128), 0, st>>>(dv.desc.mem, dv.desc.in, dv.desc.n, B, sh.n_q_heads, dv.partials, splits,
-                                                        per_request_tiles, pages_per_tile, out);
+                                                        per_request_tiles, pages_per_tile, dv.counts, min_splits, out);
     else if (sh.head_dim == 64)
         combine_kernel<64><<<grid, dim3(64), 0, st>>>(dv.desc.mem, dv.desc.in, dv.desc.n, B, sh.n_q_heads, dv.partials, splits,
-                                                      per_request_tiles, pages_per_tile, out);
+                                                      per_request_tiles, pages_per_tile, dv.counts, min_splits, out);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();

@@ -90,8 +90,9 @@ hipError_t launch_append_step(const Shape &sh, const DeviceViews &dv, void *k_po
 // lane = token.
 //
 // bf16 uses the packed dot-product instruction (two bf16 products and the fp32 accumulate in one op,
-// both operands used as stored), the query streamed through scalar registers; fp32 uses fused
-// multiply-add.  (The same contraction on the matrix cores - v_mfma_f32_16x16x32_bf16 with the four
+// both operands used as stored); fp32 uses fused multiply-add.  The group's queries come from scalar registers in
+// the sample pass and in dense attention, and from LDS (a broadcast read per 16 bytes) in the main pass, where
+// G * 64 words of them do not fit the scalar registers next to everything else that is wave-uniform there.  (The same contraction on the matrix cores - v_mfma_f32_16x16x32_bf16 with the four
 // heads of a group on four rows of the 16-row operand - was measured on a 2 GiB pool and runs at the
 // same speed, 6.09 against 6.03 TB/s: the pass is bound by the memory system, not by the arithmetic.)
 //
@@ -420,6 +421,7 @@ __device__ __forceinline__ void main_block(const int block, const Descs &desc, i
     constexpr int CAP = kPageTokens * CP; // survivors of one wavefront and head, at most
     __shared__ uint2 stage[kScoreWaves][G][CAP];
     __shared__ int32_t wcnt[G][kScoreWaves];
+    __shared__ uint4 q_lds[G * NC]; // the group's queries
 
     const int kvh = block % H_kv;
     const int tile = block / H_kv;
@@ -443,7 +445,8 @@ __device__ __forceinline__ void main_block(const int block, const Descs &desc, i
     }
     if (REPAIR && !any_act) return; // whole workgroup
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
-    const uint4 *qh = (const uint4 *)(qw + (size_t)rh0 * QW); // wave-uniform address: scalar loads
+    if (threadIdx.x < G * NC) q_lds[threadIdx.x] = ((const uint4 *)(qw + (size_t)rh0 * QW))[threadIdx.x];
+    __syncthreads();
     int cnt[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) cnt[g] = 0;
@@ -462,7 +465,7 @@ __device__ __forceinline__ void main_block(const int block, const Descs &desc, i
         const int phys = page_table[dsc.pt_off + p];
         const uint4 *base = k_pool + ((size_t)phys * H_kv + kvh) * (size_t)(NC * 64) + lane;
         float acc[G];
-        score_page<DT, D, G>(base, qh, acc);
+        score_page_lds<DT, D, G>(base, q_lds, acc);
         const int j = p * kPageTokens + lane;
         const bool valid = j < dsc.n;
         const bool win = in_window(dsc, j); // always a survivor; top-k neither counts nor ranks it
@@ -511,7 +514,8 @@ __device__ __forceinline__ void main_block(const int block, const Descs &desc, i
 }
 
 template <int DT, int D, int G, int CP, bool REPAIR, bool COARSE>
-__global__ __launch_bounds__(256) void main_kernel(const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int B,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((D * (DT == 0 ? 2 : 4) / 4 + 8 * G <= 96 && G <= 4) ? 4 : 2)))
+void main_kernel(const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int B,
                                                     const int32_t *__restrict__ page_table,
                                                     const uint32_t *__restrict__ qw, const uint4 *__restrict__ k_pool,
                                                     uint2 *__restrict__ blocks, int64_t block_stride,

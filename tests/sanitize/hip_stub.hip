@@ -148,17 +148,17 @@ hipError_t launch_select(const Shape &sh, const DeviceViews &, const SelectIO &i
     (void)sh;
     return hipSuccess;
 }
-hipError_t launch_attend(const Shape &, const DeviceViews &dv, int B, float scale, int splits, hipStream_t)
+hipError_t launch_attend(const Shape &, const DeviceViews &dv, int B, float scale, int splits, int min_splits, hipStream_t)
 {
     ++g_launches;
-    EXPECT(B >= 1 && splits >= 1 && splits <= kMaxSplits && scale > 0.f && dv.partials);
+    EXPECT(B >= 1 && min_splits >= 1 && min_splits <= splits && splits <= kMaxSplits && scale > 0.f && dv.partials);
     return hipSuccess;
 }
-hipError_t launch_combine(const Shape &, const DeviceViews &, int B, int splits, int per_request_tiles, int ppt, float *out,
-                          hipStream_t)
+hipError_t launch_combine(const Shape &, const DeviceViews &, int B, int splits, int min_splits, int per_request_tiles, int ppt,
+                          float *out, hipStream_t)
 {
     ++g_launches;
-    EXPECT(B >= 1 && out && (per_request_tiles ? ppt >= 1 : splits >= 1 && splits <= kMaxSplits));
+    EXPECT(B >= 1 && out && (per_request_tiles ? ppt >= 1 : min_splits >= 1 && min_splits <= splits && splits <= kMaxSplits));
     return hipSuccess;
 }
 hipError_t launch_full_partial(const Shape &sh, const DeviceViews &dv, int B, const void *q, float scale, int total_tiles,

@@ -479,6 +479,20 @@ def test_batched_ragged_lengths_one_call():
     c.close()
 
 
+def test_selected_lists_of_very_different_lengths_in_one_call():
+    """The attend pass sizes its grid for the longest list of the call and every head uses the share of it
+    that its own list needs: lists of 1, 130, 4000 and 7900 tokens side by side, then threshold sets whose
+    sizes differ from head to head."""
+    lens = [700, 6000, 9000, 8000]
+    w = wl.resized(wl.config("batched_16"), lens)
+    g = wl.generate(w)
+    c = make_cache(w, g)
+    run_and_compare(c, w, g, A.ALAYA_TOPK, topk=[1, 130, 4000, 7900])
+    run_and_compare(c, w, g, A.ALAYA_TOPK, topk=[129, 5999, 127, 128])
+    run_and_compare(c, w, g, A.ALAYA_DIPR, beta=[0.0, 6.0, 1.0, 100.0])
+    c.close()
+
+
 # ------------------------------------------------------------------------------------------ other shapes
 @pytest.mark.parametrize("hq,hk,d,dtype", [(4, 4, 128, "bf16"), (8, 4, 64, "bf16"), (16, 2, 128, "bf16"),
                                             (4, 2, 64, "f32"), (8, 1, 128, "f32")])
