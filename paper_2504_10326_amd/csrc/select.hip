@@ -20,6 +20,7 @@
 // Up to 16384 survivors (the usual case: the bound leaves one to two times k) are read once and kept in
 // registers for all passes; more are streamed from the blocks once per pass.
 #include "alaya_internal.h"
+#include <type_traits>
 
 namespace alaya {
 
@@ -107,21 +108,29 @@ __device__ __forceinline__ void block_find_bin(const uint32_t *hist, int nbins, 
     __syncthreads();
 }
 
-// lh[bin] += 1 for every lane with `on`.  The survivors of a head crowd into a handful of the coarse
-// buckets, and atomics of many lanes on one LDS word are carried out one after the other: the lanes that
-// share the first active lane's bucket are counted with a ballot and added at once, three times over;
-// whoever is left adds for itself.
-__device__ __forceinline__ void hist_add(uint32_t *lh, uint32_t bin, bool on)
+// lh[bin] += 1 for every lane with `on`.  Atomics of many lanes on one LDS word are carried out one after the
+// other.  When the scores crowd into one bucket (many equal keys) the lanes that share the first active lane's
+// bucket are therefore counted with a ballot and added at once (crowded); when they are spread, that costs more
+// vector instructions than the conflicts it saves (a counting pass over 3600 survivors: 2.4 us merging bucket
+// after bucket three rounds deep, 1.5 us with every lane adding for itself), so a wavefront looks at the first
+// survivors it counts in a pass (is_crowded) and goes on as they suggest.
+__device__ __forceinline__ bool is_crowded(uint32_t bin, bool on)
 {
-    const int lane = threadIdx.x & 63;
-#pragma unroll
-    for (int it = 0; it < 3; ++it) {
+    const unsigned long long act = __ballot(on);
+    if (act == 0ull) return false;
+    const uint32_t lb = (uint32_t)__builtin_amdgcn_readlane((int)bin, __ffsll((long long)act) - 1);
+    return 8 * __popcll(__ballot(on && bin == lb)) >= 7 * __popcll(act) && __popcll(act) >= 16;
+}
+
+__device__ __forceinline__ void hist_add(uint32_t *lh, uint32_t bin, bool on, bool crowded)
+{
+    if (crowded) {
         const unsigned long long act = __ballot(on);
         if (act == 0ull) return;
         const int leader = __ffsll((long long)act) - 1;
         const uint32_t lb = (uint32_t)__builtin_amdgcn_readlane((int)bin, leader); // (leader is wave-uniform: no trip through LDS)
         const unsigned long long same = __ballot(on && bin == lb);
-        if (lane == leader) atomicAdd(&lh[lb], (uint32_t)__popcll(same));
+        if ((int)(threadIdx.x & 63) == leader) atomicAdd(&lh[lb], (uint32_t)__popcll(same));
         on = on && bin != lb;
     }
     if (on) atomicAdd(&lh[bin], 1u);
@@ -259,6 +268,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
     // s * 4096 + e * 1024 + tid of the (single) batch.
     uint32_t rbits[kRegSets][kSelE]; // score bits
     int rid[kRegSets][kSelE];        // token id
+    int rrow[kRegSets][kSelE];       // the token's row in the V pool (asked for early: the counting passes hide the trip)
     bool in_regs = false;
     int reg_total = 0;
     if (n_batches == 1) {
@@ -272,7 +282,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
 #pragma unroll
             for (int s = 0; s < kRegSets; ++s) {
 #pragma unroll
-                for (int e = 0; e < kSelE; ++e) { rbits[s][e] = 0u; rid[s][e] = 0; }
+                for (int e = 0; e < kSelE; ++e) { rbits[s][e] = 0u; rid[s][e] = 0; rrow[s][e] = 0; }
                 if (s * kSelChunk >= b.total) continue; // (uniform)
 #pragma unroll
                 for (int e = 0; e < kSelE; ++e) {
@@ -283,6 +293,12 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
                         rid[s][e] = (int)pr.y;
                     }
                 }
+                if (sel_rows) {
+#pragma unroll
+                    for (int e = 0; e < kSelE; ++e)
+                        if (s * kSelChunk + e * kSelectThreads + tid < b.total)
+                            rrow[s][e] = page_table[dsc.pt_off + (rid[s][e] >> 6)] * kPageTokens + (rid[s][e] & 63);
+                }
             }
         }
     }
@@ -291,18 +307,27 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
     // the window) whose bits from `pshift` up equal `prefix` (pshift = 32: all of them).  lh must be zero;
     // the barriers around the pass are the caller's.
     auto count_pass = [&](int shift, uint32_t mask, int pshift, uint32_t prefix) {
+        auto digit = [&](uint32_t key) { return (key >> shift) & mask; };
+        auto counted = [&](uint32_t key, int tok, bool in) {
+            return in && !in_window(dsc, tok) && (pshift >= 32 || (key >> pshift) == prefix);
+        };
         if (in_regs) {
+            // (one decision per wavefront and pass, from its first survivors: two straight-line copies of the loop)
+            auto all_sets = [&](auto crowded) {
 #pragma unroll
-            for (int s = 0; s < kRegSets; ++s) {
-                if (s * kSelChunk >= reg_total) continue;
+                for (int s = 0; s < kRegSets; ++s) {
+                    if (s * kSelChunk >= reg_total) continue;
 #pragma unroll
-                for (int e = 0; e < kSelE; ++e) {
-                    const int t = s * kSelChunk + e * kSelectThreads + tid;
-                    const uint32_t key = ord_key(__uint_as_float(rbits[s][e]));
-                    hist_add(lh, (key >> shift) & mask,
-                             t < reg_total && !in_window(dsc, rid[s][e]) && (pshift >= 32 || (key >> pshift) == prefix));
+                    for (int e = 0; e < kSelE; ++e) {
+                        const uint32_t key = ord_key(__uint_as_float(rbits[s][e]));
+                        hist_add(lh, digit(key), counted(key, rid[s][e], s * kSelChunk + e * kSelectThreads + tid < reg_total),
+                                 decltype(crowded)::value);
+                    }
                 }
-            }
+            };
+            const uint32_t key0 = ord_key(__uint_as_float(rbits[0][0]));
+            if (is_crowded(digit(key0), counted(key0, rid[0][0], tid < reg_total))) all_sets(std::true_type{});
+            else all_sets(std::false_type{});
             return;
         }
         for (int bi = 0; bi < n_batches; ++bi) {
@@ -318,11 +343,12 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
                     in[u] = t < b.total;
                     pr[u] = in[u] ? batch_pair(hb, b, off, st, t) : make_uint2(0u, 0u);
                 }
+                const uint32_t key0 = ord_key(__uint_as_float(pr[0].x));
+                const bool crowded = is_crowded(digit(key0), counted(key0, (int)pr[0].y, in[0]));
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const uint32_t key = ord_key(__uint_as_float(pr[u].x));
-                    hist_add(lh, (key >> shift) & mask,
-                             in[u] && !in_window(dsc, (int)pr[u].y) && (pshift >= 32 || (key >> pshift) == prefix));
+                    hist_add(lh, digit(key), counted(key, (int)pr[u].y, in[u]), crowded);
                 }
             }
         }
@@ -374,7 +400,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
     // Placement, chunk by chunk in flat (= token) order.
     int baseA = 0, baseT = 0, parity = 0;
     float mx = -INFINITY; // maximum of the scores this thread enters into the list
-    auto place_chunk = [&](const uint32_t *bits, const int *tok, const bool *in) {
+    auto place_chunk = [&](const uint32_t *bits, const int *tok, const bool *in, const int *vrow) {
         bool fa[kSelE], fb[kSelE];
 #pragma unroll
         for (int e = 0; e < kSelE; ++e) {
@@ -401,7 +427,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
                 ids[pos] = tok[e];
                 ss[pos] = v;
                 // where the gather finds the token's value row: physical page * 64 + slot
-                if (sel_rows) rows[pos] = page_table[dsc.pt_off + (tok[e] >> 6)] * kPageTokens + (tok[e] & 63);
+                if (sel_rows) rows[pos] = vrow ? vrow[e] : page_table[dsc.pt_off + (tok[e] >> 6)] * kPageTokens + (tok[e] & 63);
                 if (out_ids && (int64_t)pos < ids_stride) out_ids[(size_t)rh * (size_t)ids_stride + pos] = tok[e];
                 mx = fmaxf(mx, v);
             }
@@ -416,7 +442,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
             bool in[kSelE];
 #pragma unroll
             for (int e = 0; e < kSelE; ++e) in[e] = s * kSelChunk + e * kSelectThreads + tid < reg_total;
-            place_chunk(rbits[s], rid[s], in);
+            place_chunk(rbits[s], rid[s], in, rrow[s]);
         }
     } else {
         for (int bi = 0; bi < n_batches; ++bi) {
@@ -434,7 +460,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
                     bits[e] = pr.x;
                     tok[e] = (int)pr.y;
                 }
-                place_chunk(bits, tok, in);
+                place_chunk(bits, tok, in, nullptr);
             }
         }
     }
