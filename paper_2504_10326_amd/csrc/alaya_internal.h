@@ -121,6 +121,22 @@ struct Shape {
     int n_kv_heads;
 };
 
+#ifdef __HIPCC__
+// Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel-primitive moves (no trip through LDS,
+// which is what a shuffle is on this chip): shifts by 1, 2, 4, 8 inside each row of 16 lanes - a lane without
+// a source adds 0 - then the last lane of row 0 / 2 is added to row 1 / 3, then lane 31 to rows 2 and 3.
+__device__ __forceinline__ int wave_scan(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false); // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false); // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false); // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false); // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false); // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false); // row_bcast:31 into rows 2 and 3
+    return v;
+}
+#endif
+
 // Launchers (one per kernel family).  Each returns the hipError_t of its launch.
 hipError_t launch_append(const Shape &sh, const int32_t *page_table_row, void *k_pool, void *v_pool,
                          const void *k, const void *v, int64_t n_old, int64_t t, hipStream_t st);

@@ -324,12 +324,7 @@ __global__ __launch_bounds__(kSelectThreads) void tau_kernel(const ReqDesc *__re
     cnts[b0] = c0;
     cnts[b0 - 1] = c1;
     if (tid == 0) found = found_est = -1;
-    int inc = c0 + c1;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const int t = __shfl_up(inc, o);
-        if (lane >= o) inc += t;
-    }
+    const int inc = wave_scan(c0 + c1);
     if (lane == 63) wtot[wave] = inc;
     __syncthreads();
     int above = inc - (c0 + c1);

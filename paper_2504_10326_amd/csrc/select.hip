@@ -58,12 +58,7 @@ __device__ __forceinline__ void chunk_ranks(ScanShared &sh, int parity, const bo
     __syncthreads();
     if (wave == 0) {
         const int a = sh.cnt[parity][0][lane], b = sh.cnt[parity][1][lane];
-        int ia = a, ib = b;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int ta = __shfl_up(ia, o), tb = __shfl_up(ib, o);
-            if (lane >= o) { ia += ta; ib += tb; }
-        }
+        const int ia = wave_scan(a), ib = wave_scan(b);
         sh.cnt[parity][0][lane] = ia - a;
         sh.cnt[parity][1][lane] = ib - b;
         if (lane == 63) { sh.tot[parity][0] = ia; sh.tot[parity][1] = ib; }
@@ -91,12 +86,7 @@ __device__ __forceinline__ void block_find_bin(const uint32_t *hist, int nbins, 
     const int c0 = (int)hist[b0];
     const int c1 = per == 2 ? (int)hist[b0 - 1] : 0;
     const int local = c0 + c1;
-    int inc = local;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const int t = __shfl_up(inc, o);
-        if (lane >= o) inc += t;
-    }
+    const int inc = wave_scan(local);
     if (lane == 63) wtot[wave] = inc;
     __syncthreads();
     int above = inc - local;
@@ -171,12 +161,7 @@ __device__ __forceinline__ Batch load_batch(const HeadBlocks &hb, int first_tile
         s4[u] = (int)hd.y;
         sum += a[u];
     }
-    int inc = sum;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const int t = __shfl_up(inc, o);
-        if (lane >= o) inc += t;
-    }
+    const int inc = wave_scan(sum);
     __syncthreads(); // wtot, off, st: the readers of the batch before this one are done
     if (lane == 63) wtot[wave] = inc;
     __syncthreads();
