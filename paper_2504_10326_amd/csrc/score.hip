@@ -91,8 +91,8 @@ hipError_t launch_append_step(const Shape &sh, const DeviceViews &dv, void *k_po
 //
 // bf16 uses the packed dot-product instruction (two bf16 products and the fp32 accumulate in one op,
 // both operands used as stored); fp32 uses fused multiply-add.  The group's queries come from scalar registers in
-// the sample pass and in dense attention, and from LDS (a broadcast read per 16 bytes) in the main pass, where
-// G * 64 words of them do not fit the scalar registers next to everything else that is wave-uniform there.  (The same contraction on the matrix cores - v_mfma_f32_16x16x32_bf16 with the four
+// dense attention, and from LDS (a broadcast read per 16 bytes) in the sample and main passes, where G * 64
+// words of them do not fit the scalar registers next to everything else that is wave-uniform there.  (The same contraction on the matrix cores - v_mfma_f32_16x16x32_bf16 with the four
 // heads of a group on four rows of the 16-row operand - was measured on a 2 GiB pool and runs at the
 // same speed, 6.09 against 6.03 TB/s: the pass is bound by the memory system, not by the arithmetic.)
 //
@@ -138,12 +138,7 @@ __global__ __launch_bounds__(256) void sample_kernel(const ReqDesc *__restrict__
     // two 16-bit counters per word: a workgroup scores 4 pages = 256 tokens per head
     __shared__ uint32_t lhist[G][kHistBins / 2];
     __shared__ float wmax[kScoreWaves][G];
-    const bool hist_on = mode == 0;
-    if (hist_on)
-        for (int i = threadIdx.x; i < G * (kHistBins / 2); i += 256) (&lhist[0][0])[i] = 0u;
-    if (threadIdx.x < kScoreWaves * G) (&wmax[0][0])[threadIdx.x] = -INFINITY;
-    __syncthreads();
-
+    __shared__ uint4 q_lds[G * NC]; // the group's queries
     const int kvh = blockIdx.x % H_kv;
     const int tile = blockIdx.x / H_kv;
     int r = 0;
@@ -151,6 +146,13 @@ __global__ __launch_bounds__(256) void sample_kernel(const ReqDesc *__restrict__
     const ReqDesc dsc = desc[r];
     const int H_q = H_kv * G;
     const int rh0 = r * H_q + kvh * G; // first head of this group
+    const bool hist_on = mode == 0;
+    if (threadIdx.x < G * NC) q_lds[threadIdx.x] = ((const uint4 *)(qw + (size_t)rh0 * QW))[threadIdx.x];
+    if (hist_on)
+        for (int i = threadIdx.x; i < G * (kHistBins / 2); i += 256) (&lhist[0][0])[i] = 0u;
+    if (threadIdx.x < kScoreWaves * G) (&wmax[0][0])[threadIdx.x] = -INFINITY;
+    __syncthreads();
+
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int S = dsc.sample_stride;
@@ -192,7 +194,7 @@ __global__ __launch_bounds__(256) void sample_kernel(const ReqDesc *__restrict__
         }
         const uint4 *base = kp + ((size_t)phys * H_kv + kvh) * (size_t)(NC * 64) + lane;
         float acc[G];
-        score_page<DT, D, G>(base, (const uint4 *)(qw + (size_t)rh0 * QW), acc);
+        score_page_lds<DT, D, G>(base, q_lds, acc);
         const int j = p * kPageTokens + lane;
         const bool valid = j < dsc.n;
         const bool win = in_window(dsc, j);
