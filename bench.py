@@ -14,16 +14,18 @@ repeats the measurement on the other configurations (128K, 256K at beta = 2 and 
 
   value       keys scored per second over the whole step  (a key-score = one (query head, token) pair)
   roofline    the main scoring kernel against the 8 TB/s HBM peak.  Algorithmic bytes per launch =
-              256 B (one bf16 K row, read once) x the K rows of the call (tokens rounded up to pages
-              x KV heads); the few survivors it writes are not counted.  Duration = the kernel's
+              256 B (one bf16 K row, read once) x the K rows that the launch has to read: those of the
+              call (tokens rounded up to pages x KV heads) less the pages that the sample pass has
+              scored already and hands over as scores (every 8th to 32nd page); the handed-over scores
+              and the few survivors it writes are not counted.  Duration = the kernel's
               average over a profiled repeat of the timed loop, taken with HIP events attached to
               the kernel's own dispatch on the launch stream (the library's profiling mode; events
               between kernels would lengthen the timed steps themselves, so the timed loop runs
               without them).  When the keys of the call are smaller than 512 MB they partly survive
               in the 256 MB last-level cache from step to step, which no model with many layers
               would see: `frac` is then taken from the cold loop (cache flushed before every step)
-              and the warm figure is reported beside it.  scoring_pass_frac = the same bytes over
-              sample pass + bound + main pass.
+              and the warm figure is reported beside it.  scoring_pass_frac = every K row of the
+              call, once, over sample pass + bound + main pass.
   gather      the gather + attend kernel: one V row (256 B) per selected (head, token), same clock
   cpu_baseline  the CPU oracle on the same step, on this host's cores (a reported baseline only)
 """
@@ -147,13 +149,15 @@ def measure(name, args, steps, warmup, cold_steps, cpu_baseline, beta=None, dens
     pages_sampled, pages_main = c.debug_pages()              # of the last step (the context grows by one token a step)
     survivors = c.debug_survivors()
     bytes_per_row = w.head_dim * 2                            # one bf16 K row, read once
-    bytes_per_launch = pages_main * 64 * w.n_kv_heads * bytes_per_row
+    bytes_per_launch = pages_main * 64 * w.n_kv_heads * bytes_per_row   # the pages whose keys the main pass reads
+    pages_call = sum((c.seq_len(r) + 63) // 64 for r in seqs)
+    bytes_per_call = pages_call * 64 * w.n_kv_heads * bytes_per_row     # every K row of the call, once
 
     def per_kernel(k):
         us = {n: round(v["sum_ms"] / v["launches"] * 1e3, 2) for n, v in k.items() if v["launches"]}
         main_s = k["score"]["sum_ms"] / max(1, k["score"]["launches"]) * 1e-3
         pass_s = main_s + k["sample"]["sum_ms"] / max(1, k["sample"]["launches"]) * 1e-3
-        return us, bytes_per_launch / main_s / 1e9, bytes_per_launch / pass_s / 1e9, main_s
+        return us, bytes_per_launch / main_s / 1e9, bytes_per_call / pass_s / 1e9, main_s
 
     kernels_us, warm_gbs, warm_pass_gbs, warm_main_s = per_kernel(kt)
     # The gather + attend kernel reads one V row per selected (head, token).
@@ -281,7 +285,7 @@ def measure(name, args, steps, warmup, cold_steps, cpu_baseline, beta=None, dens
         "survivor_fraction": survivors / (w.n_q_heads * total_n),
         "repaired_heads_per_step": repairs / steps,
         "coarse": None if coarse_div <= 0 else {"pages_per_head": kw["coarse_pages"], "recall_of_exact_topk": recall},
-        "pages": {"sampled": pages_sampled, "main_pass": pages_main},
+        "pages": {"call": pages_call, "sampled": pages_sampled, "main_pass_reads": pages_main},
         "roofline": {"bound": "hbm", "kernel": "main_kernel (main scoring pass)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "cache": "cold (last-level cache flushed before every step)" if use_cold else

@@ -74,7 +74,8 @@ int64_t alaya_debug_diprs_list(alaya_cache *c, int head, int32_t *ids, int64_t c
 
 /* How the last alaya_sparse_attn call split its pages (one page = 64 tokens of one sequence, scored
  * for every KV head): *sampled pages were scored by the sample pass for the threshold bound,
- * *main_pass pages by the main scoring kernel (all of them).  HOST pointers. */
+ * *main_pass pages whose keys the main scoring kernel read (all but those of the sample pass whose scores that pass
+ * handed over).  HOST pointers. */
 int alaya_debug_pages(const alaya_cache *c, int64_t *sampled, int64_t *main_pass);
 
 #ifdef __cplusplus

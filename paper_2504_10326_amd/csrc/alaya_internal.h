@@ -11,6 +11,7 @@ constexpr int kMaxPagesPerWave = 4;  // pages one wavefront of the main pass sco
 constexpr int kSelectThreads = 1024;
 constexpr int kAttendThreads = 256;
 constexpr int kMaxSplits = 64;
+constexpr int kSampScoresMinStride = 8; // sample strides from which the sample pass hands its scores to the main pass
 constexpr int kHistBins = 2048;      // top 11 bits of the order-preserving score image
 constexpr int kRepairGrid = 512;     // workgroups of the (normally idle) repair scoring pass, at most
 constexpr int kMaxSlots = 64;        // addresses one head's sample-pass maxima are spread over
@@ -43,7 +44,8 @@ struct ReqDesc {
                            // pass writes.  Only the every-S-th pages enter top-k's histogram.
     int32_t hist_cap;      // top-k: what one sample-pass workgroup (four sampled pages) may add to one bucket, at most
     int32_t pm_stride;     // coarse index: bytes between the KV heads' rows of this request's page mask
-    int64_t pm_off;        // coarse index: first byte of this request's page mask
+    int64_t pm_off;        // coarse index: first byte of this request's page mask; without it: this request's first
+                           // entry in the sample pass's score area (DeviceViews::samp), in pages
     int32_t flags;         // bit 0 (short_ok): top-k, fewer than k candidates is no failure, all of them are taken (coarse
                            // index without a bound); bits 8..: the request whose heads the i-th group of selection
                            // workgroups takes, this descriptor being the i-th (requests with the most to select go
@@ -112,6 +114,10 @@ struct DeviceViews {
     int32_t *status;           // device status word
     uint32_t *repairs;         // heads that took the repair path since the counter was last read (inspection)
     const uint8_t *pmask;      // coarse index: one byte per (KV head, page), bit g = head g of the group chose the page
+    // Scores of the sample pass's every-S-th pages (S >= kSampScoresMinStride, no coarse index), which the main pass
+    // takes over instead of reading those pages' keys again: [entry][KV head][G][64] floats, entry = the request's
+    // pm_off + page / S.
+    float *samp;
 };
 
 struct Shape {

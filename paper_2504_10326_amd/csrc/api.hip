@@ -90,7 +90,8 @@ Layout make_layout(const alaya_cache_config &c)
 // statistics, partial results.  Sized by the largest call it must serve.
 struct Scratch {
     size_t desc, blocks, sel_scores, sel_ids, sel_rows, zero_begin, hist, head_maxkey, sample_max, fail, zero_end, tau,
-        tau_safe, head_M, counts, partials, status, dbg_total, pg_ids, pg_scores, pg_counts, pg_M, pmask, visited, total;
+        tau_safe, head_M, counts, partials, status, dbg_total, pg_ids, pg_scores, pg_counts, pg_M, pmask, visited, samp, total;
+    int64_t samp_pages;  // capacity of the sample pass's score area, in pages
     int64_t visited_words; // capacity of the DIPRS visited bits, 32-bit words
     int64_t pg_elems;    // capacity of the chosen-page arrays of the coarse index
     int64_t pmask_bytes; // capacity of its page mask
@@ -150,6 +151,9 @@ Scratch make_scratch(int n_q_heads, int n_kv_heads, int head_dim, int64_t max_ba
     // DIPRS: one visited bit per (query head, token)
     S.visited_words = (int64_t)n_q_heads * ((max_batch_tokens + 31) / 32 + 8 * max_batch);
     S.visited = take((size_t)S.visited_words * sizeof(uint32_t));
+    // scores of the sample pass's pages: every S-th page, S >= kSampScoresMinStride, of every request
+    S.samp_pages = pages / kSampScoresMinStride + max_batch;
+    S.samp = take((size_t)S.samp_pages * n_q_heads * kPageTokens * sizeof(float));
     S.total = o;
     return S;
 }
@@ -255,6 +259,7 @@ void bind_views(DeviceViews &dv, const Scratch &S, char *base)
     dv.status = (int32_t *)(base + S.status);
     dv.pmask = (const uint8_t *)(base + S.pmask);
     dv.repairs = (uint32_t *)(base + S.dbg_total + 8);
+    dv.samp = (float *)(base + S.samp);
 }
 
 // Clears what must be zero before a scratch area's first use: statistics, repair marks, status.
@@ -793,7 +798,7 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
     ReqDesc *hp = hd + B; // page-level descriptors of the coarse index (the ring slot holds max_batch >= B more)
     const bool estimate = c->estimate_mode >= 0;
     bool any_est = false;
-    int64_t pages_a = 0, pages_all = 0;
+    int64_t pages_a = 0, pages_all = 0, samp_off = 0, pages_handed = 0;
     int64_t off = 0;
     for (int b = 0; b < B; ++b) {
         // the tokens this query sees: the whole sequence, or the prefix asked for
@@ -875,6 +880,10 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
         // a decode step: the page of the newest token belongs to the sample pass, which writes that token
         if (fused_k) d.xb = std::max(d.xf, std::min(d.xb, (d.n - 1) / kPageTokens));
         const int every = S > 1 ? (d.n_pages + S - 1) / S : 0;
+        if (!coarse) {
+            d.pm_off = samp_off; // the main pass takes the scores of these pages from the sample pass
+            if (S >= kSampScoresMinStride) { samp_off += every; pages_handed += every; }
+        }
         auto not_every = [S](int a, int b) { return S > 1 ? (b - a) - ((b + S - 1) / S - (a + S - 1) / S) : b - a; }; // in [a, b)
         pages_a += every + not_every(0, d.xf) + not_every(d.xb, d.n_pages);
         const int n_a = every + d.xf + (d.n_pages - d.xb); // wavefronts of the sample pass
@@ -916,6 +925,7 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
     }
     const int64_t block_stride = kBlockHdr + (int64_t)kScoreWaves * cp * kPageTokens * G;
     if (off > S.sel_elems) return fail(ALAYA_E_NOMEM, "scratch too small for the selected-token arrays");
+    if (samp_off > S.samp_pages) return fail(ALAYA_E_NOMEM, "scratch too small for the sample pass's scores");
     if ((int64_t)tiles_b * c->cfg.n_kv_heads * block_stride > S.block_words)
         return fail(ALAYA_E_NOMEM, "scratch too small for the survivor blocks");
     const int64_t block_stride_p = kBlockHdr + (int64_t)256 * G; // page level: a block holds the scores of 256 pages
@@ -933,7 +943,7 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
         c->last_B = B;
         c->last_tiles_b = tiles_b;
         c->last_pages_a = pages_a;
-        c->last_pages_b = pages_all;
+        c->last_pages_b = pages_all - pages_handed; // (pages whose keys the main pass reads)
     }
 
     const Shape sh{c->cfg.dtype, c->cfg.head_dim, n_q_heads, c->cfg.n_kv_heads};

@@ -130,7 +130,7 @@ __global__ __launch_bounds__(256) void sample_kernel(const ReqDesc *__restrict__
                                                       const uint32_t *__restrict__ qw, const uint4 *__restrict__ k_pool,
                                                       uint32_t *__restrict__ hist, uint32_t *__restrict__ sample_max,
                                                       int H_kv, int mode, const FusedAppend fa,
-                                                      const uint8_t *__restrict__ pmask)
+                                                      const uint8_t *__restrict__ pmask, float *__restrict__ samp)
 {
     const Descs desc{desc_mem, desc0, desc_n};
     constexpr int NC = D * (DT == 0 ? 2 : 4) / 16;
@@ -195,6 +195,12 @@ __global__ __launch_bounds__(256) void sample_kernel(const ReqDesc *__restrict__
         const uint4 *base = kp + ((size_t)phys * H_kv + kvh) * (size_t)(NC * 64) + lane;
         float acc[G];
         score_page_lds<DT, D, G>(base, q_lds, acc);
+        // The main pass takes the scores of the every-S-th pages from here instead of reading their keys again.
+        if (every_sth && S >= kSampScoresMinStride && !pmask) {
+            float *dst = samp + ((size_t)(dsc.pm_off + w_req) * H_kv + kvh) * (size_t)(G * 64) + lane;
+#pragma unroll
+            for (int g = 0; g < G; ++g) dst[g * 64] = acc[g];
+        }
         const int j = p * kPageTokens + lane;
         const bool valid = j < dsc.n;
         const bool win = in_window(dsc, j);
@@ -252,7 +258,7 @@ static hipError_t launch_sample_g(const Shape &sh, const DeviceViews &dv, int B,
     sample_kernel<DT, D, GG><<<grid, block, 0, st>>>(dv.desc.mem, dv.desc.in, dv.desc.n, B, dv.page_table,     \
                                                      (const uint32_t *)q, (const uint4 *)dv.k_pool, dv.hist,  \
                                                      dv.sample_max, sh.n_kv_heads, mode, dv.fused,           \
-                                                     coarse ? dv.pmask : nullptr)
+                                                     coarse ? dv.pmask : nullptr, dv.samp)
     switch (G) {
     case 1: ALAYA_SAMPLE(1); break;
     case 2: ALAYA_SAMPLE(2); break;
@@ -411,8 +417,11 @@ __device__ __forceinline__ void main_block(const int block, const Descs &desc, i
                                            const uint32_t *__restrict__ tau_in,
                                            const uint32_t *__restrict__ tau_safe,
                                            const uint32_t *__restrict__ fail, int H_kv, int mode,
-                                           uint32_t *head_maxkey, const uint8_t *__restrict__ pmask)
+                                           uint32_t *head_maxkey, const void *__restrict__ aux)
 {
+    // aux: COARSE - the page mask; otherwise the scores that the sample pass left of its every-S-th pages
+    const uint8_t *pmask = (const uint8_t *)aux;
+    const float *samp = (const float *)aux;
     constexpr int NC = D * (DT == 0 ? 2 : 4) / 16;
     constexpr int QW = D * (DT == 0 ? 2 : 4) / 4;
     constexpr int CAP = kPageTokens * CP; // survivors of one wavefront and head, at most
@@ -459,10 +468,18 @@ __device__ __forceinline__ void main_block(const int block, const Descs &desc, i
             const bool holds_window = p * kPageTokens < dsc.w0 || (dsc.w1 > 0 && (p + 1) * kPageTokens > dsc.n - dsc.w1);
             if (chosen == 0u && !holds_window) continue; // (wave-uniform) the page's keys are not read
         }
-        const int phys = page_table[dsc.pt_off + p];
-        const uint4 *base = k_pool + ((size_t)phys * H_kv + kvh) * (size_t)(NC * 64) + lane;
         float acc[G];
-        score_page_lds<DT, D, G>(base, q_lds, acc);
+        const int S = dsc.sample_stride;
+        if (!COARSE && S >= kSampScoresMinStride && (p & (S - 1)) == 0) {
+            // (wave-uniform) a page of the sample: scored there, 1 KiB of scores instead of 16 KiB of keys
+            const float *src = samp + ((size_t)(dsc.pm_off + (p >> (__ffs(S) - 1))) * H_kv + kvh) * (size_t)(G * 64) + lane;
+#pragma unroll
+            for (int g = 0; g < G; ++g) acc[g] = src[g * 64];
+        } else {
+            const int phys = page_table[dsc.pt_off + p];
+            const uint4 *base = k_pool + ((size_t)phys * H_kv + kvh) * (size_t)(NC * 64) + lane;
+            score_page_lds<DT, D, G>(base, q_lds, acc);
+        }
         const int j = p * kPageTokens + lane;
         const bool valid = j < dsc.n;
         const bool win = in_window(dsc, j); // always a survivor; top-k neither counts nor ranks it
@@ -521,7 +538,7 @@ void main_kernel(const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int 
                                                     const uint32_t *__restrict__ fail,
                                                     const uint32_t *__restrict__ any_fail, int H_kv, int mode,
                                                     int total_blocks, uint32_t *head_maxkey,
-                                                    const uint8_t *__restrict__ pmask)
+                                                    const void *__restrict__ aux)
 {
     const Descs desc{desc_mem, desc0, desc_n};
     if (REPAIR) {
@@ -529,12 +546,12 @@ void main_kernel(const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int 
         if (*any_fail == 0u) return;
         for (int b = blockIdx.x; b < total_blocks; b += gridDim.x) {
             main_block<DT, D, G, CP, REPAIR, COARSE>(b, desc, B, page_table, qw, k_pool, blocks, block_stride, tau_in,
-                                                     tau_safe, fail, H_kv, mode, head_maxkey, pmask);
+                                                     tau_safe, fail, H_kv, mode, head_maxkey, aux);
             __syncthreads(); // the staging area is reused
         }
     } else {
         main_block<DT, D, G, CP, REPAIR, COARSE>(blockIdx.x, desc, B, page_table, qw, k_pool, blocks, block_stride,
-                                                 tau_in, tau_safe, fail, H_kv, mode, head_maxkey, pmask);
+                                                 tau_in, tau_safe, fail, H_kv, mode, head_maxkey, aux);
     }
 }
 
@@ -561,7 +578,7 @@ static hipError_t launch_score_cp(const Shape &sh, const DeviceViews &dv, int B,
                        dv.desc.n, B, dv.page_table, (const uint32_t *)q, (const uint4 *)dv.k_pool, dv.blocks, \
                        dv.block_stride, (const uint32_t *)dv.tau, (const uint32_t *)dv.tau_safe,              \
                        (const uint32_t *)dv.fail, (const uint32_t *)dv.any_fail, sh.n_kv_heads, mode,         \
-                       total_blocks, dv.head_maxkey, dv.pmask)
+                       total_blocks, dv.head_maxkey, CO ? (const void *)dv.pmask : (const void *)dv.samp)
 #define ALAYA_MAIN(CPP)                                                                                       \
     do {                                                                                                      \
         if (coarse && repair) ALAYA_MAIN_K(CPP, true, true);                                                  \
