@@ -771,19 +771,19 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
         }
     }
     // The attend pass: `splits` workgroups per head in the grid, of which a head with `count` selected tokens
-    // uses clamp(count / 128, min_splits, splits) - about 128 tokens per workgroup (what the gather of 256-byte
-    // rows runs fastest with), more workgroups when the call is small.  The grid is sized for the longest
-    // list the call can have (a threshold set's size is not known here: 4096 is assumed, and a longer list
-    // gets more tokens per workgroup).
+    // uses clamp(count / 256, min_splits, splits) - 128 to 256 tokens per workgroup is what the gather of 256-byte
+    // rows runs fastest with, and fewer partial results make the merge shorter - more workgroups when the call
+    // is small.  The grid is sized for the longest list the call can have (a threshold set's size is not known
+    // here: 8192 is assumed, and a longer list gets more tokens per workgroup).
     int splits = c->tune_splits, min_splits = c->tune_splits;
     if (splits <= 0) {
-        int kmax = 4096;
+        int kmax = 8192;
         if (p->mode == ALAYA_TOPK) {
             kmax = 1;
             for (int b = 0; b < B; ++b) kmax = p->topk[b] > kmax ? p->topk[b] : kmax;
         }
         const int64_t kw = (int64_t)kmax + p->window_init + p->window_last;
-        const int per = (int)std::min<int64_t>((kw + 127) / 128, kMaxSplits);
+        const int per = (int)std::min<int64_t>((kw + 255) / 256, kMaxSplits);
         const int fill = (int)std::min<int64_t>((kw + 31) / 32, (512 + B * n_q_heads - 1) / (B * n_q_heads));
         splits = std::min(std::max(std::max(per, fill), 1), kMaxSplits);
         min_splits = std::min(std::max(fill, 1), splits);

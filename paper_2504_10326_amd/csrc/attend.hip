@@ -22,12 +22,13 @@ namespace alaya {
 // `counts` long, ascending by token), as the selection leaves them; sel_rows already holds the rows'
 // places in the V pool, so that the loads of a pass are two deep (row number, row), not three.
 // The grid has `splits` workgroups per head, sized for the longest list of the call; a head uses as many
-// of them as give each about 128 rows (head_splits), the others leave at once.
+// of them as give each about 256 rows (head_splits; small calls more, with fewer rows each, to fill the chip),
+// the others leave at once.
 constexpr int kAttendU = 8;
 
 __device__ __forceinline__ int head_splits(int cnt, int splits, int min_splits)
 {
-    return min(splits, max(min_splits, (cnt + 127) >> 7));
+    return min(splits, max(min_splits, (cnt + 255) >> 8));
 }
 
 template <int DT, int D>
