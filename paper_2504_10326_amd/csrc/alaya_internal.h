@@ -198,7 +198,8 @@ hipError_t launch_attend(const Shape &sh, const DeviceViews &dv, int B, float sc
 // partial layout: [slot][head_dim + 2] = {m (already times scale), l, acc[head_dim]}
 // sparse: slot = (b * n_q_heads + h) * splits + s           (per_request_tiles == 0)
 // full  : slot = (tile_start[b] + t) * n_q_heads + h        (per_request_tiles == 1)
-// sparse: a head's first head_splits(count) slots hold partials (min_splits <= that <= splits), as in the attend pass
+// sparse: a head's first head_splits(count) slots hold partials, as in the attend pass (min_splits: the least
+// number of splits | log2 of the rows per workgroup << 16)
 hipError_t launch_combine(const Shape &sh, const DeviceViews &dv, int B, int splits, int min_splits,
                           int per_request_tiles, int pages_per_tile, float *out, hipStream_t st);
 

@@ -771,22 +771,24 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
         }
     }
     // The attend pass: `splits` workgroups per head in the grid, of which a head with `count` selected tokens
-    // uses clamp(count / 256, min_splits, splits) - 128 to 256 tokens per workgroup is what the gather of 256-byte
-    // rows runs fastest with, and fewer partial results make the merge shorter - more workgroups when the call
-    // is small.  The grid is sized for the longest list the call can have (a threshold set's size is not known
-    // here: 8192 is assumed, and a longer list gets more tokens per workgroup).
-    int splits = c->tune_splits, min_splits = c->tune_splits;
+    // uses clamp(count / rows, min_splits, splits); rows = 128 tokens per workgroup (what the gather of 256-byte
+    // rows runs fastest with), 256 in calls of thousands of workgroups (they gather as fast, and the merge has
+    // half as many partial results to read); more workgroups when the call is small.  The grid is sized for the
+    // longest list the call can have (a threshold set's size is not known here: 4096 is assumed, and a longer
+    // list gets more tokens per workgroup).  The launchers get min_splits | log2(rows) << 16.
+    int splits = c->tune_splits, min_splits = c->tune_splits | (7 << 16);
     if (splits <= 0) {
-        int kmax = 8192;
+        int kmax = 4096;
         if (p->mode == ALAYA_TOPK) {
             kmax = 1;
             for (int b = 0; b < B; ++b) kmax = p->topk[b] > kmax ? p->topk[b] : kmax;
         }
         const int64_t kw = (int64_t)kmax + p->window_init + p->window_last;
-        const int per = (int)std::min<int64_t>((kw + 255) / 256, kMaxSplits);
+        const int rows_log2 = (int64_t)B * n_q_heads * ((kw + 127) / 128) >= 8192 ? 8 : 7;
+        const int per = (int)std::min<int64_t>((kw + (1 << rows_log2) - 1) >> rows_log2, kMaxSplits);
         const int fill = (int)std::min<int64_t>((kw + 31) / 32, (512 + B * n_q_heads - 1) / (B * n_q_heads));
         splits = std::min(std::max(std::max(per, fill), 1), kMaxSplits);
-        min_splits = std::min(std::max(fill, 1), splits);
+        min_splits = std::min(std::max(fill, 1), splits) | (rows_log2 << 16);
     }
 
     ReqDesc *hd;
@@ -1202,9 +1204,9 @@ int alaya_diprs_attn(alaya_cache *c, const alaya_graph *g, int n_q_heads, const 
     }
     if (e != hipSuccess) return fail_hip(e, "DIPRS launch");
     int splits = c->tune_splits > 0 ? c->tune_splits : 16;
-    { Timed tm(c, 2, st); e = launch_attend(sh, c->dv, 1, scale, splits, splits, st); }
+    { Timed tm(c, 2, st); e = launch_attend(sh, c->dv, 1, scale, splits, splits | (7 << 16), st); }
     if (e != hipSuccess) return fail_hip(e, "attend launch");
-    { Timed tm(c, 3, st); e = launch_combine(sh, c->dv, 1, splits, splits, 0, 0, out, st); }
+    { Timed tm(c, 3, st); e = launch_combine(sh, c->dv, 1, splits, splits | (7 << 16), 0, 0, out, st); }
     if (e != hipSuccess) return fail_hip(e, "combine launch");
     c->last_B = 0; // (no survivor blocks to inspect after this call)
     c->last_tiles_b = 0;

@@ -22,13 +22,16 @@ namespace alaya {
 // `counts` long, ascending by token), as the selection leaves them; sel_rows already holds the rows'
 // places in the V pool, so that the loads of a pass are two deep (row number, row), not three.
 // The grid has `splits` workgroups per head, sized for the longest list of the call; a head uses as many
-// of them as give each about 256 rows (head_splits; small calls more, with fewer rows each, to fill the chip),
-// the others leave at once.
+// of them as give each about 128 rows, 256 in large calls (head_splits; small calls more, with fewer rows each,
+// to fill the chip), the others leave at once.
 constexpr int kAttendU = 8;
 
+// min_splits carries two things: the least number of splits in its low 16 bits and log2 of the rows that a
+// workgroup should get (7 or 8) above them.
 __device__ __forceinline__ int head_splits(int cnt, int splits, int min_splits)
 {
-    return min(splits, max(min_splits, (cnt + 255) >> 8));
+    const int sh = min_splits >> 16;
+    return min(splits, max(min_splits & 0xFFFF, (cnt + (1 << sh) - 1) >> sh));
 }
 
 template <int DT, int D>

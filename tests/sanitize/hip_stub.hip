@@ -151,14 +151,15 @@ hipError_t launch_select(const Shape &sh, const DeviceViews &, const SelectIO &i
 hipError_t launch_attend(const Shape &, const DeviceViews &dv, int B, float scale, int splits, int min_splits, hipStream_t)
 {
     ++g_launches;
-    EXPECT(B >= 1 && min_splits >= 1 && min_splits <= splits && splits <= kMaxSplits && scale > 0.f && dv.partials);
+    EXPECT(B >= 1 && (min_splits & 0xFFFF) >= 1 && (min_splits & 0xFFFF) <= splits && splits <= kMaxSplits && scale > 0.f && dv.partials);
+    EXPECT((min_splits >> 16) == 7 || (min_splits >> 16) == 8);
     return hipSuccess;
 }
 hipError_t launch_combine(const Shape &, const DeviceViews &, int B, int splits, int min_splits, int per_request_tiles, int ppt,
                           float *out, hipStream_t)
 {
     ++g_launches;
-    EXPECT(B >= 1 && out && (per_request_tiles ? ppt >= 1 : min_splits >= 1 && min_splits <= splits && splits <= kMaxSplits));
+    EXPECT(B >= 1 && out && (per_request_tiles ? ppt >= 1 : (min_splits & 0xFFFF) >= 1 && (min_splits & 0xFFFF) <= splits && splits <= kMaxSplits));
     return hipSuccess;
 }
 hipError_t launch_full_partial(const Shape &sh, const DeviceViews &dv, int B, const void *q, float scale, int total_tiles,
