@@ -53,8 +53,9 @@ struct ReqDesc {
     int32_t est_cand;      // coarse index: tokens in the pages a head chose (64 P); > 0: the rank that the estimated bound is
                            // read at follows the share of them that the head's sample really holds
 };
-// (The descriptor of a one-request call travels in the kernel arguments, that is in scalar registers, which the
-// main scoring pass is short of: at 104 bytes instead of 96 that pass ran 15 to 25 % slower.)
+// (The descriptor of a one-request call travels in the kernel arguments, that is in scalar registers: at 104
+// bytes instead of 96 the main scoring pass, which then kept its queries in scalar registers too, ran 15 to 25 %
+// slower.  Keep it at 96.)
 static_assert(sizeof(ReqDesc) == 96, "ReqDesc layout");
 
 // How the kernels get at the request descriptors.  A call of one request carries its descriptor in
