@@ -16,6 +16,8 @@ constexpr int kHistBins = 2048;      // top 11 bits of the order-preserving scor
 constexpr int kRepairGrid = 512;     // workgroups of the (normally idle) repair scoring pass, at most
 constexpr int kMaxSlots = 64;        // addresses one head's sample-pass maxima are spread over
 constexpr int kBlockHdr = 8;         // 8-byte words at the head of a survivor block: {count, start} per head of the group
+constexpr int kHeadStride = 512;     // 8-byte words of a block's dense part: the header and its first kHeadCap survivors
+constexpr int kHeadCap = kHeadStride - kBlockHdr;
 constexpr int kSelBatch = 4096;      // survivor blocks whose prefix sums the selection holds in LDS at a time
 constexpr int kMaxReqBlocks = 1 << 16; // survivor blocks of one request per KV head, at most
 
@@ -86,6 +88,35 @@ struct FusedAppend {
 __device__ __forceinline__ bool in_window(const ReqDesc &d, int j) { return j < d.w0 || j >= d.n - d.w1; }
 
 // Device views handed to the launchers.
+// Where the survivor blocks lie.  A block seldom holds more than a few hundred survivors but may hold every token
+// it covers, and the blocks' writes, a KiB each, are mixed into the stream of key reads: they cost the less the
+// closer together they land.  So every block has a dense part of kHeadStride words - header and first kHeadCap
+// survivors - next to its neighbours', and the survivors beyond those, if any, go to a second area with room for
+// the rest of a full block.  (Blocks of full size next to each other, 33 KiB apart, made the main pass of the
+// batched workload 2 % slower.)
+struct BlockArea {
+    uint2 *head;         // [block][kHeadStride]
+    uint2 *rest;         // [block][rest_stride]: the block's survivors from the kHeadCap-th on
+    int64_t rest_stride; // 0 when no block can hold more than kHeadCap
+#ifdef __HIPCC__
+    __device__ __forceinline__ uint2 *hdr(size_t block) const { return head + block * (size_t)kHeadStride; }
+    __device__ __forceinline__ uint2 *at(size_t block, int p) const
+    {
+        return p < kHeadCap ? head + block * (size_t)kHeadStride + kBlockHdr + p
+                            : rest + block * (size_t)rest_stride + (p - kHeadCap);
+    }
+#endif
+};
+// 8-byte words that n_blocks blocks of at most `full` survivors take
+inline int64_t block_area_words(int64_t n_blocks, int64_t full)
+{
+    return n_blocks * (kHeadStride + (full > kHeadCap ? full - kHeadCap : 0));
+}
+inline BlockArea make_block_area(uint2 *mem, int64_t n_blocks, int64_t full)
+{
+    return BlockArea{mem, mem + n_blocks * kHeadStride, full > kHeadCap ? full - kHeadCap : 0};
+}
+
 struct DeviceViews {
     DescArgs desc;             // the call's request descriptors
     FusedAppend fused;         // set for the duration of a decode-step call, all null otherwise
@@ -93,11 +124,11 @@ struct DeviceViews {
     const void *k_pool;
     const void *v_pool;
     // Everything below lives in the scratch memory of the call.
-    // Scoring output: one block per main-pass workgroup = (tile, KV head), blocks[(tile * H_kv + kvh) * block_stride]:
-    // kBlockHdr words of header ({count, start} for each head of the group), then the survivors as
-    // (score bits, token id) pairs, head after head, each head's ascending by token.
-    uint2 *blocks;
-    int64_t block_stride;      // 8-byte words between blocks: kBlockHdr + 4 * pages per wave * 64 * G
+    // Scoring output: one block per main-pass workgroup = (tile, KV head), block = tile * H_kv + kvh: kBlockHdr words of
+    // header ({count, start} for each head of the group), then the survivors as (score bits, token id) pairs, head
+    // after head, each head's ascending by token.  See BlockArea for where the words lie.
+    uint2 *blocks;             // the memory that the call's BlockArea is laid out in
+    BlockArea area;            // of the call's token-level blocks
     // what attention reads: [head][head_stride] inside the request's block at score_off
     float *sel_scores;
     int32_t *sel_ids;
@@ -173,8 +204,7 @@ hipError_t launch_score(const Shape &sh, const DeviceViews &dv, int B, const voi
 // coarse index runs the same kernel over block scores).
 struct SelectIO {
     DescArgs desc;          // descriptors of this level
-    const uint2 *blocks;    // survivor blocks
-    int64_t block_stride;
+    BlockArea area;         // survivor blocks
     int32_t *ids;           // selected ids, [head][head_stride] at score_off
     float *scores;          // their scores
     int32_t *rows;          // their V-pool rows, or null (not wanted)
@@ -189,7 +219,7 @@ hipError_t launch_reps_range(const Shape &sh, const int32_t *pt_row, const void 
                              int count, int64_t n_new, hipStream_t st);
 hipError_t launch_reps_step(const Shape &sh, const DeviceViews &dv, void *rep_pool, int B, hipStream_t st);
 hipError_t launch_coarse_score(const Shape &sh, const DeviceViews &dv, const DescArgs &pdesc, int B, const void *q,
-                               const void *rep_pool, int total_tiles, int64_t block_stride, hipStream_t st);
+                               const void *rep_pool, int total_tiles, const BlockArea &area, hipStream_t st);
 hipError_t launch_page_mask(const Shape &sh, const DeviceViews &dv, const DescArgs &pdesc, int B, const int32_t *pg_ids,
                             const int32_t *pg_counts, uint32_t *pmask, hipStream_t st);
 

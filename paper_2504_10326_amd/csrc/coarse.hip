@@ -102,8 +102,8 @@ hipError_t launch_reps_step(const Shape &sh, const DeviceViews &dv, void *rep_po
 template <int DT, int D, int G>
 __global__ __launch_bounds__(256) void coarse_score_kernel(const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int B,
                                                             const int32_t *__restrict__ page_table, const void *__restrict__ qv,
-                                                            const char *__restrict__ rep_pool, uint2 *__restrict__ blocks,
-                                                            int64_t block_stride, int H_kv)
+                                                            const char *__restrict__ rep_pool, const BlockArea area,
+                                                            int H_kv)
 {
     const Descs desc{desc_mem, desc0, desc_n};
     using RS = RowSlice<DT, D>;
@@ -154,24 +154,23 @@ __global__ __launch_bounds__(256) void coarse_score_kernel(const ReqDesc *__rest
     }
     __syncthreads();
     const int cnt = min(256, n_pages - p_tile); // pages of this tile: every one is handed on
-    uint2 *blk = blocks + (size_t)blockIdx.x * (size_t)block_stride;
-    if (threadIdx.x < G) blk[threadIdx.x] = make_uint2((uint32_t)cnt, (uint32_t)(threadIdx.x * cnt));
+    if (threadIdx.x < G) area.hdr(blockIdx.x)[threadIdx.x] = make_uint2((uint32_t)cnt, (uint32_t)(threadIdx.x * cnt));
     if ((int)threadIdx.x < cnt) {
 #pragma unroll
         for (int g = 0; g < G; ++g)
-            blk[kBlockHdr + g * cnt + threadIdx.x] = make_uint2(__float_as_uint(ustage[g][threadIdx.x]), (uint32_t)(p_tile + threadIdx.x));
+            *area.at(blockIdx.x, g * cnt + (int)threadIdx.x) = make_uint2(__float_as_uint(ustage[g][threadIdx.x]), (uint32_t)(p_tile + threadIdx.x));
     }
 }
 
 hipError_t launch_coarse_score(const Shape &sh, const DeviceViews &dv, const DescArgs &pdesc, int B, const void *q,
-                               const void *rep_pool, int total_tiles, int64_t block_stride, hipStream_t st)
+                               const void *rep_pool, int total_tiles, const BlockArea &area, hipStream_t st)
 {
     if (total_tiles <= 0) return hipSuccess;
     const int G = sh.n_q_heads / sh.n_kv_heads;
     const dim3 grid((unsigned)(total_tiles * sh.n_kv_heads)), block(256);
 #define ALAYA_COARSE(DT, D, GG)                                                                               \
     coarse_score_kernel<DT, D, GG><<<grid, block, 0, st>>>(pdesc.mem, pdesc.in, pdesc.n, B, dv.page_table, q,  \
-                                                           (const char *)rep_pool, dv.blocks, block_stride,   \
+                                                           (const char *)rep_pool, area,                      \
                                                            sh.n_kv_heads)
 #define ALAYA_COARSE_G(DT, D)                                                                                 \
     switch (G) {                                                                                              \

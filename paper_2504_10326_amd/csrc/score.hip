@@ -413,7 +413,7 @@ template <int DT, int D, int G, int CP, bool REPAIR, bool COARSE>
 __device__ __forceinline__ void main_block(const int block, const Descs &desc, int B,
                                            const int32_t *__restrict__ page_table,
                                            const uint32_t *__restrict__ qw, const uint4 *__restrict__ k_pool,
-                                           uint2 *__restrict__ blocks, int64_t block_stride,
+                                           const BlockArea &area,
                                            const uint32_t *__restrict__ tau_in,
                                            const uint32_t *__restrict__ tau_safe,
                                            const uint32_t *__restrict__ fail, int H_kv, int mode,
@@ -515,15 +515,15 @@ __device__ __forceinline__ void main_block(const int block, const Descs &desc, i
 #pragma unroll
     for (int s = 0; s < G * kScoreWaves; ++s) off[s + 1] = off[s] + (&wcnt[0][0])[s];
     const int total = off[G * kScoreWaves];
-    uint2 *blk = blocks + (size_t)block * (size_t)block_stride;
     if (threadIdx.x < G)
-        blk[threadIdx.x] = make_uint2((uint32_t)(off[kScoreWaves * threadIdx.x + kScoreWaves] - off[kScoreWaves * threadIdx.x]),
-                                      (uint32_t)off[kScoreWaves * threadIdx.x]);
+        area.hdr(block)[threadIdx.x] =
+            make_uint2((uint32_t)(off[kScoreWaves * threadIdx.x + kScoreWaves] - off[kScoreWaves * threadIdx.x]),
+                       (uint32_t)off[kScoreWaves * threadIdx.x]);
     for (int i = threadIdx.x; i < total; i += 256) {
         int s = 0;
 #pragma unroll
         for (int t = 1; t < G * kScoreWaves; ++t) s += (off[t] <= i) ? 1 : 0;
-        blk[kBlockHdr + i] = stage[s % kScoreWaves][s / kScoreWaves][i - off[s]];
+        *area.at(block, i) = stage[s % kScoreWaves][s / kScoreWaves][i - off[s]];
     }
 }
 
@@ -532,7 +532,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((D * (DT ==
 void main_kernel(const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int B,
                                                     const int32_t *__restrict__ page_table,
                                                     const uint32_t *__restrict__ qw, const uint4 *__restrict__ k_pool,
-                                                    uint2 *__restrict__ blocks, int64_t block_stride,
+                                                    const BlockArea area,
                                                     const uint32_t *__restrict__ tau_in,
                                                     const uint32_t *__restrict__ tau_safe,
                                                     const uint32_t *__restrict__ fail,
@@ -545,12 +545,12 @@ void main_kernel(const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int 
         // launched with a small grid whose workgroups leave at once unless some head was marked
         if (*any_fail == 0u) return;
         for (int b = blockIdx.x; b < total_blocks; b += gridDim.x) {
-            main_block<DT, D, G, CP, REPAIR, COARSE>(b, desc, B, page_table, qw, k_pool, blocks, block_stride, tau_in,
+            main_block<DT, D, G, CP, REPAIR, COARSE>(b, desc, B, page_table, qw, k_pool, area, tau_in,
                                                      tau_safe, fail, H_kv, mode, head_maxkey, aux);
             __syncthreads(); // the staging area is reused
         }
     } else {
-        main_block<DT, D, G, CP, REPAIR, COARSE>(blockIdx.x, desc, B, page_table, qw, k_pool, blocks, block_stride,
+        main_block<DT, D, G, CP, REPAIR, COARSE>(blockIdx.x, desc, B, page_table, qw, k_pool, area,
                                                  tau_in, tau_safe, fail, H_kv, mode, head_maxkey, aux);
     }
 }
@@ -575,8 +575,8 @@ static hipError_t launch_score_cp(const Shape &sh, const DeviceViews &dv, int B,
     const dim3 grid((unsigned)(repair && total_blocks > kRepairGrid ? kRepairGrid : total_blocks)), block(256);
 #define ALAYA_MAIN_K(CPP, RP, CO)                                                                             \
     launch_maybe_timed(main_kernel<DT, D, G, CPP, RP, CO>, grid, block, st, ev0, ev1, dv.desc.mem, dv.desc.in, \
-                       dv.desc.n, B, dv.page_table, (const uint32_t *)q, (const uint4 *)dv.k_pool, dv.blocks, \
-                       dv.block_stride, (const uint32_t *)dv.tau, (const uint32_t *)dv.tau_safe,              \
+                       dv.desc.n, B, dv.page_table, (const uint32_t *)q, (const uint4 *)dv.k_pool, dv.area,   \
+                       (const uint32_t *)dv.tau, (const uint32_t *)dv.tau_safe,                               \
                        (const uint32_t *)dv.fail, (const uint32_t *)dv.any_fail, sh.n_kv_heads, mode,         \
                        total_blocks, dv.head_maxkey, CO ? (const void *)dv.pmask : (const void *)dv.samp)
 #define ALAYA_MAIN(CPP)                                                                                       \
@@ -643,7 +643,7 @@ hipError_t launch_fill_u32(uint32_t *p, size_t n, uint32_t v, hipStream_t st)
 // ------------------------------------------------------------------------------------------------
 // Inspection: scatter the survivors' scores of the last call into dense rows, and count them.
 __global__ __launch_bounds__(256) void debug_scatter_kernel(const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int B,
-                                                             const uint2 *__restrict__ blocks, int64_t block_stride,
+                                                             const BlockArea area,
                                                              int H_kv, int G, float *__restrict__ out,
                                                              unsigned long long *__restrict__ total)
 {
@@ -653,14 +653,13 @@ __global__ __launch_bounds__(256) void debug_scatter_kernel(const ReqDesc *__res
     int r = 0;
     while (r + 1 < B && desc[r + 1].tileb_start <= tile) ++r;
     const ReqDesc dsc = desc[r];
-    const uint2 *blk = blocks + (size_t)blockIdx.x * (size_t)block_stride;
     unsigned long long sum = 0;
     for (int g = 0; g < G; ++g) {
-        const uint2 hd = blk[g];
+        const uint2 hd = area.hdr(blockIdx.x)[g];
         sum += hd.x;
         if (out)
             for (uint32_t i = threadIdx.x; i < hd.x; i += 256) {
-                const uint2 pr = blk[kBlockHdr + hd.y + i];
+                const uint2 pr = *area.at(blockIdx.x, (int)(hd.y + i));
                 out[(size_t)dsc.score_off + (size_t)(kvh * G + g) * dsc.head_stride + pr.y] = __uint_as_float(pr.x);
             }
     }
@@ -672,7 +671,7 @@ hipError_t launch_debug_scatter(const Shape &sh, const DeviceViews &dv, int B, i
 {
     if (total_tiles <= 0) return hipSuccess;
     debug_scatter_kernel<<<dim3((unsigned)(total_tiles * sh.n_kv_heads)), dim3(256), 0, st>>>(
-        dv.desc.mem, dv.desc.in, dv.desc.n, B, dv.blocks, dv.block_stride, sh.n_kv_heads, sh.n_q_heads / sh.n_kv_heads,
+        dv.desc.mem, dv.desc.in, dv.desc.n, B, dv.area, sh.n_kv_heads, sh.n_q_heads / sh.n_kv_heads,
         out, total);
     return hipGetLastError();
 }

@@ -128,13 +128,11 @@ __device__ __forceinline__ void hist_add(uint32_t *lh, uint32_t bin, bool on, bo
 
 // Where one head's survivors are: its KV head's blocks, and its slot in their headers.
 struct HeadBlocks {
-    const uint2 *__restrict__ blocks;
-    int64_t block_stride;
+    BlockArea area;
     int H_kv, kvh, g;
-    __device__ __forceinline__ const uint2 *block(int tile) const
-    {
-        return blocks + ((size_t)tile * H_kv + kvh) * (size_t)block_stride;
-    }
+    __device__ __forceinline__ size_t block(int tile) const { return (size_t)tile * H_kv + kvh; }
+    __device__ __forceinline__ uint2 header(int tile) const { return area.hdr(block(tile))[g]; }  // {count, start}
+    __device__ __forceinline__ uint2 pair(int tile, int p) const { return *area.at(block(tile), p); } // p-th of the block
 };
 
 // The survivors of one head in a batch of consecutive blocks, addressed by a flat index.
@@ -156,7 +154,7 @@ __device__ __forceinline__ Batch load_batch(const HeadBlocks &hb, int first_tile
     for (int u = 0; u < 4; ++u) {
         const int i = 4 * tid + u;
         uint2 hd = make_uint2(0u, 0u);
-        if (i < nb) hd = hb.block(first_tile + i)[hb.g];
+        if (i < nb) hd = hb.header(first_tile + i);
         a[u] = (int)hd.x;
         s4[u] = (int)hd.y;
         sum += a[u];
@@ -197,7 +195,7 @@ __device__ __forceinline__ int batch_block(const int32_t *off, int lo, int hi, i
 __device__ __forceinline__ uint2 batch_pair(const HeadBlocks &hb, const Batch &b, const int32_t *off, const int32_t *st, int t)
 {
     const int lo = batch_block(off, 0, b.nb, t);
-    return hb.block(b.first_tile + lo)[kBlockHdr + st[lo] + (t - off[lo])];
+    return hb.pair(b.first_tile + lo, st[lo] + (t - off[lo]));
 }
 
 // The same for the 64 consecutive flat indices that the lanes of a wavefront hold (t - lane a multiple
@@ -208,13 +206,13 @@ __device__ __forceinline__ uint2 batch_pair_grouped(const HeadBlocks &hb, const 
 {
     const int grp = t >> 6;
     const int lo = batch_block(off, gfirst[grp], min(b.nb, gfirst[grp + 1] + 1), t);
-    return hb.block(b.first_tile + lo)[kBlockHdr + st[lo] + (t - off[lo])];
+    return hb.pair(b.first_tile + lo, st[lo] + (t - off[lo]));
 }
 
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kSelectThreads) void select_kernel(
     const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int H_q, int H_kv, int mode,
-    const uint2 *__restrict__ blocks, int64_t block_stride, uint32_t *__restrict__ head_maxkey,
+    const BlockArea area, uint32_t *__restrict__ head_maxkey,
     uint32_t *__restrict__ fail, uint32_t *__restrict__ any_fail, int redo, int batch_blocks,
     const int32_t *__restrict__ page_table, int32_t *__restrict__ sel_ids, int32_t *__restrict__ sel_rows,
     float *__restrict__ sel_scores, int32_t *__restrict__ counts,
@@ -237,7 +235,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
     const int rh = r * H_q + h;
     if (redo && fail[rh] == 0u) return;
     const int G = H_q / H_kv;
-    const HeadBlocks hb{blocks, block_stride, H_kv, h / G, h % G};
+    const HeadBlocks hb{area, H_kv, h / G, h % G};
     const ReqDesc dsc = desc[r];
     const int tid = threadIdx.x, lane = tid & 63;
     int32_t *ids = sel_ids + (size_t)dsc.score_off + (size_t)h * dsc.head_stride;
@@ -473,7 +471,7 @@ hipError_t launch_select(const Shape &sh, const DeviceViews &dv, const SelectIO 
 {
     if (batch_blocks <= 0 || batch_blocks > kSelBatch) batch_blocks = kSelBatch;
     select_kernel<<<dim3((unsigned)(B * sh.n_q_heads)), dim3(kSelectThreads), 0, st>>>(
-        io.desc.mem, io.desc.in, io.desc.n, sh.n_q_heads, sh.n_kv_heads, mode, io.blocks, io.block_stride,
+        io.desc.mem, io.desc.in, io.desc.n, sh.n_q_heads, sh.n_kv_heads, mode, io.area,
         dv.head_maxkey, dv.fail, dv.any_fail, redo ? 1 : 0, batch_blocks, dv.page_table, io.ids, io.rows,
         io.scores, io.counts, io.head_M, out_ids, out_counts, ids_stride, dv.status, dv.repairs);
     return hipGetLastError();

@@ -121,7 +121,8 @@ hipError_t launch_score(const Shape &sh, const DeviceViews &dv, int B, const voi
     check_descs(sh, dv.desc, B);
     EXPECT(q && (cp == 1 || cp == 2 || cp == 4));
     const int G = sh.n_q_heads / sh.n_kv_heads;
-    EXPECT(dv.block_stride >= kBlockHdr + (int64_t)kScoreWaves * cp * kPageTokens * G); // a full block fits its slot
+    // a full block fits: its dense part, and the rest of it in the second area
+    EXPECT(dv.area.head && dv.area.rest_stride >= (int64_t)kScoreWaves * cp * kPageTokens * G - kHeadCap);
     int next = 0;
     for (int r = 0; r < B; ++r) {
         const ReqDesc d = desc_of(dv.desc, r);
@@ -137,7 +138,7 @@ hipError_t launch_select(const Shape &sh, const DeviceViews &, const SelectIO &i
                          int32_t *out_ids, int32_t *, int64_t ids_stride, hipStream_t)
 {
     ++g_launches;
-    EXPECT(io.desc.n == B && io.blocks && io.ids && io.scores && io.counts && io.head_M);
+    EXPECT(io.desc.n == B && io.area.head && io.ids && io.scores && io.counts && io.head_M);
     EXPECT(mode == 0 || mode == 1);
     EXPECT(batch_blocks >= 0);
     EXPECT(!out_ids || ids_stride > 0);
@@ -203,10 +204,10 @@ hipError_t launch_reps_step(const Shape &, const DeviceViews &dv, void *rep_pool
     return hipSuccess;
 }
 hipError_t launch_coarse_score(const Shape &sh, const DeviceViews &, const DescArgs &pd, int B, const void *q, const void *rep_pool,
-                               int total_tiles, int64_t block_stride, hipStream_t)
+                               int total_tiles, const BlockArea &area, hipStream_t)
 {
     ++g_launches;
-    EXPECT(q && rep_pool && pd.n == B && block_stride >= kBlockHdr + 256 * (sh.n_q_heads / sh.n_kv_heads));
+    EXPECT(q && rep_pool && pd.n == B && area.head && area.rest_stride >= 256 * (sh.n_q_heads / sh.n_kv_heads) - kHeadCap);
     int next = 0;
     for (int r = 0; r < B; ++r) {
         const ReqDesc d = desc_of(pd, r);
