@@ -754,15 +754,25 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
 
     hipStream_t st = (hipStream_t)stream;
     const int G = n_q_heads / c->cfg.n_kv_heads;
-    // Pages per wavefront of the main pass (= pages per survivor block / 4): one, or four where that still
-    // leaves about 3072 workgroups or more (from 384K tokens of 8 KV heads on), so that the blocks are few and
-    // large.  Measured, main pass in us with 1 / 2 / 4 pages per wavefront: 256K tokens 86 / 89 / 93, 384K 132 /
-    // 144 / 128, 512K 175 / 191 / 169, 768K 259 / 282 / 251, 1M 344 / 371 / 332: two is never the best.  The
-    // staging area of a workgroup (4 * cp * 64 * G pairs) stays within 32 KiB.
+    // Pages per wavefront of the main pass (= pages per survivor block / 4): one, or four where that still leaves
+    // about 3072 workgroups or more (from 384K tokens of 8 KV heads on): the selection likes few, large blocks (at 1M
+    // one page per wavefront makes 4096 blocks per KV head and costs it 47 us more), and the pass itself runs as fast
+    // either way for one long request (us with 1 / 2 / 4: 512K tokens 164 / 164 / 163, 768K 241 / 243 / 242; a 256K
+    // threshold query is faster with one: 78 against 88).  A call of many requests runs faster with one (the batched
+    // workload: 758 against 776 us, selection 53 against 46 us), as long as none of them is so long that the
+    // selection pays more than that.  The staging area of a workgroup (4 * cp * 64 * G pairs) stays within 32 KiB.
     int cp = 1;
     {
+        int64_t max_pages = 0;
+        for (int b = 0; b < B; ++b) {
+            const int64_t n = p->n_visible ? (int64_t)p->n_visible[b] : c->seq_len[(size_t)seqs[b]];
+            max_pages = std::max(max_pages, (n + kPageTokens - 1) / kPageTokens);
+        }
         int want = c->tune_ppw;
-        if (want <= 0) want = total_pages * c->cfg.n_kv_heads / (kScoreWaves * kMaxPagesPerWave) >= 3072 ? kMaxPagesPerWave : 1;
+        if (want <= 0) {
+            want = total_pages * c->cfg.n_kv_heads / (kScoreWaves * kMaxPagesPerWave) >= 3072 ? kMaxPagesPerWave : 1;
+            if (B > 1 && max_pages <= 4096) want = 1;
+        }
         if (want > kMaxPagesPerWave) want = kMaxPagesPerWave;
         if (c->tune_ppw > 0) { // (the tests ask for every value)
             while (2 * cp <= want && 2 * cp * G <= 16) cp *= 2;
