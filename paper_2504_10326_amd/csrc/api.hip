@@ -875,7 +875,9 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
                 while (S < 32 && (int64_t)(2 * S) * (2 * S) * d.k <= n && (int64_t)2 * S * d.k * 2 <= n) S *= 2;
                 while (S > 1 && pages / S < 2) S /= 2;
             } else {
-                S = pages >= 8192 ? 32 : 16; // the sample only has to come close to the maximum
+                // (the sample only has to come close to the maximum; its pages are handed to the main pass scored, so a
+                // denser sample costs little: 256K tokens, beta = 4: 135 -> 126 us with 8 instead of 16, beta = 2 the same)
+                S = pages >= 8192 ? 32 : 8;
                 while (S > 1 && pages / S < 2) S /= 2;
             }
         }
