@@ -583,7 +583,7 @@ class Cache:
         return lib().alaya_debug_repairs(self.handle, _stream(stream))
 
     def debug_pages(self) -> Tuple[int, int]:
-        """(pages scored in full by the sample pass, pages scored by the main pass) of the last sparse call."""
+        """(pages scored by the sample pass, pages whose keys the main pass read) of the last sparse call."""
         a, b = ctypes.c_int64(0), ctypes.c_int64(0)
         _check(lib().alaya_debug_pages(self.handle, ctypes.byref(a), ctypes.byref(b)))
         return a.value, b.value
