@@ -15,9 +15,7 @@ constexpr int kSampScoresMinStride = 8; // sample strides from which the sample 
 constexpr int kHistBins = 2048;      // top 11 bits of the order-preserving score image
 constexpr int kRepairGrid = 512;     // workgroups of the (normally idle) repair scoring pass, at most
 constexpr int kMaxSlots = 64;        // addresses one head's sample-pass maxima are spread over
-constexpr int kBlockHdr = 8;         // 8-byte words at the head of a survivor block: {count, start} per head of the group
-constexpr int kHeadStride = 512;     // 8-byte words of a block's dense part: the header and its first kHeadCap survivors
-constexpr int kHeadCap = kHeadStride - kBlockHdr;
+constexpr int kHeadStride = 512;     // 8-byte words of a block's dense part: its first kHeadStride survivors
 constexpr int kSelBatch = 4096;      // survivor blocks whose prefix sums the selection holds in LDS at a time
 constexpr int kMaxReqBlocks = 1 << 16; // survivor blocks of one request per KV head, at most
 
@@ -88,33 +86,41 @@ struct FusedAppend {
 __device__ __forceinline__ bool in_window(const ReqDesc &d, int j) { return j < d.w0 || j >= d.n - d.w1; }
 
 // Device views handed to the launchers.
-// Where the survivor blocks lie.  A block seldom holds more than a few hundred survivors but may hold every token
-// it covers, and the blocks' writes, a KiB each, are mixed into the stream of key reads: they cost the less the
-// closer together they land.  So every block has a dense part of kHeadStride words - header and first kHeadCap
-// survivors - next to its neighbours', and the survivors beyond those, if any, go to a second area with room for
-// the rest of a full block.  (Blocks of full size next to each other, 33 KiB apart, made the main pass of the
-// batched workload 2 % slower.)
+// Where the survivor blocks lie.  One block per main-pass workgroup = (tile, KV head), block = tile * H_kv + kvh: the
+// survivors of the tile as (score bits, token id) pairs, head after head of the group, each head's ascending by token,
+// and a header {count, start} per head.
+//   A block seldom holds more than a few hundred survivors but may hold every token it covers, and the blocks'
+// writes, a KiB each, are mixed into the stream of key reads: they cost the less the closer together they land.  So
+// every block has a dense part of kHeadStride words next to its neighbours', and the survivors beyond those, if any,
+// go to a second area with room for the rest of a full block.  (Blocks of full size next to each other, 33 KiB
+// apart, made the main pass of the batched workload 2 % slower.)
+//   The headers lie apart, one row per query head with the tiles side by side: the selection reads the headers of
+// one head's tiles, which this way are consecutive words (a header inside every block cost it one memory
+// transaction per tile).
 struct BlockArea {
+    uint2 *hdrs;         // [query head = kvh * G + g][n_tiles]
     uint2 *head;         // [block][kHeadStride]
-    uint2 *rest;         // [block][rest_stride]: the block's survivors from the kHeadCap-th on
-    int64_t rest_stride; // 0 when no block can hold more than kHeadCap
+    uint2 *rest;         // [block][rest_stride]: the block's survivors from the kHeadStride-th on
+    int64_t rest_stride; // 0 when no block can hold more than kHeadStride
+    int64_t n_tiles;
 #ifdef __HIPCC__
-    __device__ __forceinline__ uint2 *hdr(size_t block) const { return head + block * (size_t)kHeadStride; }
+    __device__ __forceinline__ uint2 *hdr(int tile, int q_head) const { return hdrs + (size_t)q_head * (size_t)n_tiles + tile; }
     __device__ __forceinline__ uint2 *at(size_t block, int p) const
     {
-        return p < kHeadCap ? head + block * (size_t)kHeadStride + kBlockHdr + p
-                            : rest + block * (size_t)rest_stride + (p - kHeadCap);
+        return p < kHeadStride ? head + block * (size_t)kHeadStride + p : rest + block * (size_t)rest_stride + (p - kHeadStride);
     }
 #endif
 };
-// 8-byte words that n_blocks blocks of at most `full` survivors take
-inline int64_t block_area_words(int64_t n_blocks, int64_t full)
+// 8-byte words that n_tiles tiles of n_kv_heads blocks each, of at most `full` survivors for G heads, take
+inline int64_t block_area_words(int64_t n_tiles, int n_kv_heads, int G, int64_t full)
 {
-    return n_blocks * (kHeadStride + (full > kHeadCap ? full - kHeadCap : 0));
+    return n_tiles * n_kv_heads * (G + kHeadStride + (full > kHeadStride ? full - kHeadStride : 0));
 }
-inline BlockArea make_block_area(uint2 *mem, int64_t n_blocks, int64_t full)
+inline BlockArea make_block_area(uint2 *mem, int64_t n_tiles, int n_kv_heads, int G, int64_t full)
 {
-    return BlockArea{mem, mem + n_blocks * kHeadStride, full > kHeadCap ? full - kHeadCap : 0};
+    const int64_t n_blocks = n_tiles * n_kv_heads;
+    uint2 *head = mem + n_blocks * G;
+    return BlockArea{mem, head, head + n_blocks * kHeadStride, full > kHeadStride ? full - kHeadStride : 0, n_tiles};
 }
 
 struct DeviceViews {
@@ -124,9 +130,7 @@ struct DeviceViews {
     const void *k_pool;
     const void *v_pool;
     // Everything below lives in the scratch memory of the call.
-    // Scoring output: one block per main-pass workgroup = (tile, KV head), block = tile * H_kv + kvh: kBlockHdr words of
-    // header ({count, start} for each head of the group), then the survivors as (score bits, token id) pairs, head
-    // after head, each head's ascending by token.  See BlockArea for where the words lie.
+    // Scoring output: the survivor blocks (see BlockArea).
     uint2 *blocks;             // the memory that the call's BlockArea is laid out in
     BlockArea area;            // of the call's token-level blocks
     // what attention reads: [head][head_stride] inside the request's block at score_off

@@ -104,7 +104,7 @@ struct Scratch {
 int64_t block_words_for(int64_t pages, int64_t batch, int n_kv_heads, int G, int cp)
 {
     const int64_t tiles = (pages + (int64_t)kScoreWaves * cp - 1) / ((int64_t)kScoreWaves * cp) + batch;
-    return block_area_words(tiles * n_kv_heads, (int64_t)kScoreWaves * cp * kPageTokens * G);
+    return block_area_words(tiles, n_kv_heads, G, (int64_t)kScoreWaves * cp * kPageTokens * G);
 }
 
 Scratch make_scratch(int n_q_heads, int n_kv_heads, int head_dim, int64_t max_batch, int64_t max_batch_tokens)
@@ -937,14 +937,14 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
             if (coarse) hp[b].flags = (hp[b].flags & 1) | (order[(size_t)b] << 8);
         }
     }
-    const int64_t n_blocks = (int64_t)tiles_b * c->cfg.n_kv_heads, block_full = (int64_t)kScoreWaves * cp * kPageTokens * G;
+    const int64_t block_full = (int64_t)kScoreWaves * cp * kPageTokens * G;
     if (off > S.sel_elems) return fail(ALAYA_E_NOMEM, "scratch too small for the selected-token arrays");
     if (samp_off > S.samp_pages) return fail(ALAYA_E_NOMEM, "scratch too small for the sample pass's scores");
-    if (block_area_words(n_blocks, block_full) > S.block_words)
+    if (block_area_words(tiles_b, c->cfg.n_kv_heads, G, block_full) > S.block_words)
         return fail(ALAYA_E_NOMEM, "scratch too small for the survivor blocks");
     // page level: a block holds the scores of 256 pages
-    const int64_t n_blocks_p = (int64_t)tiles_p * c->cfg.n_kv_heads, block_full_p = (int64_t)256 * G;
-    if (coarse && (block_area_words(n_blocks_p, block_full_p) > S.block_words || pg_off > S.pg_elems ||
+    const int64_t block_full_p = (int64_t)256 * G;
+    if (coarse && (block_area_words(tiles_p, c->cfg.n_kv_heads, G, block_full_p) > S.block_words || pg_off > S.pg_elems ||
                    pm_off > S.pmask_bytes))
         return fail(ALAYA_E_NOMEM, "scratch too small for the coarse index");
     if (!use) {
@@ -953,7 +953,7 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
     }
     rc = ring_publish(c, dv, slot, B, st, coarse);
     if (rc != ALAYA_OK) return rc;
-    dv.area = make_block_area(dv.blocks, n_blocks, block_full);
+    dv.area = make_block_area(dv.blocks, tiles_b, c->cfg.n_kv_heads, G, block_full);
     if (!use) {
         c->last_B = B;
         c->last_tiles_b = tiles_b;
@@ -977,8 +977,8 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
         int32_t *pg_ids = (int32_t *)(sbase + S.pg_ids), *pg_counts = (int32_t *)(sbase + S.pg_counts);
         e = launch_fill_u32((uint32_t *)(sbase + S.pmask), (size_t)((pm_off + 3) / 4), 0u, st);
         if (e == hipSuccess) e = launch_coarse_score(sh, dv, pd, B, q, c->rep_pool, tiles_p,
-                                                      make_block_area(dv.blocks, n_blocks_p, block_full_p), st);
-        const SelectIO pio{pd, make_block_area(dv.blocks, n_blocks_p, block_full_p), pg_ids, (float *)(sbase + S.pg_scores), nullptr, pg_counts,
+                                                      make_block_area(dv.blocks, tiles_p, c->cfg.n_kv_heads, G, block_full_p), st);
+        const SelectIO pio{pd, make_block_area(dv.blocks, tiles_p, c->cfg.n_kv_heads, G, block_full_p), pg_ids, (float *)(sbase + S.pg_scores), nullptr, pg_counts,
                            (float *)(sbase + S.pg_M)};
         if (e == hipSuccess)
             e = launch_select(sh, dv, pio, B, ALAYA_TOPK, false, c->tune_batch, p->out_pages, nullptr, p->pages_stride, st);

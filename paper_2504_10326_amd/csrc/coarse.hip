@@ -154,7 +154,9 @@ __global__ __launch_bounds__(256) void coarse_score_kernel(const ReqDesc *__rest
     }
     __syncthreads();
     const int cnt = min(256, n_pages - p_tile); // pages of this tile: every one is handed on
-    if (threadIdx.x < G) area.hdr(blockIdx.x)[threadIdx.x] = make_uint2((uint32_t)cnt, (uint32_t)(threadIdx.x * cnt));
+    if (threadIdx.x < G)
+        *area.hdr((int)(blockIdx.x / H_kv), (int)(blockIdx.x % H_kv) * G + (int)threadIdx.x) =
+            make_uint2((uint32_t)cnt, (uint32_t)(threadIdx.x * cnt));
     if ((int)threadIdx.x < cnt) {
 #pragma unroll
         for (int g = 0; g < G; ++g)

@@ -516,7 +516,7 @@ __device__ __forceinline__ void main_block(const int block, const Descs &desc, i
     for (int s = 0; s < G * kScoreWaves; ++s) off[s + 1] = off[s] + (&wcnt[0][0])[s];
     const int total = off[G * kScoreWaves];
     if (threadIdx.x < G)
-        area.hdr(block)[threadIdx.x] =
+        *area.hdr(tile, kvh * G + (int)threadIdx.x) =
             make_uint2((uint32_t)(off[kScoreWaves * threadIdx.x + kScoreWaves] - off[kScoreWaves * threadIdx.x]),
                        (uint32_t)off[kScoreWaves * threadIdx.x]);
     for (int i = threadIdx.x; i < total; i += 256) {
@@ -655,7 +655,7 @@ __global__ __launch_bounds__(256) void debug_scatter_kernel(const ReqDesc *__res
     const ReqDesc dsc = desc[r];
     unsigned long long sum = 0;
     for (int g = 0; g < G; ++g) {
-        const uint2 hd = area.hdr(blockIdx.x)[g];
+        const uint2 hd = *area.hdr(tile, kvh * G + g);
         sum += hd.x;
         if (out)
             for (uint32_t i = threadIdx.x; i < hd.x; i += 256) {

@@ -129,9 +129,9 @@ __device__ __forceinline__ void hist_add(uint32_t *lh, uint32_t bin, bool on, bo
 // Where one head's survivors are: its KV head's blocks, and its slot in their headers.
 struct HeadBlocks {
     BlockArea area;
-    int H_kv, kvh, g;
+    int H_kv, G, kvh, g;
     __device__ __forceinline__ size_t block(int tile) const { return (size_t)tile * H_kv + kvh; }
-    __device__ __forceinline__ uint2 header(int tile) const { return area.hdr(block(tile))[g]; }  // {count, start}
+    __device__ __forceinline__ uint2 header(int tile) const { return *area.hdr(tile, kvh * G + g); } // {count, start}
     __device__ __forceinline__ uint2 pair(int tile, int p) const { return *area.at(block(tile), p); } // p-th of the block
 };
 
@@ -235,7 +235,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
     const int rh = r * H_q + h;
     if (redo && fail[rh] == 0u) return;
     const int G = H_q / H_kv;
-    const HeadBlocks hb{area, H_kv, h / G, h % G};
+    const HeadBlocks hb{area, H_kv, G, h / G, h % G};
     const ReqDesc dsc = desc[r];
     const int tid = threadIdx.x, lane = tid & 63;
     int32_t *ids = sel_ids + (size_t)dsc.score_off + (size_t)h * dsc.head_stride;

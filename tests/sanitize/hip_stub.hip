@@ -122,7 +122,8 @@ hipError_t launch_score(const Shape &sh, const DeviceViews &dv, int B, const voi
     EXPECT(q && (cp == 1 || cp == 2 || cp == 4));
     const int G = sh.n_q_heads / sh.n_kv_heads;
     // a full block fits: its dense part, and the rest of it in the second area
-    EXPECT(dv.area.head && dv.area.rest_stride >= (int64_t)kScoreWaves * cp * kPageTokens * G - kHeadCap);
+    EXPECT(dv.area.hdrs && dv.area.head && dv.area.rest_stride >= (int64_t)kScoreWaves * cp * kPageTokens * G - kHeadStride);
+    EXPECT(dv.area.n_tiles == total_tiles);
     int next = 0;
     for (int r = 0; r < B; ++r) {
         const ReqDesc d = desc_of(dv.desc, r);
@@ -207,7 +208,8 @@ hipError_t launch_coarse_score(const Shape &sh, const DeviceViews &, const DescA
                                int total_tiles, const BlockArea &area, hipStream_t)
 {
     ++g_launches;
-    EXPECT(q && rep_pool && pd.n == B && area.head && area.rest_stride >= 256 * (sh.n_q_heads / sh.n_kv_heads) - kHeadCap);
+    EXPECT(q && rep_pool && pd.n == B && area.hdrs && area.head && area.n_tiles == total_tiles &&
+           area.rest_stride >= 256 * (sh.n_q_heads / sh.n_kv_heads) - kHeadStride);
     int next = 0;
     for (int r = 0; r < B; ++r) {
         const ReqDesc d = desc_of(pd, r);
