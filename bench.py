@@ -421,9 +421,12 @@ def main() -> int:
             per_config[key] = {"ms_per_step": r["ms_per_step"], "keys_per_s": r["value"], "tokens": r["config"]["tokens"],
                                "kernels_us": r["kernels_us"], "survivor_fraction": r["survivor_fraction"],
                                "repaired_heads_per_step": r["repaired_heads_per_step"], "coarse": r["coarse"],
-                               "main_pass_frac": r["roofline"]["frac"], "main_pass_warm_frac": r["roofline"]["warm_frac"],
+                               # (through the coarse index the main pass skips the pages no head chose: the
+                               # bytes of all keys say nothing about it, and no fraction is given)
+                               "main_pass_frac": None if cdiv else r["roofline"]["frac"],
+                               "main_pass_warm_frac": None if cdiv else r["roofline"]["warm_frac"],
                                "main_pass_cache": r["roofline"]["cache"],
-                               "scoring_pass_frac": r["roofline"]["scoring_pass_frac"],
+                               "scoring_pass_frac": None if cdiv else r["roofline"]["scoring_pass_frac"],
                                "gather_frac": r["gather"]["frac"], "gather_rows": r["gather"]["selected_rows"],
                                "cold_kernels_us": r["cold_cache"]["kernels_us"] if r["cold_cache"] else None}
     line = {

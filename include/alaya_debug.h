@@ -22,11 +22,12 @@ extern "C" {
  * figure is the kernel's own run time), 1 select (the selection kernel and, for calls with an
  * estimated bound, the two repair launches), 2 attend, 3 combine, 4 full-attention partial, 5 append
  * (the append kernel; an alaya_decode_step has none: its sample pass writes the new rows), 6 sample
- * (statistics of the sampled pages + the threshold bound).  Slots other than 0 span from an event
+ * (statistics of the sampled pages + the threshold bound), 7 coarse (calls through the coarse index:
+ * block scores, selection of the pages, page mask).  Slots other than 0 span from an event
  * before their first launch to one after their last, dispatch gaps included.
  * sum_ms, launches: HOST arrays of n_slots entries (n_slots <= ALAYA_N_KERNEL_SLOTS).
  */
-#define ALAYA_N_KERNEL_SLOTS 7
+#define ALAYA_N_KERNEL_SLOTS 8
 int alaya_set_profiling(alaya_cache *c, int enabled);
 int alaya_kernel_times(alaya_cache *c, double *sum_ms, int64_t *launches, int n_slots);
 

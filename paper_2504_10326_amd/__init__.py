@@ -22,8 +22,8 @@ ALAYA_BF16, ALAYA_F32 = 0, 1
 ALAYA_TOPK, ALAYA_DIPR = 0, 1
 ALAYA_OK, ALAYA_E_INVAL, ALAYA_E_NOMEM, ALAYA_E_CAPACITY, ALAYA_E_EMPTY, ALAYA_E_DEVICE = 0, -1, -2, -3, -4, -5
 SCORE_PAD = 1088
-N_KERNEL_SLOTS = 7
-KERNEL_SLOTS = ("score", "select", "attend", "combine", "full_partial", "append", "sample")
+N_KERNEL_SLOTS = 8
+KERNEL_SLOTS = ("score", "select", "attend", "combine", "full_partial", "append", "sample", "coarse")
 
 # include/alaya.h
 EXPORTS = (

@@ -214,6 +214,7 @@ struct SelectIO {
     int32_t *rows;          // their V-pool rows, or null (not wanted)
     int32_t *counts;        // [request * head]
     float *head_M;          // [request * head]
+    uint32_t *pmask;        // selection of pages: the page mask (cleared), where each head marks its pages; else null
 };
 hipError_t launch_select(const Shape &sh, const DeviceViews &dv, const SelectIO &io, int B, int mode, bool redo,
                          int batch_blocks, int32_t *out_ids, int32_t *out_counts, int64_t ids_stride, hipStream_t st);
@@ -223,9 +224,7 @@ hipError_t launch_reps_range(const Shape &sh, const int32_t *pt_row, const void 
                              int count, int64_t n_new, hipStream_t st);
 hipError_t launch_reps_step(const Shape &sh, const DeviceViews &dv, void *rep_pool, int B, hipStream_t st);
 hipError_t launch_coarse_score(const Shape &sh, const DeviceViews &dv, const DescArgs &pdesc, int B, const void *q,
-                               const void *rep_pool, int total_tiles, const BlockArea &area, hipStream_t st);
-hipError_t launch_page_mask(const Shape &sh, const DeviceViews &dv, const DescArgs &pdesc, int B, const int32_t *pg_ids,
-                            const int32_t *pg_counts, uint32_t *pmask, hipStream_t st);
+                               const void *rep_pool, int total_tiles, const BlockArea &area, uint8_t *pmask, hipStream_t st);
 
 hipError_t launch_attend(const Shape &sh, const DeviceViews &dv, int B, float scale, int splits, int min_splits,
                          hipStream_t st);

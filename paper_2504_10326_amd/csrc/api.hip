@@ -919,6 +919,8 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
             e.head_stride = (int32_t)(pages + kPageTokens);
             e.score_off = pg_off;
             e.sample_stride = 1;
+            e.pm_off = d.pm_off; // (the block-score kernel clears the mask)
+            e.pm_stride = d.pm_stride;
             e.tileb_start = tiles_p;
             e.ntiles_b = (int32_t)((pages + 255) / 256);
             tiles_p += e.ntiles_b;
@@ -968,21 +970,20 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
     hipError_t e;
     char *sbase = (char *)dv.sel_scores - S.sel_scores; // the scratch area the views point into
     if (coarse) {
-        // Coarse index: block scores of every page -> the best pages of every head (the selection kernel,
-        // over pages) -> one byte per (KV head, page) for the main pass.
-        Timed tm(c, 6, st);
+        // Coarse index: block scores of every page (and a cleared page mask) -> the best pages of every head
+        // (the selection kernel, over pages), marked in one byte per (KV head, page) for the main pass.
+        Timed tm(c, 7, st);
         DescArgs pd = dv.desc;
         pd.mem = dv.desc.mem + B;
         pd.in = hp[0];
         int32_t *pg_ids = (int32_t *)(sbase + S.pg_ids), *pg_counts = (int32_t *)(sbase + S.pg_counts);
-        e = launch_fill_u32((uint32_t *)(sbase + S.pmask), (size_t)((pm_off + 3) / 4), 0u, st);
-        if (e == hipSuccess) e = launch_coarse_score(sh, dv, pd, B, q, c->rep_pool, tiles_p,
-                                                      make_block_area(dv.blocks, tiles_p, c->cfg.n_kv_heads, G, block_full_p), st);
+        e = launch_coarse_score(sh, dv, pd, B, q, c->rep_pool, tiles_p,
+                                make_block_area(dv.blocks, tiles_p, c->cfg.n_kv_heads, G, block_full_p),
+                                (uint8_t *)(sbase + S.pmask), st);
         const SelectIO pio{pd, make_block_area(dv.blocks, tiles_p, c->cfg.n_kv_heads, G, block_full_p), pg_ids, (float *)(sbase + S.pg_scores), nullptr, pg_counts,
-                           (float *)(sbase + S.pg_M)};
+                           (float *)(sbase + S.pg_M), (uint32_t *)(sbase + S.pmask)};
         if (e == hipSuccess)
             e = launch_select(sh, dv, pio, B, ALAYA_TOPK, false, c->tune_batch, p->out_pages, nullptr, p->pages_stride, st);
-        if (e == hipSuccess) e = launch_page_mask(sh, dv, pd, B, pg_ids, pg_counts, (uint32_t *)(sbase + S.pmask), st);
         if (e != hipSuccess) { c->scratch_ready = false; return fail_hip(e, "coarse index launch"); }
     }
     {
@@ -1001,7 +1002,7 @@ int sparse_attn_impl(alaya_cache *c, const ScratchUse *use, const int32_t *seqs,
     if (e != hipSuccess) { c->scratch_ready = false; return fail_hip(e, "score launch"); }
     {
         Timed tm(c, 1, st);
-        const SelectIO io{dv.desc, dv.area, dv.sel_ids, dv.sel_scores, dv.sel_rows, dv.counts, dv.head_M};
+        const SelectIO io{dv.desc, dv.area, dv.sel_ids, dv.sel_scores, dv.sel_rows, dv.counts, dv.head_M, nullptr};
         e = launch_select(sh, dv, io, B, p->mode, false, c->tune_batch, p->out_ids, p->out_counts, p->ids_stride, st);
         // repair of the heads whose estimated bound lost tokens (normally none: both launches are idle)
         if (e == hipSuccess && any_est) e = launch_score(sh, dv, B, q, tiles_b, cp, true, p->mode, coarse, st);

@@ -3,7 +3,7 @@
 // products of the query with the representatives are computed during retrieval, and the critical blocks
 // are selected for the attention computation.  Here a block is a page of 64 tokens and its
 // representatives are two vectors per KV head, the channel-wise minimum lo and maximum hi of its keys;
-//   u[h][b] = sum_c max(q_hc * lo_bc, q_hc * hi_bc)
+//   u[h][b] = sum_c max(q_hc * lo_bc, q_hc * hi_bc) = sum_c max(q_hc, 0) * hi_bc + min(q_hc, 0) * lo_bc
 // is an upper bound of every q_h . k in block b.  The P blocks with the largest u are the critical blocks
 // of head h (equal u: the smaller block), and the top-k query then runs over their tokens only.
 //
@@ -11,11 +11,13 @@
 //                        Session.update, so a query never builds it)
 //   coarse_score_kernel  u for every (page, head), written in the survivor-block format of the scoring
 //                        pass with the page in the place of the token, so that the selection kernel picks
-//                        the P best pages with the very code that picks the k best tokens
-//   page_mask_kernel     turns each head's chosen pages into one byte per (KV head, page), bit g = chosen
-//                        by head g of the group: what the main scoring pass needs to skip a page's keys
+//                        the P best pages with the very code that picks the k best tokens; clears the page mask
+//   select_kernel        (select.hip) also marks each head's chosen pages in one byte per (KV head, page),
+//                        bit g = chosen by head g of the group: what the main scoring pass needs to skip a
+//                        page's keys
 #include "alaya_internal.h"
 #include "row_slice.h"
+#include "score_page.h"
 
 namespace alaya {
 
@@ -96,83 +98,122 @@ hipError_t launch_reps_step(const Shape &sh, const DeviceViews &dv, void *rep_po
 }
 
 // ------------------------------------------------------------------------------------------------
-// Block scores.  Grid: (tile of 256 pages, KV head); descriptors are the PAGE-LEVEL ones (n = pages that
-// hold a visible token, tileb_start / ntiles_b = tiles of 256 pages).  16 lanes per representative row,
-// four pages per wavefront step; the lane's slice of the G queries stays in registers.
+// The sum of x over the 16 lanes of a row (lanes 16 r .. 16 r + 15), in every one of them: four additions whose
+// second operand comes through the DPP rotation of the row.
+__device__ __forceinline__ float row16_sum(float x)
+{
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x128, 0xf, 0xf, false)); // row_ror:8
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x124, 0xf, 0xf, false)); // row_ror:4
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x122, 0xf, 0xf, false)); // row_ror:2
+    x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x121, 0xf, 0xf, false)); // row_ror:1
+    return x;
+}
+
+// Block scores.  Grid: (tile of 256 pages, KV head, quarter of the tile), one wavefront each; descriptors are
+// the PAGE-LEVEL ones (n = pages that hold a visible token, tileb_start / ntiles_b = tiles of 256 pages).
+// 16 lanes per representative row, four pages per step; the lane's slice of the G queries stays in
+// registers, split by sign.  The wavefront reads the page table entries of its 64 pages with one load and then has the rows
+// of many pages on their way at once: taken page after page, every page cost two trips to memory in a row.
+// It also clears the bytes of its pages in the page mask, which the selection of the pages fills afterwards.
 template <int DT, int D, int G>
-__global__ __launch_bounds__(256) void coarse_score_kernel(const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int B,
-                                                            const int32_t *__restrict__ page_table, const void *__restrict__ qv,
-                                                            const char *__restrict__ rep_pool, const BlockArea area,
-                                                            int H_kv)
+__global__ __launch_bounds__(64) void coarse_score_kernel(const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int B,
+                                                           const int32_t *__restrict__ page_table, const void *__restrict__ qv,
+                                                           const char *__restrict__ rep_pool, const BlockArea area,
+                                                           uint8_t *__restrict__ pmask, int H_kv)
 {
     const Descs desc{desc_mem, desc0, desc_n};
     using RS = RowSlice<DT, D>;
-    constexpr int EPL = RS::EPL;
     constexpr size_t ROW_BYTES = (size_t)D * (DT == 0 ? 2 : 4);
-    __shared__ float ustage[G][256];
+    constexpr int UN = RS::WORDS == 8 ? 8 : 16; // pages (x 4) whose rows are in flight together
+    __shared__ float ustage[G][64];
 
-    const int kvh = blockIdx.x % H_kv;
-    const int tile = blockIdx.x / H_kv;
+    const int quarter = blockIdx.x & 3;
+    const int blk = blockIdx.x >> 2; // (tile, KV head): the survivor block
+    const int kvh = blk % H_kv;
+    const int tile = blk / H_kv;
     int r = 0;
     while (r + 1 < B && desc[r + 1].tileb_start <= tile) ++r;
     const ReqDesc dsc = desc[r];
     const int H_q = H_kv * G;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, sub = lane & 15, grp = lane >> 4;
-    float q[G][EPL];
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-        RS::load((const char *)qv + ((size_t)r * H_q + kvh * G + g) * ROW_BYTES, sub, q[g]);
+    const int lane = threadIdx.x, sub = lane & 15, grp = lane >> 4;
     const int p_tile = (tile - dsc.tileb_start) * 256;
     const int n_pages = dsc.n; // page-level descriptor: n counts pages
-#pragma unroll 4
-    for (int it = 0; it < 16; ++it) {
-        const int pi = wave * 64 + it * 4 + grp; // page inside the tile
-        const int p = p_tile + pi;
-        float u[G];
+    const int cnt = min(256, n_pages - p_tile); // pages of this tile: every one is handed on
+    if (quarter == 0 && lane < G) *area.hdr(tile, kvh * G + lane) = make_uint2((uint32_t)cnt, (uint32_t)(lane * cnt));
+    const int j = quarter * 64 + lane; // this lane's page inside the tile
+    if (quarter * 64 >= cnt) return;   // (uniform)
+    int phys_l = 0;                    // (beyond the last page: physical page 0, read and not used)
+    if (j < cnt) {
+        phys_l = page_table[dsc.pt_off + p_tile + j];
+        pmask[(size_t)dsc.pm_off + (size_t)kvh * dsc.pm_stride + p_tile + j] = 0;
+    }
+    // The positive and the negative part of the lane's slice of each query (bf16: as packed pairs, so that two
+    // channels take one dot instruction per part).
+    constexpr int W = RS::WORDS;
+    uint32_t qp[G][W], qn[G][W];
 #pragma unroll
-        for (int g = 0; g < G; ++g) u[g] = 0.f;
-        if (p < n_pages) {
-            const int phys = page_table[dsc.pt_off + p];
+    for (int g = 0; g < G; ++g) {
+        const typename RS::Raw qr = RS::load_raw((const char *)qv + ((size_t)r * H_q + kvh * G + g) * ROW_BYTES, sub);
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+            const uint32_t x = qr.w[w];
+            if constexpr (DT == 0) {
+                const uint32_t neg = ((x & 0x8000u) ? 0xFFFFu : 0u) | ((x & 0x80000000u) ? 0xFFFF0000u : 0u);
+                qn[g][w] = x & neg;
+                qp[g][w] = x & ~neg;
+            } else {
+                qn[g][w] = __float_as_uint(fminf(__uint_as_float(x), 0.f));
+                qp[g][w] = __float_as_uint(fmaxf(__uint_as_float(x), 0.f));
+            }
+        }
+    }
+#pragma unroll 1
+    for (int it0 = 0; it0 < 16; it0 += UN) {
+        typename RS::Raw lo[UN], hi[UN];
+#pragma unroll
+        for (int i = 0; i < UN; ++i) {
+            const int phys = __shfl(phys_l, (it0 + i) * 4 + grp);
             const char *row = rep_pool + ((size_t)phys * H_kv + kvh) * 2 * ROW_BYTES;
-            float lo[EPL], hi[EPL];
-            RS::load(row, sub, lo);
-            RS::load(row + ROW_BYTES, sub, hi);
-#pragma unroll
-            for (int g = 0; g < G; ++g)
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) u[g] += fmaxf(q[g][e] * lo[e], q[g][e] * hi[e]);
+            lo[i] = RS::load_raw(row, sub);
+            hi[i] = RS::load_raw(row + ROW_BYTES, sub);
         }
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            float x = u[g];
-            x += __shfl_xor(x, 1);
-            x += __shfl_xor(x, 2);
-            x += __shfl_xor(x, 4);
-            x += __shfl_xor(x, 8);
-            if (sub == 0) ustage[g][pi] = x;
+        for (int i = 0; i < UN; ++i) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                float x = 0.f;
+#pragma unroll
+                for (int w = 0; w < W; ++w) {
+                    if constexpr (DT == 0) {
+                        x = dot2_bf16(hi[i].w[w], qp[g][w], x);
+                        x = dot2_bf16(lo[i].w[w], qn[g][w], x);
+                    } else {
+                        x = fmaf(__uint_as_float(hi[i].w[w]), __uint_as_float(qp[g][w]), x);
+                        x = fmaf(__uint_as_float(lo[i].w[w]), __uint_as_float(qn[g][w]), x);
+                    }
+                }
+                x = row16_sum(x);
+                if (sub == 0) ustage[g][(it0 + i) * 4 + grp] = x;
+            }
         }
     }
     __syncthreads();
-    const int cnt = min(256, n_pages - p_tile); // pages of this tile: every one is handed on
-    if (threadIdx.x < G)
-        *area.hdr((int)(blockIdx.x / H_kv), (int)(blockIdx.x % H_kv) * G + (int)threadIdx.x) =
-            make_uint2((uint32_t)cnt, (uint32_t)(threadIdx.x * cnt));
-    if ((int)threadIdx.x < cnt) {
+    if (j < cnt) {
 #pragma unroll
         for (int g = 0; g < G; ++g)
-            *area.at(blockIdx.x, g * cnt + (int)threadIdx.x) = make_uint2(__float_as_uint(ustage[g][threadIdx.x]), (uint32_t)(p_tile + threadIdx.x));
+            *area.at(blk, g * cnt + j) = make_uint2(__float_as_uint(ustage[g][lane]), (uint32_t)(p_tile + j));
     }
 }
 
 hipError_t launch_coarse_score(const Shape &sh, const DeviceViews &dv, const DescArgs &pdesc, int B, const void *q,
-                               const void *rep_pool, int total_tiles, const BlockArea &area, hipStream_t st)
+                               const void *rep_pool, int total_tiles, const BlockArea &area, uint8_t *pmask, hipStream_t st)
 {
     if (total_tiles <= 0) return hipSuccess;
     const int G = sh.n_q_heads / sh.n_kv_heads;
-    const dim3 grid((unsigned)(total_tiles * sh.n_kv_heads)), block(256);
+    const dim3 grid((unsigned)(total_tiles * sh.n_kv_heads * 4)), block(64);
 #define ALAYA_COARSE(DT, D, GG)                                                                               \
     coarse_score_kernel<DT, D, GG><<<grid, block, 0, st>>>(pdesc.mem, pdesc.in, pdesc.n, B, dv.page_table, q,  \
-                                                           (const char *)rep_pool, area,                      \
+                                                           (const char *)rep_pool, area, pmask,               \
                                                            sh.n_kv_heads)
 #define ALAYA_COARSE_G(DT, D)                                                                                 \
     switch (G) {                                                                                              \
@@ -189,35 +230,6 @@ hipError_t launch_coarse_score(const Shape &sh, const DeviceViews &dv, const Des
     else return hipErrorInvalidValue;
 #undef ALAYA_COARSE_G
 #undef ALAYA_COARSE
-    return hipGetLastError();
-}
-
-// ------------------------------------------------------------------------------------------------
-// Chosen pages -> one byte per (KV head, page).  Grid: (request, head); the mask was zeroed before.
-__global__ __launch_bounds__(256) void page_mask_kernel(const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n,
-                                                         const ReqDesc *__restrict__ tdesc_mem, const ReqDesc tdesc0, int H_q,
-                                                         int H_kv, const int32_t *__restrict__ pg_ids,
-                                                         const int32_t *__restrict__ pg_counts, uint32_t *__restrict__ pmask)
-{
-    const Descs pdesc{desc_mem, desc0, desc_n};   // page-level: where the chosen pages are
-    const Descs tdesc{tdesc_mem, tdesc0, desc_n}; // token-level: where the request's mask is
-    const int rh = blockIdx.x;
-    const int r = rh / H_q, h = rh % H_q;
-    const int G = H_q / H_kv, kvh = h / G, g = h % G;
-    const ReqDesc pd = pdesc[r], td = tdesc[r];
-    const int32_t *ids = pg_ids + (size_t)pd.score_off + (size_t)h * pd.head_stride;
-    const int cnt = pg_counts[rh];
-    for (int i = threadIdx.x; i < cnt; i += 256) {
-        const size_t byte = (size_t)td.pm_off + (size_t)kvh * td.pm_stride + ids[i];
-        atomicOr(&pmask[byte >> 2], 1u << (8 * (byte & 3) + g));
-    }
-}
-
-hipError_t launch_page_mask(const Shape &sh, const DeviceViews &dv, const DescArgs &pdesc, int B, const int32_t *pg_ids,
-                            const int32_t *pg_counts, uint32_t *pmask, hipStream_t st)
-{
-    page_mask_kernel<<<dim3((unsigned)(B * sh.n_q_heads)), dim3(256), 0, st>>>(
-        pdesc.mem, pdesc.in, pdesc.n, dv.desc.mem, dv.desc.in, sh.n_q_heads, sh.n_kv_heads, pg_ids, pg_counts, pmask);
     return hipGetLastError();
 }
 

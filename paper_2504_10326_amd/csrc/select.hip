@@ -3,6 +3,8 @@
 //   top-k (Sec. 6.1.1): the k largest scores; equal scores at the k-th place go to the smaller id.
 //   DIPR  (Def. 2, 3) : every token with score >= max - beta.
 //   window (Sec. 7.1) : window tokens are always selected; top-k neither counts nor ranks them.
+// The coarse-grained index (Sec. 6.2) selects pages with the same kernel: the survivors then are (block score,
+// page) pairs, and every selected page is also marked in the page mask that the main scoring pass reads.
 // Everything is exact and order-deterministic: counting is integer (radix select on the
 // order-preserving image of the score) and placement is an ordered compaction, so the selected list
 // is the same on every run: ascending by token.
@@ -17,8 +19,8 @@
 //          than k tokens survived - possible only when the main pass filtered with an ESTIMATED bound -
 //          the head is marked for the repair pass and left alone until the kernel runs again.
 //   DIPR:  the maximum is known (the main pass raised it); one placement pass.
-// Up to 16384 survivors (the usual case: the bound leaves one to two times k) are read once and kept in
-// registers for all passes; more are streamed from the blocks once per pass.
+// The first 16384 survivors (the usual case: the bound leaves one to two times k) are read once and kept in
+// registers for all passes; what lies beyond them is streamed from the blocks once per pass.
 #include "alaya_internal.h"
 #include <type_traits>
 
@@ -217,7 +219,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
     const int32_t *__restrict__ page_table, int32_t *__restrict__ sel_ids, int32_t *__restrict__ sel_rows,
     float *__restrict__ sel_scores, int32_t *__restrict__ counts,
     float *__restrict__ head_M, int32_t *__restrict__ out_ids, int32_t *__restrict__ out_counts, int64_t ids_stride,
-    int32_t *__restrict__ status, uint32_t *__restrict__ repairs)
+    int32_t *__restrict__ status, uint32_t *__restrict__ repairs, uint32_t *__restrict__ pmask)
 {
     const Descs desc{desc_mem, desc0, desc_n};
     __shared__ uint32_t lh[kHistBins];
@@ -252,36 +254,36 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
     uint32_t rbits[kRegSets][kSelE]; // score bits
     int rid[kRegSets][kSelE];        // token id
     int rrow[kRegSets][kSelE];       // the token's row in the V pool (asked for early: the counting passes hide the trip)
-    bool in_regs = false;
+    // With all blocks in one batch (the usual case) the batch's prefix sums stay in LDS for the whole kernel and
+    // the first reg_total survivors stay in registers; what lies beyond them is streamed once per pass.
+    const bool single = n_batches == 1;
+    Batch b0{0, 0, 0};
     int reg_total = 0;
-    if (n_batches == 1) {
-        const Batch b = load_batch(hb, dsc.tileb_start, nb_all, off, st, wtot);
-        if (b.total <= kRegSets * kSelChunk) {
-            in_regs = true;
-            reg_total = b.total;
-            const int ngrp = (b.total + 63) >> 6;
-            if (tid <= ngrp) gfirst[tid] = tid < ngrp ? batch_block(off, 0, b.nb, tid << 6) : b.nb - 1;
-            __syncthreads();
+    if (single) {
+        b0 = load_batch(hb, dsc.tileb_start, nb_all, off, st, wtot);
+        reg_total = min(b0.total, kRegSets * kSelChunk);
+        const int ngrp = (reg_total + 63) >> 6;
+        if (tid <= ngrp) gfirst[tid] = (tid << 6) < b0.total ? batch_block(off, 0, b0.nb, tid << 6) : b0.nb - 1;
+        __syncthreads();
 #pragma unroll
-            for (int s = 0; s < kRegSets; ++s) {
+        for (int s = 0; s < kRegSets; ++s) {
 #pragma unroll
-                for (int e = 0; e < kSelE; ++e) { rbits[s][e] = 0u; rid[s][e] = 0; rrow[s][e] = 0; }
-                if (s * kSelChunk >= b.total) continue; // (uniform)
+            for (int e = 0; e < kSelE; ++e) { rbits[s][e] = 0u; rid[s][e] = 0; rrow[s][e] = 0; }
+            if (s * kSelChunk >= reg_total) continue; // (uniform)
 #pragma unroll
-                for (int e = 0; e < kSelE; ++e) {
-                    const int t = s * kSelChunk + e * kSelectThreads + tid;
-                    if (t < b.total) {
-                        const uint2 pr = batch_pair_grouped(hb, b, off, st, gfirst, t);
-                        rbits[s][e] = pr.x;
-                        rid[s][e] = (int)pr.y;
-                    }
+            for (int e = 0; e < kSelE; ++e) {
+                const int t = s * kSelChunk + e * kSelectThreads + tid;
+                if (t < reg_total) {
+                    const uint2 pr = batch_pair_grouped(hb, b0, off, st, gfirst, t);
+                    rbits[s][e] = pr.x;
+                    rid[s][e] = (int)pr.y;
                 }
-                if (sel_rows) {
+            }
+            if (sel_rows) {
 #pragma unroll
-                    for (int e = 0; e < kSelE; ++e)
-                        if (s * kSelChunk + e * kSelectThreads + tid < b.total)
-                            rrow[s][e] = page_table[dsc.pt_off + (rid[s][e] >> 6)] * kPageTokens + (rid[s][e] & 63);
-                }
+                for (int e = 0; e < kSelE; ++e)
+                    if (s * kSelChunk + e * kSelectThreads + tid < reg_total)
+                        rrow[s][e] = page_table[dsc.pt_off + (rid[s][e] >> 6)] * kPageTokens + (rid[s][e] & 63);
             }
         }
     }
@@ -294,30 +296,9 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
         auto counted = [&](uint32_t key, int tok, bool in) {
             return in && !in_window(dsc, tok) && (pshift >= 32 || (key >> pshift) == prefix);
         };
-        if (in_regs) {
-            // (one decision per wavefront and pass, from its first survivors: two straight-line copies of the loop)
-            auto all_sets = [&](auto crowded) {
-#pragma unroll
-                for (int s = 0; s < kRegSets; ++s) {
-                    if (s * kSelChunk >= reg_total) continue;
-#pragma unroll
-                    for (int e = 0; e < kSelE; ++e) {
-                        const uint32_t key = ord_key(__uint_as_float(rbits[s][e]));
-                        hist_add(lh, digit(key), counted(key, rid[s][e], s * kSelChunk + e * kSelectThreads + tid < reg_total),
-                                 decltype(crowded)::value);
-                    }
-                }
-            };
-            const uint32_t key0 = ord_key(__uint_as_float(rbits[0][0]));
-            if (is_crowded(digit(key0), counted(key0, rid[0][0], tid < reg_total))) all_sets(std::true_type{});
-            else all_sets(std::false_type{});
-            return;
-        }
-        for (int bi = 0; bi < n_batches; ++bi) {
-            const int first = bi * batch_blocks;
-            const Batch b = load_batch(hb, dsc.tileb_start + first, min(batch_blocks, nb_all - first), off, st, wtot);
-            constexpr int U = 4; // independent loads per thread and step
-            for (int t0 = tid; t0 < b.total; t0 += U * kSelectThreads) {
+        constexpr int U = 4; // independent loads per thread and step of the streamed part
+        auto stream = [&](const Batch &b, int from) {
+            for (int t0 = from + tid; t0 < b.total; t0 += U * kSelectThreads) {
                 uint2 pr[U];
                 bool in[U];
 #pragma unroll
@@ -334,6 +315,30 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
                     hist_add(lh, digit(key), counted(key, (int)pr[u].y, in[u]), crowded);
                 }
             }
+        };
+        if (single) {
+            // (one decision per wavefront and pass, from its first survivors: two straight-line copies of the loop)
+            auto all_sets = [&](auto crowded) {
+#pragma unroll
+                for (int s = 0; s < kRegSets; ++s) {
+                    if (s * kSelChunk >= reg_total) continue;
+#pragma unroll
+                    for (int e = 0; e < kSelE; ++e) {
+                        const uint32_t key = ord_key(__uint_as_float(rbits[s][e]));
+                        hist_add(lh, digit(key), counted(key, rid[s][e], s * kSelChunk + e * kSelectThreads + tid < reg_total),
+                                 decltype(crowded)::value);
+                    }
+                }
+            };
+            const uint32_t key0 = ord_key(__uint_as_float(rbits[0][0]));
+            if (is_crowded(digit(key0), counted(key0, rid[0][0], tid < reg_total))) all_sets(std::true_type{});
+            else all_sets(std::false_type{});
+            stream(b0, reg_total);
+            return;
+        }
+        for (int bi = 0; bi < n_batches; ++bi) {
+            const int first = bi * batch_blocks;
+            stream(load_batch(hb, dsc.tileb_start + first, min(batch_blocks, nb_all - first), off, st, wtot), 0);
         }
     };
 
@@ -412,13 +417,33 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
                 // where the gather finds the token's value row: physical page * 64 + slot
                 if (sel_rows) rows[pos] = vrow ? vrow[e] : page_table[dsc.pt_off + (tok[e] >> 6)] * kPageTokens + (tok[e] & 63);
                 if (out_ids && (int64_t)pos < ids_stride) out_ids[(size_t)rh * (size_t)ids_stride + pos] = tok[e];
+                if (pmask) { // a selection of pages: bit g of the page's byte in the KV head's row of the mask
+                    const size_t byte = (size_t)dsc.pm_off + (size_t)hb.kvh * dsc.pm_stride + tok[e];
+                    atomicOr(&pmask[byte >> 2], 1u << (8 * (int)(byte & 3) + hb.g));
+                }
                 mx = fmaxf(mx, v);
             }
         }
         baseA += tA;
         baseT += tB;
     };
-    if (in_regs) {
+    auto place_streamed = [&](const Batch &b, int from) {
+        for (int c0 = from; c0 < b.total; c0 += kSelChunk) {
+            uint32_t bits[kSelE];
+            int tok[kSelE];
+            bool in[kSelE];
+#pragma unroll
+            for (int e = 0; e < kSelE; ++e) {
+                const int t = c0 + e * kSelectThreads + tid;
+                in[e] = t < b.total;
+                const uint2 pr = in[e] ? batch_pair(hb, b, off, st, t) : make_uint2(0u, 0u);
+                bits[e] = pr.x;
+                tok[e] = (int)pr.y;
+            }
+            place_chunk(bits, tok, in, nullptr);
+        }
+    };
+    if (single) {
 #pragma unroll
         for (int s = 0; s < kRegSets; ++s) {
             if (s * kSelChunk >= reg_total) continue; // (uniform)
@@ -427,24 +452,11 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
             for (int e = 0; e < kSelE; ++e) in[e] = s * kSelChunk + e * kSelectThreads + tid < reg_total;
             place_chunk(rbits[s], rid[s], in, rrow[s]);
         }
+        place_streamed(b0, reg_total);
     } else {
         for (int bi = 0; bi < n_batches; ++bi) {
             const int first = bi * batch_blocks;
-            const Batch b = load_batch(hb, dsc.tileb_start + first, min(batch_blocks, nb_all - first), off, st, wtot);
-            for (int c0 = 0; c0 < b.total; c0 += kSelChunk) {
-                uint32_t bits[kSelE];
-                int tok[kSelE];
-                bool in[kSelE];
-#pragma unroll
-                for (int e = 0; e < kSelE; ++e) {
-                    const int t = c0 + e * kSelectThreads + tid;
-                    in[e] = t < b.total;
-                    const uint2 pr = in[e] ? batch_pair(hb, b, off, st, t) : make_uint2(0u, 0u);
-                    bits[e] = pr.x;
-                    tok[e] = (int)pr.y;
-                }
-                place_chunk(bits, tok, in, nullptr);
-            }
+            place_streamed(load_batch(hb, dsc.tileb_start + first, min(batch_blocks, nb_all - first), off, st, wtot), 0);
         }
     }
     const int count = baseA + min(baseT, ties);
@@ -473,7 +485,7 @@ hipError_t launch_select(const Shape &sh, const DeviceViews &dv, const SelectIO 
     select_kernel<<<dim3((unsigned)(B * sh.n_q_heads)), dim3(kSelectThreads), 0, st>>>(
         io.desc.mem, io.desc.in, io.desc.n, sh.n_q_heads, sh.n_kv_heads, mode, io.area,
         dv.head_maxkey, dv.fail, dv.any_fail, redo ? 1 : 0, batch_blocks, dv.page_table, io.ids, io.rows,
-        io.scores, io.counts, io.head_M, out_ids, out_counts, ids_stride, dv.status, dv.repairs);
+        io.scores, io.counts, io.head_M, out_ids, out_counts, ids_stride, dv.status, dv.repairs, io.pmask);
     return hipGetLastError();
 }
 

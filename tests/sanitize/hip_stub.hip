@@ -146,6 +146,7 @@ hipError_t launch_select(const Shape &sh, const DeviceViews &, const SelectIO &i
     for (int r = 0; r < B; ++r) {
         const ReqDesc d = desc_of(io.desc, r);
         EXPECT(d.head_stride >= d.n && d.k <= d.n);
+        if (io.pmask) EXPECT(d.pm_off >= 0 && d.pm_stride >= d.n); // (pages: one mask byte per (KV head, page))
     }
     (void)sh;
     return hipSuccess;
@@ -205,25 +206,19 @@ hipError_t launch_reps_step(const Shape &, const DeviceViews &dv, void *rep_pool
     return hipSuccess;
 }
 hipError_t launch_coarse_score(const Shape &sh, const DeviceViews &, const DescArgs &pd, int B, const void *q, const void *rep_pool,
-                               int total_tiles, const BlockArea &area, hipStream_t)
+                               int total_tiles, const BlockArea &area, uint8_t *pmask, hipStream_t)
 {
     ++g_launches;
-    EXPECT(q && rep_pool && pd.n == B && area.hdrs && area.head && area.n_tiles == total_tiles &&
+    EXPECT(q && rep_pool && pmask && pd.n == B && area.hdrs && area.head && area.n_tiles == total_tiles &&
            area.rest_stride >= 256 * (sh.n_q_heads / sh.n_kv_heads) - kHeadStride);
     int next = 0;
     for (int r = 0; r < B; ++r) {
         const ReqDesc d = desc_of(pd, r);
         EXPECT(d.tileb_start == next && d.k >= 1 && d.k <= d.n);
+        EXPECT(d.pm_off >= 0 && d.pm_stride >= d.n); // the kernel clears one mask byte per (KV head, page)
         next += d.ntiles_b;
     }
     EXPECT(next == total_tiles);
-    return hipSuccess;
-}
-hipError_t launch_page_mask(const Shape &, const DeviceViews &, const DescArgs &pd, int B, const int32_t *pg_ids,
-                            const int32_t *pg_counts, uint32_t *pmask, hipStream_t)
-{
-    ++g_launches;
-    EXPECT(pd.n == B && pg_ids && pg_counts && pmask);
     return hipSuccess;
 }
 hipError_t launch_graph_knn(const Shape &sh, const void *k_pool, const int32_t *pt_row, int n, int M, int32_t *nbr, hipStream_t)
