@@ -34,12 +34,21 @@ __device__ __forceinline__ void rep_page(const void *__restrict__ k_pool, void *
     const size_t tile = ((size_t)phys * H_kv + kvh) * (size_t)(64 * D);
     const size_t col = tile + (size_t)(c / E) * 64 * E + (c % E);
     float mn = INFINITY, mx = -INFINITY;
-    for (int j = 0; j < ntok; ++j) {
-        float x;
-        if (DT == 0) x = bf16_to_f32(((const uint16_t *)k_pool)[col + (size_t)j * E]);
-        else x = ((const float *)k_pool)[col + (size_t)j * E];
-        mn = fminf(mn, x);
-        mx = fmaxf(mx, x);
+    // (eight tokens at a time, so that their loads are on their way together; a token beyond the page's last
+    // one repeats the last one, which changes neither extreme)
+    for (int j0 = 0; j0 < ntok; j0 += 8) {
+        float x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int j = min(j0 + u, ntok - 1);
+            if (DT == 0) x[u] = bf16_to_f32(((const uint16_t *)k_pool)[col + (size_t)j * E]);
+            else x[u] = ((const float *)k_pool)[col + (size_t)j * E];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            mn = fminf(mn, x[u]);
+            mx = fmaxf(mx, x[u]);
+        }
     }
     const size_t row = ((size_t)phys * H_kv + kvh) * 2 * (size_t)D + c;
     if (DT == 0) { // the minimum and maximum of bf16 values are bf16 values: the upper halves are exact
