@@ -252,6 +252,17 @@ def test_coarse_index_finds_clustered_keys():
     c.close()
 
 
+@pytest.mark.parametrize("n,P,k", [(1048576 + 64 * 5 + 3, 40, 64), (1050000, 1100, 600)])
+def test_more_pages_than_the_selection_keeps_in_registers(n, P, k):
+    """The selection of the pages keeps the block scores of the first 16384 pages of a head in registers and
+    streams the rest: a request of a few pages more (one KV head of 64 channels keeps it small)."""
+    w = wl.Workload("coarse_long", 2, 1, 64, (n,), "bf16", 16, "topk", topk=(1,), permute_pages=True, seed=5)
+    g = wl.generate(w, threads=8)
+    c = _cache(w, g)
+    run_coarse(c, w, g, [P], [k])
+    c.close()
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_coarse_random_configurations_against_the_oracle(seed):
     """Random shapes, batches, page budgets, k, windows, prefixes and bound modes."""
