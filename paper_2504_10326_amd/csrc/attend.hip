@@ -137,17 +137,24 @@ hipError_t launch_attend(const Shape &sh, const DeviceViews &dv, int B, float sc
 }
 
 // ------------------------------------------------------------------------------------------------
-// Merge of partial results, fixed order.  Grid: (request, head); one thread per output channel.
+// Merge of partial results, fixed order.  Grid: (request, head); block: (output channel, slice).  The sparse
+// path has at most kMaxSplits partials per head and one slice.  Dense attention has one partial per tile of the
+// request, hundreds at 1M tokens: kCombineSlices slices take consecutive runs of them (one slice alone went
+// through them eight at a time, 40 us at 1M tokens), and slice 0 adds the slices' sums up, in order.
+constexpr int kCombineSlices = 8;
+
 template <int D>
-__global__ __launch_bounds__(D) void combine_kernel(const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int B, int H_q,
+__global__ __launch_bounds__(D * kCombineSlices) void combine_kernel(const ReqDesc *__restrict__ desc_mem, const ReqDesc desc0, int desc_n, int B, int H_q,
                                                      const float *__restrict__ partials, int splits,
                                                      int per_request_tiles, int pages_per_tile,
                                                      const int32_t *__restrict__ counts, int min_splits,
                                                      float *__restrict__ out)
 {
     const Descs desc{desc_mem, desc0, desc_n};
+    __shared__ float sM[kCombineSlices], sL[kCombineSlices], sO[kCombineSlices][D];
     const int rh = blockIdx.x;
     const int r = rh / H_q, h = rh % H_q;
+    const int ch = threadIdx.x, sl = threadIdx.y, S = blockDim.y;
     int np;
     size_t first, stride;
     if (per_request_tiles) {
@@ -161,28 +168,37 @@ __global__ __launch_bounds__(D) void combine_kernel(const ReqDesc *__restrict__ 
         first = (size_t)rh * splits * (D + 2);
         stride = D + 2;
     }
+    const int per = (np + S - 1) / S;
+    const int i_begin = min(np, sl * per), i_end = min(np, i_begin + per); // this slice's partials
     // loads are issued eight at a time so that their latencies overlap; the merge order stays fixed
     constexpr int U = 8;
     // The splits of a sparse call all subtracted the same maximum (or hold nothing): no rescaling, and
     // no need to look for the largest reference first.
     float M = -INFINITY;
-    for (int i0 = 0; per_request_tiles && i0 < np; i0 += U) {
-        float mm[U];
+    if (per_request_tiles) {
+        for (int i0 = i_begin; i0 < i_end; i0 += U) {
+            float mm[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) mm[u] = i0 + u < np ? partials[first + (size_t)(i0 + u) * stride] : -INFINITY;
+            for (int u = 0; u < U; ++u) mm[u] = i0 + u < i_end ? partials[first + (size_t)(i0 + u) * stride] : -INFINITY;
 #pragma unroll
-        for (int u = 0; u < U; ++u) M = fmaxf(M, mm[u]);
+            for (int u = 0; u < U; ++u) M = fmaxf(M, mm[u]);
+        }
+        if (S > 1) {
+            if (ch == 0) sM[sl] = M;
+            __syncthreads();
+            for (int t = 0; t < S; ++t) M = fmaxf(M, sM[t]);
+        }
     }
     float L = 0.f, o = 0.f;
-    for (int i0 = 0; i0 < np; i0 += U) {
+    for (int i0 = i_begin; i0 < i_end; i0 += U) {
         float mm[U], ll[U], aa[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const bool ok = i0 + u < np;
-            const float *p = partials + first + (size_t)(ok ? i0 + u : 0) * stride;
+            const bool ok = i0 + u < i_end;
+            const float *p = partials + first + (size_t)(ok ? i0 + u : i_begin) * stride;
             mm[u] = ok ? p[0] : -INFINITY;
             ll[u] = p[1];
-            aa[u] = p[2 + threadIdx.x];
+            aa[u] = p[2 + ch];
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -191,18 +207,26 @@ __global__ __launch_bounds__(D) void combine_kernel(const ReqDesc *__restrict__ 
             o = fmaf(w, aa[u], o);
         }
     }
-    out[(size_t)rh * D + threadIdx.x] = o / L;
+    if (S > 1) {
+        if (ch == 0) sL[sl] = L;
+        sO[sl][ch] = o;
+        __syncthreads();
+        if (sl != 0) return;
+        for (int t = 1; t < S; ++t) { L += sL[t]; o += sO[t][ch]; }
+    }
+    out[(size_t)rh * D + ch] = o / L;
 }
 
 hipError_t launch_combine(const Shape &sh, const DeviceViews &dv, int B, int splits, int min_splits,
                           int per_request_tiles, int pages_per_tile, float *out, hipStream_t st)
 {
     const dim3 grid((unsigned)(B * sh.n_q_heads));
+    const unsigned slices = per_request_tiles ? kCombineSlices : 1;
     if (sh.head_dim == 128)
-        combine_kernel<128><<<grid, dim3(128), 0, st>>>(dv.desc.mem, dv.desc.in, dv.desc.n, B, sh.n_q_heads, dv.partials, splits,
+        combine_kernel<128><<<grid, dim3(128, slices), 0, st>>>(dv.desc.mem, dv.desc.in, dv.desc.n, B, sh.n_q_heads, dv.partials, splits,
                                                         per_request_tiles, pages_per_tile, dv.counts, min_splits, out);
     else if (sh.head_dim == 64)
-        combine_kernel<64><<<grid, dim3(64), 0, st>>>(dv.desc.mem, dv.desc.in, dv.desc.n, B, sh.n_q_heads, dv.partials, splits,
+        combine_kernel<64><<<grid, dim3(64, slices), 0, st>>>(dv.desc.mem, dv.desc.in, dv.desc.n, B, sh.n_q_heads, dv.partials, splits,
                                                       per_request_tiles, pages_per_tile, dv.counts, min_splits, out);
     else
         return hipErrorInvalidValue;
