@@ -11,6 +11,8 @@
 #include "score_page.h"
 #include <hip/hip_ext.h>
 
+#include <algorithm>
+
 namespace alaya {
 
 // ------------------------------------------------------------------------------------------------
@@ -36,17 +38,61 @@ __global__ __launch_bounds__(256) void append_kernel(const int32_t *__restrict__
     }
 }
 
+// The same for many tokens at once (a context being loaded).  Keys: one thread per 16-byte slice with the TOKEN
+// as the fastest index, so that a wavefront writes 64 consecutive slots of one slice column - 1 KiB in a row;
+// with the slice fastest, as above, every 16-byte write goes to a line of its own, 1 KiB from the next (a
+// million tokens: 3.3 ms).  The reads are the scattered side then, and those the caches absorb.  Values keep
+// the slice as the fastest index: 256 bytes in a row on both sides.
+//   first_page = n_old / 64; n_pages = pages that the new tokens touch
+__global__ __launch_bounds__(256) void append_bulk_kernel(const int32_t *__restrict__ pt_row,
+                                                           uint4 *__restrict__ k_pool, uint4 *__restrict__ v_pool,
+                                                           const uint4 *__restrict__ k, const uint4 *__restrict__ v,
+                                                           int64_t n_old, int64_t t, int H_kv, int NC, int64_t first_page,
+                                                           int64_t n_pages)
+{
+    const int64_t total_v = t * H_kv * NC, total_k = n_pages * H_kv * NC * 64;
+    const int64_t total = total_k > total_v ? total_k : total_v;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        if (i < total_k) {
+            const int slot = (int)(i & 63);
+            const int c = (int)((i >> 6) % NC);
+            const int kvh = (int)((i / (64 * (int64_t)NC)) % H_kv);
+            const int64_t page = first_page + i / (64 * (int64_t)NC * H_kv);
+            const int64_t tok = page * 64 + slot;
+            if (tok >= n_old && tok < n_old + t) {
+                const size_t tile = ((size_t)pt_row[page] * H_kv + kvh) * (size_t)(NC * 64);
+                k_pool[tile + (size_t)c * 64 + slot] = k[((tok - n_old) * H_kv + kvh) * NC + c];
+            }
+        }
+        if (i < total_v) {
+            const int c = (int)(i % NC);
+            const int kvh = (int)((i / NC) % H_kv);
+            const int64_t tok = n_old + i / ((int64_t)NC * H_kv);
+            const size_t tile = ((size_t)pt_row[tok >> 6] * H_kv + kvh) * (size_t)(NC * 64);
+            v_pool[tile + (size_t)(tok & 63) * NC + c] = v[i];
+        }
+    }
+}
+
 hipError_t launch_append(const Shape &sh, const int32_t *pt_row, void *k_pool, void *v_pool, const void *k,
                          const void *v, int64_t n_old, int64_t t, hipStream_t st)
 {
     const int NC = sh.head_dim * (sh.dtype == 0 ? 2 : 4) / 16;
-    const int64_t total = t * sh.n_kv_heads * NC;
+    const int64_t first_page = n_old / kPageTokens, n_pages = (n_old + t + kPageTokens - 1) / kPageTokens - first_page;
+    const bool bulk = t >= 4 * kPageTokens;
+    const int64_t total = bulk ? std::max(t * sh.n_kv_heads * NC, n_pages * sh.n_kv_heads * NC * 64) : t * sh.n_kv_heads * NC;
     int64_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
     if (blocks < 1) blocks = 1;
-    append_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(pt_row, (uint4 *)k_pool, (uint4 *)v_pool,
-                                                                (const uint4 *)k, (const uint4 *)v, n_old, t,
-                                                                sh.n_kv_heads, NC);
+    if (bulk)
+        append_bulk_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(pt_row, (uint4 *)k_pool, (uint4 *)v_pool,
+                                                                         (const uint4 *)k, (const uint4 *)v, n_old, t,
+                                                                         sh.n_kv_heads, NC, first_page, n_pages);
+    else
+        append_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(pt_row, (uint4 *)k_pool, (uint4 *)v_pool,
+                                                                    (const uint4 *)k, (const uint4 *)v, n_old, t,
+                                                                    sh.n_kv_heads, NC);
     return hipGetLastError();
 }
 
