@@ -38,61 +38,58 @@ __global__ __launch_bounds__(256) void append_kernel(const int32_t *__restrict__
     }
 }
 
-// The same for many tokens at once (a context being loaded).  Keys: one thread per 16-byte slice with the TOKEN
-// as the fastest index, so that a wavefront writes 64 consecutive slots of one slice column - 1 KiB in a row;
-// with the slice fastest, as above, every 16-byte write goes to a line of its own, 1 KiB from the next (a
-// million tokens: 3.3 ms).  The reads are the scattered side then, and those the caches absorb.  Values keep
-// the slice as the fastest index: 256 bytes in a row on both sides.
-//   first_page = n_old / 64; n_pages = pages that the new tokens touch
+// The same for many tokens at once (a context being loaded).  Grid: (page that the new tokens touch, KV head).
+// The model's rows are 256-byte runs (one token's key for one KV head); the K tile wants the tokens of a
+// 16-byte slice column next to each other.  The workgroup reads the page's key rows as they lie, turns the
+// tile over in LDS and writes it column by column, 1 KiB in a row per wavefront; the value rows are copied as
+// they are.  (One thread per slice with the slice as the fastest index, as above, writes every 16 bytes of a
+// key to a line of its own, 1 KiB from the next: 3.3 ms for a million tokens; with the token as the fastest
+// index and scattered reads instead, 2.3 ms.)
+constexpr int kAppendMaxNC = 32; // 16-byte slices per row: fp32, head_dim 128
+
 __global__ __launch_bounds__(256) void append_bulk_kernel(const int32_t *__restrict__ pt_row,
                                                            uint4 *__restrict__ k_pool, uint4 *__restrict__ v_pool,
                                                            const uint4 *__restrict__ k, const uint4 *__restrict__ v,
-                                                           int64_t n_old, int64_t t, int H_kv, int NC, int64_t first_page,
-                                                           int64_t n_pages)
+                                                           int64_t n_old, int64_t t, int H_kv, int NC, int64_t first_page)
 {
-    const int64_t total_v = t * H_kv * NC, total_k = n_pages * H_kv * NC * 64;
-    const int64_t total = total_k > total_v ? total_k : total_v;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
-         i += (int64_t)gridDim.x * blockDim.x) {
-        if (i < total_k) {
-            const int slot = (int)(i & 63);
-            const int c = (int)((i >> 6) % NC);
-            const int kvh = (int)((i / (64 * (int64_t)NC)) % H_kv);
-            const int64_t page = first_page + i / (64 * (int64_t)NC * H_kv);
-            const int64_t tok = page * 64 + slot;
-            if (tok >= n_old && tok < n_old + t) {
-                const size_t tile = ((size_t)pt_row[page] * H_kv + kvh) * (size_t)(NC * 64);
-                k_pool[tile + (size_t)c * 64 + slot] = k[((tok - n_old) * H_kv + kvh) * NC + c];
-            }
-        }
-        if (i < total_v) {
-            const int c = (int)(i % NC);
-            const int kvh = (int)((i / NC) % H_kv);
-            const int64_t tok = n_old + i / ((int64_t)NC * H_kv);
-            const size_t tile = ((size_t)pt_row[tok >> 6] * H_kv + kvh) * (size_t)(NC * 64);
-            v_pool[tile + (size_t)(tok & 63) * NC + c] = v[i];
-        }
+    __shared__ uint4 turn[64][kAppendMaxNC + 1]; // (+ 1: the column reads of the second phase spread over the banks)
+    const int kvh = blockIdx.x % H_kv;
+    const int64_t page = first_page + blockIdx.x / H_kv;
+    const size_t tile = ((size_t)pt_row[page] * H_kv + kvh) * (size_t)(NC * 64);
+    // the page's slots that this append writes
+    const int s0 = (int)(n_old > page * 64 ? n_old - page * 64 : 0);
+    const int s1 = (int)(n_old + t < (page + 1) * 64 ? n_old + t - page * 64 : 64);
+    const int rows_per_turn = 256 / NC; // NC is 8, 16 or 32
+    const int c1 = threadIdx.x % NC;
+    for (int slot = s0 + threadIdx.x / NC; slot < s1; slot += rows_per_turn) {
+        const size_t src = ((size_t)(page * 64 + slot - n_old) * H_kv + kvh) * NC + c1;
+        turn[slot][c1] = k[src];
+        v_pool[tile + (size_t)slot * NC + c1] = v[src];
     }
+    __syncthreads();
+    const int slot = threadIdx.x & 63;
+    if (slot >= s0 && slot < s1)
+        for (int c = threadIdx.x >> 6; c < NC; c += 4) k_pool[tile + (size_t)c * 64 + slot] = turn[slot][c];
 }
 
 hipError_t launch_append(const Shape &sh, const int32_t *pt_row, void *k_pool, void *v_pool, const void *k,
                          const void *v, int64_t n_old, int64_t t, hipStream_t st)
 {
     const int NC = sh.head_dim * (sh.dtype == 0 ? 2 : 4) / 16;
-    const int64_t first_page = n_old / kPageTokens, n_pages = (n_old + t + kPageTokens - 1) / kPageTokens - first_page;
-    const bool bulk = t >= 4 * kPageTokens;
-    const int64_t total = bulk ? std::max(t * sh.n_kv_heads * NC, n_pages * sh.n_kv_heads * NC * 64) : t * sh.n_kv_heads * NC;
+    if (t >= 4 * kPageTokens) {
+        if (NC > kAppendMaxNC || 256 % NC != 0) return hipErrorInvalidValue;
+        const int64_t first_page = n_old / kPageTokens, n_pages = (n_old + t + kPageTokens - 1) / kPageTokens - first_page;
+        append_bulk_kernel<<<dim3((unsigned)(n_pages * sh.n_kv_heads)), dim3(256), 0, st>>>(
+            pt_row, (uint4 *)k_pool, (uint4 *)v_pool, (const uint4 *)k, (const uint4 *)v, n_old, t, sh.n_kv_heads, NC, first_page);
+        return hipGetLastError();
+    }
+    const int64_t total = t * sh.n_kv_heads * NC;
     int64_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
     if (blocks < 1) blocks = 1;
-    if (bulk)
-        append_bulk_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(pt_row, (uint4 *)k_pool, (uint4 *)v_pool,
-                                                                         (const uint4 *)k, (const uint4 *)v, n_old, t,
-                                                                         sh.n_kv_heads, NC, first_page, n_pages);
-    else
-        append_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(pt_row, (uint4 *)k_pool, (uint4 *)v_pool,
-                                                                    (const uint4 *)k, (const uint4 *)v, n_old, t,
-                                                                    sh.n_kv_heads, NC);
+    append_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(pt_row, (uint4 *)k_pool, (uint4 *)v_pool,
+                                                                (const uint4 *)k, (const uint4 *)v, n_old, t,
+                                                                sh.n_kv_heads, NC);
     return hipGetLastError();
 }
 
